@@ -1,0 +1,270 @@
+/*
+ * lpk_ref.c -- CPU oracle for the low-precision SGD update with Kahan summation
+ * ("lazy update") over dynamic fixed-point (DFX) parameters.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, one-element-at-a-time
+ * statement of what the update computes, used only to check the GPU library
+ * and to time a CPU baseline.  It shares no code with the GPU path and the
+ * GPU path never calls it.
+ *
+ * What it follows (paper: "Training Deep Neural Network in Limited Precision"):
+ *   - Section 2, Algorithm 1 (lazy update): accumulate the step into an extra
+ *     parameter, move theta by the part of it that theta's precision can hold,
+ *     keep the remainder.
+ *   - Section 2, Figure 1: parameter, gradient and accumulator share one
+ *     decimal-point axis; with k overlapping bits the parameter is effectively
+ *     m + n - 2 - k bits wide.
+ *   - Section 1 (hardware model): 8/16-bit dynamic fixed point, uniform linear
+ *     quantization, no stochastic rounding.
+ *   - Section 6: a tensor's exponent is found by scanning its maximum.
+ *
+ * Notation.  DFX(W, fl) is a two's-complement integer q of W in {8,16} bits
+ * whose real value is q * 2^-fl.  qmax = 2^(W-1)-1, qmin = -2^(W-1).
+ * RNE = round to nearest, ties to even.  The compensation c stored here is the
+ * NEGATIVE of Algorithm 1's acc, so theta + c is the "virtual" parameter.
+ *
+ * Readings where the paper is silent (rounding mode, saturation, position of
+ * the accumulator's decimal point, the fractional-length rule, the learning
+ * rate format, weight decay) are fixed as follows and nowhere else:
+ *   rounding: RNE everywhere;  overflow: saturate at store, intermediates wide;
+ *   c lives on grid fl_theta + d (d = W_c - 1 means no overlapping bit, k = 0);
+ *   fraclen: the largest fl at which the tensor's own maximum does not saturate;
+ *   lr and weight decay: unsigned Q0.16 integers.
+ *
+ * Every quantity is an exact integer; __int128 is used so that no intermediate
+ * can overflow inside the documented domain (fraclens in [-64,64], 0<=d<=24,
+ * |fl_out - fl_in| <= 15, lr_q16, wd_q16 <= 65535).
+ *
+ * Parity pins (tests/, CPU only): exact-rational brute force on tiny tensors,
+ * the Kahan conservation invariant, the quarter-LSB worked example, the
+ * effective-width closed form, torch.round cross-check for quantization,
+ * definition-level brute force for the fraclen rule.
+ */
+#include <stdint.h>
+#include <string.h>
+#include <stddef.h>
+#include <math.h>
+#include <float.h>
+
+typedef __int128 wide;
+
+#define LPK_REF_OK            0
+#define LPK_REF_ERR_ARG     (-1)
+
+#define STATUS_NONFINITE     1u   /* a NaN or Inf was seen in fp32 input        */
+#define STATUS_DOMAIN        2u   /* a fraclen / shift outside the domain; the
+                                     tensor was left untouched                 */
+
+#define FL_MIN (-64)
+#define FL_MAX   64
+#define D_MAX    24
+#define DELTA_MAX 15
+
+static const wide HUGE_W = (wide)1 << 100;   /* stands for "beyond every bound used here" */
+static const wide CAP40  = (wide)1 << 40;
+
+/* ---------- exact helpers ------------------------------------------------ */
+
+/* RNE(x * 2^-k) for any integer k, as if in unbounded integers.
+ * Callers keep |x| < 2^98.  For k <= -60 and x != 0 the exact value has
+ * magnitude >= 2^60, which exceeds every clamp applied afterwards (2^40 cap,
+ * 16-bit saturation), so +-2^100 is returned in its place. */
+static wide rescale(wide x, int k)
+{
+    if (x == 0) return 0;
+    if (k <= 0) {
+        if (k <= -60) return x > 0 ? HUGE_W : -HUGE_W;
+        return x * ((wide)1 << (-k));                /* exact */
+    }
+    if (k >= 100) return 0;                          /* |x| 2^-k < 1/4 */
+    wide p = (wide)1 << k;
+    wide q = x / p;                                  /* truncates toward zero */
+    wide r = x % p;
+    if (r < 0) { r += p; q -= 1; }                   /* now x = q p + r, 0 <= r < p (floor) */
+    if (2 * r > p || (2 * r == p && (q & 1))) q += 1;
+    return q;
+}
+
+static wide clampw(wide x, wide lo, wide hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+static wide rescale_cap(wide x, int k) { return clampw(rescale(x, k), -CAP40, CAP40); }
+
+static wide qmax_of(int bits) { return ((wide)1 << (bits - 1)) - 1; }
+static wide qmin_of(int bits) { return -((wide)1 << (bits - 1)); }
+static wide sat(wide x, int bits) { return clampw(x, qmin_of(bits), qmax_of(bits)); }
+
+static int bits_ok(int bits) { return bits == 8 || bits == 16; }
+
+static wide load_q(const void *p, uint64_t i, int bits)
+{
+    return bits == 8 ? (wide)((const int8_t *)p)[i] : (wide)((const int16_t *)p)[i];
+}
+static void store_q(void *p, uint64_t i, int bits, wide v)
+{
+    if (bits == 8) ((int8_t *)p)[i] = (int8_t)v; else ((int16_t *)p)[i] = (int16_t)v;
+}
+
+/* An fp32 is the exact dyadic rational (-1)^neg * m * 2^ex.  kind: 0 finite, 1 inf, 2 nan. */
+static int decompose_f32(float x, int *neg, wide *m, int *ex)
+{
+    uint32_t b; memcpy(&b, &x, 4);
+    uint32_t E = (b >> 23) & 0xFFu, frac = b & 0x7FFFFFu;
+    *neg = (int)(b >> 31);
+    if (E == 0xFFu) { *m = 0; *ex = 0; return frac ? 2 : 1; }
+    if (E == 0) { *m = frac; *ex = -149; }               /* zero / subnormal */
+    else        { *m = (wide)(frac | 0x800000u); *ex = (int)E - 150; }
+    return 0;
+}
+
+/* ---------- fractional-length rule --------------------------------------- */
+
+/* fl*(M, W): the LARGEST integer fl with RNE(M * 2^fl) <= qmax, for M = m * 2^ex > 0,
+ * found by trying candidates from fine to coarse; the result is then clamped to
+ * [FL_MIN, FL_MAX].  (Scanning the maximum to choose the exponent: Section 6;
+ * the rule itself is this build's reading -- the widest-precision grid on which
+ * the tensor's own maximum does not saturate.) */
+static int fraclen_of_max(wide m, int ex, int bits)
+{
+    int fl;
+    for (fl = 400; fl > -400; --fl)
+        if (rescale(m, -(ex + fl)) <= qmax_of(bits)) break;
+    if (fl > FL_MAX) fl = FL_MAX;
+    if (fl < FL_MIN) fl = FL_MIN;
+    return fl;
+}
+
+/* max|x| over an fp32 tensor -> fraclen for a W-bit grid.
+ * Zero tensor (or n == 0) -> fl_default.  Any NaN/Inf -> FL_MIN and the
+ * non-finite status bit. */
+int lpk_ref_select_fraclen_f32(const float *x, uint64_t n, int bits, int32_t fl_default,
+                               int32_t *fl_out, uint32_t *status)
+{
+    if (!bits_ok(bits) || !fl_out || (n && !x)) return LPK_REF_ERR_ARG;
+    float best = 0.0f; int nonfinite = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        float a = fabsf(x[i]);                 /* exact */
+        if (!(a <= FLT_MAX)) { nonfinite = 1; continue; }   /* NaN or Inf */
+        if (a > best) best = a;                /* exact comparison */
+    }
+    int neg, best_ex; wide best_m;
+    decompose_f32(best, &neg, &best_m, &best_ex);
+    if (nonfinite) {
+        *fl_out = FL_MIN;
+        if (status) *status |= STATUS_NONFINITE;
+        return LPK_REF_OK;
+    }
+    *fl_out = best_m == 0 ? fl_default : fraclen_of_max(best_m, best_ex, bits);
+    return LPK_REF_OK;
+}
+
+/* Re-selection from the running maximum of the compensated sum (Section 6:
+ * exponent from the history of maxima, here with a one-step lag):
+ * M = vmax * 2^-vmax_fl.  vmax == 0 keeps fl_default.  The result is clamped
+ * to fl_default +- DELTA_MAX (the next update can move the grid by at most
+ * that much) and to [FL_MIN, FL_MAX]. */
+int lpk_ref_select_fraclen_vmax(uint64_t vmax, int32_t vmax_fl, int bits, int32_t fl_default,
+                                int32_t *fl_out, uint32_t *status)
+{
+    if (!bits_ok(bits) || !fl_out) return LPK_REF_ERR_ARG;
+    if (vmax_fl < FL_MIN || vmax_fl > FL_MAX + D_MAX || fl_default < FL_MIN || fl_default > FL_MAX) {
+        *fl_out = fl_default;
+        if (status) *status |= STATUS_DOMAIN;
+        return LPK_REF_OK;
+    }
+    if (vmax == 0) { *fl_out = fl_default; return LPK_REF_OK; }
+    int fl = fraclen_of_max((wide)vmax, -vmax_fl, bits);
+    if (fl > fl_default + DELTA_MAX) fl = fl_default + DELTA_MAX;
+    if (fl < fl_default - DELTA_MAX) fl = fl_default - DELTA_MAX;
+    if (fl > FL_MAX) fl = FL_MAX;
+    if (fl < FL_MIN) fl = FL_MIN;
+    *fl_out = fl;
+    return LPK_REF_OK;
+}
+
+/* ---------- quantization -------------------------------------------------- */
+
+/* q_i = sat_W(RNE(x_i * 2^fl)): uniform linear quantization, no stochastic
+ * rounding (Section 1).  NaN -> 0, +-Inf -> qmax/qmin, both raise the
+ * non-finite status bit.  fl outside [FL_MIN, FL_MAX]: nothing written,
+ * domain status bit. */
+int lpk_ref_quantize(const float *x, uint64_t n, int bits, int32_t fl, void *dst, uint32_t *status)
+{
+    if (!bits_ok(bits) || (n && (!x || !dst))) return LPK_REF_ERR_ARG;
+    if (fl < FL_MIN || fl > FL_MAX) { if (status) *status |= STATUS_DOMAIN; return LPK_REF_OK; }
+    for (uint64_t i = 0; i < n; ++i) {
+        int neg, ex; wide m;
+        int kind = decompose_f32(x[i], &neg, &m, &ex);
+        wide q;
+        if (kind == 2)      { q = 0;                                   if (status) *status |= STATUS_NONFINITE; }
+        else if (kind == 1) { q = neg ? qmin_of(bits) : qmax_of(bits); if (status) *status |= STATUS_NONFINITE; }
+        else                 q = sat(rescale(neg ? -m : m, -(ex + fl)), bits);
+        store_q(dst, i, bits, q);
+    }
+    return LPK_REF_OK;
+}
+
+/* ---------- the update ----------------------------------------------------- */
+
+/*
+ * One lazy-update step over one tensor, in place.
+ *
+ *   theta : DFX(theta_bits, fl_in) on entry, DFX(theta_bits, fl_out) on exit
+ *   comp  : c = -acc, DFX(comp_bits, fl_in + d) on entry, (fl_out + d) on exit;
+ *           NULL = plain SGD without the accumulator (eq. 1)
+ *   grad  : DFX(grad_bits, fl_g)
+ *   lr_q, wd_q : Q0.16 (wd_q == 0: no decay)
+ *   vmax  : max_i |v_i| of the compensated sum on grid fl_in + d (may be NULL)
+ *
+ * Per element, with F = fl_in + d the working grid (units: LSBs of c):
+ *   s_g = cap( RNE( -lr_q * g * 2^-(fl_g + 16 - F) ) )      step on c's grid   [Alg. 1, 1st assignment]
+ *   s_w = cap( RNE( -lr_q * wd_q * theta * 2^-(32 - d) ) )  decay, rounded separately
+ *   v   = theta * 2^d + c + s_g + s_w                       kept wide (never cut to comp_bits)
+ *   theta' = sat( RNE( v on the fl_out grid ) )             [Alg. 1, 2nd assignment]
+ *   c'     = sat( RNE( (v - theta') on the fl_out + d grid ) )   [Alg. 1, 3rd assignment]
+ *   store theta', c'                                        [Alg. 1, 4th assignment]
+ */
+int lpk_ref_kahan_sgd_step(void *theta, void *comp, const void *grad, uint64_t n,
+                           int theta_bits, int comp_bits, int grad_bits, int d,
+                           int32_t fl_in, int32_t fl_out, int32_t fl_g,
+                           uint32_t lr_q, uint32_t wd_q,
+                           uint64_t *vmax, uint32_t *status)
+{
+    if (!bits_ok(theta_bits) || !bits_ok(grad_bits) || (comp && !bits_ok(comp_bits))) return LPK_REF_ERR_ARG;
+    if (n && (!theta || !grad)) return LPK_REF_ERR_ARG;
+    if (lr_q > 65535u || wd_q > 65535u) return LPK_REF_ERR_ARG;
+    if (!comp) d = 0;
+    if (vmax) *vmax = 0;
+    int delta = fl_out - fl_in;
+    if (fl_in < FL_MIN || fl_in > FL_MAX || fl_out < FL_MIN || fl_out > FL_MAX ||
+        fl_g < FL_MIN || fl_g > FL_MAX || d < 0 || d > D_MAX ||
+        delta > DELTA_MAX || delta < -DELTA_MAX) {
+        if (status) *status |= STATUS_DOMAIN;
+        return LPK_REF_OK;
+    }
+    const int F = fl_in + d;
+    const int u = delta > 0 ? delta : 0;
+    const int k_theta = d + u - delta;          /* >= d >= 0 */
+    wide vm = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        wide th = load_q(theta, i, theta_bits);
+        wide c  = comp ? load_q(comp, i, comp_bits) : 0;
+        wide g  = load_q(grad, i, grad_bits);
+
+        wide s = rescale_cap(-(wide)lr_q * g, fl_g + 16 - F);
+        if (wd_q) s += rescale_cap(-(wide)lr_q * (wide)wd_q * th, fl_in + 32 - F);
+
+        wide v = th * ((wide)1 << d) + c + s;
+        wide av = v < 0 ? -v : v;
+        if (av > vm) vm = av;
+
+        wide vG  = v * ((wide)1 << u);
+        wide thn = sat(rescale(vG, k_theta), theta_bits);
+        store_q(theta, i, theta_bits, thn);
+        if (comp) {
+            wide r = vG - thn * ((wide)1 << k_theta);
+            store_q(comp, i, comp_bits, sat(rescale(r, k_theta - d), comp_bits));
+        }
+    }
+    if (vmax) *vmax = (uint64_t)vm;
+    return LPK_REF_OK;
+}

@@ -1,0 +1,70 @@
+"""Do the pins bite?  Plant one plausible mistake at a time in a COPY of the oracle source (on the
+CPU), build it, and require that the brute-force / pin tests reject it.  A mutation that survives
+means a hole in the pins."""
+import os
+import subprocess
+
+import pytest
+
+from oracle import ref
+import test_oracle_bruteforce as bf
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(ref.__file__), "lpk_ref.c")
+
+MUTATIONS = [
+    ("ties_away_from_zero", "2 * r > p ||", "2 * r >= p ||"),
+    ("ties_to_odd", "(2 * r == p && (q & 1))", "(2 * r == p && !(q & 1))"),
+    ("floor_of_negatives", "if (r < 0) { r += p; q -= 1; }", "if (r < 0) { r += p; }"),
+    ("step_sign_in_sum", "+ c + s;", "+ c - s;"),
+    ("gradient_sign", "rescale_cap(-(wide)lr_q * g,", "rescale_cap((wide)lr_q * g,"),
+    ("step_grid_forgets_d", "* g, fl_g + 16 - F);", "* g, fl_g + 16 - fl_in);"),
+    ("decay_dropped", "if (wd_q) s +=", "if (0) s +="),
+    ("decay_grid", "* th, fl_in + 32 - F);", "* th, fl_in + 16 - F);"),
+    ("residual_grid", "rescale(r, k_theta - d)", "rescale(r, k_theta)"),
+    ("theta_not_saturated", "wide thn = sat(rescale(vG, k_theta), theta_bits);", "wide thn = rescale(vG, k_theta);"),
+    ("comp_not_saturated", "sat(rescale(r, k_theta - d), comp_bits)", "rescale(r, k_theta - d)"),
+    ("finer_grid_ignored", "const int u = delta > 0 ? delta : 0;", "const int u = 0;"),
+    ("k_theta_sign", "const int k_theta = d + u - delta;", "const int k_theta = d + u + delta;"),
+    ("cap_dropped", "return clampw(rescale(x, k), -CAP40, CAP40);", "return rescale(x, k);"),
+    ("fraclen_off_by_one", "<= qmax_of(bits)) break;", "< qmax_of(bits)) break;"),
+    ("fraclen_ignores_rounding", "if (rescale(m, -(ex + fl)) <= qmax_of(bits)) break;",
+     "if (m * 2 <= (qmax_of(bits) * 2 + 1) * ((wide)1 << ((-(ex + fl)) > 0 && (-(ex+fl)) < 100 ? -(ex+fl) : 0)) && -(ex+fl) > 0) break;"),
+    ("quantize_drops_sign", "rescale(neg ? -m : m, -(ex + fl))", "rescale(m, -(ex + fl))"),
+    ("quantize_fl_sign", "rescale(neg ? -m : m, -(ex + fl))", "rescale(neg ? -m : m, -(ex - fl))"),
+    ("vmax_window", "fl_default + DELTA_MAX) fl = fl_default + DELTA_MAX;", "fl_default + DELTA_MAX) fl = fl_default;"),
+    ("comp_added_twice", "wide c  = comp ? load_q(comp, i, comp_bits) : 0;", "wide c  = comp ? 2 * load_q(comp, i, comp_bits) : 0;"),
+    ("theta_unscaled", "wide v = th * ((wide)1 << d) + c + s;", "wide v = th + c + s;"),
+]
+
+CHECKS = [
+    lambda: bf.test_step_random_domain(0),
+    bf.test_step_typical_shifts,
+    bf.test_step_saturation_and_cap,
+    lambda: bf.test_quantize_bruteforce(8),
+    lambda: bf.test_fraclen_is_largest_non_saturating(8),
+    lambda: bf.test_fraclen_from_vmax_bruteforce(16),
+    lambda: pins.test_quarter_lsb_worked_example(+1),
+    lambda: pins.test_conservation_invariant(8),
+    pins.test_fraclen_hand_cases,
+    pins.test_quantize_hand_cases,
+]
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(name, old, new, tmp_path, monkeypatch):
+    text = open(SRC).read()
+    assert text.count(old) == 1, "mutation anchor must match the oracle source exactly once: %r" % old
+    c = tmp_path / "mut.c"
+    so = tmp_path / ("mut_%s.so" % name)
+    c.write_text(text.replace(old, new))
+    subprocess.check_call(["gcc", "-O1", "-w", "-shared", "-fPIC", "-o", str(so), str(c), "-lm"])
+    monkeypatch.setattr(ref, "_lib", ref.load(str(so)))
+    caught = False
+    for chk in CHECKS:
+        try:
+            chk()
+        except AssertionError:
+            caught = True
+            break
+    assert caught, "mutation %s survived every pin" % name
