@@ -1,0 +1,179 @@
+/*
+ * lpk.h -- C ABI of the MI355X (gfx950) library for the low-precision SGD
+ * parameter update with Kahan summation ("lazy update") over dynamic
+ * fixed-point (DFX) parameters.
+ *
+ * Paper: "Training Deep Neural Network in Limited Precision" (Park et al.).
+ *   Section 2 + Algorithm 1 : the update (an extra accumulation parameter
+ *                             carries the part of each step that the parameter's
+ *                             precision cannot hold).
+ *   Section 2, Figure 1     : parameter, gradient and accumulator on one
+ *                             decimal-point axis; effective width m+n-2-k.
+ *   Section 1               : 8/16-bit dynamic fixed point, uniform linear
+ *                             quantization, no stochastic rounding.
+ *   Section 6               : a tensor's exponent is chosen from its maximum.
+ *
+ * Number format.  DFX(W, fl): a two's-complement integer q of W in {8, 16}
+ * bits standing for q * 2^-fl; fl ("fractional length") is shared by a whole
+ * tensor.  qmax = 2^(W-1)-1, qmin = -2^(W-1).  RNE = round to nearest, ties
+ * to even; sat_W clamps to [qmin, qmax].
+ *
+ * The compensation tensor `comp` holds c = -acc of Algorithm 1, on the grid
+ * fl_theta + d, where d (`comp_shift`) is the distance between the two
+ * decimal points; d = bits(comp) - 1 means no overlapping bit (k = 0).
+ *
+ * Conventions for every call.
+ *   - Return value: LPK_OK (0) or a negative lpk_status_code.  Argument errors
+ *     are detected on the host before anything is launched.
+ *   - Pointers marked "device" are HIP device pointers; everything else is
+ *     host memory.  `stream` is a hipStream_t passed as void* (NULL = the
+ *     default stream).  Work is only enqueued: no call synchronizes, and the
+ *     three hot calls allocate nothing.
+ *   - The caller owns every data buffer, fraclen / vmax / status array and the
+ *     stream.  The library owns only what lpk_tensor_list_create allocates.
+ *   - Data-dependent conditions are not errors: their bits are OR-ed into
+ *     status[0] (device uint32, may be NULL) -- see LPK_STATUS_*.
+ *   - Domain: fraclens in [-64, 64]; 0 <= d <= 24; |fl_out - fl_in| <= 15;
+ *     lr_q16, wd_q16 <= 65535.  A tensor whose device-side fraclens fall
+ *     outside it is skipped untouched and LPK_STATUS_DOMAIN is raised.
+ *   - Calls on one list that overlap in time (different streams) race on the
+ *     list's reduction scratch; serialize them.
+ */
+#ifndef LPK_H
+#define LPK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LPK_OK              =  0,
+  LPK_ERR_INVALID_ARG = -1,  /* NULL where forbidden, bad dtype / selector code, n_tensors == 0,
+                                misaligned pointer, lr/wd above 65535; nothing was launched   */
+  LPK_ERR_UNSUPPORTED = -2,  /* a well-formed request this build does not implement          */
+  LPK_ERR_DEVICE      = -3   /* a HIP runtime call failed (allocation, copy, launch)         */
+} lpk_status_code;
+
+typedef enum { LPK_I8 = 1, LPK_I16 = 2, LPK_F32 = 4, LPK_VMAX_U64 = 8 } lpk_dtype;
+
+/* which member of the descriptor a call reads its width from / writes to */
+typedef enum { LPK_SEL_GRAD = 0, LPK_SEL_THETA = 1 } lpk_selector;
+
+/* bits of the device status word */
+#define LPK_STATUS_NONFINITE 1u  /* a NaN or Inf was met in fp32 input                               */
+#define LPK_STATUS_DOMAIN    2u  /* a fraclen or shift outside the domain; that tensor was skipped   */
+
+#define LPK_COMP_SHIFT_DEFAULT 0xFFu
+
+/* One tensor of the parameter set.  Host array, copied at list creation.
+ * Element pointers must be aligned to their element size; when theta, comp,
+ * grad (and src_f32) are all 16-byte aligned the tensor takes the vector path.
+ * Buffers of one tensor and of different tensors must not overlap. */
+typedef struct {
+  void*       theta;       /* device; DFX ints, updated in place; destination of quantize(LPK_SEL_THETA) */
+  void*       comp;        /* device; DFX ints, updated in place; NULL = plain SGD without the accumulator */
+  const void* grad;        /* device; DFX ints; destination of quantize(LPK_SEL_GRAD)                      */
+  const void* src_f32;     /* device; fp32 source of select_fraclen(LPK_F32) / quantize; may be NULL       */
+  uint64_t    n;           /* elements (0 allowed: the tensor is a no-op)                                  */
+  uint8_t     theta_dtype; /* LPK_I8 or LPK_I16 */
+  uint8_t     comp_dtype;  /* LPK_I8 or LPK_I16 (ignored when comp == NULL) */
+  uint8_t     grad_dtype;  /* LPK_I8 or LPK_I16 */
+  uint8_t     comp_shift;  /* d = fl_comp - fl_theta, 0..24; LPK_COMP_SHIFT_DEFAULT = bits(comp_dtype) - 1 */
+} lpk_tensor_desc;
+
+typedef struct lpk_tensor_list lpk_tensor_list;   /* opaque */
+
+/* Build the multi-tensor list: validates the descriptors, cuts every tensor
+ * into tiles, and uploads the descriptor table, the tile table and the
+ * reduction scratch to the CURRENT device.  Allocates device memory and
+ * synchronizes once.  *out is NULL on failure.
+ * Errors: INVALID_ARG (NULL descs/out, n_tensors == 0, bad dtype, d > 24,
+ * NULL theta/grad with n > 0, pointer not aligned to its element size),
+ * DEVICE. */
+int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk_tensor_list** out);
+
+/* Free what _create allocated.  NULL is accepted.  The caller must have
+ * synchronized every stream that still uses the list. */
+int lpk_tensor_list_destroy(lpk_tensor_list* list);
+
+/* Number of tensors / of tiles in a list (host-side facts, no device access); 0 for NULL. */
+uint32_t lpk_tensor_list_size(const lpk_tensor_list* list);
+uint64_t lpk_tensor_list_tiles(const lpk_tensor_list* list);
+
+/*
+ * Fractional length per tensor from a max-abs reduction (Section 6: the
+ * exponent follows the scanned maximum; Section 1: dynamic fixed point).
+ *
+ *   fl*(M, W) = the largest fl with RNE(M * 2^fl) <= 2^(W-1) - 1, clamped to [-64, 64]:
+ *   the finest grid on which the tensor's own maximum does not saturate.
+ *
+ * W = bits of desc.grad_dtype (dst_sel == LPK_SEL_GRAD) or desc.theta_dtype
+ * (LPK_SEL_THETA).
+ *
+ * src_kind == LPK_F32: M = max_i |desc.src_f32[i]| (src_f32 must be non-NULL
+ *   for every tensor with n > 0).  M == 0 (or n == 0) -> fl_default[t].  Any
+ *   NaN/Inf in the tensor -> -64 and LPK_STATUS_NONFINITE.  vmax and
+ *   fl_theta_in are ignored (may be NULL).
+ *
+ * src_kind == LPK_VMAX_U64: M = vmax[t] * 2^-(fl_theta_in[t] + d_t): the
+ *   running maximum that lpk_kahan_sgd_step wrote when it was called with
+ *   fl_theta_in (d_t = the tensor's comp shift, 0 without comp).  vmax[t] == 0
+ *   -> fl_default[t].  The result is additionally clamped to
+ *   fl_default[t] +- 15, so that it can be handed to the next step as
+ *   fl_theta_out when fl_default is that step's fl_theta_in.
+ *
+ * vmax (uint64), fl_theta_in, fl_default, fl_out (int32): device arrays of
+ * n_tensors entries.  fl_out is written for every tensor.
+ */
+int lpk_select_fraclen(lpk_tensor_list* list, int src_kind, int dst_sel,
+                       const uint64_t* vmax, const int32_t* fl_theta_in, const int32_t* fl_default,
+                       int32_t* fl_out, uint32_t* status, void* stream);
+
+/*
+ * Uniform linear quantization, no stochastic rounding (Section 1):
+ *   dst[i] = sat_W( RNE( src_f32[i] * 2^fl[t] ) )
+ * dst = desc.grad (dst_sel == LPK_SEL_GRAD; written although declared const in
+ * the descriptor, because the update only reads it) or desc.theta
+ * (LPK_SEL_THETA); W from the matching dtype.  NaN -> 0, +-Inf -> qmax/qmin,
+ * both raise LPK_STATUS_NONFINITE.  fl[t] outside [-64, 64]: tensor skipped,
+ * LPK_STATUS_DOMAIN.  fl: device int32[n_tensors].
+ */
+int lpk_quantize_tensor(lpk_tensor_list* list, int dst_sel, const int32_t* fl,
+                        uint32_t* status, void* stream);
+
+/*
+ * One lazy-update step over every tensor of the list in a single fused launch
+ * (Algorithm 1; eq. 1 when comp == NULL).  Per tensor t and element i, with
+ * F = fl_theta_in[t] + d the working grid (units: LSBs of c) and
+ * cap(x) = clamp(x, -2^40, 2^40):
+ *
+ *   s  = cap(RNE(-lr_q16 * g * 2^-(fl_grad[t] + 16 - F)))               step, on c's grid
+ *      + cap(RNE(-lr_q16 * wd_q16 * theta * 2^-(32 - d)))               if wd_q16 != 0
+ *   v  = theta * 2^d + c + s                                            compensated sum, kept wide
+ *   theta' = sat( RNE( v * 2^(fl_theta_out[t] - F) ) )                  the part theta can hold
+ *   c'     = sat( RNE( (v * 2^-F - theta' * 2^-fl_theta_out[t]) * 2^(fl_theta_out[t] + d) ) )   the rest
+ *   vmax_out[t] = max_i |v_i|                                           (on grid F)
+ *
+ * theta leaves the call on grid fl_theta_out[t], comp on fl_theta_out[t] + d.
+ * fl_theta_in, fl_theta_out (may be the same array), fl_grad: device
+ * int32[n_tensors].  vmax_out: device uint64[n_tensors] or NULL; it is
+ * cleared and rewritten by every call.  lr_q16, wd_q16: unsigned Q0.16
+ * (value / 65536), at most 65535; wd_q16 == 0 switches decay off.
+ */
+int lpk_kahan_sgd_step(lpk_tensor_list* list,
+                       const int32_t* fl_theta_in, const int32_t* fl_theta_out, const int32_t* fl_grad,
+                       uint32_t lr_q16, uint32_t wd_q16,
+                       uint64_t* vmax_out, uint32_t* status, void* stream);
+
+/* Static text for a return code ("ok", "invalid argument", ...). Never NULL. */
+const char* lpk_error_string(int code);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int lpk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LPK_H */

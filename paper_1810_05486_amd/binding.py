@@ -1,0 +1,163 @@
+"""Python binding of liblpk.so: the same names as include/lpk.h, argument
+marshalling only.  Device buffers are torch tensors (or raw integer device
+addresses); every step of the path runs inside the library's kernels.
+
+There is no fallback: if the library is missing, the first call raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblpk.so")
+
+LPK_OK, LPK_ERR_INVALID_ARG, LPK_ERR_UNSUPPORTED, LPK_ERR_DEVICE = 0, -1, -2, -3
+LPK_I8, LPK_I16, LPK_F32, LPK_VMAX_U64 = 1, 2, 4, 8
+LPK_SEL_GRAD, LPK_SEL_THETA = 0, 1
+LPK_STATUS_NONFINITE, LPK_STATUS_DOMAIN = 1, 2
+LPK_COMP_SHIFT_DEFAULT = 0xFF
+
+
+class lpk_tensor_desc(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("comp", ctypes.c_void_p), ("grad", ctypes.c_void_p),
+                ("src_f32", ctypes.c_void_p), ("n", ctypes.c_uint64),
+                ("theta_dtype", ctypes.c_uint8), ("comp_dtype", ctypes.c_uint8),
+                ("grad_dtype", ctypes.c_uint8), ("comp_shift", ctypes.c_uint8)]
+
+
+class LpkError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, lib().lpk_error_string(code).decode(), code))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library (loads on first use; raises if it was never built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("liblpk.so is not built (%s); run `python -m paper_1810_05486_amd.build`. "
+                               "There is no CPU fallback." % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u32, u64, ci = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int
+        L.lpk_tensor_list_create.argtypes = [ctypes.POINTER(lpk_tensor_desc), u32, ctypes.POINTER(vp)]
+        L.lpk_tensor_list_destroy.argtypes = [vp]
+        L.lpk_tensor_list_size.argtypes = [vp]
+        L.lpk_tensor_list_size.restype = u32
+        L.lpk_tensor_list_tiles.argtypes = [vp]
+        L.lpk_tensor_list_tiles.restype = u64
+        L.lpk_select_fraclen.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, vp]
+        L.lpk_quantize_tensor.argtypes = [vp, ci, vp, vp, vp]
+        L.lpk_kahan_sgd_step.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
+        L.lpk_error_string.argtypes = [ci]
+        L.lpk_error_string.restype = ctypes.c_char_p
+        L.lpk_version.restype = ci
+        for f in (L.lpk_tensor_list_create, L.lpk_tensor_list_destroy, L.lpk_select_fraclen,
+                  L.lpk_quantize_tensor, L.lpk_kahan_sgd_step):
+            f.restype = ci
+        _lib = L
+    return _lib
+
+
+def _addr(x):
+    """Device address of a torch tensor / raw int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.int8:
+        return LPK_I8
+    if t.dtype == torch.int16:
+        return LPK_I16
+    raise TypeError("DFX tensors are int8 or int16, got %s" % t.dtype)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(rc, where):
+    if rc != LPK_OK:
+        raise LpkError(rc, where)
+
+
+def make_desc(theta, comp, grad, src_f32=None, comp_shift=LPK_COMP_SHIFT_DEFAULT):
+    """Descriptor for one tensor from torch tensors living on the GPU."""
+    d = lpk_tensor_desc()
+    d.theta, d.comp, d.grad, d.src_f32 = _addr(theta), _addr(comp), _addr(grad), _addr(src_f32)
+    d.n = theta.numel()
+    d.theta_dtype = _dtype_code(theta)
+    d.comp_dtype = _dtype_code(comp) if comp is not None else LPK_I8
+    d.grad_dtype = _dtype_code(grad)
+    d.comp_shift = comp_shift
+    return d
+
+
+class TensorList:
+    """Owner of an lpk_tensor_list handle (lpk_tensor_list_create / _destroy)."""
+
+    def __init__(self, descs):
+        arr = (lpk_tensor_desc * len(descs))(*descs)
+        h = ctypes.c_void_p()
+        _check(lib().lpk_tensor_list_create(arr, len(descs), ctypes.byref(h)), "lpk_tensor_list_create")
+        self.handle = h
+        self.n_tensors = len(descs)
+
+    @property
+    def n_tiles(self):
+        return lib().lpk_tensor_list_tiles(self.handle)
+
+    def destroy(self):
+        if self.handle:
+            rc = lib().lpk_tensor_list_destroy(self.handle)
+            self.handle = None
+            _check(rc, "lpk_tensor_list_destroy")
+
+    def __del__(self):
+        try:
+            if getattr(self, "handle", None):
+                lib().lpk_tensor_list_destroy(self.handle)
+                self.handle = None
+        except Exception:
+            pass
+
+
+def lpk_tensor_list_create(descs):
+    return TensorList(descs)
+
+
+def lpk_tensor_list_destroy(tl):
+    tl.destroy()
+
+
+def lpk_select_fraclen(tl, src_kind, dst_sel, vmax, fl_theta_in, fl_default, fl_out, status=None, stream=None):
+    _check(lib().lpk_select_fraclen(tl.handle, src_kind, dst_sel, _addr(vmax), _addr(fl_theta_in), _addr(fl_default),
+                                    _addr(fl_out), _addr(status), _stream(stream)), "lpk_select_fraclen")
+
+
+def lpk_quantize_tensor(tl, dst_sel, fl, status=None, stream=None):
+    _check(lib().lpk_quantize_tensor(tl.handle, dst_sel, _addr(fl), _addr(status), _stream(stream)),
+           "lpk_quantize_tensor")
+
+
+def lpk_kahan_sgd_step(tl, fl_theta_in, fl_theta_out, fl_grad, lr_q16, wd_q16=0, vmax_out=None, status=None,
+                       stream=None):
+    _check(lib().lpk_kahan_sgd_step(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_grad),
+                                    int(lr_q16), int(wd_q16), _addr(vmax_out), _addr(status), _stream(stream)),
+           "lpk_kahan_sgd_step")
+
+
+def lpk_version():
+    return lib().lpk_version()

@@ -1,0 +1,376 @@
+// Fused lazy-update kernel (Algorithm 1 of the paper, Section 2): one launch
+// walks every tile of every tensor of a list.
+//
+// Work distribution: a persistent grid of wavefronts; wave w takes tiles
+// w, w + W, w + 2W, ... of the tile table, so at any moment the grid streams
+// one contiguous window of the parameter set.  A tile is 4096 elements of one
+// tensor; a lane handles 16 consecutive elements per pass (one dwordx4 of int8
+// theta, one of comp, two of int16 grad), four passes per tile with all loads
+// issued before the arithmetic.
+//
+// Arithmetic: two paths with identical results.
+//   * generic: 64-bit integers, any widths / shifts / grid move / decay /
+//     no-accumulator mode inside the documented domain;
+//   * fast: 32-bit, chosen per tensor when the shifts allow it.  The step
+//     RNE(-lr*g / 2^k) is ONE fp32 fused multiply-add: g and lr are exact in
+//     fp32, the FMA forms their product exactly and adds 1.5*2^(23+k), whose
+//     ulp is 2^k, so the single IEEE rounding of the FMA *is* the
+//     round-to-nearest-even at bit k and the integer falls out of the
+//     significand bits.  The decay term uses the same construction in fp64.
+//
+// Running maximum of |v| per tensor: per-lane max, DPP wave reduction when a
+// wave moves to another tensor, LDS stage across the four waves of a block at
+// the end, one atomic per (block, tensor).
+#include "lpk_device.hpp"
+
+namespace lpk {
+
+struct StepParams {
+  int      path;            // 0 skip, 1 generic, 2 fast
+  int      wt, wc, wg, d;
+  int      has_comp;
+  int      kg;              // shift of the gradient term: fl_g + 16 - F
+  int      kw;              // shift of the decay term: 32 - d
+  int      u, kth, kc;      // grid move: v_G = v << u; theta' = RNE(v_G >> kth); c' = RNE(r >> kc)
+  int64_t  lr, lrwd;
+  int      qmin_t, qmax_t, qmin_c, qmax_c;
+  // fast path constants
+  float    nlr_f;  float magic_f;  int magic_fi;
+  double   nlrwd_d; double magic_d; int magic_dlo;
+  int      half_m1;         // 2^(d-1) - 1
+};
+
+// ---------------------------------------------------------------- generic (int64)
+
+__device__ __forceinline__ int64_t rne_shr64(int64_t x, int k)      // RNE(x / 2^k), 0 <= k <= 62
+{
+  if (k == 0) return x;
+  int64_t  q    = x >> k;
+  uint64_t rem  = (uint64_t)x & ((1ull << k) - 1ull);
+  uint64_t half = 1ull << (k - 1);
+  return q + (int64_t)((rem > half) | ((rem == half) & (uint64_t)(q & 1)));
+}
+
+__device__ __forceinline__ int64_t rescale_cap64(int64_t x, int k)   // |x| < 2^48; clamp(RNE(x * 2^-k), +-2^40)
+{
+  const int64_t cap = 1ll << 40;
+  if (x == 0) return 0;
+  if (k > 0) {
+    if (k >= 50) return 0;
+    int64_t q = rne_shr64(x, k);
+    return q > cap ? cap : (q < -cap ? -cap : q);
+  }
+  int sh = -k;
+  if (sh >= 41) return x > 0 ? cap : -cap;
+  int64_t lim = cap >> sh;
+  if (x > lim) return cap;
+  if (x < -lim) return -cap;
+  return x * (1ll << sh);
+}
+
+__device__ __forceinline__ void update_generic(const StepParams& p, int64_t th, int64_t c, int64_t g,
+                                               int& th_new, int& c_new, uint64_t& vabs)
+{
+  int64_t s = rescale_cap64(-p.lr * g, p.kg);
+  if (p.lrwd) s += rescale_cap64(-p.lrwd * th, p.kw);
+  int64_t v = th * (1ll << p.d) + c + s;
+  vabs = (uint64_t)(v < 0 ? -v : v);
+  int64_t vG = v * (1ll << p.u);
+  int64_t tn = rne_shr64(vG, p.kth);
+  tn = tn > p.qmax_t ? p.qmax_t : (tn < p.qmin_t ? p.qmin_t : tn);
+  int64_t r  = vG - tn * (1ll << p.kth);
+  int64_t cn = rne_shr64(r, p.kc);
+  cn = cn > p.qmax_c ? p.qmax_c : (cn < p.qmin_c ? p.qmin_c : cn);
+  th_new = (int)tn; c_new = (int)cn;
+}
+
+__device__ __forceinline__ int load_elem(const void* p, uint64_t i, int bits)
+{
+  return bits == 8 ? (int)((const int8_t*)p)[i] : (int)((const int16_t*)p)[i];
+}
+__device__ __forceinline__ void store_elem(void* p, uint64_t i, int bits, int v)
+{
+  if (bits == 8) ((int8_t*)p)[i] = (int8_t)v; else ((int16_t*)p)[i] = (int16_t)v;
+}
+
+// Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
+__device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane)
+{
+  uint64_t vm = 0;
+  for (uint32_t j = lane; j < cnt; j += kWave) {
+    uint64_t i = off + j;
+    int th = load_elem(T.theta, i, p.wt);
+    int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
+    int g  = load_elem(T.grad, i, p.wg);
+    int tn, cn; uint64_t va;
+    update_generic(p, th, c, g, tn, cn, va);
+    vm = va > vm ? va : vm;
+    store_elem(T.theta, i, p.wt, tn);
+    if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
+  }
+  return vm;
+}
+
+// ---------------------------------------------------------------- fast (int32 + FMA rounding)
+
+template <bool DECAY>
+__device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, int g, int& tn, int& cn, int& vmx, int& vmn)
+{
+  int s = __float_as_int(__builtin_fmaf((float)g, p.nlr_f, p.magic_f)) - p.magic_fi;
+  if (DECAY) {
+    double r = __builtin_fma((double)th, p.nlrwd_d, p.magic_d);
+    s += __double2loint(r) - p.magic_dlo;
+  }
+  int v = (th << p.d) + c + s;          // th << d on a negative th: two's complement, what the hardware does
+  vmx = v > vmx ? v : vmx;
+  vmn = v < vmn ? v : vmn;
+  int q = (v + p.half_m1 + ((v >> p.d) & 1)) >> p.d;      // RNE(v / 2^d), d >= 1, no overflow by path choice
+  tn = min(max(q, p.qmin_t), p.qmax_t);
+  int r = v - (tn << p.d);
+  cn = min(max(r, p.qmin_c), p.qmax_c);
+}
+
+template <typename V> __device__ __forceinline__ V ld_stream(const V* p) { return __builtin_nontemporal_load(p); }
+template <typename V> __device__ __forceinline__ void st_stream(V* p, V v) { __builtin_nontemporal_store(v, p); }
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// 16 consecutive elements per lane; W = width of theta and comp (8 or 16), grads int16.
+template <int W> struct Group;
+template <> struct Group<8>  { v4i th;      v4i c;      v4i g[2]; };
+template <> struct Group<16> { v4i th[2];   v4i c[2];   v4i g[2]; };
+
+__device__ __forceinline__ void load_group(Group<8>& G, const TensorDev& T, uint64_t e)
+{
+  G.th   = ld_stream((const v4i*)((const int8_t*)T.theta + e));
+  G.c    = ld_stream((const v4i*)((const int8_t*)T.comp + e));
+  G.g[0] = ld_stream((const v4i*)((const int16_t*)T.grad + e));
+  G.g[1] = ld_stream((const v4i*)((const int16_t*)T.grad + e + 8));
+}
+__device__ __forceinline__ void load_group(Group<16>& G, const TensorDev& T, uint64_t e)
+{
+  G.th[0] = ld_stream((const v4i*)((const int16_t*)T.theta + e));
+  G.th[1] = ld_stream((const v4i*)((const int16_t*)T.theta + e + 8));
+  G.c[0]  = ld_stream((const v4i*)((const int16_t*)T.comp + e));
+  G.c[1]  = ld_stream((const v4i*)((const int16_t*)T.comp + e + 8));
+  G.g[0]  = ld_stream((const v4i*)((const int16_t*)T.grad + e));
+  G.g[1]  = ld_stream((const v4i*)((const int16_t*)T.grad + e + 8));
+}
+
+__device__ __forceinline__ int sx8(int w, int b)  { return (int)(int8_t)(w >> (8 * b)); }
+__device__ __forceinline__ int sx16(int w, int h) { return (int)(int16_t)(w >> (16 * h)); }
+
+template <bool DECAY>
+__device__ __forceinline__ void compute_store_group(const StepParams& p, Group<8>& G, const TensorDev& T, uint64_t e, int& vmx, int& vmn)
+{
+  v4i to, co;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    uint32_t tw = 0, cw = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      int k = w * 4 + b;                     // element within the group
+      int th = sx8(G.th[w], b), c = sx8(G.c[w], b), g = sx16(G.g[k >> 3][(k >> 1) & 3], k & 1);
+      int tn, cn;
+      update_fast<DECAY>(p, th, c, g, tn, cn, vmx, vmn);
+      tw |= (uint32_t)(tn & 0xff) << (8 * b);
+      cw |= (uint32_t)(cn & 0xff) << (8 * b);
+    }
+    to[w] = (int)tw; co[w] = (int)cw;
+  }
+  st_stream((v4i*)((int8_t*)T.theta + e), to);
+  st_stream((v4i*)((int8_t*)T.comp + e), co);
+}
+
+template <bool DECAY>
+__device__ __forceinline__ void compute_store_group(const StepParams& p, Group<16>& G, const TensorDev& T, uint64_t e, int& vmx, int& vmn)
+{
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    v4i to, co;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      uint32_t tw = 0, cw = 0;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        int th = sx16(G.th[q][w], h), c = sx16(G.c[q][w], h), g = sx16(G.g[q][w], h);
+        int tn, cn;
+        update_fast<DECAY>(p, th, c, g, tn, cn, vmx, vmn);
+        tw |= (uint32_t)(tn & 0xffff) << (16 * h);
+        cw |= (uint32_t)(cn & 0xffff) << (16 * h);
+      }
+      to[w] = (int)tw; co[w] = (int)cw;
+    }
+    st_stream((v4i*)((int16_t*)T.theta + e + 8 * q), to);
+    st_stream((v4i*)((int16_t*)T.comp + e + 8 * q), co);
+  }
+}
+
+// Vector tile: full 16-element groups with the fast arithmetic, the ragged end element by element.
+template <int W, bool DECAY>
+__device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane)
+{
+  int vmx = 0, vmn = 0;
+  const uint32_t ngroups = cnt / kGroup;
+  if (ngroups == kWave * kPasses) {                       // full tile: every load issued before any arithmetic
+    Group<W> G[kPasses];
+#pragma unroll
+    for (int ps = 0; ps < kPasses; ++ps) load_group(G[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup);
+#pragma unroll
+    for (int ps = 0; ps < kPasses; ++ps)
+      compute_store_group<DECAY>(p, G[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup, vmx, vmn);
+  } else {
+    for (uint32_t gi = lane; gi < ngroups; gi += kWave) {
+      Group<W> G;
+      uint64_t e = off + (uint64_t)gi * kGroup;
+      load_group(G, T, e);
+      compute_store_group<DECAY>(p, G, T, e, vmx, vmn);
+    }
+  }
+  int64_t a = vmx, b = -(int64_t)vmn;
+  uint64_t vm = (uint64_t)(a > b ? a : b);
+  const uint32_t tail = cnt - ngroups * kGroup;           // < 16 elements
+  if (tail) {
+    uint64_t t2 = tile_generic(p, T, off + (uint64_t)ngroups * kGroup, tail, lane);
+    vm = t2 > vm ? t2 : vm;
+  }
+  return vm;
+}
+
+// ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
+
+__device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, int fl_in, int fl_out, int fl_g,
+                                             uint32_t lr, uint32_t wd, uint32_t& status_bits)
+{
+  p.wt = T.wt; p.wc = T.wc; p.wg = T.wg; p.has_comp = T.comp != nullptr;
+  p.d = p.has_comp ? T.d : 0;
+  const int delta = fl_out - fl_in;
+  if (fl_in < kFlMin || fl_in > kFlMax || fl_out < kFlMin || fl_out > kFlMax || fl_g < kFlMin || fl_g > kFlMax ||
+      p.d > kDMax || delta > kDeltaMax || delta < -kDeltaMax) {
+    p.path = 0; status_bits |= kStatusDomain; return;
+  }
+  const int F = fl_in + p.d;
+  p.kg = fl_g + 16 - F;
+  p.kw = 32 - p.d;
+  p.u = delta > 0 ? delta : 0;
+  p.kth = p.d + p.u - delta;
+  p.kc = p.kth - p.d;
+  p.lr = lr; p.lrwd = (int64_t)lr * (int64_t)wd;
+  p.qmax_t = (1 << (p.wt - 1)) - 1; p.qmin_t = -(1 << (p.wt - 1));
+  const int wc = p.has_comp ? p.wc : 8;
+  p.qmax_c = (1 << (wc - 1)) - 1;   p.qmin_c = -(1 << (wc - 1));
+  p.path = 1;
+
+  // Fast path: same-width theta/comp with int16 grads on 16-byte aligned buffers, no grid move,
+  // 1 <= d, step shift >= 9 (so the fp32 FMA rounding trick is exact and |s| <= 2^22 + 1),
+  // and every intermediate provably inside int32.
+  if (!p.has_comp || !T.vec_step || p.wt != p.wc || p.wg != 16 || delta != 0 || p.d < 1 || p.kg < 9) return;
+  int64_t bound = (1ll << (p.wt - 1 + p.d)) + (1ll << (p.wc - 1));             // |theta * 2^d| + |c|
+  bound += p.kg < 32 ? (1ll << (31 - p.kg)) + 1 : 0;                            // |s_g|
+  int64_t sw = 0;
+  if (p.lrwd) sw = ((p.lrwd << (p.wt - 1)) >> p.kw) + 1;                        // |s_w|
+  bound += sw;
+  bound += 1ll << (p.d - 1);                                                    // the rounding addend
+  if (bound >= (1ll << 31)) return;
+  p.path = 2;
+  const int kg = p.kg > 40 ? 40 : p.kg;                                         // k >= 32 already gives s = 0
+  p.magic_fi = ((127 + 23 + kg) << 23) | 0x400000;                              // 1.5 * 2^(23 + k)
+  p.magic_f  = __int_as_float(p.magic_fi);
+  p.nlr_f    = -(float)lr;
+  const long long md = ((long long)(1023 + 52 + p.kw) << 52) | (1ll << 51);     // 1.5 * 2^(52 + kw)
+  p.magic_d   = __longlong_as_double(md);
+  p.magic_dlo = (int)(md & 0xffffffffll);
+  p.nlrwd_d   = -(double)p.lrwd;
+  p.half_m1   = (1 << (p.d - 1)) - 1;
+}
+
+// ---------------------------------------------------------------- the kernel
+
+__device__ __forceinline__ void flush_wave(uint64_t* vmax, int tensor, uint64_t lane_max, int lane)
+{
+  uint64_t m = wave_max_u64(lane_max);
+  if (lane == 0 && m) atomicMax((unsigned long long*)&vmax[tensor], (unsigned long long)m);
+}
+
+__global__ void __launch_bounds__(kBlock)
+kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
+                  const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out, const int32_t* __restrict__ fl_g,
+                  uint32_t lr, uint32_t wd, uint64_t* vmax, uint32_t* status)
+{
+  __shared__ int      s_tensor[kWavesPerBlock];
+  __shared__ uint64_t s_max[kWavesPerBlock];
+
+  const int lane   = threadIdx.x & (kWave - 1);
+  const int wave   = wave_uniform(threadIdx.x >> 6);
+  const uint32_t w0 = blockIdx.x * kWavesPerBlock + wave;
+  const uint32_t nw = gridDim.x * kWavesPerBlock;
+
+  int cur = -1;
+  uint64_t lane_max = 0;
+  uint32_t status_bits = 0;
+  StepParams p; p.path = 0;
+  TensorDev T;
+
+  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
+    const Tile tl = tiles[ti];
+    const int t = wave_uniform((int)tl.tensor);
+    const uint32_t cnt = (uint32_t)wave_uniform((int)tl.count);
+    const uint64_t off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
+    if (t != cur) {
+      if (cur >= 0 && vmax) flush_wave(vmax, cur, lane_max, lane);
+      lane_max = 0;
+      cur = t;
+      T = tensors[t];
+      setup_tensor(p, T, fl_in[t], fl_out[t], fl_g[t], lr, wd, status_bits);
+    }
+    uint64_t vm = 0;
+    if (p.path == 2) {
+      if (p.wt == 8) vm = p.lrwd ? tile_fast<8, true>(p, T, off, cnt, lane)  : tile_fast<8, false>(p, T, off, cnt, lane);
+      else           vm = p.lrwd ? tile_fast<16, true>(p, T, off, cnt, lane) : tile_fast<16, false>(p, T, off, cnt, lane);
+    } else if (p.path == 1) {
+      vm = tile_generic(p, T, off, cnt, lane);
+    }
+    lane_max = vm > lane_max ? vm : lane_max;
+  }
+
+  if (status && status_bits && lane == 0) atomicOr(status, status_bits);
+
+  // LDS stage: the four waves of a block usually end on the same tensor.
+  if (vmax) {
+    uint64_t m = wave_max_u64(lane_max);
+    if (lane == 0) { s_tensor[wave] = cur; s_max[wave] = m; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int a = 0; a < kWavesPerBlock; ++a) {
+        int ta = s_tensor[a];
+        if (ta < 0) continue;
+        uint64_t ma = s_max[a];
+        for (int b = a + 1; b < kWavesPerBlock; ++b)
+          if (s_tensor[b] == ta) { ma = s_max[b] > ma ? s_max[b] : ma; s_tensor[b] = -1; }
+        if (ma) atomicMax((unsigned long long*)&vmax[ta], (unsigned long long)ma);
+      }
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kBlock) fill_u64_kernel(uint64_t* p, uint32_t n, uint64_t v)
+{
+  uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+hipError_t launch_kahan_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
+                             const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_g, uint32_t lr, uint32_t wd,
+                             uint64_t* vmax, uint32_t* status, hipStream_t stream)
+{
+  if (vmax) {
+    hipLaunchKernelGGL(fill_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, n_tensors, 0ull);
+  }
+  if (n_tiles) {
+    hipLaunchKernelGGL(kahan_step_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                       fl_in, fl_out, fl_g, lr, wd, vmax, status);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace lpk

@@ -1,0 +1,70 @@
+// Shared between the host layer and the gfx950 kernels of liblpk: device-side
+// tables, launch geometry and wavefront reductions.  Nothing here is used by
+// the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lpk {
+
+constexpr int kWave           = 64;     // CDNA wavefront
+constexpr int kWavesPerBlock  = 4;
+constexpr int kBlock          = kWave * kWavesPerBlock;
+constexpr int kGroup          = 16;     // elements one lane handles per pass (one dwordx4 of int8)
+constexpr int kPassElems      = kWave * kGroup;          // 1024 elements per wave pass
+constexpr int kPasses         = 4;
+constexpr int kTileElems      = kPassElems * kPasses;    // 4096 elements per wave tile
+
+constexpr int kFlMin = -64, kFlMax = 64, kDMax = 24, kDeltaMax = 15;
+constexpr uint32_t kStatusNonFinite = 1u, kStatusDomain = 2u;
+
+// One tensor, as the kernels see it (64 bytes, read with scalar loads).
+struct TensorDev {
+  void*       theta;
+  void*       comp;      // nullptr: no accumulator
+  void*       grad;
+  const void* src;       // fp32 source
+  uint64_t    n;
+  uint8_t     wt, wc, wg, d;        // widths in bits (wc = 0 without comp), comp shift
+  uint8_t     vec_step, vec_src_grad, vec_src_theta, pad0;   // 16-byte alignment facts
+  uint32_t    pad1[4];
+};
+static_assert(sizeof(TensorDev) == 64, "descriptor layout");
+
+// One wave-sized piece of one tensor.
+struct Tile {
+  uint32_t tensor;
+  uint32_t count;        // 1..kTileElems elements
+  uint64_t offset;       // first element, a multiple of kTileElems
+};
+static_assert(sizeof(Tile) == 16, "tile layout");
+
+// ---- wavefront max over unsigned 32-bit values, via DPP -------------------
+// Row shifts build the maximum of each 16-lane row in its last lane, two row
+// broadcasts carry it across rows; lane 63 ends with the wave maximum.
+// Out-of-range and masked lanes contribute 0, the identity of unsigned max.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+  uint32_t t;
+  t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, true);  v = v > t ? v : t;   // row_shr:1
+  t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, true);  v = v > t ? v : t;   // row_shr:2
+  t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, true);  v = v > t ? v : t;   // row_shr:4
+  t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, true);  v = v > t ? v : t;   // row_shr:8
+  t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, true);  v = v > t ? v : t;   // row_bcast:15 -> rows 1,3
+  t = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, true);  v = v > t ? v : t;   // row_bcast:31 -> rows 2,3
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// 64-bit unsigned wave max: high halves first, then the low halves of the
+// lanes that hold the winning high half.
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
+{
+  uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+  uint32_t mh = wave_max_u32(hi);
+  uint32_t ml = wave_max_u32(hi == mh ? lo : 0u);
+  return ((uint64_t)mh << 32) | ml;
+}
+
+__device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+}  // namespace lpk

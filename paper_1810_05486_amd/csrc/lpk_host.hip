@@ -1,0 +1,195 @@
+// Host layer of liblpk: the C ABI declared in include/lpk.h.  Validates
+// arguments, owns the per-list device tables, and enqueues the kernels.
+#include "../../include/lpk.h"
+#include "lpk_device.hpp"
+
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+namespace lpk {
+hipError_t launch_kahan_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
+                             const int32_t*, const int32_t*, const int32_t*, uint32_t lr, uint32_t wd,
+                             uint64_t* vmax, uint32_t* status, hipStream_t);
+hipError_t launch_select_f32(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
+                             int use_theta_width, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
+                             uint32_t* status, hipStream_t);
+hipError_t launch_select_vmax(const TensorDev*, uint32_t n_tensors, int use_theta_width, const uint64_t* vmax,
+                              const int32_t* fl_theta_in, const int32_t* fl_default, int32_t* fl_out, uint32_t* status,
+                              hipStream_t);
+hipError_t launch_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t grid, int to_theta,
+                           const int32_t* fl, uint32_t* status, hipStream_t);
+}  // namespace lpk
+
+using namespace lpk;
+
+struct lpk_tensor_list {
+  uint32_t   n_tensors = 0;
+  uint32_t   n_tiles   = 0;
+  int        device    = 0;
+  uint32_t   grid      = 0;        // blocks of the persistent launches
+  bool       all_src   = false;    // every non-empty tensor has an fp32 source
+  TensorDev* d_tensors = nullptr;
+  Tile*      d_tiles   = nullptr;
+  uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls
+};
+
+static int dtype_bits(uint8_t dt) { return dt == LPK_I8 ? 8 : (dt == LPK_I16 ? 16 : 0); }
+static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+static uint32_t env_u32(const char* name, uint32_t dflt)
+{
+  const char* s = std::getenv(name);
+  if (!s || !*s) return dflt;
+  char* end = nullptr;
+  unsigned long v = std::strtoul(s, &end, 10);
+  return (end && *end == 0 && v > 0 && v < (1ul << 20)) ? (uint32_t)v : dflt;
+}
+
+extern "C" {
+
+int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk_tensor_list** out)
+{
+  if (out) *out = nullptr;
+  if (!descs || !out || n_tensors == 0) return LPK_ERR_INVALID_ARG;
+
+  std::vector<TensorDev> tensors(n_tensors);
+  std::vector<Tile> tiles;
+  bool all_src = true;
+  uint64_t total_tiles = 0;
+  for (uint32_t t = 0; t < n_tensors; ++t) {
+    const lpk_tensor_desc& D = descs[t];
+    const int wt = dtype_bits(D.theta_dtype), wg = dtype_bits(D.grad_dtype);
+    const int wc = D.comp ? dtype_bits(D.comp_dtype) : 0;
+    if (!wt || !wg || (D.comp && !wc)) return LPK_ERR_INVALID_ARG;
+    int d = 0;
+    if (D.comp) {
+      d = D.comp_shift == LPK_COMP_SHIFT_DEFAULT ? wc - 1 : (int)D.comp_shift;
+      if (d > kDMax) return LPK_ERR_INVALID_ARG;
+    }
+    if (D.n && (!D.theta || !D.grad)) return LPK_ERR_INVALID_ARG;
+    if (!aligned(D.theta, wt / 8) || !aligned(D.grad, wg / 8) || (D.comp && !aligned(D.comp, wc / 8)) ||
+        !aligned(D.src_f32, 4)) return LPK_ERR_INVALID_ARG;
+    if (D.n && !D.src_f32) all_src = false;
+
+    TensorDev& T = tensors[t];
+    T = TensorDev{};
+    T.theta = D.theta; T.comp = D.comp; T.grad = const_cast<void*>(D.grad); T.src = D.src_f32; T.n = D.n;
+    T.wt = (uint8_t)wt; T.wc = (uint8_t)wc; T.wg = (uint8_t)wg; T.d = (uint8_t)d;
+    T.vec_step      = aligned(D.theta, 16) && aligned(D.grad, 16) && D.comp && aligned(D.comp, 16);
+    T.vec_src_grad  = D.src_f32 && aligned(D.src_f32, 16) && aligned(D.grad, 16);
+    T.vec_src_theta = D.src_f32 && aligned(D.src_f32, 16) && aligned(D.theta, 16);
+    total_tiles += (D.n + kTileElems - 1) / kTileElems;
+  }
+  if (total_tiles >= (1ull << 31)) return LPK_ERR_UNSUPPORTED;
+  tiles.reserve((size_t)total_tiles);
+  for (uint32_t t = 0; t < n_tensors; ++t)
+    for (uint64_t off = 0; off < descs[t].n; off += kTileElems) {
+      const uint64_t left = descs[t].n - off;
+      tiles.push_back(Tile{t, (uint32_t)(left < (uint64_t)kTileElems ? left : (uint64_t)kTileElems), off});
+    }
+
+  lpk_tensor_list* L = new (std::nothrow) lpk_tensor_list;
+  if (!L) return LPK_ERR_DEVICE;
+  L->n_tensors = n_tensors;
+  L->n_tiles = (uint32_t)tiles.size();
+  L->all_src = all_src;
+
+  hipDeviceProp_t prop;
+  bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
+  if (ok) {
+    // Persistent grid: enough resident waves per CU to cover HBM latency, never more blocks than tile quads.
+    const uint32_t per_cu = env_u32("LPK_BLOCKS_PER_CU", 8);
+    uint32_t grid = (uint32_t)prop.multiProcessorCount * per_cu;
+    const uint32_t need = (L->n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (grid > need) grid = need;
+    if (grid == 0) grid = 1;
+    L->grid = grid;
+    ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
+         hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * n_tensors) == hipSuccess &&
+         (tiles.empty() || hipMalloc((void**)&L->d_tiles, sizeof(Tile) * tiles.size()) == hipSuccess);
+  }
+  if (ok) {
+    ok = hipMemcpy(L->d_tensors, tensors.data(), sizeof(TensorDev) * n_tensors, hipMemcpyHostToDevice) == hipSuccess &&
+         hipMemset(L->d_scratch, 0, sizeof(uint32_t) * n_tensors) == hipSuccess &&
+         (tiles.empty() || hipMemcpy(L->d_tiles, tiles.data(), sizeof(Tile) * tiles.size(), hipMemcpyHostToDevice) == hipSuccess) &&
+         hipDeviceSynchronize() == hipSuccess;
+  }
+  if (!ok) {
+    (void)hipGetLastError();
+    lpk_tensor_list_destroy(L);
+    return LPK_ERR_DEVICE;
+  }
+  *out = L;
+  return LPK_OK;
+}
+
+int lpk_tensor_list_destroy(lpk_tensor_list* L)
+{
+  if (!L) return LPK_OK;
+  bool ok = true;
+  if (L->d_tensors) ok &= hipFree(L->d_tensors) == hipSuccess;
+  if (L->d_tiles)   ok &= hipFree(L->d_tiles) == hipSuccess;
+  if (L->d_scratch) ok &= hipFree(L->d_scratch) == hipSuccess;
+  delete L;
+  return ok ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+uint32_t lpk_tensor_list_size(const lpk_tensor_list* L) { return L ? L->n_tensors : 0; }
+uint64_t lpk_tensor_list_tiles(const lpk_tensor_list* L) { return L ? L->n_tiles : 0; }
+
+int lpk_select_fraclen(lpk_tensor_list* L, int src_kind, int dst_sel,
+                       const uint64_t* vmax, const int32_t* fl_theta_in, const int32_t* fl_default,
+                       int32_t* fl_out, uint32_t* status, void* stream)
+{
+  if (!L || !fl_default || !fl_out) return LPK_ERR_INVALID_ARG;
+  if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA) return LPK_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (src_kind == LPK_F32) {
+    if (!L->all_src) return LPK_ERR_INVALID_ARG;
+    e = launch_select_f32(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, dst_sel == LPK_SEL_THETA,
+                          L->d_scratch, fl_default, fl_out, status, s);
+  } else if (src_kind == LPK_VMAX_U64) {
+    if (!vmax || !fl_theta_in) return LPK_ERR_INVALID_ARG;
+    e = launch_select_vmax(L->d_tensors, L->n_tensors, dst_sel == LPK_SEL_THETA, vmax, fl_theta_in, fl_default, fl_out, status, s);
+  } else {
+    return LPK_ERR_INVALID_ARG;
+  }
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+int lpk_quantize_tensor(lpk_tensor_list* L, int dst_sel, const int32_t* fl, uint32_t* status, void* stream)
+{
+  if (!L || !fl) return LPK_ERR_INVALID_ARG;
+  if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA) return LPK_ERR_INVALID_ARG;
+  if (!L->all_src) return LPK_ERR_INVALID_ARG;
+  hipError_t e = launch_quantize(L->d_tensors, L->d_tiles, L->n_tiles, L->grid, dst_sel == LPK_SEL_THETA, fl, status,
+                                 static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t* fl_theta_out, const int32_t* fl_grad,
+                       uint32_t lr_q16, uint32_t wd_q16, uint64_t* vmax_out, uint32_t* status, void* stream)
+{
+  if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
+  if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
+  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, fl_theta_in, fl_theta_out,
+                                   fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+const char* lpk_error_string(int code)
+{
+  switch (code) {
+    case LPK_OK:              return "ok";
+    case LPK_ERR_INVALID_ARG: return "invalid argument";
+    case LPK_ERR_UNSUPPORTED: return "unsupported request";
+    case LPK_ERR_DEVICE:      return "HIP runtime failure";
+    default:                  return "unknown lpk status code";
+  }
+}
+
+int lpk_version(void) { return 100; }
+
+}  // extern "C"

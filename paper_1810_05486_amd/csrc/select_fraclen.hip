@@ -1,0 +1,173 @@
+// Fractional length per tensor from a max-abs reduction (paper, Section 6: the
+// exponent follows the scanned maximum of the tensor; Section 1: dynamic fixed
+// point).  Rule: the largest fl at which the maximum still rounds to a code
+// <= qmax, i.e. the finest grid on which the tensor's own maximum does not
+// saturate.
+//
+// fp32 source: |x| of a finite float is ordered like its bit pattern with the
+// sign cleared, and every NaN/Inf pattern is >= 0x7f800000, so the reduction is
+// an unsigned integer max over (bits & 0x7fffffff): per-lane max, DPP wave max,
+// LDS across the waves of a block, one atomic per (block, tensor).  A second
+// small kernel turns each maximum into a fraclen in closed form and re-arms the
+// scratch word for the next call.
+#include "lpk_device.hpp"
+
+namespace lpk {
+
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t absbits(uint32_t b) { return b & 0x7fffffffu; }
+
+__global__ void __launch_bounds__(kBlock)
+maxabs_f32_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles, uint32_t* scratch)
+{
+  __shared__ int      s_tensor[kWavesPerBlock];
+  __shared__ uint32_t s_max[kWavesPerBlock];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = wave_uniform(threadIdx.x >> 6);
+  const uint32_t w0 = blockIdx.x * kWavesPerBlock + wave;
+  const uint32_t nw = gridDim.x * kWavesPerBlock;
+
+  int cur = -1;
+  uint32_t lane_max = 0;
+  const float* src = nullptr;
+  bool vec = false;
+
+  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
+    const Tile tl = tiles[ti];
+    const int t = wave_uniform((int)tl.tensor);
+    const uint32_t cnt = (uint32_t)wave_uniform((int)tl.count);
+    const uint64_t off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
+    if (t != cur) {
+      if (cur >= 0) {
+        uint32_t m = wave_max_u32(lane_max);
+        if (lane == 0 && m) atomicMax(&scratch[cur], m);
+      }
+      lane_max = 0;
+      cur = t;
+      src = (const float*)tensors[t].src;
+      vec = (((uintptr_t)src) & 15u) == 0;
+    }
+    const uint32_t* s = (const uint32_t*)src + off;
+    if (vec) {
+      // max is order-free: lane l takes the 16-byte pieces l, l+64, ... so every load instruction is fully coalesced
+      const uint32_t nv = cnt / 4;
+      if (nv == kTileElems / 4) {
+        v4u a[kTileElems / 4 / kWave];
+#pragma unroll
+        for (int j = 0; j < kTileElems / 4 / kWave; ++j) a[j] = __builtin_nontemporal_load((const v4u*)s + j * kWave + lane);
+#pragma unroll
+        for (int j = 0; j < kTileElems / 4 / kWave; ++j) {
+          uint32_t m01 = max(absbits(a[j][0]), absbits(a[j][1])), m23 = max(absbits(a[j][2]), absbits(a[j][3]));
+          lane_max = max(lane_max, max(m01, m23));
+        }
+      } else {
+        for (uint32_t j = lane; j < nv; j += kWave) {
+          v4u a = __builtin_nontemporal_load((const v4u*)s + j);
+          lane_max = max(lane_max, max(max(absbits(a[0]), absbits(a[1])), max(absbits(a[2]), absbits(a[3]))));
+        }
+        for (uint32_t j = nv * 4 + lane; j < cnt; j += kWave) lane_max = max(lane_max, absbits(s[j]));
+      }
+    } else {
+      for (uint32_t j = lane; j < cnt; j += kWave) lane_max = max(lane_max, absbits(s[j]));
+    }
+  }
+
+  uint32_t m = wave_max_u32(lane_max);
+  if (lane == 0) { s_tensor[wave] = cur; s_max[wave] = m; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int a = 0; a < kWavesPerBlock; ++a) {
+      int ta = s_tensor[a];
+      if (ta < 0) continue;
+      uint32_t ma = s_max[a];
+      for (int b = a + 1; b < kWavesPerBlock; ++b)
+        if (s_tensor[b] == ta) { ma = max(ma, s_max[b]); s_tensor[b] = -1; }
+      if (ma) atomicMax(&scratch[ta], ma);
+    }
+  }
+}
+
+__device__ __forceinline__ int clamp_fl(int fl) { return fl > kFlMax ? kFlMax : (fl < kFlMin ? kFlMin : fl); }
+
+// One thread per tensor: max bit pattern -> fraclen.  With e = floor(log2 M) the candidate is
+// W - 2 - e (M lands in [2^(W-2), 2^(W-1))); it is one too fine exactly when M * 2^fl reaches
+// 2^(W-1) - 1/2, i.e. when the 24-bit significand m satisfies m >= 2^24 - 2^(24-W).
+__global__ void __launch_bounds__(kBlock)
+fraclen_from_f32max_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tensors, int use_theta_width,
+                           uint32_t* scratch, const int32_t* __restrict__ fl_default, int32_t* fl_out, uint32_t* status)
+{
+  uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+  if (t >= n_tensors) return;
+  const uint32_t b = scratch[t];
+  scratch[t] = 0;                                   // re-arm for the next call
+  const int W = use_theta_width ? tensors[t].wt : tensors[t].wg;
+  int fl;
+  if (b >= 0x7f800000u) { fl = kFlMin; if (status) atomicOr(status, kStatusNonFinite); }
+  else if (b == 0)      { fl = fl_default[t]; }
+  else {
+    const int E = (int)(b >> 23);
+    if (E == 0) fl = kFlMax;                        // subnormal maximum: far finer than the domain allows
+    else {
+      const uint32_t m = (b & 0x7fffffu) | 0x800000u;
+      fl = W - 2 - (E - 127);
+      if (m >= (1u << 24) - (1u << (24 - W))) fl -= 1;
+      fl = clamp_fl(fl);
+    }
+  }
+  fl_out[t] = fl;
+}
+
+// One thread per tensor: vmax (an integer on grid F = fl_theta_in + d) -> fraclen, clamped to default +- 15.
+__global__ void __launch_bounds__(kBlock)
+fraclen_from_vmax_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tensors, int use_theta_width,
+                         const uint64_t* __restrict__ vmax, const int32_t* __restrict__ fl_theta_in,
+                         const int32_t* __restrict__ fl_default, int32_t* fl_out, uint32_t* status)
+{
+  uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+  if (t >= n_tensors) return;
+  const int W = use_theta_width ? tensors[t].wt : tensors[t].wg;
+  const int d = tensors[t].comp ? tensors[t].d : 0;
+  const int F = fl_theta_in[t] + d;
+  const int cur = fl_default[t];
+  if (F < kFlMin || F > kFlMax + kDMax || cur < kFlMin || cur > kFlMax) {
+    fl_out[t] = cur;
+    if (status) atomicOr(status, kStatusDomain);
+    return;
+  }
+  const uint64_t v = vmax[t];
+  if (v == 0) { fl_out[t] = cur; return; }
+  const int e = 63 - __clzll((long long)v);
+  int fl = W - 2 - e + F;
+  // too fine iff v * 2^(W-2-e) >= 2^(W-1) - 1/2  <=>  v * 2^(W-1-e) >= 2^W - 1
+  const uint64_t rail = (1ull << W) - 1ull;
+  const int sh = W - 1 - e;
+  const bool over = sh >= 0 ? (v << sh) >= rail : v >= (rail << (-sh));     // e <= 63, W <= 16: no overflow either way
+  if (over) fl -= 1;
+  if (fl > cur + kDeltaMax) fl = cur + kDeltaMax;
+  if (fl < cur - kDeltaMax) fl = cur - kDeltaMax;
+  fl_out[t] = clamp_fl(fl);
+}
+
+hipError_t launch_select_f32(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
+                             int use_theta_width, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
+                             uint32_t* status, hipStream_t stream)
+{
+  if (n_tiles)
+    hipLaunchKernelGGL(maxabs_f32_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles, scratch);
+  hipLaunchKernelGGL(fraclen_from_f32max_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream,
+                     tensors, n_tensors, use_theta_width, scratch, fl_default, fl_out, status);
+  return hipGetLastError();
+}
+
+hipError_t launch_select_vmax(const TensorDev* tensors, uint32_t n_tensors, int use_theta_width, const uint64_t* vmax,
+                              const int32_t* fl_theta_in, const int32_t* fl_default, int32_t* fl_out, uint32_t* status,
+                              hipStream_t stream)
+{
+  hipLaunchKernelGGL(fraclen_from_vmax_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream,
+                     tensors, n_tensors, use_theta_width, vmax, fl_theta_in, fl_default, fl_out, status);
+  return hipGetLastError();
+}
+
+}  // namespace lpk

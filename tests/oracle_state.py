@@ -1,0 +1,56 @@
+"""Host-side mirror of one training step, run through the CPU oracle.
+
+The same order of operations as the device harness, on numpy arrays: fp32
+gradients -> max-abs fraclen -> int16 gradients -> lazy update -> (optionally)
+fraclen re-selection from vmax with a one-step lag.
+"""
+import os
+
+import numpy as np
+
+from oracle import ref
+
+DT = {8: np.int8, 16: np.int16}
+THREADS = max(1, min(16, len(os.sched_getaffinity(0))))
+
+
+class OracleState:
+    def __init__(self, cfg, kahan=True, comp_bits=None):
+        self.cfg, self.kahan = cfg, kahan
+        nt = cfg.n_tensors
+        self.comp_bits = list(comp_bits) if comp_bits is not None else list(cfg.bits)
+        self.theta = [np.zeros(n, dtype=DT[b]) for n, b in zip(cfg.sizes, cfg.bits)]
+        self.comp = [np.zeros(n, dtype=DT[b]) if kahan else None for n, b in zip(cfg.sizes, self.comp_bits)]
+        self.grad = [np.zeros(n, dtype=np.int16) for n in cfg.sizes]
+        self.d = [(b - 1) if kahan else 0 for b in self.comp_bits]
+        self.fl_theta = [b - 1 for b in cfg.bits]
+        self.fl_next = list(self.fl_theta)
+        self.fl_grad = [15] * nt
+        self.vmax = [0] * nt
+        self.status = ref.new_status()
+
+    def init_theta(self, theta0):
+        for t, x in enumerate(theta0):
+            self.fl_theta[t] = ref.select_fraclen_f32(x, self.cfg.bits[t], self.fl_theta[t], self.status)
+            ref.quantize(x, self.cfg.bits[t], self.fl_theta[t], self.status, out=self.theta[t])
+        self.fl_next = list(self.fl_theta)
+
+    def quantize_grads(self, grads):
+        for t, g in enumerate(grads):
+            self.fl_grad[t] = ref.select_fraclen_f32(g, 16, self.fl_grad[t], self.status)
+            ref.quantize(g, 16, self.fl_grad[t], self.status, out=self.grad[t])
+
+    def update(self, lr_q16, wd_q16=0):
+        new_next = list(self.fl_next)
+        for t in range(self.cfg.n_tensors):
+            self.vmax[t] = ref.kahan_sgd_step_mt(self.theta[t], self.comp[t], self.grad[t], self.d[t],
+                                                 self.fl_theta[t], self.fl_next[t], self.fl_grad[t],
+                                                 lr_q16, wd_q16, self.status, threads=THREADS)
+            if self.cfg.reselect:
+                new_next[t] = ref.select_fraclen_vmax(self.vmax[t], self.fl_theta[t] + self.d[t], self.cfg.bits[t],
+                                                      self.fl_next[t], self.status)
+        self.fl_theta, self.fl_next = self.fl_next, new_next
+
+    def step(self, step_idx, grads):
+        self.quantize_grads(grads)
+        self.update(self.cfg.lr_q16(step_idx), self.cfg.wd_q16)

@@ -1,0 +1,80 @@
+"""The C-ABI library loads without a GPU, exports every function the header declares, and rejects bad
+arguments on the host before touching the device (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1810_05486_amd import binding as lpk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lpk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lpk_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported():
+    names = declared_functions()
+    assert {"lpk_quantize_tensor", "lpk_select_fraclen", "lpk_kahan_sgd_step", "lpk_tensor_list_create",
+            "lpk_tensor_list_destroy"} <= set(names)
+    L = lpk.lib()
+    for n in names:
+        assert hasattr(L, n), "liblpk.so does not export %s" % n
+
+
+def test_binding_has_the_same_names():
+    for n in declared_functions():
+        if n in ("lpk_error_string", "lpk_tensor_list_size", "lpk_tensor_list_tiles"):
+            continue
+        assert hasattr(lpk, n), n
+
+
+def test_descriptor_layout_matches_header():
+    assert ctypes.sizeof(lpk.lpk_tensor_desc) == 48
+    assert lpk.lpk_tensor_desc.n.offset == 32 and lpk.lpk_tensor_desc.comp_shift.offset == 43
+
+
+def test_error_strings():
+    L = lpk.lib()
+    assert L.lpk_error_string(0) == b"ok"
+    assert L.lpk_error_string(-1) == b"invalid argument"
+    assert L.lpk_error_string(-77) == b"unknown lpk status code"
+    assert L.lpk_version() >= 100
+
+
+def _desc(**kw):
+    d = lpk.lpk_tensor_desc()
+    d.theta, d.comp, d.grad, d.src_f32, d.n = 0x1000, 0x2000, 0x3000, 0x4000, 64
+    d.theta_dtype, d.comp_dtype, d.grad_dtype, d.comp_shift = lpk.LPK_I8, lpk.LPK_I8, lpk.LPK_I16, 0xFF
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+@pytest.mark.parametrize("kw", [dict(theta_dtype=3), dict(grad_dtype=lpk.LPK_F32), dict(comp_dtype=0),
+                                dict(comp_shift=25), dict(theta=None), dict(grad=None),
+                                dict(grad=0x3001), dict(theta=0x1001, theta_dtype=lpk.LPK_I16),
+                                dict(src_f32=0x4002)])
+def test_create_rejects_bad_descriptors_on_the_host(kw):
+    h = ctypes.c_void_p(123)
+    arr = (lpk.lpk_tensor_desc * 1)(_desc(**kw))
+    assert lpk.lib().lpk_tensor_list_create(arr, 1, ctypes.byref(h)) == lpk.LPK_ERR_INVALID_ARG
+    assert h.value is None
+
+
+def test_null_and_range_arguments():
+    L = lpk.lib()
+    h = ctypes.c_void_p()
+    assert L.lpk_tensor_list_create(None, 1, ctypes.byref(h)) == lpk.LPK_ERR_INVALID_ARG
+    arr = (lpk.lpk_tensor_desc * 1)(_desc())
+    assert L.lpk_tensor_list_create(arr, 0, ctypes.byref(h)) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_tensor_list_create(arr, 1, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_tensor_list_destroy(None) == lpk.LPK_OK
+    assert L.lpk_tensor_list_size(None) == 0 and L.lpk_tensor_list_tiles(None) == 0
+    assert L.lpk_kahan_sgd_step(None, 8, 8, 8, 1, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_quantize_tensor(None, 0, 8, None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_select_fraclen(None, lpk.LPK_F32, 0, None, None, 8, 8, None, None) == lpk.LPK_ERR_INVALID_ARG

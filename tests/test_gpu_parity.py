@@ -1,0 +1,90 @@
+"""GPU library vs CPU oracle, bit for bit, through the C ABI (needs an MI355X)."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_1810_05486_amd import workloads
+from oracle_state import OracleState
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def compare(dev, host, what, check_vmax=True):
+    th, co, fl_t, fl_g, vm, status = dev.download()
+    assert status == int(host.status[0]), (what, "status", status, int(host.status[0]))
+    assert fl_t.tolist() == list(host.fl_theta), (what, "fl_theta")
+    assert fl_g.tolist() == list(host.fl_grad), (what, "fl_grad")
+    if check_vmax:
+        assert vm.tolist() == list(host.vmax), (what, "vmax")
+    for t in range(host.cfg.n_tensors):
+        bad = int((th[t] != host.theta[t]).sum())
+        assert bad == 0, (what, "theta", t, bad)
+        if host.kahan:
+            bad = int((co[t] != host.comp[t]).sum())
+            assert bad == 0, (what, "comp", t, bad)
+
+
+def run_config(cfg, step_ids, compare_every=1, kahan=True):
+    from paper_1810_05486_amd.device_state import DeviceState
+    dev = DeviceState(cfg, kahan=kahan)
+    host = OracleState(cfg, kahan=kahan)
+    views = dev.host_src_views()
+    theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
+    dev.upload_src()
+    dev.init_theta()
+    host.init_theta(theta0)
+    compare(dev, host, "init", check_vmax=False)
+    for i, s in enumerate(step_ids):
+        grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
+        dev.upload_src()
+        dev.step(s)
+        host.step(s, grads)
+        if (i + 1) % compare_every == 0 or i == len(step_ids) - 1:
+            compare(dev, host, "config %d step %d" % (cfg.id, s))
+    dev.close()
+    return host
+
+
+def test_config1_single_tensor_100_steps():
+    say("config 1: 65536 int8, 100 steps")
+    host = run_config(workloads.config(1), range(100))
+    assert host.fl_theta == [7]
+
+
+def test_config1_without_accumulator():
+    say("config 1 without the accumulator (plain SGD in int8)")
+    run_config(workloads.config(1), range(20), kahan=False)
+
+
+def test_config2_lenet_reselect():
+    say("config 2: LeNet-5 shapes, int16, fraclen re-selected every step")
+    full = os.environ.get("LPK_FULL_CONFIGS") == "1"
+    run_config(workloads.config(2), range(1000 if full else 150))
+
+
+def test_config3_resnet18_stepped_lr():
+    say("config 3: ResNet-18 shapes, int8, lr steps at 300 and 600")
+    full = os.environ.get("LPK_FULL_CONFIGS") == "1"
+    steps = list(range(1000)) if full else list(range(6)) + [299, 300, 301, 599, 600, 601, 999]
+    run_config(workloads.config(3), steps, compare_every=50 if full else 1)
+
+
+def test_config4_resnet50_mixed_width_decay():
+    say("config 4: ResNet-50 shapes, int8 + int16 classifier, weight decay")
+    full = os.environ.get("LPK_FULL_CONFIGS") == "1"
+    run_config(workloads.config(4), range(200 if full else 8), compare_every=50 if full else 1)
+
+
+def test_config5_reduced():
+    say("config 5 shape at reduced size: one 8 Mi + 37-element-ragged tensor and 300 tensors of 256")
+    cfg = workloads.config(5, big_elems=(1 << 23) + 37, n_tiny=300)
+    run_config(cfg, range(6))
