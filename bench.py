@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the lazy-update hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5]
+
+A step is one pass of the whole path over one batch of synthetic fp32
+gradients already resident in HBM: max-abs fraclen selection, quantization to
+int16, the fused Kahan-SGD update with its vmax reduction (and the fraclen
+re-selection where the workload has one).  Prints ONE JSON line.
+
+  value      whole-path parameters per second (Gparam/s) over the K timed steps
+  update_only   the same for lpk_kahan_sgd_step alone (the headline kernel)
+  roofline   the update kernel against the 8 TB/s HBM peak: algorithmic bytes
+             (6 B per int8 parameter, 10 B per int16 one) over its average
+             duration, measured with HIP events around every call inside the
+             timed region
+  cpu_baseline   the CPU oracle, single thread, on a bounded slice
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(cfg, sample_elems):
+    """Time the oracle (as it stands, one thread) on the first `sample_elems` elements of tensor 0."""
+    import numpy as np
+    from oracle import ref
+    n = cfg.sizes[0] if sample_elems >= cfg.sizes[0] else sample_elems
+    bits = cfg.bits[0]
+    dt = np.int8 if bits == 8 else np.int16
+    theta0 = cfg.theta0(0, count=n)
+    grad = cfg.grad(0, 0, count=n)
+    fl_t = ref.select_fraclen_f32(theta0, bits, bits - 1)
+    theta = ref.quantize(theta0, bits, fl_t)
+    comp = np.zeros(n, dtype=dt)
+    t0 = time.perf_counter()
+    fl_g = ref.select_fraclen_f32(grad, 16, 15)
+    g = ref.quantize(grad, 16, fl_g)
+    ref.kahan_sgd_step(theta, comp, g, bits - 1, fl_t, fl_t, fl_g, cfg.lr_q16(0), cfg.wd_q16)
+    dt_s = time.perf_counter() - t0
+    return {"value": n / dt_s / 1e9, "unit": "Gparam/s", "cores": 1, "kind": "oracle",
+            "sample": "one whole-path step (select + quantize + update) over the first %d elements of tensor 0, "
+                      "%.1f s" % (n, dt_s)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 (5 = the 1 Gi-parameter headline)")
+    ap.add_argument("--big-elems", type=int, default=1 << 30, help="size of config 5's large tensor")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-gib", type=float, default=2.0,
+                    help="size of the plain-copy yardstick (lpk_stream_copy), 0 = skip")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 28)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the update is elementwise and shards without "
+                 "communication); --gpus %d is not supported." % args.gpus)
+
+    import torch
+    from paper_1810_05486_amd import workloads
+    from paper_1810_05486_amd.device_state import DeviceState
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the hot path has no CPU fallback.")
+    torch.cuda.set_device(0)
+
+    cfg = workloads.config(args.config, big_elems=args.big_elems) if args.config == 5 else workloads.config(args.config)
+    n_src = cfg.grad_cycle or 1
+    if not cfg.grad_cycle:
+        n_src = 3                                   # timing only: cycle three resident gradient draws
+    log("workload %d: %s; %d tensors, %d parameters" % (cfg.id, cfg.name, cfg.n_tensors, cfg.n_params))
+    dev = DeviceState(cfg, n_src=n_src)
+    views = dev.host_src_views()
+
+    t0 = time.perf_counter()
+    for t in range(cfg.n_tensors):
+        cfg.theta0(t, out=views[t])
+    dev.upload_src(0)
+    dev.init_theta(0)
+    torch.cuda.synchronize()
+    for k in range(n_src):
+        for t in range(cfg.n_tensors):
+            cfg.grad(t, k, out=views[t])
+        dev.upload_src(k)
+        log("gradient draw %d/%d resident" % (k + 1, n_src))
+    torch.cuda.synchronize()
+    log("inputs drawn and uploaded in %.1f s" % (time.perf_counter() - t0))
+
+    for s in range(args.warmup):
+        dev.step(s, k=s % n_src)
+    torch.cuda.synchronize()
+
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        s = args.warmup + i
+        k = s % n_src
+        ev[i][0].record()
+        from paper_1810_05486_amd import binding as lpk
+        L = dev.lists[k]
+        lpk.lpk_select_fraclen(L, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, dev.fl_grad, dev.fl_grad, dev.status)
+        ev[i][1].record()
+        lpk.lpk_quantize_tensor(L, lpk.LPK_SEL_GRAD, dev.fl_grad, dev.status)
+        ev[i][2].record()
+        dev.update(cfg.lr_q16(s), cfg.wd_q16, k)
+        ev[i][3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    sel_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
+    qnt_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / K
+    upd_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / K
+    ms_per_step = wall * 1e3 / K
+    status = int(dev.status.cpu().numpy().view("uint32")[0])
+
+    copy = None
+    if args.copy_gib > 0:
+        nb = int(args.copy_gib * (1 << 30)) // 16 * 16
+        a = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+        b = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
+        from paper_1810_05486_amd import binding as lpk
+        lpk.lpk_stream_copy(a, b, nb)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            lpk.lpk_stream_copy(a, b, nb)
+        e1.record()
+        torch.cuda.synchronize()
+        cms = e0.elapsed_time(e1) / reps
+        copy = {"bytes_read": nb, "bytes_written": nb, "ms": cms, "GB/s": 2 * nb / (cms * 1e-3) / 1e9}
+        del a, b
+
+    upd_bytes = cfg.bytes_per_step()
+    achieved = upd_bytes / (upd_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_config%d.json" % cfg.id)
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("kahan_step_kernel_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "Kahan-SGD update throughput (whole hot path: fraclen select + quantize + fused update)",
+        "value": cfg.n_params / (ms_per_step * 1e-3) / 1e9,
+        "unit": "Gparam/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8/int16 fixed point (int32/int64 accumulate)", "data": "synthetic",
+        "config": {"workload": "config %d: %s" % (cfg.id, cfg.name), "n_tensors": cfg.n_tensors,
+                   "n_params": cfg.n_params, "lr_q16": cfg.lr_q16(0), "wd_q16": cfg.wd_q16,
+                   "grad_draws_cycled": n_src},
+        "update_only": {"value": cfg.n_params / (upd_ms * 1e-3) / 1e9, "unit": "Gparam/s", "ms": upd_ms},
+        "stage_ms": {"select_fraclen": sel_ms, "quantize": qnt_ms, "kahan_sgd_step": upd_ms},
+        "roofline": {"bound": "hbm", "kernel": "kahan_step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "bytes_per_launch": upd_bytes},
+        "other_kernels": {
+            "maxabs_f32_kernel": {"GB/s": 4 * cfg.n_params / (sel_ms * 1e-3) / 1e9, "bytes_per_launch": 4 * cfg.n_params},
+            "quantize_kernel": {"GB/s": 6 * cfg.n_params / (qnt_ms * 1e-3) / 1e9, "bytes_per_launch": 6 * cfg.n_params}},
+        "stream_copy_yardstick": copy,
+        "device_status_word": status,
+    }
+    dev.close()
+    del dev
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

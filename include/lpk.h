@@ -167,6 +167,12 @@ int lpk_kahan_sgd_step(lpk_tensor_list* list,
                        uint32_t lr_q16, uint32_t wd_q16,
                        uint64_t* vmax_out, uint32_t* status, void* stream);
 
+/* Measurement aid, not part of the method: dst[0..nbytes) = src[0..nbytes) with the same 16-byte
+ * streaming accesses and grid shape as the update kernel.  Reads nbytes and writes nbytes of HBM,
+ * which calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters and gives the practical copy
+ * bandwidth of the device.  dst, src: device, 16-byte aligned, non-overlapping; nbytes % 16 == 0. */
+int lpk_stream_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
+
 /* Static text for a return code ("ok", "invalid argument", ...). Never NULL. */
 const char* lpk_error_string(int code);
 

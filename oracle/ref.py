@@ -147,3 +147,28 @@ def kahan_sgd_step_mt(theta, comp, grad, d, fl_in, fl_out, fl_g, lr_q, wd_q=0, s
         for st in stats:
             status[0] |= st[0]
     return vm
+
+
+def quantize_mt(x, bits, fl, status=None, out=None, threads=1, chunk=1 << 22):
+    """Same result as quantize (elementwise), contiguous chunks on a thread pool."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    n = x.size
+    if out is None:
+        out = np.zeros(n, dtype=np.int8 if bits == 8 else np.int16)
+    if threads <= 1 or n <= chunk:
+        return quantize(x, bits, fl, status, out)
+    flat = out.reshape(-1)
+    stats = []
+
+    def work(lo):
+        hi = min(lo + chunk, n)
+        st = new_status()
+        stats.append(st)
+        quantize(x[lo:hi], bits, fl, st, flat[lo:hi])
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(work, range(0, n, chunk)))
+    if status is not None:
+        for st in stats:
+            status[0] |= st[0]
+    return out

@@ -51,6 +51,8 @@ def lib():
         L.lpk_select_fraclen.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, vp]
         L.lpk_quantize_tensor.argtypes = [vp, ci, vp, vp, vp]
         L.lpk_kahan_sgd_step.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
+        L.lpk_stream_copy.argtypes = [vp, vp, u64, vp]
+        L.lpk_stream_copy.restype = ci
         L.lpk_error_string.argtypes = [ci]
         L.lpk_error_string.restype = ctypes.c_char_p
         L.lpk_version.restype = ci
@@ -157,6 +159,10 @@ def lpk_kahan_sgd_step(tl, fl_theta_in, fl_theta_out, fl_grad, lr_q16, wd_q16=0,
     _check(lib().lpk_kahan_sgd_step(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_grad),
                                     int(lr_q16), int(wd_q16), _addr(vmax_out), _addr(status), _stream(stream)),
            "lpk_kahan_sgd_step")
+
+
+def lpk_stream_copy(dst, src, nbytes, stream=None):
+    _check(lib().lpk_stream_copy(_addr(dst), _addr(src), int(nbytes), _stream(stream)), "lpk_stream_copy")
 
 
 def lpk_version():

@@ -116,6 +116,9 @@ __device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const Tens
 template <bool DECAY>
 __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, int g, int& tn, int& cn, int& vmx, int& vmn)
 {
+#ifdef LPK_NO_MATH
+  tn = th ^ (g & 1); cn = c; vmx = max(vmx, g); return;
+#endif
   int s = __float_as_int(__builtin_fmaf((float)g, p.nlr_f, p.magic_f)) - p.magic_fi;
   if (DECAY) {
     double r = __builtin_fma((double)th, p.nlrwd_d, p.magic_d);
@@ -130,8 +133,23 @@ __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, 
   cn = min(max(r, p.qmin_c), p.qmax_c);
 }
 
-template <typename V> __device__ __forceinline__ V ld_stream(const V* p) { return __builtin_nontemporal_load(p); }
-template <typename V> __device__ __forceinline__ void st_stream(V* p, V v) { __builtin_nontemporal_store(v, p); }
+// Streaming accesses: global address space (global_load/global_store, not flat), non-temporal.
+template <typename V> __device__ __forceinline__ V ld_stream(const V* p)
+{
+#if LPK_NT_LOAD
+  return __builtin_nontemporal_load((const LPK_GLOBAL V*)p);
+#else
+  return *(const LPK_GLOBAL V*)p;
+#endif
+}
+template <typename V> __device__ __forceinline__ void st_stream(V* p, V v)
+{
+#if LPK_NT_STORE
+  __builtin_nontemporal_store(v, (LPK_GLOBAL V*)p);
+#else
+  *(LPK_GLOBAL V*)p = v;
+#endif
+}
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 

@@ -5,6 +5,19 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#define LPK_GLOBAL __attribute__((address_space(1)))
+
+// Tuning constants of the streaming kernels (overridable at compile time for experiments).
+#ifndef LPK_PASSES
+#define LPK_PASSES 4          // 1024-element passes per wave tile, all loads of a tile in flight together
+#endif
+#ifndef LPK_NT_LOAD
+#define LPK_NT_LOAD 1         // non-temporal hint on streaming loads
+#endif
+#ifndef LPK_NT_STORE
+#define LPK_NT_STORE 1        // non-temporal hint on streaming stores
+#endif
+
 namespace lpk {
 
 constexpr int kWave           = 64;     // CDNA wavefront
@@ -12,7 +25,7 @@ constexpr int kWavesPerBlock  = 4;
 constexpr int kBlock          = kWave * kWavesPerBlock;
 constexpr int kGroup          = 16;     // elements one lane handles per pass (one dwordx4 of int8)
 constexpr int kPassElems      = kWave * kGroup;          // 1024 elements per wave pass
-constexpr int kPasses         = 4;
+constexpr int kPasses         = LPK_PASSES;
 constexpr int kTileElems      = kPassElems * kPasses;    // 4096 elements per wave tile
 
 constexpr int kFlMin = -64, kFlMax = 64, kDMax = 24, kDeltaMax = 15;

@@ -19,6 +19,7 @@ hipError_t launch_select_vmax(const TensorDev*, uint32_t n_tensors, int use_thet
                               hipStream_t);
 hipError_t launch_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t grid, int to_theta,
                            const int32_t* fl, uint32_t* status, hipStream_t);
+hipError_t launch_stream_copy(void* dst, const void* src, uint64_t nbytes, uint32_t grid, hipStream_t);
 }  // namespace lpk
 
 using namespace lpk;
@@ -99,7 +100,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
   if (ok) {
     // Persistent grid: enough resident waves per CU to cover HBM latency, never more blocks than tile quads.
-    const uint32_t per_cu = env_u32("LPK_BLOCKS_PER_CU", 8);
+    const uint32_t per_cu = env_u32("LPK_BLOCKS_PER_CU", 2);
     uint32_t grid = (uint32_t)prop.multiProcessorCount * per_cu;
     const uint32_t need = (L->n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     if (grid > need) grid = need;
@@ -176,6 +177,20 @@ int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+int lpk_stream_copy(void* dst, const void* src, uint64_t nbytes, void* stream)
+{
+  if (nbytes == 0) return LPK_OK;
+  if (!dst || !src || (nbytes & 15u) || !aligned(dst, 16) || !aligned(src, 16)) return LPK_ERR_INVALID_ARG;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return LPK_ERR_DEVICE;
+  uint64_t blocks = (nbytes / 16 + kBlock - 1) / kBlock;
+  const uint64_t cap = (uint64_t)prop.multiProcessorCount * env_u32("LPK_BLOCKS_PER_CU", 3);
+  if (blocks > cap) blocks = cap;
+  hipError_t e = launch_stream_copy(dst, src, nbytes, (uint32_t)blocks, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 

@@ -107,4 +107,21 @@ hipError_t launch_quantize(const TensorDev* tensors, const Tile* tiles, uint32_t
   return hipGetLastError();
 }
 
+// Plain streaming copy (16 bytes per lane per access, grid-stride): the yardstick the HBM counters and
+// the update kernel's bandwidth are read against.
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(kBlock) stream_copy_kernel(v4u* __restrict__ dst, const v4u* __restrict__ src, uint64_t n16)
+{
+  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
+  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride)
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+hipError_t launch_stream_copy(void* dst, const void* src, uint64_t nbytes, uint32_t grid, hipStream_t stream)
+{
+  if (nbytes)
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(kBlock), 0, stream, (v4u*)dst, (const v4u*)src, nbytes / 16);
+  return hipGetLastError();
+}
+
 }  // namespace lpk

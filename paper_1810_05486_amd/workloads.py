@@ -117,15 +117,22 @@ class Config:
         return sum(n * (4 * b // 8 + 2) for n, b in zip(self.sizes, self.bits))
 
     # -- draws ----------------------------------------------------------------------------------------
-    def theta0(self, t, out=None):
-        """fp32 initial parameters of tensor t."""
+    def _count(self, t, count):
+        n = self.sizes[t]
+        if count is None or count >= n:
+            return n
+        assert count % CHUNK == 0, "a prefix draw ends on a chunk boundary"
+        return count
+
+    def theta0(self, t, out=None, count=None):
+        """fp32 initial parameters of tensor t (count: only its first `count` elements, same values)."""
         shape = self.shapes[t]
         if self.id in (1, 5):
             b = 0.5
         else:
             b = _fan_in(shape) ** -0.5 if len(shape) >= 2 else 0.5
         fill = lambda rng, m: ((2.0 * rng.random(m) - 1.0) * b).astype(np.float32)
-        return _draw(self.sizes[t], fill, self.seed, self.id, t, 0, ROLE_THETA0, out)
+        return _draw(self._count(t, count), fill, self.seed, self.id, t, 0, ROLE_THETA0, out)
 
     def grad_scale(self, t):
         kind = self.grad_kind
@@ -140,8 +147,9 @@ class Config:
             return 1e-4 * _fan_in(self.shapes[t]) ** -0.5
         raise ValueError(kind)
 
-    def grad(self, t, step, out=None):
-        """fp32 gradient of tensor t at a 0-based step (a fresh draw per step, or a cycle of grad_cycle draws)."""
+    def grad(self, t, step, out=None, count=None):
+        """fp32 gradient of tensor t at a 0-based step (a fresh draw per step, or a cycle of grad_cycle draws);
+        count: only its first `count` elements, same values."""
         key_step = step % self.grad_cycle if self.grad_cycle else step
         scale = self.grad_scale(t)
         if self.grad_kind == "laplace_1e-4":
@@ -149,7 +157,7 @@ class Config:
         else:
             sc = np.float32(scale)
             fill = lambda rng, m: rng.standard_normal(m, dtype=np.float32) * sc
-        return _draw(self.sizes[t], fill, self.seed, self.id, t, key_step, ROLE_GRAD, out)
+        return _draw(self._count(t, count), fill, self.seed, self.id, t, key_step, ROLE_GRAD, out)
 
 
 def config(cid, big_elems=1 << 30, n_tiny=10000):

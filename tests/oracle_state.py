@@ -32,13 +32,13 @@ class OracleState:
     def init_theta(self, theta0):
         for t, x in enumerate(theta0):
             self.fl_theta[t] = ref.select_fraclen_f32(x, self.cfg.bits[t], self.fl_theta[t], self.status)
-            ref.quantize(x, self.cfg.bits[t], self.fl_theta[t], self.status, out=self.theta[t])
+            ref.quantize_mt(x, self.cfg.bits[t], self.fl_theta[t], self.status, out=self.theta[t], threads=THREADS)
         self.fl_next = list(self.fl_theta)
 
     def quantize_grads(self, grads):
         for t, g in enumerate(grads):
             self.fl_grad[t] = ref.select_fraclen_f32(g, 16, self.fl_grad[t], self.status)
-            ref.quantize(g, 16, self.fl_grad[t], self.status, out=self.grad[t])
+            ref.quantize_mt(g, 16, self.fl_grad[t], self.status, out=self.grad[t], threads=THREADS)
 
     def update(self, lr_q16, wd_q16=0):
         new_next = list(self.fl_next)

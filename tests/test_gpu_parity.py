@@ -88,3 +88,10 @@ def test_config5_reduced():
     say("config 5 shape at reduced size: one 8 Mi + 37-element-ragged tensor and 300 tensors of 256")
     cfg = workloads.config(5, big_elems=(1 << 23) + 37, n_tiny=300)
     run_config(cfg, range(6))
+
+
+def test_config5_full_size_in_bench_launch_configuration():
+    """The headline workload at full size (1 Gi + 10000 x 256 elements), same lists and launch shape as bench.py,
+    every output byte compared with the oracle after each of two steps."""
+    say("config 5 at FULL size: 1073741824 + 10000*256 elements, 2 steps (oracle on host threads)")
+    run_config(workloads.config(5), range(2))
