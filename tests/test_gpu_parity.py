@@ -18,6 +18,15 @@ def say(msg):
     sys.stdout.flush()
 
 
+def compare_scalars(dev, host, what):
+    """fraclens, vmax and the status word only (cheap: checked after every step)."""
+    torch.cuda.synchronize()
+    assert dev.fl_theta.cpu().tolist() == list(host.fl_theta), (what, "fl_theta")
+    assert dev.fl_grad.cpu().tolist() == list(host.fl_grad), (what, "fl_grad")
+    assert dev.vmax.cpu().numpy().view(np.uint64).tolist() == list(host.vmax), (what, "vmax")
+    assert int(dev.status.cpu().numpy().view(np.uint32)[0]) == int(host.status[0]), (what, "status")
+
+
 def compare(dev, host, what, check_vmax=True):
     th, co, fl_t, fl_g, vm, status = dev.download()
     assert status == int(host.status[0]), (what, "status", status, int(host.status[0]))
@@ -33,7 +42,7 @@ def compare(dev, host, what, check_vmax=True):
             assert bad == 0, (what, "comp", t, bad)
 
 
-def run_config(cfg, step_ids, compare_every=1, kahan=True):
+def run_config(cfg, step_ids, compare_every=1, kahan=True, always=()):
     from paper_1810_05486_amd.device_state import DeviceState
     dev = DeviceState(cfg, kahan=kahan)
     host = OracleState(cfg, kahan=kahan)
@@ -48,8 +57,12 @@ def run_config(cfg, step_ids, compare_every=1, kahan=True):
         dev.upload_src()
         dev.step(s)
         host.step(s, grads)
-        if (i + 1) % compare_every == 0 or i == len(step_ids) - 1:
+        if (i + 1) % compare_every == 0 or i == len(step_ids) - 1 or i in always:
             compare(dev, host, "config %d step %d" % (cfg.id, s))
+        else:
+            compare_scalars(dev, host, "config %d step %d" % (cfg.id, s))
+        if (i + 1) % 25 == 0:
+            say("  config %d: %d/%d steps bit-exact so far" % (cfg.id, i + 1, len(step_ids)))
     dev.close()
     return host
 
@@ -93,5 +106,9 @@ def test_config5_reduced():
 def test_config5_full_size_in_bench_launch_configuration():
     """The headline workload at full size (1 Gi + 10000 x 256 elements), same lists and launch shape as bench.py,
     every output byte compared with the oracle after each of two steps."""
-    say("config 5 at FULL size: 1073741824 + 10000*256 elements, 2 steps (oracle on host threads)")
-    run_config(workloads.config(5), range(2))
+    full = os.environ.get("LPK_FULL_CONFIGS") == "1"
+    say("config 5 at FULL size: 1073741824 + 10000*256 elements, %d steps (oracle on host threads)" % (50 if full else 2))
+    if full:
+        run_config(workloads.config(5), range(50), compare_every=50, always=(0, 1))
+    else:
+        run_config(workloads.config(5), range(2))
