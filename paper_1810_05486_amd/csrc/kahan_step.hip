@@ -255,6 +255,50 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
   return vm;
 }
 
+// One pipeline stage: start the loads of the wave's next tile into `nxt` if that tile continues the run
+// (same tensor, full), then compute and store `cur`.  Returns whether `nxt` was filled; ti/off advance to it.
+template <bool DECAY>
+__device__ __forceinline__ bool stage_fast8(const StepParams& p, const TensorDev& T, const Tile* __restrict__ tiles,
+                                            uint32_t n_tiles, uint32_t nw, uint32_t& ti, uint64_t& off, int tensor, int lane,
+                                            Group<8> (&cur)[kPasses], Group<8> (&nxt)[kPasses], int& vmx, int& vmn)
+{
+  const uint32_t tn = ti + nw;
+  bool more = false;
+  uint64_t noff = 0;
+  if (tn < n_tiles) {
+    const Tile nx = tiles[tn];
+    more = wave_uniform((int)nx.tensor) == tensor && (uint32_t)wave_uniform((int)nx.count) == (uint32_t)kTileElems;
+    noff = ((uint64_t)(uint32_t)wave_uniform((int)(nx.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)nx.offset);
+  }
+  if (more) {
+#pragma unroll
+    for (int ps = 0; ps < kPasses; ++ps) load_group(nxt[ps], T, noff + (uint64_t)(ps * kWave + lane) * kGroup);
+  }
+#pragma unroll
+  for (int ps = 0; ps < kPasses; ++ps)
+    compute_store_group<DECAY>(p, cur[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup, vmx, vmn);
+  if (more) { ti = tn; off = noff; }
+  return more;
+}
+
+// Processes the full tile at (ti, off) and every following tile of this wave that continues the run; on
+// return ti is the last tile consumed (the caller's loop increment moves past it).
+template <bool DECAY>
+__device__ __forceinline__ uint64_t run_fast8(const StepParams& p, const TensorDev& T, const Tile* __restrict__ tiles,
+                                              uint32_t n_tiles, uint32_t nw, uint32_t& ti, uint64_t off, int tensor, int lane)
+{
+  int vmx = 0, vmn = 0;
+  Group<8> A[kPasses], B[kPasses];
+#pragma unroll
+  for (int ps = 0; ps < kPasses; ++ps) load_group(A[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup);
+  while (true) {
+    if (!stage_fast8<DECAY>(p, T, tiles, n_tiles, nw, ti, off, tensor, lane, A, B, vmx, vmn)) break;
+    if (!stage_fast8<DECAY>(p, T, tiles, n_tiles, nw, ti, off, tensor, lane, B, A, vmx, vmn)) break;
+  }
+  int64_t a = vmx, b = -(int64_t)vmn;
+  return (uint64_t)(a > b ? a : b);
+}
+
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
 
 __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, int fl_in, int fl_out, int fl_g,
@@ -329,7 +373,7 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
   StepParams p; p.path = 0;
   TensorDev T;
 
-  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
+  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {      // ti may also be advanced inside by a pipelined run
     const Tile tl = tiles[ti];
     const int t = wave_uniform((int)tl.tensor);
     const uint32_t cnt = (uint32_t)wave_uniform((int)tl.count);
@@ -343,8 +387,14 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8) vm = p.lrwd ? tile_fast<8, true>(p, T, off, cnt, lane)  : tile_fast<8, false>(p, T, off, cnt, lane);
-      else           vm = p.lrwd ? tile_fast<16, true>(p, T, off, cnt, lane) : tile_fast<16, false>(p, T, off, cnt, lane);
+      if (p.wt == 8 && cnt == (uint32_t)kTileElems) {
+        // Run of full int8 tiles of this tensor, software-pipelined: the loads of the wave's next tile are in
+        // flight while the current one is computed and stored, so the memory pipe never waits for the ALU.
+        vm = p.lrwd ? run_fast8<true>(p, T, tiles, n_tiles, nw, ti, off, cur, lane)
+                    : run_fast8<false>(p, T, tiles, n_tiles, nw, ti, off, cur, lane);
+      }
+      else if (p.wt == 8) vm = p.lrwd ? tile_fast<8, true>(p, T, off, cnt, lane)  : tile_fast<8, false>(p, T, off, cnt, lane);
+      else                vm = p.lrwd ? tile_fast<16, true>(p, T, off, cnt, lane) : tile_fast<16, false>(p, T, off, cnt, lane);
     } else if (p.path == 1) {
       vm = tile_generic(p, T, off, cnt, lane);
     }

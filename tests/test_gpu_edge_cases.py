@@ -1,0 +1,284 @@
+"""GPU library vs CPU oracle on edge cases, through the C ABI (needs an MI355X): ragged and empty tensors,
+unaligned pointers, every width combination, grid moves, negative shifts, rails, the boundaries between the
+kernel's 32-bit and 64-bit arithmetic paths, special fp32 values, and the status word."""
+import random
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+from oracle import ref
+from paper_1810_05486_amd import binding as lpk
+
+NP = {8: np.int8, 16: np.int16}
+TT = {8: torch.int8, 16: torch.int16}
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+class Case:
+    """One tensor of a list: host copies for the oracle, device copies (possibly misaligned views) for the library."""
+
+    def __init__(self, rng, n, tb, cb, gb, d, fl_in, fl_out, fl_g, misalign=0, g_lim=None, th_lim=None):
+        self.n, self.tb, self.cb, self.gb, self.d = n, tb, cb, gb, d
+        self.fl_in, self.fl_out, self.fl_g = fl_in, fl_out, fl_g
+        lo_t, hi_t = (-(2 ** (tb - 1)), 2 ** (tb - 1)) if th_lim is None else (-th_lim, th_lim)
+        lo_g, hi_g = (-(2 ** (gb - 1)), 2 ** (gb - 1)) if g_lim is None else (-g_lim, g_lim)
+        self.theta = rng.integers(lo_t, hi_t, size=n).astype(NP[tb])
+        self.comp = rng.integers(-(2 ** (cb - 1)), 2 ** (cb - 1), size=n).astype(NP[cb]) if cb else None
+        self.grad = rng.integers(lo_g, hi_g, size=n).astype(NP[gb])
+        if n >= 4:                      # plant the extremes
+            self.grad[0], self.grad[1] = -(2 ** (gb - 1)), 2 ** (gb - 1) - 1
+            self.theta[2], self.theta[3] = -(2 ** (tb - 1)), 2 ** (tb - 1) - 1
+
+        def dev(a, bits):
+            buf = torch.zeros(n + 64, dtype=TT[bits], device=DEV)        # base is 256-byte aligned
+            v = buf[misalign:misalign + n]
+            v.copy_(torch.from_numpy(a))
+            return buf, v
+
+        self.keep = []
+        self.d_theta = self.d_comp = None
+        b, self.d_theta = dev(self.theta, tb); self.keep.append(b)
+        if cb:
+            b, self.d_comp = dev(self.comp, cb); self.keep.append(b)
+        b, self.d_grad = dev(self.grad, gb); self.keep.append(b)
+
+    def desc(self):
+        return lpk.make_desc(self.d_theta, self.d_comp, self.d_grad, None,
+                             self.d if self.cb and self.d is not None else lpk.LPK_COMP_SHIFT_DEFAULT)
+
+
+def run_list(cases, lr_q, wd_q, want_vmax=True):
+    tl = lpk.TensorList([c.desc() for c in cases])
+    i32 = dict(dtype=torch.int32, device=DEV)
+    fl_in = torch.tensor([c.fl_in for c in cases], **i32)
+    fl_out = torch.tensor([c.fl_out for c in cases], **i32)
+    fl_g = torch.tensor([c.fl_g for c in cases], **i32)
+    vmax = torch.full((len(cases),), 77, dtype=torch.int64, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    lpk.lpk_kahan_sgd_step(tl, fl_in, fl_out, fl_g, lr_q, wd_q, vmax if want_vmax else None, status)
+    torch.cuda.synchronize()
+    st = ref.new_status()
+    for i, c in enumerate(cases):
+        d = c.d if c.d is not None else (c.cb - 1 if c.cb else 0)
+        want_v = ref.kahan_sgd_step(c.theta, c.comp, c.grad, d, c.fl_in, c.fl_out, c.fl_g, lr_q, wd_q, st)
+        ctx = dict(i=i, n=c.n, tb=c.tb, cb=c.cb, gb=c.gb, d=d, fl=(c.fl_in, c.fl_out, c.fl_g), lr=lr_q, wd=wd_q)
+        assert np.array_equal(c.d_theta.cpu().numpy(), c.theta), ("theta", ctx)
+        if c.cb:
+            assert np.array_equal(c.d_comp.cpu().numpy(), c.comp), ("comp", ctx)
+        if want_vmax:
+            assert int(vmax[i].item()) == want_v, ("vmax", ctx)
+        # guard words around a misaligned view stay untouched
+        for b in c.keep:
+            assert int(b[-8:].abs().sum().item()) == 0
+    assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
+    tl.destroy()
+    return int(st[0])
+
+
+SIZES = [0, 1, 15, 16, 17, 63, 64, 255, 1023, 1024, 1025, 4095, 4096, 4097, 8191, 12289, 70001]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_lists_all_widths_shifts_and_alignments(seed):
+    say("random multi-tensor lists, seed %d" % seed)
+    rng = np.random.default_rng(100 + seed)
+    pr = random.Random(200 + seed)
+    for rep in range(6):
+        cases = []
+        for _ in range(pr.randint(1, 12)):
+            tb, gb = pr.choice([8, 16]), pr.choice([16, 16, 8])
+            cb = pr.choice([8, 16, tb, tb, 0])
+            d = pr.choice([None, None, pr.randint(0, 24)]) if cb else None
+            dd = d if d is not None else (cb - 1 if cb else 0)
+            fl_in = pr.randint(-20, 30)
+            delta = pr.choice([0, 0, 0, 1, -1, 3, -4, pr.randint(-15, 15)])
+            k = pr.choice([pr.randint(9, 33), pr.randint(9, 33), pr.randint(1, 8), pr.randint(-30, 0), pr.randint(30, 60)])
+            fl_g = max(-64, min(64, k - 16 + fl_in + dd))
+            fl_out = max(-64, min(64, fl_in + delta))
+            cases.append(Case(rng, pr.choice(SIZES), tb, cb, gb, d, fl_in, fl_out, fl_g,
+                              misalign=pr.choice([0, 0, 0, 1, 3, 8, 16])))
+        run_list(cases, pr.choice([1, 655, 6554, 32768, 65535]), pr.choice([0, 0, 7, 65535]),
+                 want_vmax=pr.random() < 0.8)
+
+
+@pytest.mark.parametrize("tb", [8, 16])
+def test_arithmetic_path_boundaries(tb):
+    """Shifts on both sides of every condition that selects the 32-bit path (step shift 8|9, d 0|1, widest d
+    that still fits, extreme lr and gradients, decay on/off), same-width aligned tensors of several tiles."""
+    say("path boundaries, %d-bit" % tb)
+    rng = np.random.default_rng(tb)
+    for kg in (8, 9, 10, 23, 31, 32, 33, 48, 90):
+        for d in (0, 1, tb - 1, 15, 16, 22, 24):
+            fl_in = 5
+            fl_g = kg - 16 + fl_in + d
+            if not -64 <= fl_g <= 64:
+                continue
+            cases = [Case(rng, 9000 + 13, tb, tb, 16, d, fl_in, fl_in, fl_g)]
+            for lr_q, wd_q in ((65535, 0), (1, 0), (6554, 7), (65535, 65535)):
+                run_list(cases, lr_q, wd_q)
+
+
+def test_rails_are_hit_in_the_vector_path():
+    """A large constant step drives theta and comp into both rails over a few steps."""
+    say("saturation in the vector path")
+    rng = np.random.default_rng(3)
+    c = Case(rng, 3 * 4096 + 5, 8, 8, 16, None, 7, 7, 10)      # step shift 12: up to 4096 theta LSBs per step
+    hit = 0
+    for _ in range(3):
+        run_list([c], 65535, 0)
+        hit += int((np.abs(c.theta.astype(np.int32)) >= 127).sum())
+    assert hit > 1000
+
+
+def test_out_of_domain_tensor_is_skipped_and_flagged():
+    say("domain status")
+    rng = np.random.default_rng(4)
+    good = Case(rng, 5000, 8, 8, 16, None, 7, 7, 20)
+    bad1 = Case(rng, 5000, 8, 8, 16, None, 7, 23, 20)          # grid move of 16
+    bad2 = Case(rng, 300, 16, 16, 16, None, 65, 65, 20)        # fraclen outside [-64, 64]
+    bad3 = Case(rng, 300, 8, 0, 16, None, 0, 0, -70)
+    assert run_list([good, bad1, bad2, bad3], 655, 0) == lpk.LPK_STATUS_DOMAIN
+
+
+def _select_quantize(xs, bits_sel, theta_bits=8):
+    """Run select(F32) + quantize through the library on a list of fp32 arrays; return (fl list, q list, status)."""
+    n_t = len(xs)
+    src = [torch.from_numpy(x.copy()).to(DEV) for x in xs]
+    theta = [torch.zeros(max(x.size, 1), dtype=TT[theta_bits], device=DEV)[:x.size] for x in xs]
+    grad = [torch.zeros(max(x.size, 1), dtype=torch.int16, device=DEV)[:x.size] for x in xs]
+    descs = []
+    for t in range(n_t):
+        d = lpk.make_desc(theta[t], None, grad[t], src[t])
+        descs.append(d)
+    tl = lpk.TensorList(descs)
+    fl = torch.tensor([40 + t for t in range(n_t)], dtype=torch.int32, device=DEV)     # defaults, recognisable
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    lpk.lpk_select_fraclen(tl, lpk.LPK_F32, bits_sel, None, None, fl, fl, status)
+    lpk.lpk_quantize_tensor(tl, bits_sel, fl, status)
+    torch.cuda.synchronize()
+    out = theta if bits_sel == lpk.LPK_SEL_THETA else grad
+    res = ([int(v) for v in fl.cpu()], [o.cpu().numpy() for o in out], int(status.cpu().numpy().view(np.uint32)[0]))
+    tl.destroy()
+    return res
+
+
+@pytest.mark.parametrize("sel,bits", [(lpk.LPK_SEL_GRAD, 16), (lpk.LPK_SEL_THETA, 8), (lpk.LPK_SEL_THETA, 16)])
+def test_select_and_quantize_special_values(sel, bits):
+    say("select + quantize special values, %d-bit" % bits)
+    f = np.float32
+    rng = np.random.default_rng(8)
+    xs = [
+        np.zeros(100, dtype=f),                                           # all zero -> default fraclen
+        np.array([], dtype=f),                                            # empty -> default
+        np.array([0.0, -0.0, 1e-45, -1e-45, 1e-40], dtype=f),             # subnormals only -> clamped to 64
+        np.array([1.0, np.nan, -2.0], dtype=f),
+        np.array([np.inf, 1.0], dtype=f),
+        np.array([-np.inf], dtype=f),
+        np.array([3e38, -1e38], dtype=f),                                 # clamps to -64, saturates
+        np.array([0.5, -0.25, 0.125], dtype=f),
+        np.array([127.5, -3.0], dtype=f), np.array([127.49, 2.0], dtype=f),
+        np.array([0.49999, 0.1], dtype=f), np.array([0.999, -0.998], dtype=f),
+        (rng.standard_normal(4096 * 3 + 7) * 1e-3).astype(f),
+        (rng.standard_normal(17) * 1e5).astype(f),
+        np.array([(i - 40 + 0.5) / 64.0 for i in range(80)], dtype=f),    # exact ties at the chosen grid
+    ]
+    # significands around the rounding edge of the fraclen rule
+    for m in (0x7FFFFF, 0x7FFFFF - (1 << (24 - bits)) + 1, 0x7FFFFF - (1 << (24 - bits)), 0x7F0000):
+        xs.append(np.array([(100 << 23) | m, (90 << 23) | 5], dtype=np.uint32).view(f).copy())
+    fls, qs, status = _select_quantize(xs, sel, theta_bits=bits if sel == lpk.LPK_SEL_THETA else 8)
+    st = ref.new_status()
+    for t, x in enumerate(xs):
+        want_fl = ref.select_fraclen_f32(x, bits, 40 + t, st)
+        assert fls[t] == want_fl, (t, fls[t], want_fl)
+        want_q = ref.quantize(x, bits, want_fl, st)
+        assert np.array_equal(qs[t], want_q), (t, x[:8], qs[t][:8], want_q[:8])
+    assert status == int(st[0]) == ref.STATUS_NONFINITE
+
+
+def test_quantize_every_fraclen_and_domain_flag():
+    say("quantize across the fraclen domain")
+    rng = np.random.default_rng(9)
+    base = np.concatenate([rng.standard_normal(1000).astype(np.float32),
+                           np.array([0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 32767.5, -32768.5, 1e15, -1e15], dtype=np.float32)])
+    fls = list(range(-64, 65, 4)) + [-64, 64, 65, -65, 1000]
+    xs = [(base * np.float32(2.0) ** np.float32(-min(max(fl, -60), 60))).astype(np.float32) for fl in fls]
+    src = [torch.from_numpy(x).to(DEV) for x in xs]
+    grad = [torch.full((x.size,), 9, dtype=torch.int16, device=DEV) for x in xs]
+    theta = [torch.zeros(x.size, dtype=torch.int8, device=DEV) for x in xs]
+    tl = lpk.TensorList([lpk.make_desc(theta[t], None, grad[t], src[t]) for t in range(len(xs))])
+    fl = torch.tensor(fls, dtype=torch.int32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    lpk.lpk_quantize_tensor(tl, lpk.LPK_SEL_GRAD, fl, status)
+    torch.cuda.synchronize()
+    st = ref.new_status()
+    for t, x in enumerate(xs):
+        want = np.full(x.size, 9, dtype=np.int16)
+        ref.quantize(x, 16, fls[t], st, out=want)
+        assert np.array_equal(grad[t].cpu().numpy(), want), fls[t]
+    assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0]) == ref.STATUS_DOMAIN
+    tl.destroy()
+
+
+def test_reselect_from_vmax_matches_oracle():
+    say("fraclen re-selection from vmax")
+    pr = random.Random(5)
+    n_t = 500
+    theta = torch.zeros(16, dtype=torch.int8, device=DEV)
+    theta16 = torch.zeros(16, dtype=torch.int16, device=DEV)
+    comp = torch.zeros(16, dtype=torch.int8, device=DEV)
+    comp16 = torch.zeros(16, dtype=torch.int16, device=DEV)
+    grad = torch.zeros(16, dtype=torch.int16, device=DEV)
+    descs, meta = [], []
+    for t in range(n_t):
+        tb = pr.choice([8, 16]); has_c = pr.random() < 0.8
+        d = pr.choice([7, 15, pr.randint(0, 24)]) if has_c else 0
+        descs.append(lpk.make_desc(theta if tb == 8 else theta16, (comp if pr.random() < .5 else comp16) if has_c else None,
+                                   grad, None, d if has_c else lpk.LPK_COMP_SHIFT_DEFAULT))
+        meta.append((tb, d))
+    tl = lpk.TensorList(descs)
+    vm, fin, cur = [], [], []
+    for t in range(n_t):
+        tb, d = meta[t]
+        vm.append(pr.choice([0, 1, 127, 128, 255, 256, (1 << pr.randint(1, 45)) - 1, pr.randint(1, 1 << 42),
+                             ((1 << tb) - 1) << pr.randint(0, 25), (((1 << tb) - 1) << pr.randint(1, 25)) - 1]))
+        fi = pr.randint(-64, 64) if pr.random() < .95 else pr.choice([-70, 70])
+        fin.append(fi)
+        cur.append(max(-64, min(64, fi + pr.randint(-15, 15))) if pr.random() < .97 else 80)
+    d_vm = torch.tensor(vm, dtype=torch.int64, device=DEV)
+    d_fin = torch.tensor(fin, dtype=torch.int32, device=DEV)
+    d_cur = torch.tensor(cur, dtype=torch.int32, device=DEV)
+    d_out = torch.zeros(n_t, dtype=torch.int32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    lpk.lpk_select_fraclen(tl, lpk.LPK_VMAX_U64, lpk.LPK_SEL_THETA, d_vm, d_fin, d_cur, d_out, status)
+    torch.cuda.synchronize()
+    st = ref.new_status()
+    want = [ref.select_fraclen_vmax(vm[t], fin[t] + meta[t][1], meta[t][0], cur[t], st) for t in range(n_t)]
+    assert d_out.cpu().tolist() == want
+    assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
+    tl.destroy()
+
+
+def test_host_side_argument_errors_with_a_live_list():
+    say("argument errors")
+    t = torch.zeros(64, dtype=torch.int8, device=DEV)
+    g = torch.zeros(64, dtype=torch.int16, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(t, t.clone(), g)])          # no fp32 source
+    fl = torch.zeros(1, dtype=torch.int32, device=DEV)
+    L = lpk.lib()
+    assert L.lpk_kahan_sgd_step(tl.handle, fl.data_ptr(), fl.data_ptr(), fl.data_ptr(), 65536, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_kahan_sgd_step(tl.handle, fl.data_ptr(), None, fl.data_ptr(), 1, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_quantize_tensor(tl.handle, lpk.LPK_SEL_GRAD, fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_select_fraclen(tl.handle, lpk.LPK_F32, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_select_fraclen(tl.handle, 3, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_select_fraclen(tl.handle, lpk.LPK_VMAX_U64, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_tensor_list_size(tl.handle) == 1 and L.lpk_tensor_list_tiles(tl.handle) == 1
+    tl.destroy()
