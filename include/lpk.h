@@ -167,6 +167,16 @@ int lpk_kahan_sgd_step(lpk_tensor_list* list,
                        uint32_t lr_q16, uint32_t wd_q16,
                        uint64_t* vmax_out, uint32_t* status, void* stream);
 
+/*
+ * Bit-width guideline for the last fully-connected layer (Section 3, eq. 4-5): the smallest width BW with
+ *   alpha / (n_classes - 1) >= 2^-(BW - 1),
+ * i.e. the sum of the round-off parts of the softmax gradient stays below alpha.  Host-only, no device
+ * access.  alpha_q16 = alpha * 65536 in (0, 65535] (the paper recommends alpha = 0.5 -> 32768).
+ * Returns BW >= 2, or LPK_ERR_INVALID_ARG for n_classes < 2 or alpha_q16 outside (0, 65535].
+ * Examples at alpha = 0.5: 10 classes -> 6, 58 -> 8, 1000 -> 12 bits.
+ */
+int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16);
+
 /* Measurement aid, not part of the method: dst[0..nbytes) = src[0..nbytes) with the same 16-byte
  * streaming accesses and grid shape as the update kernel.  Reads nbytes and writes nbytes of HBM,
  * which calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters and gives the practical copy

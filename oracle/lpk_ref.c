@@ -268,3 +268,19 @@ int lpk_ref_kahan_sgd_step(void *theta, void *comp, const void *grad, uint64_t n
     if (vmax) *vmax = (uint64_t)vm;
     return LPK_REF_OK;
 }
+
+/* ---------- classifier bit-width guideline (Section 3, eq. 4) ------------------------------------------------ */
+
+/* Smallest BW for which  alpha / (|class| - 1) >= 2^-(BW-1)  holds, alpha = alpha_q16 / 65536, found by
+ * testing the inequality itself for BW = 2, 3, ... in exact integers:
+ *   alpha_q16 * 2^(BW-1) >= (|class| - 1) * 65536.                                                         */
+int lpk_ref_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
+{
+    if (n_classes < 2 || alpha_q16 == 0 || alpha_q16 > 65535u) return LPK_REF_ERR_ARG;
+    for (int bw = 2; bw < 120; ++bw) {
+        wide lhs = (wide)alpha_q16 * ((wide)1 << (bw - 1));
+        wide rhs = (wide)(n_classes - 1) * 65536;
+        if (lhs >= rhs) return bw;
+    }
+    return LPK_REF_ERR_ARG;
+}

@@ -43,6 +43,8 @@ def load(path):
     L.lpk_ref_select_fraclen_vmax.argtypes = [u64, i32, ci, i32, vp, vp]
     L.lpk_ref_quantize.argtypes = [vp, u64, ci, i32, vp, vp]
     L.lpk_ref_kahan_sgd_step.argtypes = [vp, vp, vp, u64, ci, ci, ci, ci, i32, i32, i32, u32, u32, vp, vp]
+    L.lpk_ref_classifier_min_bits.argtypes = [u32, u32]
+    L.lpk_ref_classifier_min_bits.restype = ci
     for f in (L.lpk_ref_select_fraclen_f32, L.lpk_ref_select_fraclen_vmax,
               L.lpk_ref_quantize, L.lpk_ref_kahan_sgd_step):
         f.restype = ci
@@ -172,3 +174,9 @@ def quantize_mt(x, bits, fl, status=None, out=None, threads=1, chunk=1 << 22):
         for st in stats:
             status[0] |= st[0]
     return out
+
+
+def classifier_min_bits(n_classes, alpha_q16=32768):
+    rc = lib().lpk_ref_classifier_min_bits(int(n_classes), int(alpha_q16))
+    _check(rc if rc < 0 else 0)
+    return rc

@@ -53,6 +53,8 @@ def lib():
         L.lpk_kahan_sgd_step.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
         L.lpk_stream_copy.argtypes = [vp, vp, u64, vp]
         L.lpk_stream_copy.restype = ci
+        L.lpk_classifier_min_bits.argtypes = [u32, u32]
+        L.lpk_classifier_min_bits.restype = ci
         L.lpk_error_string.argtypes = [ci]
         L.lpk_error_string.restype = ctypes.c_char_p
         L.lpk_version.restype = ci
@@ -163,6 +165,13 @@ def lpk_kahan_sgd_step(tl, fl_theta_in, fl_theta_out, fl_grad, lr_q16, wd_q16=0,
 
 def lpk_stream_copy(dst, src, nbytes, stream=None):
     _check(lib().lpk_stream_copy(_addr(dst), _addr(src), int(nbytes), _stream(stream)), "lpk_stream_copy")
+
+
+def lpk_classifier_min_bits(n_classes, alpha_q16=32768):
+    rc = lib().lpk_classifier_min_bits(int(n_classes), int(alpha_q16))
+    if rc < 0:
+        raise LpkError(rc, "lpk_classifier_min_bits")
+    return rc
 
 
 def lpk_version():

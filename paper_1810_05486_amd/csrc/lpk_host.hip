@@ -205,6 +205,16 @@ const char* lpk_error_string(int code)
   }
 }
 
-int lpk_version(void) { return 100; }
+int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
+{
+  if (n_classes < 2 || alpha_q16 == 0 || alpha_q16 > 65535u) return LPK_ERR_INVALID_ARG;
+  // 2^(BW-1) >= (n-1) / alpha  <=>  alpha_q16 << (BW-1) >= (n-1) << 16; the left side grows past any 48-bit right side
+  const uint64_t need = (uint64_t)(n_classes - 1) << 16;
+  int bw = 2;
+  while (((uint64_t)alpha_q16 << (bw - 1)) < need) ++bw;
+  return bw;
+}
+
+int lpk_version(void) { return 101; }
 
 }  // extern "C"

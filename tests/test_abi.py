@@ -78,3 +78,15 @@ def test_null_and_range_arguments():
     assert L.lpk_kahan_sgd_step(None, 8, 8, 8, 1, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_quantize_tensor(None, 0, 8, None, None) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_select_fraclen(None, lpk.LPK_F32, 0, None, None, 8, 8, None, None) == lpk.LPK_ERR_INVALID_ARG
+
+
+def test_classifier_min_bits_matches_the_oracle_everywhere_on_the_host():
+    """Host-only entry point: compared with the oracle's definition-level search (no GPU involved)."""
+    from oracle import ref
+    for n in list(range(2, 300)) + [1000, 1001, 4097, 65536, 1 << 20, (1 << 32) - 1]:
+        for a_q in (32768, 1, 2, 65535, 6554, 16384, 40000):
+            assert lpk.lpk_classifier_min_bits(n, a_q) == ref.classifier_min_bits(n, a_q), (n, a_q)
+    L = lpk.lib()
+    assert L.lpk_classifier_min_bits(1, 32768) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_classifier_min_bits(10, 0) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_classifier_min_bits(10, 65536) == lpk.LPK_ERR_INVALID_ARG

@@ -237,3 +237,27 @@ def test_lr_constants_are_rne_of_the_decimal_literals():
     from decimal import Decimal
     for lit, q in (("0.01", 655), ("0.05", 3277), ("0.1", 6554), ("0.001", 66), ("0.0001", 7), ("0.5", 32768)):
         assert round(Fr(Decimal(lit)) * 2 ** 16) == q
+
+
+# ---- Section 3, eq. 4-5: bit-width of the classifier from the class count -------------------------------
+
+def test_classifier_bit_width_guideline():
+    """What the paper states around eq. 5 with alpha = 0.5: 10-class tasks train with 8 bits everywhere, the 58-
+    and 44-class transfer tasks use an 8-bit classifier, 1000-class ImageNet does not fit 8 bits and takes 16;
+    plus the inequality of eq. 4 checked in exact rationals and eq. 5's closed form in floating point."""
+    import math
+    assert ref.classifier_min_bits(10) <= 8 and ref.classifier_min_bits(58) <= 8 and ref.classifier_min_bits(44) <= 8
+    assert 8 < ref.classifier_min_bits(1000) <= 16
+    assert [ref.classifier_min_bits(n) for n in (10, 58, 44, 1000)] == [6, 8, 8, 12]
+    for n in (2, 3, 5, 9, 10, 17, 33, 100, 257, 1000, 21841, 1 << 20):
+        for a_q in (32768, 1, 65535, 6554, 16384):
+            bw = ref.classifier_min_bits(n, a_q)
+            alpha = Fr(a_q, 65536)
+            assert alpha / (n - 1) >= Fr(1, 2 ** (bw - 1))                      # eq. 4 holds at bw ...
+            assert bw == 2 or alpha / (n - 1) < Fr(1, 2 ** (bw - 2))            # ... and fails one bit below
+            bound = math.log2(n - 1) + math.log2(2 / float(alpha))              # eq. 5: bw > bound - (equality allowed by eq. 4)
+            assert bw >= bound - 1e-9 and bw < bound + 1 + 1e-9 or bw == 2
+    with pytest.raises(ValueError):
+        ref.classifier_min_bits(1)
+    with pytest.raises(ValueError):
+        ref.classifier_min_bits(10, 0)
