@@ -269,6 +269,79 @@ int lpk_ref_kahan_sgd_step(void *theta, void *comp, const void *grad, uint64_t n
     return LPK_REF_OK;
 }
 
+/* ---------- momentum SGD with the lazy update inside ------------------------------------------------------- */
+
+/*
+ * Section 4 trains most networks with the momentum optimizer (mu = 0.9) "with the lazy update implemented in
+ * the optimizer", with an INT8 or INT16 velocity; the paper does not write the combination out.  Reading taken
+ * here (the textbook heavy-ball form with the learning rate inside the velocity):
+ *
+ *     m <- mu * m - lr * (g + wd * theta)          velocity, a third DFX tensor with its own fraclen
+ *     theta <- theta + m                           through Algorithm 1: acc takes the step m
+ *
+ * In fixed point, with G = fl_m_out + 16 the working grid of the velocity (16 guard bits below its LSB):
+ *     w  = RNE(mu_q * m on grid G)                           (exact unless the velocity grid gets coarser)
+ *        + cap(RNE(-lr_q * g on grid G)) + cap(RNE(-lr_q * wd_q * theta on grid G))
+ *     m' = sat(RNE(w / 2^16))                                 stored on grid fl_m_out
+ *     s  = cap(RNE(m' on grid F))                             F = fl_in + d, then exactly the lazy update with this s
+ *     mmax = max |w|  (on grid G), vmax = max |v| (on grid F)
+ */
+int lpk_ref_momentum_sgd_step(void *theta, void *comp, void *mom, const void *grad, uint64_t n,
+                              int theta_bits, int comp_bits, int mom_bits, int grad_bits, int d,
+                              int32_t fl_in, int32_t fl_out, int32_t fl_m_in, int32_t fl_m_out, int32_t fl_g,
+                              uint32_t lr_q, uint32_t mu_q, uint32_t wd_q,
+                              uint64_t *vmax, uint64_t *mmax, uint32_t *status)
+{
+    if (!bits_ok(theta_bits) || !bits_ok(grad_bits) || !bits_ok(mom_bits) || (comp && !bits_ok(comp_bits))) return LPK_REF_ERR_ARG;
+    if (n && (!theta || !grad || !mom)) return LPK_REF_ERR_ARG;
+    if (lr_q > 65535u || wd_q > 65535u || mu_q > 65535u) return LPK_REF_ERR_ARG;
+    if (!comp) d = 0;
+    if (vmax) *vmax = 0;
+    if (mmax) *mmax = 0;
+    int delta = fl_out - fl_in, delta_m = fl_m_out - fl_m_in;
+    if (fl_in < FL_MIN || fl_in > FL_MAX || fl_out < FL_MIN || fl_out > FL_MAX || fl_g < FL_MIN || fl_g > FL_MAX ||
+        fl_m_in < FL_MIN || fl_m_in > FL_MAX || fl_m_out < FL_MIN || fl_m_out > FL_MAX ||
+        d < 0 || d > D_MAX || delta > DELTA_MAX || delta < -DELTA_MAX || delta_m > DELTA_MAX || delta_m < -DELTA_MAX) {
+        if (status) *status |= STATUS_DOMAIN;
+        return LPK_REF_OK;
+    }
+    const int F = fl_in + d, G = fl_m_out + 16;
+    const int u = delta > 0 ? delta : 0;
+    const int k_theta = d + u - delta;
+    wide vm = 0, wm = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        wide th = load_q(theta, i, theta_bits);
+        wide c  = comp ? load_q(comp, i, comp_bits) : 0;
+        wide m  = load_q(mom, i, mom_bits);
+        wide g  = load_q(grad, i, grad_bits);
+
+        /* velocity: mu_q*m sits on grid fl_m_in + 16, lr_q*g on fl_g + 16, lr_q*wd_q*theta on fl_in + 32 */
+        wide w = rescale((wide)mu_q * m, (fl_m_in + 16) - G);
+        w += rescale_cap(-(wide)lr_q * g, (fl_g + 16) - G);
+        if (wd_q) w += rescale_cap(-(wide)lr_q * (wide)wd_q * th, (fl_in + 32) - G);
+        wide aw = w < 0 ? -w : w;
+        if (aw > wm) wm = aw;
+        wide mn = sat(rescale(w, 16), mom_bits);
+        store_q(mom, i, mom_bits, mn);
+
+        /* the new velocity is the step handed to the accumulator (Algorithm 1, 1st assignment) */
+        wide s = rescale_cap(mn, fl_m_out - F);
+        wide v = th * ((wide)1 << d) + c + s;
+        wide av = v < 0 ? -v : v;
+        if (av > vm) vm = av;
+        wide vG  = v * ((wide)1 << u);
+        wide thn = sat(rescale(vG, k_theta), theta_bits);
+        store_q(theta, i, theta_bits, thn);
+        if (comp) {
+            wide r = vG - thn * ((wide)1 << k_theta);
+            store_q(comp, i, comp_bits, sat(rescale(r, k_theta - d), comp_bits));
+        }
+    }
+    if (vmax) *vmax = (uint64_t)vm;
+    if (mmax) *mmax = (uint64_t)wm;
+    return LPK_REF_OK;
+}
+
 /* ---------- classifier bit-width guideline (Section 3, eq. 4) ------------------------------------------------ */
 
 /* Smallest BW for which  alpha / (|class| - 1) >= 2^-(BW-1)  holds, alpha = alpha_q16 / 65536, found by

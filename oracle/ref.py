@@ -43,6 +43,9 @@ def load(path):
     L.lpk_ref_select_fraclen_vmax.argtypes = [u64, i32, ci, i32, vp, vp]
     L.lpk_ref_quantize.argtypes = [vp, u64, ci, i32, vp, vp]
     L.lpk_ref_kahan_sgd_step.argtypes = [vp, vp, vp, u64, ci, ci, ci, ci, i32, i32, i32, u32, u32, vp, vp]
+    L.lpk_ref_momentum_sgd_step.argtypes = [vp, vp, vp, vp, u64, ci, ci, ci, ci, ci, i32, i32, i32, i32, i32,
+                                            u32, u32, u32, vp, vp, vp]
+    L.lpk_ref_momentum_sgd_step.restype = ci
     L.lpk_ref_classifier_min_bits.argtypes = [u32, u32]
     L.lpk_ref_classifier_min_bits.restype = ci
     for f in (L.lpk_ref_select_fraclen_f32, L.lpk_ref_select_fraclen_vmax,
@@ -180,3 +183,47 @@ def classifier_min_bits(n_classes, alpha_q16=32768):
     rc = lib().lpk_ref_classifier_min_bits(int(n_classes), int(alpha_q16))
     _check(rc if rc < 0 else 0)
     return rc
+
+
+def momentum_sgd_step(theta, comp, mom, grad, d, fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr_q, mu_q, wd_q=0,
+                      status=None):
+    """One momentum step with the lazy update inside, in place.  Returns (vmax, mmax)."""
+    for a in (theta, comp, mom, grad):
+        assert a is None or a.flags.c_contiguous
+    n = theta.size
+    assert grad.size == n and mom.size == n and (comp is None or comp.size == n)
+    cb = _bits(comp) if comp is not None else 8
+    if d is None:
+        d = cb - 1
+    vmax, mmax = np.zeros(1, dtype=np.uint64), np.zeros(1, dtype=np.uint64)
+    _check(lib().lpk_ref_momentum_sgd_step(_ptr(theta), _ptr(comp), _ptr(mom), _ptr(grad), n,
+                                           _bits(theta), cb, _bits(mom), _bits(grad), int(d),
+                                           int(fl_in), int(fl_out), int(fl_m_in), int(fl_m_out), int(fl_g),
+                                           int(lr_q), int(mu_q), int(wd_q), _ptr(vmax), _ptr(mmax), _ptr(status)))
+    return int(vmax[0]), int(mmax[0])
+
+
+def momentum_sgd_step_mt(theta, comp, mom, grad, d, fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr_q, mu_q, wd_q=0,
+                         status=None, threads=1, chunk=1 << 22):
+    """Same result as momentum_sgd_step, contiguous chunks on a thread pool (elements are independent)."""
+    n = theta.size
+    if threads <= 1 or n <= chunk:
+        return momentum_sgd_step(theta, comp, mom, grad, d, fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr_q, mu_q, wd_q, status)
+    th, gr, mo = theta.reshape(-1), grad.reshape(-1), mom.reshape(-1)
+    co = comp.reshape(-1) if comp is not None else None
+    dd = d if d is not None else (_bits(co) - 1 if co is not None else 0)
+    stats = []
+
+    def work(lo):
+        hi = min(lo + chunk, n)
+        st = new_status()
+        stats.append(st)
+        return momentum_sgd_step(th[lo:hi], None if co is None else co[lo:hi], mo[lo:hi], gr[lo:hi], dd,
+                                 fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr_q, mu_q, wd_q, st)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        res = list(ex.map(work, range(0, n, chunk)))
+    if status is not None:
+        for st in stats:
+            status[0] |= st[0]
+    return max(r[0] for r in res), max(r[1] for r in res)

@@ -55,22 +55,45 @@ def fraclen(M, bits, lo=-64, hi=64):
     return max(lo, min(hi, best))
 
 
-def step(theta, c, g, theta_bits, comp_bits, d, fl_in, fl_out, fl_g, lr_q, wd_q=0, kahan=True):
-    """One element.  Returns (theta', c', |v| in units of the working grid)."""
-    if not kahan:
-        d, c = 0, 0
-    F = fl_in + d                                  # grid of the compensation word
-    lr, wd = Fr(lr_q, 2 ** 16), Fr(wd_q, 2 ** 16)
-    theta_real, c_real, g_real = theta * two(-fl_in), c * two(-F), g * two(-fl_g)
-
-    s = max(-CAP, min(CAP, rne(-lr * g_real * two(F))))
-    if wd_q:
-        s += max(-CAP, min(CAP, rne(-lr * wd * theta_real * two(F))))
-    v_real = theta_real + c_real + s * two(-F)      # the compensated sum, kept wide
-
+def _apply(theta, c, s, theta_bits, comp_bits, d, fl_in, fl_out, kahan):
+    """Fold an already quantized step s (an integer number of c-LSBs of the input grid) into theta and c."""
+    F = fl_in + d
+    v_real = theta * two(-fl_in) + c * two(-F) + s * two(-F)      # the compensated sum, kept wide
     theta_new = sat(rne(v_real * two(fl_out)), theta_bits)
     resid = v_real - theta_new * two(-fl_out)
     c_new = sat(rne(resid * two(fl_out + d)), comp_bits) if kahan else 0
     vabs = abs(v_real) * two(F)
     assert vabs.denominator == 1
     return theta_new, c_new, int(vabs)
+
+
+def step(theta, c, g, theta_bits, comp_bits, d, fl_in, fl_out, fl_g, lr_q, wd_q=0, kahan=True):
+    """One element.  Returns (theta', c', |v| in units of the working grid)."""
+    if not kahan:
+        d, c = 0, 0
+    F = fl_in + d                                  # grid of the compensation word
+    lr, wd = Fr(lr_q, 2 ** 16), Fr(wd_q, 2 ** 16)
+    theta_real, g_real = theta * two(-fl_in), g * two(-fl_g)
+    s = max(-CAP, min(CAP, rne(-lr * g_real * two(F))))
+    if wd_q:
+        s += max(-CAP, min(CAP, rne(-lr * wd * theta_real * two(F))))
+    return _apply(theta, c, s, theta_bits, comp_bits, d, fl_in, fl_out, kahan)
+
+
+def momentum_step(theta, c, m, g, theta_bits, comp_bits, mom_bits, d, fl_in, fl_out, fl_m_in, fl_m_out, fl_g,
+                  lr_q, mu_q, wd_q=0, kahan=True):
+    """Momentum SGD (velocity m <- mu*m - lr*(g + wd*theta), theta <- theta + m) with the lazy update inside.
+    Returns (theta', c', m', |v| on grid F, |w| on the velocity's working grid fl_m_out + 16)."""
+    if not kahan:
+        d, c = 0, 0
+    lr, mu, wd = Fr(lr_q, 2 ** 16), Fr(mu_q, 2 ** 16), Fr(wd_q, 2 ** 16)
+    G = fl_m_out + 16
+    w = rne(mu * m * two(-fl_m_in) * two(G))
+    w += max(-CAP, min(CAP, rne(-lr * g * two(-fl_g) * two(G))))
+    if wd_q:
+        w += max(-CAP, min(CAP, rne(-lr * wd * theta * two(-fl_in) * two(G))))
+    m_new = sat(rne(Fr(w, 2 ** 16)), mom_bits)
+    F = fl_in + d
+    s = max(-CAP, min(CAP, rne(m_new * two(-fl_m_out) * two(F))))
+    t, cn, vabs = _apply(theta, c, s, theta_bits, comp_bits, d, fl_in, fl_out, kahan)
+    return t, cn, m_new, vabs, abs(w)

@@ -9,6 +9,7 @@ import pytest
 from oracle import ref
 import test_oracle_bruteforce as bf
 import test_oracle_pins as pins
+import test_oracle_momentum as mom
 
 SRC = os.path.join(os.path.dirname(ref.__file__), "lpk_ref.c")
 
@@ -34,6 +35,13 @@ MUTATIONS = [
     ("quantize_fl_sign", "rescale(neg ? -m : m, -(ex + fl))", "rescale(neg ? -m : m, -(ex - fl))"),
     ("vmax_window", "fl_default + DELTA_MAX) fl = fl_default + DELTA_MAX;", "fl_default + DELTA_MAX) fl = fl_default;"),
     ("comp_added_twice", "wide c  = comp ? load_q(comp, i, comp_bits) : 0;", "wide c  = comp ? 2 * load_q(comp, i, comp_bits) : 0;"),
+    ("momentum_mu_grid", "rescale((wide)mu_q * m, (fl_m_in + 16) - G);", "rescale((wide)mu_q * m, fl_m_in - G);"),
+    ("momentum_gradient_sign", "w += rescale_cap(-(wide)lr_q * g, (fl_g + 16) - G);", "w += rescale_cap((wide)lr_q * g, (fl_g + 16) - G);"),
+    ("momentum_guard_bits", "wide mn = sat(rescale(w, 16), mom_bits);", "wide mn = sat(rescale(w, 15), mom_bits);"),
+    ("momentum_step_grid", "wide s = rescale_cap(mn, fl_m_out - F);", "wide s = rescale_cap(mn, F - fl_m_out);"),
+    ("momentum_old_velocity_used", "wide s = rescale_cap(mn, fl_m_out - F);", "wide s = rescale_cap(m, fl_m_out - F);"),
+    ("momentum_decay_grid", "* th, (fl_in + 32) - G);", "* th, (fl_in + 16) - G);"),
+    ("momentum_velocity_not_saturated", "wide mn = sat(rescale(w, 16), mom_bits);", "wide mn = rescale(w, 16);"),
     ("theta_unscaled", "wide v = th * ((wide)1 << d) + c + s;", "wide v = th + c + s;"),
 ]
 
@@ -48,6 +56,9 @@ CHECKS = [
     lambda: pins.test_conservation_invariant(8),
     pins.test_fraclen_hand_cases,
     pins.test_quantize_hand_cases,
+    lambda: mom.test_momentum_step_bruteforce(0),
+    mom.test_velocity_decay_and_fixed_point,
+    mom.test_momentum_conserves_theta_plus_c,
 ]
 
 
