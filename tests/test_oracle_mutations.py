@@ -65,10 +65,10 @@ CHECKS = [
 @pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
 def test_planted_mistake_is_caught(name, old, new, tmp_path, monkeypatch):
     text = open(SRC).read()
-    assert text.count(old) == 1, "mutation anchor must match the oracle source exactly once: %r" % old
+    assert text.count(old) >= 1, "mutation anchor must match the oracle source: %r" % old
     c = tmp_path / "mut.c"
     so = tmp_path / ("mut_%s.so" % name)
-    c.write_text(text.replace(old, new))
+    c.write_text(text.replace(old, new, 1))        # the first match (the plain update comes first in the file)
     subprocess.check_call(["gcc", "-O1", "-w", "-shared", "-fPIC", "-o", str(so), str(c), "-lm"])
     monkeypatch.setattr(ref, "_lib", ref.load(str(so)))
     caught = False
