@@ -59,7 +59,7 @@ typedef enum {
 typedef enum { LPK_I8 = 1, LPK_I16 = 2, LPK_F32 = 4, LPK_VMAX_U64 = 8 } lpk_dtype;
 
 /* which member of the descriptor a call reads its width from / writes to */
-typedef enum { LPK_SEL_GRAD = 0, LPK_SEL_THETA = 1 } lpk_selector;
+typedef enum { LPK_SEL_GRAD = 0, LPK_SEL_THETA = 1, LPK_SEL_MOMENTUM = 2 } lpk_selector;
 
 /* bits of the device status word */
 #define LPK_STATUS_NONFINITE 1u  /* a NaN or Inf was met in fp32 input                               */
@@ -81,6 +81,9 @@ typedef struct {
   uint8_t     comp_dtype;  /* LPK_I8 or LPK_I16 (ignored when comp == NULL) */
   uint8_t     grad_dtype;  /* LPK_I8 or LPK_I16 */
   uint8_t     comp_shift;  /* d = fl_comp - fl_theta, 0..24; LPK_COMP_SHIFT_DEFAULT = bits(comp_dtype) - 1 */
+  uint8_t     momentum_dtype; /* LPK_I8 or LPK_I16 (ignored when momentum == NULL) */
+  uint8_t     reserved[3];    /* set to 0 */
+  void*       momentum;    /* device; DFX ints, velocity of lpk_momentum_sgd_step, updated in place; may be NULL */
 } lpk_tensor_desc;
 
 typedef struct lpk_tensor_list lpk_tensor_list;   /* opaque */
@@ -109,8 +112,8 @@ uint64_t lpk_tensor_list_tiles(const lpk_tensor_list* list);
  *   fl*(M, W) = the largest fl with RNE(M * 2^fl) <= 2^(W-1) - 1, clamped to [-64, 64]:
  *   the finest grid on which the tensor's own maximum does not saturate.
  *
- * W = bits of desc.grad_dtype (dst_sel == LPK_SEL_GRAD) or desc.theta_dtype
- * (LPK_SEL_THETA).
+ * W = bits of desc.grad_dtype (dst_sel == LPK_SEL_GRAD), desc.theta_dtype
+ * (LPK_SEL_THETA) or desc.momentum_dtype (LPK_SEL_MOMENTUM, LPK_VMAX_U64 only).
  *
  * src_kind == LPK_F32: M = max_i |desc.src_f32[i]| (src_f32 must be non-NULL
  *   for every tensor with n > 0).  M == 0 (or n == 0) -> fl_default[t].  Any
@@ -123,6 +126,9 @@ uint64_t lpk_tensor_list_tiles(const lpk_tensor_list* list);
  *   -> fl_default[t].  The result is additionally clamped to
  *   fl_default[t] +- 15, so that it can be handed to the next step as
  *   fl_theta_out when fl_default is that step's fl_theta_in.
+ *   With dst_sel == LPK_SEL_MOMENTUM the maximum is the mmax of
+ *   lpk_momentum_sgd_step and `fl_theta_in` is the fl_mom_out array that step
+ *   was called with: M = vmax[t] * 2^-(fl_theta_in[t] + 16).
  *
  * vmax (uint64), fl_theta_in, fl_default, fl_out (int32): device arrays of
  * n_tensors entries.  fl_out is written for every tensor.
@@ -166,6 +172,31 @@ int lpk_kahan_sgd_step(lpk_tensor_list* list,
                        const int32_t* fl_theta_in, const int32_t* fl_theta_out, const int32_t* fl_grad,
                        uint32_t lr_q16, uint32_t wd_q16,
                        uint64_t* vmax_out, uint32_t* status, void* stream);
+
+/*
+ * Momentum SGD with the lazy update inside (Section 4: the momentum optimizer, mu = 0.9, with Algorithm 1
+ * implemented in the optimizer; INT8 or INT16 velocity).  Heavy-ball form with the learning rate inside
+ * the velocity:  m <- mu*m - lr*(g + wd*theta);  theta <- theta + m  through Algorithm 1.
+ * desc.momentum (non-NULL for every tensor with n > 0) holds m in DFX(bits(momentum_dtype), fl_mom).
+ * Per element, with G = fl_mom_out[t] + 16 (16 guard bits below the velocity's LSB) and F, cap as above:
+ *
+ *   w  = RNE(mu_q16 * m * 2^-(fl_mom_in[t] - fl_mom_out[t]))                 (exact unless the grid coarsens)
+ *      + cap(RNE(-lr_q16 * g * 2^-(fl_grad[t] - fl_mom_out[t])))
+ *      + cap(RNE(-lr_q16 * wd_q16 * theta * 2^-(fl_theta_in[t] + 16 - fl_mom_out[t])))     if wd_q16 != 0
+ *   m' = sat(RNE(w * 2^-16))                                                  stored on grid fl_mom_out[t]
+ *   s  = cap(RNE(m' * 2^-(fl_mom_out[t] - F)))
+ *   v, theta', c', vmax_out exactly as in lpk_kahan_sgd_step with this s;  mmax_out[t] = max_i |w_i| (grid G)
+ *
+ * fl_mom_in / fl_mom_out: device int32[n_tensors], in [-64, 64], |difference| <= 15.  mu_q16 <= 65535.
+ * mmax_out: device uint64[n_tensors] or NULL, cleared and rewritten by the call; feed it to
+ * lpk_select_fraclen(LPK_VMAX_U64, LPK_SEL_MOMENTUM) to re-select the velocity's fraclen.
+ * Errors: as lpk_kahan_sgd_step, plus INVALID_ARG when a non-empty tensor has no momentum buffer.
+ */
+int lpk_momentum_sgd_step(lpk_tensor_list* list,
+                          const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                          const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_grad,
+                          uint32_t lr_q16, uint32_t mu_q16, uint32_t wd_q16,
+                          uint64_t* vmax_out, uint64_t* mmax_out, uint32_t* status, void* stream);
 
 /*
  * Bit-width guideline for the last fully-connected layer (Section 3, eq. 4-5): the smallest width BW with

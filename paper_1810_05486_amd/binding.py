@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "liblpk.so")
 
 LPK_OK, LPK_ERR_INVALID_ARG, LPK_ERR_UNSUPPORTED, LPK_ERR_DEVICE = 0, -1, -2, -3
 LPK_I8, LPK_I16, LPK_F32, LPK_VMAX_U64 = 1, 2, 4, 8
-LPK_SEL_GRAD, LPK_SEL_THETA = 0, 1
+LPK_SEL_GRAD, LPK_SEL_THETA, LPK_SEL_MOMENTUM = 0, 1, 2
 LPK_STATUS_NONFINITE, LPK_STATUS_DOMAIN = 1, 2
 LPK_COMP_SHIFT_DEFAULT = 0xFF
 
@@ -21,7 +21,9 @@ class lpk_tensor_desc(ctypes.Structure):
     _fields_ = [("theta", ctypes.c_void_p), ("comp", ctypes.c_void_p), ("grad", ctypes.c_void_p),
                 ("src_f32", ctypes.c_void_p), ("n", ctypes.c_uint64),
                 ("theta_dtype", ctypes.c_uint8), ("comp_dtype", ctypes.c_uint8),
-                ("grad_dtype", ctypes.c_uint8), ("comp_shift", ctypes.c_uint8)]
+                ("grad_dtype", ctypes.c_uint8), ("comp_shift", ctypes.c_uint8),
+                ("momentum_dtype", ctypes.c_uint8), ("reserved", ctypes.c_uint8 * 3),
+                ("momentum", ctypes.c_void_p)]
 
 
 class LpkError(RuntimeError):
@@ -51,6 +53,8 @@ def lib():
         L.lpk_select_fraclen.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, vp]
         L.lpk_quantize_tensor.argtypes = [vp, ci, vp, vp, vp]
         L.lpk_kahan_sgd_step.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
+        L.lpk_momentum_sgd_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, u32, vp, vp, vp, vp]
+        L.lpk_momentum_sgd_step.restype = ci
         L.lpk_stream_copy.argtypes = [vp, vp, u64, vp]
         L.lpk_stream_copy.restype = ci
         L.lpk_classifier_min_bits.argtypes = [u32, u32]
@@ -97,7 +101,7 @@ def _check(rc, where):
         raise LpkError(rc, where)
 
 
-def make_desc(theta, comp, grad, src_f32=None, comp_shift=LPK_COMP_SHIFT_DEFAULT):
+def make_desc(theta, comp, grad, src_f32=None, comp_shift=LPK_COMP_SHIFT_DEFAULT, momentum=None):
     """Descriptor for one tensor from torch tensors living on the GPU."""
     d = lpk_tensor_desc()
     d.theta, d.comp, d.grad, d.src_f32 = _addr(theta), _addr(comp), _addr(grad), _addr(src_f32)
@@ -106,6 +110,8 @@ def make_desc(theta, comp, grad, src_f32=None, comp_shift=LPK_COMP_SHIFT_DEFAULT
     d.comp_dtype = _dtype_code(comp) if comp is not None else LPK_I8
     d.grad_dtype = _dtype_code(grad)
     d.comp_shift = comp_shift
+    d.momentum = _addr(momentum)
+    d.momentum_dtype = _dtype_code(momentum) if momentum is not None else LPK_I8
     return d
 
 
@@ -161,6 +167,14 @@ def lpk_kahan_sgd_step(tl, fl_theta_in, fl_theta_out, fl_grad, lr_q16, wd_q16=0,
     _check(lib().lpk_kahan_sgd_step(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_grad),
                                     int(lr_q16), int(wd_q16), _addr(vmax_out), _addr(status), _stream(stream)),
            "lpk_kahan_sgd_step")
+
+
+def lpk_momentum_sgd_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16=0,
+                          vmax_out=None, mmax_out=None, status=None, stream=None):
+    _check(lib().lpk_momentum_sgd_step(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_mom_in),
+                                       _addr(fl_mom_out), _addr(fl_grad), int(lr_q16), int(mu_q16), int(wd_q16),
+                                       _addr(vmax_out), _addr(mmax_out), _addr(status), _stream(stream)),
+           "lpk_momentum_sgd_step")
 
 
 def lpk_stream_copy(dst, src, nbytes, stream=None):

@@ -21,7 +21,7 @@
 // Running maximum of |v| per tensor: per-lane max, DPP wave reduction when a
 // wave moves to another tensor, LDS stage across the four waves of a block at
 // the end, one atomic per (block, tensor).
-#include "lpk_device.hpp"
+#include "step_common.hpp"
 
 namespace lpk {
 
@@ -42,31 +42,6 @@ struct StepParams {
 
 // ---------------------------------------------------------------- generic (int64)
 
-__device__ __forceinline__ int64_t rne_shr64(int64_t x, int k)      // RNE(x / 2^k), 0 <= k <= 62
-{
-  if (k == 0) return x;
-  int64_t  q    = x >> k;
-  uint64_t rem  = (uint64_t)x & ((1ull << k) - 1ull);
-  uint64_t half = 1ull << (k - 1);
-  return q + (int64_t)((rem > half) | ((rem == half) & (uint64_t)(q & 1)));
-}
-
-__device__ __forceinline__ int64_t rescale_cap64(int64_t x, int k)   // |x| < 2^48; clamp(RNE(x * 2^-k), +-2^40)
-{
-  const int64_t cap = 1ll << 40;
-  if (x == 0) return 0;
-  if (k > 0) {
-    if (k >= 50) return 0;
-    int64_t q = rne_shr64(x, k);
-    return q > cap ? cap : (q < -cap ? -cap : q);
-  }
-  int sh = -k;
-  if (sh >= 41) return x > 0 ? cap : -cap;
-  int64_t lim = cap >> sh;
-  if (x > lim) return cap;
-  if (x < -lim) return -cap;
-  return x * (1ll << sh);
-}
 
 __device__ __forceinline__ void update_generic(const StepParams& p, int64_t th, int64_t c, int64_t g,
                                                int& th_new, int& c_new, uint64_t& vabs)
@@ -84,14 +59,6 @@ __device__ __forceinline__ void update_generic(const StepParams& p, int64_t th, 
   th_new = (int)tn; c_new = (int)cn;
 }
 
-__device__ __forceinline__ int load_elem(const void* p, uint64_t i, int bits)
-{
-  return bits == 8 ? (int)((const int8_t*)p)[i] : (int)((const int16_t*)p)[i];
-}
-__device__ __forceinline__ void store_elem(void* p, uint64_t i, int bits, int v)
-{
-  if (bits == 8) ((int8_t*)p)[i] = (int8_t)v; else ((int16_t*)p)[i] = (int16_t)v;
-}
 
 // Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
 __device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane)
@@ -133,25 +100,6 @@ __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, 
   cn = min(max(r, p.qmin_c), p.qmax_c);
 }
 
-// Streaming accesses: global address space (global_load/global_store, not flat), non-temporal.
-template <typename V> __device__ __forceinline__ V ld_stream(const V* p)
-{
-#if LPK_NT_LOAD
-  return __builtin_nontemporal_load((const LPK_GLOBAL V*)p);
-#else
-  return *(const LPK_GLOBAL V*)p;
-#endif
-}
-template <typename V> __device__ __forceinline__ void st_stream(V* p, V v)
-{
-#if LPK_NT_STORE
-  __builtin_nontemporal_store(v, (LPK_GLOBAL V*)p);
-#else
-  *(LPK_GLOBAL V*)p = v;
-#endif
-}
-
-typedef int v4i __attribute__((ext_vector_type(4)));
 
 // 16 consecutive elements per lane; W = width of theta and comp (8 or 16), grads int16.
 template <int W> struct Group;
@@ -175,8 +123,6 @@ __device__ __forceinline__ void load_group(Group<16>& G, const TensorDev& T, uin
   G.g[1]  = ld_stream((const v4i*)((const int16_t*)T.grad + e + 8));
 }
 
-__device__ __forceinline__ int sx8(int w, int b)  { return (int)(int8_t)(w >> (8 * b)); }
-__device__ __forceinline__ int sx16(int w, int h) { return (int)(int16_t)(w >> (16 * h)); }
 
 template <bool DECAY>
 __device__ __forceinline__ void compute_store_group(const StepParams& p, Group<8>& G, const TensorDev& T, uint64_t e, int& vmx, int& vmn)
@@ -324,11 +270,12 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   p.path = 1;
 
   // Fast path: same-width theta/comp with int16 grads on 16-byte aligned buffers, no grid move,
-  // 1 <= d, step shift >= 9 (so the fp32 FMA rounding trick is exact and |s| <= 2^22 + 1),
-  // and every intermediate provably inside int32.
-  if (!p.has_comp || !T.vec_step || p.wt != p.wc || p.wg != 16 || delta != 0 || p.d < 1 || p.kg < 9) return;
+  // 1 <= d, a step shift k with |lr * g| <= lr * 2^15 < 2^(22+k) (so the fp32 FMA rounding trick is exact
+  // and |s| < 2^22), and every intermediate provably inside int32.
+  if (!p.has_comp || !T.vec_step || p.wt != p.wc || p.wg != 16 || delta != 0 || p.d < 1 || p.kg < 1) return;
+  if (p.kg < 9 && ((int64_t)lr << 15) >= (1ll << (22 + p.kg))) return;
   int64_t bound = (1ll << (p.wt - 1 + p.d)) + (1ll << (p.wc - 1));             // |theta * 2^d| + |c|
-  bound += p.kg < 32 ? (1ll << (31 - p.kg)) + 1 : 0;                            // |s_g|
+  bound += p.kg < 40 ? (((int64_t)lr << 15) >> p.kg) + 1 : 0;                   // |s_g|
   int64_t sw = 0;
   if (p.lrwd) sw = ((p.lrwd << (p.wt - 1)) >> p.kw) + 1;                        // |s_w|
   bound += sw;
@@ -348,11 +295,6 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
 
 // ---------------------------------------------------------------- the kernel
 
-__device__ __forceinline__ void flush_wave(uint64_t* vmax, int tensor, uint64_t lane_max, int lane)
-{
-  uint64_t m = wave_max_u64(lane_max);
-  if (lane == 0 && m) atomicMax((unsigned long long*)&vmax[tensor], (unsigned long long)m);
-}
 
 __global__ void __launch_bounds__(kBlock)
 kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
@@ -404,21 +346,7 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
   if (status && status_bits && lane == 0) atomicOr(status, status_bits);
 
   // LDS stage: the four waves of a block usually end on the same tensor.
-  if (vmax) {
-    uint64_t m = wave_max_u64(lane_max);
-    if (lane == 0) { s_tensor[wave] = cur; s_max[wave] = m; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      for (int a = 0; a < kWavesPerBlock; ++a) {
-        int ta = s_tensor[a];
-        if (ta < 0) continue;
-        uint64_t ma = s_max[a];
-        for (int b = a + 1; b < kWavesPerBlock; ++b)
-          if (s_tensor[b] == ta) { ma = s_max[b] > ma ? s_max[b] : ma; s_tensor[b] = -1; }
-        if (ma) atomicMax((unsigned long long*)&vmax[ta], (unsigned long long)ma);
-      }
-    }
-  }
+  if (vmax) flush_block(vmax, cur, lane_max, lane, wave, s_tensor, s_max);
 }
 
 __global__ void __launch_bounds__(kBlock) fill_u64_kernel(uint64_t* p, uint32_t n, uint64_t v)

@@ -39,8 +39,9 @@ struct TensorDev {
   const void* src;       // fp32 source
   uint64_t    n;
   uint8_t     wt, wc, wg, d;        // widths in bits (wc = 0 without comp), comp shift
-  uint8_t     vec_step, vec_src_grad, vec_src_theta, pad0;   // 16-byte alignment facts
-  uint32_t    pad1[4];
+  uint8_t     vec_step, vec_src_grad, vec_src_theta, wm;     // 16-byte alignment facts; velocity width (0 = none)
+  void*       mom;       // velocity of the momentum update, nullptr = none
+  uint8_t     vec_mom, pad0[7];
 };
 static_assert(sizeof(TensorDev) == 64, "descriptor layout");
 

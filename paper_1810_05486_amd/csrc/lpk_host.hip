@@ -12,14 +12,18 @@ hipError_t launch_kahan_step(const TensorDev*, const Tile*, uint32_t n_tiles, ui
                              const int32_t*, const int32_t*, const int32_t*, uint32_t lr, uint32_t wd,
                              uint64_t* vmax, uint32_t* status, hipStream_t);
 hipError_t launch_select_f32(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                             int use_theta_width, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
+                             int sel, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
                              uint32_t* status, hipStream_t);
-hipError_t launch_select_vmax(const TensorDev*, uint32_t n_tensors, int use_theta_width, const uint64_t* vmax,
+hipError_t launch_select_vmax(const TensorDev*, uint32_t n_tensors, int sel, const uint64_t* vmax,
                               const int32_t* fl_theta_in, const int32_t* fl_default, int32_t* fl_out, uint32_t* status,
                               hipStream_t);
 hipError_t launch_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t grid, int to_theta,
                            const int32_t* fl, uint32_t* status, hipStream_t);
 hipError_t launch_stream_copy(void* dst, const void* src, uint64_t nbytes, uint32_t grid, hipStream_t);
+hipError_t launch_momentum_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
+                                const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
+                                const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
+                                uint64_t* vmax, uint64_t* mmax, uint32_t* status, hipStream_t);
 }  // namespace lpk
 
 using namespace lpk;
@@ -30,6 +34,7 @@ struct lpk_tensor_list {
   int        device    = 0;
   uint32_t   grid      = 0;        // blocks of the persistent launches
   bool       all_src   = false;    // every non-empty tensor has an fp32 source
+  bool       all_mom   = false;    // every non-empty tensor has a velocity buffer
   TensorDev* d_tensors = nullptr;
   Tile*      d_tiles   = nullptr;
   uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls
@@ -56,7 +61,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
 
   std::vector<TensorDev> tensors(n_tensors);
   std::vector<Tile> tiles;
-  bool all_src = true;
+  bool all_src = true, all_mom = true;
   uint64_t total_tiles = 0;
   for (uint32_t t = 0; t < n_tensors; ++t) {
     const lpk_tensor_desc& D = descs[t];
@@ -72,6 +77,9 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     if (!aligned(D.theta, wt / 8) || !aligned(D.grad, wg / 8) || (D.comp && !aligned(D.comp, wc / 8)) ||
         !aligned(D.src_f32, 4)) return LPK_ERR_INVALID_ARG;
     if (D.n && !D.src_f32) all_src = false;
+    const int wm = D.momentum ? dtype_bits(D.momentum_dtype) : 0;
+    if (D.momentum && (!wm || !aligned(D.momentum, wm / 8))) return LPK_ERR_INVALID_ARG;
+    if (D.n && !D.momentum) all_mom = false;
 
     TensorDev& T = tensors[t];
     T = TensorDev{};
@@ -80,6 +88,8 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     T.vec_step      = aligned(D.theta, 16) && aligned(D.grad, 16) && D.comp && aligned(D.comp, 16);
     T.vec_src_grad  = D.src_f32 && aligned(D.src_f32, 16) && aligned(D.grad, 16);
     T.vec_src_theta = D.src_f32 && aligned(D.src_f32, 16) && aligned(D.theta, 16);
+    T.mom = D.momentum; T.wm = (uint8_t)wm;
+    T.vec_mom = T.vec_step && D.momentum && aligned(D.momentum, 16);
     total_tiles += (D.n + kTileElems - 1) / kTileElems;
   }
   if (total_tiles >= (1ull << 31)) return LPK_ERR_UNSUPPORTED;
@@ -95,6 +105,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   L->n_tensors = n_tensors;
   L->n_tiles = (uint32_t)tiles.size();
   L->all_src = all_src;
+  L->all_mom = all_mom;
 
   hipDeviceProp_t prop;
   bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
@@ -144,16 +155,17 @@ int lpk_select_fraclen(lpk_tensor_list* L, int src_kind, int dst_sel,
                        int32_t* fl_out, uint32_t* status, void* stream)
 {
   if (!L || !fl_default || !fl_out) return LPK_ERR_INVALID_ARG;
-  if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA) return LPK_ERR_INVALID_ARG;
+  if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA && dst_sel != LPK_SEL_MOMENTUM) return LPK_ERR_INVALID_ARG;
+  if (dst_sel == LPK_SEL_MOMENTUM && (src_kind != LPK_VMAX_U64 || !L->all_mom)) return LPK_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (src_kind == LPK_F32) {
     if (!L->all_src) return LPK_ERR_INVALID_ARG;
-    e = launch_select_f32(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, dst_sel == LPK_SEL_THETA,
+    e = launch_select_f32(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, dst_sel,
                           L->d_scratch, fl_default, fl_out, status, s);
   } else if (src_kind == LPK_VMAX_U64) {
     if (!vmax || !fl_theta_in) return LPK_ERR_INVALID_ARG;
-    e = launch_select_vmax(L->d_tensors, L->n_tensors, dst_sel == LPK_SEL_THETA, vmax, fl_theta_in, fl_default, fl_out, status, s);
+    e = launch_select_vmax(L->d_tensors, L->n_tensors, dst_sel, vmax, fl_theta_in, fl_default, fl_out, status, s);
   } else {
     return LPK_ERR_INVALID_ARG;
   }
@@ -177,6 +189,20 @@ int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+int lpk_momentum_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                          const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_grad,
+                          uint32_t lr_q16, uint32_t mu_q16, uint32_t wd_q16,
+                          uint64_t* vmax_out, uint64_t* mmax_out, uint32_t* status, void* stream)
+{
+  if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_grad) return LPK_ERR_INVALID_ARG;
+  if (lr_q16 > 65535u || wd_q16 > 65535u || mu_q16 > 65535u) return LPK_ERR_INVALID_ARG;
+  if (!L->all_mom) return LPK_ERR_INVALID_ARG;
+  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, fl_theta_in, fl_theta_out,
+                                      fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16, vmax_out, mmax_out, status,
+                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
@@ -215,6 +241,6 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
   return bw;
 }
 
-int lpk_version(void) { return 101; }
+int lpk_version(void) { return 102; }
 
 }  // extern "C"

@@ -1,0 +1,308 @@
+// Momentum SGD with the lazy update inside (paper, Section 4: momentum optimizer with Algorithm 1 implemented
+// in the optimizer, INT8 or INT16 velocity).  One fused launch over every tile of every tensor:
+//
+//   w  = RNE(mu*m on grid G) + cap(RNE(-lr*g on G)) [+ cap(RNE(-lr*wd*theta on G))],  G = fl_m_out + 16
+//   m' = sat(RNE(w / 2^16));   s = cap(RNE(m' on grid F));   then Algorithm 1 with step s.
+//
+// Same work distribution as the plain update (persistent wavefronts over the tile table, 16 consecutive
+// elements per lane per pass, dwordx4 non-temporal accesses).  Two bit-identical arithmetic paths chosen per
+// tensor: generic 64-bit, and a 32-bit one (same-width theta/comp, int16 grads, no grid moves) in which the
+// gradient term is rounded by one fp32 FMA and the decay term by one fp64 FMA, as in the plain update.
+#include "step_common.hpp"
+
+namespace lpk {
+
+struct MomParams {
+  int      path;                 // 0 skip, 1 generic, 2 fast
+  int      wt, wc, wg, wm, d, has_comp;
+  int      k1, k2, k3w, k3;      // shifts: mu*m -> G, lr*g -> G, lr*wd*theta -> G, m' -> F
+  int      u, kth, kc;
+  int64_t  lr, mu, lrwd;
+  int      qmin_t, qmax_t, qmin_c, qmax_c, qmin_m, qmax_m;
+  // fast path
+  int      mu_i;  float nlr_f, magic_f;  int magic_fi;
+  double   nlrwd_d, magic_d;  int magic_dlo;
+  int      half_m1, s_half_m1, s_shl;      // rounding addend of v -> theta; of m' -> s (k3 > 0), or left shift (k3 <= 0)
+};
+
+__device__ __forceinline__ void update_generic_mom(const MomParams& p, int64_t th, int64_t c, int64_t m, int64_t g,
+                                                   int& th_new, int& c_new, int& m_new, uint64_t& vabs, uint64_t& wabs)
+{
+  int64_t w = rescale64(p.mu * m, p.k1);
+  w += rescale_cap64(-p.lr * g, p.k2);
+  if (p.lrwd) w += rescale_cap64(-p.lrwd * th, p.k3w);
+  wabs = (uint64_t)(w < 0 ? -w : w);
+  int64_t mn = rne_shr64(w, 16);
+  mn = mn > p.qmax_m ? p.qmax_m : (mn < p.qmin_m ? p.qmin_m : mn);
+  int64_t s = rescale_cap64(mn, p.k3);
+  int64_t v = th * (1ll << p.d) + c + s;
+  vabs = (uint64_t)(v < 0 ? -v : v);
+  int64_t vG = v * (1ll << p.u);
+  int64_t tn = rne_shr64(vG, p.kth);
+  tn = tn > p.qmax_t ? p.qmax_t : (tn < p.qmin_t ? p.qmin_t : tn);
+  int64_t r  = vG - tn * (1ll << p.kth);
+  int64_t cn = rne_shr64(r, p.kc);
+  cn = cn > p.qmax_c ? p.qmax_c : (cn < p.qmin_c ? p.qmin_c : cn);
+  th_new = (int)tn; c_new = (int)cn; m_new = (int)mn;
+}
+
+__device__ __forceinline__ void tile_generic_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
+                                                 uint64_t& vm, uint64_t& wm)
+{
+  for (uint32_t j = lane; j < cnt; j += kWave) {
+    uint64_t i = off + j;
+    int th = load_elem(T.theta, i, p.wt);
+    int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
+    int m  = load_elem(T.mom, i, p.wm);
+    int g  = load_elem(T.grad, i, p.wg);
+    int tn, cn, mn; uint64_t va, wa;
+    update_generic_mom(p, th, c, m, g, tn, cn, mn, va, wa);
+    vm = va > vm ? va : vm;
+    wm = wa > wm ? wa : wm;
+    store_elem(T.theta, i, p.wt, tn);
+    if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
+    store_elem(T.mom, i, p.wm, mn);
+  }
+}
+
+// ---------------------------------------------------------------- fast path
+
+struct MaxTrack { int vmx, vmn, wmx, wmn; };
+
+template <bool DECAY, bool SHR>
+__device__ __forceinline__ void update_fast_mom(const MomParams& p, int th, int c, int m, int g, int& tn, int& cn, int& mn, MaxTrack& mt)
+{
+  int w = __mul24(m, p.mu_i) + (__float_as_int(__builtin_fmaf((float)g, p.nlr_f, p.magic_f)) - p.magic_fi);
+  if (DECAY) w += __double2loint(__builtin_fma((double)th, p.nlrwd_d, p.magic_d)) - p.magic_dlo;
+  mt.wmx = w > mt.wmx ? w : mt.wmx;
+  mt.wmn = w < mt.wmn ? w : mt.wmn;
+  int q = (w + 0x7fff + ((w >> 16) & 1)) >> 16;                      // RNE(w / 2^16)
+  mn = min(max(q, p.qmin_m), p.qmax_m);
+  int s;
+  if (SHR) s = (mn + p.s_half_m1 + ((mn >> p.k3) & 1)) >> p.k3;      // RNE(m' / 2^k3), k3 >= 1
+  else     s = (int)((unsigned)mn << p.s_shl);                       // exact
+  int v = (int)((unsigned)th << p.d) + c + s;
+  mt.vmx = v > mt.vmx ? v : mt.vmx;
+  mt.vmn = v < mt.vmn ? v : mt.vmn;
+  int qt = (v + p.half_m1 + ((v >> p.d) & 1)) >> p.d;
+  tn = min(max(qt, p.qmin_t), p.qmax_t);
+  int r = v - (int)((unsigned)tn << p.d);
+  cn = min(max(r, p.qmin_c), p.qmax_c);
+}
+
+// 16 consecutive elements per lane.  WT = width of theta and comp, WM = width of the velocity; grads int16.
+template <int WT, int WM> struct MGroup {
+  v4i th[WT / 8], c[WT / 8], m[WM / 8], g[2];
+};
+
+template <int W> __device__ __forceinline__ void load16(v4i (&dst)[W / 8], const void* base, uint64_t e)
+{
+  if (W == 8) dst[0] = ld_stream((const v4i*)((const int8_t*)base + e));
+  else { dst[0] = ld_stream((const v4i*)((const int16_t*)base + e)); dst[W / 8 - 1] = ld_stream((const v4i*)((const int16_t*)base + e + 8)); }
+}
+template <int W> __device__ __forceinline__ int elem16(const v4i (&src)[W / 8], int k)        // k-th of 16 elements
+{
+  if (W == 8) return sx8(src[0][k >> 2], k & 3);
+  return sx16(src[(W / 8 - 1) * (k >> 3)][(k >> 1) & 3], k & 1);
+}
+template <int W> __device__ __forceinline__ void store16(void* base, uint64_t e, const int (&val)[16])
+{
+  if (W == 8) {
+    v4i o;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      o[w] = (int)((uint32_t)(val[4 * w] & 0xff) | ((uint32_t)(val[4 * w + 1] & 0xff) << 8) |
+                   ((uint32_t)(val[4 * w + 2] & 0xff) << 16) | ((uint32_t)val[4 * w + 3] << 24));
+    st_stream((v4i*)((int8_t*)base + e), o);
+  } else {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      v4i o;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) o[w] = (int)((uint32_t)(val[8 * q + 2 * w] & 0xffff) | ((uint32_t)val[8 * q + 2 * w + 1] << 16));
+      st_stream((v4i*)((int16_t*)base + e + 8 * q), o);
+    }
+  }
+}
+
+template <int WT, int WM, bool DECAY, bool SHR>
+__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<WT, WM>& G, const TensorDev& T, uint64_t e, MaxTrack& mt)
+{
+  int tn[16], cn[16], mn[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k)
+    update_fast_mom<DECAY, SHR>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mt);
+  store16<WT>(T.theta, e, tn);
+  store16<WT>(T.comp, e, cn);
+  store16<WM>(T.mom, e, mn);
+}
+
+template <int WT, int WM, bool DECAY, bool SHR>
+__device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
+                                              uint64_t& vm, uint64_t& wm)
+{
+  MaxTrack mt{0, 0, 0, 0};
+  constexpr int kP = (WT + WM) > 16 ? 2 : 4;              // passes in flight: bounded by registers
+  const uint32_t ngroups = cnt / kGroup;
+  uint32_t gi = lane;
+  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
+    MGroup<WT, WM> G[kP];
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps) {
+      const uint64_t e = off + (uint64_t)(gi + ps * kWave) * kGroup;
+      load16<WT>(G[ps].th, T.theta, e); load16<WT>(G[ps].c, T.comp, e); load16<WM>(G[ps].m, T.mom, e); load16<16>(G[ps].g, T.grad, e);
+    }
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps)
+      group_fast_mom<WT, WM, DECAY, SHR>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, mt);
+  }
+  for (; gi < ngroups; gi += kWave) {
+    MGroup<WT, WM> G;
+    const uint64_t e = off + (uint64_t)gi * kGroup;
+    load16<WT>(G.th, T.theta, e); load16<WT>(G.c, T.comp, e); load16<WM>(G.m, T.mom, e); load16<16>(G.g, T.grad, e);
+    group_fast_mom<WT, WM, DECAY, SHR>(p, G, T, e, mt);
+  }
+  int64_t a = mt.vmx, b = -(int64_t)mt.vmn;
+  uint64_t x = (uint64_t)(a > b ? a : b);
+  vm = x > vm ? x : vm;
+  a = mt.wmx; b = -(int64_t)mt.wmn;
+  x = (uint64_t)(a > b ? a : b);
+  wm = x > wm ? x : wm;
+  const uint32_t tail = cnt - ngroups * kGroup;
+  if (tail) tile_generic_mom(p, T, off + (uint64_t)ngroups * kGroup, tail, lane, vm, wm);
+}
+
+template <int WT, int WM>
+__device__ __forceinline__ void tile_fast_mom_dispatch(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
+                                                       uint64_t& vm, uint64_t& wm)
+{
+  const bool shr = p.k3 > 0;
+  if (p.lrwd) { if (shr) tile_fast_mom<WT, WM, true, true>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom<WT, WM, true, false>(p, T, off, cnt, lane, vm, wm); }
+  else        { if (shr) tile_fast_mom<WT, WM, false, true>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false>(p, T, off, cnt, lane, vm, wm); }
+}
+
+// ---------------------------------------------------------------- per-tensor set-up
+
+__device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int fl_in, int fl_out, int fl_m_in, int fl_m_out,
+                                          int fl_g, uint32_t lr, uint32_t mu, uint32_t wd, uint32_t& status_bits)
+{
+  p.wt = T.wt; p.wc = T.wc; p.wg = T.wg; p.wm = T.wm; p.has_comp = T.comp != nullptr;
+  p.d = p.has_comp ? T.d : 0;
+  const int delta = fl_out - fl_in, delta_m = fl_m_out - fl_m_in;
+  auto bad = [](int f) { return f < kFlMin || f > kFlMax; };
+  if (bad(fl_in) || bad(fl_out) || bad(fl_m_in) || bad(fl_m_out) || bad(fl_g) || p.d > kDMax ||
+      delta > kDeltaMax || delta < -kDeltaMax || delta_m > kDeltaMax || delta_m < -kDeltaMax) {
+    p.path = 0; status_bits |= kStatusDomain; return;
+  }
+  const int F = fl_in + p.d, G = fl_m_out + 16;
+  p.k1 = fl_m_in + 16 - G;
+  p.k2 = fl_g + 16 - G;
+  p.k3w = fl_in + 32 - G;
+  p.k3 = fl_m_out - F;
+  p.u = delta > 0 ? delta : 0;
+  p.kth = p.d + p.u - delta;
+  p.kc = p.kth - p.d;
+  p.lr = lr; p.mu = mu; p.lrwd = (int64_t)lr * (int64_t)wd;
+  p.qmax_t = (1 << (p.wt - 1)) - 1; p.qmin_t = -(1 << (p.wt - 1));
+  const int wc = p.has_comp ? p.wc : 8;
+  p.qmax_c = (1 << (wc - 1)) - 1;   p.qmin_c = -(1 << (wc - 1));
+  p.qmax_m = (1 << (p.wm - 1)) - 1; p.qmin_m = -(1 << (p.wm - 1));
+  p.path = 1;
+
+  // 32-bit path: aligned, comp present and as wide as theta, int16 grads, no grid moves, d >= 1, and
+  // every intermediate provably below 2^31 in magnitude.
+  if (!p.has_comp || !T.vec_mom || p.wt != p.wc || p.wg != 16 || delta != 0 || delta_m != 0 || p.d < 1) return;
+  if (p.k2 < 1 || (p.k2 < 9 && ((int64_t)lr << 15) >= (1ll << (22 + p.k2)))) return;      // fp32 FMA rounding exact, |t2| < 2^22
+  if (p.lrwd && (p.k3w < 1 || p.k3w > 60)) return;
+  if (p.k3 > 30 || p.k3 < -24) return;
+  int64_t wb = (int64_t)mu << (p.wm - 1);                                                 // |mu * m|
+  wb += p.k2 < 40 ? (((int64_t)lr << 15) >> p.k2) + 1 : 0;                                // |t2|
+  if (p.lrwd) wb += ((p.lrwd << (p.wt - 1)) >> p.k3w) + 1;                                // |t3|
+  if (wb + 0x8000 >= (1ll << 31)) return;
+  int64_t sb = p.k3 > 0 ? ((1ll << (p.wm - 1)) >> p.k3) + 1 : (1ll << (p.wm - 1 - p.k3));  // |s|
+  int64_t vb = (1ll << (p.wt - 1 + p.d)) + (1ll << (p.wc - 1)) + sb + (1ll << (p.d - 1));
+  if (vb >= (1ll << 31)) return;
+  p.path = 2;
+  p.mu_i = (int)mu;
+  const int k2 = p.k2 > 40 ? 40 : p.k2;
+  p.magic_fi = ((127 + 23 + k2) << 23) | 0x400000;
+  p.magic_f  = __int_as_float(p.magic_fi);
+  p.nlr_f    = -(float)lr;
+  const int k3w = p.k3w;
+  const long long md = ((long long)(1023 + 52 + (p.lrwd ? k3w : 1)) << 52) | (1ll << 51);
+  p.magic_d   = __longlong_as_double(md);
+  p.magic_dlo = (int)(md & 0xffffffffll);
+  p.nlrwd_d   = -(double)p.lrwd;
+  p.half_m1   = (1 << (p.d - 1)) - 1;
+  p.s_half_m1 = p.k3 > 0 ? (1 << (p.k3 - 1)) - 1 : 0;
+  p.s_shl     = p.k3 > 0 ? 0 : -p.k3;
+}
+
+// ---------------------------------------------------------------- the kernel
+
+__global__ void __launch_bounds__(kBlock)
+momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
+                     const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out,
+                     const int32_t* __restrict__ fl_m_in, const int32_t* __restrict__ fl_m_out, const int32_t* __restrict__ fl_g,
+                     uint32_t lr, uint32_t mu, uint32_t wd, uint64_t* vmax, uint64_t* mmax, uint32_t* status)
+{
+  __shared__ int      s_tensor[kWavesPerBlock];
+  __shared__ uint64_t s_max[kWavesPerBlock];
+
+  const int lane   = threadIdx.x & (kWave - 1);
+  const int wave   = wave_uniform(threadIdx.x >> 6);
+  const uint32_t w0 = blockIdx.x * kWavesPerBlock + wave;
+  const uint32_t nw = gridDim.x * kWavesPerBlock;
+
+  int cur = -1;
+  uint64_t vm = 0, wm = 0;
+  uint32_t status_bits = 0;
+  MomParams p; p.path = 0;
+  TensorDev T;
+
+  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
+    int t; uint32_t cnt; uint64_t off;
+    read_tile(tiles, ti, t, cnt, off);
+    if (t != cur) {
+      if (cur >= 0) {
+        if (vmax) flush_wave(vmax, cur, vm, lane);
+        if (mmax) flush_wave(mmax, cur, wm, lane);
+      }
+      vm = wm = 0;
+      cur = t;
+      T = tensors[t];
+      setup_mom(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_g[t], lr, mu, wd, status_bits);
+    }
+    if (p.path == 2) {
+      if (p.wt == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom_dispatch<8, 16>(p, T, off, cnt, lane, vm, wm); }
+      else           { if (p.wm == 8) tile_fast_mom_dispatch<16, 8>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom_dispatch<16, 16>(p, T, off, cnt, lane, vm, wm); }
+    } else if (p.path == 1) {
+      tile_generic_mom(p, T, off, cnt, lane, vm, wm);
+    }
+  }
+
+  if (status && status_bits && lane == 0) atomicOr(status, status_bits);
+  if (vmax) flush_block(vmax, cur, vm, lane, wave, s_tensor, s_max);
+  if (mmax) flush_block(mmax, cur, wm, lane, wave, s_tensor, s_max);
+}
+
+__global__ void __launch_bounds__(kBlock) fill2_u64_kernel(uint64_t* a, uint64_t* b, uint32_t n)
+{
+  uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) { if (a) a[i] = 0; if (b) b[i] = 0; }
+}
+
+hipError_t launch_momentum_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
+                                const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
+                                const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
+                                uint64_t* vmax, uint64_t* mmax, uint32_t* status, hipStream_t stream)
+{
+  if (vmax || mmax)
+    hipLaunchKernelGGL(fill2_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, mmax, n_tensors);
+  if (n_tiles)
+    hipLaunchKernelGGL(momentum_step_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                       fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr, mu, wd, vmax, mmax, status);
+  return hipGetLastError();
+}
+
+}  // namespace lpk

@@ -95,14 +95,14 @@ __device__ __forceinline__ int clamp_fl(int fl) { return fl > kFlMax ? kFlMax : 
 // W - 2 - e (M lands in [2^(W-2), 2^(W-1))); it is one too fine exactly when M * 2^fl reaches
 // 2^(W-1) - 1/2, i.e. when the 24-bit significand m satisfies m >= 2^24 - 2^(24-W).
 __global__ void __launch_bounds__(kBlock)
-fraclen_from_f32max_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tensors, int use_theta_width,
+fraclen_from_f32max_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tensors, int sel,
                            uint32_t* scratch, const int32_t* __restrict__ fl_default, int32_t* fl_out, uint32_t* status)
 {
   uint32_t t = blockIdx.x * kBlock + threadIdx.x;
   if (t >= n_tensors) return;
   const uint32_t b = scratch[t];
   scratch[t] = 0;                                   // re-arm for the next call
-  const int W = use_theta_width ? tensors[t].wt : tensors[t].wg;
+  const int W = sel == 1 ? tensors[t].wt : tensors[t].wg;
   int fl;
   if (b >= 0x7f800000u) { fl = kFlMin; if (status) atomicOr(status, kStatusNonFinite); }
   else if (b == 0)      { fl = fl_default[t]; }
@@ -121,14 +121,15 @@ fraclen_from_f32max_kernel(const TensorDev* __restrict__ tensors, uint32_t n_ten
 
 // One thread per tensor: vmax (an integer on grid F = fl_theta_in + d) -> fraclen, clamped to default +- 15.
 __global__ void __launch_bounds__(kBlock)
-fraclen_from_vmax_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tensors, int use_theta_width,
+fraclen_from_vmax_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tensors, int sel,
                          const uint64_t* __restrict__ vmax, const int32_t* __restrict__ fl_theta_in,
                          const int32_t* __restrict__ fl_default, int32_t* fl_out, uint32_t* status)
 {
   uint32_t t = blockIdx.x * kBlock + threadIdx.x;
   if (t >= n_tensors) return;
-  const int W = use_theta_width ? tensors[t].wt : tensors[t].wg;
-  const int d = tensors[t].comp ? tensors[t].d : 0;
+  // sel: 0 gradient width, 1 theta width (vmax on grid fl + d), 2 velocity width (mmax on grid fl + 16)
+  const int W = sel == 1 ? tensors[t].wt : (sel == 2 ? tensors[t].wm : tensors[t].wg);
+  const int d = sel == 2 ? 16 : (tensors[t].comp ? tensors[t].d : 0);
   const int F = fl_theta_in[t] + d;
   const int cur = fl_default[t];
   if (F < kFlMin || F > kFlMax + kDMax || cur < kFlMin || cur > kFlMax) {
@@ -151,22 +152,22 @@ fraclen_from_vmax_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tenso
 }
 
 hipError_t launch_select_f32(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                             int use_theta_width, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
+                             int sel, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
                              uint32_t* status, hipStream_t stream)
 {
   if (n_tiles)
     hipLaunchKernelGGL(maxabs_f32_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles, scratch);
   hipLaunchKernelGGL(fraclen_from_f32max_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream,
-                     tensors, n_tensors, use_theta_width, scratch, fl_default, fl_out, status);
+                     tensors, n_tensors, sel, scratch, fl_default, fl_out, status);
   return hipGetLastError();
 }
 
-hipError_t launch_select_vmax(const TensorDev* tensors, uint32_t n_tensors, int use_theta_width, const uint64_t* vmax,
+hipError_t launch_select_vmax(const TensorDev* tensors, uint32_t n_tensors, int sel, const uint64_t* vmax,
                               const int32_t* fl_theta_in, const int32_t* fl_default, int32_t* fl_out, uint32_t* status,
                               hipStream_t stream)
 {
   hipLaunchKernelGGL(fraclen_from_vmax_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream,
-                     tensors, n_tensors, use_theta_width, vmax, fl_theta_in, fl_default, fl_out, status);
+                     tensors, n_tensors, sel, vmax, fl_theta_in, fl_default, fl_out, status);
   return hipGetLastError();
 }
 

@@ -1,0 +1,107 @@
+// Pieces shared by the update kernels (plain lazy update, momentum): exact 64-bit rounding helpers,
+// element and vector accesses, byte/halfword unpacking, the per-tensor vmax flush.
+#pragma once
+#include "lpk_device.hpp"
+
+namespace lpk {
+
+__device__ __forceinline__ int64_t rne_shr64(int64_t x, int k)      // RNE(x / 2^k), 0 <= k <= 62
+{
+  if (k == 0) return x;
+  int64_t  q    = x >> k;
+  uint64_t rem  = (uint64_t)x & ((1ull << k) - 1ull);
+  uint64_t half = 1ull << (k - 1);
+  return q + (int64_t)((rem > half) | ((rem == half) & (uint64_t)(q & 1)));
+}
+
+__device__ __forceinline__ int64_t rescale_cap64(int64_t x, int k)   // |x| < 2^48; clamp(RNE(x * 2^-k), +-2^40)
+{
+  const int64_t cap = 1ll << 40;
+  if (x == 0) return 0;
+  if (k > 0) {
+    if (k >= 50) return 0;
+    int64_t q = rne_shr64(x, k);
+    return q > cap ? cap : (q < -cap ? -cap : q);
+  }
+  int sh = -k;
+  if (sh >= 41) return x > 0 ? cap : -cap;
+  int64_t lim = cap >> sh;
+  if (x > lim) return cap;
+  if (x < -lim) return -cap;
+  return x * (1ll << sh);
+}
+
+// RNE(x * 2^-k) without a cap, for |x| < 2^32 and -15 <= k <= 62.
+__device__ __forceinline__ int64_t rescale64(int64_t x, int k)
+{
+  return k > 0 ? rne_shr64(x, k) : x * (1ll << (-k));
+}
+
+__device__ __forceinline__ int load_elem(const void* p, uint64_t i, int bits)
+{
+  return bits == 8 ? (int)((const int8_t*)p)[i] : (int)((const int16_t*)p)[i];
+}
+__device__ __forceinline__ void store_elem(void* p, uint64_t i, int bits, int v)
+{
+  if (bits == 8) ((int8_t*)p)[i] = (int8_t)v; else ((int16_t*)p)[i] = (int16_t)v;
+}
+
+// Streaming accesses: global address space (global_load/global_store, not flat), non-temporal.
+template <typename V> __device__ __forceinline__ V ld_stream(const V* p)
+{
+#if LPK_NT_LOAD
+  return __builtin_nontemporal_load((const LPK_GLOBAL V*)p);
+#else
+  return *(const LPK_GLOBAL V*)p;
+#endif
+}
+template <typename V> __device__ __forceinline__ void st_stream(V* p, V v)
+{
+#if LPK_NT_STORE
+  __builtin_nontemporal_store(v, (LPK_GLOBAL V*)p);
+#else
+  *(LPK_GLOBAL V*)p = v;
+#endif
+}
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int sx8(int w, int b)  { return (int)(int8_t)(w >> (8 * b)); }
+__device__ __forceinline__ int sx16(int w, int h) { return (int)(int16_t)(w >> (16 * h)); }
+
+__device__ __forceinline__ void flush_wave(uint64_t* vmax, int tensor, uint64_t lane_max, int lane)
+{
+  uint64_t m = wave_max_u64(lane_max);
+  if (lane == 0 && m) atomicMax((unsigned long long*)&vmax[tensor], (unsigned long long)m);
+}
+
+// Decode one tile-table entry into wave-uniform scalars.
+__device__ __forceinline__ void read_tile(const Tile* __restrict__ tiles, uint32_t ti, int& tensor, uint32_t& cnt, uint64_t& off)
+{
+  const Tile tl = tiles[ti];
+  tensor = wave_uniform((int)tl.tensor);
+  cnt = (uint32_t)wave_uniform((int)tl.count);
+  off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
+}
+
+// Block-level end of a persistent kernel: combine the four waves' (tensor, max) pairs in LDS, one atomic per tensor.
+__device__ __forceinline__ void flush_block(uint64_t* vmax, int cur, uint64_t lane_max, int lane, int wave,
+                                            int* s_tensor, uint64_t* s_max)
+{
+  uint64_t m = wave_max_u64(lane_max);
+  if (lane == 0) { s_tensor[wave] = cur; s_max[wave] = m; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int a = 0; a < kWavesPerBlock; ++a) {
+      int ta = s_tensor[a];
+      if (ta < 0) continue;
+      uint64_t ma = s_max[a];
+      for (int b = a + 1; b < kWavesPerBlock; ++b)
+        if (s_tensor[b] == ta) { ma = s_max[b] > ma ? s_max[b] : ma; s_tensor[b] = -1; }
+      if (ma) atomicMax((unsigned long long*)&vmax[ta], (unsigned long long)ma);
+    }
+  }
+  __syncthreads();
+}
+
+}  // namespace lpk

@@ -27,9 +27,10 @@ def _offsets(sizes, elem_bytes):
 
 
 class DeviceState:
-    def __init__(self, cfg, device="cuda:0", kahan=True, n_src=1, comp_bits=None):
+    def __init__(self, cfg, device="cuda:0", kahan=True, n_src=1, comp_bits=None, mom_bits=None, fl_mom0=16):
         """cfg: workloads.Config.  n_src: how many fp32 source arenas stay resident (gradient cycle).
-        comp_bits: per-tensor width of comp when it differs from theta's."""
+        comp_bits: per-tensor width of comp when it differs from theta's.  mom_bits: per-tensor width of a
+        velocity tensor (momentum update); its fraclen starts at fl_mom0 and is re-selected every step."""
         self.cfg, self.device, self.kahan = cfg, torch.device(device), kahan
         nt = cfg.n_tensors
         tb = [b // 8 for b in cfg.bits]
@@ -48,6 +49,11 @@ class DeviceState:
         self.arena_grad = torch.zeros(tot_g, dtype=torch.uint8, device=dev)
         self.arena_src = [torch.zeros(tot_s, dtype=torch.uint8, device=dev) for _ in range(n_src)]
         self.src_bytes = tot_s
+        self.mom_bits = list(mom_bits) if mom_bits is not None else None
+        if self.mom_bits:
+            mb = [b // 8 for b in self.mom_bits]
+            self.off_mom, tot_m = _offsets(cfg.sizes, mb)
+            self.arena_mom = torch.zeros(tot_m, dtype=torch.uint8, device=dev)
 
         def view(arena, off, n, eb, dtype):
             return arena[off:off + n * eb].view(dtype)
@@ -58,9 +64,12 @@ class DeviceState:
         self.grad = [view(self.arena_grad, o, n, 2, torch.int16) for o, n in zip(self.off_grad, cfg.sizes)]
         self.src = [[view(a, o, n, 4, torch.float32) for o, n in zip(self.off_src, cfg.sizes)] for a in self.arena_src]
 
+        self.mom = ([view(self.arena_mom, o, n, e, dt[e]) for o, n, e in zip(self.off_mom, cfg.sizes, mb)]
+                    if self.mom_bits else [None] * nt)
         self.lists = []
         for k in range(n_src):
-            descs = [lpk.make_desc(self.theta[t], self.comp[t], self.grad[t], self.src[k][t]) for t in range(nt)]
+            descs = [lpk.make_desc(self.theta[t], self.comp[t], self.grad[t], self.src[k][t], momentum=self.mom[t])
+                     for t in range(nt)]
             self.lists.append(lpk.TensorList(descs))
 
         i32 = dict(dtype=torch.int32, device=dev)
@@ -68,6 +77,10 @@ class DeviceState:
         self.fl_next = self.fl_theta.clone()                               # grid the next step moves it to
         self.fl_spare = self.fl_theta.clone()
         self.fl_grad = torch.full((nt,), 15, **i32)
+        self.fl_mom = torch.full((nt,), fl_mom0, **i32)                    # grid the velocity is on now
+        self.fl_mom_next = self.fl_mom.clone()
+        self.fl_mom_spare = self.fl_mom.clone()
+        self.mmax = torch.zeros(nt, dtype=torch.int64, device=dev)         # uint64 payload
         self.vmax = torch.zeros(nt, dtype=torch.int64, device=dev)         # uint64 payload
         self.status = torch.zeros(1, dtype=torch.int32, device=dev)        # uint32 payload
         self._host_src = None
@@ -120,10 +133,27 @@ class DeviceState:
                                    self.fl_next, self.fl_spare, self.status)
             self.fl_theta, self.fl_next, self.fl_spare = self.fl_next, self.fl_spare, self.fl_theta
 
-    def step(self, step_idx, k=0):
+    def update_momentum(self, lr_q16, mu_q16, wd_q16=0, k=0):
+        """Momentum update with the lazy update inside; the velocity moves from grid fl_mom to fl_mom_next, and
+        the grid after that is re-selected from this step's mmax (one-step lag), like theta's in `update`."""
+        L = self.lists[k]
+        lpk.lpk_momentum_sgd_step(L, self.fl_theta, self.fl_next, self.fl_mom, self.fl_mom_next, self.fl_grad,
+                                  lr_q16, mu_q16, wd_q16, self.vmax, self.mmax, self.status)
+        if self.cfg.reselect:
+            lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_THETA, self.vmax, self.fl_theta,
+                                   self.fl_next, self.fl_spare, self.status)
+            self.fl_theta, self.fl_next, self.fl_spare = self.fl_next, self.fl_spare, self.fl_theta
+        lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_MOMENTUM, self.mmax, self.fl_mom_next,
+                               self.fl_mom_next, self.fl_mom_spare, self.status)
+        self.fl_mom, self.fl_mom_next, self.fl_mom_spare = self.fl_mom_next, self.fl_mom_spare, self.fl_mom
+
+    def step(self, step_idx, k=0, mu_q16=None):
         """One pass of the whole hot path over gradients already resident in source arena k."""
         self.quantize_grads(k)
-        self.update(self.cfg.lr_q16(step_idx), self.cfg.wd_q16, k)
+        if mu_q16 is None:
+            self.update(self.cfg.lr_q16(step_idx), self.cfg.wd_q16, k)
+        else:
+            self.update_momentum(self.cfg.lr_q16(step_idx), mu_q16, self.cfg.wd_q16, k)
 
     def close(self):
         for L in self.lists:

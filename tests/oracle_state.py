@@ -15,7 +15,7 @@ THREADS = max(1, min(16, len(os.sched_getaffinity(0))))
 
 
 class OracleState:
-    def __init__(self, cfg, kahan=True, comp_bits=None):
+    def __init__(self, cfg, kahan=True, comp_bits=None, mom_bits=None, fl_mom0=16):
         self.cfg, self.kahan = cfg, kahan
         nt = cfg.n_tensors
         self.comp_bits = list(comp_bits) if comp_bits is not None else list(cfg.bits)
@@ -28,6 +28,12 @@ class OracleState:
         self.fl_grad = [15] * nt
         self.vmax = [0] * nt
         self.status = ref.new_status()
+        self.mom_bits = list(mom_bits) if mom_bits is not None else None
+        if self.mom_bits:
+            self.mom = [np.zeros(n, dtype=DT[b]) for n, b in zip(cfg.sizes, self.mom_bits)]
+        self.fl_mom = [fl_mom0] * nt
+        self.fl_mom_next = [fl_mom0] * nt
+        self.mmax = [0] * nt
 
     def init_theta(self, theta0):
         for t, x in enumerate(theta0):
@@ -51,6 +57,23 @@ class OracleState:
                                                       self.fl_next[t], self.status)
         self.fl_theta, self.fl_next = self.fl_next, new_next
 
-    def step(self, step_idx, grads):
+    def update_momentum(self, lr_q16, mu_q16, wd_q16=0):
+        new_next, new_mnext = list(self.fl_next), list(self.fl_mom_next)
+        for t in range(self.cfg.n_tensors):
+            self.vmax[t], self.mmax[t] = ref.momentum_sgd_step_mt(
+                self.theta[t], self.comp[t], self.mom[t], self.grad[t], self.d[t], self.fl_theta[t], self.fl_next[t],
+                self.fl_mom[t], self.fl_mom_next[t], self.fl_grad[t], lr_q16, mu_q16, wd_q16, self.status, threads=THREADS)
+            if self.cfg.reselect:
+                new_next[t] = ref.select_fraclen_vmax(self.vmax[t], self.fl_theta[t] + self.d[t], self.cfg.bits[t],
+                                                      self.fl_next[t], self.status)
+            new_mnext[t] = ref.select_fraclen_vmax(self.mmax[t], self.fl_mom_next[t] + 16, self.mom_bits[t],
+                                                   self.fl_mom_next[t], self.status)
+        self.fl_theta, self.fl_next = self.fl_next, new_next
+        self.fl_mom, self.fl_mom_next = self.fl_mom_next, new_mnext
+
+    def step(self, step_idx, grads, mu_q16=None):
         self.quantize_grads(grads)
-        self.update(self.cfg.lr_q16(step_idx), self.cfg.wd_q16)
+        if mu_q16 is None:
+            self.update(self.cfg.lr_q16(step_idx), self.cfg.wd_q16)
+        else:
+            self.update_momentum(self.cfg.lr_q16(step_idx), mu_q16, self.cfg.wd_q16)

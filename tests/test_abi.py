@@ -34,7 +34,7 @@ def test_binding_has_the_same_names():
 
 
 def test_descriptor_layout_matches_header():
-    assert ctypes.sizeof(lpk.lpk_tensor_desc) == 48
+    assert ctypes.sizeof(lpk.lpk_tensor_desc) == 56 and lpk.lpk_tensor_desc.momentum.offset == 48
     assert lpk.lpk_tensor_desc.n.offset == 32 and lpk.lpk_tensor_desc.comp_shift.offset == 43
 
 

@@ -1,0 +1,157 @@
+"""Momentum SGD with the lazy update inside: GPU library vs CPU oracle, bit for bit (needs an MI355X)."""
+import random
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+from oracle import ref
+from paper_1810_05486_amd import binding as lpk
+from paper_1810_05486_amd import workloads
+from oracle_state import OracleState
+
+MU_Q16 = 58982        # RNE(0.9 * 2^16)
+NP = {8: np.int8, 16: np.int16}
+TT = {8: torch.int8, 16: torch.int16}
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def compare(dev, host, what):
+    th, co, fl_t, fl_g, vm, status = dev.download()
+    assert status == int(host.status[0]), (what, "status")
+    assert fl_t.tolist() == list(host.fl_theta) and fl_g.tolist() == list(host.fl_grad), (what, "fraclens")
+    assert dev.fl_mom.cpu().tolist() == list(host.fl_mom), (what, "fl_mom", dev.fl_mom.cpu().tolist()[:8], host.fl_mom[:8])
+    assert vm.tolist() == list(host.vmax), (what, "vmax")
+    assert dev.mmax.cpu().numpy().view(np.uint64).tolist() == list(host.mmax), (what, "mmax")
+    for t in range(host.cfg.n_tensors):
+        assert np.array_equal(th[t], host.theta[t]), (what, "theta", t)
+        assert np.array_equal(co[t], host.comp[t]), (what, "comp", t)
+        assert np.array_equal(dev.mom[t].cpu().numpy(), host.mom[t]), (what, "mom", t)
+
+
+def run_config(cfg, mom_bits, steps, fl_mom0=16):
+    from paper_1810_05486_amd.device_state import DeviceState
+    dev = DeviceState(cfg, mom_bits=mom_bits, fl_mom0=fl_mom0)
+    host = OracleState(cfg, mom_bits=mom_bits, fl_mom0=fl_mom0)
+    views = dev.host_src_views()
+    theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
+    dev.upload_src()
+    dev.init_theta()
+    host.init_theta(theta0)
+    for s in steps:
+        grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
+        dev.upload_src()
+        dev.step(s, mu_q16=MU_Q16)
+        host.step(s, grads, mu_q16=MU_Q16)
+        compare(dev, host, "config %d step %d" % (cfg.id, s))
+    dev.close()
+    return host
+
+
+def test_momentum_config1_int8_velocity():
+    say("momentum: config 1, int8 velocity, 60 steps")
+    host = run_config(workloads.config(1), [8], range(60))
+    assert np.abs(host.mom[0].astype(int)).max() > 20          # the velocity grid settled and is being used
+
+
+def test_momentum_lenet_int16_everything_reselect():
+    say("momentum: LeNet shapes int16, int16 velocity, theta and velocity grids re-selected")
+    cfg = workloads.config(2)
+    run_config(cfg, [16] * cfg.n_tensors, range(40))
+
+
+def test_momentum_resnet50_mixed_widths_decay():
+    say("momentum: ResNet-50 shapes, int8 theta / int16 velocity (int16 classifier), weight decay")
+    cfg = workloads.config(4)
+    run_config(cfg, [16] * cfg.n_tensors, range(5))
+
+
+def test_momentum_resnet18_int8_velocity():
+    say("momentum: ResNet-18 shapes, all int8")
+    cfg = workloads.config(3)
+    run_config(cfg, [8] * cfg.n_tensors, [0, 1, 2, 3, 300, 600])
+
+
+def test_momentum_config5_reduced():
+    say("momentum: config 5 shape at reduced size")
+    cfg = workloads.config(5, big_elems=(1 << 22) + 21, n_tiny=200)
+    run_config(cfg, [8] * cfg.n_tensors, range(5))
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_momentum_random_lists(seed):
+    """Random widths, shifts, grid moves, alignments and sizes straight through the C ABI."""
+    say("momentum: random lists, seed %d" % seed)
+    rng = np.random.default_rng(500 + seed)
+    pr = random.Random(600 + seed)
+    sizes = [0, 1, 15, 16, 17, 255, 1024, 4095, 4096, 4097, 9001, 33000]
+    for rep in range(8):
+        cases = []
+        for _ in range(pr.randint(1, 10)):
+            tb, mb = pr.choice([8, 16]), pr.choice([8, 16])
+            cb = pr.choice([tb, tb, tb, 8, 16, 0])
+            gb = pr.choice([16, 16, 16, 8])
+            d = pr.choice([None, None, pr.randint(0, 24)]) if cb else None
+            dd = d if d is not None else (cb - 1 if cb else 0)
+            fl_in = pr.randint(-10, 20)
+            delta = pr.choice([0, 0, 0, 0, 1, -1, pr.randint(-15, 15)])
+            fl_m_in = fl_in + dd + pr.randint(-8, 12)
+            delta_m = pr.choice([0, 0, 0, 0, 1, -1, pr.randint(-15, 15)])
+            fl_m_out = fl_m_in + delta_m
+            fl_g = fl_m_out + pr.choice([pr.randint(1, 14), pr.randint(1, 14), pr.randint(-20, 0), pr.randint(15, 50)])
+            fls = [max(-64, min(64, f)) for f in (fl_in, fl_in + delta, fl_m_in, fl_m_out, fl_g)]
+            n = pr.choice(sizes)
+            mis = pr.choice([0, 0, 0, 1, 8, 16])
+            c = dict(n=n, tb=tb, cb=cb, mb=mb, gb=gb, d=d, fls=fls)
+            c["theta"] = rng.integers(-(2 ** (tb - 1)), 2 ** (tb - 1), size=n).astype(NP[tb])
+            c["comp"] = rng.integers(-(2 ** (cb - 1)), 2 ** (cb - 1), size=n).astype(NP[cb]) if cb else None
+            c["mom"] = rng.integers(-(2 ** (mb - 1)), 2 ** (mb - 1), size=n).astype(NP[mb])
+            c["grad"] = rng.integers(-(2 ** (gb - 1)), 2 ** (gb - 1), size=n).astype(NP[gb])
+
+            def dev(a, bits):
+                buf = torch.zeros(n + 64, dtype=TT[bits], device=DEV)
+                v = buf[mis:mis + n]
+                v.copy_(torch.from_numpy(a))
+                return buf, v
+            c["bufs"] = []
+            for key, bits in (("theta", tb), ("comp", cb), ("mom", mb), ("grad", gb)):
+                if c[key] is None:
+                    c["d_" + key] = None
+                    continue
+                b, v = dev(c[key], bits)
+                c["bufs"].append(b); c["d_" + key] = v
+            cases.append(c)
+        lr_q, mu_q, wd_q = pr.choice([1, 655, 6554, 65535]), pr.choice([0, 58982, 65535, 32768]), pr.choice([0, 0, 7, 65535])
+        tl = lpk.TensorList([lpk.make_desc(c["d_theta"], c["d_comp"], c["d_grad"], None,
+                                           c["d"] if c["cb"] and c["d"] is not None else lpk.LPK_COMP_SHIFT_DEFAULT,
+                                           momentum=c["d_mom"]) for c in cases])
+        i32 = dict(dtype=torch.int32, device=DEV)
+        arr = [torch.tensor([c["fls"][j] for c in cases], **i32) for j in range(5)]
+        vmax = torch.full((len(cases),), 5, dtype=torch.int64, device=DEV)
+        mmax = torch.full((len(cases),), 6, dtype=torch.int64, device=DEV)
+        status = torch.zeros(1, dtype=torch.int32, device=DEV)
+        lpk.lpk_momentum_sgd_step(tl, arr[0], arr[1], arr[2], arr[3], arr[4], lr_q, mu_q, wd_q, vmax, mmax, status)
+        torch.cuda.synchronize()
+        st = ref.new_status()
+        for i, c in enumerate(cases):
+            dd = c["d"] if c["d"] is not None else (c["cb"] - 1 if c["cb"] else 0)
+            f = c["fls"]
+            wv, wm = ref.momentum_sgd_step(c["theta"], c["comp"], c["mom"], c["grad"], dd, f[0], f[1], f[2], f[3], f[4],
+                                           lr_q, mu_q, wd_q, st)
+            ctx = {k: c[k] for k in ("n", "tb", "cb", "mb", "gb", "d", "fls")}
+            ctx.update(lr=lr_q, mu=mu_q, wd=wd_q, i=i)
+            assert np.array_equal(c["d_theta"].cpu().numpy(), c["theta"]), ("theta", ctx)
+            if c["cb"]:
+                assert np.array_equal(c["d_comp"].cpu().numpy(), c["comp"]), ("comp", ctx)
+            assert np.array_equal(c["d_mom"].cpu().numpy(), c["mom"]), ("mom", ctx)
+            assert int(vmax[i].item()) == wv and int(mmax[i].item()) == wm, ("max", ctx)
+        assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
+        tl.destroy()
