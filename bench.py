@@ -61,6 +61,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (5 = the 1 Gi-parameter headline)")
     ap.add_argument("--big-elems", type=int, default=1 << 30, help="size of config 5's large tensor")
+    ap.add_argument("--momentum-bits", type=int, default=0, choices=[0, 8, 16],
+                    help="time the momentum variant of the update (velocity of this width, mu = 0.9) instead of plain SGD")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-gib", type=float, default=2.0,
                     help="size of the plain-copy yardstick (lpk_stream_copy), 0 = skip")
@@ -83,7 +85,9 @@ def main():
     if not cfg.grad_cycle:
         n_src = 3                                   # timing only: cycle three resident gradient draws
     log("workload %d: %s; %d tensors, %d parameters" % (cfg.id, cfg.name, cfg.n_tensors, cfg.n_params))
-    dev = DeviceState(cfg, n_src=n_src)
+    mom_bits = [args.momentum_bits] * cfg.n_tensors if args.momentum_bits else None
+    mu_q16 = 58982 if args.momentum_bits else None
+    dev = DeviceState(cfg, n_src=n_src, mom_bits=mom_bits)
     views = dev.host_src_views()
 
     t0 = time.perf_counter()
@@ -101,7 +105,7 @@ def main():
     log("inputs drawn and uploaded in %.1f s" % (time.perf_counter() - t0))
 
     for s in range(args.warmup):
-        dev.step(s, k=s % n_src)
+        dev.step(s, k=s % n_src, mu_q16=mu_q16)
     torch.cuda.synchronize()
 
     K = args.steps
@@ -118,7 +122,10 @@ def main():
         ev[i][1].record()
         lpk.lpk_quantize_tensor(L, lpk.LPK_SEL_GRAD, dev.fl_grad, dev.status)
         ev[i][2].record()
-        dev.update(cfg.lr_q16(s), cfg.wd_q16, k)
+        if mu_q16 is None:
+            dev.update(cfg.lr_q16(s), cfg.wd_q16, k)
+        else:
+            dev.update_momentum(cfg.lr_q16(s), mu_q16, cfg.wd_q16, k)
         ev[i][3].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -147,13 +154,14 @@ def main():
         copy = {"bytes_read": nb, "bytes_written": nb, "ms": cms, "GB/s": 2 * nb / (cms * 1e-3) / 1e9}
         del a, b
 
-    upd_bytes = cfg.bytes_per_step()
+    upd_bytes = cfg.bytes_per_step() + (2 * (args.momentum_bits // 8) * cfg.n_params if args.momentum_bits else 0)
+    upd_kernel = "momentum_step_kernel" if args.momentum_bits else "kahan_step_kernel"
     achieved = upd_bytes / (upd_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_config%d.json" % cfg.id)
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("kahan_step_kernel_bytes_per_launch")
+            traffic = json.load(open(tpath)).get(upd_kernel + "_bytes_per_launch")
         except Exception:
             traffic = None
 
@@ -164,12 +172,13 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8/int16 fixed point (int32/int64 accumulate)", "data": "synthetic",
-        "config": {"workload": "config %d: %s" % (cfg.id, cfg.name), "n_tensors": cfg.n_tensors,
+        "config": {"workload": "config %d: %s%s" % (cfg.id, cfg.name, ", momentum 0.9 with int%d velocity" % args.momentum_bits
+                                                    if args.momentum_bits else ""), "n_tensors": cfg.n_tensors,
                    "n_params": cfg.n_params, "lr_q16": cfg.lr_q16(0), "wd_q16": cfg.wd_q16,
                    "grad_draws_cycled": n_src},
         "update_only": {"value": cfg.n_params / (upd_ms * 1e-3) / 1e9, "unit": "Gparam/s", "ms": upd_ms},
         "stage_ms": {"select_fraclen": sel_ms, "quantize": qnt_ms, "kahan_sgd_step": upd_ms},
-        "roofline": {"bound": "hbm", "kernel": "kahan_step_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": upd_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": upd_bytes},
         "other_kernels": {

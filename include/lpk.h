@@ -128,7 +128,7 @@ uint64_t lpk_tensor_list_tiles(const lpk_tensor_list* list);
  *   fl_theta_out when fl_default is that step's fl_theta_in.
  *   With dst_sel == LPK_SEL_MOMENTUM the maximum is the mmax of
  *   lpk_momentum_sgd_step and `fl_theta_in` is the fl_mom_out array that step
- *   was called with: M = vmax[t] * 2^-(fl_theta_in[t] + 16).
+ *   was called with: M = vmax[t] * 2^-fl_theta_in[t].
  *
  * vmax (uint64), fl_theta_in, fl_default, fl_out (int32): device arrays of
  * n_tensors entries.  fl_out is written for every tensor.
@@ -183,9 +183,9 @@ int lpk_kahan_sgd_step(lpk_tensor_list* list,
  *   w  = RNE(mu_q16 * m * 2^-(fl_mom_in[t] - fl_mom_out[t]))                 (exact unless the grid coarsens)
  *      + cap(RNE(-lr_q16 * g * 2^-(fl_grad[t] - fl_mom_out[t])))
  *      + cap(RNE(-lr_q16 * wd_q16 * theta * 2^-(fl_theta_in[t] + 16 - fl_mom_out[t])))     if wd_q16 != 0
- *   m' = sat(RNE(w * 2^-16))                                                  stored on grid fl_mom_out[t]
+ *   mq = RNE(w * 2^-16);  m' = sat(mq)                                        stored on grid fl_mom_out[t]
  *   s  = cap(RNE(m' * 2^-(fl_mom_out[t] - F)))
- *   v, theta', c', vmax_out exactly as in lpk_kahan_sgd_step with this s;  mmax_out[t] = max_i |w_i| (grid G)
+ *   v, theta', c', vmax_out exactly as in lpk_kahan_sgd_step with this s;  mmax_out[t] = max_i |mq_i|
  *
  * fl_mom_in / fl_mom_out: device int32[n_tensors], in [-64, 64], |difference| <= 15.  mu_q16 <= 65535.
  * mmax_out: device uint64[n_tensors] or NULL, cleared and rewritten by the call; feed it to

@@ -284,7 +284,7 @@ int lpk_ref_kahan_sgd_step(void *theta, void *comp, const void *grad, uint64_t n
  *        + cap(RNE(-lr_q * g on grid G)) + cap(RNE(-lr_q * wd_q * theta on grid G))
  *     m' = sat(RNE(w / 2^16))                                 stored on grid fl_m_out
  *     s  = cap(RNE(m' on grid F))                             F = fl_in + d, then exactly the lazy update with this s
- *     mmax = max |w|  (on grid G), vmax = max |v| (on grid F)
+ *     mmax = max |RNE(w / 2^16)|  (the velocity before saturation, on grid fl_m_out), vmax = max |v| (on grid F)
  */
 int lpk_ref_momentum_sgd_step(void *theta, void *comp, void *mom, const void *grad, uint64_t n,
                               int theta_bits, int comp_bits, int mom_bits, int grad_bits, int d,
@@ -319,9 +319,10 @@ int lpk_ref_momentum_sgd_step(void *theta, void *comp, void *mom, const void *gr
         wide w = rescale((wide)mu_q * m, (fl_m_in + 16) - G);
         w += rescale_cap(-(wide)lr_q * g, (fl_g + 16) - G);
         if (wd_q) w += rescale_cap(-(wide)lr_q * (wide)wd_q * th, (fl_in + 32) - G);
-        wide aw = w < 0 ? -w : w;
+        wide mq = rescale(w, 16);                 /* the new velocity before saturation */
+        wide aw = mq < 0 ? -mq : mq;
         if (aw > wm) wm = aw;
-        wide mn = sat(rescale(w, 16), mom_bits);
+        wide mn = sat(mq, mom_bits);
         store_q(mom, i, mom_bits, mn);
 
         /* the new velocity is the step handed to the accumulator (Algorithm 1, 1st assignment) */

@@ -130,17 +130,14 @@ __device__ __forceinline__ void compute_store_group(const StepParams& p, Group<8
   v4i to, co;
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
-    uint32_t tw = 0, cw = 0;
+    int tn[4], cn[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       int k = w * 4 + b;                     // element within the group
-      int th = sx8(G.th[w], b), c = sx8(G.c[w], b), g = sx16(G.g[k >> 3][(k >> 1) & 3], k & 1);
-      int tn, cn;
-      update_fast<DECAY>(p, th, c, g, tn, cn, vmx, vmn);
-      tw |= (uint32_t)(tn & 0xff) << (8 * b);
-      cw |= (uint32_t)(cn & 0xff) << (8 * b);
+      update_fast<DECAY>(p, sx8(G.th[w], b), sx8(G.c[w], b), sx16(G.g[k >> 3][(k >> 1) & 3], k & 1), tn[b], cn[b], vmx, vmn);
     }
-    to[w] = (int)tw; co[w] = (int)cw;
+    to[w] = pack4x8(tn[0], tn[1], tn[2], tn[3]);
+    co[w] = pack4x8(cn[0], cn[1], cn[2], cn[3]);
   }
   st_stream((v4i*)((int8_t*)T.theta + e), to);
   st_stream((v4i*)((int8_t*)T.comp + e), co);
@@ -154,16 +151,12 @@ __device__ __forceinline__ void compute_store_group(const StepParams& p, Group<1
     v4i to, co;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      uint32_t tw = 0, cw = 0;
+      int tn[2], cn[2];
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        int th = sx16(G.th[q][w], h), c = sx16(G.c[q][w], h), g = sx16(G.g[q][w], h);
-        int tn, cn;
-        update_fast<DECAY>(p, th, c, g, tn, cn, vmx, vmn);
-        tw |= (uint32_t)(tn & 0xffff) << (16 * h);
-        cw |= (uint32_t)(cn & 0xffff) << (16 * h);
-      }
-      to[w] = (int)tw; co[w] = (int)cw;
+      for (int h = 0; h < 2; ++h)
+        update_fast<DECAY>(p, sx16(G.th[q][w], h), sx16(G.c[q][w], h), sx16(G.g[q][w], h), tn[h], cn[h], vmx, vmn);
+      to[w] = pack2x16(tn[0], tn[1]);
+      co[w] = pack2x16(cn[0], cn[1]);
     }
     st_stream((v4i*)((int16_t*)T.theta + e + 8 * q), to);
     st_stream((v4i*)((int16_t*)T.comp + e + 8 * q), co);

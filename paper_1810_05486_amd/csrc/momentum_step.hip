@@ -2,12 +2,13 @@
 // in the optimizer, INT8 or INT16 velocity).  One fused launch over every tile of every tensor:
 //
 //   w  = RNE(mu*m on grid G) + cap(RNE(-lr*g on G)) [+ cap(RNE(-lr*wd*theta on G))],  G = fl_m_out + 16
-//   m' = sat(RNE(w / 2^16));   s = cap(RNE(m' on grid F));   then Algorithm 1 with step s.
+//   mq = RNE(w / 2^16);  m' = sat(mq);  mmax = max|mq|;  s = cap(RNE(m' on grid F));  then Algorithm 1 with step s.
 //
 // Same work distribution as the plain update (persistent wavefronts over the tile table, 16 consecutive
 // elements per lane per pass, dwordx4 non-temporal accesses).  Two bit-identical arithmetic paths chosen per
-// tensor: generic 64-bit, and a 32-bit one (same-width theta/comp, int16 grads, no grid moves) in which the
-// gradient term is rounded by one fp32 FMA and the decay term by one fp64 FMA, as in the plain update.
+// tensor: generic 64-bit, and a 32-bit one (same-width theta/comp, int16 grads, theta's grid fixed) whose
+// shifts are wave-uniform operands of branch-free integer roundings (the velocity grid may move); the decay
+// term is rounded by one fp64 FMA as in the plain update.
 #include "step_common.hpp"
 
 namespace lpk {
@@ -19,10 +20,12 @@ struct MomParams {
   int      u, kth, kc;
   int64_t  lr, mu, lrwd;
   int      qmin_t, qmax_t, qmin_c, qmax_c, qmin_m, qmax_m;
-  // fast path
-  int      mu_i;  float nlr_f, magic_f;  int magic_fi;
+  // 32-bit path: each term is (x << a) then RNE >> b with exactly one of a, b non-zero
+  int      mu_i, a1, b1, h1, nz1;          // mu*m -> grid G
+  int      c2, b2, h2, nz2;                // (-lr << a2) * g -> grid G
+  int      a3, b3, h3, nz3;                // m' -> grid F
   double   nlrwd_d, magic_d;  int magic_dlo;
-  int      half_m1, s_half_m1, s_shl;      // rounding addend of v -> theta; of m' -> s (k3 > 0), or left shift (k3 <= 0)
+  int      half_m1;                        // rounding addend of v -> theta
 };
 
 __device__ __forceinline__ void update_generic_mom(const MomParams& p, int64_t th, int64_t c, int64_t m, int64_t g,
@@ -31,8 +34,8 @@ __device__ __forceinline__ void update_generic_mom(const MomParams& p, int64_t t
   int64_t w = rescale64(p.mu * m, p.k1);
   w += rescale_cap64(-p.lr * g, p.k2);
   if (p.lrwd) w += rescale_cap64(-p.lrwd * th, p.k3w);
-  wabs = (uint64_t)(w < 0 ? -w : w);
   int64_t mn = rne_shr64(w, 16);
+  wabs = (uint64_t)(mn < 0 ? -mn : mn);
   mn = mn > p.qmax_m ? p.qmax_m : (mn < p.qmin_m ? p.qmin_m : mn);
   int64_t s = rescale_cap64(mn, p.k3);
   int64_t v = th * (1ll << p.d) + c + s;
@@ -69,18 +72,28 @@ __device__ __forceinline__ void tile_generic_mom(const MomParams& p, const Tenso
 
 struct MaxTrack { int vmx, vmn, wmx, wmn; };
 
-template <bool DECAY, bool SHR>
+template <bool DECAY, bool K1ZERO, bool WIDEW>
 __device__ __forceinline__ void update_fast_mom(const MomParams& p, int th, int c, int m, int g, int& tn, int& cn, int& mn, MaxTrack& mt)
 {
-  int w = __mul24(m, p.mu_i) + (__float_as_int(__builtin_fmaf((float)g, p.nlr_f, p.magic_f)) - p.magic_fi);
-  if (DECAY) w += __double2loint(__builtin_fma((double)th, p.nlrwd_d, p.magic_d)) - p.magic_dlo;
-  mt.wmx = w > mt.wmx ? w : mt.wmx;
-  mt.wmn = w < mt.wmn ? w : mt.wmn;
-  int q = (w + 0x7fff + ((w >> 16) & 1)) >> 16;                      // RNE(w / 2^16)
+  int t1 = __mul24(m, p.mu_i);
+  if (!K1ZERO) t1 = rne_shr32((int)((unsigned)t1 << p.a1), p.b1, p.h1, p.nz1);
+  int t2 = rne_shr32(__mul24(g, p.c2), p.b2, p.h2, p.nz2);
+  if (DECAY) t2 += __double2loint(__builtin_fma((double)th, p.nlrwd_d, p.magic_d)) - p.magic_dlo;
+  int q;
+  if (WIDEW) {
+    // |t1| and |t2| are each below 2^31 but their sum may not be: add high and low halves separately.
+    const int lo = (t1 & 0xffff) + (t2 & 0xffff);                    // 0 .. 131070
+    const int fl = (t1 >> 16) + (t2 >> 16) + (lo >> 16);             // floor(w / 2^16)
+    const unsigned rem = (unsigned)lo & 0xffffu;
+    q = fl + (int)((rem | (unsigned)(fl & 1)) > 0x8000u);            // round half to even
+  } else {
+    const int w = t1 + t2;
+    q = (w + 0x7fff + ((w >> 16) & 1)) >> 16;                        // RNE(w / 2^16)
+  }
+  mt.wmx = q > mt.wmx ? q : mt.wmx;
+  mt.wmn = q < mt.wmn ? q : mt.wmn;
   mn = min(max(q, p.qmin_m), p.qmax_m);
-  int s;
-  if (SHR) s = (mn + p.s_half_m1 + ((mn >> p.k3) & 1)) >> p.k3;      // RNE(m' / 2^k3), k3 >= 1
-  else     s = (int)((unsigned)mn << p.s_shl);                       // exact
+  int s = rne_shr32((int)((unsigned)mn << p.a3), p.b3, p.h3, p.nz3);
   int v = (int)((unsigned)th << p.d) + c + s;
   mt.vmx = v > mt.vmx ? v : mt.vmx;
   mt.vmn = v < mt.vmn ? v : mt.vmn;
@@ -110,34 +123,32 @@ template <int W> __device__ __forceinline__ void store16(void* base, uint64_t e,
   if (W == 8) {
     v4i o;
 #pragma unroll
-    for (int w = 0; w < 4; ++w)
-      o[w] = (int)((uint32_t)(val[4 * w] & 0xff) | ((uint32_t)(val[4 * w + 1] & 0xff) << 8) |
-                   ((uint32_t)(val[4 * w + 2] & 0xff) << 16) | ((uint32_t)val[4 * w + 3] << 24));
+    for (int w = 0; w < 4; ++w) o[w] = pack4x8(val[4 * w], val[4 * w + 1], val[4 * w + 2], val[4 * w + 3]);
     st_stream((v4i*)((int8_t*)base + e), o);
   } else {
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       v4i o;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) o[w] = (int)((uint32_t)(val[8 * q + 2 * w] & 0xffff) | ((uint32_t)val[8 * q + 2 * w + 1] << 16));
+      for (int w = 0; w < 4; ++w) o[w] = pack2x16(val[8 * q + 2 * w], val[8 * q + 2 * w + 1]);
       st_stream((v4i*)((int16_t*)base + e + 8 * q), o);
     }
   }
 }
 
-template <int WT, int WM, bool DECAY, bool SHR>
+template <int WT, int WM, bool DECAY, bool K1ZERO>
 __device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<WT, WM>& G, const TensorDev& T, uint64_t e, MaxTrack& mt)
 {
   int tn[16], cn[16], mn[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k)
-    update_fast_mom<DECAY, SHR>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mt);
+    update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mt);
   store16<WT>(T.theta, e, tn);
   store16<WT>(T.comp, e, cn);
   store16<WM>(T.mom, e, mn);
 }
 
-template <int WT, int WM, bool DECAY, bool SHR>
+template <int WT, int WM, bool DECAY, bool K1ZERO>
 __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                               uint64_t& vm, uint64_t& wm)
 {
@@ -154,13 +165,13 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
     }
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps)
-      group_fast_mom<WT, WM, DECAY, SHR>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, mt);
+      group_fast_mom<WT, WM, DECAY, K1ZERO>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, mt);
   }
   for (; gi < ngroups; gi += kWave) {
     MGroup<WT, WM> G;
     const uint64_t e = off + (uint64_t)gi * kGroup;
     load16<WT>(G.th, T.theta, e); load16<WT>(G.c, T.comp, e); load16<WM>(G.m, T.mom, e); load16<16>(G.g, T.grad, e);
-    group_fast_mom<WT, WM, DECAY, SHR>(p, G, T, e, mt);
+    group_fast_mom<WT, WM, DECAY, K1ZERO>(p, G, T, e, mt);
   }
   int64_t a = mt.vmx, b = -(int64_t)mt.vmn;
   uint64_t x = (uint64_t)(a > b ? a : b);
@@ -176,9 +187,9 @@ template <int WT, int WM>
 __device__ __forceinline__ void tile_fast_mom_dispatch(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                                        uint64_t& vm, uint64_t& wm)
 {
-  const bool shr = p.k3 > 0;
-  if (p.lrwd) { if (shr) tile_fast_mom<WT, WM, true, true>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom<WT, WM, true, false>(p, T, off, cnt, lane, vm, wm); }
-  else        { if (shr) tile_fast_mom<WT, WM, false, true>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false>(p, T, off, cnt, lane, vm, wm); }
+  const bool k1z = p.k1 == 0;
+  if (p.lrwd) { if (k1z) tile_fast_mom<WT, WM, true, true>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom<WT, WM, true, false>(p, T, off, cnt, lane, vm, wm); }
+  else        { if (k1z) tile_fast_mom<WT, WM, false, true>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false>(p, T, off, cnt, lane, vm, wm); }
 }
 
 // ---------------------------------------------------------------- per-tensor set-up
@@ -209,33 +220,46 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   p.qmax_m = (1 << (p.wm - 1)) - 1; p.qmin_m = -(1 << (p.wm - 1));
   p.path = 1;
 
-  // 32-bit path: aligned, comp present and as wide as theta, int16 grads, no grid moves, d >= 1, and
-  // every intermediate provably below 2^31 in magnitude.
-  if (!p.has_comp || !T.vec_mom || p.wt != p.wc || p.wg != 16 || delta != 0 || delta_m != 0 || p.d < 1) return;
-  if (p.k2 < 1 || (p.k2 < 9 && ((int64_t)lr << 15) >= (1ll << (22 + p.k2)))) return;      // fp32 FMA rounding exact, |t2| < 2^22
-  if (p.lrwd && (p.k3w < 1 || p.k3w > 60)) return;
+  // 32-bit path: aligned, comp present and as wide as theta, int16 grads, theta's grid fixed, d >= 1, and every
+  // intermediate (including each rounding addend) provably below 2^31 in magnitude.
+  if (!p.has_comp || !T.vec_mom || p.wt != p.wc || p.wg != 16 || delta != 0 || p.d < 1) return;
+  const int64_t lim = 1ll << 31;
+  // t1 = mu*m brought to grid G
+  const int64_t X1 = (int64_t)mu << (p.wm - 1);
+  int64_t T1;
+  p.a1 = p.k1 < 0 ? -p.k1 : 0; p.b1 = p.k1 > 0 ? p.k1 : 0;
+  p.nz1 = p.b1 > 0; p.h1 = p.b1 > 0 ? (1 << (p.b1 - 1)) - 1 : 0;
+  if (p.b1 == 0) T1 = X1 << p.a1; else { if (X1 + (1ll << (p.b1 - 1)) >= lim) return; T1 = (X1 >> p.b1) + 1; }
+  if (T1 >= lim) return;
+  // t2 = -lr*g brought to grid G: the left shift is folded into the 24-bit multiplier
+  if (p.k2 < -8 || p.k2 > 30) return;
+  const int a2 = p.k2 < 0 ? -p.k2 : 0;
+  const int64_t C2 = (int64_t)lr << a2;
+  if (C2 >= (1ll << 23)) return;
+  const int64_t P2 = C2 << 15;
+  int64_t T2;
+  p.c2 = -(int)C2; p.b2 = p.k2 > 0 ? p.k2 : 0;
+  p.nz2 = p.b2 > 0; p.h2 = p.b2 > 0 ? (1 << (p.b2 - 1)) - 1 : 0;
+  if (p.b2 == 0) T2 = P2; else { if (P2 + (1ll << (p.b2 - 1)) >= lim) return; T2 = (P2 >> p.b2) + 1; }
+  // t3 = decay term (fp64 FMA rounding)
+  int64_t T3 = 0;
+  if (p.lrwd) { if (p.k3w < 1 || p.k3w > 60) return; T3 = ((p.lrwd << (p.wt - 1)) >> p.k3w) + 1; }
+  if (p.wm == 16 ? (T1 >= lim || T2 + T3 >= lim) : (T1 + T2 + T3 + 0x8000 >= lim)) return;   // 16-bit velocity adds in two halves
+  // s = m' brought to grid F
   if (p.k3 > 30 || p.k3 < -24) return;
-  int64_t wb = (int64_t)mu << (p.wm - 1);                                                 // |mu * m|
-  wb += p.k2 < 40 ? (((int64_t)lr << 15) >> p.k2) + 1 : 0;                                // |t2|
-  if (p.lrwd) wb += ((p.lrwd << (p.wt - 1)) >> p.k3w) + 1;                                // |t3|
-  if (wb + 0x8000 >= (1ll << 31)) return;
-  int64_t sb = p.k3 > 0 ? ((1ll << (p.wm - 1)) >> p.k3) + 1 : (1ll << (p.wm - 1 - p.k3));  // |s|
-  int64_t vb = (1ll << (p.wt - 1 + p.d)) + (1ll << (p.wc - 1)) + sb + (1ll << (p.d - 1));
-  if (vb >= (1ll << 31)) return;
+  p.a3 = p.k3 < 0 ? -p.k3 : 0; p.b3 = p.k3 > 0 ? p.k3 : 0;
+  p.nz3 = p.b3 > 0; p.h3 = p.b3 > 0 ? (1 << (p.b3 - 1)) - 1 : 0;
+  const int64_t M = 1ll << (p.wm - 1);
+  const int64_t S = p.b3 == 0 ? (M << p.a3) : (M >> p.b3) + 1;
+  const int64_t V = (1ll << (p.wt - 1 + p.d)) + (1ll << (p.wc - 1)) + S + (1ll << (p.d - 1));
+  if (V >= lim) return;
   p.path = 2;
   p.mu_i = (int)mu;
-  const int k2 = p.k2 > 40 ? 40 : p.k2;
-  p.magic_fi = ((127 + 23 + k2) << 23) | 0x400000;
-  p.magic_f  = __int_as_float(p.magic_fi);
-  p.nlr_f    = -(float)lr;
-  const int k3w = p.k3w;
-  const long long md = ((long long)(1023 + 52 + (p.lrwd ? k3w : 1)) << 52) | (1ll << 51);
+  const long long md = ((long long)(1023 + 52 + (p.lrwd ? p.k3w : 1)) << 52) | (1ll << 51);
   p.magic_d   = __longlong_as_double(md);
   p.magic_dlo = (int)(md & 0xffffffffll);
   p.nlrwd_d   = -(double)p.lrwd;
   p.half_m1   = (1 << (p.d - 1)) - 1;
-  p.s_half_m1 = p.k3 > 0 ? (1 << (p.k3 - 1)) - 1 : 0;
-  p.s_shl     = p.k3 > 0 ? 0 : -p.k3;
 }
 
 // ---------------------------------------------------------------- the kernel

@@ -75,6 +75,28 @@ __device__ __forceinline__ void flush_wave(uint64_t* vmax, int tensor, uint64_t 
   if (lane == 0 && m) atomicMax((unsigned long long*)&vmax[tensor], (unsigned long long)m);
 }
 
+// Low bytes of four ints -> one dword (a in byte 0), low halves of two ints -> one dword (a low), via
+// v_perm_b32: selector bytes 0-3 pick bytes of the second operand, 4-7 of the first, 0x0c gives 0x00.
+__device__ __forceinline__ int pack4x8(int a, int b, int c, int d)
+{
+  const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);
+  const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x0c0c0400u);
+  return (int)(lo | (hi << 16));
+}
+__device__ __forceinline__ int pack2x16(int a, int b)
+{
+  return (int)__builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x05040100u);
+}
+
+// RNE(y / 2^b) for a wave-uniform 0 <= b <= 30 without a branch: `half_m1` = 2^(b-1) - 1 (0 when b == 0),
+// `nz` = 1 when b > 0 else 0 (a zero-width bit-field extract yields 0, so b == 0 returns y itself).
+// The caller has shown |y| + 2^(b-1) < 2^31.
+__device__ __forceinline__ int rne_shr32(int y, int b, int half_m1, int nz)
+{
+  const int lsb = (int)__builtin_amdgcn_ubfe((uint32_t)y, (uint32_t)b, (uint32_t)nz);
+  return (y + half_m1 + lsb) >> b;
+}
+
 // Decode one tile-table entry into wave-uniform scalars.
 __device__ __forceinline__ void read_tile(const Tile* __restrict__ tiles, uint32_t ti, int& tensor, uint32_t& cnt, uint64_t& off)
 {

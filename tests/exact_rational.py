@@ -83,7 +83,7 @@ def step(theta, c, g, theta_bits, comp_bits, d, fl_in, fl_out, fl_g, lr_q, wd_q=
 def momentum_step(theta, c, m, g, theta_bits, comp_bits, mom_bits, d, fl_in, fl_out, fl_m_in, fl_m_out, fl_g,
                   lr_q, mu_q, wd_q=0, kahan=True):
     """Momentum SGD (velocity m <- mu*m - lr*(g + wd*theta), theta <- theta + m) with the lazy update inside.
-    Returns (theta', c', m', |v| on grid F, |w| on the velocity's working grid fl_m_out + 16)."""
+    Returns (theta', c', m', |v| on grid F, |velocity before saturation| on grid fl_m_out)."""
     if not kahan:
         d, c = 0, 0
     lr, mu, wd = Fr(lr_q, 2 ** 16), Fr(mu_q, 2 ** 16), Fr(wd_q, 2 ** 16)
@@ -92,8 +92,9 @@ def momentum_step(theta, c, m, g, theta_bits, comp_bits, mom_bits, d, fl_in, fl_
     w += max(-CAP, min(CAP, rne(-lr * g * two(-fl_g) * two(G))))
     if wd_q:
         w += max(-CAP, min(CAP, rne(-lr * wd * theta * two(-fl_in) * two(G))))
-    m_new = sat(rne(Fr(w, 2 ** 16)), mom_bits)
+    m_wide = rne(Fr(w, 2 ** 16))
+    m_new = sat(m_wide, mom_bits)
     F = fl_in + d
     s = max(-CAP, min(CAP, rne(m_new * two(-fl_m_out) * two(F))))
     t, cn, vabs = _apply(theta, c, s, theta_bits, comp_bits, d, fl_in, fl_out, kahan)
-    return t, cn, m_new, vabs, abs(w)
+    return t, cn, m_new, vabs, abs(m_wide)

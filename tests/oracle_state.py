@@ -66,7 +66,7 @@ class OracleState:
             if self.cfg.reselect:
                 new_next[t] = ref.select_fraclen_vmax(self.vmax[t], self.fl_theta[t] + self.d[t], self.cfg.bits[t],
                                                       self.fl_next[t], self.status)
-            new_mnext[t] = ref.select_fraclen_vmax(self.mmax[t], self.fl_mom_next[t] + 16, self.mom_bits[t],
+            new_mnext[t] = ref.select_fraclen_vmax(self.mmax[t], self.fl_mom_next[t], self.mom_bits[t],
                                                    self.fl_mom_next[t], self.status)
         self.fl_theta, self.fl_next = self.fl_next, new_next
         self.fl_mom, self.fl_mom_next = self.fl_mom_next, new_mnext

@@ -37,11 +37,11 @@ MUTATIONS = [
     ("comp_added_twice", "wide c  = comp ? load_q(comp, i, comp_bits) : 0;", "wide c  = comp ? 2 * load_q(comp, i, comp_bits) : 0;"),
     ("momentum_mu_grid", "rescale((wide)mu_q * m, (fl_m_in + 16) - G);", "rescale((wide)mu_q * m, fl_m_in - G);"),
     ("momentum_gradient_sign", "w += rescale_cap(-(wide)lr_q * g, (fl_g + 16) - G);", "w += rescale_cap((wide)lr_q * g, (fl_g + 16) - G);"),
-    ("momentum_guard_bits", "wide mn = sat(rescale(w, 16), mom_bits);", "wide mn = sat(rescale(w, 15), mom_bits);"),
+    ("momentum_guard_bits", "wide mq = rescale(w, 16);", "wide mq = rescale(w, 15);"),
     ("momentum_step_grid", "wide s = rescale_cap(mn, fl_m_out - F);", "wide s = rescale_cap(mn, F - fl_m_out);"),
     ("momentum_old_velocity_used", "wide s = rescale_cap(mn, fl_m_out - F);", "wide s = rescale_cap(m, fl_m_out - F);"),
     ("momentum_decay_grid", "* th, (fl_in + 32) - G);", "* th, (fl_in + 16) - G);"),
-    ("momentum_velocity_not_saturated", "wide mn = sat(rescale(w, 16), mom_bits);", "wide mn = rescale(w, 16);"),
+    ("momentum_velocity_not_saturated", "wide mn = sat(mq, mom_bits);", "wide mn = mq;"),
     ("theta_unscaled", "wide v = th * ((wide)1 << d) + c + s;", "wide v = th + c + s;"),
 ]
 
