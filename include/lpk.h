@@ -174,6 +174,19 @@ int lpk_kahan_sgd_step(lpk_tensor_list* list,
                        uint64_t* vmax_out, uint32_t* status, void* stream);
 
 /*
+ * The same update fed from the fp32 gradients: exactly lpk_quantize_tensor(LPK_SEL_GRAD, fl_grad) followed by
+ * lpk_kahan_sgd_step, in ONE pass that reads desc.src_f32, quantizes each gradient in registers
+ * (sat_W(RNE(x * 2^fl_grad[t])), W = bits(grad_dtype); NaN -> 0, +-Inf -> rails, LPK_STATUS_NONFINITE) and never
+ * touches desc.grad -- the int16 round trip through HBM (2 B written + 2 B read per element) disappears.
+ * Results (theta, comp, vmax, status) are bit-identical to the two-call sequence.  Every non-empty tensor
+ * needs src_f32 (else INVALID_ARG); fl_grad normally comes from lpk_select_fraclen(LPK_F32, LPK_SEL_GRAD).
+ */
+int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* list,
+                               const int32_t* fl_theta_in, const int32_t* fl_theta_out, const int32_t* fl_grad,
+                               uint32_t lr_q16, uint32_t wd_q16,
+                               uint64_t* vmax_out, uint32_t* status, void* stream);
+
+/*
  * Momentum SGD with the lazy update inside (Section 4: the momentum optimizer, mu = 0.9, with Algorithm 1
  * implemented in the optimizer; INT8 or INT16 velocity).  Heavy-ball form with the learning rate inside
  * the velocity:  m <- mu*m - lr*(g + wd*theta);  theta <- theta + m  through Algorithm 1.

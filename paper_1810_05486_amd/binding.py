@@ -53,6 +53,8 @@ def lib():
         L.lpk_select_fraclen.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, vp]
         L.lpk_quantize_tensor.argtypes = [vp, ci, vp, vp, vp]
         L.lpk_kahan_sgd_step.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
+        L.lpk_kahan_sgd_step_f32grad.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
+        L.lpk_kahan_sgd_step_f32grad.restype = ci
         L.lpk_momentum_sgd_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, u32, vp, vp, vp, vp]
         L.lpk_momentum_sgd_step.restype = ci
         L.lpk_stream_copy.argtypes = [vp, vp, u64, vp]
@@ -167,6 +169,13 @@ def lpk_kahan_sgd_step(tl, fl_theta_in, fl_theta_out, fl_grad, lr_q16, wd_q16=0,
     _check(lib().lpk_kahan_sgd_step(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_grad),
                                     int(lr_q16), int(wd_q16), _addr(vmax_out), _addr(status), _stream(stream)),
            "lpk_kahan_sgd_step")
+
+
+def lpk_kahan_sgd_step_f32grad(tl, fl_theta_in, fl_theta_out, fl_grad, lr_q16, wd_q16=0, vmax_out=None, status=None,
+                               stream=None):
+    _check(lib().lpk_kahan_sgd_step_f32grad(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_grad),
+                                            int(lr_q16), int(wd_q16), _addr(vmax_out), _addr(status), _stream(stream)),
+           "lpk_kahan_sgd_step_f32grad")
 
 
 def lpk_momentum_sgd_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16=0,

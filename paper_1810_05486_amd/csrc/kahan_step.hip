@@ -5,8 +5,14 @@
 // w, w + W, w + 2W, ... of the tile table, so at any moment the grid streams
 // one contiguous window of the parameter set.  A tile is 4096 elements of one
 // tensor; a lane handles 16 consecutive elements per pass (one dwordx4 of int8
-// theta, one of comp, two of int16 grad), four passes per tile with all loads
-// issued before the arithmetic.
+// theta, one of comp, two of int16 grad), several passes in flight together.
+// Runs of full int8 tiles are software-pipelined: the next tile's loads are
+// issued before the current tile is computed and stored.
+//
+// Gradient source: the int16 gradients written by the quantization kernel, or
+// (second kernel instance) the fp32 gradients themselves, quantized in
+// registers exactly as the quantization kernel would -- the fused form saves
+// the int16 round trip through HBM.
 //
 // Arithmetic: two paths with identical results.
 //   * generic: 64-bit integers, any widths / shifts / grid move / decay /
@@ -25,6 +31,8 @@
 
 namespace lpk {
 
+enum { kGradI16 = 0, kGradF32 = 1 };
+
 struct StepParams {
   int      path;            // 0 skip, 1 generic, 2 fast
   int      wt, wc, wg, d;
@@ -34,14 +42,25 @@ struct StepParams {
   int      u, kth, kc;      // grid move: v_G = v << u; theta' = RNE(v_G >> kth); c' = RNE(r >> kc)
   int64_t  lr, lrwd;
   int      qmin_t, qmax_t, qmin_c, qmax_c;
+  float    gscale, glo, ghi;            // fp32 gradient source: 2^fl_g and the rails of the gradient width
   // fast path constants
   float    nlr_f;  float magic_f;  int magic_fi;
   double   nlrwd_d; double magic_d; int magic_dlo;
   int      half_m1;         // 2^(d-1) - 1
 };
 
-// ---------------------------------------------------------------- generic (int64)
+// Quantize one fp32 gradient exactly as the quantization kernel does; the result is an integer-valued float.
+// `ab_max` collects the largest |bit pattern| seen (>= 0x7f800000 means a NaN or Inf went by).
+__device__ __forceinline__ float quant_grad(const StepParams& p, float x, uint32_t& ab_max)
+{
+  const uint32_t ab = __float_as_uint(x) & 0x7fffffffu;
+  ab_max = ab > ab_max ? ab : ab_max;
+  float y = __builtin_rintf(x * p.gscale);
+  y = __builtin_fminf(__builtin_fmaxf(y, p.glo), p.ghi);
+  return ab > 0x7f800000u ? 0.0f : y;                  // NaN -> 0
+}
 
+// ---------------------------------------------------------------- generic (int64)
 
 __device__ __forceinline__ void update_generic(const StepParams& p, int64_t th, int64_t c, int64_t g,
                                                int& th_new, int& c_new, uint64_t& vabs)
@@ -59,16 +78,17 @@ __device__ __forceinline__ void update_generic(const StepParams& p, int64_t th, 
   th_new = (int)tn; c_new = (int)cn;
 }
 
-
 // Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
-__device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane)
+template <int GS>
+__device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
+                                                 uint32_t& ab_max)
 {
   uint64_t vm = 0;
   for (uint32_t j = lane; j < cnt; j += kWave) {
     uint64_t i = off + j;
     int th = load_elem(T.theta, i, p.wt);
     int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
-    int g  = load_elem(T.grad, i, p.wg);
+    int g  = GS == kGradF32 ? (int)quant_grad(p, ((const float*)T.src)[i], ab_max) : load_elem(T.grad, i, p.wg);
     int tn, cn; uint64_t va;
     update_generic(p, th, c, g, tn, cn, va);
     vm = va > vm ? va : vm;
@@ -80,115 +100,95 @@ __device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const Tens
 
 // ---------------------------------------------------------------- fast (int32 + FMA rounding)
 
+struct Track { int vmx, vmn; uint32_t ab; };
+
 template <bool DECAY>
-__device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, int g, int& tn, int& cn, int& vmx, int& vmn)
+__device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, float gf, int& tn, int& cn, Track& tr)
 {
 #ifdef LPK_NO_MATH
-  tn = th ^ (g & 1); cn = c; vmx = max(vmx, g); return;
+  tn = th ^ (__float_as_int(gf) & 1); cn = c; return;
 #endif
-  int s = __float_as_int(__builtin_fmaf((float)g, p.nlr_f, p.magic_f)) - p.magic_fi;
+  int s = __float_as_int(__builtin_fmaf(gf, p.nlr_f, p.magic_f)) - p.magic_fi;
   if (DECAY) {
     double r = __builtin_fma((double)th, p.nlrwd_d, p.magic_d);
     s += __double2loint(r) - p.magic_dlo;
   }
-  int v = (th << p.d) + c + s;          // th << d on a negative th: two's complement, what the hardware does
-  vmx = v > vmx ? v : vmx;
-  vmn = v < vmn ? v : vmn;
+  int v = (int)((unsigned)th << p.d) + c + s;
+  tr.vmx = v > tr.vmx ? v : tr.vmx;
+  tr.vmn = v < tr.vmn ? v : tr.vmn;
   int q = (v + p.half_m1 + ((v >> p.d) & 1)) >> p.d;      // RNE(v / 2^d), d >= 1, no overflow by path choice
   tn = min(max(q, p.qmin_t), p.qmax_t);
-  int r = v - (tn << p.d);
+  int r = v - (int)((unsigned)tn << p.d);
   cn = min(max(r, p.qmin_c), p.qmax_c);
 }
 
+// 16 consecutive elements of one lane.  WT / WC = widths of theta and comp; GS = gradient source.
+template <int WT, int WC, int GS> struct Group {
+  v4i th[WT / 8], c[WC / 8], g[GS == kGradF32 ? 4 : 2];
+};
 
-// 16 consecutive elements per lane; W = width of theta and comp (8 or 16), grads int16.
-template <int W> struct Group;
-template <> struct Group<8>  { v4i th;      v4i c;      v4i g[2]; };
-template <> struct Group<16> { v4i th[2];   v4i c[2];   v4i g[2]; };
-
-__device__ __forceinline__ void load_group(Group<8>& G, const TensorDev& T, uint64_t e)
+template <int WT, int WC, int GS>
+__device__ __forceinline__ void load_group(Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e)
 {
-  G.th   = ld_stream((const v4i*)((const int8_t*)T.theta + e));
-  G.c    = ld_stream((const v4i*)((const int8_t*)T.comp + e));
-  G.g[0] = ld_stream((const v4i*)((const int16_t*)T.grad + e));
-  G.g[1] = ld_stream((const v4i*)((const int16_t*)T.grad + e + 8));
-}
-__device__ __forceinline__ void load_group(Group<16>& G, const TensorDev& T, uint64_t e)
-{
-  G.th[0] = ld_stream((const v4i*)((const int16_t*)T.theta + e));
-  G.th[1] = ld_stream((const v4i*)((const int16_t*)T.theta + e + 8));
-  G.c[0]  = ld_stream((const v4i*)((const int16_t*)T.comp + e));
-  G.c[1]  = ld_stream((const v4i*)((const int16_t*)T.comp + e + 8));
-  G.g[0]  = ld_stream((const v4i*)((const int16_t*)T.grad + e));
-  G.g[1]  = ld_stream((const v4i*)((const int16_t*)T.grad + e + 8));
-}
-
-
-template <bool DECAY>
-__device__ __forceinline__ void compute_store_group(const StepParams& p, Group<8>& G, const TensorDev& T, uint64_t e, int& vmx, int& vmn)
-{
-  v4i to, co;
+  load16<WT>(G.th, T.theta, e);
+  load16<WC>(G.c, T.comp, e);
+  if (GS == kGradF32) {
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    int tn[4], cn[4];
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      int k = w * 4 + b;                     // element within the group
-      update_fast<DECAY>(p, sx8(G.th[w], b), sx8(G.c[w], b), sx16(G.g[k >> 3][(k >> 1) & 3], k & 1), tn[b], cn[b], vmx, vmn);
-    }
-    to[w] = pack4x8(tn[0], tn[1], tn[2], tn[3]);
-    co[w] = pack4x8(cn[0], cn[1], cn[2], cn[3]);
+    for (int j = 0; j < (GS == kGradF32 ? 4 : 2); ++j) G.g[j] = ld_stream((const v4i*)((const float*)T.src + e + 4 * j));
+  } else {
+    G.g[0] = ld_stream((const v4i*)((const int16_t*)T.grad + e));
+    G.g[1] = ld_stream((const v4i*)((const int16_t*)T.grad + e + 8));
   }
-  st_stream((v4i*)((int8_t*)T.theta + e), to);
-  st_stream((v4i*)((int8_t*)T.comp + e), co);
 }
 
-template <bool DECAY>
-__device__ __forceinline__ void compute_store_group(const StepParams& p, Group<16>& G, const TensorDev& T, uint64_t e, int& vmx, int& vmn)
+template <int WT, int WC, int GS, bool DECAY>
+__device__ __forceinline__ void compute_store_group(const StepParams& p, const Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
+  int tn[16], cn[16];
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    v4i to, co;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      int tn[2], cn[2];
-#pragma unroll
-      for (int h = 0; h < 2; ++h)
-        update_fast<DECAY>(p, sx16(G.th[q][w], h), sx16(G.c[q][w], h), sx16(G.g[q][w], h), tn[h], cn[h], vmx, vmn);
-      to[w] = pack2x16(tn[0], tn[1]);
-      co[w] = pack2x16(cn[0], cn[1]);
-    }
-    st_stream((v4i*)((int16_t*)T.theta + e + 8 * q), to);
-    st_stream((v4i*)((int16_t*)T.comp + e + 8 * q), co);
+  for (int k = 0; k < 16; ++k) {
+    float gf;
+    if (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[(k >> 2) & (GS == kGradF32 ? 3 : 1)][k & 3]), tr.ab);
+    else                gf = (float)sx16(G.g[(k >> 3) & 1][(k >> 1) & 3], k & 1);
+    update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
+  store16<WT>(T.theta, e, tn);
+  store16<WC>(T.comp, e, cn);
+}
+
+__device__ __forceinline__ uint64_t track_max(const Track& tr)
+{
+  int64_t a = tr.vmx, b = -(int64_t)tr.vmn;
+  return (uint64_t)(a > b ? a : b);
 }
 
 // Vector tile: full 16-element groups with the fast arithmetic, the ragged end element by element.
-template <int W, bool DECAY>
-__device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane)
+template <int WT, int WC, int GS, bool DECAY>
+__device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
 {
-  int vmx = 0, vmn = 0;
+  Track tr{0, 0, ab_max};
+  constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : 8);     // VGPRs of one group
+  constexpr int kP = kRegs <= 16 ? 4 : 2;                               // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
-  if (ngroups == kWave * kPasses) {                       // full tile: every load issued before any arithmetic
-    Group<W> G[kPasses];
+  uint32_t gi = lane;
+  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
+    Group<WT, WC, GS> G[kP];
 #pragma unroll
-    for (int ps = 0; ps < kPasses; ++ps) load_group(G[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup);
+    for (int ps = 0; ps < kP; ++ps) load_group(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
 #pragma unroll
-    for (int ps = 0; ps < kPasses; ++ps)
-      compute_store_group<DECAY>(p, G[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup, vmx, vmn);
-  } else {
-    for (uint32_t gi = lane; gi < ngroups; gi += kWave) {
-      Group<W> G;
-      uint64_t e = off + (uint64_t)gi * kGroup;
-      load_group(G, T, e);
-      compute_store_group<DECAY>(p, G, T, e, vmx, vmn);
-    }
+    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
   }
-  int64_t a = vmx, b = -(int64_t)vmn;
-  uint64_t vm = (uint64_t)(a > b ? a : b);
+  for (; gi < ngroups; gi += kWave) {
+    Group<WT, WC, GS> G;
+    const uint64_t e = off + (uint64_t)gi * kGroup;
+    load_group(G, T, e);
+    compute_store_group<WT, WC, GS, DECAY>(p, G, T, e, tr);
+  }
+  ab_max = tr.ab;
+  uint64_t vm = track_max(tr);
   const uint32_t tail = cnt - ngroups * kGroup;           // < 16 elements
   if (tail) {
-    uint64_t t2 = tile_generic(p, T, off + (uint64_t)ngroups * kGroup, tail, lane);
+    uint64_t t2 = tile_generic<GS>(p, T, off + (uint64_t)ngroups * kGroup, tail, lane, ab_max);
     vm = t2 > vm ? t2 : vm;
   }
   return vm;
@@ -196,18 +196,18 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 
 // One pipeline stage: start the loads of the wave's next tile into `nxt` if that tile continues the run
 // (same tensor, full), then compute and store `cur`.  Returns whether `nxt` was filled; ti/off advance to it.
-template <bool DECAY>
+template <int GS, bool DECAY>
 __device__ __forceinline__ bool stage_fast8(const StepParams& p, const TensorDev& T, const Tile* __restrict__ tiles,
                                             uint32_t n_tiles, uint32_t nw, uint32_t& ti, uint64_t& off, int tensor, int lane,
-                                            Group<8> (&cur)[kPasses], Group<8> (&nxt)[kPasses], int& vmx, int& vmn)
+                                            Group<8, 8, GS> (&cur)[kPasses], Group<8, 8, GS> (&nxt)[kPasses], Track& tr)
 {
   const uint32_t tn = ti + nw;
   bool more = false;
   uint64_t noff = 0;
   if (tn < n_tiles) {
-    const Tile nx = tiles[tn];
-    more = wave_uniform((int)nx.tensor) == tensor && (uint32_t)wave_uniform((int)nx.count) == (uint32_t)kTileElems;
-    noff = ((uint64_t)(uint32_t)wave_uniform((int)(nx.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)nx.offset);
+    int nt; uint32_t ncnt;
+    read_tile(tiles, tn, nt, ncnt, noff);
+    more = nt == tensor && ncnt == (uint32_t)kTileElems;
   }
   if (more) {
 #pragma unroll
@@ -215,31 +215,33 @@ __device__ __forceinline__ bool stage_fast8(const StepParams& p, const TensorDev
   }
 #pragma unroll
   for (int ps = 0; ps < kPasses; ++ps)
-    compute_store_group<DECAY>(p, cur[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup, vmx, vmn);
+    compute_store_group<8, 8, GS, DECAY>(p, cur[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup, tr);
   if (more) { ti = tn; off = noff; }
   return more;
 }
 
 // Processes the full tile at (ti, off) and every following tile of this wave that continues the run; on
 // return ti is the last tile consumed (the caller's loop increment moves past it).
-template <bool DECAY>
+template <int GS, bool DECAY>
 __device__ __forceinline__ uint64_t run_fast8(const StepParams& p, const TensorDev& T, const Tile* __restrict__ tiles,
-                                              uint32_t n_tiles, uint32_t nw, uint32_t& ti, uint64_t off, int tensor, int lane)
+                                              uint32_t n_tiles, uint32_t nw, uint32_t& ti, uint64_t off, int tensor, int lane,
+                                              uint32_t& ab_max)
 {
-  int vmx = 0, vmn = 0;
-  Group<8> A[kPasses], B[kPasses];
+  Track tr{0, 0, ab_max};
+  Group<8, 8, GS> A[kPasses], B[kPasses];
 #pragma unroll
   for (int ps = 0; ps < kPasses; ++ps) load_group(A[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup);
   while (true) {
-    if (!stage_fast8<DECAY>(p, T, tiles, n_tiles, nw, ti, off, tensor, lane, A, B, vmx, vmn)) break;
-    if (!stage_fast8<DECAY>(p, T, tiles, n_tiles, nw, ti, off, tensor, lane, B, A, vmx, vmn)) break;
+    if (!stage_fast8<GS, DECAY>(p, T, tiles, n_tiles, nw, ti, off, tensor, lane, A, B, tr)) break;
+    if (!stage_fast8<GS, DECAY>(p, T, tiles, n_tiles, nw, ti, off, tensor, lane, B, A, tr)) break;
   }
-  int64_t a = vmx, b = -(int64_t)vmn;
-  return (uint64_t)(a > b ? a : b);
+  ab_max = tr.ab;
+  return track_max(tr);
 }
 
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
 
+template <int GS>
 __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, int fl_in, int fl_out, int fl_g,
                                              uint32_t lr, uint32_t wd, uint32_t& status_bits)
 {
@@ -260,12 +262,16 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   p.qmax_t = (1 << (p.wt - 1)) - 1; p.qmin_t = -(1 << (p.wt - 1));
   const int wc = p.has_comp ? p.wc : 8;
   p.qmax_c = (1 << (wc - 1)) - 1;   p.qmin_c = -(1 << (wc - 1));
+  p.gscale = __uint_as_float((uint32_t)(127 + fl_g) << 23);
+  p.glo = -(float)(1 << (p.wg - 1)); p.ghi = (float)((1 << (p.wg - 1)) - 1);
   p.path = 1;
 
-  // Fast path: same-width theta/comp with int16 grads on 16-byte aligned buffers, no grid move,
-  // 1 <= d, a step shift k with |lr * g| <= lr * 2^15 < 2^(22+k) (so the fp32 FMA rounding trick is exact
-  // and |s| < 2^22), and every intermediate provably inside int32.
-  if (!p.has_comp || !T.vec_step || p.wt != p.wc || p.wg != 16 || delta != 0 || p.d < 1 || p.kg < 1) return;
+  // Fast path: int8/int8, int16/int16 or int8/int16 theta/comp with 16-bit grads on 16-byte aligned buffers,
+  // no grid move, 1 <= d, a step shift k with |lr * g| <= lr * 2^15 < 2^(22+k) (so the fp32 FMA rounding trick
+  // is exact and |s| < 2^22), and every intermediate provably inside int32.
+  const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
+  const bool vec = T.vec_step && (GS == kGradI16 || (((uintptr_t)T.src) & 15u) == 0);
+  if (!p.has_comp || !vec || !widths_ok || p.wg != 16 || delta != 0 || p.d < 1 || p.kg < 1) return;
   if (p.kg < 9 && ((int64_t)lr << 15) >= (1ll << (22 + p.kg))) return;
   int64_t bound = (1ll << (p.wt - 1 + p.d)) + (1ll << (p.wc - 1));             // |theta * 2^d| + |c|
   bound += p.kg < 40 ? (((int64_t)lr << 15) >> p.kg) + 1 : 0;                   // |s_g|
@@ -288,7 +294,13 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
 
 // ---------------------------------------------------------------- the kernel
 
+template <int WT, int WC, int GS>
+__device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
+{
+  return p.lrwd ? tile_fast<WT, WC, GS, true>(p, T, off, cnt, lane, ab) : tile_fast<WT, WC, GS, false>(p, T, off, cnt, lane, ab);
+}
 
+template <int GS>
 __global__ void __launch_bounds__(kBlock)
 kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                   const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out, const int32_t* __restrict__ fl_g,
@@ -304,38 +316,39 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
 
   int cur = -1;
   uint64_t lane_max = 0;
-  uint32_t status_bits = 0;
+  uint32_t status_bits = 0, ab_max = 0;
   StepParams p; p.path = 0;
   TensorDev T;
 
   for (uint32_t ti = w0; ti < n_tiles; ti += nw) {      // ti may also be advanced inside by a pipelined run
-    const Tile tl = tiles[ti];
-    const int t = wave_uniform((int)tl.tensor);
-    const uint32_t cnt = (uint32_t)wave_uniform((int)tl.count);
-    const uint64_t off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
+    int t; uint32_t cnt; uint64_t off;
+    read_tile(tiles, ti, t, cnt, off);
     if (t != cur) {
       if (cur >= 0 && vmax) flush_wave(vmax, cur, lane_max, lane);
       lane_max = 0;
       cur = t;
       T = tensors[t];
-      setup_tensor(p, T, fl_in[t], fl_out[t], fl_g[t], lr, wd, status_bits);
+      setup_tensor<GS>(p, T, fl_in[t], fl_out[t], fl_g[t], lr, wd, status_bits);
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && cnt == (uint32_t)kTileElems) {
-        // Run of full int8 tiles of this tensor, software-pipelined: the loads of the wave's next tile are in
-        // flight while the current one is computed and stored, so the memory pipe never waits for the ALU.
-        vm = p.lrwd ? run_fast8<true>(p, T, tiles, n_tiles, nw, ti, off, cur, lane)
-                    : run_fast8<false>(p, T, tiles, n_tiles, nw, ti, off, cur, lane);
+      if (p.wt == 8 && p.wc == 8) {
+        if (GS == kGradI16 && cnt == (uint32_t)kTileElems) {
+          // Run of full int8 tiles of this tensor, software-pipelined: the loads of the wave's next tile are in
+          // flight while the current one is computed and stored, so the memory pipe never waits for the ALU.
+          vm = p.lrwd ? run_fast8<GS, true>(p, T, tiles, n_tiles, nw, ti, off, cur, lane, ab_max)
+                      : run_fast8<GS, false>(p, T, tiles, n_tiles, nw, ti, off, cur, lane, ab_max);
+        } else vm = tile_fast_decay<8, 8, GS>(p, T, off, cnt, lane, ab_max);
       }
-      else if (p.wt == 8) vm = p.lrwd ? tile_fast<8, true>(p, T, off, cnt, lane)  : tile_fast<8, false>(p, T, off, cnt, lane);
-      else                vm = p.lrwd ? tile_fast<16, true>(p, T, off, cnt, lane) : tile_fast<16, false>(p, T, off, cnt, lane);
+      else if (p.wt == 16) vm = tile_fast_decay<16, 16, GS>(p, T, off, cnt, lane, ab_max);
+      else                 vm = tile_fast_decay<8, 16, GS>(p, T, off, cnt, lane, ab_max);
     } else if (p.path == 1) {
-      vm = tile_generic(p, T, off, cnt, lane);
+      vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
     }
     lane_max = vm > lane_max ? vm : lane_max;
   }
 
+  if (GS == kGradF32 && __ballot(ab_max >= 0x7f800000u)) status_bits |= kStatusNonFinite;
   if (status && status_bits && lane == 0) atomicOr(status, status_bits);
 
   // LDS stage: the four waves of a block usually end on the same tensor.
@@ -349,15 +362,19 @@ __global__ void __launch_bounds__(kBlock) fill_u64_kernel(uint64_t* p, uint32_t 
 }
 
 hipError_t launch_kahan_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                             const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_g, uint32_t lr, uint32_t wd,
-                             uint64_t* vmax, uint32_t* status, hipStream_t stream)
+                             int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_g,
+                             uint32_t lr, uint32_t wd, uint64_t* vmax, uint32_t* status, hipStream_t stream)
 {
   if (vmax) {
     hipLaunchKernelGGL(fill_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, n_tensors, 0ull);
   }
   if (n_tiles) {
-    hipLaunchKernelGGL(kahan_step_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                       fl_in, fl_out, fl_g, lr, wd, vmax, status);
+    if (grad_is_f32)
+      hipLaunchKernelGGL(kahan_step_kernel<kGradF32>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                         fl_in, fl_out, fl_g, lr, wd, vmax, status);
+    else
+      hipLaunchKernelGGL(kahan_step_kernel<kGradI16>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                         fl_in, fl_out, fl_g, lr, wd, vmax, status);
   }
   return hipGetLastError();
 }

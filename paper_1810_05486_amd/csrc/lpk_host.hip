@@ -9,7 +9,7 @@
 
 namespace lpk {
 hipError_t launch_kahan_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                             const int32_t*, const int32_t*, const int32_t*, uint32_t lr, uint32_t wd,
+                             int grad_is_f32, const int32_t*, const int32_t*, const int32_t*, uint32_t lr, uint32_t wd,
                              uint64_t* vmax, uint32_t* status, hipStream_t);
 hipError_t launch_select_f32(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int sel, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
@@ -187,7 +187,19 @@ int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int
 {
   if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, fl_theta_in, fl_theta_out,
+  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, 0, fl_theta_in, fl_theta_out,
+                                   fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                               const int32_t* fl_grad, uint32_t lr_q16, uint32_t wd_q16, uint64_t* vmax_out,
+                               uint32_t* status, void* stream)
+{
+  if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
+  if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
+  if (!L->all_src) return LPK_ERR_INVALID_ARG;
+  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, 1, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
@@ -241,6 +253,6 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
   return bw;
 }
 
-int lpk_version(void) { return 102; }
+int lpk_version(void) { return 103; }
 
 }  // extern "C"

@@ -108,34 +108,6 @@ template <int WT, int WM> struct MGroup {
   v4i th[WT / 8], c[WT / 8], m[WM / 8], g[2];
 };
 
-template <int W> __device__ __forceinline__ void load16(v4i (&dst)[W / 8], const void* base, uint64_t e)
-{
-  if (W == 8) dst[0] = ld_stream((const v4i*)((const int8_t*)base + e));
-  else { dst[0] = ld_stream((const v4i*)((const int16_t*)base + e)); dst[W / 8 - 1] = ld_stream((const v4i*)((const int16_t*)base + e + 8)); }
-}
-template <int W> __device__ __forceinline__ int elem16(const v4i (&src)[W / 8], int k)        // k-th of 16 elements
-{
-  if (W == 8) return sx8(src[0][k >> 2], k & 3);
-  return sx16(src[(W / 8 - 1) * (k >> 3)][(k >> 1) & 3], k & 1);
-}
-template <int W> __device__ __forceinline__ void store16(void* base, uint64_t e, const int (&val)[16])
-{
-  if (W == 8) {
-    v4i o;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) o[w] = pack4x8(val[4 * w], val[4 * w + 1], val[4 * w + 2], val[4 * w + 3]);
-    st_stream((v4i*)((int8_t*)base + e), o);
-  } else {
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      v4i o;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) o[w] = pack2x16(val[8 * q + 2 * w], val[8 * q + 2 * w + 1]);
-      st_stream((v4i*)((int16_t*)base + e + 8 * q), o);
-    }
-  }
-}
-
 template <int WT, int WM, bool DECAY, bool K1ZERO>
 __device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<WT, WM>& G, const TensorDev& T, uint64_t e, MaxTrack& mt)
 {

@@ -88,6 +88,35 @@ __device__ __forceinline__ int pack2x16(int a, int b)
   return (int)__builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x05040100u);
 }
 
+// 16 consecutive W-bit elements of one lane: load (one or two dwordx4), pick the k-th, pack and store.
+template <int W> __device__ __forceinline__ void load16(v4i (&dst)[W / 8], const void* base, uint64_t e)
+{
+  if (W == 8) dst[0] = ld_stream((const v4i*)((const int8_t*)base + e));
+  else { dst[0] = ld_stream((const v4i*)((const int16_t*)base + e)); dst[W / 8 - 1] = ld_stream((const v4i*)((const int16_t*)base + e + 8)); }
+}
+template <int W> __device__ __forceinline__ int elem16(const v4i (&src)[W / 8], int k)        // k-th of 16 elements
+{
+  if (W == 8) return sx8(src[0][k >> 2], k & 3);
+  return sx16(src[(W / 8 - 1) * (k >> 3)][(k >> 1) & 3], k & 1);
+}
+template <int W> __device__ __forceinline__ void store16(void* base, uint64_t e, const int (&val)[16])
+{
+  if (W == 8) {
+    v4i o;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) o[w] = pack4x8(val[4 * w], val[4 * w + 1], val[4 * w + 2], val[4 * w + 3]);
+    st_stream((v4i*)((int8_t*)base + e), o);
+  } else {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      v4i o;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) o[w] = pack2x16(val[8 * q + 2 * w], val[8 * q + 2 * w + 1]);
+      st_stream((v4i*)((int16_t*)base + e + 8 * q), o);
+    }
+  }
+}
+
 // RNE(y / 2^b) for a wave-uniform 0 <= b <= 30 without a branch: `half_m1` = 2^(b-1) - 1 (0 when b == 0),
 // `nz` = 1 when b > 0 else 0 (a zero-width bit-field extract yields 0, so b == 0 returns y itself).
 // The caller has shown |y| + 2^(b-1) < 2^31.

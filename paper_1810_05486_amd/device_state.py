@@ -147,6 +147,18 @@ class DeviceState:
                                self.fl_mom_next, self.fl_mom_spare, self.status)
         self.fl_mom, self.fl_mom_next, self.fl_mom_spare = self.fl_mom_next, self.fl_mom_spare, self.fl_mom
 
+    def step_fused(self, step_idx, k=0):
+        """The whole path with quantization fused into the update: max-abs fraclen selection, then one pass that
+        reads the fp32 gradients directly (the int16 gradient arena is not touched)."""
+        L = self.lists[k]
+        lpk.lpk_select_fraclen(L, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, self.fl_grad, self.fl_grad, self.status)
+        lpk.lpk_kahan_sgd_step_f32grad(L, self.fl_theta, self.fl_next, self.fl_grad, self.cfg.lr_q16(step_idx),
+                                       self.cfg.wd_q16, self.vmax, self.status)
+        if self.cfg.reselect:
+            lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_THETA, self.vmax, self.fl_theta,
+                                   self.fl_next, self.fl_spare, self.status)
+            self.fl_theta, self.fl_next, self.fl_spare = self.fl_next, self.fl_spare, self.fl_theta
+
     def step(self, step_idx, k=0, mu_q16=None):
         """One pass of the whole hot path over gradients already resident in source arena k."""
         self.quantize_grads(k)

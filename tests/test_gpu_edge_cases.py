@@ -282,3 +282,34 @@ def test_host_side_argument_errors_with_a_live_list():
     assert L.lpk_select_fraclen(tl.handle, lpk.LPK_VMAX_U64, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_tensor_list_size(tl.handle) == 1 and L.lpk_tensor_list_tiles(tl.handle) == 1
     tl.destroy()
+
+
+def test_fused_step_with_special_gradient_values():
+    """NaN / Inf / subnormal / huge fp32 gradients through the fused call: same theta, comp, vmax and status as
+    quantizing first (oracle), for the vector path and for a misaligned tensor."""
+    say("fused step, special fp32 values")
+    rng = np.random.default_rng(12)
+    f = np.float32
+    for mis in (0, 1):
+        n = 3 * 4096 + 9
+        x = (rng.standard_normal(n) * 1e-3).astype(f)
+        x[5], x[77], x[4096], x[4097], x[9000], x[n - 1] = np.nan, np.inf, -np.inf, 1e-45, 3e38, -0.0
+        theta = rng.integers(-128, 128, size=n).astype(np.int8); comp = rng.integers(-64, 64, size=n).astype(np.int8)
+        bt = torch.zeros(n + 64, dtype=torch.int8, device=DEV); dt = bt[mis:mis + n]; dt.copy_(torch.from_numpy(theta))
+        bc = torch.zeros(n + 64, dtype=torch.int8, device=DEV); dc = bc[mis:mis + n]; dc.copy_(torch.from_numpy(comp))
+        dg = torch.zeros(n, dtype=torch.int16, device=DEV)
+        dx = torch.from_numpy(x).to(DEV)
+        tl = lpk.TensorList([lpk.make_desc(dt, dc, dg, dx)])
+        i32 = dict(dtype=torch.int32, device=DEV)
+        for fl_g in (22, -64, 10):
+            fl_t, fl_gd = torch.tensor([7], **i32), torch.tensor([fl_g], **i32)
+            vmax = torch.zeros(1, dtype=torch.int64, device=DEV); status = torch.zeros(1, dtype=torch.int32, device=DEV)
+            lpk.lpk_kahan_sgd_step_f32grad(tl, fl_t, fl_t, fl_gd, 655, 0, vmax, status)
+            torch.cuda.synchronize()
+            st = ref.new_status()
+            g = ref.quantize(x, 16, fl_g, st)
+            wv = ref.kahan_sgd_step(theta, comp, g, 7, 7, 7, fl_g, 655, 0, st)
+            assert np.array_equal(dt.cpu().numpy(), theta) and np.array_equal(dc.cpu().numpy(), comp), (mis, fl_g)
+            assert int(vmax.item()) == wv and int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0]) == ref.STATUS_NONFINITE
+        assert int(dg.count_nonzero().item()) == 0
+        tl.destroy()

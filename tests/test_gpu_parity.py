@@ -42,10 +42,10 @@ def compare(dev, host, what, check_vmax=True):
             assert bad == 0, (what, "comp", t, bad)
 
 
-def run_config(cfg, step_ids, compare_every=1, kahan=True, always=()):
+def run_config(cfg, step_ids, compare_every=1, kahan=True, always=(), comp_bits=None, fused=False):
     from paper_1810_05486_amd.device_state import DeviceState
-    dev = DeviceState(cfg, kahan=kahan)
-    host = OracleState(cfg, kahan=kahan)
+    dev = DeviceState(cfg, kahan=kahan, comp_bits=comp_bits)
+    host = OracleState(cfg, kahan=kahan, comp_bits=comp_bits)
     views = dev.host_src_views()
     theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
     dev.upload_src()
@@ -55,7 +55,10 @@ def run_config(cfg, step_ids, compare_every=1, kahan=True, always=()):
     for i, s in enumerate(step_ids):
         grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
         dev.upload_src()
-        dev.step(s)
+        if fused:
+            dev.step_fused(s)
+        else:
+            dev.step(s)
         host.step(s, grads)
         if (i + 1) % compare_every == 0 or i == len(step_ids) - 1 or i in always:
             compare(dev, host, "config %d step %d" % (cfg.id, s))
@@ -63,6 +66,8 @@ def run_config(cfg, step_ids, compare_every=1, kahan=True, always=()):
             compare_scalars(dev, host, "config %d step %d" % (cfg.id, s))
         if (i + 1) % 25 == 0:
             say("  config %d: %d/%d steps bit-exact so far" % (cfg.id, i + 1, len(step_ids)))
+    if fused:                                   # the fused call never writes the int16 gradient arena
+        assert int(dev.arena_grad.count_nonzero().item()) == 0
     dev.close()
     return host
 
@@ -112,3 +117,28 @@ def test_config5_full_size_in_bench_launch_configuration():
         run_config(workloads.config(5), range(50), compare_every=50, always=(0, 1))
     else:
         run_config(workloads.config(5), range(2))
+
+
+def test_fused_fp32_gradient_step_equals_quantize_then_step():
+    """lpk_kahan_sgd_step_f32grad against the oracle's quantize + update, on every kind of workload."""
+    say("fused fp32-gradient update: config 1")
+    run_config(workloads.config(1), range(40), fused=True)
+    say("fused fp32-gradient update: config 2 (int16, grid moves)")
+    run_config(workloads.config(2), range(60), fused=True)
+    say("fused fp32-gradient update: config 4 (mixed widths, decay)")
+    run_config(workloads.config(4), range(4), fused=True)
+    say("fused fp32-gradient update: config 5 reduced")
+    run_config(workloads.config(5, big_elems=(1 << 23) + 37, n_tiny=300), range(4), fused=True)
+    say("fused fp32-gradient update: without the accumulator")
+    run_config(workloads.config(1), range(10), fused=True, kahan=False)
+
+
+def test_int8_theta_with_int16_accumulator():
+    """The paper's 22-bit example (Section 2): 8-bit parameter, 16-bit accumulator, no overlapping bit (d = 15)."""
+    say("int8 theta + int16 comp: config 3 shapes")
+    cfg = workloads.config(3)
+    run_config(cfg, [0, 1, 2, 300, 600], comp_bits=[16] * cfg.n_tensors)
+    say("int8 theta + int16 comp: config 5 reduced, plain and fused")
+    cfg = workloads.config(5, big_elems=(1 << 22) + 5, n_tiny=100)
+    run_config(cfg, range(4), comp_bits=[16] * cfg.n_tensors)
+    run_config(cfg, range(4), comp_bits=[16] * cfg.n_tensors, fused=True)
