@@ -63,6 +63,8 @@ def main():
     ap.add_argument("--big-elems", type=int, default=1 << 30, help="size of config 5's large tensor")
     ap.add_argument("--momentum-bits", type=int, default=0, choices=[0, 8, 16],
                     help="time the momentum variant of the update (velocity of this width, mu = 0.9) instead of plain SGD")
+    ap.add_argument("--comp-bits", type=int, default=0, choices=[0, 8, 16],
+                    help="width of the accumulator when it differs from theta's (16 = the paper's 8+16 -> 22-bit example)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-gib", type=float, default=2.0,
                     help="size of the plain-copy yardstick (lpk_stream_copy), 0 = skip")
@@ -75,6 +77,7 @@ def main():
     import torch
     from paper_1810_05486_amd import workloads
     from paper_1810_05486_amd.device_state import DeviceState
+    from paper_1810_05486_amd import binding as lpk
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the hot path has no CPU fallback.")
@@ -87,7 +90,8 @@ def main():
     log("workload %d: %s; %d tensors, %d parameters" % (cfg.id, cfg.name, cfg.n_tensors, cfg.n_params))
     mom_bits = [args.momentum_bits] * cfg.n_tensors if args.momentum_bits else None
     mu_q16 = 58982 if args.momentum_bits else None
-    dev = DeviceState(cfg, n_src=n_src, mom_bits=mom_bits)
+    comp_bits = [args.comp_bits] * cfg.n_tensors if args.comp_bits else None
+    dev = DeviceState(cfg, n_src=n_src, mom_bits=mom_bits, comp_bits=comp_bits)
     views = dev.host_src_views()
 
     t0 = time.perf_counter()
@@ -116,7 +120,6 @@ def main():
         s = args.warmup + i
         k = s % n_src
         ev[i][0].record()
-        from paper_1810_05486_amd import binding as lpk
         L = dev.lists[k]
         lpk.lpk_select_fraclen(L, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, dev.fl_grad, dev.fl_grad, dev.status)
         ev[i][1].record()
@@ -130,6 +133,33 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    # the same whole path with quantization fused into the update (select + lpk_kahan_sgd_step_f32grad)
+    fused = None
+    if mu_q16 is None:
+        fev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+        for s in range(2):
+            dev.step_fused(s, k=s % n_src)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(K):
+            s = args.warmup + K + i
+            k = s % n_src
+            fev[i][0].record()
+            lpk.lpk_select_fraclen(dev.lists[k], lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, dev.fl_grad, dev.fl_grad, dev.status)
+            fev[i][1].record()
+            lpk.lpk_kahan_sgd_step_f32grad(dev.lists[k], dev.fl_theta, dev.fl_next, dev.fl_grad, cfg.lr_q16(s), cfg.wd_q16,
+                                           dev.vmax, dev.status)
+            fev[i][2].record()
+        torch.cuda.synchronize()
+        fwall = time.perf_counter() - t1
+        f_upd_ms = sum(e[1].elapsed_time(e[2]) for e in fev) / K
+        fbytes = sum(n * (4 * (b // 8 + (cb // 8)) // 2 + 4) for n, b, cb in zip(cfg.sizes, cfg.bits, dev.comp_bits))
+        fused = {"value": cfg.n_params / (fwall / K) / 1e9, "unit": "Gparam/s", "ms_per_step": fwall * 1e3 / K,
+                 "stage_ms": {"select_fraclen": sum(e[0].elapsed_time(e[1]) for e in fev) / K, "kahan_sgd_step_f32grad": f_upd_ms},
+                 "roofline": {"bound": "hbm", "kernel": "kahan_step_kernel<fp32 grad>", "achieved": fbytes / (f_upd_ms * 1e-3) / 1e9,
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fbytes / (f_upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "bytes_per_launch": fbytes}}
+
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
     qnt_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / K
     upd_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / K
@@ -141,7 +171,6 @@ def main():
         nb = int(args.copy_gib * (1 << 30)) // 16 * 16
         a = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
         b = torch.zeros(nb, dtype=torch.uint8, device="cuda:0")
-        from paper_1810_05486_amd import binding as lpk
         lpk.lpk_stream_copy(a, b, nb)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = 10
@@ -154,7 +183,8 @@ def main():
         copy = {"bytes_read": nb, "bytes_written": nb, "ms": cms, "GB/s": 2 * nb / (cms * 1e-3) / 1e9}
         del a, b
 
-    upd_bytes = cfg.bytes_per_step() + (2 * (args.momentum_bits // 8) * cfg.n_params if args.momentum_bits else 0)
+    upd_bytes = sum(n * (2 * (b // 8) + 2 * (cb // 8) + 2) for n, b, cb in zip(cfg.sizes, cfg.bits, dev.comp_bits))
+    upd_bytes += 2 * (args.momentum_bits // 8) * cfg.n_params if args.momentum_bits else 0
     upd_kernel = "momentum_step_kernel" if args.momentum_bits else "kahan_step_kernel"
     achieved = upd_bytes / (upd_ms * 1e-3) / 1e9
     traffic = None
@@ -173,7 +203,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8/int16 fixed point (int32/int64 accumulate)", "data": "synthetic",
         "config": {"workload": "config %d: %s%s" % (cfg.id, cfg.name, ", momentum 0.9 with int%d velocity" % args.momentum_bits
-                                                    if args.momentum_bits else ""), "n_tensors": cfg.n_tensors,
+                                                    if args.momentum_bits else "") + (", int%d accumulator" % args.comp_bits if args.comp_bits else ""),
+                   "n_tensors": cfg.n_tensors,
                    "n_params": cfg.n_params, "lr_q16": cfg.lr_q16(0), "wd_q16": cfg.wd_q16,
                    "grad_draws_cycled": n_src},
         "update_only": {"value": cfg.n_params / (upd_ms * 1e-3) / 1e9, "unit": "Gparam/s", "ms": upd_ms},
@@ -184,6 +215,7 @@ def main():
         "other_kernels": {
             "maxabs_f32_kernel": {"GB/s": 4 * cfg.n_params / (sel_ms * 1e-3) / 1e9, "bytes_per_launch": 4 * cfg.n_params},
             "quantize_kernel": {"GB/s": 6 * cfg.n_params / (qnt_ms * 1e-3) / 1e9, "bytes_per_launch": 6 * cfg.n_params}},
+        "fused_path": fused,
         "stream_copy_yardstick": copy,
         "device_status_word": status,
     }

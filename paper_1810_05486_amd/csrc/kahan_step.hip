@@ -168,7 +168,7 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 {
   Track tr{0, 0, ab_max};
   constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : 8);     // VGPRs of one group
-  constexpr int kP = kRegs <= 16 ? 4 : 2;                               // groups in flight per lane
+  constexpr int kP = kRegs <= 16 ? 4 : LPK_KP_WIDE;                     // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
@@ -239,6 +239,110 @@ __device__ __forceinline__ uint64_t run_fast8(const StepParams& p, const TensorD
   return track_max(tr);
 }
 
+// ---------------------------------------------------------------- E consecutive elements per lane
+//
+// How many consecutive elements one lane owns decides which of its loads are fully coalesced.  With fp32
+// gradients, 16 per lane would mean 64 contiguous bytes of gradients per lane (four loads whose lanes sit 64
+// bytes apart), which the memory pipeline handles far worse than HBM itself; fewer elements per lane trade
+// wider gradient accesses for narrower theta/comp accesses.  This path is generic in E (4, 8 or 16).
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+template <int N> struct DW { int d[N]; };                 // N = 1, 2 or 4 dwords moved by one access
+
+template <int N> __device__ __forceinline__ DW<N> ld_dw(const void* p)
+{
+  DW<N> r;
+  if constexpr (N == 1) { r.d[0] = ld_stream((const int*)p); }
+  else if constexpr (N == 2) { v2i v = ld_stream((const v2i*)p); r.d[0] = v[0]; r.d[1] = v[1]; }
+  else { v4i v = ld_stream((const v4i*)p); r.d[0] = v[0]; r.d[1] = v[1]; r.d[2] = v[2]; r.d[3] = v[3]; }
+  return r;
+}
+template <int N> __device__ __forceinline__ void st_dw(void* p, const DW<N>& r)
+{
+  if constexpr (N == 1) { st_stream((int*)p, r.d[0]); }
+  else if constexpr (N == 2) { v2i v; v[0] = r.d[0]; v[1] = r.d[1]; st_stream((v2i*)p, v); }
+  else { v4i v; v[0] = r.d[0]; v[1] = r.d[1]; v[2] = r.d[2]; v[3] = r.d[3]; st_stream((v4i*)p, v); }
+}
+template <int W, int N> __device__ __forceinline__ int elem_dw(const DW<N>& r, int k)
+{
+  if constexpr (W == 8) return sx8(r.d[k >> 2], k & 3); else return sx16(r.d[k >> 1], k & 1);
+}
+template <int W, int E> __device__ __forceinline__ DW<E * W / 32> pack_dw(const int (&val)[E])
+{
+  DW<E * W / 32> r;
+#pragma unroll
+  for (int w = 0; w < E * W / 32; ++w) {
+    if constexpr (W == 8) r.d[w] = pack4x8(val[4 * w], val[4 * w + 1], val[4 * w + 2], val[4 * w + 3]);
+    else                  r.d[w] = pack2x16(val[2 * w], val[2 * w + 1]);
+  }
+  return r;
+}
+
+template <int E, int WT, int WC, int GS> struct GroupE {
+  static constexpr int kG = GS == kGradF32 ? E / 4 : (E >= 8 ? E / 8 : 1);      // gradient accesses
+  static constexpr int kGN = GS == kGradF32 ? 4 : (E >= 8 ? 4 : 2);            // dwords per gradient access
+  DW<E * WT / 32> th;
+  DW<E * WC / 32> c;
+  DW<kGN> g[kG];
+};
+
+template <int E, int WT, int WC, int GS>
+__device__ __forceinline__ void load_group_e(GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e)
+{
+  using GT = GroupE<E, WT, WC, GS>;
+  G.th = ld_dw<E * WT / 32>((const int8_t*)T.theta + e * (WT / 8));
+  G.c  = ld_dw<E * WC / 32>((const int8_t*)T.comp + e * (WC / 8));
+#pragma unroll
+  for (int j = 0; j < GT::kG; ++j) {
+    if constexpr (GS == kGradF32) G.g[j] = ld_dw<4>((const float*)T.src + e + 4 * j);
+    else                          G.g[j] = ld_dw<GT::kGN>((const int16_t*)T.grad + e + 8 * j);
+  }
+}
+
+template <int E, int WT, int WC, int GS, bool DECAY>
+__device__ __forceinline__ void compute_store_group_e(const StepParams& p, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
+{
+  int tn[E], cn[E];
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    float gf;
+    if constexpr (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[k >> 2].d[k & 3]), tr.ab);
+    else                          gf = (float)sx16(G.g[k >> 3].d[(k >> 1) & 3], k & 1);
+    update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
+  }
+  st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
+  st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
+}
+
+template <int E, int KP, int WT, int WC, int GS, bool DECAY>
+__device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
+{
+  Track tr{0, 0, ab_max};
+  const uint32_t ngroups = cnt / E;
+  uint32_t gi = lane;
+  for (; gi + (KP - 1) * kWave < ngroups; gi += KP * kWave) {
+    GroupE<E, WT, WC, GS> G[KP];
+#pragma unroll
+    for (int ps = 0; ps < KP; ++ps) load_group_e(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
+#pragma unroll
+    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
+  }
+  for (; gi < ngroups; gi += kWave) {
+    GroupE<E, WT, WC, GS> G;
+    const uint64_t e = off + (uint64_t)gi * E;
+    load_group_e(G, T, e);
+    compute_store_group_e<E, WT, WC, GS, DECAY>(p, G, T, e, tr);
+  }
+  ab_max = tr.ab;
+  uint64_t vm = track_max(tr);
+  const uint32_t tail = cnt - ngroups * E;                // < E elements
+  if (tail) {
+    uint64_t t2 = tile_generic<GS>(p, T, off + (uint64_t)ngroups * E, tail, lane, ab_max);
+    vm = t2 > vm ? t2 : vm;
+  }
+  return vm;
+}
+
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
 
 template <int GS>
@@ -297,6 +401,13 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
 template <int WT, int WC, int GS>
 __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
 {
+  if (GS == kGradF32)
+    return p.lrwd ? tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, true>(p, T, off, cnt, lane, ab)
+                  : tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, false>(p, T, off, cnt, lane, ab);
+#if LPK_I16_E != 16
+  return p.lrwd ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true>(p, T, off, cnt, lane, ab)
+                : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false>(p, T, off, cnt, lane, ab);
+#endif
   return p.lrwd ? tile_fast<WT, WC, GS, true>(p, T, off, cnt, lane, ab) : tile_fast<WT, WC, GS, false>(p, T, off, cnt, lane, ab);
 }
 
@@ -333,7 +444,7 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     uint64_t vm = 0;
     if (p.path == 2) {
       if (p.wt == 8 && p.wc == 8) {
-        if (GS == kGradI16 && cnt == (uint32_t)kTileElems) {
+        if (GS == kGradI16 && LPK_I16_E == 16 && cnt == (uint32_t)kTileElems) {
           // Run of full int8 tiles of this tensor, software-pipelined: the loads of the wave's next tile are in
           // flight while the current one is computed and stored, so the memory pipe never waits for the ALU.
           vm = p.lrwd ? run_fast8<GS, true>(p, T, tiles, n_tiles, nw, ti, off, cur, lane, ab_max)

@@ -11,6 +11,21 @@
 #ifndef LPK_PASSES
 #define LPK_PASSES 4          // 1024-element passes per wave tile, all loads of a tile in flight together
 #endif
+#ifndef LPK_KP_WIDE
+#define LPK_KP_WIDE 2         // groups in flight per lane when one group needs more than 16 VGPRs
+#endif
+#ifndef LPK_F32_E
+#define LPK_F32_E 8           // consecutive elements per lane in the fp32-gradient update
+#endif
+#ifndef LPK_F32_GROUPS
+#define LPK_F32_GROUPS 4      // such groups in flight per lane
+#endif
+#ifndef LPK_I16_E
+#define LPK_I16_E 16          // consecutive elements per lane with int16 gradients (16 = the pipelined dwordx4 path)
+#endif
+#ifndef LPK_I16_GROUPS
+#define LPK_I16_GROUPS 4
+#endif
 #ifndef LPK_NT_LOAD
 #define LPK_NT_LOAD 1         // non-temporal hint on streaming loads
 #endif
