@@ -5,9 +5,10 @@
 // w, w + W, w + 2W, ... of the tile table, so at any moment the grid streams
 // one contiguous window of the parameter set.  A tile is 4096 elements of one
 // tensor; a lane handles 16 consecutive elements per pass (one dwordx4 of int8
-// theta, one of comp, two of int16 grad), several passes in flight together.
-// Runs of full int8 tiles are software-pipelined: the next tile's loads are
-// issued before the current tile is computed and stored.
+// theta, one of comp, two of int16 grad), four passes in flight together.
+// One workgroup of four waves per CU (one wave per SIMD): with the 2:1
+// read/write byte mix of this update, HBM delivers most when few, large
+// bursts are in flight; more resident waves only lengthen the DRAM queues.
 //
 // Gradient source: the int16 gradients written by the quantization kernel, or
 // (second kernel instance) the fp32 gradients themselves, quantized in
@@ -141,8 +142,29 @@ __device__ __forceinline__ void load_group(Group<WT, WC, GS>& G, const TensorDev
   }
 }
 
+// The packed results of one group, kept in registers until they are stored.
+template <int WT, int WC> struct GroupOut { v4i th[WT / 8], c[WC / 8]; };
+
+template <int W> __device__ __forceinline__ void pack16(v4i (&dst)[W / 8], const int (&val)[16])
+{
+  if (W == 8) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) dst[0][w] = pack4x8(val[4 * w], val[4 * w + 1], val[4 * w + 2], val[4 * w + 3]);
+  } else {
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) dst[(W / 8 - 1) * q][w] = pack2x16(val[8 * q + 2 * w], val[8 * q + 2 * w + 1]);
+  }
+}
+template <int W> __device__ __forceinline__ void store16v(void* base, uint64_t e, const v4i (&src)[W / 8])
+{
+  if (W == 8) st_stream((v4i*)((int8_t*)base + e), src[0]);
+  else { st_stream((v4i*)((int16_t*)base + e), src[0]); st_stream((v4i*)((int16_t*)base + e + 8), src[W / 8 - 1]); }
+}
+
 template <int WT, int WC, int GS, bool DECAY>
-__device__ __forceinline__ void compute_store_group(const StepParams& p, const Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
+__device__ __forceinline__ void compute_group(const StepParams& p, const Group<WT, WC, GS>& G, GroupOut<WT, WC>& O, Track& tr)
 {
   int tn[16], cn[16];
 #pragma unroll
@@ -152,8 +174,23 @@ __device__ __forceinline__ void compute_store_group(const StepParams& p, const G
     else                gf = (float)sx16(G.g[(k >> 3) & 1][(k >> 1) & 3], k & 1);
     update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
-  store16<WT>(T.theta, e, tn);
-  store16<WC>(T.comp, e, cn);
+  pack16<WT>(O.th, tn);
+  pack16<WC>(O.c, cn);
+}
+
+template <int WT, int WC>
+__device__ __forceinline__ void store_group(const GroupOut<WT, WC>& O, const TensorDev& T, uint64_t e)
+{
+  store16v<WT>(T.theta, e, O.th);
+  store16v<WC>(T.comp, e, O.c);
+}
+
+template <int WT, int WC, int GS, bool DECAY>
+__device__ __forceinline__ void compute_store_group(const StepParams& p, const Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
+{
+  GroupOut<WT, WC> O;
+  compute_group<WT, WC, GS, DECAY>(p, G, O, tr);
+  store_group<WT, WC>(O, T, e);
 }
 
 __device__ __forceinline__ uint64_t track_max(const Track& tr)
@@ -168,7 +205,7 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 {
   Track tr{0, 0, ab_max};
   constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : 8);     // VGPRs of one group
-  constexpr int kP = kRegs <= 16 ? 4 : LPK_KP_WIDE;                     // groups in flight per lane
+  constexpr int kP = kRegs <= 16 ? LPK_I16_GROUPS : LPK_KP_WIDE;                     // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
@@ -192,51 +229,6 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
     vm = t2 > vm ? t2 : vm;
   }
   return vm;
-}
-
-// One pipeline stage: start the loads of the wave's next tile into `nxt` if that tile continues the run
-// (same tensor, full), then compute and store `cur`.  Returns whether `nxt` was filled; ti/off advance to it.
-template <int GS, bool DECAY>
-__device__ __forceinline__ bool stage_fast8(const StepParams& p, const TensorDev& T, const Tile* __restrict__ tiles,
-                                            uint32_t n_tiles, uint32_t nw, uint32_t& ti, uint64_t& off, int tensor, int lane,
-                                            Group<8, 8, GS> (&cur)[kPasses], Group<8, 8, GS> (&nxt)[kPasses], Track& tr)
-{
-  const uint32_t tn = ti + nw;
-  bool more = false;
-  uint64_t noff = 0;
-  if (tn < n_tiles) {
-    int nt; uint32_t ncnt;
-    read_tile(tiles, tn, nt, ncnt, noff);
-    more = nt == tensor && ncnt == (uint32_t)kTileElems;
-  }
-  if (more) {
-#pragma unroll
-    for (int ps = 0; ps < kPasses; ++ps) load_group(nxt[ps], T, noff + (uint64_t)(ps * kWave + lane) * kGroup);
-  }
-#pragma unroll
-  for (int ps = 0; ps < kPasses; ++ps)
-    compute_store_group<8, 8, GS, DECAY>(p, cur[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup, tr);
-  if (more) { ti = tn; off = noff; }
-  return more;
-}
-
-// Processes the full tile at (ti, off) and every following tile of this wave that continues the run; on
-// return ti is the last tile consumed (the caller's loop increment moves past it).
-template <int GS, bool DECAY>
-__device__ __forceinline__ uint64_t run_fast8(const StepParams& p, const TensorDev& T, const Tile* __restrict__ tiles,
-                                              uint32_t n_tiles, uint32_t nw, uint32_t& ti, uint64_t off, int tensor, int lane,
-                                              uint32_t& ab_max)
-{
-  Track tr{0, 0, ab_max};
-  Group<8, 8, GS> A[kPasses], B[kPasses];
-#pragma unroll
-  for (int ps = 0; ps < kPasses; ++ps) load_group(A[ps], T, off + (uint64_t)(ps * kWave + lane) * kGroup);
-  while (true) {
-    if (!stage_fast8<GS, DECAY>(p, T, tiles, n_tiles, nw, ti, off, tensor, lane, A, B, tr)) break;
-    if (!stage_fast8<GS, DECAY>(p, T, tiles, n_tiles, nw, ti, off, tensor, lane, B, A, tr)) break;
-  }
-  ab_max = tr.ab;
-  return track_max(tr);
 }
 
 // ---------------------------------------------------------------- E consecutive elements per lane
@@ -431,7 +423,7 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
   StepParams p; p.path = 0;
   TensorDev T;
 
-  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {      // ti may also be advanced inside by a pipelined run
+  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
     int t; uint32_t cnt; uint64_t off;
     read_tile(tiles, ti, t, cnt, off);
     if (t != cur) {
@@ -443,14 +435,7 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && p.wc == 8) {
-        if (GS == kGradI16 && LPK_I16_E == 16 && cnt == (uint32_t)kTileElems) {
-          // Run of full int8 tiles of this tensor, software-pipelined: the loads of the wave's next tile are in
-          // flight while the current one is computed and stored, so the memory pipe never waits for the ALU.
-          vm = p.lrwd ? run_fast8<GS, true>(p, T, tiles, n_tiles, nw, ti, off, cur, lane, ab_max)
-                      : run_fast8<GS, false>(p, T, tiles, n_tiles, nw, ti, off, cur, lane, ab_max);
-        } else vm = tile_fast_decay<8, 8, GS>(p, T, off, cnt, lane, ab_max);
-      }
+      if (p.wt == 8 && p.wc == 8) vm = tile_fast_decay<8, 8, GS>(p, T, off, cnt, lane, ab_max);
       else if (p.wt == 16) vm = tile_fast_decay<16, 16, GS>(p, T, off, cnt, lane, ab_max);
       else                 vm = tile_fast_decay<8, 16, GS>(p, T, off, cnt, lane, ab_max);
     } else if (p.path == 1) {

@@ -26,6 +26,9 @@
 #ifndef LPK_I16_GROUPS
 #define LPK_I16_GROUPS 4
 #endif
+#ifndef LPK_WAVES_PER_BLOCK
+#define LPK_WAVES_PER_BLOCK 4 // wavefronts per workgroup of the persistent kernels
+#endif
 #ifndef LPK_NT_LOAD
 #define LPK_NT_LOAD 1         // non-temporal hint on streaming loads
 #endif
@@ -36,7 +39,7 @@
 namespace lpk {
 
 constexpr int kWave           = 64;     // CDNA wavefront
-constexpr int kWavesPerBlock  = 4;
+constexpr int kWavesPerBlock  = LPK_WAVES_PER_BLOCK;
 constexpr int kBlock          = kWave * kWavesPerBlock;
 constexpr int kGroup          = 16;     // elements one lane handles per pass (one dwordx4 of int8)
 constexpr int kPassElems      = kWave * kGroup;          // 1024 elements per wave pass

@@ -32,7 +32,8 @@ struct lpk_tensor_list {
   uint32_t   n_tensors = 0;
   uint32_t   n_tiles   = 0;
   int        device    = 0;
-  uint32_t   grid      = 0;        // blocks of the persistent launches
+  uint32_t   grid      = 0;        // blocks of the persistent read-mostly launches (max-abs, quantize)
+  uint32_t   grid_step = 0;        // blocks of the persistent update launches
   bool       all_src   = false;    // every non-empty tensor has an fp32 source
   bool       all_mom   = false;    // every non-empty tensor has a velocity buffer
   TensorDev* d_tensors = nullptr;
@@ -110,13 +111,16 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   hipDeviceProp_t prop;
   bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
   if (ok) {
-    // Persistent grid: enough resident waves per CU to cover HBM latency, never more blocks than tile quads.
-    const uint32_t per_cu = env_u32("LPK_BLOCKS_PER_CU", 2);
-    uint32_t grid = (uint32_t)prop.multiProcessorCount * per_cu;
+    // Persistent grids, never more blocks than tile quads.  Measured on MI355X: the read-modify-write update
+    // kernels stream fastest with ONE workgroup (one wave per SIMD) per CU, the read-mostly ones with two.
     const uint32_t need = (L->n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (grid > need) grid = need;
-    if (grid == 0) grid = 1;
-    L->grid = grid;
+    auto clampg = [&](uint32_t per_cu) {
+      uint32_t g = (uint32_t)prop.multiProcessorCount * per_cu;
+      if (g > need) g = need;
+      return g ? g : 1u;
+    };
+    L->grid = clampg(env_u32("LPK_BLOCKS_PER_CU", 2));
+    L->grid_step = clampg(env_u32("LPK_STEP_BLOCKS_PER_CU", 1));
     ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
          hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * n_tensors) == hipSuccess &&
          (tiles.empty() || hipMalloc((void**)&L->d_tiles, sizeof(Tile) * tiles.size()) == hipSuccess);
@@ -187,7 +191,7 @@ int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int
 {
   if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, 0, fl_theta_in, fl_theta_out,
+  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_step, 0, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
@@ -199,7 +203,7 @@ int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, c
   if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   if (!L->all_src) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, 1, fl_theta_in, fl_theta_out,
+  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_step, 1, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
@@ -212,7 +216,7 @@ int lpk_momentum_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const 
   if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u || mu_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   if (!L->all_mom) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, fl_theta_in, fl_theta_out,
+  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_step, fl_theta_in, fl_theta_out,
                                       fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16, vmax_out, mmax_out, status,
                                       static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
