@@ -29,6 +29,12 @@
 #ifndef LPK_WAVES_PER_BLOCK
 #define LPK_WAVES_PER_BLOCK 4 // wavefronts per workgroup of the persistent kernels
 #endif
+#ifndef LPK_Q_E
+#define LPK_Q_E 4             // consecutive elements per lane in the quantization kernel
+#endif
+#ifndef LPK_Q_GROUPS
+#define LPK_Q_GROUPS 4        // such groups in flight per lane
+#endif
 #ifndef LPK_NT_LOAD
 #define LPK_NT_LOAD 1         // non-temporal hint on streaming loads
 #endif

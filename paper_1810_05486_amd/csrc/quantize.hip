@@ -13,6 +13,7 @@ namespace lpk {
 
 typedef float    v4f __attribute__((ext_vector_type(4)));
 typedef unsigned v2u __attribute__((ext_vector_type(2)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int quant1(float x, float scale, float lo, float hi, bool& nonfinite)
 {
@@ -24,44 +25,48 @@ __device__ __forceinline__ int quant1(float x, float scale, float lo, float hi, 
   return ab > 0x7f800000u ? 0 : q;                     // NaN -> 0
 }
 
-template <int W>
-__device__ __forceinline__ void quant4_store(void* dst, uint64_t e, v4f x, float scale, bool& nf)
-{
-  const float lo = -(float)(1 << (W - 1)), hi = (float)((1 << (W - 1)) - 1);
-  int q0 = quant1(x[0], scale, lo, hi, nf), q1 = quant1(x[1], scale, lo, hi, nf);
-  int q2 = quant1(x[2], scale, lo, hi, nf), q3 = quant1(x[3], scale, lo, hi, nf);
-  if (W == 16) {
-    v2u o;
-    o[0] = (uint32_t)(q0 & 0xffff) | ((uint32_t)q1 << 16);
-    o[1] = (uint32_t)(q2 & 0xffff) | ((uint32_t)q3 << 16);
-    __builtin_nontemporal_store(o, (v2u*)((int16_t*)dst + e));
-  } else {
-    uint32_t o = (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) | ((uint32_t)(q2 & 0xff) << 16) | ((uint32_t)q3 << 24);
-    __builtin_nontemporal_store(o, (uint32_t*)((int8_t*)dst + e));
-  }
-}
-
-template <int W>
+// E = 4 (int16 out: 8-byte store, int8 out: 4-byte store) or E = 8 (int16: 16-byte store, int8: 8-byte store)
+// consecutive elements per lane; KP such groups in flight.
+template <int W, int E, int KP>
 __device__ __forceinline__ void quant_tile(const float* src, void* dst, bool vec, uint64_t off, uint32_t cnt, float scale, int lane, bool& nf)
 {
   const float lo = -(float)(1 << (W - 1)), hi = (float)((1 << (W - 1)) - 1);
   uint32_t done = 0;
   if (vec) {
-    const uint32_t nv = cnt / 4;
-    constexpr int kUnroll = 4;
-    uint32_t j = lane;
-    for (; j + (kUnroll - 1) * kWave < nv; j += kUnroll * kWave) {
-      v4f x[kUnroll];
+    const uint32_t ng = cnt / E;
+    auto convert_store = [&](const v4f (&x)[E / 4], uint64_t e) {
+      int q[E];
 #pragma unroll
-      for (int k = 0; k < kUnroll; ++k) x[k] = __builtin_nontemporal_load((const v4f*)(src + off) + j + k * kWave);
+      for (int k = 0; k < E; ++k) q[k] = quant1(x[k >> 2][k & 3], scale, lo, hi, nf);
+      uint32_t o[E * W / 32];
 #pragma unroll
-      for (int k = 0; k < kUnroll; ++k) quant4_store<W>(dst, off + 4ull * (j + k * kWave), x[k], scale, nf);
+      for (int w = 0; w < E * W / 32; ++w) {
+        if (W == 16) o[w] = (uint32_t)(q[2 * w] & 0xffff) | ((uint32_t)q[2 * w + 1] << 16);
+        else o[w] = (uint32_t)(q[4 * w] & 0xff) | ((uint32_t)(q[4 * w + 1] & 0xff) << 8) | ((uint32_t)(q[4 * w + 2] & 0xff) << 16) | ((uint32_t)q[4 * w + 3] << 24);
+      }
+      char* d = (char*)dst + e * (W / 8);
+      if constexpr (E * W / 32 == 1) __builtin_nontemporal_store(o[0], (LPK_GLOBAL uint32_t*)d);
+      else if constexpr (E * W / 32 == 2) { v2u v; v[0] = o[0]; v[1] = o[1]; __builtin_nontemporal_store(v, (LPK_GLOBAL v2u*)d); }
+      else { v4u v; v[0] = o[0]; v[1] = o[1]; v[2] = o[2]; v[3] = o[3]; __builtin_nontemporal_store(v, (LPK_GLOBAL v4u*)d); }
+    };
+    uint32_t gi = lane;
+    for (; gi + (KP - 1) * kWave < ng; gi += KP * kWave) {
+      v4f x[KP][E / 4];
+#pragma unroll
+      for (int k = 0; k < KP; ++k)
+#pragma unroll
+        for (int j = 0; j < E / 4; ++j)
+          x[k][j] = __builtin_nontemporal_load((const LPK_GLOBAL v4f*)(src + off + (uint64_t)(gi + k * kWave) * E + 4 * j));
+#pragma unroll
+      for (int k = 0; k < KP; ++k) convert_store(x[k], off + (uint64_t)(gi + k * kWave) * E);
     }
-    for (; j < nv; j += kWave) {
-      v4f x = __builtin_nontemporal_load((const v4f*)(src + off) + j);
-      quant4_store<W>(dst, off + 4ull * j, x, scale, nf);
+    for (; gi < ng; gi += kWave) {
+      v4f x[E / 4];
+#pragma unroll
+      for (int j = 0; j < E / 4; ++j) x[j] = __builtin_nontemporal_load((const LPK_GLOBAL v4f*)(src + off + (uint64_t)gi * E + 4 * j));
+      convert_store(x, off + (uint64_t)gi * E);
     }
-    done = nv * 4;
+    done = ng * E;
   }
   for (uint32_t j = done + lane; j < cnt; j += kWave) {
     int q = quant1(src[off + j], scale, lo, hi, nf);
@@ -92,8 +97,8 @@ quantize_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ 
     void* dst = to_theta ? T.theta : T.grad;
     const int W = to_theta ? T.wt : T.wg;
     const bool vec = to_theta ? T.vec_src_theta : T.vec_src_grad;
-    if (W == 16) quant_tile<16>((const float*)T.src, dst, vec, off, cnt, scale, lane, nf);
-    else         quant_tile<8>((const float*)T.src, dst, vec, off, cnt, scale, lane, nf);
+    if (W == 16) quant_tile<16, LPK_Q_E, LPK_Q_GROUPS>((const float*)T.src, dst, vec, off, cnt, scale, lane, nf);
+    else         quant_tile<8, LPK_Q_E, LPK_Q_GROUPS>((const float*)T.src, dst, vec, off, cnt, scale, lane, nf);
   }
   if (__ballot(nf)) bits |= kStatusNonFinite;
   if (status && bits && lane == 0) atomicOr(status, bits);
@@ -109,7 +114,6 @@ hipError_t launch_quantize(const TensorDev* tensors, const Tile* tiles, uint32_t
 
 // Plain streaming copy (16 bytes per lane per access, grid-stride): the yardstick the HBM counters and
 // the update kernel's bandwidth are read against.
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
 __global__ void __launch_bounds__(kBlock) stream_copy_kernel(v4u* __restrict__ dst, const v4u* __restrict__ src, uint64_t n16)
 {
   const uint64_t stride = (uint64_t)gridDim.x * kBlock;
