@@ -61,6 +61,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (5 = the 1 Gi-parameter headline)")
     ap.add_argument("--big-elems", type=int, default=1 << 30, help="size of config 5's large tensor")
+    ap.add_argument("--n-tiny", type=int, default=10000, help="number of 256-element tensors in config 5")
     ap.add_argument("--momentum-bits", type=int, default=0, choices=[0, 8, 16],
                     help="time the momentum variant of the update (velocity of this width, mu = 0.9) instead of plain SGD")
     ap.add_argument("--comp-bits", type=int, default=0, choices=[0, 8, 16],
@@ -83,7 +84,7 @@ def main():
         sys.exit("bench.py: no GPU visible; the hot path has no CPU fallback.")
     torch.cuda.set_device(0)
 
-    cfg = workloads.config(args.config, big_elems=args.big_elems) if args.config == 5 else workloads.config(args.config)
+    cfg = workloads.config(args.config, big_elems=args.big_elems, n_tiny=args.n_tiny) if args.config == 5 else workloads.config(args.config)
     n_src = cfg.grad_cycle or 1
     if not cfg.grad_cycle:
         n_src = 3                                   # timing only: cycle three resident gradient draws

@@ -48,6 +48,13 @@ struct StepParams {
   float    nlr_f;  float magic_f;  int magic_fi;
   double   nlrwd_d; double magic_d; int magic_dlo;
   int      half_m1;         // 2^(d-1) - 1
+  // small-value variant of the fast path (every |intermediate| < 2^22, d <= 8): roundings on the FMA unit
+  int      small;
+  int      bias_i;          // -bits(1.5 * 2^23): takes the FMA's offset out of the step
+  float    inv2d_f;         // 2^-d
+  float    lo_tf, hi_tf;    // 1.5 * 2^23 + rails of theta
+  int      neg2d;           // -2^d
+  int      lo_cb, hi_cb;    // rails of comp minus 2^(22 + d)
 };
 
 // Quantize one fp32 gradient exactly as the quantization kernel does; the result is an integer-valued float.
@@ -123,6 +130,43 @@ __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, 
   cn = min(max(r, p.qmin_c), p.qmax_c);
 }
 
+// The same update when every intermediate is below 2^22 in magnitude and d <= 8 (int8 theta with an int8
+// accumulator): both roundings run on the FMA unit.  The step is the bit pattern of the same FMA as in
+// update_fast minus the bit pattern of its offset (folded into one constant added with comp).  With
+// M = 1.5 * 2^23 (ulp 1), fma(v, 2^-d, M) is M + RNE(v / 2^d) after its single IEEE rounding (v is exact in
+// fp32), clamped as a float between M + qmin and M + qmax.  The low
+// 24 bits of that float are 2^22 + theta', so one 24-bit multiply-add forms v - theta' * 2^d - 2^(22 + d); the
+// accumulator rails are shifted by the same constant, and the low bytes of both results are the bytes to store.
+__device__ __forceinline__ int med3_i32(int x, int lo, int hi)
+{
+  int r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "v"(hi));
+  return r;
+}
+
+__device__ __forceinline__ int mad_i24(int a, int b, int c)          // sext24(a) * sext24(b) + c
+{
+  int r;
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+template <bool DECAY>
+__device__ __forceinline__ void update_small(const StepParams& p, int th, int c, float gf, int& tn, int& cn, Track& tr)
+{
+  int s = __float_as_int(__builtin_fmaf(gf, p.nlr_f, p.magic_f));
+  if (DECAY) {
+    double r = __builtin_fma((double)th, p.nlrwd_d, p.magic_d);
+    s += __double2loint(r) - p.magic_dlo;
+  }
+  const int v = (int)((unsigned)th << p.d) + (c + p.bias_i) + s;
+  tr.vmx = v > tr.vmx ? v : tr.vmx;
+  tr.vmn = v < tr.vmn ? v : tr.vmn;
+  const float q = __builtin_amdgcn_fmed3f(__builtin_fmaf((float)v, p.inv2d_f, 12582912.0f), p.lo_tf, p.hi_tf);
+  tn = __float_as_int(q);
+  cn = med3_i32(mad_i24(tn, p.neg2d, v), p.lo_cb, p.hi_cb);
+}
+
 // 16 consecutive elements of one lane.  WT / WC = widths of theta and comp; GS = gradient source.
 template <int WT, int WC, int GS> struct Group {
   v4i th[WT / 8], c[WC / 8], g[GS == kGradF32 ? 4 : 2];
@@ -163,7 +207,7 @@ template <int W> __device__ __forceinline__ void store16v(void* base, uint64_t e
   else { st_stream((v4i*)((int16_t*)base + e), src[0]); st_stream((v4i*)((int16_t*)base + e + 8), src[W / 8 - 1]); }
 }
 
-template <int WT, int WC, int GS, bool DECAY>
+template <int WT, int WC, int GS, bool DECAY, bool SMALL>
 __device__ __forceinline__ void compute_group(const StepParams& p, const Group<WT, WC, GS>& G, GroupOut<WT, WC>& O, Track& tr)
 {
   int tn[16], cn[16];
@@ -172,7 +216,8 @@ __device__ __forceinline__ void compute_group(const StepParams& p, const Group<W
     float gf;
     if (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[(k >> 2) & (GS == kGradF32 ? 3 : 1)][k & 3]), tr.ab);
     else                gf = (float)sx16(G.g[(k >> 3) & 1][(k >> 1) & 3], k & 1);
-    update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    if (SMALL) update_small<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    else       update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
   pack16<WT>(O.th, tn);
   pack16<WC>(O.c, cn);
@@ -185,11 +230,11 @@ __device__ __forceinline__ void store_group(const GroupOut<WT, WC>& O, const Ten
   store16v<WC>(T.comp, e, O.c);
 }
 
-template <int WT, int WC, int GS, bool DECAY>
+template <int WT, int WC, int GS, bool DECAY, bool SMALL>
 __device__ __forceinline__ void compute_store_group(const StepParams& p, const Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
   GroupOut<WT, WC> O;
-  compute_group<WT, WC, GS, DECAY>(p, G, O, tr);
+  compute_group<WT, WC, GS, DECAY, SMALL>(p, G, O, tr);
   store_group<WT, WC>(O, T, e);
 }
 
@@ -200,7 +245,7 @@ __device__ __forceinline__ uint64_t track_max(const Track& tr)
 }
 
 // Vector tile: full 16-element groups with the fast arithmetic, the ragged end element by element.
-template <int WT, int WC, int GS, bool DECAY>
+template <int WT, int WC, int GS, bool DECAY, bool SMALL>
 __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
 {
   Track tr{0, 0, ab_max};
@@ -213,13 +258,13 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
+    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, SMALL>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     Group<WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * kGroup;
     load_group(G, T, e);
-    compute_store_group<WT, WC, GS, DECAY>(p, G, T, e, tr);
+    compute_store_group<WT, WC, GS, DECAY, SMALL>(p, G, T, e, tr);
   }
   ab_max = tr.ab;
   uint64_t vm = track_max(tr);
@@ -291,7 +336,7 @@ __device__ __forceinline__ void load_group_e(GroupE<E, WT, WC, GS>& G, const Ten
   }
 }
 
-template <int E, int WT, int WC, int GS, bool DECAY>
+template <int E, int WT, int WC, int GS, bool DECAY, bool SMALL>
 __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
   int tn[E], cn[E];
@@ -300,13 +345,14 @@ __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const
     float gf;
     if constexpr (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[k >> 2].d[k & 3]), tr.ab);
     else                          gf = (float)sx16(G.g[k >> 3].d[(k >> 1) & 3], k & 1);
-    update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    if constexpr (SMALL) update_small<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    else                 update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
   st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
   st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
 }
 
-template <int E, int KP, int WT, int WC, int GS, bool DECAY>
+template <int E, int KP, int WT, int WC, int GS, bool DECAY, bool SMALL>
 __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
 {
   Track tr{0, 0, ab_max};
@@ -317,13 +363,13 @@ __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const Tenso
 #pragma unroll
     for (int ps = 0; ps < KP; ++ps) load_group_e(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
-    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
+    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, SMALL>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     GroupE<E, WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * E;
     load_group_e(G, T, e);
-    compute_store_group_e<E, WT, WC, GS, DECAY>(p, G, T, e, tr);
+    compute_store_group_e<E, WT, WC, GS, DECAY, SMALL>(p, G, T, e, tr);
   }
   ab_max = tr.ab;
   uint64_t vm = track_max(tr);
@@ -386,21 +432,31 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   p.magic_dlo = (int)(md & 0xffffffffll);
   p.nlrwd_d   = -(double)p.lrwd;
   p.half_m1   = (1 << (p.d - 1)) - 1;
+  // small-value variant: |v| and |v| + rounding addend below 2^22 (exact in fp32, quotient inside the 2^22 window
+  // of the 1.5 * 2^23 offset), and (2^22 + theta') * 2^d inside int32
+  p.small = p.wt == 8 && p.wc == 8 && p.d <= 8 && bound < (1ll << 22);
+  p.bias_i  = -p.magic_fi;
+  p.inv2d_f = __uint_as_float((uint32_t)(127 - p.d) << 23);
+  p.lo_tf   = 12582912.0f + (float)p.qmin_t;
+  p.hi_tf   = 12582912.0f + (float)p.qmax_t;
+  p.neg2d   = -(1 << p.d);
+  p.lo_cb   = p.qmin_c - (1 << (22 + (p.d <= 8 ? p.d : 8)));
+  p.hi_cb   = p.qmax_c - (1 << (22 + (p.d <= 8 ? p.d : 8)));
 }
 
 // ---------------------------------------------------------------- the kernel
 
-template <int WT, int WC, int GS>
+template <int WT, int WC, int GS, bool SMALL>
 __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
 {
   if (GS == kGradF32)
-    return p.lrwd ? tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, true>(p, T, off, cnt, lane, ab)
-                  : tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, false>(p, T, off, cnt, lane, ab);
+    return p.lrwd ? tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, true, SMALL>(p, T, off, cnt, lane, ab)
+                  : tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, false, SMALL>(p, T, off, cnt, lane, ab);
 #if LPK_I16_E != 16
-  return p.lrwd ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true>(p, T, off, cnt, lane, ab)
-                : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false>(p, T, off, cnt, lane, ab);
+  return p.lrwd ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, SMALL>(p, T, off, cnt, lane, ab)
+                : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, SMALL>(p, T, off, cnt, lane, ab);
 #endif
-  return p.lrwd ? tile_fast<WT, WC, GS, true>(p, T, off, cnt, lane, ab) : tile_fast<WT, WC, GS, false>(p, T, off, cnt, lane, ab);
+  return p.lrwd ? tile_fast<WT, WC, GS, true, SMALL>(p, T, off, cnt, lane, ab) : tile_fast<WT, WC, GS, false, SMALL>(p, T, off, cnt, lane, ab);
 }
 
 template <int GS>
@@ -435,9 +491,10 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && p.wc == 8) vm = tile_fast_decay<8, 8, GS>(p, T, off, cnt, lane, ab_max);
-      else if (p.wt == 16) vm = tile_fast_decay<16, 16, GS>(p, T, off, cnt, lane, ab_max);
-      else                 vm = tile_fast_decay<8, 16, GS>(p, T, off, cnt, lane, ab_max);
+      if (p.wt == 8 && p.wc == 8) vm = p.small ? tile_fast_decay<8, 8, GS, true>(p, T, off, cnt, lane, ab_max)
+                                               : tile_fast_decay<8, 8, GS, false>(p, T, off, cnt, lane, ab_max);
+      else if (p.wt == 16) vm = tile_fast_decay<16, 16, GS, false>(p, T, off, cnt, lane, ab_max);
+      else                 vm = tile_fast_decay<8, 16, GS, false>(p, T, off, cnt, lane, ab_max);
     } else if (p.path == 1) {
       vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
     }
