@@ -167,7 +167,7 @@ def main():
     ms_per_step = wall * 1e3 / K
     status = int(dev.status.cpu().numpy().view("uint32")[0])
 
-    copy = None
+    copy = mix = None
     if args.copy_gib > 0:
         nb = int(args.copy_gib * (1 << 30)) // 16 * 16
         a = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
@@ -183,6 +183,20 @@ def main():
         cms = e0.elapsed_time(e1) / reps
         copy = {"bytes_read": nb, "bytes_written": nb, "ms": cms, "GB/s": 2 * nb / (cms * 1e-3) / 1e9}
         del a, b
+        # the update's own byte mix (4 read : 2 written, in place) with no arithmetic, at the headline size
+        nm = min(cfg.n_params, 1 << 30) // 4096 * 4096
+        a = torch.zeros(nm, dtype=torch.uint8, device="cuda:0")
+        b = torch.zeros(nm, dtype=torch.uint8, device="cuda:0")
+        c = torch.zeros(2 * nm, dtype=torch.uint8, device="cuda:0")
+        lpk.lpk_stream_mix(a, b, c, nm)
+        e0.record()
+        for _ in range(reps):
+            lpk.lpk_stream_mix(a, b, c, nm)
+        e1.record()
+        torch.cuda.synchronize()
+        mms = e0.elapsed_time(e1) / reps
+        mix = {"bytes_read": 4 * nm, "bytes_written": 2 * nm, "ms": mms, "GB/s": 6 * nm / (mms * 1e-3) / 1e9}
+        del a, b, c
 
     upd_bytes = sum(n * (2 * (b // 8) + 2 * (cb // 8) + 2) for n, b, cb in zip(cfg.sizes, cfg.bits, dev.comp_bits))
     upd_bytes += 2 * (args.momentum_bits // 8) * cfg.n_params if args.momentum_bits else 0
@@ -197,12 +211,15 @@ def main():
             traffic = None
 
     out = {
-        "metric": "Kahan-SGD update throughput (whole hot path: fraclen select + quantize + fused update)",
+        "metric": "Kahan-SGD update Gparams/s + achieved HBM GB/s (% of peak), 1 MI355X",
+        "metric_note": "value = parameters per second over whole steps (max-abs fraclen selection + quantization to int16 + "
+                       "fused Kahan update with vmax), fp32 gradients resident in HBM; update_only and roofline = the update kernel alone",
         "value": cfg.n_params / (ms_per_step * 1e-3) / 1e9,
         "unit": "Gparam/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8/int16 fixed point (int32/int64 accumulate)", "data": "synthetic",
+        "dtype": "int32", "data": "synthetic",
+        "storage": "int8/int16 dynamic fixed point (int64 arithmetic outside the 32-bit fast path)",
         "config": {"workload": "config %d: %s%s" % (cfg.id, cfg.name, ", momentum 0.9 with int%d velocity" % args.momentum_bits
                                                     if args.momentum_bits else "") + (", int%d accumulator" % args.comp_bits if args.comp_bits else ""),
                    "n_tensors": cfg.n_tensors,
@@ -218,6 +235,7 @@ def main():
             "quantize_kernel": {"GB/s": 6 * cfg.n_params / (qnt_ms * 1e-3) / 1e9, "bytes_per_launch": 6 * cfg.n_params}},
         "fused_path": fused,
         "stream_copy_yardstick": copy,
+        "stream_mix_yardstick": mix,
         "device_status_word": status,
     }
     dev.close()

@@ -227,6 +227,14 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16);
  * bandwidth of the device.  dst, src: device, 16-byte aligned, non-overlapping; nbytes % 16 == 0. */
 int lpk_stream_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
 
+/* Measurement aid, not part of the method: the HBM byte mix of the int8 lazy update with no arithmetic.
+ * For every 16-byte word j < nbytes / 16: reads a[j], b[j], c[2j], c[2j+1] and writes a[j] ^= c[2j],
+ * b[j] ^= c[2j+1] in place -- 4 bytes read and 2 written per byte of a, in the update kernel's launch
+ * shape.  Its bandwidth is what the memory system gives this access mix; the update kernel is read
+ * against it.  a, b: device, nbytes each; c: device, 2 * nbytes; all 16-byte aligned, non-overlapping;
+ * nbytes a multiple of 4096. */
+int lpk_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, void* stream);
+
 /* Static text for a return code ("ok", "invalid argument", ...). Never NULL. */
 const char* lpk_error_string(int code);
 

@@ -59,6 +59,8 @@ def lib():
         L.lpk_momentum_sgd_step.restype = ci
         L.lpk_stream_copy.argtypes = [vp, vp, u64, vp]
         L.lpk_stream_copy.restype = ci
+        L.lpk_stream_mix.argtypes = [vp, vp, vp, u64, vp]
+        L.lpk_stream_mix.restype = ci
         L.lpk_classifier_min_bits.argtypes = [u32, u32]
         L.lpk_classifier_min_bits.restype = ci
         L.lpk_error_string.argtypes = [ci]
@@ -184,6 +186,10 @@ def lpk_momentum_sgd_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, 
                                        _addr(fl_mom_out), _addr(fl_grad), int(lr_q16), int(mu_q16), int(wd_q16),
                                        _addr(vmax_out), _addr(mmax_out), _addr(status), _stream(stream)),
            "lpk_momentum_sgd_step")
+
+
+def lpk_stream_mix(a, b, c, nbytes, stream=None):
+    _check(lib().lpk_stream_mix(_addr(a), _addr(b), _addr(c), int(nbytes), _stream(stream)), "lpk_stream_mix")
 
 
 def lpk_stream_copy(dst, src, nbytes, stream=None):

@@ -20,6 +20,7 @@ hipError_t launch_select_vmax(const TensorDev*, uint32_t n_tensors, int sel, con
 hipError_t launch_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t grid, int to_theta,
                            const int32_t* fl, uint32_t* status, hipStream_t);
 hipError_t launch_stream_copy(void* dst, const void* src, uint64_t nbytes, uint32_t grid, hipStream_t);
+hipError_t launch_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, uint32_t grid, hipStream_t);
 hipError_t launch_momentum_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                                 const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                                 const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
@@ -236,6 +237,20 @@ int lpk_stream_copy(void* dst, const void* src, uint64_t nbytes, void* stream)
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
+int lpk_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, void* stream)
+{
+  if (nbytes == 0) return LPK_OK;
+  if (!a || !b || !c || (nbytes % (uint64_t)kTileElems) || !aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16)) return LPK_ERR_INVALID_ARG;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return LPK_ERR_DEVICE;
+  uint64_t blocks = (nbytes / kTileElems + kWavesPerBlock - 1) / kWavesPerBlock;
+  const uint64_t cap = (uint64_t)prop.multiProcessorCount * env_u32("LPK_STEP_BLOCKS_PER_CU", 1);
+  if (blocks > cap) blocks = cap;
+  hipError_t e = launch_stream_mix(a, b, c, nbytes, (uint32_t)blocks, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
 const char* lpk_error_string(int code)
 {
   switch (code) {
@@ -257,6 +272,6 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
   return bw;
 }
 
-int lpk_version(void) { return 103; }
+int lpk_version(void) { return 104; }
 
 }  // extern "C"
