@@ -343,6 +343,135 @@ int lpk_ref_momentum_sgd_step(void *theta, void *comp, void *mom, const void *gr
     return LPK_REF_OK;
 }
 
+/* ---------- ADAM with the lazy update inside ------------------------------------------------------------------ */
+
+/* floor(sqrt(a)) for 0 <= a < 2^62, one result bit at a time: keep the bit when the square still fits. */
+static wide isqrt_floor(wide a)
+{
+    wide r = 0;
+    for (int b = 31; b >= 0; --b) {
+        wide t = r + ((wide)1 << b);
+        if (t * t <= a) r = t;
+    }
+    return r;
+}
+
+/* RNE(num / den) for integers, den > 0: floor quotient, then compare twice the remainder with den. */
+static wide div_rne(wide num, wide den)
+{
+    wide q = num / den, r = num % den;
+    if (r < 0) { r += den; q -= 1; }                 /* num = q den + r, 0 <= r < den */
+    if (2 * r > den || (2 * r == den && (q & 1))) q += 1;
+    return q;
+}
+
+/*
+ * Section 4 trains the SVHN network, the GANs and the LSTM with the ADAM optimizer in INT16 "with the lazy update
+ * implemented in the optimizer"; the paper names only the hyper-parameters (beta1, beta2, epsilon, learning rate)
+ * and that 16 bits are needed because of beta2.  Reading taken here: the textbook rule
+ *
+ *     m <- beta1 m + (1 - beta1) g        u <- beta2 u + (1 - beta2) g^2        theta <- theta - lr_t m / (sqrt(u) + eps)
+ *
+ * with the bias corrections folded into the step size lr_t = lr sqrt(1 - beta2^t) / (1 - beta1^t) by the caller,
+ * m and u two DFX state tensors with fraclens of their own, and the step handed to Algorithm 1's accumulator.
+ * Constants: beta1, beta2 as Q0.16 (their complements are 65536 - beta); lr_t = lr_q * 2^-(16 + lr_exp) and
+ * eps = eps_q * 2^-(16 + eps_exp) with 16-bit lr_q, eps_q and 0 <= lr_exp, eps_exp <= 48.
+ *
+ * In fixed point (every RNE as if in unbounded integers, cap = clamp to +-2^40):
+ *     wM = RNE(b1 m on grid Gm) + cap(RNE((65536 - b1) g on Gm)),   Gm = fl_m_out + 16
+ *     mq = RNE(wM / 2^16);  m' = sat(mq);  mmax = max |mq|
+ *     wU = RNE(b2 u on grid Gu) + cap(RNE((65536 - b2) g^2 on Gu)), Gu = fl_u_out + 16
+ *     uq = RNE(wU / 2^16);  u' = clamp(uq, 0, qmax);  umax = max(uq, 0) over the tensor
+ *     rt = floor(sqrt(u' 2^(24 + p))),  p = parity of fl_u_out: the root on grid R = (fl_u_out + 24 + p) / 2
+ *     den = max(rt + min(RNE(eps on grid R), 2^30), 1)
+ *     s  = cap(RNE(-lr_q m' 2^e / den)),  e = F + R - 16 - lr_exp - fl_m_out,  F = fl_in + d
+ *   then exactly the lazy update with this s.  e > 20 is outside the domain (the tensor is skipped).
+ */
+int lpk_ref_adam_step(void *theta, void *comp, void *mom, void *sec, const void *grad, uint64_t n,
+                      int theta_bits, int comp_bits, int mom_bits, int sec_bits, int grad_bits, int d,
+                      int32_t fl_in, int32_t fl_out, int32_t fl_m_in, int32_t fl_m_out,
+                      int32_t fl_u_in, int32_t fl_u_out, int32_t fl_g,
+                      uint32_t lr_q, uint32_t lr_exp, uint32_t b1_q, uint32_t b2_q, uint32_t eps_q, uint32_t eps_exp,
+                      uint64_t *vmax, uint64_t *mmax, uint64_t *umax, uint32_t *status)
+{
+    if (!bits_ok(theta_bits) || !bits_ok(grad_bits) || !bits_ok(mom_bits) || !bits_ok(sec_bits) ||
+        (comp && !bits_ok(comp_bits))) return LPK_REF_ERR_ARG;
+    if (n && (!theta || !grad || !mom || !sec)) return LPK_REF_ERR_ARG;
+    if (lr_q > 65535u || b1_q > 65535u || b2_q > 65535u || eps_q > 65535u || lr_exp > 48u || eps_exp > 48u) return LPK_REF_ERR_ARG;
+    if (!comp) d = 0;
+    if (vmax) *vmax = 0;
+    if (mmax) *mmax = 0;
+    if (umax) *umax = 0;
+    const int delta = fl_out - fl_in, delta_m = fl_m_out - fl_m_in, delta_u = fl_u_out - fl_u_in;
+    const int F = fl_in + d, Gm = fl_m_out + 16, Gu = fl_u_out + 16;
+    const int par = ((fl_u_out % 2) + 2) % 2;
+    const int R = (fl_u_out + 24 + par) / 2;                      /* exact: the numerator is even */
+    const int e = F + R - 16 - (int)lr_exp - fl_m_out;
+    if (fl_in < FL_MIN || fl_in > FL_MAX || fl_out < FL_MIN || fl_out > FL_MAX || fl_g < FL_MIN || fl_g > FL_MAX ||
+        fl_m_in < FL_MIN || fl_m_in > FL_MAX || fl_m_out < FL_MIN || fl_m_out > FL_MAX ||
+        fl_u_in < FL_MIN || fl_u_in > FL_MAX || fl_u_out < FL_MIN || fl_u_out > FL_MAX ||
+        d < 0 || d > D_MAX || delta > DELTA_MAX || delta < -DELTA_MAX || delta_m > DELTA_MAX || delta_m < -DELTA_MAX ||
+        delta_u > DELTA_MAX || delta_u < -DELTA_MAX || e > 20) {
+        if (status) *status |= STATUS_DOMAIN;
+        return LPK_REF_OK;
+    }
+    const int u_shift = delta > 0 ? delta : 0;
+    const int k_theta = d + u_shift - delta;
+    wide eps_R = rescale((wide)eps_q, 16 + (int)eps_exp - R);
+    if (eps_R > ((wide)1 << 30)) eps_R = (wide)1 << 30;
+    wide vm = 0, wm = 0, um = 0;
+    for (uint64_t i = 0; i < n; ++i) {
+        wide th = load_q(theta, i, theta_bits);
+        wide c  = comp ? load_q(comp, i, comp_bits) : 0;
+        wide m  = load_q(mom, i, mom_bits);
+        wide u  = load_q(sec, i, sec_bits);
+        wide g  = load_q(grad, i, grad_bits);
+
+        /* first moment: b1*m sits on grid fl_m_in + 16, (1 - b1)*g on fl_g + 16 */
+        wide wM = rescale((wide)b1_q * m, (fl_m_in + 16) - Gm);
+        wM += rescale_cap((wide)(65536u - b1_q) * g, (fl_g + 16) - Gm);
+        wide mq = rescale(wM, 16);
+        wide am = mq < 0 ? -mq : mq;
+        if (am > wm) wm = am;
+        wide mn = sat(mq, mom_bits);
+        store_q(mom, i, mom_bits, mn);
+
+        /* second moment: b2*u sits on grid fl_u_in + 16, (1 - b2)*g^2 on 2 fl_g + 16 */
+        wide wU = rescale((wide)b2_q * u, (fl_u_in + 16) - Gu);
+        wU += rescale_cap((wide)(65536u - b2_q) * g * g, (2 * fl_g + 16) - Gu);
+        wide uq = rescale(wU, 16);
+        if (uq > um) um = uq;
+        wide un = clampw(uq, 0, qmax_of(sec_bits));
+        store_q(sec, i, sec_bits, un);
+
+        /* the step: -lr_t * m' / (sqrt(u') + eps) on grid F */
+        wide rt  = isqrt_floor(un * ((wide)1 << (24 + par)));
+        wide den = rt + eps_R;
+        if (den < 1) den = 1;
+        wide num = -(wide)lr_q * mn;
+        wide s;
+        if (e >= 0) s = div_rne(num * ((wide)1 << e), den);
+        else if (e > -80) s = div_rne(num, den * ((wide)1 << (-e)));
+        else s = 0;                                   /* |num| < 2^31 against a divisor >= 2^80 */
+        s = clampw(s, -CAP40, CAP40);
+
+        wide v = th * ((wide)1 << d) + c + s;
+        wide av = v < 0 ? -v : v;
+        if (av > vm) vm = av;
+        wide vG  = v * ((wide)1 << u_shift);
+        wide thn = sat(rescale(vG, k_theta), theta_bits);
+        store_q(theta, i, theta_bits, thn);
+        if (comp) {
+            wide r = vG - thn * ((wide)1 << k_theta);
+            store_q(comp, i, comp_bits, sat(rescale(r, k_theta - d), comp_bits));
+        }
+    }
+    if (vmax) *vmax = (uint64_t)vm;
+    if (mmax) *mmax = (uint64_t)wm;
+    if (umax) *umax = (uint64_t)um;
+    return LPK_REF_OK;
+}
+
 /* ---------- classifier bit-width guideline (Section 3, eq. 4) ------------------------------------------------ */
 
 /* Smallest BW for which  alpha / (|class| - 1) >= 2^-(BW-1)  holds, alpha = alpha_q16 / 65536, found by

@@ -46,6 +46,9 @@ def load(path):
     L.lpk_ref_momentum_sgd_step.argtypes = [vp, vp, vp, vp, u64, ci, ci, ci, ci, ci, i32, i32, i32, i32, i32,
                                             u32, u32, u32, vp, vp, vp]
     L.lpk_ref_momentum_sgd_step.restype = ci
+    L.lpk_ref_adam_step.argtypes = [vp, vp, vp, vp, vp, u64, ci, ci, ci, ci, ci, ci, i32, i32, i32, i32, i32, i32, i32,
+                                    u32, u32, u32, u32, u32, u32, vp, vp, vp, vp]
+    L.lpk_ref_adam_step.restype = ci
     L.lpk_ref_classifier_min_bits.argtypes = [u32, u32]
     L.lpk_ref_classifier_min_bits.restype = ci
     for f in (L.lpk_ref_select_fraclen_f32, L.lpk_ref_select_fraclen_vmax,
@@ -227,3 +230,48 @@ def momentum_sgd_step_mt(theta, comp, mom, grad, d, fl_in, fl_out, fl_m_in, fl_m
         for st in stats:
             status[0] |= st[0]
     return max(r[0] for r in res), max(r[1] for r in res)
+
+
+def adam_step(theta, comp, mom, sec, grad, d, fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g,
+              lr_q, lr_exp, b1_q, b2_q, eps_q, eps_exp, status=None):
+    """One ADAM step with the lazy update inside, in place.  Returns (vmax, mmax, umax)."""
+    for a in (theta, comp, mom, sec, grad):
+        assert a is None or a.flags.c_contiguous
+    n = theta.size
+    assert grad.size == n and mom.size == n and sec.size == n and (comp is None or comp.size == n)
+    cb = _bits(comp) if comp is not None else 8
+    if d is None:
+        d = cb - 1
+    vmax, mmax, umax = (np.zeros(1, dtype=np.uint64) for _ in range(3))
+    _check(lib().lpk_ref_adam_step(_ptr(theta), _ptr(comp), _ptr(mom), _ptr(sec), _ptr(grad), n,
+                                   _bits(theta), cb, _bits(mom), _bits(sec), _bits(grad), int(d),
+                                   int(fl_in), int(fl_out), int(fl_m_in), int(fl_m_out), int(fl_u_in), int(fl_u_out), int(fl_g),
+                                   int(lr_q), int(lr_exp), int(b1_q), int(b2_q), int(eps_q), int(eps_exp),
+                                   _ptr(vmax), _ptr(mmax), _ptr(umax), _ptr(status)))
+    return int(vmax[0]), int(mmax[0]), int(umax[0])
+
+
+def adam_step_mt(theta, comp, mom, sec, grad, d, fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g,
+                 lr_q, lr_exp, b1_q, b2_q, eps_q, eps_exp, status=None, threads=1, chunk=1 << 22):
+    """Same result as adam_step, contiguous chunks on a thread pool (elements are independent)."""
+    n = theta.size
+    args = (fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, lr_q, lr_exp, b1_q, b2_q, eps_q, eps_exp)
+    if threads <= 1 or n <= chunk:
+        return adam_step(theta, comp, mom, sec, grad, d, *args, status)
+    th, gr, mo, se = theta.reshape(-1), grad.reshape(-1), mom.reshape(-1), sec.reshape(-1)
+    co = comp.reshape(-1) if comp is not None else None
+    dd = d if d is not None else (_bits(co) - 1 if co is not None else 0)
+    stats = []
+
+    def work(lo):
+        hi = min(lo + chunk, n)
+        st = new_status()
+        stats.append(st)
+        return adam_step(th[lo:hi], None if co is None else co[lo:hi], mo[lo:hi], se[lo:hi], gr[lo:hi], dd, *args, st)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        res = list(ex.map(work, range(0, n, chunk)))
+    if status is not None:
+        for st in stats:
+            status[0] |= st[0]
+    return tuple(max(r[k] for r in res) for k in range(3))

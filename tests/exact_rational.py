@@ -98,3 +98,37 @@ def momentum_step(theta, c, m, g, theta_bits, comp_bits, mom_bits, d, fl_in, fl_
     s = max(-CAP, min(CAP, rne(m_new * two(-fl_m_out) * two(F))))
     t, cn, vabs = _apply(theta, c, s, theta_bits, comp_bits, d, fl_in, fl_out, kahan)
     return t, cn, m_new, vabs, abs(m_wide)
+
+
+def adam_step(theta, c, m, u, g, theta_bits, comp_bits, mom_bits, sec_bits, d, fl_in, fl_out, fl_m_in, fl_m_out,
+              fl_u_in, fl_u_out, fl_g, lr_q, lr_exp, b1_q, b2_q, eps_q, eps_exp, kahan=True):
+    """ADAM (m <- b1 m + (1-b1) g, u <- b2 u + (1-b2) g^2, theta <- theta - lr_t m / (sqrt(u) + eps)) with the lazy
+    update inside, in real-number terms.  The root is taken on the grid R = (fl_u_out + 24 + parity) / 2 and
+    checked here by its defining inequality.  Returns (theta', c', m', u', |v| on grid F, |m| and max(u, 0)
+    before saturation)."""
+    import math
+    if not kahan:
+        d, c = 0, 0
+    b1, b2 = Fr(b1_q, 2 ** 16), Fr(b2_q, 2 ** 16)
+    lr_t, eps = Fr(lr_q) * two(-(16 + lr_exp)), Fr(eps_q) * two(-(16 + eps_exp))
+    g_real = g * two(-fl_g)
+    Gm, Gu = fl_m_out + 16, fl_u_out + 16
+    wM = rne(b1 * m * two(-fl_m_in) * two(Gm)) + max(-CAP, min(CAP, rne((1 - b1) * g_real * two(Gm))))
+    m_wide = rne(Fr(wM, 2 ** 16))
+    m_new = sat(m_wide, mom_bits)
+    wU = rne(b2 * u * two(-fl_u_in) * two(Gu)) + max(-CAP, min(CAP, rne((1 - b2) * g_real * g_real * two(Gu))))
+    u_wide = rne(Fr(wU, 2 ** 16))
+    u_new = max(0, min(2 ** (sec_bits - 1) - 1, u_wide))
+    par = fl_u_out % 2                                  # Python's % is already the non-negative parity
+    R = Fr(fl_u_out + 24 + par, 2)
+    assert R.denominator == 1
+    R = int(R)
+    x = u_new * two(-fl_u_out) * two(2 * R)             # the radicand on grid 2R: an integer
+    assert x.denominator == 1
+    rt = math.isqrt(int(x))
+    assert Fr(rt * rt) <= x < Fr((rt + 1) * (rt + 1))   # rt * 2^-R <= sqrt(u') < (rt + 1) * 2^-R
+    den = max(rt + min(rne(eps * two(R)), 2 ** 30), 1)
+    F = fl_in + d
+    s = max(-CAP, min(CAP, rne(-lr_t * m_new * two(-fl_m_out) / (den * two(-R)) * two(F))))
+    t, cn, vabs = _apply(theta, c, s, theta_bits, comp_bits, d, fl_in, fl_out, kahan)
+    return t, cn, m_new, u_new, vabs, abs(m_wide), max(u_wide, 0)

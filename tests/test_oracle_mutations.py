@@ -10,6 +10,7 @@ from oracle import ref
 import test_oracle_bruteforce as bf
 import test_oracle_pins as pins
 import test_oracle_momentum as mom
+import test_oracle_adam as adam
 
 SRC = os.path.join(os.path.dirname(ref.__file__), "lpk_ref.c")
 
@@ -43,6 +44,22 @@ MUTATIONS = [
     ("momentum_decay_grid", "* th, (fl_in + 32) - G);", "* th, (fl_in + 16) - G);"),
     ("momentum_velocity_not_saturated", "wide mn = sat(mq, mom_bits);", "wide mn = mq;"),
     ("theta_unscaled", "wide v = th * ((wide)1 << d) + c + s;", "wide v = th + c + s;"),
+    ("adam_betas_swapped", "wide wM = rescale((wide)b1_q * m,", "wide wM = rescale((wide)b2_q * m,"),
+    ("adam_complement_forgotten", "rescale_cap((wide)(65536u - b1_q) * g,", "rescale_cap((wide)b1_q * g,"),
+    ("adam_gradient_not_squared", "(wide)(65536u - b2_q) * g * g,", "(wide)(65536u - b2_q) * g,"),
+    ("adam_square_grid", "(2 * fl_g + 16) - Gu);", "(fl_g + 16) - Gu);"),
+    ("adam_root_grid_parity", "const int par = ((fl_u_out % 2) + 2) % 2;", "const int par = 0;"),
+    ("adam_root_rounds_up", "if (t * t <= a) r = t;", "if (t * t < a) r = t + 1;"),
+    ("adam_root_misses_squares", "if (t * t <= a) r = t;", "if (t * t < a) r = t;"),
+    ("adam_eps_dropped", "wide den = rt + eps_R;", "wide den = rt;"),
+    ("adam_step_sign", "wide num = -(wide)lr_q * mn;", "wide num = (wide)lr_q * mn;"),
+    ("adam_old_moment_in_step", "wide num = -(wide)lr_q * mn;", "wide num = -(wide)lr_q * m;"),
+    ("adam_division_truncates", "if (2 * r > den || (2 * r == den && (q & 1))) q += 1;", "if (0) q += 1;"),
+    ("adam_division_ties_up", "if (2 * r > den || (2 * r == den && (q & 1))) q += 1;", "if (2 * r >= den) q += 1;"),
+    ("adam_step_exponent", "const int e = F + R - 16 - (int)lr_exp - fl_m_out;", "const int e = F + R - 16 - (int)lr_exp + fl_m_out;"),
+    ("adam_lr_exponent_ignored", "const int e = F + R - 16 - (int)lr_exp - fl_m_out;", "const int e = F + R - 16 - fl_m_out;"),
+    ("adam_second_moment_goes_negative", "wide un = clampw(uq, 0, qmax_of(sec_bits));", "wide un = sat(uq, sec_bits);"),
+    ("adam_moment_guard_bits", "wide uq = rescale(wU, 16);", "wide uq = rescale(wU, 15);"),
 ]
 
 CHECKS = [
@@ -59,6 +76,9 @@ CHECKS = [
     lambda: mom.test_momentum_step_bruteforce(0),
     mom.test_velocity_decay_and_fixed_point,
     mom.test_momentum_conserves_theta_plus_c,
+    lambda: adam.test_adam_step_bruteforce(0),
+    adam.test_constant_gradient_moves_theta_by_lr_per_step,
+    adam.test_against_float64_adam,
 ]
 
 
@@ -72,7 +92,8 @@ def test_planted_mistake_is_caught(name, old, new, tmp_path, monkeypatch):
     subprocess.check_call(["gcc", "-O1", "-w", "-shared", "-fPIC", "-o", str(so), str(c), "-lm"])
     monkeypatch.setattr(ref, "_lib", ref.load(str(so)))
     caught = False
-    for chk in CHECKS:
+    order = CHECKS[::-1] if name.startswith(("adam", "momentum")) else CHECKS      # likeliest catchers first: same verdict, sooner
+    for chk in order:
         try:
             chk()
         except AssertionError:
