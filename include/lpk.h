@@ -59,7 +59,7 @@ typedef enum {
 typedef enum { LPK_I8 = 1, LPK_I16 = 2, LPK_F32 = 4, LPK_VMAX_U64 = 8 } lpk_dtype;
 
 /* which member of the descriptor a call reads its width from / writes to */
-typedef enum { LPK_SEL_GRAD = 0, LPK_SEL_THETA = 1, LPK_SEL_MOMENTUM = 2 } lpk_selector;
+typedef enum { LPK_SEL_GRAD = 0, LPK_SEL_THETA = 1, LPK_SEL_MOMENTUM = 2, LPK_SEL_SECOND = 3 } lpk_selector;
 
 /* bits of the device status word */
 #define LPK_STATUS_NONFINITE 1u  /* a NaN or Inf was met in fp32 input                               */
@@ -82,8 +82,11 @@ typedef struct {
   uint8_t     grad_dtype;  /* LPK_I8 or LPK_I16 */
   uint8_t     comp_shift;  /* d = fl_comp - fl_theta, 0..24; LPK_COMP_SHIFT_DEFAULT = bits(comp_dtype) - 1 */
   uint8_t     momentum_dtype; /* LPK_I8 or LPK_I16 (ignored when momentum == NULL) */
-  uint8_t     reserved[3];    /* set to 0 */
-  void*       momentum;    /* device; DFX ints, velocity of lpk_momentum_sgd_step, updated in place; may be NULL */
+  uint8_t     second_dtype;   /* LPK_I8 or LPK_I16 (ignored when second == NULL) */
+  uint8_t     reserved[2];    /* set to 0 */
+  void*       momentum;    /* device; DFX ints, updated in place; may be NULL.  The velocity of
+                              lpk_momentum_sgd_step, the first moment of lpk_adam_step                      */
+  void*       second;      /* device; DFX ints >= 0, second moment of lpk_adam_step, updated in place; may be NULL */
 } lpk_tensor_desc;
 
 typedef struct lpk_tensor_list lpk_tensor_list;   /* opaque */
@@ -113,7 +116,8 @@ uint64_t lpk_tensor_list_tiles(const lpk_tensor_list* list);
  *   the finest grid on which the tensor's own maximum does not saturate.
  *
  * W = bits of desc.grad_dtype (dst_sel == LPK_SEL_GRAD), desc.theta_dtype
- * (LPK_SEL_THETA) or desc.momentum_dtype (LPK_SEL_MOMENTUM, LPK_VMAX_U64 only).
+ * (LPK_SEL_THETA), desc.momentum_dtype (LPK_SEL_MOMENTUM) or desc.second_dtype
+ * (LPK_SEL_SECOND); the last two with LPK_VMAX_U64 only.
  *
  * src_kind == LPK_F32: M = max_i |desc.src_f32[i]| (src_f32 must be non-NULL
  *   for every tensor with n > 0).  M == 0 (or n == 0) -> fl_default[t].  Any
@@ -128,7 +132,8 @@ uint64_t lpk_tensor_list_tiles(const lpk_tensor_list* list);
  *   fl_theta_out when fl_default is that step's fl_theta_in.
  *   With dst_sel == LPK_SEL_MOMENTUM the maximum is the mmax of
  *   lpk_momentum_sgd_step and `fl_theta_in` is the fl_mom_out array that step
- *   was called with: M = vmax[t] * 2^-fl_theta_in[t].
+ *   was called with: M = vmax[t] * 2^-fl_theta_in[t].  The same holds for the mmax
+ *   (LPK_SEL_MOMENTUM, fl_mom_out) and the umax (LPK_SEL_SECOND, fl_sec_out) of lpk_adam_step.
  *
  * vmax (uint64), fl_theta_in, fl_default, fl_out (int32): device arrays of
  * n_tensors entries.  fl_out is written for every tensor.
@@ -210,6 +215,45 @@ int lpk_momentum_sgd_step(lpk_tensor_list* list,
                           const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_grad,
                           uint32_t lr_q16, uint32_t mu_q16, uint32_t wd_q16,
                           uint64_t* vmax_out, uint64_t* mmax_out, uint32_t* status, void* stream);
+
+/*
+ * ADAM with the lazy update inside (Section 4: the ADAM optimizer in INT16 -- 16 bits because of beta2 --
+ * with Algorithm 1 implemented in the optimizer; the paper names only the hyper-parameters).  Textbook rule
+ *   m <- beta1 m + (1 - beta1) g;  u <- beta2 u + (1 - beta2) g^2;  theta <- theta - lr_t m / (sqrt(u) + eps)
+ * with the bias corrections folded into lr_t = lr sqrt(1 - beta2^t) / (1 - beta1^t) by the caller, and the step
+ * handed to Algorithm 1's accumulator.  desc.momentum holds m in DFX(bits(momentum_dtype), fl_mom), desc.second
+ * holds u >= 0 in DFX(bits(second_dtype), fl_sec); both non-NULL for every tensor with n > 0.
+ * Per element (every RNE as if in unbounded integers; cap = clamp to +-2^40; F = fl_theta_in[t] + d):
+ *
+ *   wM = RNE(beta1_q16 * m * 2^-(fl_mom_in[t] - fl_mom_out[t])) + cap(RNE((65536 - beta1_q16) * g * 2^-(fl_grad[t] - fl_mom_out[t])))
+ *   mq = RNE(wM * 2^-16);  m' = sat(mq);  mmax_out[t] = max_i |mq_i|
+ *   wU = RNE(beta2_q16 * u * 2^-(fl_sec_in[t] - fl_sec_out[t])) + cap(RNE((65536 - beta2_q16) * g^2 * 2^-(2 fl_grad[t] - fl_sec_out[t])))
+ *   uq = RNE(wU * 2^-16);  u' = clamp(uq, 0, qmax);  umax_out[t] = max_i max(uq_i, 0)
+ *   rt = floor(sqrt(u' * 2^(24 + p))),  p = fl_sec_out[t] mod 2 in {0, 1}: the root on grid R = (fl_sec_out[t] + 24 + p) / 2
+ *   den = max(rt + min(RNE(eps_q16 * 2^-(16 + eps_exp - R)), 2^30), 1)
+ *   s  = cap(RNE(-lr_q16 * m' * 2^e / den)),  e = F + R - 16 - lr_exp - fl_mom_out[t]
+ *   v, theta', c', vmax_out exactly as in lpk_kahan_sgd_step with this s
+ *
+ * lr_t = lr_q16 * 2^-(16 + lr_exp), eps = eps_q16 * 2^-(16 + eps_exp): 16-bit mantissas, exponents 0..48.
+ * Domain, beyond that of lpk_kahan_sgd_step: the four moment fraclens in [-64, 64], each pair at most 15
+ * apart, and e <= 20; outside it the tensor is skipped and LPK_STATUS_DOMAIN raised.
+ * mmax_out, umax_out: device uint64[n_tensors] or NULL, cleared and rewritten by the call; feed them to
+ * lpk_select_fraclen(LPK_VMAX_U64, LPK_SEL_MOMENTUM / LPK_SEL_SECOND) to re-select the moments' fraclens.
+ * Errors: INVALID_ARG (NULL list / fraclen array / hyper, a mantissa above 65535, an exponent above 48, a
+ * non-empty tensor without momentum or second buffer), DEVICE.
+ */
+typedef struct {
+  uint32_t lr_q16, lr_exp;        /* bias-corrected step size lr_t = lr_q16 * 2^-(16 + lr_exp) */
+  uint32_t beta1_q16, beta2_q16;  /* Q0.16 */
+  uint32_t eps_q16, eps_exp;      /* eps = eps_q16 * 2^-(16 + eps_exp) */
+} lpk_adam_hyper;
+
+int lpk_adam_step(lpk_tensor_list* list,
+                  const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                  const int32_t* fl_mom_in, const int32_t* fl_mom_out,
+                  const int32_t* fl_sec_in, const int32_t* fl_sec_out, const int32_t* fl_grad,
+                  const lpk_adam_hyper* hyper /* host */,
+                  uint64_t* vmax_out, uint64_t* mmax_out, uint64_t* umax_out, uint32_t* status, void* stream);
 
 /*
  * Bit-width guideline for the last fully-connected layer (Section 3, eq. 4-5): the smallest width BW with

@@ -234,6 +234,7 @@ int lpk_ref_kahan_sgd_step(void *theta, void *comp, const void *grad, uint64_t n
     if (lr_q > 65535u || wd_q > 65535u) return LPK_REF_ERR_ARG;
     if (!comp) d = 0;
     if (vmax) *vmax = 0;
+    if (n == 0) return LPK_REF_OK;                    /* an empty tensor is a no-op: nothing to flag */
     int delta = fl_out - fl_in;
     if (fl_in < FL_MIN || fl_in > FL_MAX || fl_out < FL_MIN || fl_out > FL_MAX ||
         fl_g < FL_MIN || fl_g > FL_MAX || d < 0 || d > D_MAX ||
@@ -298,6 +299,7 @@ int lpk_ref_momentum_sgd_step(void *theta, void *comp, void *mom, const void *gr
     if (!comp) d = 0;
     if (vmax) *vmax = 0;
     if (mmax) *mmax = 0;
+    if (n == 0) return LPK_REF_OK;                    /* an empty tensor is a no-op: nothing to flag */
     int delta = fl_out - fl_in, delta_m = fl_m_out - fl_m_in;
     if (fl_in < FL_MIN || fl_in > FL_MAX || fl_out < FL_MIN || fl_out > FL_MAX || fl_g < FL_MIN || fl_g > FL_MAX ||
         fl_m_in < FL_MIN || fl_m_in > FL_MAX || fl_m_out < FL_MIN || fl_m_out > FL_MAX ||
@@ -402,6 +404,7 @@ int lpk_ref_adam_step(void *theta, void *comp, void *mom, void *sec, const void 
     if (vmax) *vmax = 0;
     if (mmax) *mmax = 0;
     if (umax) *umax = 0;
+    if (n == 0) return LPK_REF_OK;                    /* an empty tensor is a no-op: nothing to flag */
     const int delta = fl_out - fl_in, delta_m = fl_m_out - fl_m_in, delta_u = fl_u_out - fl_u_in;
     const int F = fl_in + d, Gm = fl_m_out + 16, Gu = fl_u_out + 16;
     const int par = ((fl_u_out % 2) + 2) % 2;

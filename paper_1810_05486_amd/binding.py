@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_HERE, "liblpk.so")
 
 LPK_OK, LPK_ERR_INVALID_ARG, LPK_ERR_UNSUPPORTED, LPK_ERR_DEVICE = 0, -1, -2, -3
 LPK_I8, LPK_I16, LPK_F32, LPK_VMAX_U64 = 1, 2, 4, 8
-LPK_SEL_GRAD, LPK_SEL_THETA, LPK_SEL_MOMENTUM = 0, 1, 2
+LPK_SEL_GRAD, LPK_SEL_THETA, LPK_SEL_MOMENTUM, LPK_SEL_SECOND = 0, 1, 2, 3
 LPK_STATUS_NONFINITE, LPK_STATUS_DOMAIN = 1, 2
 LPK_COMP_SHIFT_DEFAULT = 0xFF
 
@@ -22,8 +22,13 @@ class lpk_tensor_desc(ctypes.Structure):
                 ("src_f32", ctypes.c_void_p), ("n", ctypes.c_uint64),
                 ("theta_dtype", ctypes.c_uint8), ("comp_dtype", ctypes.c_uint8),
                 ("grad_dtype", ctypes.c_uint8), ("comp_shift", ctypes.c_uint8),
-                ("momentum_dtype", ctypes.c_uint8), ("reserved", ctypes.c_uint8 * 3),
-                ("momentum", ctypes.c_void_p)]
+                ("momentum_dtype", ctypes.c_uint8), ("second_dtype", ctypes.c_uint8), ("reserved", ctypes.c_uint8 * 2),
+                ("momentum", ctypes.c_void_p), ("second", ctypes.c_void_p)]
+
+
+class lpk_adam_hyper(ctypes.Structure):
+    _fields_ = [("lr_q16", ctypes.c_uint32), ("lr_exp", ctypes.c_uint32), ("beta1_q16", ctypes.c_uint32),
+                ("beta2_q16", ctypes.c_uint32), ("eps_q16", ctypes.c_uint32), ("eps_exp", ctypes.c_uint32)]
 
 
 class LpkError(RuntimeError):
@@ -57,6 +62,8 @@ def lib():
         L.lpk_kahan_sgd_step_f32grad.restype = ci
         L.lpk_momentum_sgd_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, u32, vp, vp, vp, vp]
         L.lpk_momentum_sgd_step.restype = ci
+        L.lpk_adam_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(lpk_adam_hyper), vp, vp, vp, vp, vp]
+        L.lpk_adam_step.restype = ci
         L.lpk_stream_copy.argtypes = [vp, vp, u64, vp]
         L.lpk_stream_copy.restype = ci
         L.lpk_stream_mix.argtypes = [vp, vp, vp, u64, vp]
@@ -105,7 +112,7 @@ def _check(rc, where):
         raise LpkError(rc, where)
 
 
-def make_desc(theta, comp, grad, src_f32=None, comp_shift=LPK_COMP_SHIFT_DEFAULT, momentum=None):
+def make_desc(theta, comp, grad, src_f32=None, comp_shift=LPK_COMP_SHIFT_DEFAULT, momentum=None, second=None):
     """Descriptor for one tensor from torch tensors living on the GPU."""
     d = lpk_tensor_desc()
     d.theta, d.comp, d.grad, d.src_f32 = _addr(theta), _addr(comp), _addr(grad), _addr(src_f32)
@@ -116,6 +123,8 @@ def make_desc(theta, comp, grad, src_f32=None, comp_shift=LPK_COMP_SHIFT_DEFAULT
     d.comp_shift = comp_shift
     d.momentum = _addr(momentum)
     d.momentum_dtype = _dtype_code(momentum) if momentum is not None else LPK_I8
+    d.second = _addr(second)
+    d.second_dtype = _dtype_code(second) if second is not None else LPK_I8
     return d
 
 
@@ -186,6 +195,16 @@ def lpk_momentum_sgd_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, 
                                        _addr(fl_mom_out), _addr(fl_grad), int(lr_q16), int(mu_q16), int(wd_q16),
                                        _addr(vmax_out), _addr(mmax_out), _addr(status), _stream(stream)),
            "lpk_momentum_sgd_step")
+
+
+def lpk_adam_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, hyper,
+                  vmax_out=None, mmax_out=None, umax_out=None, status=None, stream=None):
+    """hyper: an lpk_adam_hyper, or a tuple (lr_q16, lr_exp, beta1_q16, beta2_q16, eps_q16, eps_exp)."""
+    h = hyper if isinstance(hyper, lpk_adam_hyper) else lpk_adam_hyper(*[int(x) for x in hyper])
+    _check(lib().lpk_adam_step(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_mom_in), _addr(fl_mom_out),
+                               _addr(fl_sec_in), _addr(fl_sec_out), _addr(fl_grad), ctypes.byref(h),
+                               _addr(vmax_out), _addr(mmax_out), _addr(umax_out), _addr(status), _stream(stream)),
+           "lpk_adam_step")
 
 
 def lpk_stream_mix(a, b, c, nbytes, stream=None):

@@ -1,0 +1,263 @@
+// ADAM with the lazy update inside (paper, Section 4: the ADAM optimizer in INT16 with Algorithm 1 implemented in
+// the optimizer).  One fused launch over every tile of every tensor:
+//
+//   wM = RNE(b1*m on grid Gm) + cap(RNE((1-b1)*g on Gm));   mq = RNE(wM / 2^16);  m' = sat(mq)
+//   wU = RNE(b2*u on grid Gu) + cap(RNE((1-b2)*g^2 on Gu)); uq = RNE(wU / 2^16);  u' = clamp(uq, 0, qmax)
+//   rt = floor(sqrt(u' * 2^(24+p)));  den = max(rt + eps_R, 1);  s = cap(RNE(-lr*m'*2^e / den))
+//   then Algorithm 1 with step s.
+//
+// Arithmetic: everything runs on the fp64 unit, and every value is exact.  Each intermediate above is an integer
+// below 2^53 times a power of two (16-bit words times 17-bit constants, 2^40 caps, shifts of the documented
+// domain), so products, sums and scalings by powers of two are exact in binary64 and v_rndne_f64 is the
+// round-to-nearest-even of the definition, for every shift direction, without a branch.  The two inexact
+// operations are repaired with exact residuals: the root by the sign of fma(r, r, -A), the quotient by the
+// remainder fma(-q, den, num) compared with half the divisor (ties to even).
+//
+// Same work distribution as the plain update (persistent wavefronts over the tile table, 16 consecutive elements
+// per lane per pass, dwordx4 non-temporal accesses) for int16 moments and gradients on 16-byte aligned buffers;
+// anything else goes element by element through the same arithmetic.
+#include "step_common.hpp"
+
+namespace lpk {
+
+struct AdamParams {
+  int    path;                     // 0 skip, 1 element by element, 2 vector
+  int    wt, wc, wg, wm, wu, has_comp;
+  double a1, a2, a3, a4;           // b1 * 2^-k1, (65536 - b1) * 2^-k2, b2 * 2^-k4, (65536 - b2) * 2^-k5
+  double qmin_t, qmax_t, qmin_c, qmax_c, qmin_m, qmax_m, qmax_u;
+  double ascale;                   // 2^(24 + p): radicand scale
+  double eps_r;                    // eps on the root's grid, at most 2^30
+  double nlr;                      // -lr * 2^max(e, 0)
+  double dscale;                   // 2^max(-e, 0)
+  double p2d, p2u, inv_kth, p2kth, inv_kc;
+};
+
+struct AdamTrack { double vm, mm, um; };
+
+__device__ __forceinline__ double pow2d(int k) { return __longlong_as_double((long long)(1023 + k) << 52); }
+
+__device__ __forceinline__ double clampd(double x, double lo, double hi) { return __builtin_fmin(__builtin_fmax(x, lo), hi); }
+
+__device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, int m, int u, int g,
+                                            int& tn, int& cn, int& mn, int& un, AdamTrack& tr)
+{
+  const double cap = 1099511627776.0;                       // 2^40
+  const double gd = (double)g;
+  // first moment
+  const double t1 = __builtin_rint((double)m * p.a1);
+  const double t2 = clampd(__builtin_rint(gd * p.a2), -cap, cap);
+  const double mq = __builtin_rint((t1 + t2) * 0x1p-16);
+  tr.mm = __builtin_fmax(tr.mm, __builtin_fabs(mq));
+  const double mnew = clampd(mq, p.qmin_m, p.qmax_m);
+  // second moment
+  const double t3 = __builtin_rint((double)u * p.a3);
+  const double t4 = clampd(__builtin_rint(gd * gd * p.a4), -cap, cap);
+  const double uq = __builtin_rint((t3 + t4) * 0x1p-16);
+  tr.um = __builtin_fmax(tr.um, uq);
+  const double unew = clampd(uq, 0.0, p.qmax_u);
+  // root of the new second moment on its fixed grid: floor, repaired by exact residuals
+  const double A = unew * p.ascale;                         // an integer below 2^40
+  double r = __builtin_floor(__builtin_sqrt(A));
+  const double r1 = r + 1.0;
+  const bool too_big = __builtin_fma(r, r, -A) > 0.0, too_small = __builtin_fma(r1, r1, -A) <= 0.0;
+  r = too_big ? r - 1.0 : (too_small ? r1 : r);
+  const double den = __builtin_fmax(r + p.eps_r, 1.0) * p.dscale;
+  // step: RNE(num / den), the rounded quotient repaired by its exact remainder
+  const double num = mnew * p.nlr;
+  double q = __builtin_rint(num / den);
+  const double two_rem = 2.0 * __builtin_fma(-q, den, num);
+  const double hq = 0.5 * q;
+  const bool odd = hq != __builtin_floor(hq);
+  const bool up = two_rem > den || (two_rem == den && odd), down = two_rem < -den || (two_rem == -den && odd);
+  q += up ? 1.0 : (down ? -1.0 : 0.0);
+  const double s = clampd(q, -cap, cap);
+  // Algorithm 1 with this step
+  const double v = __builtin_fma((double)th, p.p2d, (double)c) + s;
+  tr.vm = __builtin_fmax(tr.vm, __builtin_fabs(v));
+  const double vG = v * p.p2u;
+  const double tnew = clampd(__builtin_rint(vG * p.inv_kth), p.qmin_t, p.qmax_t);
+  const double rr = __builtin_fma(-tnew, p.p2kth, vG);      // exact below 2^53; beyond that comp saturates either way
+  const double cnew = clampd(__builtin_rint(rr * p.inv_kc), p.qmin_c, p.qmax_c);
+  tn = (int)tnew; cn = (int)cnew; mn = (int)mnew; un = (int)unew;
+}
+
+// Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
+__device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
+{
+  for (uint32_t j = lane; j < cnt; j += kWave) {
+    const uint64_t i = off + j;
+    const int th = load_elem(T.theta, i, p.wt);
+    const int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
+    const int m  = load_elem(T.mom, i, p.wm);
+    const int u  = load_elem(T.sec, i, p.wu);
+    const int g  = load_elem(T.grad, i, p.wg);
+    int tn, cn, mn, un;
+    update_adam(p, th, c, m, u, g, tn, cn, mn, un, tr);
+    store_elem(T.theta, i, p.wt, tn);
+    if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
+    store_elem(T.mom, i, p.wm, mn);
+    store_elem(T.sec, i, p.wu, un);
+  }
+}
+
+// 16 consecutive elements per lane; int16 moments and gradients.
+template <int WT, int WC> struct AGroup {
+  v4i th[WT / 8], c[WC / 8], m[2], u[2], g[2];
+};
+
+template <int WT, int WC>
+__device__ __forceinline__ void load_group_adam(AGroup<WT, WC>& G, const TensorDev& T, uint64_t e)
+{
+  load16<WT>(G.th, T.theta, e); load16<WC>(G.c, T.comp, e);
+  load16<16>(G.m, T.mom, e); load16<16>(G.u, T.sec, e); load16<16>(G.g, T.grad, e);
+}
+
+template <int WT, int WC>
+__device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<WT, WC>& G, const TensorDev& T, uint64_t e, AdamTrack& tr)
+{
+  int tn[16], cn[16], mn[16], un[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k)
+    update_adam(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), elem16<16>(G.m, k), elem16<16>(G.u, k), elem16<16>(G.g, k),
+                tn[k], cn[k], mn[k], un[k], tr);
+  store16<WT>(T.theta, e, tn);
+  store16<WC>(T.comp, e, cn);
+  store16<16>(T.mom, e, mn);
+  store16<16>(T.sec, e, un);
+}
+
+template <int WT, int WC>
+__device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
+{
+  constexpr int kP = 2;                                    // groups in flight per lane
+  const uint32_t ngroups = cnt / kGroup;
+  uint32_t gi = lane;
+  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
+    AGroup<WT, WC> G[kP];
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps) load_group_adam(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps) group_adam<WT, WC>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
+  }
+  for (; gi < ngroups; gi += kWave) {
+    AGroup<WT, WC> G;
+    const uint64_t e = off + (uint64_t)gi * kGroup;
+    load_group_adam(G, T, e);
+    group_adam<WT, WC>(p, G, T, e, tr);
+  }
+  const uint32_t tail = cnt - ngroups * kGroup;
+  if (tail) tile_generic_adam(p, T, off + (uint64_t)ngroups * kGroup, tail, lane, tr);
+}
+
+// ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
+
+__device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, int fl_in, int fl_out, int fl_m_in, int fl_m_out,
+                                           int fl_u_in, int fl_u_out, int fl_g, const AdamHyperDev& h, uint32_t& status_bits)
+{
+  p.wt = T.wt; p.wc = T.wc; p.wg = T.wg; p.wm = T.wm; p.wu = T.wu; p.has_comp = T.comp != nullptr;
+  const int d = p.has_comp ? T.d : 0;
+  const int delta = fl_out - fl_in, delta_m = fl_m_out - fl_m_in, delta_u = fl_u_out - fl_u_in;
+  const int par = fl_u_out & 1;                             // two's complement: the non-negative parity
+  const int R = (fl_u_out + 24 + par) >> 1;                 // exact, the numerator is even
+  const int F = fl_in + d;
+  const int e = F + R - 16 - (int)h.lr_exp - fl_m_out;
+  auto bad = [](int f) { return f < kFlMin || f > kFlMax; };
+  auto far = [](int x) { return x > kDeltaMax || x < -kDeltaMax; };
+  if (bad(fl_in) || bad(fl_out) || bad(fl_m_in) || bad(fl_m_out) || bad(fl_u_in) || bad(fl_u_out) || bad(fl_g) ||
+      d > kDMax || far(delta) || far(delta_m) || far(delta_u) || e > 20) {
+    p.path = 0; status_bits |= kStatusDomain; return;
+  }
+  p.a1 = (double)h.b1 * pow2d(delta_m);                     // b1 * 2^-(fl_m_in - fl_m_out)
+  p.a2 = (double)(65536u - h.b1) * pow2d(fl_m_out - fl_g);
+  p.a3 = (double)h.b2 * pow2d(delta_u);
+  p.a4 = (double)(65536u - h.b2) * pow2d(fl_u_out - 2 * fl_g);
+  p.qmax_t = (double)((1 << (p.wt - 1)) - 1); p.qmin_t = -(double)(1 << (p.wt - 1));
+  const int wc = p.has_comp ? p.wc : 8;
+  p.qmax_c = (double)((1 << (wc - 1)) - 1);   p.qmin_c = -(double)(1 << (wc - 1));
+  p.qmax_m = (double)((1 << (p.wm - 1)) - 1); p.qmin_m = -(double)(1 << (p.wm - 1));
+  p.qmax_u = (double)((1 << (p.wu - 1)) - 1);
+  p.ascale = pow2d(24 + par);
+  p.eps_r  = __builtin_fmin(__builtin_rint((double)h.eps * pow2d(R - 16 - (int)h.eps_exp)), 1073741824.0);
+  p.nlr    = -(double)h.lr * pow2d(e > 0 ? e : 0);
+  p.dscale = pow2d(e < 0 ? -e : 0);
+  const int u = delta > 0 ? delta : 0, kth = d + u - delta, kc = kth - d;
+  p.p2d = pow2d(d); p.p2u = pow2d(u); p.inv_kth = pow2d(-kth); p.p2kth = pow2d(kth); p.inv_kc = pow2d(-kc);
+  p.path = 1;
+  const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
+  if (p.has_comp && T.vec_adam && widths_ok && p.wg == 16 && p.wm == 16 && p.wu == 16) p.path = 2;
+}
+
+// ---------------------------------------------------------------- the kernel
+
+__device__ __forceinline__ uint64_t track_u64(double x) { return (uint64_t)x; }     // an integer below 2^53
+
+__global__ void __launch_bounds__(kBlock)
+adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
+                 const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out,
+                 const int32_t* __restrict__ fl_m_in, const int32_t* __restrict__ fl_m_out,
+                 const int32_t* __restrict__ fl_u_in, const int32_t* __restrict__ fl_u_out, const int32_t* __restrict__ fl_g,
+                 AdamHyperDev h, uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status)
+{
+  __shared__ int      s_tensor[kWavesPerBlock];
+  __shared__ uint64_t s_max[kWavesPerBlock];
+
+  const int lane   = threadIdx.x & (kWave - 1);
+  const int wave   = wave_uniform(threadIdx.x >> 6);
+  const uint32_t w0 = blockIdx.x * kWavesPerBlock + wave;
+  const uint32_t nw = gridDim.x * kWavesPerBlock;
+
+  int cur = -1;
+  AdamTrack tr{0.0, 0.0, 0.0};
+  uint32_t status_bits = 0;
+  AdamParams p; p.path = 0;
+  TensorDev T;
+
+  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
+    int t; uint32_t cnt; uint64_t off;
+    read_tile(tiles, ti, t, cnt, off);
+    if (t != cur) {
+      if (cur >= 0) {
+        if (vmax) flush_wave(vmax, cur, track_u64(tr.vm), lane);
+        if (mmax) flush_wave(mmax, cur, track_u64(tr.mm), lane);
+        if (umax) flush_wave(umax, cur, track_u64(tr.um), lane);
+      }
+      tr = AdamTrack{0.0, 0.0, 0.0};
+      cur = t;
+      T = tensors[t];
+      setup_adam(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_u_in[t], fl_u_out[t], fl_g[t], h, status_bits);
+    }
+    if (p.path == 2) {
+      if (p.wt == 8 && p.wc == 8) tile_vec_adam<8, 8>(p, T, off, cnt, lane, tr);
+      else if (p.wt == 16)        tile_vec_adam<16, 16>(p, T, off, cnt, lane, tr);
+      else                        tile_vec_adam<8, 16>(p, T, off, cnt, lane, tr);
+    } else if (p.path == 1) {
+      tile_generic_adam(p, T, off, cnt, lane, tr);
+    }
+  }
+
+  if (status && status_bits && lane == 0) atomicOr(status, status_bits);
+  if (vmax) flush_block(vmax, cur, track_u64(tr.vm), lane, wave, s_tensor, s_max);
+  if (mmax) flush_block(mmax, cur, track_u64(tr.mm), lane, wave, s_tensor, s_max);
+  if (umax) flush_block(umax, cur, track_u64(tr.um), lane, wave, s_tensor, s_max);
+}
+
+__global__ void __launch_bounds__(kBlock) fill3_u64_kernel(uint64_t* a, uint64_t* b, uint64_t* c, uint32_t n)
+{
+  const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) { if (a) a[i] = 0; if (b) b[i] = 0; if (c) c[i] = 0; }
+}
+
+hipError_t launch_adam_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
+                            const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
+                            const int32_t* fl_u_in, const int32_t* fl_u_out, const int32_t* fl_g, AdamHyperDev h,
+                            uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, hipStream_t stream)
+{
+  if (vmax || mmax || umax)
+    hipLaunchKernelGGL(fill3_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, mmax, umax, n_tensors);
+  if (n_tiles)
+    hipLaunchKernelGGL(adam_step_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                       fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, h, vmax, mmax, umax, status);
+  return hipGetLastError();
+}
+
+}  // namespace lpk

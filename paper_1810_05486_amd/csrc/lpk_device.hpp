@@ -55,7 +55,7 @@ constexpr int kTileElems      = kPassElems * kPasses;    // 4096 elements per wa
 constexpr int kFlMin = -64, kFlMax = 64, kDMax = 24, kDeltaMax = 15;
 constexpr uint32_t kStatusNonFinite = 1u, kStatusDomain = 2u;
 
-// One tensor, as the kernels see it (64 bytes, read with scalar loads).
+// One tensor, as the kernels see it (72 bytes, read with scalar loads).
 struct TensorDev {
   void*       theta;
   void*       comp;      // nullptr: no accumulator
@@ -64,10 +64,11 @@ struct TensorDev {
   uint64_t    n;
   uint8_t     wt, wc, wg, d;        // widths in bits (wc = 0 without comp), comp shift
   uint8_t     vec_step, vec_src_grad, vec_src_theta, wm;     // 16-byte alignment facts; velocity width (0 = none)
-  void*       mom;       // velocity of the momentum update, nullptr = none
-  uint8_t     vec_mom, pad0[7];
+  void*       mom;       // velocity of the momentum update / first moment of ADAM, nullptr = none
+  uint8_t     vec_mom, wu, vec_adam, pad0[5];                // wu: width of the second moment (0 = none)
+  void*       sec;       // second moment of ADAM, nullptr = none
 };
-static_assert(sizeof(TensorDev) == 64, "descriptor layout");
+static_assert(sizeof(TensorDev) == 72, "descriptor layout");
 
 // One wave-sized piece of one tensor.
 struct Tile {
@@ -76,6 +77,9 @@ struct Tile {
   uint64_t offset;       // first element, a multiple of kTileElems
 };
 static_assert(sizeof(Tile) == 16, "tile layout");
+
+// Hyper-parameters of the ADAM update as the kernel receives them (by value).
+struct AdamHyperDev { uint32_t lr, lr_exp, b1, b2, eps, eps_exp; };
 
 // ---- wavefront max over unsigned 32-bit values, via DPP -------------------
 // Row shifts build the maximum of each 16-lane row in its last lane, two row

@@ -25,6 +25,10 @@ hipError_t launch_momentum_step(const TensorDev*, const Tile*, uint32_t n_tiles,
                                 const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                                 const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
                                 uint64_t* vmax, uint64_t* mmax, uint32_t* status, hipStream_t);
+hipError_t launch_adam_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
+                            const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
+                            const int32_t* fl_u_in, const int32_t* fl_u_out, const int32_t* fl_g, AdamHyperDev h,
+                            uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, hipStream_t);
 }  // namespace lpk
 
 using namespace lpk;
@@ -37,6 +41,7 @@ struct lpk_tensor_list {
   uint32_t   grid_step = 0;        // blocks of the persistent update launches
   bool       all_src   = false;    // every non-empty tensor has an fp32 source
   bool       all_mom   = false;    // every non-empty tensor has a velocity buffer
+  bool       all_sec   = false;    // ... and a second-moment buffer
   TensorDev* d_tensors = nullptr;
   Tile*      d_tiles   = nullptr;
   uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls
@@ -63,7 +68,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
 
   std::vector<TensorDev> tensors(n_tensors);
   std::vector<Tile> tiles;
-  bool all_src = true, all_mom = true;
+  bool all_src = true, all_mom = true, all_sec = true;
   uint64_t total_tiles = 0;
   for (uint32_t t = 0; t < n_tensors; ++t) {
     const lpk_tensor_desc& D = descs[t];
@@ -82,6 +87,9 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     const int wm = D.momentum ? dtype_bits(D.momentum_dtype) : 0;
     if (D.momentum && (!wm || !aligned(D.momentum, wm / 8))) return LPK_ERR_INVALID_ARG;
     if (D.n && !D.momentum) all_mom = false;
+    const int wu = D.second ? dtype_bits(D.second_dtype) : 0;
+    if (D.second && (!wu || !aligned(D.second, wu / 8))) return LPK_ERR_INVALID_ARG;
+    if (D.n && !D.second) all_sec = false;
 
     TensorDev& T = tensors[t];
     T = TensorDev{};
@@ -92,6 +100,8 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     T.vec_src_theta = D.src_f32 && aligned(D.src_f32, 16) && aligned(D.theta, 16);
     T.mom = D.momentum; T.wm = (uint8_t)wm;
     T.vec_mom = T.vec_step && D.momentum && aligned(D.momentum, 16);
+    T.sec = D.second; T.wu = (uint8_t)wu;
+    T.vec_adam = T.vec_mom && D.second && aligned(D.second, 16);
     total_tiles += (D.n + kTileElems - 1) / kTileElems;
   }
   if (total_tiles >= (1ull << 31)) return LPK_ERR_UNSUPPORTED;
@@ -108,6 +118,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   L->n_tiles = (uint32_t)tiles.size();
   L->all_src = all_src;
   L->all_mom = all_mom;
+  L->all_sec = all_sec;
 
   hipDeviceProp_t prop;
   bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
@@ -160,8 +171,10 @@ int lpk_select_fraclen(lpk_tensor_list* L, int src_kind, int dst_sel,
                        int32_t* fl_out, uint32_t* status, void* stream)
 {
   if (!L || !fl_default || !fl_out) return LPK_ERR_INVALID_ARG;
-  if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA && dst_sel != LPK_SEL_MOMENTUM) return LPK_ERR_INVALID_ARG;
+  if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA && dst_sel != LPK_SEL_MOMENTUM && dst_sel != LPK_SEL_SECOND)
+    return LPK_ERR_INVALID_ARG;
   if (dst_sel == LPK_SEL_MOMENTUM && (src_kind != LPK_VMAX_U64 || !L->all_mom)) return LPK_ERR_INVALID_ARG;
+  if (dst_sel == LPK_SEL_SECOND && (src_kind != LPK_VMAX_U64 || !L->all_sec)) return LPK_ERR_INVALID_ARG;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (src_kind == LPK_F32) {
@@ -223,6 +236,23 @@ int lpk_momentum_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const 
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
+int lpk_adam_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                  const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_sec_in, const int32_t* fl_sec_out,
+                  const int32_t* fl_grad, const lpk_adam_hyper* hyper,
+                  uint64_t* vmax_out, uint64_t* mmax_out, uint64_t* umax_out, uint32_t* status, void* stream)
+{
+  if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_sec_in || !fl_sec_out || !fl_grad || !hyper)
+    return LPK_ERR_INVALID_ARG;
+  if (hyper->lr_q16 > 65535u || hyper->beta1_q16 > 65535u || hyper->beta2_q16 > 65535u || hyper->eps_q16 > 65535u ||
+      hyper->lr_exp > 48u || hyper->eps_exp > 48u) return LPK_ERR_INVALID_ARG;
+  if (!L->all_mom || !L->all_sec) return LPK_ERR_INVALID_ARG;
+  const AdamHyperDev h{hyper->lr_q16, hyper->lr_exp, hyper->beta1_q16, hyper->beta2_q16, hyper->eps_q16, hyper->eps_exp};
+  hipError_t e = launch_adam_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_step, fl_theta_in, fl_theta_out,
+                                  fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, h, vmax_out, mmax_out, umax_out, status,
+                                  static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
 int lpk_stream_copy(void* dst, const void* src, uint64_t nbytes, void* stream)
 {
   if (nbytes == 0) return LPK_OK;
@@ -272,6 +302,6 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
   return bw;
 }
 
-int lpk_version(void) { return 104; }
+int lpk_version(void) { return 105; }
 
 }  // extern "C"

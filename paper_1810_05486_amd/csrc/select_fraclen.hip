@@ -127,9 +127,10 @@ fraclen_from_vmax_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tenso
 {
   uint32_t t = blockIdx.x * kBlock + threadIdx.x;
   if (t >= n_tensors) return;
-  // sel: 0 gradient width, 1 theta width (vmax on grid fl + d), 2 velocity width (mmax on the velocity's own grid)
-  const int W = sel == 1 ? tensors[t].wt : (sel == 2 ? tensors[t].wm : tensors[t].wg);
-  const int d = sel == 2 ? 0 : (tensors[t].comp ? tensors[t].d : 0);
+  // sel: 0 gradient width, 1 theta width (vmax on grid fl + d), 2 velocity / first-moment width and 3 second-moment
+  // width (maxima on the state's own grid)
+  const int W = sel == 1 ? tensors[t].wt : (sel == 2 ? tensors[t].wm : (sel == 3 ? tensors[t].wu : tensors[t].wg));
+  const int d = sel >= 2 ? 0 : (tensors[t].comp ? tensors[t].d : 0);
   const int F = fl_theta_in[t] + d;
   const int cur = fl_default[t];
   if (F < kFlMin || F > kFlMax + kDMax || cur < kFlMin || cur > kFlMax) {

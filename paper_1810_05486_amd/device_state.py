@@ -27,10 +27,12 @@ def _offsets(sizes, elem_bytes):
 
 
 class DeviceState:
-    def __init__(self, cfg, device="cuda:0", kahan=True, n_src=1, comp_bits=None, mom_bits=None, fl_mom0=16):
+    def __init__(self, cfg, device="cuda:0", kahan=True, n_src=1, comp_bits=None, mom_bits=None, fl_mom0=16,
+                 sec_bits=None, fl_sec0=40):
         """cfg: workloads.Config.  n_src: how many fp32 source arenas stay resident (gradient cycle).
         comp_bits: per-tensor width of comp when it differs from theta's.  mom_bits: per-tensor width of a
-        velocity tensor (momentum update); its fraclen starts at fl_mom0 and is re-selected every step."""
+        velocity tensor (momentum update; ADAM's first moment); its fraclen starts at fl_mom0 and is re-selected
+        every step.  sec_bits: per-tensor width of ADAM's second moment, fraclen from fl_sec0, re-selected too."""
         self.cfg, self.device, self.kahan = cfg, torch.device(device), kahan
         nt = cfg.n_tensors
         tb = [b // 8 for b in cfg.bits]
@@ -55,6 +57,12 @@ class DeviceState:
             self.off_mom, tot_m = _offsets(cfg.sizes, mb)
             self.arena_mom = torch.zeros(tot_m, dtype=torch.uint8, device=dev)
 
+        self.sec_bits = list(sec_bits) if sec_bits is not None else None
+        if self.sec_bits:
+            sb = [b // 8 for b in self.sec_bits]
+            self.off_sec, tot_u = _offsets(cfg.sizes, sb)
+            self.arena_sec = torch.zeros(tot_u, dtype=torch.uint8, device=dev)
+
         def view(arena, off, n, eb, dtype):
             return arena[off:off + n * eb].view(dtype)
 
@@ -66,10 +74,12 @@ class DeviceState:
 
         self.mom = ([view(self.arena_mom, o, n, e, dt[e]) for o, n, e in zip(self.off_mom, cfg.sizes, mb)]
                     if self.mom_bits else [None] * nt)
+        self.sec = ([view(self.arena_sec, o, n, e, dt[e]) for o, n, e in zip(self.off_sec, cfg.sizes, sb)]
+                    if self.sec_bits else [None] * nt)
         self.lists = []
         for k in range(n_src):
-            descs = [lpk.make_desc(self.theta[t], self.comp[t], self.grad[t], self.src[k][t], momentum=self.mom[t])
-                     for t in range(nt)]
+            descs = [lpk.make_desc(self.theta[t], self.comp[t], self.grad[t], self.src[k][t], momentum=self.mom[t],
+                                   second=self.sec[t]) for t in range(nt)]
             self.lists.append(lpk.TensorList(descs))
 
         i32 = dict(dtype=torch.int32, device=dev)
@@ -80,6 +90,10 @@ class DeviceState:
         self.fl_mom = torch.full((nt,), fl_mom0, **i32)                    # grid the velocity is on now
         self.fl_mom_next = self.fl_mom.clone()
         self.fl_mom_spare = self.fl_mom.clone()
+        self.fl_sec = torch.full((nt,), fl_sec0, **i32)                    # grid the second moment is on now
+        self.fl_sec_next = self.fl_sec.clone()
+        self.fl_sec_spare = self.fl_sec.clone()
+        self.umax = torch.zeros(nt, dtype=torch.int64, device=dev)         # uint64 payload
         self.mmax = torch.zeros(nt, dtype=torch.int64, device=dev)         # uint64 payload
         self.vmax = torch.zeros(nt, dtype=torch.int64, device=dev)         # uint64 payload
         self.status = torch.zeros(1, dtype=torch.int32, device=dev)        # uint32 payload
@@ -146,6 +160,23 @@ class DeviceState:
         lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_MOMENTUM, self.mmax, self.fl_mom_next,
                                self.fl_mom_next, self.fl_mom_spare, self.status)
         self.fl_mom, self.fl_mom_next, self.fl_mom_spare = self.fl_mom_next, self.fl_mom_spare, self.fl_mom
+
+    def update_adam(self, hyper, k=0):
+        """ADAM with the lazy update inside; both moments move to the grids chosen one step earlier, and the grids
+        after those are re-selected from this step's mmax / umax (one-step lag), like theta's in `update`."""
+        L = self.lists[k]
+        lpk.lpk_adam_step(L, self.fl_theta, self.fl_next, self.fl_mom, self.fl_mom_next, self.fl_sec, self.fl_sec_next,
+                          self.fl_grad, hyper, self.vmax, self.mmax, self.umax, self.status)
+        if self.cfg.reselect:
+            lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_THETA, self.vmax, self.fl_theta,
+                                   self.fl_next, self.fl_spare, self.status)
+            self.fl_theta, self.fl_next, self.fl_spare = self.fl_next, self.fl_spare, self.fl_theta
+        lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_MOMENTUM, self.mmax, self.fl_mom_next,
+                               self.fl_mom_next, self.fl_mom_spare, self.status)
+        self.fl_mom, self.fl_mom_next, self.fl_mom_spare = self.fl_mom_next, self.fl_mom_spare, self.fl_mom
+        lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_SECOND, self.umax, self.fl_sec_next,
+                               self.fl_sec_next, self.fl_sec_spare, self.status)
+        self.fl_sec, self.fl_sec_next, self.fl_sec_spare = self.fl_sec_next, self.fl_sec_spare, self.fl_sec
 
     def step_fused(self, step_idx, k=0):
         """The whole path with quantization fused into the update: max-abs fraclen selection, then one pass that

@@ -183,3 +183,23 @@ def config(cid, big_elems=1 << 30, n_tiny=10000):
         return Config(5, "stress: one %d-element int8 tensor + %d tensors of 256" % (big_elems, n_tiny), sh,
                       [8] * len(sh), 50, [(0, 655)], 0, "normal_1e-3", False, grad_cycle=3)
     raise ValueError("config id must be 1..5")
+
+
+def q16_pair(x):
+    """A positive real as a 16-bit mantissa and an exponent: x ~ q * 2^-(16 + e), 0 <= e <= 48, the largest e that
+    keeps q within 16 bits (host-side scalar conversion, like the Q0.16 learning rates above)."""
+    if x <= 0.0:
+        return 0, 0
+    e = 0
+    while e < 48 and x * 2.0 ** (16 + e + 1) <= 65535.0:
+        e += 1
+    return min(65535, int(round(x * 2.0 ** (16 + e)))), e
+
+
+def adam_hyper(step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8):
+    """(lr_q16, lr_exp, beta1_q16, beta2_q16, eps_q16, eps_exp) for the 0-based `step`: the betas as Q0.16, the
+    bias corrections 1 - beta^t (t = step + 1, with the quantized betas) folded into the step size."""
+    b1_q, b2_q = int(round(beta1 * 65536)), int(round(beta2 * 65536))
+    t = step + 1
+    lr_t = lr * (1.0 - (b2_q / 65536.0) ** t) ** 0.5 / (1.0 - (b1_q / 65536.0) ** t)
+    return q16_pair(lr_t) + (b1_q, b2_q) + q16_pair(eps)

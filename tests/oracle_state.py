@@ -15,7 +15,7 @@ THREADS = max(1, min(16, len(os.sched_getaffinity(0))))
 
 
 class OracleState:
-    def __init__(self, cfg, kahan=True, comp_bits=None, mom_bits=None, fl_mom0=16):
+    def __init__(self, cfg, kahan=True, comp_bits=None, mom_bits=None, fl_mom0=16, sec_bits=None, fl_sec0=40):
         self.cfg, self.kahan = cfg, kahan
         nt = cfg.n_tensors
         self.comp_bits = list(comp_bits) if comp_bits is not None else list(cfg.bits)
@@ -34,6 +34,12 @@ class OracleState:
         self.fl_mom = [fl_mom0] * nt
         self.fl_mom_next = [fl_mom0] * nt
         self.mmax = [0] * nt
+        self.sec_bits = list(sec_bits) if sec_bits is not None else None
+        if self.sec_bits:
+            self.sec = [np.zeros(n, dtype=DT[b]) for n, b in zip(cfg.sizes, self.sec_bits)]
+        self.fl_sec = [fl_sec0] * nt
+        self.fl_sec_next = [fl_sec0] * nt
+        self.umax = [0] * nt
 
     def init_theta(self, theta0):
         for t, x in enumerate(theta0):
@@ -70,6 +76,25 @@ class OracleState:
                                                    self.fl_mom_next[t], self.status)
         self.fl_theta, self.fl_next = self.fl_next, new_next
         self.fl_mom, self.fl_mom_next = self.fl_mom_next, new_mnext
+
+    def update_adam(self, hyper):
+        """hyper = (lr_q16, lr_exp, beta1_q16, beta2_q16, eps_q16, eps_exp)."""
+        new_next, new_mnext, new_unext = list(self.fl_next), list(self.fl_mom_next), list(self.fl_sec_next)
+        for t in range(self.cfg.n_tensors):
+            self.vmax[t], self.mmax[t], self.umax[t] = ref.adam_step_mt(
+                self.theta[t], self.comp[t], self.mom[t], self.sec[t], self.grad[t], self.d[t], self.fl_theta[t], self.fl_next[t],
+                self.fl_mom[t], self.fl_mom_next[t], self.fl_sec[t], self.fl_sec_next[t], self.fl_grad[t], *hyper,
+                status=self.status, threads=THREADS)
+            if self.cfg.reselect:
+                new_next[t] = ref.select_fraclen_vmax(self.vmax[t], self.fl_theta[t] + self.d[t], self.cfg.bits[t],
+                                                      self.fl_next[t], self.status)
+            new_mnext[t] = ref.select_fraclen_vmax(self.mmax[t], self.fl_mom_next[t], self.mom_bits[t],
+                                                   self.fl_mom_next[t], self.status)
+            new_unext[t] = ref.select_fraclen_vmax(self.umax[t], self.fl_sec_next[t], self.sec_bits[t],
+                                                   self.fl_sec_next[t], self.status)
+        self.fl_theta, self.fl_next = self.fl_next, new_next
+        self.fl_mom, self.fl_mom_next = self.fl_mom_next, new_mnext
+        self.fl_sec, self.fl_sec_next = self.fl_sec_next, new_unext
 
     def step(self, step_idx, grads, mu_q16=None):
         self.quantize_grads(grads)

@@ -34,7 +34,9 @@ def test_binding_has_the_same_names():
 
 
 def test_descriptor_layout_matches_header():
-    assert ctypes.sizeof(lpk.lpk_tensor_desc) == 56 and lpk.lpk_tensor_desc.momentum.offset == 48
+    assert ctypes.sizeof(lpk.lpk_tensor_desc) == 64 and lpk.lpk_tensor_desc.momentum.offset == 48
+    assert lpk.lpk_tensor_desc.second.offset == 56 and lpk.lpk_tensor_desc.second_dtype.offset == 45
+    assert ctypes.sizeof(lpk.lpk_adam_hyper) == 24
     assert lpk.lpk_tensor_desc.n.offset == 32 and lpk.lpk_tensor_desc.comp_shift.offset == 43
 
 

@@ -1,0 +1,199 @@
+"""ADAM with the lazy update inside: GPU library vs CPU oracle, bit for bit (needs an MI355X)."""
+import random
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+from oracle import ref
+from paper_1810_05486_amd import binding as lpk
+from paper_1810_05486_amd import workloads
+from oracle_state import OracleState
+
+NP = {8: np.int8, 16: np.int16}
+TT = {8: torch.int8, 16: torch.int16}
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def u64(t):
+    return t.cpu().numpy().view(np.uint64).tolist()
+
+
+def compare(dev, host, what):
+    th, co, fl_t, fl_g, vm, status = dev.download()
+    assert status == int(host.status[0]), (what, "status", status, int(host.status[0]))
+    assert fl_t.tolist() == list(host.fl_theta) and fl_g.tolist() == list(host.fl_grad), (what, "fraclens")
+    assert dev.fl_mom.cpu().tolist() == list(host.fl_mom), (what, "fl_mom")
+    assert dev.fl_sec.cpu().tolist() == list(host.fl_sec), (what, "fl_sec", dev.fl_sec.cpu().tolist()[:8], host.fl_sec[:8])
+    assert vm.tolist() == list(host.vmax), (what, "vmax")
+    assert u64(dev.mmax) == list(host.mmax), (what, "mmax")
+    assert u64(dev.umax) == list(host.umax), (what, "umax")
+    for t in range(host.cfg.n_tensors):
+        assert np.array_equal(th[t], host.theta[t]), (what, "theta", t)
+        assert np.array_equal(co[t], host.comp[t]), (what, "comp", t)
+        assert np.array_equal(dev.mom[t].cpu().numpy(), host.mom[t]), (what, "mom", t)
+        assert np.array_equal(dev.sec[t].cpu().numpy(), host.sec[t]), (what, "sec", t)
+
+
+def run_config(cfg, steps, lr=1e-3, eps=1e-8, comp_bits=None, fl_mom0=24, fl_sec0=38, state_bits=16):
+    from paper_1810_05486_amd.device_state import DeviceState
+    bits = [state_bits] * cfg.n_tensors
+    kw = dict(comp_bits=comp_bits, mom_bits=bits, sec_bits=bits, fl_mom0=fl_mom0, fl_sec0=fl_sec0)
+    dev, host = DeviceState(cfg, **kw), OracleState(cfg, **kw)
+    views = dev.host_src_views()
+    theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
+    dev.upload_src()
+    dev.init_theta()
+    host.init_theta(theta0)
+    for s in steps:
+        grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
+        dev.upload_src()
+        hyper = workloads.adam_hyper(s, lr=lr, eps=eps)
+        dev.quantize_grads()
+        dev.update_adam(hyper)
+        host.quantize_grads(grads)
+        host.update_adam(hyper)
+        compare(dev, host, "config %d step %d" % (cfg.id, s))
+    dev.close()
+    return host
+
+
+def test_adam_config1_int8_theta_int16_moments():
+    say("adam: config 1, int8 theta and accumulator, int16 moments, 60 steps")
+    host = run_config(workloads.config(1), range(60))
+    assert int(host.status[0]) == 0
+    assert np.abs(host.mom[0].astype(int)).max() > 2000 and host.sec[0].max() > 2000      # both grids settled and in use
+    assert len(np.unique(host.theta[0])) > 50
+
+
+def test_adam_lenet_int16_everything_reselect():
+    say("adam: LeNet shapes, all int16, theta and both moment grids re-selected every step")
+    run_config(workloads.config(2), range(30), lr=2e-3, eps=1e-6)
+
+
+def test_adam_resnet50_mixed_widths():
+    say("adam: ResNet-50 shapes, int8 theta with the int16 classifier")
+    run_config(workloads.config(4), range(4), fl_mom0=36, fl_sec0=60)
+
+
+def test_adam_int8_theta_with_int16_accumulator():
+    say("adam: ResNet-18 shapes, int8 theta with an int16 accumulator (22-bit parameter)")
+    cfg = workloads.config(3)
+    run_config(cfg, [0, 1, 2, 40], comp_bits=[16] * cfg.n_tensors, fl_mom0=28, fl_sec0=46)
+
+
+def test_adam_config5_reduced_and_int8_moments():
+    say("adam: config 5 shape at reduced size; then 8-bit moments (element path)")
+    cfg = workloads.config(5, big_elems=(1 << 22) + 21, n_tiny=200)
+    run_config(cfg, range(4))
+    run_config(workloads.config(5, big_elems=70001, n_tiny=20), range(3), state_bits=8, fl_mom0=16, fl_sec0=30)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_adam_random_lists(seed):
+    """Random widths, shifts, grid moves, alignments, sizes and hyper-parameters straight through the C ABI,
+    including tensors that fall outside the domain (skipped and flagged on both sides)."""
+    say("adam: random lists, seed %d" % seed)
+    rng = np.random.default_rng(800 + seed)
+    pr = random.Random(900 + seed)
+    sizes = [0, 1, 15, 16, 17, 255, 1024, 4095, 4096, 4097, 9001, 33000]
+    for rep in range(8):
+        cases = []
+        for _ in range(pr.randint(1, 10)):
+            tb = pr.choice([8, 16])
+            mb, ub = pr.choice([(16, 16), (16, 16), (16, 16), (8, 16), (16, 8), (8, 8)])
+            cb = pr.choice([tb, tb, tb, 8, 16, 0])
+            gb = pr.choice([16, 16, 16, 8])
+            d = pr.choice([None, None, pr.randint(0, 24)]) if cb else None
+            fl_in = pr.randint(-10, 20)
+            delta = pr.choice([0, 0, 0, 0, 1, -1, pr.randint(-15, 15)])
+            fl_g = pr.randint(0, 40)
+            fl_m_in = fl_g + pr.choice([0, 1, -1, pr.randint(-12, 12)])
+            fl_m_out = fl_m_in + pr.choice([0, 0, 0, 0, 1, -1, pr.randint(-15, 15)])
+            fl_u_in = 2 * fl_g + pr.choice([0, -3, pr.randint(-25, 8), pr.randint(-40, 30)])
+            fl_u_out = fl_u_in + pr.choice([0, 0, 0, 0, 1, -1, pr.randint(-15, 15)])
+            fls = [max(-64, min(64, f)) for f in (fl_in, fl_in + delta, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g)]
+            n = pr.choice(sizes)
+            mis = pr.choice([0, 0, 0, 1, 8, 16])
+            c = dict(n=n, tb=tb, cb=cb, mb=mb, ub=ub, gb=gb, d=d, fls=fls)
+            c["theta"] = rng.integers(-(2 ** (tb - 1)), 2 ** (tb - 1), size=n).astype(NP[tb])
+            c["comp"] = rng.integers(-(2 ** (cb - 1)), 2 ** (cb - 1), size=n).astype(NP[cb]) if cb else None
+            c["mom"] = rng.integers(-(2 ** (mb - 1)), 2 ** (mb - 1), size=n).astype(NP[mb])
+            lo_u = pr.choice([0, 0, 0, -(2 ** (ub - 1))])                       # mostly valid (non-negative) second moments
+            c["sec"] = rng.integers(lo_u, pr.choice([4, 300, 2 ** (ub - 1)]), size=n).astype(NP[ub])
+            c["grad"] = rng.integers(-(2 ** (gb - 1)), 2 ** (gb - 1), size=n).astype(NP[gb])
+
+            def dev(a, bits):
+                buf = torch.zeros(n + 64, dtype=TT[bits], device=DEV)
+                v = buf[mis:mis + n]
+                v.copy_(torch.from_numpy(a))
+                return buf, v
+            c["bufs"] = []
+            for key, bits in (("theta", tb), ("comp", cb), ("mom", mb), ("sec", ub), ("grad", gb)):
+                if c[key] is None:
+                    c["d_" + key] = None
+                    continue
+                b, v = dev(c[key], bits)
+                c["bufs"].append(b); c["d_" + key] = v
+            cases.append(c)
+        hyper = (pr.choice([1, 66, 21000, 65535]), pr.choice([0, 0, 4, 11, pr.randint(0, 48)]),
+                 pr.choice([58982, 32768, 0, 65535]), pr.choice([65470, 58982, 0, 65535]),
+                 pr.choice([0, 43980, 65535, 1]), pr.choice([0, 26, 10, pr.randint(0, 48)]))
+        tl = lpk.TensorList([lpk.make_desc(c["d_theta"], c["d_comp"], c["d_grad"], None,
+                                           c["d"] if c["cb"] and c["d"] is not None else lpk.LPK_COMP_SHIFT_DEFAULT,
+                                           momentum=c["d_mom"], second=c["d_sec"]) for c in cases])
+        i32 = dict(dtype=torch.int32, device=DEV)
+        arr = [torch.tensor([c["fls"][j] for c in cases], **i32) for j in range(7)]
+        vmax, mmax, umax = (torch.full((len(cases),), 5 + k, dtype=torch.int64, device=DEV) for k in range(3))
+        status = torch.zeros(1, dtype=torch.int32, device=DEV)
+        lpk.lpk_adam_step(tl, arr[0], arr[1], arr[2], arr[3], arr[4], arr[5], arr[6], hyper, vmax, mmax, umax, status)
+        torch.cuda.synchronize()
+        st = ref.new_status()
+        for i, c in enumerate(cases):
+            dd = c["d"] if c["d"] is not None else (c["cb"] - 1 if c["cb"] else 0)
+            f = c["fls"]
+            want = ref.adam_step(c["theta"], c["comp"], c["mom"], c["sec"], c["grad"], dd, f[0], f[1], f[2], f[3], f[4], f[5], f[6],
+                                 *hyper, status=st)
+            ctx = {k: c[k] for k in ("n", "tb", "cb", "mb", "ub", "gb", "d", "fls")}
+            ctx.update(hyper=hyper, i=i)
+            assert np.array_equal(c["d_theta"].cpu().numpy(), c["theta"]), ("theta", ctx)
+            if c["cb"]:
+                assert np.array_equal(c["d_comp"].cpu().numpy(), c["comp"]), ("comp", ctx)
+            assert np.array_equal(c["d_mom"].cpu().numpy(), c["mom"]), ("mom", ctx)
+            assert np.array_equal(c["d_sec"].cpu().numpy(), c["sec"]), ("sec", ctx)
+            got = (int(vmax[i].item()), int(mmax[i].item()), int(umax[i].item()))
+            assert got == want, ("max", got, want, ctx)
+        assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
+        tl.destroy()
+
+
+def test_adam_argument_errors():
+    say("adam: host-side argument errors")
+    n = 64
+    th = torch.zeros(n, dtype=torch.int8, device=DEV); co = torch.zeros(n, dtype=torch.int8, device=DEV)
+    g = torch.zeros(n, dtype=torch.int16, device=DEV); m = torch.zeros(n, dtype=torch.int16, device=DEV)
+    u = torch.zeros(n, dtype=torch.int16, device=DEV)
+    fl = torch.zeros(1, dtype=torch.int32, device=DEV)
+    good = (66, 0, 58982, 65470, 0, 0)
+    full = lpk.TensorList([lpk.make_desc(th, co, g, None, momentum=m, second=u)])
+    for bad in ((65536, 0, 1, 1, 0, 0), (1, 49, 1, 1, 0, 0), (1, 0, 65536, 1, 0, 0), (1, 0, 1, 1, 65536, 0), (1, 0, 1, 1, 0, 49)):
+        with pytest.raises(lpk.LpkError):
+            lpk.lpk_adam_step(full, fl, fl, fl, fl, fl, fl, fl, bad)
+    with pytest.raises(lpk.LpkError):
+        lpk.lpk_adam_step(full, fl, fl, fl, None, fl, fl, fl, good)
+    no_second = lpk.TensorList([lpk.make_desc(th, co, g, None, momentum=m)])
+    with pytest.raises(lpk.LpkError):
+        lpk.lpk_adam_step(no_second, fl, fl, fl, fl, fl, fl, fl, good)
+    with pytest.raises(lpk.LpkError):
+        lpk.lpk_select_fraclen(no_second, lpk.LPK_VMAX_U64, lpk.LPK_SEL_SECOND, fl, fl, fl, fl)
+    lpk.lpk_adam_step(full, fl, fl, fl, fl, fl, fl, fl, good)       # the good call goes through
+    torch.cuda.synchronize()
+    full.destroy(); no_second.destroy()
