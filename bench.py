@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--n-tiny", type=int, default=10000, help="number of 256-element tensors in config 5")
     ap.add_argument("--momentum-bits", type=int, default=0, choices=[0, 8, 16],
                     help="time the momentum variant of the update (velocity of this width, mu = 0.9) instead of plain SGD")
+    ap.add_argument("--adam", action="store_true",
+                    help="time the ADAM variant of the update (int16 first and second moments) instead of plain SGD")
     ap.add_argument("--comp-bits", type=int, default=0, choices=[0, 8, 16],
                     help="width of the accumulator when it differs from theta's (16 = the paper's 8+16 -> 22-bit example)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -92,7 +94,10 @@ def main():
     mom_bits = [args.momentum_bits] * cfg.n_tensors if args.momentum_bits else None
     mu_q16 = 58982 if args.momentum_bits else None
     comp_bits = [args.comp_bits] * cfg.n_tensors if args.comp_bits else None
-    dev = DeviceState(cfg, n_src=n_src, mom_bits=mom_bits, comp_bits=comp_bits)
+    if args.adam:
+        mom_bits = [16] * cfg.n_tensors
+    sec_bits = [16] * cfg.n_tensors if args.adam else None
+    dev = DeviceState(cfg, n_src=n_src, mom_bits=mom_bits, comp_bits=comp_bits, sec_bits=sec_bits, fl_mom0=24, fl_sec0=38)
     views = dev.host_src_views()
 
     t0 = time.perf_counter()
@@ -110,7 +115,11 @@ def main():
     log("inputs drawn and uploaded in %.1f s" % (time.perf_counter() - t0))
 
     for s in range(args.warmup):
-        dev.step(s, k=s % n_src, mu_q16=mu_q16)
+        if args.adam:
+            dev.quantize_grads(s % n_src)
+            dev.update_adam(workloads.adam_hyper(s), s % n_src)
+        else:
+            dev.step(s, k=s % n_src, mu_q16=mu_q16)
     torch.cuda.synchronize()
 
     K = args.steps
@@ -126,7 +135,9 @@ def main():
         ev[i][1].record()
         lpk.lpk_quantize_tensor(L, lpk.LPK_SEL_GRAD, dev.fl_grad, dev.status)
         ev[i][2].record()
-        if mu_q16 is None:
+        if args.adam:
+            dev.update_adam(workloads.adam_hyper(s), k)
+        elif mu_q16 is None:
             dev.update(cfg.lr_q16(s), cfg.wd_q16, k)
         else:
             dev.update_momentum(cfg.lr_q16(s), mu_q16, cfg.wd_q16, k)
@@ -136,7 +147,7 @@ def main():
 
     # the same whole path with quantization fused into the update (select + lpk_kahan_sgd_step_f32grad)
     fused = None
-    if mu_q16 is None:
+    if mu_q16 is None and not args.adam:
         fev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
         for s in range(2):
             dev.step_fused(s, k=s % n_src)
@@ -200,7 +211,8 @@ def main():
 
     upd_bytes = sum(n * (2 * (b // 8) + 2 * (cb // 8) + 2) for n, b, cb in zip(cfg.sizes, cfg.bits, dev.comp_bits))
     upd_bytes += 2 * (args.momentum_bits // 8) * cfg.n_params if args.momentum_bits else 0
-    upd_kernel = "momentum_step_kernel" if args.momentum_bits else "kahan_step_kernel"
+    upd_bytes += 8 * cfg.n_params if args.adam else 0
+    upd_kernel = "adam_step_kernel" if args.adam else ("momentum_step_kernel" if args.momentum_bits else "kahan_step_kernel")
     achieved = upd_bytes / (upd_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_config%d.json" % cfg.id)
@@ -221,7 +233,7 @@ def main():
         "dtype": "int32", "data": "synthetic",
         "storage": "int8/int16 dynamic fixed point (int64 arithmetic outside the 32-bit fast path)",
         "config": {"workload": "config %d: %s%s" % (cfg.id, cfg.name, ", momentum 0.9 with int%d velocity" % args.momentum_bits
-                                                    if args.momentum_bits else "") + (", int%d accumulator" % args.comp_bits if args.comp_bits else ""),
+                                                    if args.momentum_bits else "") + (", ADAM with int16 moments" if args.adam else "") + (", int%d accumulator" % args.comp_bits if args.comp_bits else ""),
                    "n_tensors": cfg.n_tensors,
                    "n_params": cfg.n_params, "lr_q16": cfg.lr_q16(0), "wd_q16": cfg.wd_q16,
                    "grad_draws_cycled": n_src},

@@ -18,11 +18,19 @@
 // anything else goes element by element through the same arithmetic.
 #include "step_common.hpp"
 
+#ifndef LPK_ADAM_GROUPS
+#define LPK_ADAM_GROUPS 1
+#endif
+#ifndef LPK_ADAM_WAVES_PER_SIMD
+#define LPK_ADAM_WAVES_PER_SIMD 2      // register budget: 512 / this many VGPRs per lane
+#endif
+
 namespace lpk {
 
 struct AdamParams {
   int    path;                     // 0 skip, 1 element by element, 2 vector
   int    wt, wc, wg, wm, wu, has_comp;
+  int    caps;                     // some 2^40 cap may bind
   double a1, a2, a3, a4;           // b1 * 2^-k1, (65536 - b1) * 2^-k2, b2 * 2^-k4, (65536 - b2) * 2^-k5
   double qmin_t, qmax_t, qmin_c, qmax_c, qmin_m, qmax_m, qmax_u;
   double ascale;                   // 2^(24 + p): radicand scale
@@ -36,8 +44,12 @@ struct AdamTrack { double vm, mm, um; };
 
 __device__ __forceinline__ double pow2d(int k) { return __longlong_as_double((long long)(1023 + k) << 52); }
 
+__device__ __forceinline__ double cap_d() { return 1099511627776.0; }          // 2^40
+
 __device__ __forceinline__ double clampd(double x, double lo, double hi) { return __builtin_fmin(__builtin_fmax(x, lo), hi); }
 
+// CAPS: whether a 2^40 cap can bind for this tensor's shifts (wave-uniform; almost never).
+template <bool CAPS>
 __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, int m, int u, int g,
                                             int& tn, int& cn, int& mn, int& un, AdamTrack& tr)
 {
@@ -45,32 +57,41 @@ __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, 
   const double gd = (double)g;
   // first moment
   const double t1 = __builtin_rint((double)m * p.a1);
-  const double t2 = clampd(__builtin_rint(gd * p.a2), -cap, cap);
+  double t2 = __builtin_rint(gd * p.a2);
+  if (CAPS) t2 = clampd(t2, -cap, cap);
   const double mq = __builtin_rint((t1 + t2) * 0x1p-16);
   tr.mm = __builtin_fmax(tr.mm, __builtin_fabs(mq));
   const double mnew = clampd(mq, p.qmin_m, p.qmax_m);
   // second moment
   const double t3 = __builtin_rint((double)u * p.a3);
-  const double t4 = clampd(__builtin_rint(gd * gd * p.a4), -cap, cap);
+  double t4 = __builtin_rint(gd * gd * p.a4);
+  if (CAPS) t4 = clampd(t4, -cap, cap);
   const double uq = __builtin_rint((t3 + t4) * 0x1p-16);
   tr.um = __builtin_fmax(tr.um, uq);
   const double unew = clampd(uq, 0.0, p.qmax_u);
-  // root of the new second moment on its fixed grid: floor, repaired by exact residuals
-  const double A = unew * p.ascale;                         // an integer below 2^40
-  double r = __builtin_floor(__builtin_sqrt(A));
+  // Root of the new second moment on its fixed grid.  A is an integer below 2^40; the fp32 root of its fp32
+  // rounding is within 0.2 of the true root (two relative errors of at most 2^-23 on a value below 2^20), so its
+  // floor is off by at most one, which the signs of the exact residuals r^2 - A and (r + 1)^2 - A repair.
+  const double A = unew * p.ascale;
+  double r = __builtin_floor((double)__builtin_amdgcn_sqrtf((float)A));
   const double r1 = r + 1.0;
   const bool too_big = __builtin_fma(r, r, -A) > 0.0, too_small = __builtin_fma(r1, r1, -A) <= 0.0;
   r = too_big ? r - 1.0 : (too_small ? r1 : r);
   const double den = __builtin_fmax(r + p.eps_r, 1.0) * p.dscale;
-  // step: RNE(num / den), the rounded quotient repaired by its exact remainder
+  // Step: RNE(num / den).  Reciprocal seed plus two Newton steps (relative error near 2^-52), so the rounded
+  // product is within one of the exact rounded quotient whenever that is below 2^41 (larger ones end at the
+  // cap regardless); the exact remainder num - q den, compared with half the divisor, repairs it, ties to even.
   const double num = mnew * p.nlr;
-  double q = __builtin_rint(num / den);
+  double x = __builtin_amdgcn_rcp(den);
+  x = __builtin_fma(__builtin_fma(-den, x, 1.0), x, x);
+  x = __builtin_fma(__builtin_fma(-den, x, 1.0), x, x);
+  double q = __builtin_rint(num * x);
   const double two_rem = 2.0 * __builtin_fma(-q, den, num);
   const double hq = 0.5 * q;
   const bool odd = hq != __builtin_floor(hq);
-  const bool up = two_rem > den || (two_rem == den && odd), down = two_rem < -den || (two_rem == -den && odd);
+  const bool up = (two_rem > den) | ((two_rem == den) & odd), down = (two_rem < -den) | ((two_rem == -den) & odd);
   q += up ? 1.0 : (down ? -1.0 : 0.0);
-  const double s = clampd(q, -cap, cap);
+  const double s = CAPS ? clampd(q, -cap, cap) : q;
   // Algorithm 1 with this step
   const double v = __builtin_fma((double)th, p.p2d, (double)c) + s;
   tr.vm = __builtin_fmax(tr.vm, __builtin_fabs(v));
@@ -82,6 +103,7 @@ __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, 
 }
 
 // Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
+template <bool CAPS>
 __device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
 {
   for (uint32_t j = lane; j < cnt; j += kWave) {
@@ -92,7 +114,7 @@ __device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const Ten
     const int u  = load_elem(T.sec, i, p.wu);
     const int g  = load_elem(T.grad, i, p.wg);
     int tn, cn, mn, un;
-    update_adam(p, th, c, m, u, g, tn, cn, mn, un, tr);
+    update_adam<CAPS>(p, th, c, m, u, g, tn, cn, mn, un, tr);
     store_elem(T.theta, i, p.wt, tn);
     if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
     store_elem(T.mom, i, p.wm, mn);
@@ -112,13 +134,13 @@ __device__ __forceinline__ void load_group_adam(AGroup<WT, WC>& G, const TensorD
   load16<16>(G.m, T.mom, e); load16<16>(G.u, T.sec, e); load16<16>(G.g, T.grad, e);
 }
 
-template <int WT, int WC>
+template <int WT, int WC, bool CAPS>
 __device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<WT, WC>& G, const TensorDev& T, uint64_t e, AdamTrack& tr)
 {
   int tn[16], cn[16], mn[16], un[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k)
-    update_adam(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), elem16<16>(G.m, k), elem16<16>(G.u, k), elem16<16>(G.g, k),
+    update_adam<CAPS>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), elem16<16>(G.m, k), elem16<16>(G.u, k), elem16<16>(G.g, k),
                 tn[k], cn[k], mn[k], un[k], tr);
   store16<WT>(T.theta, e, tn);
   store16<WC>(T.comp, e, cn);
@@ -126,10 +148,10 @@ __device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<WT,
   store16<16>(T.sec, e, un);
 }
 
-template <int WT, int WC>
+template <int WT, int WC, bool CAPS>
 __device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
 {
-  constexpr int kP = 2;                                    // groups in flight per lane
+  constexpr int kP = LPK_ADAM_GROUPS;                      // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
@@ -137,16 +159,16 @@ __device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorD
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group_adam(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) group_adam<WT, WC>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
+    for (int ps = 0; ps < kP; ++ps) group_adam<WT, WC, CAPS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     AGroup<WT, WC> G;
     const uint64_t e = off + (uint64_t)gi * kGroup;
     load_group_adam(G, T, e);
-    group_adam<WT, WC>(p, G, T, e, tr);
+    group_adam<WT, WC, CAPS>(p, G, T, e, tr);
   }
   const uint32_t tail = cnt - ngroups * kGroup;
-  if (tail) tile_generic_adam(p, T, off + (uint64_t)ngroups * kGroup, tail, lane, tr);
+  if (tail) tile_generic_adam<CAPS>(p, T, off + (uint64_t)ngroups * kGroup, tail, lane, tr);
 }
 
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
@@ -182,6 +204,10 @@ __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, in
   p.dscale = pow2d(e < 0 ? -e : 0);
   const int u = delta > 0 ? delta : 0, kth = d + u - delta, kc = kth - d;
   p.p2d = pow2d(d); p.p2u = pow2d(u); p.inv_kth = pow2d(-kth); p.p2kth = pow2d(kth); p.inv_kc = pow2d(-kc);
+  // Can a cap bind?  |g| <= 2^15 and g^2 <= 2^30 bound the two gradient terms; the step is at most
+  // |num| / den <= 2^15 lr 2^e / max(eps_R, 1) (2^-e in the divisor when e < 0).
+  const double step_bound = 32768.0 * (double)h.lr * pow2d(e) / __builtin_fmax(p.eps_r, 1.0);
+  p.caps = !(32768.0 * p.a2 < cap_d() && 1073741824.0 * p.a4 < cap_d() && step_bound < cap_d());
   p.path = 1;
   const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
   if (p.has_comp && T.vec_adam && widths_ok && p.wg == 16 && p.wm == 16 && p.wu == 16) p.path = 2;
@@ -191,7 +217,7 @@ __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, in
 
 __device__ __forceinline__ uint64_t track_u64(double x) { return (uint64_t)x; }     // an integer below 2^53
 
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(LPK_ADAM_WAVES_PER_SIMD, LPK_ADAM_WAVES_PER_SIMD)))
 adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                  const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out,
                  const int32_t* __restrict__ fl_m_in, const int32_t* __restrict__ fl_m_out,
@@ -226,12 +252,12 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
       T = tensors[t];
       setup_adam(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_u_in[t], fl_u_out[t], fl_g[t], h, status_bits);
     }
-    if (p.path == 2) {
-      if (p.wt == 8 && p.wc == 8) tile_vec_adam<8, 8>(p, T, off, cnt, lane, tr);
-      else if (p.wt == 16)        tile_vec_adam<16, 16>(p, T, off, cnt, lane, tr);
-      else                        tile_vec_adam<8, 16>(p, T, off, cnt, lane, tr);
-    } else if (p.path == 1) {
-      tile_generic_adam(p, T, off, cnt, lane, tr);
+    if (p.path == 2 && !p.caps) {
+      if (p.wt == 8 && p.wc == 8) tile_vec_adam<8, 8, false>(p, T, off, cnt, lane, tr);
+      else if (p.wt == 16)        tile_vec_adam<16, 16, false>(p, T, off, cnt, lane, tr);
+      else                        tile_vec_adam<8, 16, false>(p, T, off, cnt, lane, tr);
+    } else if (p.path) {
+      if (p.caps) tile_generic_adam<true>(p, T, off, cnt, lane, tr); else tile_generic_adam<false>(p, T, off, cnt, lane, tr);
     }
   }
 

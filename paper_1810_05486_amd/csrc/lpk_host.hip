@@ -39,6 +39,7 @@ struct lpk_tensor_list {
   int        device    = 0;
   uint32_t   grid      = 0;        // blocks of the persistent read-mostly launches (max-abs, quantize)
   uint32_t   grid_step = 0;        // blocks of the persistent update launches
+  uint32_t   grid_adam = 0;        // blocks of the ADAM launch (bound by fp64 arithmetic, not by HBM: more waves help)
   bool       all_src   = false;    // every non-empty tensor has an fp32 source
   bool       all_mom   = false;    // every non-empty tensor has a velocity buffer
   bool       all_sec   = false;    // ... and a second-moment buffer
@@ -133,6 +134,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     };
     L->grid = clampg(env_u32("LPK_BLOCKS_PER_CU", 2));
     L->grid_step = clampg(env_u32("LPK_STEP_BLOCKS_PER_CU", 1));
+    L->grid_adam = clampg(env_u32("LPK_ADAM_BLOCKS_PER_CU", 2));
     ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
          hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * n_tensors) == hipSuccess &&
          (tiles.empty() || hipMalloc((void**)&L->d_tiles, sizeof(Tile) * tiles.size()) == hipSuccess);
@@ -247,7 +249,7 @@ int lpk_adam_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t*
       hyper->lr_exp > 48u || hyper->eps_exp > 48u) return LPK_ERR_INVALID_ARG;
   if (!L->all_mom || !L->all_sec) return LPK_ERR_INVALID_ARG;
   const AdamHyperDev h{hyper->lr_q16, hyper->lr_exp, hyper->beta1_q16, hyper->beta2_q16, hyper->eps_q16, hyper->eps_exp};
-  hipError_t e = launch_adam_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_step, fl_theta_in, fl_theta_out,
+  hipError_t e = launch_adam_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_adam, fl_theta_in, fl_theta_out,
                                   fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, h, vmax_out, mmax_out, umax_out, status,
                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
