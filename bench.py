@@ -14,7 +14,7 @@ re-selection where the workload has one).  Prints ONE JSON line.
              (6 B per int8 parameter, 10 B per int16 one) over its average
              duration, measured with HIP events around every call inside the
              timed region
-  cpu_baseline   the CPU oracle, single thread, on a bounded slice
+  cpu_baseline   the CPU oracle on the host cores (and on one thread), on a bounded slice
 """
 import argparse
 import json
@@ -32,8 +32,10 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(cfg, sample_elems):
-    """Time the oracle (as it stands, one thread) on the first `sample_elems` elements of tensor 0."""
+def cpu_baseline(cfg, sample_elems, threads):
+    """Time the oracle (as it stands) on the first `sample_elems` elements of tensor 0: one whole-path step
+    (max-abs fraclen selection, quantization, lazy update), with `threads` host threads over contiguous
+    element ranges (the selection scan stays on one thread, as the oracle has it)."""
     import numpy as np
     from oracle import ref
     n = cfg.sizes[0] if sample_elems >= cfg.sizes[0] else sample_elems
@@ -46,10 +48,10 @@ def cpu_baseline(cfg, sample_elems):
     comp = np.zeros(n, dtype=dt)
     t0 = time.perf_counter()
     fl_g = ref.select_fraclen_f32(grad, 16, 15)
-    g = ref.quantize(grad, 16, fl_g)
-    ref.kahan_sgd_step(theta, comp, g, bits - 1, fl_t, fl_t, fl_g, cfg.lr_q16(0), cfg.wd_q16)
+    g = ref.quantize_mt(grad, 16, fl_g, threads=threads)
+    ref.kahan_sgd_step_mt(theta, comp, g, bits - 1, fl_t, fl_t, fl_g, cfg.lr_q16(0), cfg.wd_q16, threads=threads)
     dt_s = time.perf_counter() - t0
-    return {"value": n / dt_s / 1e9, "unit": "Gparam/s", "cores": 1, "kind": "oracle",
+    return {"value": n / dt_s / 1e9, "unit": "Gparam/s", "cores": threads, "kind": "oracle",
             "sample": "one whole-path step (select + quantize + update) over the first %d elements of tensor 0, "
                       "%.1f s" % (n, dt_s)}
 
@@ -255,7 +257,9 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
-        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample)
+        cores = max(1, min(16, len(os.sched_getaffinity(0))))
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample, cores)
+        out["cpu_baseline_one_thread"] = cpu_baseline(cfg, args.cpu_sample // 2, 1)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)

@@ -15,15 +15,17 @@
 // registers exactly as the quantization kernel would -- the fused form saves
 // the int16 round trip through HBM.
 //
-// Arithmetic: two paths with identical results.
+// Arithmetic: three paths with identical results, chosen per tensor.
 //   * generic: 64-bit integers, any widths / shifts / grid move / decay /
 //     no-accumulator mode inside the documented domain;
-//   * fast: 32-bit, chosen per tensor when the shifts allow it.  The step
+//   * fast: 32-bit, when the shifts allow it.  The step
 //     RNE(-lr*g / 2^k) is ONE fp32 fused multiply-add: g and lr are exact in
 //     fp32, the FMA forms their product exactly and adds 1.5*2^(23+k), whose
 //     ulp is 2^k, so the single IEEE rounding of the FMA *is* the
 //     round-to-nearest-even at bit k and the integer falls out of the
-//     significand bits.  The decay term uses the same construction in fp64.
+//     significand bits.  The decay term uses the same construction in fp64;
+//   * small: int8 theta with an int8 accumulator and every intermediate below
+//     2^22 -- the rounding of v onto theta's grid runs on the FMA unit too.
 //
 // Running maximum of |v| per tensor: per-lane max, DPP wave reduction when a
 // wave moves to another tensor, LDS stage across the four waves of a block at
@@ -113,9 +115,6 @@ struct Track { int vmx, vmn; uint32_t ab; };
 template <bool DECAY>
 __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, float gf, int& tn, int& cn, Track& tr)
 {
-#ifdef LPK_NO_MATH
-  tn = th ^ (__float_as_int(gf) & 1); cn = c; return;
-#endif
   int s = __float_as_int(__builtin_fmaf(gf, p.nlr_f, p.magic_f)) - p.magic_fi;
   if (DECAY) {
     double r = __builtin_fma((double)th, p.nlrwd_d, p.magic_d);
