@@ -42,11 +42,7 @@ struct AdamParams {
 
 struct AdamTrack { double vm, mm, um; };
 
-__device__ __forceinline__ double pow2d(int k) { return __longlong_as_double((long long)(1023 + k) << 52); }
-
 __device__ __forceinline__ double cap_d() { return 1099511627776.0; }          // 2^40
-
-__device__ __forceinline__ double clampd(double x, double lo, double hi) { return __builtin_fmin(__builtin_fmax(x, lo), hi); }
 
 // CAPS: whether a 2^40 cap can bind for this tensor's shifts (wave-uniform; almost never).
 template <bool CAPS>

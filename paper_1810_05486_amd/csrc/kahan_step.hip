@@ -37,7 +37,7 @@ namespace lpk {
 enum { kGradI16 = 0, kGradF32 = 1 };
 
 struct StepParams {
-  int      path;            // 0 skip, 1 generic, 2 fast
+  int      path;            // 0 skip, 1 element by element (wide arithmetic), 2 vector (arithmetic by `mode`)
   int      wt, wc, wg, d;
   int      has_comp;
   int      kg;              // shift of the gradient term: fl_g + 16 - F
@@ -51,13 +51,17 @@ struct StepParams {
   double   nlrwd_d; double magic_d; int magic_dlo;
   int      half_m1;         // 2^(d-1) - 1
   // small-value variant of the fast path (every |intermediate| < 2^22, d <= 8): roundings on the FMA unit
-  int      small;
   int      bias_i;          // -bits(1.5 * 2^23): takes the FMA's offset out of the step
   float    inv2d_f;         // 2^-d
   float    lo_tf, hi_tf;    // 1.5 * 2^23 + rails of theta
   int      neg2d;           // -2^d
   int      lo_cb, hi_cb;    // rails of comp minus 2^(22 + d)
+  // wide path (fp64, any shifts): -lr * 2^-kg, -lr * wd * 2^-kw, 2^d, 2^u, 2^-kth, 2^kth, 2^-kc, rails
+  int      mode;            // vector arithmetic: kModeFast, kModeSmall or kModeWide
+  double   w_ag, w_aw, w_p2d, w_p2u, w_inv_kth, w_p2kth, w_inv_kc, w_lo_t, w_hi_t, w_lo_c, w_hi_c;
 };
+
+enum { kModeFast = 0, kModeSmall = 1, kModeWide = 2 };
 
 // Quantize one fp32 gradient exactly as the quantization kernel does; the result is an integer-valued float.
 // `ab_max` collects the largest |bit pattern| seen (>= 0x7f800000 means a NaN or Inf went by).
@@ -70,21 +74,25 @@ __device__ __forceinline__ float quant_grad(const StepParams& p, float x, uint32
   return ab > 0x7f800000u ? 0.0f : y;                  // NaN -> 0
 }
 
-// ---------------------------------------------------------------- generic (int64)
+// ---------------------------------------------------------------- wide (fp64, any shifts of the domain)
+//
+// Every quantity of the definition is an integer below 2^53 times a power of two: |lr * g| < 2^31,
+// |lr * wd * theta| < 2^47, each term capped at 2^40, |v| < 2^42.  Products, sums and scalings by powers of two are
+// therefore exact in binary64, and v_rndne_f64 is the round-to-nearest-even of the definition whichever way a
+// shift points -- no branches, no 64-bit integer sequences.  The residual v_G - theta' * 2^kth is exact while it is
+// below 2^53; beyond that the accumulator saturates whatever the last bits are.
 
-__device__ __forceinline__ void update_generic(const StepParams& p, int64_t th, int64_t c, int64_t g,
-                                               int& th_new, int& c_new, uint64_t& vabs)
+__device__ __forceinline__ void update_wide(const StepParams& p, int th, int c, double g, int& th_new, int& c_new, double& vabs_max)
 {
-  int64_t s = rescale_cap64(-p.lr * g, p.kg);
-  if (p.lrwd) s += rescale_cap64(-p.lrwd * th, p.kw);
-  int64_t v = th * (1ll << p.d) + c + s;
-  vabs = (uint64_t)(v < 0 ? -v : v);
-  int64_t vG = v * (1ll << p.u);
-  int64_t tn = rne_shr64(vG, p.kth);
-  tn = tn > p.qmax_t ? p.qmax_t : (tn < p.qmin_t ? p.qmin_t : tn);
-  int64_t r  = vG - tn * (1ll << p.kth);
-  int64_t cn = rne_shr64(r, p.kc);
-  cn = cn > p.qmax_c ? p.qmax_c : (cn < p.qmin_c ? p.qmin_c : cn);
+  const double cap = 1099511627776.0;                       // 2^40
+  double s = clampd(__builtin_rint(g * p.w_ag), -cap, cap);
+  if (p.lrwd) s += clampd(__builtin_rint((double)th * p.w_aw), -cap, cap);
+  const double v = __builtin_fma((double)th, p.w_p2d, (double)c) + s;
+  vabs_max = __builtin_fmax(vabs_max, __builtin_fabs(v));
+  const double vG = v * p.w_p2u;
+  const double tn = clampd(__builtin_rint(vG * p.w_inv_kth), p.w_lo_t, p.w_hi_t);
+  const double rr = __builtin_fma(-tn, p.w_p2kth, vG);
+  const double cn = clampd(__builtin_rint(rr * p.w_inv_kc), p.w_lo_c, p.w_hi_c);
   th_new = (int)tn; c_new = (int)cn;
 }
 
@@ -93,24 +101,23 @@ template <int GS>
 __device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                                  uint32_t& ab_max)
 {
-  uint64_t vm = 0;
+  double vw = 0.0;
   for (uint32_t j = lane; j < cnt; j += kWave) {
     uint64_t i = off + j;
     int th = load_elem(T.theta, i, p.wt);
     int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
     int g  = GS == kGradF32 ? (int)quant_grad(p, ((const float*)T.src)[i], ab_max) : load_elem(T.grad, i, p.wg);
-    int tn, cn; uint64_t va;
-    update_generic(p, th, c, g, tn, cn, va);
-    vm = va > vm ? va : vm;
+    int tn, cn;
+    update_wide(p, th, c, (double)g, tn, cn, vw);
     store_elem(T.theta, i, p.wt, tn);
     if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
   }
-  return vm;
+  return (uint64_t)vw;                                   // an integer below 2^42
 }
 
 // ---------------------------------------------------------------- fast (int32 + FMA rounding)
 
-struct Track { int vmx, vmn; uint32_t ab; };
+struct Track { int vmx, vmn; uint32_t ab; double vw; };
 
 template <bool DECAY>
 __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, float gf, int& tn, int& cn, Track& tr)
@@ -206,7 +213,7 @@ template <int W> __device__ __forceinline__ void store16v(void* base, uint64_t e
   else { st_stream((v4i*)((int16_t*)base + e), src[0]); st_stream((v4i*)((int16_t*)base + e + 8), src[W / 8 - 1]); }
 }
 
-template <int WT, int WC, int GS, bool DECAY, bool SMALL>
+template <int WT, int WC, int GS, bool DECAY, int MODE>
 __device__ __forceinline__ void compute_group(const StepParams& p, const Group<WT, WC, GS>& G, GroupOut<WT, WC>& O, Track& tr)
 {
   int tn[16], cn[16];
@@ -215,8 +222,9 @@ __device__ __forceinline__ void compute_group(const StepParams& p, const Group<W
     float gf;
     if (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[(k >> 2) & (GS == kGradF32 ? 3 : 1)][k & 3]), tr.ab);
     else                gf = (float)sx16(G.g[(k >> 3) & 1][(k >> 1) & 3], k & 1);
-    if (SMALL) update_small<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
-    else       update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    if (MODE == kModeSmall)     update_small<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    else if (MODE == kModeWide) update_wide(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
+    else                        update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
   pack16<WT>(O.th, tn);
   pack16<WC>(O.c, cn);
@@ -229,25 +237,26 @@ __device__ __forceinline__ void store_group(const GroupOut<WT, WC>& O, const Ten
   store16v<WC>(T.comp, e, O.c);
 }
 
-template <int WT, int WC, int GS, bool DECAY, bool SMALL>
+template <int WT, int WC, int GS, bool DECAY, int MODE>
 __device__ __forceinline__ void compute_store_group(const StepParams& p, const Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
   GroupOut<WT, WC> O;
-  compute_group<WT, WC, GS, DECAY, SMALL>(p, G, O, tr);
+  compute_group<WT, WC, GS, DECAY, MODE>(p, G, O, tr);
   store_group<WT, WC>(O, T, e);
 }
 
 __device__ __forceinline__ uint64_t track_max(const Track& tr)
 {
   int64_t a = tr.vmx, b = -(int64_t)tr.vmn;
-  return (uint64_t)(a > b ? a : b);
+  const uint64_t m32 = (uint64_t)(a > b ? a : b), m64 = (uint64_t)tr.vw;
+  return m32 > m64 ? m32 : m64;
 }
 
 // Vector tile: full 16-element groups with the fast arithmetic, the ragged end element by element.
-template <int WT, int WC, int GS, bool DECAY, bool SMALL>
+template <int WT, int WC, int GS, bool DECAY, int MODE>
 __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
 {
-  Track tr{0, 0, ab_max};
+  Track tr{0, 0, ab_max, 0.0};
   constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : 8);     // VGPRs of one group
   constexpr int kP = kRegs <= 16 ? LPK_I16_GROUPS : LPK_KP_WIDE;                     // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
@@ -257,13 +266,13 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, SMALL>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
+    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, MODE>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     Group<WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * kGroup;
     load_group(G, T, e);
-    compute_store_group<WT, WC, GS, DECAY, SMALL>(p, G, T, e, tr);
+    compute_store_group<WT, WC, GS, DECAY, MODE>(p, G, T, e, tr);
   }
   ab_max = tr.ab;
   uint64_t vm = track_max(tr);
@@ -335,7 +344,7 @@ __device__ __forceinline__ void load_group_e(GroupE<E, WT, WC, GS>& G, const Ten
   }
 }
 
-template <int E, int WT, int WC, int GS, bool DECAY, bool SMALL>
+template <int E, int WT, int WC, int GS, bool DECAY, int MODE>
 __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
   int tn[E], cn[E];
@@ -344,17 +353,18 @@ __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const
     float gf;
     if constexpr (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[k >> 2].d[k & 3]), tr.ab);
     else                          gf = (float)sx16(G.g[k >> 3].d[(k >> 1) & 3], k & 1);
-    if constexpr (SMALL) update_small<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
-    else                 update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    if constexpr (MODE == kModeSmall)     update_small<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    else if constexpr (MODE == kModeWide) update_wide(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
+    else                                  update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
   st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
   st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
 }
 
-template <int E, int KP, int WT, int WC, int GS, bool DECAY, bool SMALL>
+template <int E, int KP, int WT, int WC, int GS, bool DECAY, int MODE>
 __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
 {
-  Track tr{0, 0, ab_max};
+  Track tr{0, 0, ab_max, 0.0};
   const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;
   for (; gi + (KP - 1) * kWave < ngroups; gi += KP * kWave) {
@@ -362,13 +372,13 @@ __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const Tenso
 #pragma unroll
     for (int ps = 0; ps < KP; ++ps) load_group_e(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
-    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, SMALL>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
+    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, MODE>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     GroupE<E, WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * E;
     load_group_e(G, T, e);
-    compute_store_group_e<E, WT, WC, GS, DECAY, SMALL>(p, G, T, e, tr);
+    compute_store_group_e<E, WT, WC, GS, DECAY, MODE>(p, G, T, e, tr);
   }
   ab_max = tr.ab;
   uint64_t vm = track_max(tr);
@@ -405,14 +415,21 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   p.qmax_c = (1 << (wc - 1)) - 1;   p.qmin_c = -(1 << (wc - 1));
   p.gscale = __uint_as_float((uint32_t)(127 + fl_g) << 23);
   p.glo = -(float)(1 << (p.wg - 1)); p.ghi = (float)((1 << (p.wg - 1)) - 1);
-  p.path = 1;
+  p.w_ag = -(double)lr * pow2d(-p.kg);
+  p.w_aw = -(double)p.lrwd * pow2d(-p.kw);
+  p.w_p2d = pow2d(p.d); p.w_p2u = pow2d(p.u); p.w_inv_kth = pow2d(-p.kth); p.w_p2kth = pow2d(p.kth); p.w_inv_kc = pow2d(-p.kc);
+  p.w_lo_t = (double)p.qmin_t; p.w_hi_t = (double)p.qmax_t; p.w_lo_c = (double)p.qmin_c; p.w_hi_c = (double)p.qmax_c;
+  p.path = 1; p.mode = kModeWide;
 
-  // Fast path: int8/int8, int16/int16 or int8/int16 theta/comp with 16-bit grads on 16-byte aligned buffers,
+  // Vector path: theta, comp and 16-bit gradients on 16-byte aligned buffers, comp as wide as theta (or int8 theta
+  // with an int16 accumulator).  Its arithmetic is the wide one unless the shifts allow 32 bits:
   // no grid move, 1 <= d, a step shift k with |lr * g| <= lr * 2^15 < 2^(22+k) (so the fp32 FMA rounding trick
   // is exact and |s| < 2^22), and every intermediate provably inside int32.
   const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
   const bool vec = T.vec_step && (GS == kGradI16 || (((uintptr_t)T.src) & 15u) == 0);
-  if (!p.has_comp || !vec || !widths_ok || p.wg != 16 || delta != 0 || p.d < 1 || p.kg < 1) return;
+  if (!p.has_comp || !vec || !widths_ok || p.wg != 16) return;
+  p.path = 2;
+  if (delta != 0 || p.d < 1 || p.kg < 1) return;
   if (p.kg < 9 && ((int64_t)lr << 15) >= (1ll << (22 + p.kg))) return;
   int64_t bound = (1ll << (p.wt - 1 + p.d)) + (1ll << (p.wc - 1));             // |theta * 2^d| + |c|
   bound += p.kg < 40 ? (((int64_t)lr << 15) >> p.kg) + 1 : 0;                   // |s_g|
@@ -421,7 +438,7 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   bound += sw;
   bound += 1ll << (p.d - 1);                                                    // the rounding addend
   if (bound >= (1ll << 31)) return;
-  p.path = 2;
+  p.mode = kModeFast;
   const int kg = p.kg > 40 ? 40 : p.kg;                                         // k >= 32 already gives s = 0
   p.magic_fi = ((127 + 23 + kg) << 23) | 0x400000;                              // 1.5 * 2^(23 + k)
   p.magic_f  = __int_as_float(p.magic_fi);
@@ -433,7 +450,7 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   p.half_m1   = (1 << (p.d - 1)) - 1;
   // small-value variant: |v| and |v| + rounding addend below 2^22 (exact in fp32, quotient inside the 2^22 window
   // of the 1.5 * 2^23 offset), and (2^22 + theta') * 2^d inside int32
-  p.small = p.wt == 8 && p.wc == 8 && p.d <= 8 && bound < (1ll << 22);
+  if (p.wt == 8 && p.wc == 8 && p.d <= 8 && bound < (1ll << 22)) p.mode = kModeSmall;
   p.bias_i  = -p.magic_fi;
   p.inv2d_f = __uint_as_float((uint32_t)(127 - p.d) << 23);
   p.lo_tf   = 12582912.0f + (float)p.qmin_t;
@@ -445,17 +462,26 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
 
 // ---------------------------------------------------------------- the kernel
 
-template <int WT, int WC, int GS, bool SMALL>
+template <int WT, int WC, int GS, int MODE>
 __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
 {
+  const bool decay = MODE != kModeWide && p.lrwd;           // the wide arithmetic tests the decay term itself
   if (GS == kGradF32)
-    return p.lrwd ? tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, true, SMALL>(p, T, off, cnt, lane, ab)
-                  : tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, false, SMALL>(p, T, off, cnt, lane, ab);
+    return decay ? tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
+                 : tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
 #if LPK_I16_E != 16
-  return p.lrwd ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, SMALL>(p, T, off, cnt, lane, ab)
-                : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, SMALL>(p, T, off, cnt, lane, ab);
+  return decay ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
+               : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
 #endif
-  return p.lrwd ? tile_fast<WT, WC, GS, true, SMALL>(p, T, off, cnt, lane, ab) : tile_fast<WT, WC, GS, false, SMALL>(p, T, off, cnt, lane, ab);
+  return decay ? tile_fast<WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab) : tile_fast<WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
+}
+
+template <int WT, int WC, int GS>
+__device__ __forceinline__ uint64_t tile_vector(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
+{
+  if (p.mode == kModeWide) return tile_fast_decay<WT, WC, GS, kModeWide>(p, T, off, cnt, lane, ab);
+  if (WT == 8 && WC == 8 && p.mode == kModeSmall) return tile_fast_decay<WT, WC, GS, kModeSmall>(p, T, off, cnt, lane, ab);
+  return tile_fast_decay<WT, WC, GS, kModeFast>(p, T, off, cnt, lane, ab);
 }
 
 template <int GS>
@@ -490,10 +516,9 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && p.wc == 8) vm = p.small ? tile_fast_decay<8, 8, GS, true>(p, T, off, cnt, lane, ab_max)
-                                               : tile_fast_decay<8, 8, GS, false>(p, T, off, cnt, lane, ab_max);
-      else if (p.wt == 16) vm = tile_fast_decay<16, 16, GS, false>(p, T, off, cnt, lane, ab_max);
-      else                 vm = tile_fast_decay<8, 16, GS, false>(p, T, off, cnt, lane, ab_max);
+      if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS>(p, T, off, cnt, lane, ab_max);
+      else if (p.wt == 16)        vm = tile_vector<16, 16, GS>(p, T, off, cnt, lane, ab_max);
+      else                        vm = tile_vector<8, 16, GS>(p, T, off, cnt, lane, ab_max);
     } else if (p.path == 1) {
       vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
     }

@@ -14,7 +14,8 @@
 namespace lpk {
 
 struct MomParams {
-  int      path;                 // 0 skip, 1 generic, 2 fast
+  int      path;                 // 0 skip, 1 element by element (wide arithmetic), 2 vector
+  int      wide;                 // vector path: wide (fp64) arithmetic instead of the 32-bit one
   int      wt, wc, wg, wm, d, has_comp;
   int      k1, k2, k3w, k3;      // shifts: mu*m -> G, lr*g -> G, lr*wd*theta -> G, m' -> F
   int      u, kth, kc;
@@ -26,46 +27,57 @@ struct MomParams {
   int      a3, b3, h3, nz3;                // m' -> grid F
   double   nlrwd_d, magic_d;  int magic_dlo;
   int      half_m1;                        // rounding addend of v -> theta
+  // wide path: mu * 2^-k1, -lr * 2^-k2, -lr * wd * 2^-k3w, 2^-k3, 2^d, 2^u, 2^-kth, 2^kth, 2^-kc, rails
+  double   w_a1, w_a2, w_a3, w_inv_k3, w_p2d, w_p2u, w_inv_kth, w_p2kth, w_inv_kc;
+  double   w_lo_t, w_hi_t, w_lo_c, w_hi_c, w_lo_m, w_hi_m;
 };
 
-__device__ __forceinline__ void update_generic_mom(const MomParams& p, int64_t th, int64_t c, int64_t m, int64_t g,
-                                                   int& th_new, int& c_new, int& m_new, uint64_t& vabs, uint64_t& wabs)
+struct WideMax { double v, w; };
+
+__device__ __forceinline__ void update_wide_mom(const MomParams& p, int th, int c, int m, int g,
+                                                int& th_new, int& c_new, int& m_new, WideMax& mx)
 {
-  int64_t w = rescale64(p.mu * m, p.k1);
-  w += rescale_cap64(-p.lr * g, p.k2);
-  if (p.lrwd) w += rescale_cap64(-p.lrwd * th, p.k3w);
-  int64_t mn = rne_shr64(w, 16);
-  wabs = (uint64_t)(mn < 0 ? -mn : mn);
-  mn = mn > p.qmax_m ? p.qmax_m : (mn < p.qmin_m ? p.qmin_m : mn);
-  int64_t s = rescale_cap64(mn, p.k3);
-  int64_t v = th * (1ll << p.d) + c + s;
-  vabs = (uint64_t)(v < 0 ? -v : v);
-  int64_t vG = v * (1ll << p.u);
-  int64_t tn = rne_shr64(vG, p.kth);
-  tn = tn > p.qmax_t ? p.qmax_t : (tn < p.qmin_t ? p.qmin_t : tn);
-  int64_t r  = vG - tn * (1ll << p.kth);
-  int64_t cn = rne_shr64(r, p.kc);
-  cn = cn > p.qmax_c ? p.qmax_c : (cn < p.qmin_c ? p.qmin_c : cn);
+  const double cap = 1099511627776.0;                       // 2^40
+  double w = __builtin_rint((double)m * p.w_a1);
+  w += clampd(__builtin_rint((double)g * p.w_a2), -cap, cap);
+  if (p.lrwd) w += clampd(__builtin_rint((double)th * p.w_a3), -cap, cap);
+  const double mq = __builtin_rint(w * 0x1p-16);
+  mx.w = __builtin_fmax(mx.w, __builtin_fabs(mq));
+  const double mn = clampd(mq, p.w_lo_m, p.w_hi_m);
+  const double s = clampd(__builtin_rint(mn * p.w_inv_k3), -cap, cap);
+  const double v = __builtin_fma((double)th, p.w_p2d, (double)c) + s;
+  mx.v = __builtin_fmax(mx.v, __builtin_fabs(v));
+  const double vG = v * p.w_p2u;
+  const double tn = clampd(__builtin_rint(vG * p.w_inv_kth), p.w_lo_t, p.w_hi_t);
+  const double rr = __builtin_fma(-tn, p.w_p2kth, vG);      // exact below 2^53; beyond that comp saturates either way
+  const double cn = clampd(__builtin_rint(rr * p.w_inv_kc), p.w_lo_c, p.w_hi_c);
   th_new = (int)tn; c_new = (int)cn; m_new = (int)mn;
+}
+
+__device__ __forceinline__ void fold_wide(const WideMax& mx, uint64_t& vm, uint64_t& wm)
+{
+  const uint64_t a = (uint64_t)mx.v, b = (uint64_t)mx.w;    // integers below 2^53
+  vm = a > vm ? a : vm;
+  wm = b > wm ? b : wm;
 }
 
 __device__ __forceinline__ void tile_generic_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                                  uint64_t& vm, uint64_t& wm)
 {
+  WideMax mx{0.0, 0.0};
   for (uint32_t j = lane; j < cnt; j += kWave) {
     uint64_t i = off + j;
     int th = load_elem(T.theta, i, p.wt);
     int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
     int m  = load_elem(T.mom, i, p.wm);
     int g  = load_elem(T.grad, i, p.wg);
-    int tn, cn, mn; uint64_t va, wa;
-    update_generic_mom(p, th, c, m, g, tn, cn, mn, va, wa);
-    vm = va > vm ? va : vm;
-    wm = wa > wm ? wa : wm;
+    int tn, cn, mn;
+    update_wide_mom(p, th, c, m, g, tn, cn, mn, mx);
     store_elem(T.theta, i, p.wt, tn);
     if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
     store_elem(T.mom, i, p.wm, mn);
   }
+  fold_wide(mx, vm, wm);
 }
 
 // ---------------------------------------------------------------- fast path
@@ -108,24 +120,27 @@ template <int WT, int WM> struct MGroup {
   v4i th[WT / 8], c[WT / 8], m[WM / 8], g[2];
 };
 
-template <int WT, int WM, bool DECAY, bool K1ZERO>
-__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<WT, WM>& G, const TensorDev& T, uint64_t e, MaxTrack& mt)
+template <int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE>
+__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<WT, WM>& G, const TensorDev& T, uint64_t e, MaxTrack& mt, WideMax& mx)
 {
   int tn[16], cn[16], mn[16];
 #pragma unroll
-  for (int k = 0; k < 16; ++k)
-    update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mt);
+  for (int k = 0; k < 16; ++k) {
+    if (WIDE) update_wide_mom(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mx);
+    else update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mt);
+  }
   store16<WT>(T.theta, e, tn);
   store16<WT>(T.comp, e, cn);
   store16<WM>(T.mom, e, mn);
 }
 
-template <int WT, int WM, bool DECAY, bool K1ZERO>
+template <int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE>
 __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                               uint64_t& vm, uint64_t& wm)
 {
   MaxTrack mt{0, 0, 0, 0};
-  constexpr int kP = (WT + WM) > 16 ? 2 : 4;              // passes in flight: bounded by registers
+  WideMax mx{0.0, 0.0};
+  constexpr int kP = (WT + WM) > 16 || WIDE ? 2 : 4;      // passes in flight: bounded by registers
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
@@ -137,13 +152,13 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
     }
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps)
-      group_fast_mom<WT, WM, DECAY, K1ZERO>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, mt);
+      group_fast_mom<WT, WM, DECAY, K1ZERO, WIDE>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, mt, mx);
   }
   for (; gi < ngroups; gi += kWave) {
     MGroup<WT, WM> G;
     const uint64_t e = off + (uint64_t)gi * kGroup;
     load16<WT>(G.th, T.theta, e); load16<WT>(G.c, T.comp, e); load16<WM>(G.m, T.mom, e); load16<16>(G.g, T.grad, e);
-    group_fast_mom<WT, WM, DECAY, K1ZERO>(p, G, T, e, mt);
+    group_fast_mom<WT, WM, DECAY, K1ZERO, WIDE>(p, G, T, e, mt, mx);
   }
   int64_t a = mt.vmx, b = -(int64_t)mt.vmn;
   uint64_t x = (uint64_t)(a > b ? a : b);
@@ -151,6 +166,7 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
   a = mt.wmx; b = -(int64_t)mt.wmn;
   x = (uint64_t)(a > b ? a : b);
   wm = x > wm ? x : wm;
+  fold_wide(mx, vm, wm);
   const uint32_t tail = cnt - ngroups * kGroup;
   if (tail) tile_generic_mom(p, T, off + (uint64_t)ngroups * kGroup, tail, lane, vm, wm);
 }
@@ -159,9 +175,10 @@ template <int WT, int WM>
 __device__ __forceinline__ void tile_fast_mom_dispatch(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                                        uint64_t& vm, uint64_t& wm)
 {
+  if (p.wide) { tile_fast_mom<WT, WM, false, false, true>(p, T, off, cnt, lane, vm, wm); return; }
   const bool k1z = p.k1 == 0;
-  if (p.lrwd) { if (k1z) tile_fast_mom<WT, WM, true, true>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom<WT, WM, true, false>(p, T, off, cnt, lane, vm, wm); }
-  else        { if (k1z) tile_fast_mom<WT, WM, false, true>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false>(p, T, off, cnt, lane, vm, wm); }
+  if (p.lrwd) { if (k1z) tile_fast_mom<WT, WM, true, true, false>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom<WT, WM, true, false, false>(p, T, off, cnt, lane, vm, wm); }
+  else        { if (k1z) tile_fast_mom<WT, WM, false, true, false>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false, false>(p, T, off, cnt, lane, vm, wm); }
 }
 
 // ---------------------------------------------------------------- per-tensor set-up
@@ -190,11 +207,19 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   const int wc = p.has_comp ? p.wc : 8;
   p.qmax_c = (1 << (wc - 1)) - 1;   p.qmin_c = -(1 << (wc - 1));
   p.qmax_m = (1 << (p.wm - 1)) - 1; p.qmin_m = -(1 << (p.wm - 1));
-  p.path = 1;
+  p.w_a1 = (double)mu * pow2d(-p.k1); p.w_a2 = -(double)lr * pow2d(-p.k2); p.w_a3 = -(double)p.lrwd * pow2d(-p.k3w);
+  p.w_inv_k3 = pow2d(-p.k3);
+  p.w_p2d = pow2d(p.d); p.w_p2u = pow2d(p.u); p.w_inv_kth = pow2d(-p.kth); p.w_p2kth = pow2d(p.kth); p.w_inv_kc = pow2d(-p.kc);
+  p.w_lo_t = (double)p.qmin_t; p.w_hi_t = (double)p.qmax_t; p.w_lo_c = (double)p.qmin_c; p.w_hi_c = (double)p.qmax_c;
+  p.w_lo_m = (double)p.qmin_m; p.w_hi_m = (double)p.qmax_m;
+  p.path = 1; p.wide = 1;
 
-  // 32-bit path: aligned, comp present and as wide as theta, int16 grads, theta's grid fixed, d >= 1, and every
-  // intermediate (including each rounding addend) provably below 2^31 in magnitude.
-  if (!p.has_comp || !T.vec_mom || p.wt != p.wc || p.wg != 16 || delta != 0 || p.d < 1) return;
+  // Vector path: aligned, comp present and as wide as theta, int16 grads.  32-bit arithmetic on it when theta's
+  // grid is fixed, d >= 1, and every intermediate (including each rounding addend) is provably below 2^31 in
+  // magnitude; the wide arithmetic otherwise.
+  if (!p.has_comp || !T.vec_mom || p.wt != p.wc || p.wg != 16) return;
+  p.path = 2;
+  if (delta != 0 || p.d < 1) return;
   const int64_t lim = 1ll << 31;
   // t1 = mu*m brought to grid G
   const int64_t X1 = (int64_t)mu << (p.wm - 1);
@@ -225,7 +250,7 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   const int64_t S = p.b3 == 0 ? (M << p.a3) : (M >> p.b3) + 1;
   const int64_t V = (1ll << (p.wt - 1 + p.d)) + (1ll << (p.wc - 1)) + S + (1ll << (p.d - 1));
   if (V >= lim) return;
-  p.path = 2;
+  p.wide = 0;
   p.mu_i = (int)mu;
   const long long md = ((long long)(1023 + 52 + (p.lrwd ? p.k3w : 1)) << 52) | (1ll << 51);
   p.magic_d   = __longlong_as_double(md);

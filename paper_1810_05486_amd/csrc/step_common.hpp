@@ -1,41 +1,13 @@
-// Pieces shared by the update kernels (plain lazy update, momentum): exact 64-bit rounding helpers,
-// element and vector accesses, byte/halfword unpacking, the per-tensor vmax flush.
+// Pieces shared by the update kernels (plain lazy update, momentum, ADAM): exact fp64 helpers of the wide
+// arithmetic, element and vector accesses, byte/halfword unpacking, the per-tensor vmax flush.
 #pragma once
 #include "lpk_device.hpp"
 
 namespace lpk {
 
-__device__ __forceinline__ int64_t rne_shr64(int64_t x, int k)      // RNE(x / 2^k), 0 <= k <= 62
-{
-  if (k == 0) return x;
-  int64_t  q    = x >> k;
-  uint64_t rem  = (uint64_t)x & ((1ull << k) - 1ull);
-  uint64_t half = 1ull << (k - 1);
-  return q + (int64_t)((rem > half) | ((rem == half) & (uint64_t)(q & 1)));
-}
-
-__device__ __forceinline__ int64_t rescale_cap64(int64_t x, int k)   // |x| < 2^48; clamp(RNE(x * 2^-k), +-2^40)
-{
-  const int64_t cap = 1ll << 40;
-  if (x == 0) return 0;
-  if (k > 0) {
-    if (k >= 50) return 0;
-    int64_t q = rne_shr64(x, k);
-    return q > cap ? cap : (q < -cap ? -cap : q);
-  }
-  int sh = -k;
-  if (sh >= 41) return x > 0 ? cap : -cap;
-  int64_t lim = cap >> sh;
-  if (x > lim) return cap;
-  if (x < -lim) return -cap;
-  return x * (1ll << sh);
-}
-
-// RNE(x * 2^-k) without a cap, for |x| < 2^32 and -15 <= k <= 62.
-__device__ __forceinline__ int64_t rescale64(int64_t x, int k)
-{
-  return k > 0 ? rne_shr64(x, k) : x * (1ll << (-k));
-}
+// Exact fp64 helpers of the wide arithmetic: 2^k for -1022 <= k <= 1023, and a clamp.
+__device__ __forceinline__ double pow2d(int k) { return __longlong_as_double((long long)(1023 + k) << 52); }
+__device__ __forceinline__ double clampd(double x, double lo, double hi) { return __builtin_fmin(__builtin_fmax(x, lo), hi); }
 
 __device__ __forceinline__ int load_elem(const void* p, uint64_t i, int bits)
 {

@@ -113,11 +113,12 @@ def test_random_lists_all_widths_shifts_and_alignments(seed):
 @pytest.mark.parametrize("tb", [8, 16])
 def test_arithmetic_path_boundaries(tb):
     """Shifts on both sides of every condition that selects the 32-bit path (step shift 8|9, d 0|1, widest d
-    that still fits, extreme lr and gradients, decay on/off), same-width aligned tensors of several tiles."""
+    that still fits, extreme lr and gradients, decay on/off) and its FMA-rounding variant for small values
+    (d 8|9, step bound either side of 2^22), same-width aligned tensors of several tiles."""
     say("path boundaries, %d-bit" % tb)
     rng = np.random.default_rng(tb)
     for kg in (8, 9, 10, 23, 31, 32, 33, 48, 90):
-        for d in (0, 1, tb - 1, 15, 16, 22, 24):
+        for d in (0, 1, tb - 1, 8, 9, 15, 16, 22, 24):
             fl_in = 5
             fl_g = kg - 16 + fl_in + d
             if not -64 <= fl_g <= 64:
