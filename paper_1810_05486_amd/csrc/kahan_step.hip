@@ -157,7 +157,9 @@ __device__ __forceinline__ int mad_i24(int a, int b, int c)          // sext24(a
   return r;
 }
 
-template <bool DECAY>
+// BIGD (d > 8, the int16 accumulator under an int8 theta): (2^22 + theta') * 2^d no longer fits 32 bits, so
+// theta' is first taken out of the float's bit pattern and the residual is formed and clamped unshifted.
+template <bool DECAY, bool BIGD>
 __device__ __forceinline__ void update_small(const StepParams& p, int th, int c, float gf, int& tn, int& cn, Track& tr)
 {
   int s = __float_as_int(__builtin_fmaf(gf, p.nlr_f, p.magic_f));
@@ -170,7 +172,8 @@ __device__ __forceinline__ void update_small(const StepParams& p, int th, int c,
   tr.vmn = v < tr.vmn ? v : tr.vmn;
   const float q = __builtin_amdgcn_fmed3f(__builtin_fmaf((float)v, p.inv2d_f, 12582912.0f), p.lo_tf, p.hi_tf);
   tn = __float_as_int(q);
-  cn = med3_i32(mad_i24(tn, p.neg2d, v), p.lo_cb, p.hi_cb);
+  if (BIGD) cn = med3_i32(mad_i24(tn - 0x4B400000, p.neg2d, v), p.qmin_c, p.qmax_c);      // 0x4B400000 = bits(1.5 * 2^23)
+  else      cn = med3_i32(mad_i24(tn, p.neg2d, v), p.lo_cb, p.hi_cb);
 }
 
 // 16 consecutive elements of one lane.  WT / WC = widths of theta and comp; GS = gradient source.
@@ -222,7 +225,7 @@ __device__ __forceinline__ void compute_group(const StepParams& p, const Group<W
     float gf;
     if (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[(k >> 2) & (GS == kGradF32 ? 3 : 1)][k & 3]), tr.ab);
     else                gf = (float)sx16(G.g[(k >> 3) & 1][(k >> 1) & 3], k & 1);
-    if (MODE == kModeSmall)     update_small<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    if (MODE == kModeSmall)     update_small<DECAY, (WC == 16)>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
     else if (MODE == kModeWide) update_wide(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                        update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
@@ -353,7 +356,7 @@ __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const
     float gf;
     if constexpr (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[k >> 2].d[k & 3]), tr.ab);
     else                          gf = (float)sx16(G.g[k >> 3].d[(k >> 1) & 3], k & 1);
-    if constexpr (MODE == kModeSmall)     update_small<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
+    if constexpr (MODE == kModeSmall)     update_small<DECAY, (WC == 16)>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
     else if constexpr (MODE == kModeWide) update_wide(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                                  update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
@@ -448,9 +451,11 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   p.magic_dlo = (int)(md & 0xffffffffll);
   p.nlrwd_d   = -(double)p.lrwd;
   p.half_m1   = (1 << (p.d - 1)) - 1;
-  // small-value variant: |v| and |v| + rounding addend below 2^22 (exact in fp32, quotient inside the 2^22 window
-  // of the 1.5 * 2^23 offset), and (2^22 + theta') * 2^d inside int32
+  // small-value variant, int8 theta: |v| plus the rounding addend below 2^22 and (2^22 + theta') * 2^d inside int32
+  // (int8 accumulator, d <= 8), or below 2^23 with the residual formed unshifted (int16 accumulator, d <= 22);
+  // either way v is exact in fp32 and the quotient sits inside the 2^22 window of the 1.5 * 2^23 offset
   if (p.wt == 8 && p.wc == 8 && p.d <= 8 && bound < (1ll << 22)) p.mode = kModeSmall;
+  if (p.wt == 8 && p.wc == 16 && p.d <= 22 && bound < (1ll << 23)) p.mode = kModeSmall;
   p.bias_i  = -p.magic_fi;
   p.inv2d_f = __uint_as_float((uint32_t)(127 - p.d) << 23);
   p.lo_tf   = 12582912.0f + (float)p.qmin_t;
@@ -480,7 +485,7 @@ template <int WT, int WC, int GS>
 __device__ __forceinline__ uint64_t tile_vector(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
 {
   if (p.mode == kModeWide) return tile_fast_decay<WT, WC, GS, kModeWide>(p, T, off, cnt, lane, ab);
-  if (WT == 8 && WC == 8 && p.mode == kModeSmall) return tile_fast_decay<WT, WC, GS, kModeSmall>(p, T, off, cnt, lane, ab);
+  if (WT == 8 && p.mode == kModeSmall) return tile_fast_decay<WT, WC, GS, kModeSmall>(p, T, off, cnt, lane, ab);
   return tile_fast_decay<WT, WC, GS, kModeFast>(p, T, off, cnt, lane, ab);
 }
 
