@@ -97,6 +97,13 @@ def test_adam_config5_reduced_and_int8_moments():
     run_config(workloads.config(5, big_elems=70001, n_tiny=20), range(3), state_bits=8, fl_mom0=16, fl_sec0=30)
 
 
+def test_adam_config5_full_size_in_bench_launch_configuration():
+    """The 1 Gi + 10000 x 256 workload at full size, the lists and launch shape `bench.py --adam` times, every
+    output byte of two steps compared with the oracle (run on the host's threads)."""
+    say("adam: config 5 at FULL size, 2 steps")
+    run_config(workloads.config(5), range(2))
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_adam_random_lists(seed):
     """Random widths, shifts, grid moves, alignments, sizes and hyper-parameters straight through the C ABI,

@@ -86,6 +86,14 @@ def test_momentum_config5_reduced():
     run_config(cfg, [8] * cfg.n_tensors, range(5))
 
 
+def test_momentum_config5_full_size_in_bench_launch_configuration():
+    """The 1 Gi + 10000 x 256 workload at full size, the lists and launch shape `bench.py --momentum-bits 8` times,
+    every output byte of two steps compared with the oracle (run on the host's threads)."""
+    say("momentum: config 5 at FULL size, int8 velocity, 2 steps")
+    cfg = workloads.config(5)
+    run_config(cfg, [8] * cfg.n_tensors, range(2))
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_momentum_random_lists(seed):
     """Random widths, shifts, grid moves, alignments and sizes straight through the C ABI."""
