@@ -174,6 +174,22 @@ def main():
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fbytes / (f_upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                               "bytes_per_launch": fbytes}}
 
+    # the same whole step replayed from HIP graphs (one recording per resident gradient draw): what launch
+    # overhead is left once the three calls are captured -- matters for the small, launch-bound workloads
+    graph = None
+    if mu_q16 is None and not args.adam and not cfg.reselect:
+        graphs = [dev.capture_step(args.warmup, k) for k in range(n_src)]
+        for k in range(n_src):
+            graphs[k].replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for i in range(K):
+            graphs[i % n_src].replay()
+        torch.cuda.synchronize()
+        gwall = time.perf_counter() - t2
+        graph = {"ms_per_step": gwall * 1e3 / K, "value": cfg.n_params / (gwall / K) / 1e9, "unit": "Gparam/s"}
+        del graphs
+
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
     qnt_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / K
     upd_ms = sum(e[2].elapsed_time(e[3]) for e in ev) / K
@@ -248,6 +264,7 @@ def main():
             "maxabs_f32_kernel": {"GB/s": 4 * cfg.n_params / (sel_ms * 1e-3) / 1e9, "bytes_per_launch": 4 * cfg.n_params},
             "quantize_kernel": {"GB/s": 6 * cfg.n_params / (qnt_ms * 1e-3) / 1e9, "bytes_per_launch": 6 * cfg.n_params}},
         "fused_path": fused,
+        "graph_replay": graph,
         "stream_copy_yardstick": copy,
         "stream_mix_yardstick": mix,
         "device_status_word": status,

@@ -56,9 +56,14 @@ struct StepParams {
   float    lo_tf, hi_tf;    // 1.5 * 2^23 + rails of theta
   int      neg2d;           // -2^d
   int      lo_cb, hi_cb;    // rails of comp minus 2^(22 + d)
-  // wide path (fp64, any shifts): -lr * 2^-kg, -lr * wd * 2^-kw, 2^d, 2^u, 2^-kth, 2^kth, 2^-kc, rails
   int      mode;            // vector arithmetic: kModeFast, kModeSmall or kModeWide
-  double   w_ag, w_aw, w_p2d, w_p2u, w_inv_kth, w_p2kth, w_inv_kc, w_lo_t, w_hi_t, w_lo_c, w_hi_c;
+};
+
+// Constants of the wide path (fp64, any shifts), built from the shifts where that path starts so that they hold
+// no registers while the 32-bit loops run: -lr * 2^-kg, -lr * wd * 2^-kw, 2^d, 2^u, 2^-kth, 2^kth, 2^-kc, rails.
+struct WideParams {
+  bool   decay;
+  double ag, aw, p2d, p2u, inv_kth, p2kth, inv_kc, lo_t, hi_t, lo_c, hi_c;
 };
 
 enum { kModeFast = 0, kModeSmall = 1, kModeWide = 2 };
@@ -82,17 +87,28 @@ __device__ __forceinline__ float quant_grad(const StepParams& p, float x, uint32
 // shift points -- no branches, no 64-bit integer sequences.  The residual v_G - theta' * 2^kth is exact while it is
 // below 2^53; beyond that the accumulator saturates whatever the last bits are.
 
-__device__ __forceinline__ void update_wide(const StepParams& p, int th, int c, double g, int& th_new, int& c_new, double& vabs_max)
+__device__ __forceinline__ WideParams make_wide(const StepParams& p)
+{
+  WideParams w;
+  w.decay = p.lrwd != 0;
+  w.ag = -(double)p.lr * pow2d(-p.kg);
+  w.aw = -(double)p.lrwd * pow2d(-p.kw);
+  w.p2d = pow2d(p.d); w.p2u = pow2d(p.u); w.inv_kth = pow2d(-p.kth); w.p2kth = pow2d(p.kth); w.inv_kc = pow2d(-p.kc);
+  w.lo_t = (double)p.qmin_t; w.hi_t = (double)p.qmax_t; w.lo_c = (double)p.qmin_c; w.hi_c = (double)p.qmax_c;
+  return w;
+}
+
+__device__ __forceinline__ void update_wide(const WideParams& w, int th, int c, double g, int& th_new, int& c_new, double& vabs_max)
 {
   const double cap = 1099511627776.0;                       // 2^40
-  double s = clampd(__builtin_rint(g * p.w_ag), -cap, cap);
-  if (p.lrwd) s += clampd(__builtin_rint((double)th * p.w_aw), -cap, cap);
-  const double v = __builtin_fma((double)th, p.w_p2d, (double)c) + s;
+  double s = clampd(__builtin_rint(g * w.ag), -cap, cap);
+  if (w.decay) s += clampd(__builtin_rint((double)th * w.aw), -cap, cap);
+  const double v = __builtin_fma((double)th, w.p2d, (double)c) + s;
   vabs_max = __builtin_fmax(vabs_max, __builtin_fabs(v));
-  const double vG = v * p.w_p2u;
-  const double tn = clampd(__builtin_rint(vG * p.w_inv_kth), p.w_lo_t, p.w_hi_t);
-  const double rr = __builtin_fma(-tn, p.w_p2kth, vG);
-  const double cn = clampd(__builtin_rint(rr * p.w_inv_kc), p.w_lo_c, p.w_hi_c);
+  const double vG = v * w.p2u;
+  const double tn = clampd(__builtin_rint(vG * w.inv_kth), w.lo_t, w.hi_t);
+  const double rr = __builtin_fma(-tn, w.p2kth, vG);
+  const double cn = clampd(__builtin_rint(rr * w.inv_kc), w.lo_c, w.hi_c);
   th_new = (int)tn; c_new = (int)cn;
 }
 
@@ -102,13 +118,14 @@ __device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const Tens
                                                  uint32_t& ab_max)
 {
   double vw = 0.0;
+  const WideParams w = make_wide(p);
   for (uint32_t j = lane; j < cnt; j += kWave) {
     uint64_t i = off + j;
     int th = load_elem(T.theta, i, p.wt);
     int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
     int g  = GS == kGradF32 ? (int)quant_grad(p, ((const float*)T.src)[i], ab_max) : load_elem(T.grad, i, p.wg);
     int tn, cn;
-    update_wide(p, th, c, (double)g, tn, cn, vw);
+    update_wide(w, th, c, (double)g, tn, cn, vw);
     store_elem(T.theta, i, p.wt, tn);
     if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
   }
@@ -217,7 +234,7 @@ template <int W> __device__ __forceinline__ void store16v(void* base, uint64_t e
 }
 
 template <int WT, int WC, int GS, bool DECAY, int MODE>
-__device__ __forceinline__ void compute_group(const StepParams& p, const Group<WT, WC, GS>& G, GroupOut<WT, WC>& O, Track& tr)
+__device__ __forceinline__ void compute_group(const StepParams& p, const WideParams& w, const Group<WT, WC, GS>& G, GroupOut<WT, WC>& O, Track& tr)
 {
   int tn[16], cn[16];
 #pragma unroll
@@ -226,7 +243,7 @@ __device__ __forceinline__ void compute_group(const StepParams& p, const Group<W
     if (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[(k >> 2) & (GS == kGradF32 ? 3 : 1)][k & 3]), tr.ab);
     else                gf = (float)sx16(G.g[(k >> 3) & 1][(k >> 1) & 3], k & 1);
     if (MODE == kModeSmall)     update_small<DECAY, (WC == 16)>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
-    else if (MODE == kModeWide) update_wide(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
+    else if (MODE == kModeWide) update_wide(w, elem16<WT>(G.th, k), elem16<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                        update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
   pack16<WT>(O.th, tn);
@@ -241,10 +258,10 @@ __device__ __forceinline__ void store_group(const GroupOut<WT, WC>& O, const Ten
 }
 
 template <int WT, int WC, int GS, bool DECAY, int MODE>
-__device__ __forceinline__ void compute_store_group(const StepParams& p, const Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
+__device__ __forceinline__ void compute_store_group(const StepParams& p, const WideParams& w, const Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
   GroupOut<WT, WC> O;
-  compute_group<WT, WC, GS, DECAY, MODE>(p, G, O, tr);
+  compute_group<WT, WC, GS, DECAY, MODE>(p, w, G, O, tr);
   store_group<WT, WC>(O, T, e);
 }
 
@@ -260,8 +277,11 @@ template <int WT, int WC, int GS, bool DECAY, int MODE>
 __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
 {
   Track tr{0, 0, ab_max, 0.0};
+  const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
   constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : 8);     // VGPRs of one group
-  constexpr int kP = kRegs <= 16 ? LPK_I16_GROUPS : LPK_KP_WIDE;                     // groups in flight per lane
+  // groups in flight per lane; one in the wide arithmetic, whose fp64 temporaries would otherwise set the register
+  // count of the whole kernel
+  constexpr int kP = MODE == kModeWide ? 1 : (kRegs <= 16 ? LPK_I16_GROUPS : LPK_KP_WIDE);
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
@@ -269,13 +289,13 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, MODE>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
+    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, MODE>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     Group<WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * kGroup;
     load_group(G, T, e);
-    compute_store_group<WT, WC, GS, DECAY, MODE>(p, G, T, e, tr);
+    compute_store_group<WT, WC, GS, DECAY, MODE>(p, w, G, T, e, tr);
   }
   ab_max = tr.ab;
   uint64_t vm = track_max(tr);
@@ -348,7 +368,7 @@ __device__ __forceinline__ void load_group_e(GroupE<E, WT, WC, GS>& G, const Ten
 }
 
 template <int E, int WT, int WC, int GS, bool DECAY, int MODE>
-__device__ __forceinline__ void compute_store_group_e(const StepParams& p, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
+__device__ __forceinline__ void compute_store_group_e(const StepParams& p, const WideParams& w, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
   int tn[E], cn[E];
 #pragma unroll
@@ -357,7 +377,7 @@ __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const
     if constexpr (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[k >> 2].d[k & 3]), tr.ab);
     else                          gf = (float)sx16(G.g[k >> 3].d[(k >> 1) & 3], k & 1);
     if constexpr (MODE == kModeSmall)     update_small<DECAY, (WC == 16)>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
-    else if constexpr (MODE == kModeWide) update_wide(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
+    else if constexpr (MODE == kModeWide) update_wide(w, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                                  update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
   st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
@@ -368,6 +388,7 @@ template <int E, int KP, int WT, int WC, int GS, bool DECAY, int MODE>
 __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
 {
   Track tr{0, 0, ab_max, 0.0};
+  const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
   const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;
   for (; gi + (KP - 1) * kWave < ngroups; gi += KP * kWave) {
@@ -375,13 +396,13 @@ __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const Tenso
 #pragma unroll
     for (int ps = 0; ps < KP; ++ps) load_group_e(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
-    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, MODE>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
+    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, MODE>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     GroupE<E, WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * E;
     load_group_e(G, T, e);
-    compute_store_group_e<E, WT, WC, GS, DECAY, MODE>(p, G, T, e, tr);
+    compute_store_group_e<E, WT, WC, GS, DECAY, MODE>(p, w, G, T, e, tr);
   }
   ab_max = tr.ab;
   uint64_t vm = track_max(tr);
@@ -418,10 +439,6 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   p.qmax_c = (1 << (wc - 1)) - 1;   p.qmin_c = -(1 << (wc - 1));
   p.gscale = __uint_as_float((uint32_t)(127 + fl_g) << 23);
   p.glo = -(float)(1 << (p.wg - 1)); p.ghi = (float)((1 << (p.wg - 1)) - 1);
-  p.w_ag = -(double)lr * pow2d(-p.kg);
-  p.w_aw = -(double)p.lrwd * pow2d(-p.kw);
-  p.w_p2d = pow2d(p.d); p.w_p2u = pow2d(p.u); p.w_inv_kth = pow2d(-p.kth); p.w_p2kth = pow2d(p.kth); p.w_inv_kc = pow2d(-p.kc);
-  p.w_lo_t = (double)p.qmin_t; p.w_hi_t = (double)p.qmax_t; p.w_lo_c = (double)p.qmin_c; p.w_hi_c = (double)p.qmax_c;
   p.path = 1; p.mode = kModeWide;
 
   // Vector path: theta, comp and 16-bit gradients on 16-byte aligned buffers, comp as wide as theta (or int8 theta
@@ -472,8 +489,8 @@ __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const T
 {
   const bool decay = MODE != kModeWide && p.lrwd;           // the wide arithmetic tests the decay term itself
   if (GS == kGradF32)
-    return decay ? tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
-                 : tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
+    return decay ? tile_fast_e<LPK_F32_E, (MODE == kModeWide ? 1 : LPK_F32_GROUPS), WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
+                 : tile_fast_e<LPK_F32_E, (MODE == kModeWide ? 1 : LPK_F32_GROUPS), WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
 #if LPK_I16_E != 16
   return decay ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
                : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);

@@ -140,7 +140,7 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
 {
   MaxTrack mt{0, 0, 0, 0};
   WideMax mx{0.0, 0.0};
-  constexpr int kP = (WT + WM) > 16 || WIDE ? 2 : 4;      // passes in flight: bounded by registers
+  constexpr int kP = WIDE ? 1 : ((WT + WM) > 16 ? 2 : 4);  // passes in flight: bounded by registers (the wide path would set the kernel's count)
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {

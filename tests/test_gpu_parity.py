@@ -142,3 +142,30 @@ def test_int8_theta_with_int16_accumulator():
     cfg = workloads.config(5, big_elems=(1 << 22) + 5, n_tiny=100)
     run_config(cfg, range(4), comp_bits=[16] * cfg.n_tensors)
     run_config(cfg, range(4), comp_bits=[16] * cfg.n_tensors, fused=True)
+
+
+def test_whole_step_replayed_from_a_hip_graph():
+    """The three hot calls only enqueue kernels, so a whole step can be recorded once and replayed: every replay
+    (fresh gradients uploaded eagerly in between, a synchronization and a download after each) matches the oracle."""
+    from paper_1810_05486_amd.device_state import DeviceState
+    for cfg in (workloads.config(1), workloads.config(3), workloads.config(5, big_elems=(1 << 21) + 77, n_tiny=64)):
+        say("hip graph replay: config %d" % cfg.id)
+        dev, host = DeviceState(cfg), OracleState(cfg)
+        views = dev.host_src_views()
+        theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
+        dev.upload_src()
+        dev.init_theta()
+        host.init_theta(theta0)
+        grads = [cfg.grad(t, 0, out=views[t]) for t in range(cfg.n_tensors)]
+        dev.upload_src()
+        graph = dev.capture_step(0)                 # runs step 0 eagerly once, then records it (recording executes nothing)
+        host.step(0, grads)
+        compare(dev, host, "config %d eager step before the replays" % cfg.id)
+        for s in range(1, 7):
+            grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
+            dev.upload_src()
+            graph.replay()
+            host.step(s, grads)
+            compare(dev, host, "config %d graph replay %d" % (cfg.id, s))
+        del graph
+        dev.close()
