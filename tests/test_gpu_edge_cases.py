@@ -314,3 +314,39 @@ def test_fused_step_with_special_gradient_values():
             assert int(vmax.item()) == wv and int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0]) == ref.STATUS_NONFINITE
         assert int(dg.count_nonzero().item()) == 0
         tl.destroy()
+
+
+def test_calls_follow_the_stream_they_are_given():
+    """Every call takes its hipStream_t explicitly: the whole path enqueued on a side stream (default priority),
+    ordered after the upload by an event, while the default stream is kept busy with unrelated work."""
+    say("explicit side stream")
+    rng = np.random.default_rng(11)
+    n = 3 * 4096 + 19
+    x = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    theta = rng.integers(-100, 100, size=n).astype(np.int8); comp = rng.integers(-60, 60, size=n).astype(np.int8)
+    side = torch.cuda.Stream()
+    d_src = torch.from_numpy(x).to(DEV)
+    d_theta = torch.from_numpy(theta).to(DEV); d_comp = torch.from_numpy(comp).to(DEV)
+    d_grad = torch.zeros(n, dtype=torch.int16, device=DEV)
+    fl_t = torch.tensor([7], dtype=torch.int32, device=DEV); fl_g = torch.tensor([15], dtype=torch.int32, device=DEV)
+    vmax = torch.zeros(1, dtype=torch.int64, device=DEV); status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(d_theta, d_comp, d_grad, d_src)])
+    ready = torch.cuda.Event()
+    ready.record()                                         # inputs are on the device once the default stream gets here
+    busy = torch.zeros(1 << 24, dtype=torch.float32, device=DEV)
+    for _ in range(20):
+        busy.add_(1.0)                                     # unrelated default-stream work in flight meanwhile
+    side.wait_event(ready)
+    lpk.lpk_select_fraclen(tl, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, fl_g, fl_g, status, stream=side)
+    lpk.lpk_quantize_tensor(tl, lpk.LPK_SEL_GRAD, fl_g, status, stream=side)
+    lpk.lpk_kahan_sgd_step(tl, fl_t, fl_t, fl_g, 6554, 0, vmax, status, stream=side)
+    side.synchronize()
+    torch.cuda.synchronize()
+    want_fl = ref.select_fraclen_f32(x, 16, 15)
+    g = ref.quantize(x, 16, want_fl)
+    want_v = ref.kahan_sgd_step(theta, comp, g, 7, 7, 7, want_fl, 6554)
+    assert int(fl_g.item()) == want_fl and int(vmax.item()) == want_v and int(status.item()) == 0
+    assert np.array_equal(d_grad.cpu().numpy(), g)
+    assert np.array_equal(d_theta.cpu().numpy(), theta) and np.array_equal(d_comp.cpu().numpy(), comp)
+    assert float(busy[0].item()) == 20.0
+    tl.destroy()
