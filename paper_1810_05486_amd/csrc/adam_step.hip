@@ -13,16 +13,19 @@
 // operations are repaired with exact residuals: the root by the sign of fma(r, r, -A), the quotient by the
 // remainder fma(-q, den, num) compared with half the divisor (ties to even).
 //
-// Same work distribution as the plain update (persistent wavefronts over the tile table, 16 consecutive elements
-// per lane per pass, dwordx4 non-temporal accesses) for int16 moments and gradients on 16-byte aligned buffers;
-// anything else goes element by element through the same arithmetic.
+// Same work distribution as the plain update (persistent wavefronts over the tile table, non-temporal vector
+// accesses) for int16 moments and gradients on 16-byte aligned buffers; anything else goes element by element
+// through the same arithmetic.
 #include "step_common.hpp"
 
+#ifndef LPK_ADAM_E
+#define LPK_ADAM_E 8                   // consecutive elements per lane per group (4 or 8)
+#endif
 #ifndef LPK_ADAM_GROUPS
-#define LPK_ADAM_GROUPS 1
+#define LPK_ADAM_GROUPS 2              // groups in flight per lane
 #endif
 #ifndef LPK_ADAM_WAVES_PER_SIMD
-#define LPK_ADAM_WAVES_PER_SIMD 2      // register budget: 512 / this many VGPRs per lane
+#define LPK_ADAM_WAVES_PER_SIMD 3      // register budget: 512 / this many VGPRs per lane
 #endif
 
 namespace lpk {
@@ -38,14 +41,21 @@ struct AdamParams {
   double nlr;                      // -lr * 2^max(e, 0)
   double dscale;                   // 2^max(-e, 0)
   double p2d, p2u, inv_kth, p2kth, inv_kc;
+  // 32-bit tail (int8 theta, fixed grid, every |intermediate| of Algorithm 1 below 2^22): as in the plain update,
+  // fma(v, 2^-d, 1.5 * 2^23) rounds v onto theta's grid and one 24-bit multiply-add forms the residual
+  int    tail;                     // kTailWide, kTailSmall (int8 accumulator, d <= 8) or kTailSmallBigD (int16 accumulator)
+  int    d, neg2d, lo_cb, hi_cb, lo_c, hi_c;
+  float  inv2d_f, lo_tf, hi_tf;
 };
 
-struct AdamTrack { double vm, mm, um; };
+enum { kTailWide = 0, kTailSmall = 1, kTailSmallBigD = 2 };
+
+struct AdamTrack { double vm, mm, um; int vmx, vmn; };
 
 __device__ __forceinline__ double cap_d() { return 1099511627776.0; }          // 2^40
 
 // CAPS: whether a 2^40 cap can bind for this tensor's shifts (wave-uniform; almost never).
-template <bool CAPS>
+template <bool CAPS, int TAIL>
 __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, int m, int u, int g,
                                             int& tn, int& cn, int& mn, int& un, AdamTrack& tr)
 {
@@ -71,8 +81,10 @@ __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, 
   const double A = unew * p.ascale;
   double r = __builtin_floor((double)__builtin_amdgcn_sqrtf((float)A));
   const double r1 = r + 1.0;
-  const bool too_big = __builtin_fma(r, r, -A) > 0.0, too_small = __builtin_fma(r1, r1, -A) <= 0.0;
-  r = too_big ? r - 1.0 : (too_small ? r1 : r);
+  // both residuals unconditionally (r^2 > A excludes (r + 1)^2 <= A), so the repair is two selects and no branch:
+  // a branch here would keep the compiler from interleaving the sixteen elements' dependency chains
+  const double r_dn = __builtin_fma(r, r, -A) > 0.0 ? 1.0 : 0.0, r_up = __builtin_fma(r1, r1, -A) <= 0.0 ? 1.0 : 0.0;
+  r = (r - r_dn) + r_up;
   const double den = __builtin_fmax(r + p.eps_r, 1.0) * p.dscale;
   // Step: RNE(num / den).  Reciprocal seed plus two Newton steps (relative error near 2^-52), so the rounded
   // product is within one of the exact rounded quotient whenever that is below 2^41 (larger ones end at the
@@ -88,14 +100,24 @@ __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, 
   const bool up = (two_rem > den) | ((two_rem == den) & odd), down = (two_rem < -den) | ((two_rem == -den) & odd);
   q += up ? 1.0 : (down ? -1.0 : 0.0);
   const double s = CAPS ? clampd(q, -cap, cap) : q;
+  mn = (int)mnew; un = (int)unew;
   // Algorithm 1 with this step
+  if (TAIL != kTailWide) {
+    const int v = (int)((unsigned)th << p.d) + c + (int)s;
+    tr.vmx = v > tr.vmx ? v : tr.vmx;
+    tr.vmn = v < tr.vmn ? v : tr.vmn;
+    tn = __float_as_int(__builtin_amdgcn_fmed3f(__builtin_fmaf((float)v, p.inv2d_f, 12582912.0f), p.lo_tf, p.hi_tf));
+    if (TAIL == kTailSmallBigD) cn = med3_i32(mad_i24(tn - 0x4B400000, p.neg2d, v), p.lo_c, p.hi_c);   // bits(1.5 * 2^23)
+    else                        cn = med3_i32(mad_i24(tn, p.neg2d, v), p.lo_cb, p.hi_cb);
+    return;
+  }
   const double v = __builtin_fma((double)th, p.p2d, (double)c) + s;
   tr.vm = __builtin_fmax(tr.vm, __builtin_fabs(v));
   const double vG = v * p.p2u;
   const double tnew = clampd(__builtin_rint(vG * p.inv_kth), p.qmin_t, p.qmax_t);
   const double rr = __builtin_fma(-tnew, p.p2kth, vG);      // exact below 2^53; beyond that comp saturates either way
   const double cnew = clampd(__builtin_rint(rr * p.inv_kc), p.qmin_c, p.qmax_c);
-  tn = (int)tnew; cn = (int)cnew; mn = (int)mnew; un = (int)unew;
+  tn = (int)tnew; cn = (int)cnew;
 }
 
 // Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
@@ -110,7 +132,7 @@ __device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const Ten
     const int u  = load_elem(T.sec, i, p.wu);
     const int g  = load_elem(T.grad, i, p.wg);
     int tn, cn, mn, un;
-    update_adam<CAPS>(p, th, c, m, u, g, tn, cn, mn, un, tr);
+    update_adam<CAPS, kTailWide>(p, th, c, m, u, g, tn, cn, mn, un, tr);
     store_elem(T.theta, i, p.wt, tn);
     if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
     store_elem(T.mom, i, p.wm, mn);
@@ -118,53 +140,60 @@ __device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const Ten
   }
 }
 
-// 16 consecutive elements per lane; int16 moments and gradients.
-template <int WT, int WC> struct AGroup {
-  v4i th[WT / 8], c[WC / 8], m[2], u[2], g[2];
+// E consecutive elements per lane; int16 moments and gradients.  With E = 8 every access of a wave is one contiguous
+// run (dwordx4 for the 16-bit arrays, dwordx2 for 8-bit ones) and the fp64 temporaries of a group fit a register
+// budget that leaves room for more than two waves per SIMD.
+template <int E, int WT, int WC> struct AGroup {
+  DW<E * WT / 32> th;
+  DW<E * WC / 32> c;
+  DW<E / 2> m, u, g;
 };
 
-template <int WT, int WC>
-__device__ __forceinline__ void load_group_adam(AGroup<WT, WC>& G, const TensorDev& T, uint64_t e)
+template <int E, int WT, int WC>
+__device__ __forceinline__ void load_group_adam(AGroup<E, WT, WC>& G, const TensorDev& T, uint64_t e)
 {
-  load16<WT>(G.th, T.theta, e); load16<WC>(G.c, T.comp, e);
-  load16<16>(G.m, T.mom, e); load16<16>(G.u, T.sec, e); load16<16>(G.g, T.grad, e);
+  G.th = ld_dw<E * WT / 32>((const int8_t*)T.theta + e * (WT / 8));
+  G.c  = ld_dw<E * WC / 32>((const int8_t*)T.comp + e * (WC / 8));
+  G.m  = ld_dw<E / 2>((const int16_t*)T.mom + e);
+  G.u  = ld_dw<E / 2>((const int16_t*)T.sec + e);
+  G.g  = ld_dw<E / 2>((const int16_t*)T.grad + e);
 }
 
-template <int WT, int WC, bool CAPS>
-__device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<WT, WC>& G, const TensorDev& T, uint64_t e, AdamTrack& tr)
+template <int E, int WT, int WC, bool CAPS, int TAIL>
+__device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, WT, WC>& G, const TensorDev& T, uint64_t e, AdamTrack& tr)
 {
-  int tn[16], cn[16], mn[16], un[16];
+  int tn[E], cn[E], mn[E], un[E];
 #pragma unroll
-  for (int k = 0; k < 16; ++k)
-    update_adam<CAPS>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), elem16<16>(G.m, k), elem16<16>(G.u, k), elem16<16>(G.g, k),
-                tn[k], cn[k], mn[k], un[k], tr);
-  store16<WT>(T.theta, e, tn);
-  store16<WC>(T.comp, e, cn);
-  store16<16>(T.mom, e, mn);
-  store16<16>(T.sec, e, un);
+  for (int k = 0; k < E; ++k)
+    update_adam<CAPS, TAIL>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), elem_dw<16>(G.m, k), elem_dw<16>(G.u, k), elem_dw<16>(G.g, k),
+                            tn[k], cn[k], mn[k], un[k], tr);
+  st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
+  st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
+  st_dw((int16_t*)T.mom + e, pack_dw<16, E>(mn));
+  st_dw((int16_t*)T.sec + e, pack_dw<16, E>(un));
 }
 
-template <int WT, int WC, bool CAPS>
+template <int WT, int WC, bool CAPS, int TAIL>
 __device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
 {
-  constexpr int kP = LPK_ADAM_GROUPS;                      // groups in flight per lane
-  const uint32_t ngroups = cnt / kGroup;
+  constexpr int E = LPK_ADAM_E, kP = LPK_ADAM_GROUPS;      // elements per lane per group, groups in flight per lane
+  const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
-    AGroup<WT, WC> G[kP];
+    AGroup<E, WT, WC> G[kP];
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) load_group_adam(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
+    for (int ps = 0; ps < kP; ++ps) load_group_adam(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) group_adam<WT, WC, CAPS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
+    for (int ps = 0; ps < kP; ++ps) group_adam<E, WT, WC, CAPS, TAIL>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
   }
   for (; gi < ngroups; gi += kWave) {
-    AGroup<WT, WC> G;
-    const uint64_t e = off + (uint64_t)gi * kGroup;
+    AGroup<E, WT, WC> G;
+    const uint64_t e = off + (uint64_t)gi * E;
     load_group_adam(G, T, e);
-    group_adam<WT, WC, CAPS>(p, G, T, e, tr);
+    group_adam<E, WT, WC, CAPS, TAIL>(p, G, T, e, tr);
   }
-  const uint32_t tail = cnt - ngroups * kGroup;
-  if (tail) tile_generic_adam<CAPS>(p, T, off + (uint64_t)ngroups * kGroup, tail, lane, tr);
+  const uint32_t tail = cnt - ngroups * E;
+  if (tail) tile_generic_adam<CAPS>(p, T, off + (uint64_t)ngroups * E, tail, lane, tr);
 }
 
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
@@ -207,11 +236,30 @@ __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, in
   p.path = 1;
   const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
   if (p.has_comp && T.vec_adam && widths_ok && p.wg == 16 && p.wm == 16 && p.wu == 16) p.path = 2;
+  // 32-bit tail: |theta * 2^d| + |c| + |s| + the rounding addend provably below 2^22 (2^23 with the residual formed
+  // unshifted), theta's grid fixed, 1 <= d
+  p.tail = kTailWide;
+  const double vbound = pow2d(p.wt - 1 + d) + pow2d(wc - 1) + step_bound + 1.0 + pow2d(d > 0 ? d - 1 : 0);
+  if (p.path == 2 && p.wt == 8 && delta == 0 && d >= 1 && !p.caps) {
+    if (p.wc == 8 && d <= 8 && vbound < 4194304.0) p.tail = kTailSmall;
+    if (p.wc == 16 && d <= 22 && vbound < 8388608.0) p.tail = kTailSmallBigD;
+  }
+  p.d = d; p.neg2d = -(1 << d);
+  p.inv2d_f = __uint_as_float((uint32_t)(127 - d) << 23);
+  p.lo_tf = 12582912.0f - (float)(1 << (p.wt - 1)); p.hi_tf = 12582912.0f + (float)((1 << (p.wt - 1)) - 1);
+  p.lo_c = -(1 << (wc - 1)); p.hi_c = (1 << (wc - 1)) - 1;
+  p.lo_cb = p.lo_c - (1 << (22 + (d <= 8 ? d : 8))); p.hi_cb = p.hi_c - (1 << (22 + (d <= 8 ? d : 8)));
 }
 
 // ---------------------------------------------------------------- the kernel
 
 __device__ __forceinline__ uint64_t track_u64(double x) { return (uint64_t)x; }     // an integer below 2^53
+__device__ __forceinline__ uint64_t track_v(const AdamTrack& tr)                    // both tails' maxima of |v|
+{
+  const int64_t a = tr.vmx, b = -(int64_t)tr.vmn;
+  const uint64_t m32 = (uint64_t)(a > b ? a : b), m64 = (uint64_t)tr.vm;
+  return m32 > m64 ? m32 : m64;
+}
 
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(LPK_ADAM_WAVES_PER_SIMD, LPK_ADAM_WAVES_PER_SIMD)))
 adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
@@ -229,7 +277,7 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
   const uint32_t nw = gridDim.x * kWavesPerBlock;
 
   int cur = -1;
-  AdamTrack tr{0.0, 0.0, 0.0};
+  AdamTrack tr{0.0, 0.0, 0.0, 0, 0};
   uint32_t status_bits = 0;
   AdamParams p; p.path = 0;
   TensorDev T;
@@ -239,26 +287,32 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
     read_tile(tiles, ti, t, cnt, off);
     if (t != cur) {
       if (cur >= 0) {
-        if (vmax) flush_wave(vmax, cur, track_u64(tr.vm), lane);
+        if (vmax) flush_wave(vmax, cur, track_v(tr), lane);
         if (mmax) flush_wave(mmax, cur, track_u64(tr.mm), lane);
         if (umax) flush_wave(umax, cur, track_u64(tr.um), lane);
       }
-      tr = AdamTrack{0.0, 0.0, 0.0};
+      tr = AdamTrack{0.0, 0.0, 0.0, 0, 0};
       cur = t;
       T = tensors[t];
       setup_adam(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_u_in[t], fl_u_out[t], fl_g[t], h, status_bits);
     }
     if (p.path == 2 && !p.caps) {
-      if (p.wt == 8 && p.wc == 8) tile_vec_adam<8, 8, false>(p, T, off, cnt, lane, tr);
-      else if (p.wt == 16)        tile_vec_adam<16, 16, false>(p, T, off, cnt, lane, tr);
-      else                        tile_vec_adam<8, 16, false>(p, T, off, cnt, lane, tr);
+      if (p.wt == 8 && p.wc == 8) {
+        if (p.tail == kTailSmall) tile_vec_adam<8, 8, false, kTailSmall>(p, T, off, cnt, lane, tr);
+        else                      tile_vec_adam<8, 8, false, kTailWide>(p, T, off, cnt, lane, tr);
+      } else if (p.wt == 16) {
+        tile_vec_adam<16, 16, false, kTailWide>(p, T, off, cnt, lane, tr);
+      } else {
+        if (p.tail == kTailSmallBigD) tile_vec_adam<8, 16, false, kTailSmallBigD>(p, T, off, cnt, lane, tr);
+        else                          tile_vec_adam<8, 16, false, kTailWide>(p, T, off, cnt, lane, tr);
+      }
     } else if (p.path) {
       if (p.caps) tile_generic_adam<true>(p, T, off, cnt, lane, tr); else tile_generic_adam<false>(p, T, off, cnt, lane, tr);
     }
   }
 
   if (status && status_bits && lane == 0) atomicOr(status, status_bits);
-  if (vmax) flush_block(vmax, cur, track_u64(tr.vm), lane, wave, s_tensor, s_max);
+  if (vmax) flush_block(vmax, cur, track_v(tr), lane, wave, s_tensor, s_max);
   if (mmax) flush_block(mmax, cur, track_u64(tr.mm), lane, wave, s_tensor, s_max);
   if (umax) flush_block(umax, cur, track_u64(tr.um), lane, wave, s_tensor, s_max);
 }

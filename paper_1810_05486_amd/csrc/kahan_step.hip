@@ -160,20 +160,6 @@ __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, 
 // fp32), clamped as a float between M + qmin and M + qmax.  The low
 // 24 bits of that float are 2^22 + theta', so one 24-bit multiply-add forms v - theta' * 2^d - 2^(22 + d); the
 // accumulator rails are shifted by the same constant, and the low bytes of both results are the bytes to store.
-__device__ __forceinline__ int med3_i32(int x, int lo, int hi)
-{
-  int r;
-  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "v"(hi));
-  return r;
-}
-
-__device__ __forceinline__ int mad_i24(int a, int b, int c)          // sext24(a) * sext24(b) + c
-{
-  int r;
-  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
-}
-
 // BIGD (d > 8, the int16 accumulator under an int8 theta): (2^22 + theta') * 2^d no longer fits 32 bits, so
 // theta' is first taken out of the float's bit pattern and the residual is formed and clamped unshifted.
 template <bool DECAY, bool BIGD>
@@ -313,38 +299,6 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 // gradients, 16 per lane would mean 64 contiguous bytes of gradients per lane (four loads whose lanes sit 64
 // bytes apart), which the memory pipeline handles far worse than HBM itself; fewer elements per lane trade
 // wider gradient accesses for narrower theta/comp accesses.  This path is generic in E (4, 8 or 16).
-
-typedef int v2i __attribute__((ext_vector_type(2)));
-template <int N> struct DW { int d[N]; };                 // N = 1, 2 or 4 dwords moved by one access
-
-template <int N> __device__ __forceinline__ DW<N> ld_dw(const void* p)
-{
-  DW<N> r;
-  if constexpr (N == 1) { r.d[0] = ld_stream((const int*)p); }
-  else if constexpr (N == 2) { v2i v = ld_stream((const v2i*)p); r.d[0] = v[0]; r.d[1] = v[1]; }
-  else { v4i v = ld_stream((const v4i*)p); r.d[0] = v[0]; r.d[1] = v[1]; r.d[2] = v[2]; r.d[3] = v[3]; }
-  return r;
-}
-template <int N> __device__ __forceinline__ void st_dw(void* p, const DW<N>& r)
-{
-  if constexpr (N == 1) { st_stream((int*)p, r.d[0]); }
-  else if constexpr (N == 2) { v2i v; v[0] = r.d[0]; v[1] = r.d[1]; st_stream((v2i*)p, v); }
-  else { v4i v; v[0] = r.d[0]; v[1] = r.d[1]; v[2] = r.d[2]; v[3] = r.d[3]; st_stream((v4i*)p, v); }
-}
-template <int W, int N> __device__ __forceinline__ int elem_dw(const DW<N>& r, int k)
-{
-  if constexpr (W == 8) return sx8(r.d[k >> 2], k & 3); else return sx16(r.d[k >> 1], k & 1);
-}
-template <int W, int E> __device__ __forceinline__ DW<E * W / 32> pack_dw(const int (&val)[E])
-{
-  DW<E * W / 32> r;
-#pragma unroll
-  for (int w = 0; w < E * W / 32; ++w) {
-    if constexpr (W == 8) r.d[w] = pack4x8(val[4 * w], val[4 * w + 1], val[4 * w + 2], val[4 * w + 3]);
-    else                  r.d[w] = pack2x16(val[2 * w], val[2 * w + 1]);
-  }
-  return r;
-}
 
 template <int E, int WT, int WC, int GS> struct GroupE {
   static constexpr int kG = GS == kGradF32 ? E / 4 : (E >= 8 ? E / 8 : 1);      // gradient accesses

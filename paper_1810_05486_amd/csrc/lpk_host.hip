@@ -134,7 +134,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     };
     L->grid = clampg(env_u32("LPK_BLOCKS_PER_CU", 2));
     L->grid_step = clampg(env_u32("LPK_STEP_BLOCKS_PER_CU", 1));
-    L->grid_adam = clampg(env_u32("LPK_ADAM_BLOCKS_PER_CU", 2));
+    L->grid_adam = clampg(env_u32("LPK_ADAM_BLOCKS_PER_CU", 3));
     ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
          hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * n_tensors) == hipSuccess &&
          (tiles.empty() || hipMalloc((void**)&L->d_tiles, sizeof(Tile) * tiles.size()) == hipSuccess);

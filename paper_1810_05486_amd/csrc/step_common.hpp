@@ -9,6 +9,21 @@ namespace lpk {
 __device__ __forceinline__ double pow2d(int k) { return __longlong_as_double((long long)(1023 + k) << 52); }
 __device__ __forceinline__ double clampd(double x, double lo, double hi) { return __builtin_fmin(__builtin_fmax(x, lo), hi); }
 
+// Median of three (a clamp when lo <= hi) and the 24-bit multiply-add, as single VALU operations.
+__device__ __forceinline__ int med3_i32(int x, int lo, int hi)
+{
+  int r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "v"(hi));
+  return r;
+}
+
+__device__ __forceinline__ int mad_i24(int a, int b, int c)          // sext24(a) * sext24(b) + c
+{
+  int r;
+  asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 __device__ __forceinline__ int load_elem(const void* p, uint64_t i, int bits)
 {
   return bits == 8 ? (int)((const int8_t*)p)[i] : (int)((const int16_t*)p)[i];
@@ -87,6 +102,39 @@ template <int W> __device__ __forceinline__ void store16(void* base, uint64_t e,
       st_stream((v4i*)((int16_t*)base + e + 8 * q), o);
     }
   }
+}
+
+// E consecutive elements of one lane as 1, 2 or 4 dwords per array: load, pick the k-th element, pack, store.
+typedef int v2i __attribute__((ext_vector_type(2)));
+template <int N> struct DW { int d[N]; };                 // N = 1, 2 or 4 dwords moved by one access
+
+template <int N> __device__ __forceinline__ DW<N> ld_dw(const void* p)
+{
+  DW<N> r;
+  if constexpr (N == 1) { r.d[0] = ld_stream((const int*)p); }
+  else if constexpr (N == 2) { v2i v = ld_stream((const v2i*)p); r.d[0] = v[0]; r.d[1] = v[1]; }
+  else { v4i v = ld_stream((const v4i*)p); r.d[0] = v[0]; r.d[1] = v[1]; r.d[2] = v[2]; r.d[3] = v[3]; }
+  return r;
+}
+template <int N> __device__ __forceinline__ void st_dw(void* p, const DW<N>& r)
+{
+  if constexpr (N == 1) { st_stream((int*)p, r.d[0]); }
+  else if constexpr (N == 2) { v2i v; v[0] = r.d[0]; v[1] = r.d[1]; st_stream((v2i*)p, v); }
+  else { v4i v; v[0] = r.d[0]; v[1] = r.d[1]; v[2] = r.d[2]; v[3] = r.d[3]; st_stream((v4i*)p, v); }
+}
+template <int W, int N> __device__ __forceinline__ int elem_dw(const DW<N>& r, int k)
+{
+  if constexpr (W == 8) return sx8(r.d[k >> 2], k & 3); else return sx16(r.d[k >> 1], k & 1);
+}
+template <int W, int E> __device__ __forceinline__ DW<E * W / 32> pack_dw(const int (&val)[E])
+{
+  DW<E * W / 32> r;
+#pragma unroll
+  for (int w = 0; w < E * W / 32; ++w) {
+    if constexpr (W == 8) r.d[w] = pack4x8(val[4 * w], val[4 * w + 1], val[4 * w + 2], val[4 * w + 3]);
+    else                  r.d[w] = pack2x16(val[2 * w], val[2 * w + 1]);
+  }
+  return r;
 }
 
 // RNE(y / 2^b) for a wave-uniform 0 <= b <= 30 without a branch: `half_m1` = 2^(b-1) - 1 (0 when b == 0),
