@@ -98,11 +98,14 @@ __device__ __forceinline__ WideParams make_wide(const StepParams& p)
   return w;
 }
 
+// DECAY is a template parameter here too: a branch per element, even a uniform one, would keep the compiler from
+// interleaving the elements of a group.
+template <bool DECAY>
 __device__ __forceinline__ void update_wide(const WideParams& w, int th, int c, double g, int& th_new, int& c_new, double& vabs_max)
 {
   const double cap = 1099511627776.0;                       // 2^40
   double s = clampd(__builtin_rint(g * w.ag), -cap, cap);
-  if (w.decay) s += clampd(__builtin_rint((double)th * w.aw), -cap, cap);
+  if (DECAY) s += clampd(__builtin_rint((double)th * w.aw), -cap, cap);
   const double v = __builtin_fma((double)th, w.p2d, (double)c) + s;
   vabs_max = __builtin_fmax(vabs_max, __builtin_fabs(v));
   const double vG = v * w.p2u;
@@ -125,7 +128,7 @@ __device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const Tens
     int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
     int g  = GS == kGradF32 ? (int)quant_grad(p, ((const float*)T.src)[i], ab_max) : load_elem(T.grad, i, p.wg);
     int tn, cn;
-    update_wide(w, th, c, (double)g, tn, cn, vw);
+    if (w.decay) update_wide<true>(w, th, c, (double)g, tn, cn, vw); else update_wide<false>(w, th, c, (double)g, tn, cn, vw);
     store_elem(T.theta, i, p.wt, tn);
     if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
   }
@@ -229,7 +232,7 @@ __device__ __forceinline__ void compute_group(const StepParams& p, const WidePar
     if (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[(k >> 2) & (GS == kGradF32 ? 3 : 1)][k & 3]), tr.ab);
     else                gf = (float)sx16(G.g[(k >> 3) & 1][(k >> 1) & 3], k & 1);
     if (MODE == kModeSmall)     update_small<DECAY, (WC == 16)>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
-    else if (MODE == kModeWide) update_wide(w, elem16<WT>(G.th, k), elem16<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
+    else if (MODE == kModeWide) update_wide<DECAY>(w, elem16<WT>(G.th, k), elem16<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                        update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
   pack16<WT>(O.th, tn);
@@ -331,7 +334,7 @@ __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const
     if constexpr (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[k >> 2].d[k & 3]), tr.ab);
     else                          gf = (float)sx16(G.g[k >> 3].d[(k >> 1) & 3], k & 1);
     if constexpr (MODE == kModeSmall)     update_small<DECAY, (WC == 16)>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
-    else if constexpr (MODE == kModeWide) update_wide(w, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
+    else if constexpr (MODE == kModeWide) update_wide<DECAY>(w, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                                  update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
   st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
@@ -441,7 +444,7 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
 template <int WT, int WC, int GS, int MODE>
 __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
 {
-  const bool decay = MODE != kModeWide && p.lrwd;           // the wide arithmetic tests the decay term itself
+  const bool decay = p.lrwd != 0;
   if (GS == kGradF32)
     return decay ? tile_fast_e<LPK_F32_E, (MODE == kModeWide ? 1 : LPK_F32_GROUPS), WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
                  : tile_fast_e<LPK_F32_E, (MODE == kModeWide ? 1 : LPK_F32_GROUPS), WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);

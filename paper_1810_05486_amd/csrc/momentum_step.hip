@@ -34,13 +34,14 @@ struct MomParams {
 
 struct WideMax { double v, w; };
 
+template <bool DECAY>
 __device__ __forceinline__ void update_wide_mom(const MomParams& p, int th, int c, int m, int g,
                                                 int& th_new, int& c_new, int& m_new, WideMax& mx)
 {
   const double cap = 1099511627776.0;                       // 2^40
   double w = __builtin_rint((double)m * p.w_a1);
   w += clampd(__builtin_rint((double)g * p.w_a2), -cap, cap);
-  if (p.lrwd) w += clampd(__builtin_rint((double)th * p.w_a3), -cap, cap);
+  if (DECAY) w += clampd(__builtin_rint((double)th * p.w_a3), -cap, cap);
   const double mq = __builtin_rint(w * 0x1p-16);
   mx.w = __builtin_fmax(mx.w, __builtin_fabs(mq));
   const double mn = clampd(mq, p.w_lo_m, p.w_hi_m);
@@ -72,7 +73,7 @@ __device__ __forceinline__ void tile_generic_mom(const MomParams& p, const Tenso
     int m  = load_elem(T.mom, i, p.wm);
     int g  = load_elem(T.grad, i, p.wg);
     int tn, cn, mn;
-    update_wide_mom(p, th, c, m, g, tn, cn, mn, mx);
+    if (p.lrwd) update_wide_mom<true>(p, th, c, m, g, tn, cn, mn, mx); else update_wide_mom<false>(p, th, c, m, g, tn, cn, mn, mx);
     store_elem(T.theta, i, p.wt, tn);
     if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
     store_elem(T.mom, i, p.wm, mn);
@@ -126,7 +127,7 @@ __device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<
   int tn[16], cn[16], mn[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k) {
-    if (WIDE) update_wide_mom(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mx);
+    if (WIDE) update_wide_mom<DECAY>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mx);
     else update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mt);
   }
   store16<WT>(T.theta, e, tn);
@@ -175,7 +176,10 @@ template <int WT, int WM>
 __device__ __forceinline__ void tile_fast_mom_dispatch(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                                        uint64_t& vm, uint64_t& wm)
 {
-  if (p.wide) { tile_fast_mom<WT, WM, false, false, true>(p, T, off, cnt, lane, vm, wm); return; }
+  if (p.wide) {
+    if (p.lrwd) tile_fast_mom<WT, WM, true, false, true>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false, true>(p, T, off, cnt, lane, vm, wm);
+    return;
+  }
   const bool k1z = p.k1 == 0;
   if (p.lrwd) { if (k1z) tile_fast_mom<WT, WM, true, true, false>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom<WT, WM, true, false, false>(p, T, off, cnt, lane, vm, wm); }
   else        { if (k1z) tile_fast_mom<WT, WM, false, true, false>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false, false>(p, T, off, cnt, lane, vm, wm); }
