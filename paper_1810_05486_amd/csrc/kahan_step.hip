@@ -452,6 +452,11 @@ __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const T
   return decay ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
                : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
 #endif
+  // a 16-bit theta or comp: 8 elements per lane, so that every access of a wave is one contiguous run (with 16, a
+  // lane's 16-bit data spans two stores 32 bytes apart and HBM sees partial-line writes)
+  if constexpr (WC == 16)
+    return decay ? tile_fast_e<8, (MODE == kModeWide ? 1 : LPK_W16_GROUPS), WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
+                 : tile_fast_e<8, (MODE == kModeWide ? 1 : LPK_W16_GROUPS), WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
   return decay ? tile_fast<WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab) : tile_fast<WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
 }
 

@@ -26,6 +26,9 @@
 #ifndef LPK_I16_GROUPS
 #define LPK_I16_GROUPS 4
 #endif
+#ifndef LPK_W16_GROUPS
+#define LPK_W16_GROUPS 4      // groups of 8 elements in flight per lane when theta or comp is 16 bits wide
+#endif
 #ifndef LPK_WAVES_PER_BLOCK
 #define LPK_WAVES_PER_BLOCK 4 // wavefronts per workgroup of the persistent kernels
 #endif
