@@ -4,8 +4,8 @@
 //   w  = RNE(mu*m on grid G) + cap(RNE(-lr*g on G)) [+ cap(RNE(-lr*wd*theta on G))],  G = fl_m_out + 16
 //   mq = RNE(w / 2^16);  m' = sat(mq);  mmax = max|mq|;  s = cap(RNE(m' on grid F));  then Algorithm 1 with step s.
 //
-// Same work distribution as the plain update (persistent wavefronts over the tile table, 16 consecutive
-// elements per lane per pass, dwordx4 non-temporal accesses).  Two bit-identical arithmetic paths chosen per
+// Same work distribution as the plain update (persistent wavefronts over the tile table, 16 or 8 consecutive
+// elements per lane per pass, non-temporal vector accesses).  Two bit-identical arithmetic paths chosen per
 // tensor: generic 64-bit, and a 32-bit one (same-width theta/comp, int16 grads, theta's grid fixed) whose
 // shifts are wave-uniform operands of branch-free integer roundings (the velocity grid may move); the decay
 // term is rounded by one fp64 FMA as in the plain update.
@@ -116,23 +116,39 @@ __device__ __forceinline__ void update_fast_mom(const MomParams& p, int th, int 
   cn = min(max(r, p.qmin_c), p.qmax_c);
 }
 
-// 16 consecutive elements per lane.  WT = width of theta and comp, WM = width of the velocity; grads int16.
-template <int WT, int WM> struct MGroup {
-  v4i th[WT / 8], c[WT / 8], m[WM / 8], g[2];
+// E consecutive elements per lane.  WT = width of theta and comp, WM = width of the velocity; grads int16.
+// E = 16 when all three are 8 bits wide (dwordx4 each), E = 8 as soon as one of them is 16 bits wide: then every
+// access of a wave is still one contiguous run (with 16, a lane's 16-bit data would span two stores 32 bytes
+// apart, which reach HBM as partial lines).
+template <int E, int WT, int WM> struct MGroup {
+  DW<E * WT / 32> th, c;
+  DW<E * WM / 32> m;
+  DW<4> g[E / 8];
 };
 
-template <int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE>
-__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<WT, WM>& G, const TensorDev& T, uint64_t e, MaxTrack& mt, WideMax& mx)
+template <int E, int WT, int WM>
+__device__ __forceinline__ void load_group_mom(MGroup<E, WT, WM>& G, const TensorDev& T, uint64_t e)
 {
-  int tn[16], cn[16], mn[16];
+  G.th = ld_dw<E * WT / 32>((const int8_t*)T.theta + e * (WT / 8));
+  G.c  = ld_dw<E * WT / 32>((const int8_t*)T.comp + e * (WT / 8));
+  G.m  = ld_dw<E * WM / 32>((const int8_t*)T.mom + e * (WM / 8));
 #pragma unroll
-  for (int k = 0; k < 16; ++k) {
-    if (WIDE) update_wide_mom<DECAY>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mx);
-    else update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, elem16<WT>(G.th, k), elem16<WT>(G.c, k), elem16<WM>(G.m, k), elem16<16>(G.g, k), tn[k], cn[k], mn[k], mt);
+  for (int j = 0; j < E / 8; ++j) G.g[j] = ld_dw<4>((const int16_t*)T.grad + e + 8 * j);
+}
+
+template <int E, int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE>
+__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<E, WT, WM>& G, const TensorDev& T, uint64_t e, MaxTrack& mt, WideMax& mx)
+{
+  int tn[E], cn[E], mn[E];
+#pragma unroll
+  for (int k = 0; k < E; ++k) {
+    const int th = elem_dw<WT>(G.th, k), c = elem_dw<WT>(G.c, k), m = elem_dw<WM>(G.m, k), g = elem_dw<16>(G.g[k >> 3], k & 7);
+    if (WIDE) update_wide_mom<DECAY>(p, th, c, m, g, tn[k], cn[k], mn[k], mx);
+    else      update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, th, c, m, g, tn[k], cn[k], mn[k], mt);
   }
-  store16<WT>(T.theta, e, tn);
-  store16<WT>(T.comp, e, cn);
-  store16<WM>(T.mom, e, mn);
+  st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
+  st_dw((int8_t*)T.comp + e * (WT / 8), pack_dw<WT, E>(cn));
+  st_dw((int8_t*)T.mom + e * (WM / 8), pack_dw<WM, E>(mn));
 }
 
 template <int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE>
@@ -141,25 +157,23 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
 {
   MaxTrack mt{0, 0, 0, 0};
   WideMax mx{0.0, 0.0};
-  constexpr int kP = WIDE ? 1 : ((WT + WM) > 16 ? 2 : 4);  // passes in flight: bounded by registers (the wide path would set the kernel's count)
-  const uint32_t ngroups = cnt / kGroup;
+  constexpr int E = (WT == 16 || WM == 16) ? 8 : 16;
+  constexpr int kP = WIDE ? 1 : 4;                         // groups in flight (the wide path would set the kernel's register count)
+  const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
-    MGroup<WT, WM> G[kP];
+    MGroup<E, WT, WM> G[kP];
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) {
-      const uint64_t e = off + (uint64_t)(gi + ps * kWave) * kGroup;
-      load16<WT>(G[ps].th, T.theta, e); load16<WT>(G[ps].c, T.comp, e); load16<WM>(G[ps].m, T.mom, e); load16<16>(G[ps].g, T.grad, e);
-    }
+    for (int ps = 0; ps < kP; ++ps) load_group_mom(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps)
-      group_fast_mom<WT, WM, DECAY, K1ZERO, WIDE>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, mt, mx);
+      group_fast_mom<E, WT, WM, DECAY, K1ZERO, WIDE>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, mt, mx);
   }
   for (; gi < ngroups; gi += kWave) {
-    MGroup<WT, WM> G;
-    const uint64_t e = off + (uint64_t)gi * kGroup;
-    load16<WT>(G.th, T.theta, e); load16<WT>(G.c, T.comp, e); load16<WM>(G.m, T.mom, e); load16<16>(G.g, T.grad, e);
-    group_fast_mom<WT, WM, DECAY, K1ZERO, WIDE>(p, G, T, e, mt, mx);
+    MGroup<E, WT, WM> G;
+    const uint64_t e = off + (uint64_t)gi * E;
+    load_group_mom(G, T, e);
+    group_fast_mom<E, WT, WM, DECAY, K1ZERO, WIDE>(p, G, T, e, mt, mx);
   }
   int64_t a = mt.vmx, b = -(int64_t)mt.vmn;
   uint64_t x = (uint64_t)(a > b ? a : b);
@@ -168,8 +182,8 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
   x = (uint64_t)(a > b ? a : b);
   wm = x > wm ? x : wm;
   fold_wide(mx, vm, wm);
-  const uint32_t tail = cnt - ngroups * kGroup;
-  if (tail) tile_generic_mom(p, T, off + (uint64_t)ngroups * kGroup, tail, lane, vm, wm);
+  const uint32_t tail = cnt - ngroups * E;
+  if (tail) tile_generic_mom(p, T, off + (uint64_t)ngroups * E, tail, lane, vm, wm);
 }
 
 template <int WT, int WM>
