@@ -73,7 +73,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-gib", type=float, default=2.0,
                     help="size of the plain-copy yardstick (lpk_stream_copy), 0 = skip")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 28)
+    ap.add_argument("--cpu-sample", type=int, default=1 << 29,
+                    help="elements of the oracle's all-threads sample (the one-thread sample is a quarter of it)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the update is elementwise and shards without "
@@ -276,7 +277,7 @@ def main():
         log("timing the CPU oracle on a bounded sample ...")
         cores = max(1, min(16, len(os.sched_getaffinity(0))))
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample, cores)
-        out["cpu_baseline_one_thread"] = cpu_baseline(cfg, args.cpu_sample // 2, 1)
+        out["cpu_baseline_one_thread"] = cpu_baseline(cfg, args.cpu_sample // 4, 1)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)
