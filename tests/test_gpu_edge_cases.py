@@ -350,3 +350,28 @@ def test_calls_follow_the_stream_they_are_given():
     assert np.array_equal(d_theta.cpu().numpy(), theta) and np.array_equal(d_comp.cpu().numpy(), comp)
     assert float(busy[0].item()) == 20.0
     tl.destroy()
+
+
+def test_a_list_of_empty_tensors_is_a_no_op():
+    """n = 0 for every tensor: no tiles, nothing launched over data; fraclens fall back to their defaults, the
+    maxima are cleared, the status word stays clean -- for every entry point."""
+    say("all-empty list")
+    e8 = torch.zeros(0, dtype=torch.int8, device=DEV); e16 = torch.zeros(0, dtype=torch.int16, device=DEV)
+    ef = torch.zeros(0, dtype=torch.float32, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(e8, e8, e16, ef, momentum=e16, second=e16) for _ in range(3)])
+    assert tl.n_tiles == 0
+    i32 = dict(dtype=torch.int32, device=DEV)
+    fl = torch.tensor([3, -4, 60], **i32); fl_bad = torch.tensor([99, 99, 99], **i32)     # out-of-domain values must not matter
+    out = torch.full((3,), 77, **i32)
+    mx = [torch.full((3,), 9, dtype=torch.int64, device=DEV) for _ in range(3)]
+    status = torch.zeros(1, **i32)
+    lpk.lpk_select_fraclen(tl, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, fl, out, status)
+    lpk.lpk_quantize_tensor(tl, lpk.LPK_SEL_GRAD, fl, status)
+    lpk.lpk_kahan_sgd_step(tl, fl_bad, fl_bad, fl_bad, 655, 7, mx[0], status)
+    lpk.lpk_kahan_sgd_step_f32grad(tl, fl_bad, fl_bad, fl_bad, 655, 0, mx[0], status)
+    lpk.lpk_momentum_sgd_step(tl, fl_bad, fl_bad, fl_bad, fl_bad, fl_bad, 655, 58982, 0, mx[0], mx[1], status)
+    lpk.lpk_adam_step(tl, fl_bad, fl_bad, fl_bad, fl_bad, fl_bad, fl_bad, fl_bad, (66, 0, 58982, 65470, 0, 0), mx[0], mx[1], mx[2], status)
+    torch.cuda.synchronize()
+    assert out.cpu().tolist() == [3, -4, 60]
+    assert all(m.cpu().tolist() == [0, 0, 0] for m in mx) and int(status.item()) == 0
+    tl.destroy()
