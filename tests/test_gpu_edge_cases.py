@@ -375,3 +375,32 @@ def test_a_list_of_empty_tensors_is_a_no_op():
     assert out.cpu().tolist() == [3, -4, 60]
     assert all(m.cpu().tolist() == [0, 0, 0] for m in mx) and int(status.item()) == 0
     tl.destroy()
+
+
+def test_tensor_longer_than_2_to_the_32_elements():
+    """Element offsets past 32 bits: one int8 tensor of 2^32 + 3 tiles + 5 elements, one update straight through the
+    C ABI, every byte and vmax compared with the oracle (host threads over contiguous ranges)."""
+    say("tensor of 2^32 + 12293 elements")
+    n = (1 << 32) + 3 * 4096 + 5
+    rng = np.random.default_rng(21)
+    blk = 1 << 24
+
+    def tiled(lo, hi, dtype):
+        base = rng.integers(lo, hi, size=blk + 1237).astype(dtype)      # period not a power of two
+        reps = n // base.size + 1
+        return np.tile(base, reps)[:n].copy()
+    theta, comp, grad = tiled(-128, 128, np.int8), tiled(-128, 128, np.int8), tiled(-32768, 32768, np.int16)
+    d_theta, d_comp, d_grad = (torch.from_numpy(a).to(DEV) for a in (theta, comp, grad))
+    tl = lpk.TensorList([lpk.make_desc(d_theta, d_comp, d_grad, None)])
+    assert tl.n_tiles == (n + 4095) // 4096
+    i32 = dict(dtype=torch.int32, device=DEV)
+    fl_t, fl_g = torch.tensor([7], **i32), torch.tensor([14], **i32)
+    vmax = torch.zeros(1, dtype=torch.int64, device=DEV); status = torch.zeros(1, **i32)
+    lpk.lpk_kahan_sgd_step(tl, fl_t, fl_t, fl_g, 40000, 0, vmax, status)
+    torch.cuda.synchronize()
+    say("  device step done; oracle on the host ...")
+    want_v = ref.kahan_sgd_step_mt(theta, comp, grad, 7, 7, 7, 14, 40000, threads=16)
+    assert int(vmax.item()) == want_v and int(status.item()) == 0
+    got_t, got_c = d_theta.cpu().numpy(), d_comp.cpu().numpy()
+    assert np.array_equal(got_t, theta) and np.array_equal(got_c, comp)
+    tl.destroy()
