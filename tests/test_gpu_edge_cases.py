@@ -404,3 +404,27 @@ def test_tensor_longer_than_2_to_the_32_elements():
     got_t, got_c = d_theta.cpu().numpy(), d_comp.cpu().numpy()
     assert np.array_equal(got_t, theta) and np.array_equal(got_c, comp)
     tl.destroy()
+
+
+def test_select_and_quantize_longer_than_2_to_the_32_elements():
+    """The same length through the max-abs selection and the quantization kernel: the maximum sits past the 2^32-th
+    element, so a wrapped offset would lose it."""
+    say("select + quantize over 2^32 + 12293 elements")
+    n = (1 << 32) + 3 * 4096 + 5
+    rng = np.random.default_rng(22)
+    base = (rng.standard_normal((1 << 24) + 1237) * 1e-3).astype(np.float32)
+    x = np.tile(base, n // base.size + 1)[:n].copy()
+    x[n - 7] = 0.0625                                       # the maximum, in the last partial tile
+    d_src = torch.from_numpy(x).to(DEV)
+    d_theta = torch.zeros(n, dtype=torch.int8, device=DEV); d_grad = torch.zeros(n, dtype=torch.int16, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(d_theta, None, d_grad, d_src)])
+    fl = torch.tensor([15], dtype=torch.int32, device=DEV); status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    lpk.lpk_select_fraclen(tl, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, fl, fl, status)
+    lpk.lpk_quantize_tensor(tl, lpk.LPK_SEL_GRAD, fl, status)
+    torch.cuda.synchronize()
+    say("  device done; oracle on the host ...")
+    want_fl = ref.select_fraclen_f32(x, 16, 15)
+    assert want_fl == 18 and int(fl.item()) == want_fl and int(status.item()) == 0      # 0.0625 * 2^18 = 16384 fits, 2^19 does not
+    want = ref.quantize_mt(x, 16, want_fl, threads=16)
+    assert np.array_equal(d_grad.cpu().numpy(), want)
+    tl.destroy()
