@@ -92,3 +92,38 @@ def test_classifier_min_bits_matches_the_oracle_everywhere_on_the_host():
     assert L.lpk_classifier_min_bits(1, 32768) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_classifier_min_bits(10, 0) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_classifier_min_bits(10, 65536) == lpk.LPK_ERR_INVALID_ARG
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/lpk.h compiles as C99 with warnings as errors, and a C program linked against liblpk.so calls the
+    host-only entry points (no GPU needed)."""
+    import subprocess
+    src = tmp_path / "use_lpk.c"
+    src.write_text(r'''
+#include "lpk.h"
+#include <stdio.h>
+#include <string.h>
+int main(void)
+{
+  lpk_tensor_desc d;
+  lpk_adam_hyper h = {66u, 0u, 58982u, 65470u, 0u, 0u};
+  lpk_tensor_list* list = (lpk_tensor_list*)0;
+  memset(&d, 0, sizeof d);
+  if (sizeof(d) != 64 || sizeof(h) != 24) return 2;
+  if (lpk_version() < 100) return 3;
+  if (lpk_classifier_min_bits(10u, 32768u) != 6 || lpk_classifier_min_bits(1000u, 32768u) != 12) return 4;
+  if (strcmp(lpk_error_string(LPK_ERR_INVALID_ARG), "invalid argument") != 0) return 5;
+  if (lpk_tensor_list_create(&d, 0u, &list) != LPK_ERR_INVALID_ARG || list) return 6;   /* rejected on the host */
+  if (lpk_tensor_list_size(list) != 0u || lpk_tensor_list_destroy(list) != LPK_OK) return 7;
+  if (lpk_adam_step(list, 0, 0, 0, 0, 0, 0, 0, &h, 0, 0, 0, 0, 0) != LPK_ERR_INVALID_ARG) return 8;
+  puts("ok");
+  return 0;
+}
+''')
+    exe = tmp_path / "use_lpk"
+    libdir = os.path.dirname(lpk.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                           str(src), "-o", str(exe), "-L", libdir, "-llpk", "-Wl,-rpath," + libdir,
+                           "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"])
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr[-2000:])
