@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (5 = the 1 Gi-parameter headline)")
     ap.add_argument("--big-elems", type=int, default=1 << 30, help="size of config 5's large tensor")
     ap.add_argument("--n-tiny", type=int, default=10000, help="number of 256-element tensors in config 5")
+    ap.add_argument("--lr-q16", type=int, default=0,
+                    help="override the workload's Q0.16 learning rate (a larger step makes more parameters change per update)")
     ap.add_argument("--momentum-bits", type=int, default=0, choices=[0, 8, 16],
                     help="time the momentum variant of the update (velocity of this width, mu = 0.9) instead of plain SGD")
     ap.add_argument("--adam", action="store_true",
@@ -90,6 +92,8 @@ def main():
     torch.cuda.set_device(0)
 
     cfg = workloads.config(args.config, big_elems=args.big_elems, n_tiny=args.n_tiny) if args.config == 5 else workloads.config(args.config)
+    if args.lr_q16:
+        cfg.lr_schedule = [(0, args.lr_q16)]
     n_src = cfg.grad_cycle or 1
     if not cfg.grad_cycle:
         n_src = 3                                   # timing only: cycle three resident gradient draws
@@ -175,6 +179,25 @@ def main():
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fbytes / (f_upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                               "bytes_per_launch": fbytes}}
 
+    # the update alone with LPK_OPT_STORE_ALL: every result written, changed or not (the int16 gradients of the last
+    # step are still in place) -- the figure to read against the HBM roofline as a dense read-modify-write stream
+    all_stores = None
+    if mu_q16 is None and not args.adam:
+        for L in dev.lists:
+            lpk.lpk_tensor_list_set_option(L, lpk.LPK_OPT_STORE_ALL, 1)
+        aev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(K)]
+        for i in range(K + 2):
+            if i >= 2:
+                aev[i - 2][0].record()
+            lpk.lpk_kahan_sgd_step(dev.lists[0], dev.fl_theta, dev.fl_next, dev.fl_grad, cfg.lr_q16(args.warmup), cfg.wd_q16,
+                                   dev.vmax, dev.status)
+            if i >= 2:
+                aev[i - 2][1].record()
+        torch.cuda.synchronize()
+        all_stores = {"ms": sum(e[0].elapsed_time(e[1]) for e in aev) / K}
+        for L in dev.lists:
+            lpk.lpk_tensor_list_set_option(L, lpk.LPK_OPT_STORE_ALL, 0)
+
     # the same whole step replayed from HIP graphs (one recording per resident gradient draw): what launch
     # overhead is left once the three calls are captured -- matters for the small, launch-bound workloads
     graph = None
@@ -233,13 +256,20 @@ def main():
     upd_bytes += 8 * cfg.n_params if args.adam else 0
     upd_kernel = "adam_step_kernel" if args.adam else ("momentum_step_kernel" if args.momentum_bits else "kahan_step_kernel")
     achieved = upd_bytes / (upd_ms * 1e-3) / 1e9
-    traffic = None
+    traffic = traffic_all = None
     tpath = os.path.join(ROOT, "profiles", "traffic_config%d.json" % cfg.id)
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.lr_q16:
         try:
-            traffic = json.load(open(tpath)).get(upd_kernel + "_bytes_per_launch")
+            tj = json.load(open(tpath))
+            traffic = tj.get(upd_kernel + "_bytes_per_launch")
+            traffic_all = tj.get(upd_kernel + "_all_stores_bytes_per_launch")
         except Exception:
             traffic = None
+    if all_stores:
+        a_gbs = upd_bytes / (all_stores["ms"] * 1e-3) / 1e9
+        all_stores = {"bound": "hbm", "kernel": upd_kernel + " with LPK_OPT_STORE_ALL", "achieved": a_gbs, "peak": HBM_PEAK_GBS,
+                      "unit": "GB/s", "frac": a_gbs / HBM_PEAK_GBS, "traffic": traffic_all, "bytes_per_launch": upd_bytes,
+                      "ms": all_stores["ms"]}
 
     out = {
         "metric": "Kahan-SGD update Gparams/s + achieved HBM GB/s (% of peak), 1 MI355X",
@@ -261,8 +291,14 @@ def main():
         "roofline": {"bound": "hbm", "kernel": upd_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "bytes_per_launch": upd_bytes,
+                     "stores": (None if (args.adam or args.momentum_bits) else
+                                "16-byte groups of theta / comp that the step leaves unchanged are not written back "
+                                "(the lazy update's usual case), so the HBM traffic per launch (`traffic`) is below the "
+                                "algorithmic bytes `achieved` is computed from; `roofline_all_stores` times the same kernel "
+                                "writing everything"),
                      "note": ("the ADAM kernel is limited by its exact fp64 arithmetic (about 65 VALU instructions per "
                               "parameter), not by HBM; the fraction is still quoted against the HBM peak") if args.adam else None},
+        "roofline_all_stores": all_stores,
         "other_kernels": {
             "maxabs_f32_kernel": {"GB/s": 4 * cfg.n_params / (sel_ms * 1e-3) / 1e9, "bytes_per_launch": 4 * cfg.n_params},
             "quantize_kernel": {"GB/s": 6 * cfg.n_params / (qnt_ms * 1e-3) / 1e9, "bytes_per_launch": 6 * cfg.n_params}},

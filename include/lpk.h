@@ -104,6 +104,14 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
  * synchronized every stream that still uses the list. */
 int lpk_tensor_list_destroy(lpk_tensor_list* list);
 
+/* Per-list options.  LPK_OPT_STORE_ALL (default 0): the update kernels normally do not issue the store of a
+ * 16-byte group of theta or comp whose new value equals the one loaded (in the lazy update most parameters do not
+ * move in a step, so this saves most of the write traffic); with value 1 every result is written.  The results
+ * in memory are the same either way.  Takes effect for calls enqueued afterwards.
+ * Errors: INVALID_ARG (NULL list, unknown option). */
+typedef enum { LPK_OPT_STORE_ALL = 1 } lpk_option;
+int lpk_tensor_list_set_option(lpk_tensor_list* list, int option, int value);
+
 /* Number of tensors / of tiles in a list (host-side facts, no device access); 0 for NULL. */
 uint32_t lpk_tensor_list_size(const lpk_tensor_list* list);
 uint64_t lpk_tensor_list_tiles(const lpk_tensor_list* list);

@@ -15,6 +15,7 @@ LPK_I8, LPK_I16, LPK_F32, LPK_VMAX_U64 = 1, 2, 4, 8
 LPK_SEL_GRAD, LPK_SEL_THETA, LPK_SEL_MOMENTUM, LPK_SEL_SECOND = 0, 1, 2, 3
 LPK_STATUS_NONFINITE, LPK_STATUS_DOMAIN = 1, 2
 LPK_COMP_SHIFT_DEFAULT = 0xFF
+LPK_OPT_STORE_ALL = 1
 
 
 class lpk_tensor_desc(ctypes.Structure):
@@ -51,6 +52,8 @@ def lib():
         vp, u32, u64, ci = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int
         L.lpk_tensor_list_create.argtypes = [ctypes.POINTER(lpk_tensor_desc), u32, ctypes.POINTER(vp)]
         L.lpk_tensor_list_destroy.argtypes = [vp]
+        L.lpk_tensor_list_set_option.argtypes = [vp, ci, ci]
+        L.lpk_tensor_list_set_option.restype = ci
         L.lpk_tensor_list_size.argtypes = [vp]
         L.lpk_tensor_list_size.restype = u32
         L.lpk_tensor_list_tiles.argtypes = [vp]
@@ -159,6 +162,10 @@ class TensorList:
 
 def lpk_tensor_list_create(descs):
     return TensorList(descs)
+
+
+def lpk_tensor_list_set_option(tl, option, value):
+    _check(lib().lpk_tensor_list_set_option(tl.handle, int(option), int(value)), "lpk_tensor_list_set_option")
 
 
 def lpk_tensor_list_destroy(tl):

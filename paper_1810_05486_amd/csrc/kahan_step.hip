@@ -137,7 +137,7 @@ __device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const Tens
 
 // ---------------------------------------------------------------- fast (int32 + FMA rounding)
 
-struct Track { int vmx, vmn; uint32_t ab; double vw; };
+struct Track { int vmx, vmn; uint32_t ab; double vw; int dense_t, dense_c; };     // groups of this tile whose theta / comp stores went out dense
 
 template <bool DECAY>
 __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, float gf, int& tn, int& cn, Track& tr)
@@ -246,12 +246,56 @@ __device__ __forceinline__ void store_group(const GroupOut<WT, WC>& O, const Ten
   store16v<WC>(T.comp, e, O.c);
 }
 
-template <int WT, int WC, int GS, bool DECAY, int MODE>
+// Lazy stores.  In the lazy update most parameters do not move in a step (that is its premise: a step is usually
+// far below the parameter's grid, and often below the accumulator's), so most 16-byte groups a lane computes equal
+// the ones it loaded.  A wave first asks whether any of its lanes changed anything: if none did, the store is not
+// issued at all; if a few did, only those lanes store; otherwise every lane stores, so that HBM sees whole lines
+// (a lone 16-byte write costs the memory system about as much as 128 bytes of a full-line stream, hence "a few" =
+// at most 8 of the 64 lanes for 16-byte stores, 4 for 8-byte ones).  The tile functions exist in three forms (LAZY): kLazyBoth tests theta and comp,
+// kLazyTheta tests theta only (a step around one accumulator LSB changes most of comp and hardly any theta),
+// kLazyNone tests nothing.  A wave whose tile turned out mostly dense in comp, or in theta too, runs its next
+// kDenseTiles tiles through the form that no longer tests that array, then probes again: this keeps the cost of
+// the tests out of workloads where everything changes.  A list with LPK_OPT_STORE_ALL only ever uses kLazyNone.
+constexpr int kDenseTiles = 16;
+enum { kLazyNone = 0, kLazyTheta = 1, kLazyBoth = 2 };
+struct LazyRun { int tiles, form; };                        // a wave's state across tiles: `tiles` more tiles in `form`
+
+// returns true when the store went out dense (every lane)
+template <int SPARSE_LANES, typename StoreFn>
+__device__ __forceinline__ bool lazy_store(bool changed, StoreFn store)
+{
+  const uint64_t m = __builtin_amdgcn_ballot_w64(changed);
+  if (m == 0) return false;
+  if (__builtin_popcountll(m) > SPARSE_LANES) { store(); return true; }
+  if (changed) store();
+  return false;
+}
+
+template <int W> __device__ __forceinline__ bool store16_lazy(void* base, uint64_t e, const v4i (&o)[W / 8], const v4i (&in)[W / 8])
+{
+  int x = 0;
+#pragma unroll
+  for (int q = 0; q < W / 8; ++q)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) x |= o[q][k] ^ in[q][k];
+  return lazy_store<8>(x != 0, [&] { store16v<W>(base, e, o); });
+}
+
+template <int N> __device__ __forceinline__ bool st_dw_lazy(void* p, const DW<N>& o, const DW<N>& in)
+{
+  int x = 0;
+#pragma unroll
+  for (int k = 0; k < N; ++k) x |= o.d[k] ^ in.d[k];
+  return lazy_store<2 * N>(x != 0, [&] { st_dw(p, o); });
+}
+
+template <int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
 __device__ __forceinline__ void compute_store_group(const StepParams& p, const WideParams& w, const Group<WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
   GroupOut<WT, WC> O;
   compute_group<WT, WC, GS, DECAY, MODE>(p, w, G, O, tr);
-  store_group<WT, WC>(O, T, e);
+  if (LAZY == kLazyNone) store16v<WT>(T.theta, e, O.th); else tr.dense_t += store16_lazy<WT>(T.theta, e, O.th, G.th) ? 1 : 0;
+  if (LAZY != kLazyBoth) store16v<WC>(T.comp, e, O.c);   else tr.dense_c += store16_lazy<WC>(T.comp, e, O.c, G.c) ? 1 : 0;
 }
 
 __device__ __forceinline__ uint64_t track_max(const Track& tr)
@@ -262,15 +306,13 @@ __device__ __forceinline__ uint64_t track_max(const Track& tr)
 }
 
 // Vector tile: full 16-element groups with the fast arithmetic, the ragged end element by element.
-template <int WT, int WC, int GS, bool DECAY, int MODE>
-__device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
+template <int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
+__device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max, LazyRun& lz)
 {
-  Track tr{0, 0, ab_max, 0.0};
+  Track tr{0, 0, ab_max, 0.0, 0, 0};
   const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
   constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : 8);     // VGPRs of one group
-  // groups in flight per lane; one in the wide arithmetic, whose fp64 temporaries would otherwise set the register
-  // count of the whole kernel
-  constexpr int kP = MODE == kModeWide ? 1 : (kRegs <= 16 ? LPK_I16_GROUPS : LPK_KP_WIDE);
+  constexpr int kP = kRegs <= 16 ? LPK_I16_GROUPS : LPK_KP_WIDE;                     // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
@@ -278,15 +320,20 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, MODE>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
+    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, MODE, LAZY>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     Group<WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * kGroup;
     load_group(G, T, e);
-    compute_store_group<WT, WC, GS, DECAY, MODE>(p, w, G, T, e, tr);
+    compute_store_group<WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, e, tr);
   }
   ab_max = tr.ab;
+  if (LAZY != kLazyNone) {                                 // most of this tile's groups dense in theta / in comp?
+    const bool mt = 2 * (uint32_t)wave_uniform(tr.dense_t) * kWave > ngroups, mc = 2 * (uint32_t)wave_uniform(tr.dense_c) * kWave > ngroups;
+    if (mt)      { lz.tiles = kDenseTiles; lz.form = kLazyNone; }
+    else if (mc) { lz.tiles = kDenseTiles; lz.form = kLazyTheta; }
+  }
   uint64_t vm = track_max(tr);
   const uint32_t tail = cnt - ngroups * kGroup;           // < 16 elements
   if (tail) {
@@ -324,7 +371,7 @@ __device__ __forceinline__ void load_group_e(GroupE<E, WT, WC, GS>& G, const Ten
   }
 }
 
-template <int E, int WT, int WC, int GS, bool DECAY, int MODE>
+template <int E, int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
 __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const WideParams& w, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
 {
   int tn[E], cn[E];
@@ -337,14 +384,16 @@ __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const
     else if constexpr (MODE == kModeWide) update_wide<DECAY>(w, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                                  update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
-  st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
-  st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
+  if constexpr (LAZY == kLazyNone) st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
+  else tr.dense_t += st_dw_lazy((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn), G.th) ? 1 : 0;
+  if constexpr (LAZY != kLazyBoth) st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
+  else tr.dense_c += st_dw_lazy((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn), G.c) ? 1 : 0;
 }
 
-template <int E, int KP, int WT, int WC, int GS, bool DECAY, int MODE>
-__device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
+template <int E, int KP, int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
+__device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max, LazyRun& lz)
 {
-  Track tr{0, 0, ab_max, 0.0};
+  Track tr{0, 0, ab_max, 0.0, 0, 0};
   const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
   const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;
@@ -353,15 +402,20 @@ __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const Tenso
 #pragma unroll
     for (int ps = 0; ps < KP; ++ps) load_group_e(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
-    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, MODE>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
+    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, MODE, LAZY>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     GroupE<E, WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * E;
     load_group_e(G, T, e);
-    compute_store_group_e<E, WT, WC, GS, DECAY, MODE>(p, w, G, T, e, tr);
+    compute_store_group_e<E, WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, e, tr);
   }
   ab_max = tr.ab;
+  if (LAZY != kLazyNone) {                                 // most of this tile's groups dense in theta / in comp?
+    const bool mt = 2 * (uint32_t)wave_uniform(tr.dense_t) * kWave > ngroups, mc = 2 * (uint32_t)wave_uniform(tr.dense_c) * kWave > ngroups;
+    if (mt)      { lz.tiles = kDenseTiles; lz.form = kLazyNone; }
+    else if (mc) { lz.tiles = kDenseTiles; lz.form = kLazyTheta; }
+  }
   uint64_t vm = track_max(tr);
   const uint32_t tail = cnt - ngroups * E;                // < E elements
   if (tail) {
@@ -441,38 +495,55 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
 
 // ---------------------------------------------------------------- the kernel
 
-template <int WT, int WC, int GS, int MODE>
-__device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
+template <int WT, int WC, int GS, int MODE, int LAZY>
+__device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab, LazyRun& lz)
 {
   const bool decay = p.lrwd != 0;
+  // the wide arithmetic: 8 elements per lane, one group in flight -- its fp64 temporaries would otherwise set the
+  // register count of the whole kernel, and the 32-bit loops lose speed above about 160 VGPRs
+  if constexpr (MODE == kModeWide)
+    return decay ? tile_fast_e<8, 1, WT, WC, GS, true, MODE, kLazyNone>(p, T, off, cnt, lane, ab, lz)
+                 : tile_fast_e<8, 1, WT, WC, GS, false, MODE, kLazyNone>(p, T, off, cnt, lane, ab, lz);
   if (GS == kGradF32)
-    return decay ? tile_fast_e<LPK_F32_E, (MODE == kModeWide ? 1 : LPK_F32_GROUPS), WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
-                 : tile_fast_e<LPK_F32_E, (MODE == kModeWide ? 1 : LPK_F32_GROUPS), WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
+    return decay ? tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
+                 : tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
 #if LPK_I16_E != 16
-  return decay ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
-               : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
+  return decay ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
+               : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
 #endif
   // a 16-bit theta or comp: 8 elements per lane, so that every access of a wave is one contiguous run (with 16, a
   // lane's 16-bit data spans two stores 32 bytes apart and HBM sees partial-line writes)
   if constexpr (WC == 16)
-    return decay ? tile_fast_e<8, (MODE == kModeWide ? 1 : LPK_W16_GROUPS), WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab)
-                 : tile_fast_e<8, (MODE == kModeWide ? 1 : LPK_W16_GROUPS), WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
-  return decay ? tile_fast<WT, WC, GS, true, MODE>(p, T, off, cnt, lane, ab) : tile_fast<WT, WC, GS, false, MODE>(p, T, off, cnt, lane, ab);
+    return decay ? tile_fast_e<8, LPK_W16_GROUPS, WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
+                 : tile_fast_e<8, LPK_W16_GROUPS, WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
+  return decay ? tile_fast<WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
+               : tile_fast<WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
+}
+
+template <int WT, int WC, int GS, int LAZY>
+__device__ __forceinline__ uint64_t tile_vector_mode(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab, LazyRun& lz)
+{
+  if (p.mode == kModeWide) return tile_fast_decay<WT, WC, GS, kModeWide, kLazyNone>(p, T, off, cnt, lane, ab, lz);
+  if (WT == 8 && p.mode == kModeSmall) return tile_fast_decay<WT, WC, GS, kModeSmall, LAZY>(p, T, off, cnt, lane, ab, lz);
+  return tile_fast_decay<WT, WC, GS, kModeFast, LAZY>(p, T, off, cnt, lane, ab, lz);
 }
 
 template <int WT, int WC, int GS>
-__device__ __forceinline__ uint64_t tile_vector(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab)
+__device__ __forceinline__ uint64_t tile_vector(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab, LazyRun& lz)
 {
-  if (p.mode == kModeWide) return tile_fast_decay<WT, WC, GS, kModeWide>(p, T, off, cnt, lane, ab);
-  if (WT == 8 && p.mode == kModeSmall) return tile_fast_decay<WT, WC, GS, kModeSmall>(p, T, off, cnt, lane, ab);
-  return tile_fast_decay<WT, WC, GS, kModeFast>(p, T, off, cnt, lane, ab);
+  if (lz.tiles > 0) {                                      // a dense run, or stores forced for the list
+    --lz.tiles;
+    if (lz.form == kLazyNone) return tile_vector_mode<WT, WC, GS, kLazyNone>(p, T, off, cnt, lane, ab, lz);
+    return tile_vector_mode<WT, WC, GS, kLazyTheta>(p, T, off, cnt, lane, ab, lz);
+  }
+  return tile_vector_mode<WT, WC, GS, kLazyBoth>(p, T, off, cnt, lane, ab, lz);
 }
 
 template <int GS>
 __global__ void __launch_bounds__(kBlock)
 kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                   const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out, const int32_t* __restrict__ fl_g,
-                  uint32_t lr, uint32_t wd, uint64_t* vmax, uint32_t* status)
+                  uint32_t lr, uint32_t wd, uint32_t store_all, uint64_t* vmax, uint32_t* status)
 {
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint64_t s_max[kWavesPerBlock];
@@ -487,6 +558,7 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
   uint32_t status_bits = 0, ab_max = 0;
   StepParams p; p.path = 0;
   TensorDev T;
+  LazyRun lz{store_all ? 0x7fffffff : 0, kLazyNone};
 
   for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
     int t; uint32_t cnt; uint64_t off;
@@ -500,9 +572,9 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS>(p, T, off, cnt, lane, ab_max);
-      else if (p.wt == 16)        vm = tile_vector<16, 16, GS>(p, T, off, cnt, lane, ab_max);
-      else                        vm = tile_vector<8, 16, GS>(p, T, off, cnt, lane, ab_max);
+      if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS>(p, T, off, cnt, lane, ab_max, lz);
+      else if (p.wt == 16)        vm = tile_vector<16, 16, GS>(p, T, off, cnt, lane, ab_max, lz);
+      else                        vm = tile_vector<8, 16, GS>(p, T, off, cnt, lane, ab_max, lz);
     } else if (p.path == 1) {
       vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
     }
@@ -524,7 +596,7 @@ __global__ void __launch_bounds__(kBlock) fill_u64_kernel(uint64_t* p, uint32_t 
 
 hipError_t launch_kahan_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_g,
-                             uint32_t lr, uint32_t wd, uint64_t* vmax, uint32_t* status, hipStream_t stream)
+                             uint32_t lr, uint32_t wd, uint32_t store_all, uint64_t* vmax, uint32_t* status, hipStream_t stream)
 {
   if (vmax) {
     hipLaunchKernelGGL(fill_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, n_tensors, 0ull);
@@ -532,10 +604,10 @@ hipError_t launch_kahan_step(const TensorDev* tensors, const Tile* tiles, uint32
   if (n_tiles) {
     if (grad_is_f32)
       hipLaunchKernelGGL(kahan_step_kernel<kGradF32>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                         fl_in, fl_out, fl_g, lr, wd, vmax, status);
+                         fl_in, fl_out, fl_g, lr, wd, store_all, vmax, status);
     else
       hipLaunchKernelGGL(kahan_step_kernel<kGradI16>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                         fl_in, fl_out, fl_g, lr, wd, vmax, status);
+                         fl_in, fl_out, fl_g, lr, wd, store_all, vmax, status);
   }
   return hipGetLastError();
 }

@@ -10,7 +10,7 @@
 namespace lpk {
 hipError_t launch_kahan_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int grad_is_f32, const int32_t*, const int32_t*, const int32_t*, uint32_t lr, uint32_t wd,
-                             uint64_t* vmax, uint32_t* status, hipStream_t);
+                             uint32_t store_all, uint64_t* vmax, uint32_t* status, hipStream_t);
 hipError_t launch_select_f32(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int sel, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
                              uint32_t* status, hipStream_t);
@@ -38,11 +38,13 @@ struct lpk_tensor_list {
   uint32_t   n_tiles   = 0;
   int        device    = 0;
   uint32_t   grid      = 0;        // blocks of the persistent read-mostly launches (max-abs, quantize)
-  uint32_t   grid_step = 0;        // blocks of the persistent update launches
+  uint32_t   grid_step = 0;        // blocks of the plain update launches with lazy stores (read-dominated)
+  uint32_t   grid_dense = 0;       // blocks of update launches that write everything (plain with LPK_OPT_STORE_ALL, momentum)
   uint32_t   grid_adam = 0;        // blocks of the ADAM launch (bound by fp64 arithmetic, not by HBM: more waves help)
   bool       all_src   = false;    // every non-empty tensor has an fp32 source
   bool       all_mom   = false;    // every non-empty tensor has a velocity buffer
   bool       all_sec   = false;    // ... and a second-moment buffer
+  bool       store_all = false;    // LPK_OPT_STORE_ALL: write every result, changed or not
   TensorDev* d_tensors = nullptr;
   Tile*      d_tiles   = nullptr;
   uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls
@@ -124,8 +126,9 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   hipDeviceProp_t prop;
   bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
   if (ok) {
-    // Persistent grids, never more blocks than tile quads.  Measured on MI355X: the read-modify-write update
-    // kernels stream fastest with ONE workgroup (one wave per SIMD) per CU, the read-mostly ones with two.
+    // Persistent grids, never more blocks than tile quads.  Measured on MI355X: update kernels that write as much
+    // as they read stream fastest with ONE workgroup (one wave per SIMD) per CU, the read-mostly ones (max-abs,
+    // quantization, the plain update once its unchanged groups are not stored) with two.
     const uint32_t need = (L->n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     auto clampg = [&](uint32_t per_cu) {
       uint32_t g = (uint32_t)prop.multiProcessorCount * per_cu;
@@ -133,7 +136,9 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
       return g ? g : 1u;
     };
     L->grid = clampg(env_u32("LPK_BLOCKS_PER_CU", 2));
-    L->grid_step = clampg(env_u32("LPK_STEP_BLOCKS_PER_CU", 1));
+    L->grid_step = clampg(env_u32("LPK_STEP_BLOCKS_PER_CU", 2));
+    L->grid_dense = clampg(env_u32("LPK_DENSE_BLOCKS_PER_CU", 1));
+    L->store_all = env_u32("LPK_STORE_ALL", 0) == 1;
     L->grid_adam = clampg(env_u32("LPK_ADAM_BLOCKS_PER_CU", 3));
     ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
          hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * n_tensors) == hipSuccess &&
@@ -163,6 +168,13 @@ int lpk_tensor_list_destroy(lpk_tensor_list* L)
   if (L->d_scratch) ok &= hipFree(L->d_scratch) == hipSuccess;
   delete L;
   return ok ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+int lpk_tensor_list_set_option(lpk_tensor_list* L, int option, int value)
+{
+  if (!L) return LPK_ERR_INVALID_ARG;
+  if (option == LPK_OPT_STORE_ALL) { L->store_all = value != 0; return LPK_OK; }
+  return LPK_ERR_INVALID_ARG;
 }
 
 uint32_t lpk_tensor_list_size(const lpk_tensor_list* L) { return L ? L->n_tensors : 0; }
@@ -207,8 +219,8 @@ int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int
 {
   if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_step, 0, fl_theta_in, fl_theta_out,
-                                   fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->store_all ? L->grid_dense : L->grid_step, 0, fl_theta_in, fl_theta_out,
+                                   fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, vmax_out, status, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
@@ -219,8 +231,8 @@ int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, c
   if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   if (!L->all_src) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_step, 1, fl_theta_in, fl_theta_out,
-                                   fl_grad, lr_q16, wd_q16, vmax_out, status, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->store_all ? L->grid_dense : L->grid_step, 1, fl_theta_in, fl_theta_out,
+                                   fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, vmax_out, status, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
@@ -232,7 +244,7 @@ int lpk_momentum_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const 
   if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u || mu_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   if (!L->all_mom) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_step, fl_theta_in, fl_theta_out,
+  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_dense, fl_theta_in, fl_theta_out,
                                       fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16, vmax_out, mmax_out, status,
                                       static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
@@ -277,7 +289,7 @@ int lpk_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, void* strea
   hipDeviceProp_t prop;
   if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return LPK_ERR_DEVICE;
   uint64_t blocks = (nbytes / kTileElems + kWavesPerBlock - 1) / kWavesPerBlock;
-  const uint64_t cap = (uint64_t)prop.multiProcessorCount * env_u32("LPK_STEP_BLOCKS_PER_CU", 1);
+  const uint64_t cap = (uint64_t)prop.multiProcessorCount * env_u32("LPK_DENSE_BLOCKS_PER_CU", 1);
   if (blocks > cap) blocks = cap;
   hipError_t e = launch_stream_mix(a, b, c, nbytes, (uint32_t)blocks, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
@@ -304,6 +316,6 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
   return bw;
 }
 
-int lpk_version(void) { return 105; }
+int lpk_version(void) { return 106; }
 
 }  // extern "C"

@@ -428,3 +428,51 @@ def test_select_and_quantize_longer_than_2_to_the_32_elements():
     want = ref.quantize_mt(x, 16, want_fl, threads=16)
     assert np.array_equal(d_grad.cpu().numpy(), want)
     tl.destroy()
+
+
+@pytest.mark.parametrize("store_all", [0, 1])
+@pytest.mark.parametrize("cb", [8, 16])
+def test_lazy_stores_in_every_regime(cb, store_all):
+    """Stores of unchanged 16-byte groups are not issued (unless LPK_OPT_STORE_ALL): gradients crafted so that within
+    one tensor some wave-sized runs change nothing, some change in one lane, some in a dozen lanes, some everywhere,
+    in an order that makes a wave switch between its sparse and dense forms; int16 and fp32 gradient entry points,
+    four steps, every byte against the oracle after each."""
+    say("lazy stores, comp int%d, store_all=%d" % (cb, store_all))
+    rng = np.random.default_rng(40 + cb + store_all)
+    n = 70 * 4096 + 1000                                   # 70 full tiles and a ragged one: several per wave of a small grid
+    theta = rng.integers(-100, 100, size=n).astype(np.int8)
+    comp = np.zeros(n, dtype=NP[cb])
+    d = cb - 1
+    fl_t, fl_g = 7, (10 if cb == 8 else 19)                # step shift 12 (13): the 32-bit arithmetic, where stores are lazy
+    d_theta = torch.from_numpy(theta).to(DEV); d_comp = torch.from_numpy(comp).to(DEV)
+    d_grad = torch.zeros(n, dtype=torch.int16, device=DEV); d_src = torch.zeros(n, dtype=torch.float32, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(d_theta, d_comp, d_grad, d_src)])
+    lpk.lpk_tensor_list_set_option(tl, lpk.LPK_OPT_STORE_ALL, store_all)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    a_fl_t, a_fl_g = torch.tensor([fl_t], **i32), torch.tensor([fl_g], **i32)
+    vmax = torch.zeros(1, dtype=torch.int64, device=DEV); status = torch.zeros(1, **i32)
+    lr_q = 16384                                           # 1/4: g = 4 moves comp by one theta LSB's worth of 2^(d - 3)
+    for step in range(4):
+        g = np.zeros(n, dtype=np.int16)
+        runs = n // 1024
+        kind = rng.integers(0, 5, size=runs)
+        kind[(np.arange(runs) // 12) % 2 == 1] = 4                      # stretches where everything changes
+        for r in range(runs):
+            lo = r * 1024
+            if kind[r] == 1:   g[lo + int(rng.integers(0, 1024))] = 8                                   # one lane
+            elif kind[r] == 2: g[lo + rng.choice(1024, size=12, replace=False)] = -8                     # about a dozen lanes
+            elif kind[r] == 3: g[lo + int(rng.integers(0, 1024))] = 32767                               # theta moves too
+            elif kind[r] == 4: g[lo:lo + 1024] = rng.integers(200, 20000, size=1024)                     # everything
+        want_v = ref.kahan_sgd_step(theta, comp, g, d, fl_t, fl_t, fl_g, lr_q)
+        if step % 2 == 0:
+            d_grad.copy_(torch.from_numpy(g))
+            lpk.lpk_kahan_sgd_step(tl, a_fl_t, a_fl_t, a_fl_g, lr_q, 0, vmax, status)
+        else:                                              # the same integers as exact fp32 values through the fused call
+            d_src.copy_(torch.from_numpy(g.astype(np.float32) * np.float32(2.0 ** -fl_g)))
+            lpk.lpk_kahan_sgd_step_f32grad(tl, a_fl_t, a_fl_t, a_fl_g, lr_q, 0, vmax, status)
+        torch.cuda.synchronize()
+        assert int(vmax.item()) == want_v and int(status.item()) == 0, step
+        bad_t = int((d_theta.cpu().numpy() != theta).sum()); bad_c = int((d_comp.cpu().numpy() != comp).sum())
+        assert bad_t == 0 and bad_c == 0, (step, bad_t, bad_c)
+    assert len(np.unique(theta)) > 50 and int(np.abs(comp.astype(np.int64)).max()) > 0
+    tl.destroy()
