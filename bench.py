@@ -290,6 +290,7 @@ def main():
         "stage_ms": {"select_fraclen": sel_ms, "quantize": qnt_ms, "kahan_sgd_step": upd_ms},
         "roofline": {"bound": "hbm", "kernel": upd_kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_GB/s": (traffic / (upd_ms * 1e-3) / 1e9) if traffic else None,
                      "bytes_per_launch": upd_bytes,
                      "stores": (None if (args.adam or args.momentum_bits) else
                                 "16-byte groups of theta / comp that the step leaves unchanged are not written back "

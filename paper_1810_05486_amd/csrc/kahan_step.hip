@@ -249,9 +249,9 @@ __device__ __forceinline__ void store_group(const GroupOut<WT, WC>& O, const Ten
 // Lazy stores.  In the lazy update most parameters do not move in a step (that is its premise: a step is usually
 // far below the parameter's grid, and often below the accumulator's), so most 16-byte groups a lane computes equal
 // the ones it loaded.  A wave first asks whether any of its lanes changed anything: if none did, the store is not
-// issued at all; if a few did, only those lanes store; otherwise every lane stores, so that HBM sees whole lines
-// (a lone 16-byte write costs the memory system about as much as 128 bytes of a full-line stream, hence "a few" =
-// at most 8 of the 64 lanes for 16-byte stores, 4 for 8-byte ones).  The tile functions exist in three forms (LAZY): kLazyBoth tests theta and comp,
+// issued at all; if a few did, only those lanes store, together with the lanes that share an aligned 64-byte run
+// with them (lone 16-byte writes cost the memory system far more than their size); if more than half the wave
+// would store, every lane does, so that HBM sees whole lines.  The tile functions exist in three forms (LAZY): kLazyBoth tests theta and comp,
 // kLazyTheta tests theta only (a step around one accumulator LSB changes most of comp and hardly any theta),
 // kLazyNone tests nothing.  A wave whose tile turned out mostly dense in comp, or in theta too, runs its next
 // kDenseTiles tiles through the form that no longer tests that array, then probes again: this keeps the cost of
@@ -261,13 +261,32 @@ enum { kLazyNone = 0, kLazyTheta = 1, kLazyBoth = 2 };
 struct LazyRun { int tiles, form; };                        // a wave's state across tiles: `tiles` more tiles in `form`
 
 // returns true when the store went out dense (every lane)
-template <int SPARSE_LANES, typename StoreFn>
+#ifndef LPK_GRANULE
+#define LPK_GRANULE 64        // bytes: the lanes that share such an aligned run of a wave's store go out together
+#endif
+
+// Spread each set bit of a lane mask over its aligned group of GL lanes (GL = 1, 2, 4, 8 or 16).
+template <int GL> __device__ __forceinline__ uint64_t spread_groups(uint64_t m)
+{
+  if (GL >= 2)  m |= ((m >> 1) & 0x5555555555555555ull) | ((m & 0x5555555555555555ull) << 1);
+  if (GL >= 4)  m |= ((m >> 2) & 0x3333333333333333ull) | ((m & 0x3333333333333333ull) << 2);
+  if (GL >= 8)  m |= ((m >> 4) & 0x0f0f0f0f0f0f0f0full) | ((m & 0x0f0f0f0f0f0f0f0full) << 4);
+  if (GL >= 16) m |= ((m >> 8) & 0x00ff00ff00ff00ffull) | ((m & 0x00ff00ff00ff00ffull) << 8);
+  return m;
+}
+
+// LANE_BYTES: bytes one lane stores.  Sparse: only the changed lanes and their neighbours inside the same
+// LPK_GRANULE-byte run store, so that memory sees whole granules rather than lone 8- or 16-byte writes.
+template <int LANE_BYTES, typename StoreFn>
 __device__ __forceinline__ bool lazy_store(bool changed, StoreFn store)
 {
-  const uint64_t m = __builtin_amdgcn_ballot_w64(changed);
+  constexpr int GL = LPK_GRANULE / LANE_BYTES > 1 ? LPK_GRANULE / LANE_BYTES : 1;
+  uint64_t m = __builtin_amdgcn_ballot_w64(changed);
   if (m == 0) return false;
-  if (__builtin_popcountll(m) > SPARSE_LANES) { store(); return true; }
-  if (changed) store();
+  m = spread_groups<GL>(m);
+  if (__builtin_popcountll(m) * 2 > kWave) { store(); return true; }       // more than half the wave: whole lines
+  const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  if ((m >> lane) & 1ull) store();
   return false;
 }
 
@@ -278,7 +297,7 @@ template <int W> __device__ __forceinline__ bool store16_lazy(void* base, uint64
   for (int q = 0; q < W / 8; ++q)
 #pragma unroll
     for (int k = 0; k < 4; ++k) x |= o[q][k] ^ in[q][k];
-  return lazy_store<8>(x != 0, [&] { store16v<W>(base, e, o); });
+  return lazy_store<16>(x != 0, [&] { store16v<W>(base, e, o); });
 }
 
 template <int N> __device__ __forceinline__ bool st_dw_lazy(void* p, const DW<N>& o, const DW<N>& in)
@@ -286,7 +305,7 @@ template <int N> __device__ __forceinline__ bool st_dw_lazy(void* p, const DW<N>
   int x = 0;
 #pragma unroll
   for (int k = 0; k < N; ++k) x |= o.d[k] ^ in.d[k];
-  return lazy_store<2 * N>(x != 0, [&] { st_dw(p, o); });
+  return lazy_store<4 * N>(x != 0, [&] { st_dw(p, o); });
 }
 
 template <int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
@@ -528,10 +547,11 @@ __device__ __forceinline__ uint64_t tile_vector_mode(const StepParams& p, const 
   return tile_fast_decay<WT, WC, GS, kModeFast, LAZY>(p, T, off, cnt, lane, ab, lz);
 }
 
-template <int WT, int WC, int GS>
+template <int WT, int WC, int GS, bool STORE_ALL>
 __device__ __forceinline__ uint64_t tile_vector(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab, LazyRun& lz)
 {
-  if (lz.tiles > 0) {                                      // a dense run, or stores forced for the list
+  if constexpr (STORE_ALL) return tile_vector_mode<WT, WC, GS, kLazyNone>(p, T, off, cnt, lane, ab, lz);
+  if (lz.tiles > 0) {                                      // inside a dense run
     --lz.tiles;
     if (lz.form == kLazyNone) return tile_vector_mode<WT, WC, GS, kLazyNone>(p, T, off, cnt, lane, ab, lz);
     return tile_vector_mode<WT, WC, GS, kLazyTheta>(p, T, off, cnt, lane, ab, lz);
@@ -539,11 +559,12 @@ __device__ __forceinline__ uint64_t tile_vector(const StepParams& p, const Tenso
   return tile_vector_mode<WT, WC, GS, kLazyBoth>(p, T, off, cnt, lane, ab, lz);
 }
 
-template <int GS>
+// STORE_ALL: the instance for lists with LPK_OPT_STORE_ALL, which holds none of the store tests.
+template <int GS, bool STORE_ALL>
 __global__ void __launch_bounds__(kBlock)
 kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                   const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out, const int32_t* __restrict__ fl_g,
-                  uint32_t lr, uint32_t wd, uint32_t store_all, uint64_t* vmax, uint32_t* status)
+                  uint32_t lr, uint32_t wd, uint64_t* vmax, uint32_t* status)
 {
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint64_t s_max[kWavesPerBlock];
@@ -558,7 +579,7 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
   uint32_t status_bits = 0, ab_max = 0;
   StepParams p; p.path = 0;
   TensorDev T;
-  LazyRun lz{store_all ? 0x7fffffff : 0, kLazyNone};
+  LazyRun lz{0, kLazyNone};
 
   for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
     int t; uint32_t cnt; uint64_t off;
@@ -572,9 +593,9 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS>(p, T, off, cnt, lane, ab_max, lz);
-      else if (p.wt == 16)        vm = tile_vector<16, 16, GS>(p, T, off, cnt, lane, ab_max, lz);
-      else                        vm = tile_vector<8, 16, GS>(p, T, off, cnt, lane, ab_max, lz);
+      if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+      else if (p.wt == 16)        vm = tile_vector<16, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+      else                        vm = tile_vector<8, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
     } else if (p.path == 1) {
       vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
     }
@@ -602,12 +623,11 @@ hipError_t launch_kahan_step(const TensorDev* tensors, const Tile* tiles, uint32
     hipLaunchKernelGGL(fill_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, n_tensors, 0ull);
   }
   if (n_tiles) {
-    if (grad_is_f32)
-      hipLaunchKernelGGL(kahan_step_kernel<kGradF32>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                         fl_in, fl_out, fl_g, lr, wd, store_all, vmax, status);
-    else
-      hipLaunchKernelGGL(kahan_step_kernel<kGradI16>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                         fl_in, fl_out, fl_g, lr, wd, store_all, vmax, status);
+    auto go = [&](auto kernel) {
+      hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles, fl_in, fl_out, fl_g, lr, wd, vmax, status);
+    };
+    if (grad_is_f32) { if (store_all) go(kahan_step_kernel<kGradF32, true>); else go(kahan_step_kernel<kGradF32, false>); }
+    else             { if (store_all) go(kahan_step_kernel<kGradI16, true>); else go(kahan_step_kernel<kGradI16, false>); }
   }
   return hipGetLastError();
 }
