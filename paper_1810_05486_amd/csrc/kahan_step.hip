@@ -248,47 +248,15 @@ __device__ __forceinline__ void store_group(const GroupOut<WT, WC>& O, const Ten
 
 // Lazy stores.  In the lazy update most parameters do not move in a step (that is its premise: a step is usually
 // far below the parameter's grid, and often below the accumulator's), so most 16-byte groups a lane computes equal
-// the ones it loaded.  A wave first asks whether any of its lanes changed anything: if none did, the store is not
-// issued at all; if a few did, only those lanes store, together with the lanes that share an aligned 64-byte run
-// with them (lone 16-byte writes cost the memory system far more than their size); if more than half the wave
-// would store, every lane does, so that HBM sees whole lines.  The tile functions exist in three forms (LAZY): kLazyBoth tests theta and comp,
-// kLazyTheta tests theta only (a step around one accumulator LSB changes most of comp and hardly any theta),
-// kLazyNone tests nothing.  A wave whose tile turned out mostly dense in comp, or in theta too, runs its next
-// kDenseTiles tiles through the form that no longer tests that array, then probes again: this keeps the cost of
-// the tests out of workloads where everything changes.  A list with LPK_OPT_STORE_ALL only ever uses kLazyNone.
+// the ones it loaded and need not be written back (lazy_store).  The tile functions exist in three forms (LAZY):
+// kLazyBoth tests theta and comp, kLazyTheta tests theta only (a step around one accumulator LSB changes most of
+// comp and hardly any theta), kLazyNone tests nothing.  A wave whose tile turned out mostly dense in comp, or in
+// theta too, runs its next kDenseTiles tiles through the form that no longer tests that array, then probes again:
+// this keeps the cost of the tests out of workloads where everything changes.  The kernel instance for lists with
+// LPK_OPT_STORE_ALL only holds kLazyNone.
 constexpr int kDenseTiles = 16;
 enum { kLazyNone = 0, kLazyTheta = 1, kLazyBoth = 2 };
 struct LazyRun { int tiles, form; };                        // a wave's state across tiles: `tiles` more tiles in `form`
-
-// returns true when the store went out dense (every lane)
-#ifndef LPK_GRANULE
-#define LPK_GRANULE 64        // bytes: the lanes that share such an aligned run of a wave's store go out together
-#endif
-
-// Spread each set bit of a lane mask over its aligned group of GL lanes (GL = 1, 2, 4, 8 or 16).
-template <int GL> __device__ __forceinline__ uint64_t spread_groups(uint64_t m)
-{
-  if (GL >= 2)  m |= ((m >> 1) & 0x5555555555555555ull) | ((m & 0x5555555555555555ull) << 1);
-  if (GL >= 4)  m |= ((m >> 2) & 0x3333333333333333ull) | ((m & 0x3333333333333333ull) << 2);
-  if (GL >= 8)  m |= ((m >> 4) & 0x0f0f0f0f0f0f0f0full) | ((m & 0x0f0f0f0f0f0f0f0full) << 4);
-  if (GL >= 16) m |= ((m >> 8) & 0x00ff00ff00ff00ffull) | ((m & 0x00ff00ff00ff00ffull) << 8);
-  return m;
-}
-
-// LANE_BYTES: bytes one lane stores.  Sparse: only the changed lanes and their neighbours inside the same
-// LPK_GRANULE-byte run store, so that memory sees whole granules rather than lone 8- or 16-byte writes.
-template <int LANE_BYTES, typename StoreFn>
-__device__ __forceinline__ bool lazy_store(bool changed, StoreFn store)
-{
-  constexpr int GL = LPK_GRANULE / LANE_BYTES > 1 ? LPK_GRANULE / LANE_BYTES : 1;
-  uint64_t m = __builtin_amdgcn_ballot_w64(changed);
-  if (m == 0) return false;
-  m = spread_groups<GL>(m);
-  if (__builtin_popcountll(m) * 2 > kWave) { store(); return true; }       // more than half the wave: whole lines
-  const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-  if ((m >> lane) & 1ull) store();
-  return false;
-}
 
 template <int W> __device__ __forceinline__ bool store16_lazy(void* base, uint64_t e, const v4i (&o)[W / 8], const v4i (&in)[W / 8])
 {
@@ -300,12 +268,11 @@ template <int W> __device__ __forceinline__ bool store16_lazy(void* base, uint64
   return lazy_store<16>(x != 0, [&] { store16v<W>(base, e, o); });
 }
 
-template <int N> __device__ __forceinline__ bool st_dw_lazy(void* p, const DW<N>& o, const DW<N>& in)
+template <int WT, int WC, int LAZY>
+__device__ __forceinline__ void store_group_lazy(const GroupOut<WT, WC>& O, const v4i (&th_in)[WT / 8], const v4i (&c_in)[WC / 8], const TensorDev& T, uint64_t e, Track& tr)
 {
-  int x = 0;
-#pragma unroll
-  for (int k = 0; k < N; ++k) x |= o.d[k] ^ in.d[k];
-  return lazy_store<4 * N>(x != 0, [&] { st_dw(p, o); });
+  if (LAZY == kLazyNone) store16v<WT>(T.theta, e, O.th); else tr.dense_t += store16_lazy<WT>(T.theta, e, O.th, th_in) ? 1 : 0;
+  if (LAZY != kLazyBoth) store16v<WC>(T.comp, e, O.c);   else tr.dense_c += store16_lazy<WC>(T.comp, e, O.c, c_in) ? 1 : 0;
 }
 
 template <int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
@@ -313,8 +280,7 @@ __device__ __forceinline__ void compute_store_group(const StepParams& p, const W
 {
   GroupOut<WT, WC> O;
   compute_group<WT, WC, GS, DECAY, MODE>(p, w, G, O, tr);
-  if (LAZY == kLazyNone) store16v<WT>(T.theta, e, O.th); else tr.dense_t += store16_lazy<WT>(T.theta, e, O.th, G.th) ? 1 : 0;
-  if (LAZY != kLazyBoth) store16v<WC>(T.comp, e, O.c);   else tr.dense_c += store16_lazy<WC>(T.comp, e, O.c, G.c) ? 1 : 0;
+  store_group_lazy<WT, WC, LAZY>(O, G.th, G.c, T, e, tr);
 }
 
 __device__ __forceinline__ uint64_t track_max(const Track& tr)
@@ -390,8 +356,10 @@ __device__ __forceinline__ void load_group_e(GroupE<E, WT, WC, GS>& G, const Ten
   }
 }
 
-template <int E, int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
-__device__ __forceinline__ void compute_store_group_e(const StepParams& p, const WideParams& w, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
+template <int E, int WT, int WC> struct GroupOutE { DW<E * WT / 32> th; DW<E * WC / 32> c; };
+
+template <int E, int WT, int WC, int GS, bool DECAY, int MODE>
+__device__ __forceinline__ void compute_group_e(const StepParams& p, const WideParams& w, const GroupE<E, WT, WC, GS>& G, GroupOutE<E, WT, WC>& O, Track& tr)
 {
   int tn[E], cn[E];
 #pragma unroll
@@ -403,10 +371,25 @@ __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const
     else if constexpr (MODE == kModeWide) update_wide<DECAY>(w, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                                  update_fast<DECAY>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
   }
-  if constexpr (LAZY == kLazyNone) st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
-  else tr.dense_t += st_dw_lazy((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn), G.th) ? 1 : 0;
-  if constexpr (LAZY != kLazyBoth) st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
-  else tr.dense_c += st_dw_lazy((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn), G.c) ? 1 : 0;
+  O.th = pack_dw<WT, E>(tn);
+  O.c  = pack_dw<WC, E>(cn);
+}
+
+template <int E, int WT, int WC, int GS, int LAZY>
+__device__ __forceinline__ void store_group_e(const GroupOutE<E, WT, WC>& O, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
+{
+  if constexpr (LAZY == kLazyNone) st_dw((int8_t*)T.theta + e * (WT / 8), O.th);
+  else tr.dense_t += st_dw_lazy((int8_t*)T.theta + e * (WT / 8), O.th, G.th) ? 1 : 0;
+  if constexpr (LAZY != kLazyBoth) st_dw((int8_t*)T.comp + e * (WC / 8), O.c);
+  else tr.dense_c += st_dw_lazy((int8_t*)T.comp + e * (WC / 8), O.c, G.c) ? 1 : 0;
+}
+
+template <int E, int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
+__device__ __forceinline__ void compute_store_group_e(const StepParams& p, const WideParams& w, const GroupE<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, Track& tr)
+{
+  GroupOutE<E, WT, WC> O;
+  compute_group_e<E, WT, WC, GS, DECAY, MODE>(p, w, G, O, tr);
+  store_group_e<E, WT, WC, GS, LAZY>(O, G, T, e, tr);
 }
 
 template <int E, int KP, int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>

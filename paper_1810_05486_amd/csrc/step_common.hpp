@@ -175,4 +175,48 @@ __device__ __forceinline__ void flush_block(uint64_t* vmax, int cur, uint64_t la
   __syncthreads();
 }
 
+// ---------------------------------------------------------------- stores that skip unchanged data
+//
+// A lane compares the group it is about to store with the group it loaded.  The wave then decides together: no
+// lane saw a change -> no store is issued at all; a few did -> those lanes store, together with the lanes that
+// share an aligned LPK_GRANULE-byte run with them (lone 8- or 16-byte writes cost the memory system far more
+// than their size); more than half the wave would store -> every lane does, so that HBM sees whole lines.
+// Returns true when the store went out dense (every lane).
+#ifndef LPK_GRANULE
+#define LPK_GRANULE 64        // bytes: the lanes that share such an aligned run of a wave's store go out together
+#endif
+
+// Spread each set bit of a lane mask over its aligned group of GL lanes (GL = 1, 2, 4, 8 or 16).
+template <int GL> __device__ __forceinline__ uint64_t spread_groups(uint64_t m)
+{
+  if (GL >= 2)  m |= ((m >> 1) & 0x5555555555555555ull) | ((m & 0x5555555555555555ull) << 1);
+  if (GL >= 4)  m |= ((m >> 2) & 0x3333333333333333ull) | ((m & 0x3333333333333333ull) << 2);
+  if (GL >= 8)  m |= ((m >> 4) & 0x0f0f0f0f0f0f0f0full) | ((m & 0x0f0f0f0f0f0f0f0full) << 4);
+  if (GL >= 16) m |= ((m >> 8) & 0x00ff00ff00ff00ffull) | ((m & 0x00ff00ff00ff00ffull) << 8);
+  return m;
+}
+
+// LANE_BYTES: bytes one lane stores.  Sparse: only the changed lanes and their neighbours inside the same
+// LPK_GRANULE-byte run store, so that memory sees whole granules rather than lone 8- or 16-byte writes.
+template <int LANE_BYTES, typename StoreFn>
+__device__ __forceinline__ bool lazy_store(bool changed, StoreFn store)
+{
+  constexpr int GL = LPK_GRANULE / LANE_BYTES > 1 ? LPK_GRANULE / LANE_BYTES : 1;
+  uint64_t m = __builtin_amdgcn_ballot_w64(changed);
+  if (m == 0) return false;
+  m = spread_groups<GL>(m);
+  if (__builtin_popcountll(m) * 2 > kWave) { store(); return true; }       // more than half the wave: whole lines
+  const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  if ((m >> lane) & 1ull) store();
+  return false;
+}
+
+template <int N> __device__ __forceinline__ bool st_dw_lazy(void* p, const DW<N>& o, const DW<N>& in)
+{
+  int x = 0;
+#pragma unroll
+  for (int k = 0; k < N; ++k) x |= o.d[k] ^ in.d[k];
+  return lazy_store<4 * N>(x != 0, [&] { st_dw(p, o); });
+}
+
 }  // namespace lpk

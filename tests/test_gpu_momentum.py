@@ -163,3 +163,49 @@ def test_momentum_random_lists(seed):
             assert int(vmax[i].item()) == wv and int(mmax[i].item()) == wm, ("max", ctx)
         assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
         tl.destroy()
+
+
+@pytest.mark.parametrize("store_all", [0, 1])
+@pytest.mark.parametrize("tb,mb", [(8, 8), (8, 16), (16, 16)])
+def test_momentum_runs_where_theta_moves_nowhere_somewhere_everywhere(tb, mb, store_all):
+    """Gradients crafted so that, within one tensor, some wave-sized runs move no theta, some move one, some a dozen,
+    some all of them; five steps with the velocity carrying over, every byte against the oracle, with and without
+    LPK_OPT_STORE_ALL on the list (which must not change any result)."""
+    say("momentum, theta moving in patches: theta int%d, velocity int%d, store_all=%d" % (tb, mb, store_all))
+    rng = np.random.default_rng(500 + tb + mb + store_all)
+    n = 40 * 4096 + 777
+    theta = rng.integers(-100, 100, size=n).astype(NP[tb])
+    comp = np.zeros(n, dtype=NP[tb]); mom = np.zeros(n, dtype=NP[mb])
+    d = tb - 1
+    fl_t, fl_g, fl_m = tb - 1, 15, (6 if mb == 8 else 14)
+    d_theta, d_comp, d_mom = (torch.from_numpy(x).to(DEV) for x in (theta, comp, mom))
+    d_grad = torch.zeros(n, dtype=torch.int16, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(d_theta, d_comp, d_grad, None, momentum=d_mom)])
+    lpk.lpk_tensor_list_set_option(tl, lpk.LPK_OPT_STORE_ALL, store_all)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    a_t, a_g, a_m = torch.tensor([fl_t], **i32), torch.tensor([fl_g], **i32), torch.tensor([fl_m], **i32)
+    vmax = torch.zeros(1, dtype=torch.int64, device=DEV); mmax = torch.zeros(1, dtype=torch.int64, device=DEV)
+    status = torch.zeros(1, **i32)
+    lr_q = 32768                                           # 1/2: a full-scale gradient moves theta by many LSBs
+    moved = 0
+    for step in range(5):
+        g = np.zeros(n, dtype=np.int16)
+        runs = n // 1024
+        kind = rng.integers(0, 8, size=runs)              # most runs get no gradient (what moved before coasts on)
+        for r in range(runs):
+            lo = r * 1024
+            if kind[r] == 5:   g[lo + int(rng.integers(0, 1024))] = 30000
+            elif kind[r] == 6: g[lo + rng.choice(1024, size=12, replace=False)] = -30000
+            elif kind[r] == 7: g[lo:lo + 1024] = rng.integers(-32768, 32767, size=1024)
+        before = theta.copy()
+        want_v, want_m = ref.momentum_sgd_step(theta, comp, mom, g, d, fl_t, fl_t, fl_m, fl_m, fl_g, lr_q, MU_Q16)
+        moved += int((theta != before).sum())
+        d_grad.copy_(torch.from_numpy(g))
+        lpk.lpk_momentum_sgd_step(tl, a_t, a_t, a_m, a_m, a_g, lr_q, MU_Q16, 0, vmax, mmax, status)
+        torch.cuda.synchronize()
+        assert int(vmax.item()) == want_v and int(mmax.item()) == want_m and int(status.item()) == 0, step
+        for name, dv, hv in (("theta", d_theta, theta), ("comp", d_comp, comp), ("mom", d_mom, mom)):
+            bad = int((dv.cpu().numpy() != hv).sum())
+            assert bad == 0, (step, name, bad)
+    assert 0 < moved < 5 * n // 2                           # some theta moved, most did not
+    tl.destroy()
