@@ -297,8 +297,9 @@ def main():
                                 "(the lazy update's usual case), so the HBM traffic per launch (`traffic`) is below the "
                                 "algorithmic bytes `achieved` is computed from; `roofline_all_stores` times the same kernel "
                                 "writing everything"),
-                     "note": ("the ADAM kernel is limited by its exact fp64 arithmetic (about 65 VALU instructions per "
-                              "parameter), not by HBM; the fraction is still quoted against the HBM peak") if args.adam else None},
+                     "note": ("the ADAM kernel sits where two bounds meet: its exact fp64 arithmetic (77 VALU instructions per "
+                              "parameter, about 2.4 ms of issue time) and its in-place byte mix (8 read : 6 written per "
+                              "parameter, 2.6-3.0 ms for the memory system alone, depending on the launch shape)") if args.adam else None},
         "roofline_all_stores": all_stores,
         "other_kernels": {
             "maxabs_f32_kernel": {"GB/s": 4 * cfg.n_params / (sel_ms * 1e-3) / 1e9, "bytes_per_launch": 4 * cfg.n_params},

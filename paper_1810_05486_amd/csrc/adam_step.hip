@@ -22,10 +22,10 @@
 #define LPK_ADAM_E 8                   // consecutive elements per lane per group (4 or 8)
 #endif
 #ifndef LPK_ADAM_GROUPS
-#define LPK_ADAM_GROUPS 2              // groups in flight per lane
+#define LPK_ADAM_GROUPS 4              // groups in flight per lane
 #endif
 #ifndef LPK_ADAM_WAVES_PER_SIMD
-#define LPK_ADAM_WAVES_PER_SIMD 3      // register budget: 512 / this many VGPRs per lane
+#define LPK_ADAM_WAVES_PER_SIMD 2      // register budget: 512 / this many VGPRs per lane
 #endif
 
 namespace lpk {
@@ -34,12 +34,12 @@ struct AdamParams {
   int    path;                     // 0 skip, 1 element by element, 2 vector
   int    wt, wc, wg, wm, wu, has_comp;
   int    caps;                     // some 2^40 cap may bind
+  int    exact3;                   // a1, a2, a3 are integers (and no cap binds): three of the four products need no rounding
   double a1, a2, a3, a4;           // b1 * 2^-k1, (65536 - b1) * 2^-k2, b2 * 2^-k4, (65536 - b2) * 2^-k5
   double qmin_t, qmax_t, qmin_c, qmax_c, qmin_m, qmax_m, qmax_u;
   double ascale;                   // 2^(24 + p): radicand scale
   double eps_r;                    // eps on the root's grid, at most 2^30
-  double nlr;                      // -lr * 2^max(e, 0)
-  double dscale;                   // 2^max(-e, 0)
+  double nlr;                      // -lr * 2^e
   double p2d, p2u, inv_kth, p2kth, inv_kc;
   // 32-bit tail (int8 theta, fixed grid, every |intermediate| of Algorithm 1 below 2^22): as in the plain update,
   // fma(v, 2^-d, 1.5 * 2^23) rounds v onto theta's grid and one 24-bit multiply-add forms the residual
@@ -55,24 +55,33 @@ struct AdamTrack { double vm, mm, um; int vmx, vmn; };
 __device__ __forceinline__ double cap_d() { return 1099511627776.0; }          // 2^40
 
 // CAPS: whether a 2^40 cap can bind for this tensor's shifts (wave-uniform; almost never).
-template <bool CAPS, int TAIL>
+// EXACT3: b1 * 2^-k1, (1 - b1) * 2^-k2 and b2 * 2^-k4 are integers, as they are whenever the moments' grids stand
+// still and the first moment's grid is not coarser than the gradient's: those three products are then integers
+// already, their roundings are identities and are left out (never together with CAPS).
+template <bool CAPS, int TAIL, bool EXACT3>
 __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, int m, int u, int g,
                                             int& tn, int& cn, int& mn, int& un, AdamTrack& tr)
 {
   const double cap = 1099511627776.0;                       // 2^40
   const double gd = (double)g;
   // first moment
-  const double t1 = __builtin_rint((double)m * p.a1);
-  double t2 = __builtin_rint(gd * p.a2);
-  if (CAPS) t2 = clampd(t2, -cap, cap);
-  const double mq = __builtin_rint((t1 + t2) * 0x1p-16);
+  double wm;
+  if (EXACT3) {
+    wm = __builtin_fma((double)m, p.a1, gd * p.a2);         // integers below 2^47: exact
+  } else {
+    const double t1 = __builtin_rint((double)m * p.a1);
+    double t2 = __builtin_rint(gd * p.a2);
+    if (CAPS) t2 = clampd(t2, -cap, cap);
+    wm = t1 + t2;
+  }
+  const double mq = __builtin_rint(wm * 0x1p-16);
   tr.mm = __builtin_fmax(tr.mm, __builtin_fabs(mq));
   const double mnew = clampd(mq, p.qmin_m, p.qmax_m);
   // second moment
-  const double t3 = __builtin_rint((double)u * p.a3);
   double t4 = __builtin_rint(gd * gd * p.a4);
   if (CAPS) t4 = clampd(t4, -cap, cap);
-  const double uq = __builtin_rint((t3 + t4) * 0x1p-16);
+  const double wu = EXACT3 ? __builtin_fma((double)u, p.a3, t4) : __builtin_rint((double)u * p.a3) + t4;
+  const double uq = __builtin_rint(wu * 0x1p-16);
   tr.um = __builtin_fmax(tr.um, uq);
   const double unew = clampd(uq, 0.0, p.qmax_u);
   // Root of the new second moment on its fixed grid.  A is an integer below 2^40; the fp32 root of its fp32
@@ -85,20 +94,21 @@ __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, 
   // a branch here would keep the compiler from interleaving the sixteen elements' dependency chains
   const double r_dn = __builtin_fma(r, r, -A) > 0.0 ? 1.0 : 0.0, r_up = __builtin_fma(r1, r1, -A) <= 0.0 ? 1.0 : 0.0;
   r = (r - r_dn) + r_up;
-  const double den = __builtin_fmax(r + p.eps_r, 1.0) * p.dscale;
-  // Step: RNE(num / den).  Reciprocal seed plus two Newton steps (relative error near 2^-52), so the rounded
-  // product is within one of the exact rounded quotient whenever that is below 2^41 (larger ones end at the
-  // cap regardless); the exact remainder num - q den, compared with half the divisor, repairs it, ties to even.
+  const double den = __builtin_fmax(r + p.eps_r, 1.0);
+  // Step: RNE(num / den) with num = -lr m' 2^e (the power of two folded into the numerator: exact).  The
+  // reciprocal seed (relative error below 2^-22) plus one Newton step leaves a relative error below 2^-43, so the
+  // rounded product is within one of the exact rounded quotient whenever that is below 2^41 (larger ones end at
+  // the cap regardless).  The exact remainder num - q den then decides: beyond half the divisor, or at half with
+  // q odd, q moves by one towards the remainder's sign.  q's parity is read from the low word of q + 1.5 * 2^52.
   const double num = mnew * p.nlr;
   double x = __builtin_amdgcn_rcp(den);
   x = __builtin_fma(__builtin_fma(-den, x, 1.0), x, x);
-  x = __builtin_fma(__builtin_fma(-den, x, 1.0), x, x);
   double q = __builtin_rint(num * x);
-  const double two_rem = 2.0 * __builtin_fma(-q, den, num);
-  const double hq = 0.5 * q;
-  const bool odd = hq != __builtin_floor(hq);
-  const bool up = (two_rem > den) | ((two_rem == den) & odd), down = (two_rem < -den) | ((two_rem == -den) & odd);
-  q += up ? 1.0 : (down ? -1.0 : 0.0);
+  const double rem = __builtin_fma(-q, den, num);
+  const double t = __builtin_fabs(rem) * 2.0;
+  const bool odd = (__double2loint(q + 6755399441055744.0) & 1) != 0;
+  const bool adj = (t > den) | ((t == den) & odd);
+  q += __hiloint2double(adj ? (0x3ff00000 | (__double2hiint(rem) & (int)0x80000000)) : 0, 0);
   const double s = CAPS ? clampd(q, -cap, cap) : q;
   mn = (int)mnew; un = (int)unew;
   // Algorithm 1 with this step
@@ -132,7 +142,7 @@ __device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const Ten
     const int u  = load_elem(T.sec, i, p.wu);
     const int g  = load_elem(T.grad, i, p.wg);
     int tn, cn, mn, un;
-    update_adam<CAPS, kTailWide>(p, th, c, m, u, g, tn, cn, mn, un, tr);
+    update_adam<CAPS, kTailWide, false>(p, th, c, m, u, g, tn, cn, mn, un, tr);
     store_elem(T.theta, i, p.wt, tn);
     if (p.has_comp) store_elem(T.comp, i, p.wc, cn);
     store_elem(T.mom, i, p.wm, mn);
@@ -141,8 +151,7 @@ __device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const Ten
 }
 
 // E consecutive elements per lane; int16 moments and gradients.  With E = 8 every access of a wave is one contiguous
-// run (dwordx4 for the 16-bit arrays, dwordx2 for 8-bit ones) and the fp64 temporaries of a group fit a register
-// budget that leaves room for more than two waves per SIMD.
+// run (dwordx4 for the 16-bit arrays, dwordx2 for 8-bit ones); four groups in flight at two waves per SIMD.
 template <int E, int WT, int WC> struct AGroup {
   DW<E * WT / 32> th;
   DW<E * WC / 32> c;
@@ -159,13 +168,13 @@ __device__ __forceinline__ void load_group_adam(AGroup<E, WT, WC>& G, const Tens
   G.g  = ld_dw<E / 2>((const int16_t*)T.grad + e);
 }
 
-template <int E, int WT, int WC, bool CAPS, int TAIL>
+template <int E, int WT, int WC, bool CAPS, int TAIL, bool EXACT3>
 __device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, WT, WC>& G, const TensorDev& T, uint64_t e, AdamTrack& tr)
 {
   int tn[E], cn[E], mn[E], un[E];
 #pragma unroll
   for (int k = 0; k < E; ++k)
-    update_adam<CAPS, TAIL>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), elem_dw<16>(G.m, k), elem_dw<16>(G.u, k), elem_dw<16>(G.g, k),
+    update_adam<CAPS, TAIL, EXACT3>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), elem_dw<16>(G.m, k), elem_dw<16>(G.u, k), elem_dw<16>(G.g, k),
                             tn[k], cn[k], mn[k], un[k], tr);
   st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
   st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
@@ -173,8 +182,8 @@ __device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, 
   st_dw((int16_t*)T.sec + e, pack_dw<16, E>(un));
 }
 
-template <int WT, int WC, bool CAPS, int TAIL>
-__device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
+template <int WT, int WC, bool CAPS, int TAIL, bool EXACT3>
+__device__ __forceinline__ void tile_vec_adam_x(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
 {
   constexpr int E = LPK_ADAM_E, kP = LPK_ADAM_GROUPS;      // elements per lane per group, groups in flight per lane
   const uint32_t ngroups = cnt / E;
@@ -184,16 +193,23 @@ __device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorD
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group_adam(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) group_adam<E, WT, WC, CAPS, TAIL>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
+    for (int ps = 0; ps < kP; ++ps) group_adam<E, WT, WC, CAPS, TAIL, EXACT3>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
   }
   for (; gi < ngroups; gi += kWave) {
     AGroup<E, WT, WC> G;
     const uint64_t e = off + (uint64_t)gi * E;
     load_group_adam(G, T, e);
-    group_adam<E, WT, WC, CAPS, TAIL>(p, G, T, e, tr);
+    group_adam<E, WT, WC, CAPS, TAIL, EXACT3>(p, G, T, e, tr);
   }
   const uint32_t tail = cnt - ngroups * E;
   if (tail) tile_generic_adam<CAPS>(p, T, off + (uint64_t)ngroups * E, tail, lane, tr);
+}
+
+template <int WT, int WC, bool CAPS, int TAIL>
+__device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
+{
+  if (!CAPS && p.exact3) tile_vec_adam_x<WT, WC, false, TAIL, true>(p, T, off, cnt, lane, tr);
+  else                   tile_vec_adam_x<WT, WC, CAPS, TAIL, false>(p, T, off, cnt, lane, tr);
 }
 
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
@@ -225,14 +241,15 @@ __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, in
   p.qmax_u = (double)((1 << (p.wu - 1)) - 1);
   p.ascale = pow2d(24 + par);
   p.eps_r  = __builtin_fmin(__builtin_rint((double)h.eps * pow2d(R - 16 - (int)h.eps_exp)), 1073741824.0);
-  p.nlr    = -(double)h.lr * pow2d(e > 0 ? e : 0);
-  p.dscale = pow2d(e < 0 ? -e : 0);
+  p.nlr    = -(double)h.lr * pow2d(e);
   const int u = delta > 0 ? delta : 0, kth = d + u - delta, kc = kth - d;
   p.p2d = pow2d(d); p.p2u = pow2d(u); p.inv_kth = pow2d(-kth); p.p2kth = pow2d(kth); p.inv_kc = pow2d(-kc);
   // Can a cap bind?  |g| <= 2^15 and g^2 <= 2^30 bound the two gradient terms; the step is at most
   // |num| / den <= 2^15 lr 2^e / max(eps_R, 1) (2^-e in the divisor when e < 0).
   const double step_bound = 32768.0 * (double)h.lr * pow2d(e) / __builtin_fmax(p.eps_r, 1.0);
   p.caps = !(32768.0 * p.a2 < cap_d() && 1073741824.0 * p.a4 < cap_d() && step_bound < cap_d());
+  auto whole = [](double x) { return x == __builtin_rint(x); };
+  p.exact3 = !p.caps && whole(p.a1) && whole(p.a2) && whole(p.a3);
   p.path = 1;
   const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
   if (p.has_comp && T.vec_adam && widths_ok && p.wg == 16 && p.wm == 16 && p.wu == 16) p.path = 2;

@@ -40,7 +40,7 @@ struct lpk_tensor_list {
   uint32_t   grid      = 0;        // blocks of the persistent read-mostly launches (max-abs, quantize)
   uint32_t   grid_step = 0;        // blocks of the plain update launches with lazy stores (read-dominated)
   uint32_t   grid_dense = 0;       // blocks of update launches that write everything (plain with LPK_OPT_STORE_ALL, momentum)
-  uint32_t   grid_adam = 0;        // blocks of the ADAM launch (bound by fp64 arithmetic, not by HBM: more waves help)
+  uint32_t   grid_adam = 0;        // blocks of the ADAM launch (two waves per SIMD: arithmetic and memory time are about equal)
   bool       all_src   = false;    // every non-empty tensor has an fp32 source
   bool       all_mom   = false;    // every non-empty tensor has a velocity buffer
   bool       all_sec   = false;    // ... and a second-moment buffer
@@ -139,7 +139,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     L->grid_step = clampg(env_u32("LPK_STEP_BLOCKS_PER_CU", 2));
     L->grid_dense = clampg(env_u32("LPK_DENSE_BLOCKS_PER_CU", 1));
     L->store_all = env_u32("LPK_STORE_ALL", 0) == 1;
-    L->grid_adam = clampg(env_u32("LPK_ADAM_BLOCKS_PER_CU", 3));
+    L->grid_adam = clampg(env_u32("LPK_ADAM_BLOCKS_PER_CU", 2));
     ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
          hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * n_tensors) == hipSuccess &&
          (tiles.empty() || hipMalloc((void**)&L->d_tiles, sizeof(Tile) * tiles.size()) == hipSuccess);
