@@ -431,16 +431,16 @@ def test_select_and_quantize_longer_than_2_to_the_32_elements():
 
 
 @pytest.mark.parametrize("store_all", [0, 1])
-@pytest.mark.parametrize("cb", [8, 16])
-def test_lazy_stores_in_every_regime(cb, store_all):
+@pytest.mark.parametrize("tb,cb", [(8, 8), (8, 16), (16, 16)])
+def test_lazy_stores_in_every_regime(tb, cb, store_all):
     """Stores of unchanged 16-byte groups are not issued (unless LPK_OPT_STORE_ALL): gradients crafted so that within
     one tensor some wave-sized runs change nothing, some change in one lane, some in a dozen lanes, some everywhere,
     in an order that makes a wave switch between its sparse and dense forms; int16 and fp32 gradient entry points,
     four steps, every byte against the oracle after each."""
-    say("lazy stores, comp int%d, store_all=%d" % (cb, store_all))
-    rng = np.random.default_rng(40 + cb + store_all)
+    say("lazy stores, theta int%d, comp int%d, store_all=%d" % (tb, cb, store_all))
+    rng = np.random.default_rng(40 + tb + cb + store_all)
     n = 70 * 4096 + 1000                                   # 70 full tiles and a ragged one: several per wave of a small grid
-    theta = rng.integers(-100, 100, size=n).astype(np.int8)
+    theta = rng.integers(-100, 100, size=n).astype(NP[tb])
     comp = np.zeros(n, dtype=NP[cb])
     d = cb - 1
     fl_t, fl_g = 7, (10 if cb == 8 else 19)                # step shift 12 (13): the 32-bit arithmetic, where stores are lazy
