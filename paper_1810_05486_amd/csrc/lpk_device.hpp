@@ -44,6 +44,16 @@
 #ifndef LPK_NT_STORE
 #define LPK_NT_STORE 1        // non-temporal hint on streaming stores
 #endif
+#if LPK_NT_LOAD
+#define LPK_LDNT(p) __builtin_nontemporal_load(p)
+#else
+#define LPK_LDNT(p) (*(p))
+#endif
+#if LPK_NT_STORE
+#define LPK_STNT(v, p) __builtin_nontemporal_store(v, p)
+#else
+#define LPK_STNT(v, p) (*(p) = (v))
+#endif
 
 namespace lpk {
 

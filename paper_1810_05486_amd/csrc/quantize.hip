@@ -45,9 +45,9 @@ __device__ __forceinline__ void quant_tile(const float* src, void* dst, bool vec
         else o[w] = (uint32_t)(q[4 * w] & 0xff) | ((uint32_t)(q[4 * w + 1] & 0xff) << 8) | ((uint32_t)(q[4 * w + 2] & 0xff) << 16) | ((uint32_t)q[4 * w + 3] << 24);
       }
       char* d = (char*)dst + e * (W / 8);
-      if constexpr (E * W / 32 == 1) __builtin_nontemporal_store(o[0], (LPK_GLOBAL uint32_t*)d);
-      else if constexpr (E * W / 32 == 2) { v2u v; v[0] = o[0]; v[1] = o[1]; __builtin_nontemporal_store(v, (LPK_GLOBAL v2u*)d); }
-      else { v4u v; v[0] = o[0]; v[1] = o[1]; v[2] = o[2]; v[3] = o[3]; __builtin_nontemporal_store(v, (LPK_GLOBAL v4u*)d); }
+      if constexpr (E * W / 32 == 1) LPK_STNT(o[0], (LPK_GLOBAL uint32_t*)d);
+      else if constexpr (E * W / 32 == 2) { v2u v; v[0] = o[0]; v[1] = o[1]; LPK_STNT(v, (LPK_GLOBAL v2u*)d); }
+      else { v4u v; v[0] = o[0]; v[1] = o[1]; v[2] = o[2]; v[3] = o[3]; LPK_STNT(v, (LPK_GLOBAL v4u*)d); }
     };
     uint32_t gi = lane;
     for (; gi + (KP - 1) * kWave < ng; gi += KP * kWave) {
@@ -56,14 +56,14 @@ __device__ __forceinline__ void quant_tile(const float* src, void* dst, bool vec
       for (int k = 0; k < KP; ++k)
 #pragma unroll
         for (int j = 0; j < E / 4; ++j)
-          x[k][j] = __builtin_nontemporal_load((const LPK_GLOBAL v4f*)(src + off + (uint64_t)(gi + k * kWave) * E + 4 * j));
+          x[k][j] = LPK_LDNT((const LPK_GLOBAL v4f*)(src + off + (uint64_t)(gi + k * kWave) * E + 4 * j));
 #pragma unroll
       for (int k = 0; k < KP; ++k) convert_store(x[k], off + (uint64_t)(gi + k * kWave) * E);
     }
     for (; gi < ng; gi += kWave) {
       v4f x[E / 4];
 #pragma unroll
-      for (int j = 0; j < E / 4; ++j) x[j] = __builtin_nontemporal_load((const LPK_GLOBAL v4f*)(src + off + (uint64_t)gi * E + 4 * j));
+      for (int j = 0; j < E / 4; ++j) x[j] = LPK_LDNT((const LPK_GLOBAL v4f*)(src + off + (uint64_t)gi * E + 4 * j));
       convert_store(x, off + (uint64_t)gi * E);
     }
     done = ng * E;

@@ -56,7 +56,7 @@ maxabs_f32_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
       if (nv == kTileElems / 4) {
         v4u a[kTileElems / 4 / kWave];
 #pragma unroll
-        for (int j = 0; j < kTileElems / 4 / kWave; ++j) a[j] = __builtin_nontemporal_load((const v4u*)s + j * kWave + lane);
+        for (int j = 0; j < kTileElems / 4 / kWave; ++j) a[j] = LPK_LDNT((const v4u*)s + j * kWave + lane);
 #pragma unroll
         for (int j = 0; j < kTileElems / 4 / kWave; ++j) {
           uint32_t m01 = max(absbits(a[j][0]), absbits(a[j][1])), m23 = max(absbits(a[j][2]), absbits(a[j][3]));
@@ -64,7 +64,7 @@ maxabs_f32_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
         }
       } else {
         for (uint32_t j = lane; j < nv; j += kWave) {
-          v4u a = __builtin_nontemporal_load((const v4u*)s + j);
+          v4u a = LPK_LDNT((const v4u*)s + j);
           lane_max = max(lane_max, max(max(absbits(a[0]), absbits(a[1])), max(absbits(a[2]), absbits(a[3]))));
         }
         for (uint32_t j = nv * 4 + lane; j < cnt; j += kWave) lane_max = max(lane_max, absbits(s[j]));
