@@ -23,6 +23,16 @@ def say(msg):
     sys.stdout.flush()
 
 
+def fuzz_seeds(default_count):
+    """Seeds of the random-list tests: 0..default_count-1, or LPK_FUZZ_SEEDS=lo:hi for a longer differential run."""
+    import os
+    spec = os.environ.get("LPK_FUZZ_SEEDS")
+    if not spec:
+        return range(default_count)
+    lo, hi = (int(x) for x in spec.split(":"))
+    return range(lo, hi)
+
+
 def u64(t):
     return t.cpu().numpy().view(np.uint64).tolist()
 
@@ -104,7 +114,7 @@ def test_adam_config5_full_size_in_bench_launch_configuration():
     run_config(workloads.config(5), range(2))
 
 
-@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("seed", fuzz_seeds(4))
 def test_adam_random_lists(seed):
     """Random widths, shifts, grid moves, alignments, sizes and hyper-parameters straight through the C ABI,
     including tensors that fall outside the domain (skipped and flagged on both sides)."""

@@ -23,6 +23,16 @@ def say(msg):
     sys.stdout.flush()
 
 
+def fuzz_seeds(default_count):
+    """Seeds of the random-list tests: 0..default_count-1, or LPK_FUZZ_SEEDS=lo:hi for a longer differential run."""
+    import os
+    spec = os.environ.get("LPK_FUZZ_SEEDS")
+    if not spec:
+        return range(default_count)
+    lo, hi = (int(x) for x in spec.split(":"))
+    return range(lo, hi)
+
+
 class Case:
     """One tensor of a list: host copies for the oracle, device copies (possibly misaligned views) for the library."""
 
@@ -87,7 +97,7 @@ def run_list(cases, lr_q, wd_q, want_vmax=True):
 SIZES = [0, 1, 15, 16, 17, 63, 64, 255, 1023, 1024, 1025, 4095, 4096, 4097, 8191, 12289, 70001]
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", fuzz_seeds(6))
 def test_random_lists_all_widths_shifts_and_alignments(seed):
     say("random multi-tensor lists, seed %d" % seed)
     rng = np.random.default_rng(100 + seed)

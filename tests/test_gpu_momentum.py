@@ -24,6 +24,16 @@ def say(msg):
     sys.stdout.flush()
 
 
+def fuzz_seeds(default_count):
+    """Seeds of the random-list tests: 0..default_count-1, or LPK_FUZZ_SEEDS=lo:hi for a longer differential run."""
+    import os
+    spec = os.environ.get("LPK_FUZZ_SEEDS")
+    if not spec:
+        return range(default_count)
+    lo, hi = (int(x) for x in spec.split(":"))
+    return range(lo, hi)
+
+
 def compare(dev, host, what):
     th, co, fl_t, fl_g, vm, status = dev.download()
     assert status == int(host.status[0]), (what, "status")
@@ -94,7 +104,7 @@ def test_momentum_config5_full_size_in_bench_launch_configuration():
     run_config(cfg, [8] * cfg.n_tensors, range(2))
 
 
-@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("seed", fuzz_seeds(4))
 def test_momentum_random_lists(seed):
     """Random widths, shifts, grid moves, alignments and sizes straight through the C ABI."""
     say("momentum: random lists, seed %d" % seed)
