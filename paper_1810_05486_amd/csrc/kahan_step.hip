@@ -297,7 +297,7 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
   Track tr{0, 0, ab_max, 0.0, 0, 0};
   const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
   constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : 8);     // VGPRs of one group
-  constexpr int kP = kRegs <= 16 ? LPK_I16_GROUPS : LPK_KP_WIDE;                     // groups in flight per lane
+  constexpr int kP = kRegs <= 16 ? (LAZY == kLazyNone ? LPK_I16_GROUPS : LPK_I16_GROUPS_LAZY) : LPK_KP_WIDE;   // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
@@ -507,8 +507,8 @@ __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const T
     return decay ? tile_fast_e<8, 1, WT, WC, GS, true, MODE, kLazyNone>(p, T, off, cnt, lane, ab, lz)
                  : tile_fast_e<8, 1, WT, WC, GS, false, MODE, kLazyNone>(p, T, off, cnt, lane, ab, lz);
   if (GS == kGradF32)
-    return decay ? tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
-                 : tile_fast_e<LPK_F32_E, LPK_F32_GROUPS, WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
+    return decay ? tile_fast_e<LPK_F32_E, (LAZY == kLazyNone ? LPK_F32_GROUPS : LPK_F32_GROUPS_LAZY), WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
+                 : tile_fast_e<LPK_F32_E, (LAZY == kLazyNone ? LPK_F32_GROUPS : LPK_F32_GROUPS_LAZY), WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
 #if LPK_I16_E != 16
   return decay ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
                : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
@@ -516,8 +516,8 @@ __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const T
   // a 16-bit theta or comp: 8 elements per lane, so that every access of a wave is one contiguous run (with 16, a
   // lane's 16-bit data spans two stores 32 bytes apart and HBM sees partial-line writes)
   if constexpr (WC == 16)
-    return decay ? tile_fast_e<8, LPK_W16_GROUPS, WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
-                 : tile_fast_e<8, LPK_W16_GROUPS, WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
+    return decay ? tile_fast_e<8, (LAZY == kLazyNone ? LPK_W16_GROUPS : LPK_W16_GROUPS_LAZY), WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
+                 : tile_fast_e<8, (LAZY == kLazyNone ? LPK_W16_GROUPS : LPK_W16_GROUPS_LAZY), WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
   return decay ? tile_fast<WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
                : tile_fast<WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
 }
