@@ -152,30 +152,41 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    # the same whole path with quantization fused into the update (select + lpk_kahan_sgd_step_f32grad)
+    # the same whole path with quantization fused into the update (select + the optimizer's *_f32grad call)
     fused = None
-    if mu_q16 is None and not args.adam:
+    if True:
+        def fused_update(s, k):
+            if args.adam:
+                dev.update_adam(workloads.adam_hyper(s), k, fused=True)
+            elif mu_q16 is not None:
+                dev.update_momentum(cfg.lr_q16(s), mu_q16, cfg.wd_q16, k, fused=True)
+            else:
+                lpk.lpk_kahan_sgd_step_f32grad(dev.lists[k], dev.fl_theta, dev.fl_next, dev.fl_grad, cfg.lr_q16(s), cfg.wd_q16,
+                                               dev.vmax, dev.status)
         fev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
         for s in range(2):
-            dev.step_fused(s, k=s % n_src)
+            dev.select_grads(s % n_src)
+            fused_update(s, s % n_src)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         for i in range(K):
             s = args.warmup + K + i
             k = s % n_src
             fev[i][0].record()
-            lpk.lpk_select_fraclen(dev.lists[k], lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, dev.fl_grad, dev.fl_grad, dev.status)
+            dev.select_grads(k)
             fev[i][1].record()
-            lpk.lpk_kahan_sgd_step_f32grad(dev.lists[k], dev.fl_theta, dev.fl_next, dev.fl_grad, cfg.lr_q16(s), cfg.wd_q16,
-                                           dev.vmax, dev.status)
+            fused_update(s, k)
             fev[i][2].record()
         torch.cuda.synchronize()
         fwall = time.perf_counter() - t1
         f_upd_ms = sum(e[1].elapsed_time(e[2]) for e in fev) / K
         fbytes = sum(n * (4 * (b // 8 + (cb // 8)) // 2 + 4) for n, b, cb in zip(cfg.sizes, cfg.bits, dev.comp_bits))
+        fbytes += 2 * (args.momentum_bits // 8) * cfg.n_params if args.momentum_bits else 0
+        fbytes += 8 * cfg.n_params if args.adam else 0
+        fname = "adam_step_kernel<fp32 grad>" if args.adam else ("momentum_step_kernel<fp32 grad>" if args.momentum_bits else "kahan_step_kernel<fp32 grad>")
         fused = {"value": cfg.n_params / (fwall / K) / 1e9, "unit": "Gparam/s", "ms_per_step": fwall * 1e3 / K,
                  "stage_ms": {"select_fraclen": sum(e[0].elapsed_time(e[1]) for e in fev) / K, "kahan_sgd_step_f32grad": f_upd_ms},
-                 "roofline": {"bound": "hbm", "kernel": "kahan_step_kernel<fp32 grad>", "achieved": fbytes / (f_upd_ms * 1e-3) / 1e9,
+                 "roofline": {"bound": "hbm", "kernel": fname, "achieved": fbytes / (f_upd_ms * 1e-3) / 1e9,
                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fbytes / (f_upd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                               "bytes_per_launch": fbytes}}
 

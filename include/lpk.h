@@ -225,6 +225,19 @@ int lpk_momentum_sgd_step(lpk_tensor_list* list,
                           uint64_t* vmax_out, uint64_t* mmax_out, uint32_t* status, void* stream);
 
 /*
+ * The same momentum step fed from the fp32 gradients (Sections 1, 2, 4): exactly
+ * lpk_quantize_tensor(LPK_SEL_GRAD, fl_grad) followed by lpk_momentum_sgd_step, in ONE pass that reads desc.src_f32,
+ * quantizes each gradient in registers as lpk_kahan_sgd_step_f32grad does, and never touches desc.grad.  Results
+ * (theta, comp, momentum, vmax, mmax, status) are bit-identical to the two-call sequence.  Every non-empty tensor
+ * needs src_f32 and a momentum buffer (else INVALID_ARG).
+ */
+int lpk_momentum_sgd_step_f32grad(lpk_tensor_list* list,
+                                  const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                                  const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_grad,
+                                  uint32_t lr_q16, uint32_t mu_q16, uint32_t wd_q16,
+                                  uint64_t* vmax_out, uint64_t* mmax_out, uint32_t* status, void* stream);
+
+/*
  * ADAM with the lazy update inside (Section 4: the ADAM optimizer in INT16 -- 16 bits because of beta2 --
  * with Algorithm 1 implemented in the optimizer; the paper names only the hyper-parameters).  Textbook rule
  *   m <- beta1 m + (1 - beta1) g;  u <- beta2 u + (1 - beta2) g^2;  theta <- theta - lr_t m / (sqrt(u) + eps)
@@ -262,6 +275,19 @@ int lpk_adam_step(lpk_tensor_list* list,
                   const int32_t* fl_sec_in, const int32_t* fl_sec_out, const int32_t* fl_grad,
                   const lpk_adam_hyper* hyper /* host */,
                   uint64_t* vmax_out, uint64_t* mmax_out, uint64_t* umax_out, uint32_t* status, void* stream);
+
+/*
+ * The same ADAM step fed from the fp32 gradients (Sections 1, 2, 4): exactly
+ * lpk_quantize_tensor(LPK_SEL_GRAD, fl_grad) followed by lpk_adam_step, in ONE pass that reads desc.src_f32,
+ * quantizes each gradient in registers and never touches desc.grad.  Results are bit-identical to the two-call
+ * sequence.  Every non-empty tensor needs src_f32, a momentum and a second-moment buffer (else INVALID_ARG).
+ */
+int lpk_adam_step_f32grad(lpk_tensor_list* list,
+                          const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                          const int32_t* fl_mom_in, const int32_t* fl_mom_out,
+                          const int32_t* fl_sec_in, const int32_t* fl_sec_out, const int32_t* fl_grad,
+                          const lpk_adam_hyper* hyper /* host */,
+                          uint64_t* vmax_out, uint64_t* mmax_out, uint64_t* umax_out, uint32_t* status, void* stream);
 
 /*
  * Bit-width guideline for the last fully-connected layer (Section 3, eq. 4-5): the smallest width BW with

@@ -67,6 +67,10 @@ def lib():
         L.lpk_momentum_sgd_step.restype = ci
         L.lpk_adam_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(lpk_adam_hyper), vp, vp, vp, vp, vp]
         L.lpk_adam_step.restype = ci
+        L.lpk_momentum_sgd_step_f32grad.argtypes = L.lpk_momentum_sgd_step.argtypes
+        L.lpk_momentum_sgd_step_f32grad.restype = ci
+        L.lpk_adam_step_f32grad.argtypes = L.lpk_adam_step.argtypes
+        L.lpk_adam_step_f32grad.restype = ci
         L.lpk_stream_copy.argtypes = [vp, vp, u64, vp]
         L.lpk_stream_copy.restype = ci
         L.lpk_stream_mix.argtypes = [vp, vp, vp, u64, vp]
@@ -204,6 +208,14 @@ def lpk_momentum_sgd_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, 
            "lpk_momentum_sgd_step")
 
 
+def lpk_momentum_sgd_step_f32grad(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16=0,
+                                  vmax_out=None, mmax_out=None, status=None, stream=None):
+    _check(lib().lpk_momentum_sgd_step_f32grad(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_mom_in),
+                                               _addr(fl_mom_out), _addr(fl_grad), int(lr_q16), int(mu_q16), int(wd_q16),
+                                               _addr(vmax_out), _addr(mmax_out), _addr(status), _stream(stream)),
+           "lpk_momentum_sgd_step_f32grad")
+
+
 def lpk_adam_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, hyper,
                   vmax_out=None, mmax_out=None, umax_out=None, status=None, stream=None):
     """hyper: an lpk_adam_hyper, or a tuple (lr_q16, lr_exp, beta1_q16, beta2_q16, eps_q16, eps_exp)."""
@@ -212,6 +224,16 @@ def lpk_adam_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_sec_i
                                _addr(fl_sec_in), _addr(fl_sec_out), _addr(fl_grad), ctypes.byref(h),
                                _addr(vmax_out), _addr(mmax_out), _addr(umax_out), _addr(status), _stream(stream)),
            "lpk_adam_step")
+
+
+def lpk_adam_step_f32grad(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, hyper,
+                          vmax_out=None, mmax_out=None, umax_out=None, status=None, stream=None):
+    """lpk_adam_step fed from the fp32 gradients; hyper as there."""
+    h = hyper if isinstance(hyper, lpk_adam_hyper) else lpk_adam_hyper(*[int(x) for x in hyper])
+    _check(lib().lpk_adam_step_f32grad(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_mom_in), _addr(fl_mom_out),
+                                       _addr(fl_sec_in), _addr(fl_sec_out), _addr(fl_grad), ctypes.byref(h),
+                                       _addr(vmax_out), _addr(mmax_out), _addr(umax_out), _addr(status), _stream(stream)),
+           "lpk_adam_step_f32grad")
 
 
 def lpk_stream_mix(a, b, c, nbytes, stream=None):

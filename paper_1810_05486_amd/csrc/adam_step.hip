@@ -41,6 +41,7 @@ struct AdamParams {
   double eps_r;                    // eps on the root's grid, at most 2^30
   double nlr;                      // -lr * 2^e
   double p2d, p2u, inv_kth, p2kth, inv_kc;
+  float  gscale, glo, ghi;         // fp32 gradient source: 2^fl_g and the rails of the gradient width
   // 32-bit tail (int8 theta, fixed grid, every |intermediate| of Algorithm 1 below 2^22): as in the plain update,
   // fma(v, 2^-d, 1.5 * 2^23) rounds v onto theta's grid and one 24-bit multiply-add forms the residual
   int    tail;                     // kTailWide, kTailSmall (int8 accumulator, d <= 8) or kTailSmallBigD (int16 accumulator)
@@ -131,8 +132,9 @@ __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, 
 }
 
 // Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
-template <bool CAPS>
-__device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
+template <bool CAPS, int GS>
+__device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr,
+                                                  uint32_t& ab)
 {
   for (uint32_t j = lane; j < cnt; j += kWave) {
     const uint64_t i = off + j;
@@ -140,7 +142,7 @@ __device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const Ten
     const int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
     const int m  = load_elem(T.mom, i, p.wm);
     const int u  = load_elem(T.sec, i, p.wu);
-    const int g  = load_elem(T.grad, i, p.wg);
+    const int g  = GS == kGradF32 ? (int)quant_f32(((const float*)T.src)[i], p.gscale, p.glo, p.ghi, ab) : load_elem(T.grad, i, p.wg);
     int tn, cn, mn, un;
     update_adam<CAPS, kTailWide, false>(p, th, c, m, u, g, tn, cn, mn, un, tr);
     store_elem(T.theta, i, p.wt, tn);
@@ -152,68 +154,84 @@ __device__ __forceinline__ void tile_generic_adam(const AdamParams& p, const Ten
 
 // E consecutive elements per lane; int16 moments and gradients.  With E = 8 every access of a wave is one contiguous
 // run (dwordx4 for the 16-bit arrays, dwordx2 for 8-bit ones); four groups in flight at two waves per SIMD.
-template <int E, int WT, int WC> struct AGroup {
+template <int E, int WT, int WC, int GS> struct AGroup {
+  static constexpr int kG = GS == kGradF32 ? E / 4 : 1;          // gradient accesses: dwordx4 of fp32, or one of E int16
+  static constexpr int kGN = GS == kGradF32 ? 4 : E / 2;
   DW<E * WT / 32> th;
   DW<E * WC / 32> c;
-  DW<E / 2> m, u, g;
+  DW<E / 2> m, u;
+  DW<kGN> g[kG];
 };
 
-template <int E, int WT, int WC>
-__device__ __forceinline__ void load_group_adam(AGroup<E, WT, WC>& G, const TensorDev& T, uint64_t e)
+template <int E, int WT, int WC, int GS>
+__device__ __forceinline__ void load_group_adam(AGroup<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e)
 {
   G.th = ld_dw<E * WT / 32>((const int8_t*)T.theta + e * (WT / 8));
   G.c  = ld_dw<E * WC / 32>((const int8_t*)T.comp + e * (WC / 8));
   G.m  = ld_dw<E / 2>((const int16_t*)T.mom + e);
   G.u  = ld_dw<E / 2>((const int16_t*)T.sec + e);
-  G.g  = ld_dw<E / 2>((const int16_t*)T.grad + e);
+  if constexpr (GS == kGradF32) {
+#pragma unroll
+    for (int j = 0; j < E / 4; ++j) G.g[j] = ld_dw<4>((const float*)T.src + e + 4 * j);
+  } else {
+    G.g[0] = ld_dw<E / 2>((const int16_t*)T.grad + e);
+  }
 }
 
-template <int E, int WT, int WC, bool CAPS, int TAIL, bool EXACT3>
-__device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, WT, WC>& G, const TensorDev& T, uint64_t e, AdamTrack& tr)
+template <int E, int WT, int WC, bool CAPS, int TAIL, bool EXACT3, int GS>
+__device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, AdamTrack& tr,
+                                           uint32_t& ab)
 {
   int tn[E], cn[E], mn[E], un[E];
 #pragma unroll
-  for (int k = 0; k < E; ++k)
-    update_adam<CAPS, TAIL, EXACT3>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), elem_dw<16>(G.m, k), elem_dw<16>(G.u, k), elem_dw<16>(G.g, k),
-                            tn[k], cn[k], mn[k], un[k], tr);
+  for (int k = 0; k < E; ++k) {
+    int g;
+    if constexpr (GS == kGradF32) g = (int)quant_f32(__int_as_float(G.g[k >> 2].d[k & 3]), p.gscale, p.glo, p.ghi, ab);
+    else                          g = elem_dw<16>(G.g[0], k);
+    update_adam<CAPS, TAIL, EXACT3>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), elem_dw<16>(G.m, k), elem_dw<16>(G.u, k), g,
+                                    tn[k], cn[k], mn[k], un[k], tr);
+  }
   st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
   st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
   st_dw((int16_t*)T.mom + e, pack_dw<16, E>(mn));
   st_dw((int16_t*)T.sec + e, pack_dw<16, E>(un));
 }
 
-template <int WT, int WC, bool CAPS, int TAIL, bool EXACT3>
-__device__ __forceinline__ void tile_vec_adam_x(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
+template <int WT, int WC, bool CAPS, int TAIL, bool EXACT3, int GS>
+__device__ __forceinline__ void tile_vec_adam_x(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr,
+                                                uint32_t& ab)
 {
   constexpr int E = LPK_ADAM_E, kP = LPK_ADAM_GROUPS;      // elements per lane per group, groups in flight per lane
   const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
-    AGroup<E, WT, WC> G[kP];
+    AGroup<E, WT, WC, GS> G[kP];
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group_adam(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
-    for (int ps = 0; ps < kP; ++ps) group_adam<E, WT, WC, CAPS, TAIL, EXACT3>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
+    for (int ps = 0; ps < kP; ++ps) group_adam<E, WT, WC, CAPS, TAIL, EXACT3, GS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr, ab);
   }
   for (; gi < ngroups; gi += kWave) {
-    AGroup<E, WT, WC> G;
+    AGroup<E, WT, WC, GS> G;
     const uint64_t e = off + (uint64_t)gi * E;
     load_group_adam(G, T, e);
-    group_adam<E, WT, WC, CAPS, TAIL, EXACT3>(p, G, T, e, tr);
+    group_adam<E, WT, WC, CAPS, TAIL, EXACT3, GS>(p, G, T, e, tr, ab);
   }
   const uint32_t tail = cnt - ngroups * E;
-  if (tail) tile_generic_adam<CAPS>(p, T, off + (uint64_t)ngroups * E, tail, lane, tr);
+  if (tail) tile_generic_adam<CAPS, GS>(p, T, off + (uint64_t)ngroups * E, tail, lane, tr, ab);
 }
 
-template <int WT, int WC, bool CAPS, int TAIL>
-__device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr)
+template <int WT, int WC, bool CAPS, int TAIL, int GS>
+__device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr,
+                                              uint32_t& ab)
 {
-  if (!CAPS && p.exact3) tile_vec_adam_x<WT, WC, false, TAIL, true>(p, T, off, cnt, lane, tr);
-  else                   tile_vec_adam_x<WT, WC, CAPS, TAIL, false>(p, T, off, cnt, lane, tr);
+  if (!CAPS && p.exact3) tile_vec_adam_x<WT, WC, false, TAIL, true, GS>(p, T, off, cnt, lane, tr, ab);
+  else                   tile_vec_adam_x<WT, WC, CAPS, TAIL, false, GS>(p, T, off, cnt, lane, tr, ab);
 }
 
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
 
+template <int GS>
 __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, int fl_in, int fl_out, int fl_m_in, int fl_m_out,
                                            int fl_u_in, int fl_u_out, int fl_g, const AdamHyperDev& h, uint32_t& status_bits)
 {
@@ -250,9 +268,12 @@ __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, in
   p.caps = !(32768.0 * p.a2 < cap_d() && 1073741824.0 * p.a4 < cap_d() && step_bound < cap_d());
   auto whole = [](double x) { return x == __builtin_rint(x); };
   p.exact3 = !p.caps && whole(p.a1) && whole(p.a2) && whole(p.a3);
+  p.gscale = __uint_as_float((uint32_t)(127 + fl_g) << 23);
+  p.glo = -(float)(1 << (p.wg - 1)); p.ghi = (float)((1 << (p.wg - 1)) - 1);
   p.path = 1;
   const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
-  if (p.has_comp && T.vec_adam && widths_ok && p.wg == 16 && p.wm == 16 && p.wu == 16) p.path = 2;
+  const bool src_ok = GS == kGradI16 || (((uintptr_t)T.src) & 15u) == 0;
+  if (p.has_comp && T.vec_adam && src_ok && widths_ok && p.wg == 16 && p.wm == 16 && p.wu == 16) p.path = 2;
   // 32-bit tail: |theta * 2^d| + |c| + |s| + the rounding addend provably below 2^22 (2^23 with the residual formed
   // unshifted), theta's grid fixed, 1 <= d
   p.tail = kTailWide;
@@ -278,6 +299,7 @@ __device__ __forceinline__ uint64_t track_v(const AdamTrack& tr)                
   return m32 > m64 ? m32 : m64;
 }
 
+template <int GS>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(LPK_ADAM_WAVES_PER_SIMD, LPK_ADAM_WAVES_PER_SIMD)))
 adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                  const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out,
@@ -295,7 +317,7 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
 
   int cur = -1;
   AdamTrack tr{0.0, 0.0, 0.0, 0, 0};
-  uint32_t status_bits = 0;
+  uint32_t status_bits = 0, ab_max = 0;
   AdamParams p; p.path = 0;
   TensorDev T;
 
@@ -311,23 +333,24 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
       tr = AdamTrack{0.0, 0.0, 0.0, 0, 0};
       cur = t;
       T = tensors[t];
-      setup_adam(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_u_in[t], fl_u_out[t], fl_g[t], h, status_bits);
+      setup_adam<GS>(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_u_in[t], fl_u_out[t], fl_g[t], h, status_bits);
     }
     if (p.path == 2 && !p.caps) {
       if (p.wt == 8 && p.wc == 8) {
-        if (p.tail == kTailSmall) tile_vec_adam<8, 8, false, kTailSmall>(p, T, off, cnt, lane, tr);
-        else                      tile_vec_adam<8, 8, false, kTailWide>(p, T, off, cnt, lane, tr);
+        if (p.tail == kTailSmall) tile_vec_adam<8, 8, false, kTailSmall, GS>(p, T, off, cnt, lane, tr, ab_max);
+        else                      tile_vec_adam<8, 8, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
       } else if (p.wt == 16) {
-        tile_vec_adam<16, 16, false, kTailWide>(p, T, off, cnt, lane, tr);
+        tile_vec_adam<16, 16, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
       } else {
-        if (p.tail == kTailSmallBigD) tile_vec_adam<8, 16, false, kTailSmallBigD>(p, T, off, cnt, lane, tr);
-        else                          tile_vec_adam<8, 16, false, kTailWide>(p, T, off, cnt, lane, tr);
+        if (p.tail == kTailSmallBigD) tile_vec_adam<8, 16, false, kTailSmallBigD, GS>(p, T, off, cnt, lane, tr, ab_max);
+        else                          tile_vec_adam<8, 16, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
       }
     } else if (p.path) {
-      if (p.caps) tile_generic_adam<true>(p, T, off, cnt, lane, tr); else tile_generic_adam<false>(p, T, off, cnt, lane, tr);
+      if (p.caps) tile_generic_adam<true, GS>(p, T, off, cnt, lane, tr, ab_max); else tile_generic_adam<false, GS>(p, T, off, cnt, lane, tr, ab_max);
     }
   }
 
+  if (GS == kGradF32 && __ballot(ab_max >= 0x7f800000u)) status_bits |= kStatusNonFinite;
   if (status && status_bits && lane == 0) atomicOr(status, status_bits);
   if (vmax) flush_block(vmax, cur, track_v(tr), lane, wave, s_tensor, s_max);
   if (mmax) flush_block(mmax, cur, track_u64(tr.mm), lane, wave, s_tensor, s_max);
@@ -341,15 +364,20 @@ __global__ void __launch_bounds__(kBlock) fill3_u64_kernel(uint64_t* a, uint64_t
 }
 
 hipError_t launch_adam_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                            const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
+                            int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                             const int32_t* fl_u_in, const int32_t* fl_u_out, const int32_t* fl_g, AdamHyperDev h,
                             uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, hipStream_t stream)
 {
   if (vmax || mmax || umax)
     hipLaunchKernelGGL(fill3_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, mmax, umax, n_tensors);
-  if (n_tiles)
-    hipLaunchKernelGGL(adam_step_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                       fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, h, vmax, mmax, umax, status);
+  if (n_tiles) {
+    if (grad_is_f32)
+      hipLaunchKernelGGL(adam_step_kernel<kGradF32>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                         fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, h, vmax, mmax, umax, status);
+    else
+      hipLaunchKernelGGL(adam_step_kernel<kGradI16>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                         fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, h, vmax, mmax, umax, status);
+  }
   return hipGetLastError();
 }
 

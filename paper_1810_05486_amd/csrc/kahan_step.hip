@@ -34,7 +34,6 @@
 
 namespace lpk {
 
-enum { kGradI16 = 0, kGradF32 = 1 };
 
 struct StepParams {
   int      path;            // 0 skip, 1 element by element (wide arithmetic), 2 vector (arithmetic by `mode`)

@@ -22,11 +22,11 @@ hipError_t launch_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint
 hipError_t launch_stream_copy(void* dst, const void* src, uint64_t nbytes, uint32_t grid, hipStream_t);
 hipError_t launch_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, uint32_t grid, hipStream_t);
 hipError_t launch_momentum_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                                const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
+                                int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                                 const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
                                 uint64_t* vmax, uint64_t* mmax, uint32_t* status, hipStream_t);
 hipError_t launch_adam_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                            const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
+                            int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                             const int32_t* fl_u_in, const int32_t* fl_u_out, const int32_t* fl_g, AdamHyperDev h,
                             uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, hipStream_t);
 }  // namespace lpk
@@ -236,17 +236,52 @@ int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, c
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
+static int momentum_step(lpk_tensor_list* L, int grad_is_f32, const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                         const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_grad,
+                         uint32_t lr_q16, uint32_t mu_q16, uint32_t wd_q16,
+                         uint64_t* vmax_out, uint64_t* mmax_out, uint32_t* status, void* stream)
+{
+  if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_grad) return LPK_ERR_INVALID_ARG;
+  if (lr_q16 > 65535u || wd_q16 > 65535u || mu_q16 > 65535u) return LPK_ERR_INVALID_ARG;
+  if (!L->all_mom || (grad_is_f32 && !L->all_src)) return LPK_ERR_INVALID_ARG;
+  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_dense, grad_is_f32,
+                                      fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16,
+                                      vmax_out, mmax_out, status, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
 int lpk_momentum_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t* fl_theta_out,
                           const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_grad,
                           uint32_t lr_q16, uint32_t mu_q16, uint32_t wd_q16,
                           uint64_t* vmax_out, uint64_t* mmax_out, uint32_t* status, void* stream)
 {
-  if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_grad) return LPK_ERR_INVALID_ARG;
-  if (lr_q16 > 65535u || wd_q16 > 65535u || mu_q16 > 65535u) return LPK_ERR_INVALID_ARG;
-  if (!L->all_mom) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_dense, fl_theta_in, fl_theta_out,
-                                      fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16, vmax_out, mmax_out, status,
-                                      static_cast<hipStream_t>(stream));
+  return momentum_step(L, 0, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16,
+                       vmax_out, mmax_out, status, stream);
+}
+
+int lpk_momentum_sgd_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                                  const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_grad,
+                                  uint32_t lr_q16, uint32_t mu_q16, uint32_t wd_q16,
+                                  uint64_t* vmax_out, uint64_t* mmax_out, uint32_t* status, void* stream)
+{
+  return momentum_step(L, 1, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16,
+                       vmax_out, mmax_out, status, stream);
+}
+
+static int adam_step(lpk_tensor_list* L, int grad_is_f32, const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                     const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_sec_in, const int32_t* fl_sec_out,
+                     const int32_t* fl_grad, const lpk_adam_hyper* hyper,
+                     uint64_t* vmax_out, uint64_t* mmax_out, uint64_t* umax_out, uint32_t* status, void* stream)
+{
+  if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_sec_in || !fl_sec_out || !fl_grad || !hyper)
+    return LPK_ERR_INVALID_ARG;
+  if (hyper->lr_q16 > 65535u || hyper->beta1_q16 > 65535u || hyper->beta2_q16 > 65535u || hyper->eps_q16 > 65535u ||
+      hyper->lr_exp > 48u || hyper->eps_exp > 48u) return LPK_ERR_INVALID_ARG;
+  if (!L->all_mom || !L->all_sec || (grad_is_f32 && !L->all_src)) return LPK_ERR_INVALID_ARG;
+  const AdamHyperDev h{hyper->lr_q16, hyper->lr_exp, hyper->beta1_q16, hyper->beta2_q16, hyper->eps_q16, hyper->eps_exp};
+  hipError_t e = launch_adam_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_adam, grad_is_f32,
+                                  fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, h,
+                                  vmax_out, mmax_out, umax_out, status, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
@@ -255,16 +290,17 @@ int lpk_adam_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t*
                   const int32_t* fl_grad, const lpk_adam_hyper* hyper,
                   uint64_t* vmax_out, uint64_t* mmax_out, uint64_t* umax_out, uint32_t* status, void* stream)
 {
-  if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_sec_in || !fl_sec_out || !fl_grad || !hyper)
-    return LPK_ERR_INVALID_ARG;
-  if (hyper->lr_q16 > 65535u || hyper->beta1_q16 > 65535u || hyper->beta2_q16 > 65535u || hyper->eps_q16 > 65535u ||
-      hyper->lr_exp > 48u || hyper->eps_exp > 48u) return LPK_ERR_INVALID_ARG;
-  if (!L->all_mom || !L->all_sec) return LPK_ERR_INVALID_ARG;
-  const AdamHyperDev h{hyper->lr_q16, hyper->lr_exp, hyper->beta1_q16, hyper->beta2_q16, hyper->eps_q16, hyper->eps_exp};
-  hipError_t e = launch_adam_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_adam, fl_theta_in, fl_theta_out,
-                                  fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, h, vmax_out, mmax_out, umax_out, status,
-                                  static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+  return adam_step(L, 0, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, hyper,
+                   vmax_out, mmax_out, umax_out, status, stream);
+}
+
+int lpk_adam_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, const int32_t* fl_theta_out,
+                          const int32_t* fl_mom_in, const int32_t* fl_mom_out, const int32_t* fl_sec_in, const int32_t* fl_sec_out,
+                          const int32_t* fl_grad, const lpk_adam_hyper* hyper,
+                          uint64_t* vmax_out, uint64_t* mmax_out, uint64_t* umax_out, uint32_t* status, void* stream)
+{
+  return adam_step(L, 1, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, hyper,
+                   vmax_out, mmax_out, umax_out, status, stream);
 }
 
 int lpk_stream_copy(void* dst, const void* src, uint64_t nbytes, void* stream)
@@ -316,6 +352,6 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
   return bw;
 }
 
-int lpk_version(void) { return 106; }
+int lpk_version(void) { return 107; }
 
 }  // extern "C"

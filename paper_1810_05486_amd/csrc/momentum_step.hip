@@ -20,6 +20,7 @@ struct MomParams {
   int      k1, k2, k3w, k3;      // shifts: mu*m -> G, lr*g -> G, lr*wd*theta -> G, m' -> F
   int      u, kth, kc;
   int64_t  lr, mu, lrwd;
+  float    gscale, glo, ghi;            // fp32 gradient source: 2^fl_g and the rails of the gradient width
   int      qmin_t, qmax_t, qmin_c, qmax_c, qmin_m, qmax_m;
   // 32-bit path: each term is (x << a) then RNE >> b with exactly one of a, b non-zero
   int      mu_i, a1, b1, h1, nz1;          // mu*m -> grid G
@@ -62,8 +63,9 @@ __device__ __forceinline__ void fold_wide(const WideMax& mx, uint64_t& vm, uint6
   wm = b > wm ? b : wm;
 }
 
+template <int GS>
 __device__ __forceinline__ void tile_generic_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
-                                                 uint64_t& vm, uint64_t& wm)
+                                                 uint64_t& vm, uint64_t& wm, uint32_t& ab)
 {
   WideMax mx{0.0, 0.0};
   for (uint32_t j = lane; j < cnt; j += kWave) {
@@ -71,7 +73,7 @@ __device__ __forceinline__ void tile_generic_mom(const MomParams& p, const Tenso
     int th = load_elem(T.theta, i, p.wt);
     int c  = p.has_comp ? load_elem(T.comp, i, p.wc) : 0;
     int m  = load_elem(T.mom, i, p.wm);
-    int g  = load_elem(T.grad, i, p.wg);
+    int g  = GS == kGradF32 ? (int)quant_f32(((const float*)T.src)[i], p.gscale, p.glo, p.ghi, ab) : load_elem(T.grad, i, p.wg);
     int tn, cn, mn;
     if (p.lrwd) update_wide_mom<true>(p, th, c, m, g, tn, cn, mn, mx); else update_wide_mom<false>(p, th, c, m, g, tn, cn, mn, mx);
     store_elem(T.theta, i, p.wt, tn);
@@ -120,29 +122,37 @@ __device__ __forceinline__ void update_fast_mom(const MomParams& p, int th, int 
 // E = 16 when all three are 8 bits wide (dwordx4 each), E = 8 as soon as one of them is 16 bits wide: then every
 // access of a wave is still one contiguous run (with 16, a lane's 16-bit data would span two stores 32 bytes
 // apart, which reach HBM as partial lines).
-template <int E, int WT, int WM> struct MGroup {
+template <int E, int WT, int WM, int GS> struct MGroup {
+  static constexpr int kG = GS == kGradF32 ? E / 4 : E / 8;       // dwordx4 gradient accesses
   DW<E * WT / 32> th, c;
   DW<E * WM / 32> m;
-  DW<4> g[E / 8];
+  DW<4> g[kG];
 };
 
-template <int E, int WT, int WM>
-__device__ __forceinline__ void load_group_mom(MGroup<E, WT, WM>& G, const TensorDev& T, uint64_t e)
+template <int E, int WT, int WM, int GS>
+__device__ __forceinline__ void load_group_mom(MGroup<E, WT, WM, GS>& G, const TensorDev& T, uint64_t e)
 {
   G.th = ld_dw<E * WT / 32>((const int8_t*)T.theta + e * (WT / 8));
   G.c  = ld_dw<E * WT / 32>((const int8_t*)T.comp + e * (WT / 8));
   G.m  = ld_dw<E * WM / 32>((const int8_t*)T.mom + e * (WM / 8));
 #pragma unroll
-  for (int j = 0; j < E / 8; ++j) G.g[j] = ld_dw<4>((const int16_t*)T.grad + e + 8 * j);
+  for (int j = 0; j < MGroup<E, WT, WM, GS>::kG; ++j) {
+    if constexpr (GS == kGradF32) G.g[j] = ld_dw<4>((const float*)T.src + e + 4 * j);
+    else                          G.g[j] = ld_dw<4>((const int16_t*)T.grad + e + 8 * j);
+  }
 }
 
-template <int E, int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE>
-__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<E, WT, WM>& G, const TensorDev& T, uint64_t e, MaxTrack& mt, WideMax& mx)
+template <int E, int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE, int GS>
+__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<E, WT, WM, GS>& G, const TensorDev& T, uint64_t e, MaxTrack& mt, WideMax& mx,
+                                               uint32_t& ab)
 {
   int tn[E], cn[E], mn[E];
 #pragma unroll
   for (int k = 0; k < E; ++k) {
-    const int th = elem_dw<WT>(G.th, k), c = elem_dw<WT>(G.c, k), m = elem_dw<WM>(G.m, k), g = elem_dw<16>(G.g[k >> 3], k & 7);
+    const int th = elem_dw<WT>(G.th, k), c = elem_dw<WT>(G.c, k), m = elem_dw<WM>(G.m, k);
+    int g;
+    if constexpr (GS == kGradF32) g = (int)quant_f32(__int_as_float(G.g[k >> 2].d[k & 3]), p.gscale, p.glo, p.ghi, ab);
+    else                          g = elem_dw<16>(G.g[k >> 3], k & 7);
     if (WIDE) update_wide_mom<DECAY>(p, th, c, m, g, tn[k], cn[k], mn[k], mx);
     else      update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, th, c, m, g, tn[k], cn[k], mn[k], mt);
   }
@@ -151,29 +161,29 @@ __device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<
   st_dw((int8_t*)T.mom + e * (WM / 8), pack_dw<WM, E>(mn));
 }
 
-template <int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE>
+template <int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE, int GS>
 __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
-                                              uint64_t& vm, uint64_t& wm)
+                                              uint64_t& vm, uint64_t& wm, uint32_t& ab)
 {
   MaxTrack mt{0, 0, 0, 0};
   WideMax mx{0.0, 0.0};
-  constexpr int E = (WT == 16 || WM == 16) ? 8 : 16;
+  constexpr int E = (WT == 16 || WM == 16 || GS == kGradF32) ? 8 : 16;   // fp32 gradients: two dwordx4 per lane, as in the plain update
   constexpr int kP = WIDE ? 1 : 4;                         // groups in flight (the wide path would set the kernel's register count)
   const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
-    MGroup<E, WT, WM> G[kP];
+    MGroup<E, WT, WM, GS> G[kP];
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group_mom(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps)
-      group_fast_mom<E, WT, WM, DECAY, K1ZERO, WIDE>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, mt, mx);
+      group_fast_mom<E, WT, WM, DECAY, K1ZERO, WIDE, GS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, mt, mx, ab);
   }
   for (; gi < ngroups; gi += kWave) {
-    MGroup<E, WT, WM> G;
+    MGroup<E, WT, WM, GS> G;
     const uint64_t e = off + (uint64_t)gi * E;
     load_group_mom(G, T, e);
-    group_fast_mom<E, WT, WM, DECAY, K1ZERO, WIDE>(p, G, T, e, mt, mx);
+    group_fast_mom<E, WT, WM, DECAY, K1ZERO, WIDE, GS>(p, G, T, e, mt, mx, ab);
   }
   int64_t a = mt.vmx, b = -(int64_t)mt.vmn;
   uint64_t x = (uint64_t)(a > b ? a : b);
@@ -183,24 +193,25 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
   wm = x > wm ? x : wm;
   fold_wide(mx, vm, wm);
   const uint32_t tail = cnt - ngroups * E;
-  if (tail) tile_generic_mom(p, T, off + (uint64_t)ngroups * E, tail, lane, vm, wm);
+  if (tail) tile_generic_mom<GS>(p, T, off + (uint64_t)ngroups * E, tail, lane, vm, wm, ab);
 }
 
-template <int WT, int WM>
+template <int WT, int WM, int GS>
 __device__ __forceinline__ void tile_fast_mom_dispatch(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
-                                                       uint64_t& vm, uint64_t& wm)
+                                                       uint64_t& vm, uint64_t& wm, uint32_t& ab)
 {
   if (p.wide) {
-    if (p.lrwd) tile_fast_mom<WT, WM, true, false, true>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false, true>(p, T, off, cnt, lane, vm, wm);
+    if (p.lrwd) tile_fast_mom<WT, WM, true, false, true, GS>(p, T, off, cnt, lane, vm, wm, ab); else tile_fast_mom<WT, WM, false, false, true, GS>(p, T, off, cnt, lane, vm, wm, ab);
     return;
   }
   const bool k1z = p.k1 == 0;
-  if (p.lrwd) { if (k1z) tile_fast_mom<WT, WM, true, true, false>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom<WT, WM, true, false, false>(p, T, off, cnt, lane, vm, wm); }
-  else        { if (k1z) tile_fast_mom<WT, WM, false, true, false>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom<WT, WM, false, false, false>(p, T, off, cnt, lane, vm, wm); }
+  if (p.lrwd) { if (k1z) tile_fast_mom<WT, WM, true, true, false, GS>(p, T, off, cnt, lane, vm, wm, ab);  else tile_fast_mom<WT, WM, true, false, false, GS>(p, T, off, cnt, lane, vm, wm, ab); }
+  else        { if (k1z) tile_fast_mom<WT, WM, false, true, false, GS>(p, T, off, cnt, lane, vm, wm, ab); else tile_fast_mom<WT, WM, false, false, false, GS>(p, T, off, cnt, lane, vm, wm, ab); }
 }
 
 // ---------------------------------------------------------------- per-tensor set-up
 
+template <int GS>
 __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int fl_in, int fl_out, int fl_m_in, int fl_m_out,
                                           int fl_g, uint32_t lr, uint32_t mu, uint32_t wd, uint32_t& status_bits)
 {
@@ -230,12 +241,15 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   p.w_p2d = pow2d(p.d); p.w_p2u = pow2d(p.u); p.w_inv_kth = pow2d(-p.kth); p.w_p2kth = pow2d(p.kth); p.w_inv_kc = pow2d(-p.kc);
   p.w_lo_t = (double)p.qmin_t; p.w_hi_t = (double)p.qmax_t; p.w_lo_c = (double)p.qmin_c; p.w_hi_c = (double)p.qmax_c;
   p.w_lo_m = (double)p.qmin_m; p.w_hi_m = (double)p.qmax_m;
+  p.gscale = __uint_as_float((uint32_t)(127 + fl_g) << 23);
+  p.glo = -(float)(1 << (p.wg - 1)); p.ghi = (float)((1 << (p.wg - 1)) - 1);
   p.path = 1; p.wide = 1;
 
   // Vector path: aligned, comp present and as wide as theta, int16 grads.  32-bit arithmetic on it when theta's
   // grid is fixed, d >= 1, and every intermediate (including each rounding addend) is provably below 2^31 in
   // magnitude; the wide arithmetic otherwise.
   if (!p.has_comp || !T.vec_mom || p.wt != p.wc || p.wg != 16) return;
+  if (GS == kGradF32 && (((uintptr_t)T.src) & 15u) != 0) return;
   p.path = 2;
   if (delta != 0 || p.d < 1) return;
   const int64_t lim = 1ll << 31;
@@ -279,6 +293,7 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
 
 // ---------------------------------------------------------------- the kernel
 
+template <int GS>
 __global__ void __launch_bounds__(kBlock)
 momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                      const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out,
@@ -295,7 +310,7 @@ momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restri
 
   int cur = -1;
   uint64_t vm = 0, wm = 0;
-  uint32_t status_bits = 0;
+  uint32_t status_bits = 0, ab_max = 0;
   MomParams p; p.path = 0;
   TensorDev T;
 
@@ -310,16 +325,17 @@ momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restri
       vm = wm = 0;
       cur = t;
       T = tensors[t];
-      setup_mom(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_g[t], lr, mu, wd, status_bits);
+      setup_mom<GS>(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_g[t], lr, mu, wd, status_bits);
     }
     if (p.path == 2) {
-      if (p.wt == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8>(p, T, off, cnt, lane, vm, wm);  else tile_fast_mom_dispatch<8, 16>(p, T, off, cnt, lane, vm, wm); }
-      else           { if (p.wm == 8) tile_fast_mom_dispatch<16, 8>(p, T, off, cnt, lane, vm, wm); else tile_fast_mom_dispatch<16, 16>(p, T, off, cnt, lane, vm, wm); }
+      if (p.wt == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+      else           { if (p.wm == 8) tile_fast_mom_dispatch<16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
     } else if (p.path == 1) {
-      tile_generic_mom(p, T, off, cnt, lane, vm, wm);
+      tile_generic_mom<GS>(p, T, off, cnt, lane, vm, wm, ab_max);
     }
   }
 
+  if (GS == kGradF32 && __ballot(ab_max >= 0x7f800000u)) status_bits |= kStatusNonFinite;
   if (status && status_bits && lane == 0) atomicOr(status, status_bits);
   if (vmax) flush_block(vmax, cur, vm, lane, wave, s_tensor, s_max);
   if (mmax) flush_block(mmax, cur, wm, lane, wave, s_tensor, s_max);
@@ -332,15 +348,20 @@ __global__ void __launch_bounds__(kBlock) fill2_u64_kernel(uint64_t* a, uint64_t
 }
 
 hipError_t launch_momentum_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                                const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
+                                int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                                 const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
                                 uint64_t* vmax, uint64_t* mmax, uint32_t* status, hipStream_t stream)
 {
   if (vmax || mmax)
     hipLaunchKernelGGL(fill2_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, mmax, n_tensors);
-  if (n_tiles)
-    hipLaunchKernelGGL(momentum_step_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                       fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr, mu, wd, vmax, mmax, status);
+  if (n_tiles) {
+    if (grad_is_f32)
+      hipLaunchKernelGGL(momentum_step_kernel<kGradF32>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                         fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr, mu, wd, vmax, mmax, status);
+    else
+      hipLaunchKernelGGL(momentum_step_kernel<kGradI16>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
+                         fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr, mu, wd, vmax, mmax, status);
+  }
   return hipGetLastError();
 }
 

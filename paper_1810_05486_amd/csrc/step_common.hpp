@@ -53,6 +53,21 @@ template <typename V> __device__ __forceinline__ void st_stream(V* p, V v)
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
+// Where an update kernel takes its gradients from: the int16 array, or the fp32 source quantized in registers.
+enum { kGradI16 = 0, kGradF32 = 1 };
+
+// One fp32 gradient onto the int16 grid exactly as the quantization kernel does it: x * 2^fl is exact in fp32,
+// v_rndne rounds half to even, the rails clamp, NaN becomes 0.  The result is an integer-valued float.  `ab_max`
+// collects the largest |bit pattern| seen (>= 0x7f800000 means a NaN or Inf went by).
+__device__ __forceinline__ float quant_f32(float x, float scale, float lo, float hi, uint32_t& ab_max)
+{
+  const uint32_t ab = __float_as_uint(x) & 0x7fffffffu;
+  ab_max = ab > ab_max ? ab : ab_max;
+  float y = __builtin_rintf(x * scale);
+  y = __builtin_fminf(__builtin_fmaxf(y, lo), hi);
+  return ab > 0x7f800000u ? 0.0f : y;
+}
+
 __device__ __forceinline__ int sx8(int w, int b)  { return (int)(int8_t)(w >> (8 * b)); }
 __device__ __forceinline__ int sx16(int w, int h) { return (int)(int16_t)(w >> (16 * h)); }
 

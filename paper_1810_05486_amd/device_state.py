@@ -137,6 +137,10 @@ class DeviceState:
         lpk.lpk_select_fraclen(L, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, self.fl_grad, self.fl_grad, self.status)
         lpk.lpk_quantize_tensor(L, lpk.LPK_SEL_GRAD, self.fl_grad, self.status)
 
+    def select_grads(self, k=0):
+        """fp32 gradients in source arena k -> per-tensor fraclen only (for the steps that quantize in registers)."""
+        lpk.lpk_select_fraclen(self.lists[k], lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, self.fl_grad, self.fl_grad, self.status)
+
     def update(self, lr_q16, wd_q16=0, k=0, want_vmax=True):
         """The fused lazy update; theta moves from grid fl_theta to fl_next."""
         lpk.lpk_kahan_sgd_step(self.lists[k], self.fl_theta, self.fl_next, self.fl_grad, lr_q16, wd_q16,
@@ -147,11 +151,13 @@ class DeviceState:
                                    self.fl_next, self.fl_spare, self.status)
             self.fl_theta, self.fl_next, self.fl_spare = self.fl_next, self.fl_spare, self.fl_theta
 
-    def update_momentum(self, lr_q16, mu_q16, wd_q16=0, k=0):
+    def update_momentum(self, lr_q16, mu_q16, wd_q16=0, k=0, fused=False):
         """Momentum update with the lazy update inside; the velocity moves from grid fl_mom to fl_mom_next, and
-        the grid after that is re-selected from this step's mmax (one-step lag), like theta's in `update`."""
+        the grid after that is re-selected from this step's mmax (one-step lag), like theta's in `update`.
+        fused: read the fp32 gradients directly instead of the int16 ones."""
         L = self.lists[k]
-        lpk.lpk_momentum_sgd_step(L, self.fl_theta, self.fl_next, self.fl_mom, self.fl_mom_next, self.fl_grad,
+        call = lpk.lpk_momentum_sgd_step_f32grad if fused else lpk.lpk_momentum_sgd_step
+        call(L, self.fl_theta, self.fl_next, self.fl_mom, self.fl_mom_next, self.fl_grad,
                                   lr_q16, mu_q16, wd_q16, self.vmax, self.mmax, self.status)
         if self.cfg.reselect:
             lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_THETA, self.vmax, self.fl_theta,
@@ -161,11 +167,13 @@ class DeviceState:
                                self.fl_mom_next, self.fl_mom_spare, self.status)
         self.fl_mom, self.fl_mom_next, self.fl_mom_spare = self.fl_mom_next, self.fl_mom_spare, self.fl_mom
 
-    def update_adam(self, hyper, k=0):
+    def update_adam(self, hyper, k=0, fused=False):
         """ADAM with the lazy update inside; both moments move to the grids chosen one step earlier, and the grids
-        after those are re-selected from this step's mmax / umax (one-step lag), like theta's in `update`."""
+        after those are re-selected from this step's mmax / umax (one-step lag), like theta's in `update`.
+        fused: read the fp32 gradients directly instead of the int16 ones."""
         L = self.lists[k]
-        lpk.lpk_adam_step(L, self.fl_theta, self.fl_next, self.fl_mom, self.fl_mom_next, self.fl_sec, self.fl_sec_next,
+        call = lpk.lpk_adam_step_f32grad if fused else lpk.lpk_adam_step
+        call(L, self.fl_theta, self.fl_next, self.fl_mom, self.fl_mom_next, self.fl_sec, self.fl_sec_next,
                           self.fl_grad, hyper, self.vmax, self.mmax, self.umax, self.status)
         if self.cfg.reselect:
             lpk.lpk_select_fraclen(L, lpk.LPK_VMAX_U64, lpk.LPK_SEL_THETA, self.vmax, self.fl_theta,

@@ -53,7 +53,7 @@ def compare(dev, host, what):
         assert np.array_equal(dev.sec[t].cpu().numpy(), host.sec[t]), (what, "sec", t)
 
 
-def run_config(cfg, steps, lr=1e-3, eps=1e-8, comp_bits=None, fl_mom0=24, fl_sec0=38, state_bits=16):
+def run_config(cfg, steps, lr=1e-3, eps=1e-8, comp_bits=None, fl_mom0=24, fl_sec0=38, state_bits=16, fused=False):
     from paper_1810_05486_amd.device_state import DeviceState
     bits = [state_bits] * cfg.n_tensors
     kw = dict(comp_bits=comp_bits, mom_bits=bits, sec_bits=bits, fl_mom0=fl_mom0, fl_sec0=fl_sec0)
@@ -67,8 +67,12 @@ def run_config(cfg, steps, lr=1e-3, eps=1e-8, comp_bits=None, fl_mom0=24, fl_sec
         grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
         dev.upload_src()
         hyper = workloads.adam_hyper(s, lr=lr, eps=eps)
-        dev.quantize_grads()
-        dev.update_adam(hyper)
+        if fused:                                          # fp32 gradients straight into the update, no int16 round trip
+            dev.select_grads()
+            dev.update_adam(hyper, fused=True)
+        else:
+            dev.quantize_grads()
+            dev.update_adam(hyper)
         host.quantize_grads(grads)
         host.update_adam(hyper)
         compare(dev, host, "config %d step %d" % (cfg.id, s))
@@ -214,3 +218,18 @@ def test_adam_argument_errors():
     lpk.lpk_adam_step(full, fl, fl, fl, fl, fl, fl, fl, good)       # the good call goes through
     torch.cuda.synchronize()
     full.destroy(); no_second.destroy()
+
+
+def test_adam_fused_fp32_gradient_step_equals_quantize_then_step():
+    """lpk_adam_step_f32grad against the oracle's quantize + ADAM step, on every kind of workload."""
+    say("fused adam: config 1")
+    run_config(workloads.config(1), range(30), fused=True)
+    say("fused adam: config 2 (int16 everything, grid moves)")
+    run_config(workloads.config(2), range(20), lr=2e-3, eps=1e-6, fused=True)
+    say("fused adam: config 4 (mixed widths)")
+    run_config(workloads.config(4), range(3), fl_mom0=36, fl_sec0=60, fused=True)
+    say("fused adam: config 5 reduced, ragged sizes; int8 theta with an int16 accumulator; 8-bit moments (element path)")
+    cfg = workloads.config(5, big_elems=(1 << 22) + 21, n_tiny=200)
+    run_config(cfg, range(4), fused=True)
+    run_config(cfg, range(3), comp_bits=[16] * cfg.n_tensors, fused=True)
+    run_config(workloads.config(5, big_elems=70001, n_tiny=20), range(3), state_bits=8, fl_mom0=16, fl_sec0=30, fused=True)

@@ -47,7 +47,7 @@ def compare(dev, host, what):
         assert np.array_equal(dev.mom[t].cpu().numpy(), host.mom[t]), (what, "mom", t)
 
 
-def run_config(cfg, mom_bits, steps, fl_mom0=16):
+def run_config(cfg, mom_bits, steps, fl_mom0=16, fused=False):
     from paper_1810_05486_amd.device_state import DeviceState
     dev = DeviceState(cfg, mom_bits=mom_bits, fl_mom0=fl_mom0)
     host = OracleState(cfg, mom_bits=mom_bits, fl_mom0=fl_mom0)
@@ -59,7 +59,11 @@ def run_config(cfg, mom_bits, steps, fl_mom0=16):
     for s in steps:
         grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
         dev.upload_src()
-        dev.step(s, mu_q16=MU_Q16)
+        if fused:                                          # fp32 gradients straight into the update, no int16 round trip
+            dev.select_grads()
+            dev.update_momentum(cfg.lr_q16(s), MU_Q16, cfg.wd_q16, fused=True)
+        else:
+            dev.step(s, mu_q16=MU_Q16)
         host.step(s, grads, mu_q16=MU_Q16)
         compare(dev, host, "config %d step %d" % (cfg.id, s))
     dev.close()
@@ -218,4 +222,51 @@ def test_momentum_runs_where_theta_moves_nowhere_somewhere_everywhere(tb, mb, st
             bad = int((dv.cpu().numpy() != hv).sum())
             assert bad == 0, (step, name, bad)
     assert 0 < moved < 5 * n // 2                           # some theta moved, most did not
+    tl.destroy()
+
+
+def test_momentum_fused_fp32_gradient_step_equals_quantize_then_step():
+    """lpk_momentum_sgd_step_f32grad against the oracle's quantize + momentum step, on every kind of workload."""
+    say("fused momentum: config 1, int8 velocity")
+    run_config(workloads.config(1), [8], range(40), fused=True)
+    say("fused momentum: config 2 (int16 everything, grid moves)")
+    cfg = workloads.config(2)
+    run_config(cfg, [16] * cfg.n_tensors, range(40), fused=True)
+    say("fused momentum: config 4 (mixed widths, decay, int16 velocity)")
+    cfg = workloads.config(4)
+    run_config(cfg, [16] * cfg.n_tensors, range(4), fused=True)
+    say("fused momentum: config 5 reduced, ragged sizes, int8 then int16 velocity")
+    cfg = workloads.config(5, big_elems=(1 << 22) + 37, n_tiny=300)
+    run_config(cfg, [8] * cfg.n_tensors, range(4), fused=True)
+    run_config(cfg, [16] * cfg.n_tensors, range(3), fused=True)
+
+
+def test_momentum_fused_step_flags_non_finite_gradients():
+    """NaN and +-Inf among the fp32 gradients: NaN quantizes to 0, Inf to the rails, the status word says so, and
+    every other element goes on as usual -- as in the two-call sequence."""
+    say("fused momentum: special gradient values")
+    rng = np.random.default_rng(77)
+    n = 3 * 4096 + 123
+    theta = rng.integers(-100, 100, size=n).astype(np.int8); comp = rng.integers(-100, 100, size=n).astype(np.int8)
+    mom = rng.integers(-3000, 3000, size=n).astype(np.int16)
+    src = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    src[[5, 4096 + 17, n - 1]] = [np.nan, np.inf, -np.inf]
+    fl_t, fl_m, fl_g = 7, 20, 18
+    d_theta, d_comp, d_mom, d_src = (torch.from_numpy(x).to(DEV) for x in (theta, comp, mom, src))
+    d_grad = torch.zeros(n, dtype=torch.int16, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(d_theta, d_comp, d_grad, d_src, momentum=d_mom)])
+    i32 = dict(dtype=torch.int32, device=DEV)
+    a_t, a_m, a_g = torch.tensor([fl_t], **i32), torch.tensor([fl_m], **i32), torch.tensor([fl_g], **i32)
+    vmax = torch.zeros(1, dtype=torch.int64, device=DEV); mmax = torch.zeros(1, dtype=torch.int64, device=DEV)
+    status = torch.zeros(1, **i32)
+    lpk.lpk_momentum_sgd_step_f32grad(tl, a_t, a_t, a_m, a_m, a_g, 6554, MU_Q16, 0, vmax, mmax, status)
+    torch.cuda.synchronize()
+    st = ref.new_status()
+    g = ref.quantize(src, 16, fl_g, st)
+    want_v, want_m = ref.momentum_sgd_step(theta, comp, mom, g, 7, fl_t, fl_t, fl_m, fl_m, fl_g, 6554, MU_Q16, 0, st)
+    assert int(status.item()) == int(st[0]) and int(st[0]) & 1
+    assert int(vmax.item()) == want_v and int(mmax.item()) == want_m
+    assert np.array_equal(d_theta.cpu().numpy(), theta) and np.array_equal(d_comp.cpu().numpy(), comp)
+    assert np.array_equal(d_mom.cpu().numpy(), mom)
+    assert not d_grad.any().item()                          # the int16 gradient buffer was not touched
     tl.destroy()
