@@ -291,7 +291,7 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
-        "storage": "int8/int16 dynamic fixed point (int64 arithmetic outside the 32-bit fast path)",
+        "storage": "int8/int16 dynamic fixed point (32-bit integer + FMA-rounded arithmetic on the fast path, exact fp64 arithmetic elsewhere)",
         "config": {"workload": "config %d: %s%s" % (cfg.id, cfg.name, ", momentum 0.9 with int%d velocity" % args.momentum_bits
                                                     if args.momentum_bits else "") + (", ADAM with int16 moments" if args.adam else "") + (", int%d accumulator" % args.comp_bits if args.comp_bits else ""),
                    "n_tensors": cfg.n_tensors,
