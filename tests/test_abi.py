@@ -116,6 +116,9 @@ int main(void)
   if (lpk_tensor_list_create(&d, 0u, &list) != LPK_ERR_INVALID_ARG || list) return 6;   /* rejected on the host */
   if (lpk_tensor_list_size(list) != 0u || lpk_tensor_list_destroy(list) != LPK_OK) return 7;
   if (lpk_adam_step(list, 0, 0, 0, 0, 0, 0, 0, &h, 0, 0, 0, 0, 0) != LPK_ERR_INVALID_ARG) return 8;
+  if (lpk_adam_step_f32grad(list, 0, 0, 0, 0, 0, 0, 0, &h, 0, 0, 0, 0, 0) != LPK_ERR_INVALID_ARG) return 9;
+  if (lpk_momentum_sgd_step_f32grad(list, 0, 0, 0, 0, 0, 655u, 58982u, 0u, 0, 0, 0, 0) != LPK_ERR_INVALID_ARG) return 10;
+  if (lpk_tensor_list_set_option(list, LPK_OPT_STORE_ALL, 1) != LPK_ERR_INVALID_ARG) return 11;
   puts("ok");
   return 0;
 }
