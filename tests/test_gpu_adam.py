@@ -111,11 +111,13 @@ def test_adam_config5_reduced_and_int8_moments():
     run_config(workloads.config(5, big_elems=70001, n_tiny=20), range(3), state_bits=8, fl_mom0=16, fl_sec0=30)
 
 
-def test_adam_config5_full_size_in_bench_launch_configuration():
-    """The 1 Gi + 10000 x 256 workload at full size, the lists and launch shape `bench.py --adam` times, every
-    output byte of two steps compared with the oracle (run on the host's threads)."""
-    say("adam: config 5 at FULL size, 2 steps")
-    run_config(workloads.config(5), range(2))
+@pytest.mark.parametrize("fused", [False, True])
+def test_adam_config5_full_size_in_bench_launch_configuration(fused):
+    """The 1 Gi + 10000 x 256 workload at full size, the lists and launch shape `bench.py --adam` times (its
+    int16-gradient step, then its fp32-gradient step), every output byte of two steps compared with the oracle (run
+    on the host's threads)."""
+    say("adam: config 5 at FULL size, 2 steps, fp32 gradients=%s" % fused)
+    run_config(workloads.config(5), range(2), fused=fused)
 
 
 @pytest.mark.parametrize("seed", fuzz_seeds(4))

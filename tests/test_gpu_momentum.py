@@ -100,12 +100,14 @@ def test_momentum_config5_reduced():
     run_config(cfg, [8] * cfg.n_tensors, range(5))
 
 
-def test_momentum_config5_full_size_in_bench_launch_configuration():
-    """The 1 Gi + 10000 x 256 workload at full size, the lists and launch shape `bench.py --momentum-bits 8` times,
-    every output byte of two steps compared with the oracle (run on the host's threads)."""
-    say("momentum: config 5 at FULL size, int8 velocity, 2 steps")
+@pytest.mark.parametrize("fused", [False, True])
+def test_momentum_config5_full_size_in_bench_launch_configuration(fused):
+    """The 1 Gi + 10000 x 256 workload at full size, the lists and launch shape `bench.py --momentum-bits 8` times
+    (its int16-gradient step, then its fp32-gradient step), every output byte of two steps compared with the oracle
+    (run on the host's threads)."""
+    say("momentum: config 5 at FULL size, int8 velocity, 2 steps, fp32 gradients=%s" % fused)
     cfg = workloads.config(5)
-    run_config(cfg, [8] * cfg.n_tensors, range(2))
+    run_config(cfg, [8] * cfg.n_tensors, range(2), fused=fused)
 
 
 @pytest.mark.parametrize("seed", fuzz_seeds(4))
