@@ -15,7 +15,8 @@
 //
 // Same work distribution as the plain update (persistent wavefronts over the tile table, non-temporal vector
 // accesses) for int16 moments and gradients on 16-byte aligned buffers; anything else goes element by element
-// through the same arithmetic.
+// through the same arithmetic.  Gradients come from the int16 array or, in a second kernel instance, from the
+// fp32 source, quantized in registers.
 #include "step_common.hpp"
 
 #ifndef LPK_ADAM_E

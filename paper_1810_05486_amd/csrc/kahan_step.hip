@@ -5,18 +5,22 @@
 // w, w + W, w + 2W, ... of the tile table, so at any moment the grid streams
 // one contiguous window of the parameter set.  A tile is 4096 elements of one
 // tensor; a lane handles 16 consecutive elements per pass (one dwordx4 of int8
-// theta, one of comp, two of int16 grad), four passes in flight together.
-// One workgroup of four waves per CU (one wave per SIMD): with the 2:1
-// read/write byte mix of this update, HBM delivers most when few, large
-// bursts are in flight; more resident waves only lengthen the DRAM queues.
+// theta, one of comp, two of int16 grad), several passes in flight together.
+//
+// Stores: a 16-byte group of theta or comp that the step left unchanged is not
+// written back (see "Lazy stores" below); a second kernel instance, for lists
+// with LPK_OPT_STORE_ALL, writes everything.  The host launches one workgroup
+// of four waves per CU for that dense read-modify-write stream (with its 2:1
+// read/write byte mix HBM delivers most when few, large bursts are in flight)
+// and two per CU for the read-mostly stream of the default instance.
 //
 // Gradient source: the int16 gradients written by the quantization kernel, or
-// (second kernel instance) the fp32 gradients themselves, quantized in
+// (further kernel instances) the fp32 gradients themselves, quantized in
 // registers exactly as the quantization kernel would -- the fused form saves
 // the int16 round trip through HBM.
 //
 // Arithmetic: three paths with identical results, chosen per tensor.
-//   * generic: 64-bit integers, any widths / shifts / grid move / decay /
+//   * wide: exact fp64, any widths / shifts / grid move / decay /
 //     no-accumulator mode inside the documented domain;
 //   * fast: 32-bit, when the shifts allow it.  The step
 //     RNE(-lr*g / 2^k) is ONE fp32 fused multiply-add: g and lr are exact in

@@ -6,9 +6,10 @@
 //
 // Same work distribution as the plain update (persistent wavefronts over the tile table, 16 or 8 consecutive
 // elements per lane per pass, non-temporal vector accesses).  Two bit-identical arithmetic paths chosen per
-// tensor: generic 64-bit, and a 32-bit one (same-width theta/comp, int16 grads, theta's grid fixed) whose
-// shifts are wave-uniform operands of branch-free integer roundings (the velocity grid may move); the decay
-// term is rounded by one fp64 FMA as in the plain update.
+// tensor: wide (exact fp64, anything inside the domain), and a 32-bit one (same-width theta/comp, 16-bit
+// gradients, theta's grid fixed) whose shifts are wave-uniform operands of branch-free integer roundings (the
+// velocity grid may move); the decay term is rounded by one fp64 FMA as in the plain update.  Gradients come
+// from the int16 array or, in a second kernel instance, from the fp32 source, quantized in registers.
 #include "step_common.hpp"
 
 namespace lpk {
