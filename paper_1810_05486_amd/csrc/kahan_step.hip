@@ -513,9 +513,16 @@ __device__ __forceinline__ uint64_t tile_fast_decay(const StepParams& p, const T
     return decay ? tile_fast_e<LPK_F32_E, (LAZY == kLazyNone ? LPK_F32_GROUPS : LPK_F32_GROUPS_LAZY), WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
                  : tile_fast_e<LPK_F32_E, (LAZY == kLazyNone ? LPK_F32_GROUPS : LPK_F32_GROUPS_LAZY), WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
 #if LPK_I16_E != 16
-  return decay ? tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
-               : tile_fast_e<LPK_I16_E, LPK_I16_GROUPS, WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
+  return decay ? tile_fast_e<LPK_I16_E, (LAZY == kLazyNone ? LPK_I16_GROUPS : LPK_I16_GROUPS_LAZY), WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
+               : tile_fast_e<LPK_I16_E, (LAZY == kLazyNone ? LPK_I16_GROUPS : LPK_I16_GROUPS_LAZY), WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
 #endif
+  // 8-bit theta and comp while both arrays' stores are tested (few groups change): 8 elements per lane, four groups
+  // in flight -- the same bytes in flight as 16 per lane with two groups, in narrower accesses, measured 3 % faster
+  // on that read-mostly stream with scattered writes (and 5 % slower once comp is written densely, which is why the
+  // other forms keep 16 per lane)
+  if constexpr (WC == 8 && LAZY == kLazyBoth)
+    return decay ? tile_fast_e<8, LPK_I8_GROUPS_BOTH, WT, WC, GS, true, MODE, LAZY>(p, T, off, cnt, lane, ab, lz)
+                 : tile_fast_e<8, LPK_I8_GROUPS_BOTH, WT, WC, GS, false, MODE, LAZY>(p, T, off, cnt, lane, ab, lz);
   // a 16-bit theta or comp: 8 elements per lane, so that every access of a wave is one contiguous run (with 16, a
   // lane's 16-bit data spans two stores 32 bytes apart and HBM sees partial-line writes)
   if constexpr (WC == 16)

@@ -31,6 +31,9 @@
 #ifndef LPK_I16_GROUPS_LAZY
 #define LPK_I16_GROUPS_LAZY 2
 #endif
+#ifndef LPK_I8_GROUPS_BOTH
+#define LPK_I8_GROUPS_BOTH 4    // groups of 8 elements in flight in the form that tests theta's and comp's stores (8-bit arrays)
+#endif
 #ifndef LPK_F32_GROUPS_LAZY
 #define LPK_F32_GROUPS_LAZY 2
 #endif

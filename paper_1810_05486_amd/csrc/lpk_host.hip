@@ -244,7 +244,8 @@ static int momentum_step(lpk_tensor_list* L, int grad_is_f32, const int32_t* fl_
   if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u || mu_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   if (!L->all_mom || (grad_is_f32 && !L->all_src)) return LPK_ERR_INVALID_ARG;
-  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_dense, grad_is_f32,
+  // fed from fp32 gradients the stream reads 7 bytes per 3 written and runs slightly faster with two workgroups per CU
+  hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, grad_is_f32 ? L->grid : L->grid_dense, grad_is_f32,
                                       fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16,
                                       vmax_out, mmax_out, status, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
