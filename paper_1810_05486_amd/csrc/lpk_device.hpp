@@ -31,11 +31,20 @@
 #ifndef LPK_I16_GROUPS_LAZY
 #define LPK_I16_GROUPS_LAZY 2
 #endif
+#ifndef LPK_I8_E_BOTH
+#define LPK_I8_E_BOTH 8       // int16 gradients, 8-bit arrays, form that tests theta's and comp's stores: elements per lane ...
+#endif
 #ifndef LPK_I8_GROUPS_BOTH
-#define LPK_I8_GROUPS_BOTH 4    // groups of 8 elements in flight in the form that tests theta's and comp's stores (8-bit arrays)
+#define LPK_I8_GROUPS_BOTH 4  // ... and groups in flight
 #endif
 #ifndef LPK_F32_GROUPS_LAZY
 #define LPK_F32_GROUPS_LAZY 2
+#endif
+#ifndef LPK_F32_E_BOTH
+#define LPK_F32_E_BOTH 4      // fp32 gradients, form that tests theta's and comp's stores: elements per lane ...
+#endif
+#ifndef LPK_F32_GROUPS_BOTH
+#define LPK_F32_GROUPS_BOTH 8 // ... and groups in flight
 #endif
 #ifndef LPK_W16_GROUPS_LAZY
 #define LPK_W16_GROUPS_LAZY 2
