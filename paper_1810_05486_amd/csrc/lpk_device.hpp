@@ -59,7 +59,7 @@
 #define LPK_Q_E 4             // consecutive elements per lane in the quantization kernel
 #endif
 #ifndef LPK_Q_GROUPS
-#define LPK_Q_GROUPS 4        // such groups in flight per lane
+#define LPK_Q_GROUPS 8        // such groups in flight per lane (with one workgroup per CU; measured best of 2-16 x 1-3)
 #endif
 #ifndef LPK_NT_LOAD
 #define LPK_NT_LOAD 1         // non-temporal hint on streaming loads
