@@ -187,7 +187,7 @@ __device__ __forceinline__ void update_small(const StepParams& p, int th, int c,
 
 // 16 consecutive elements of one lane.  WT / WC = widths of theta and comp; GS = gradient source.
 template <int WT, int WC, int GS> struct Group {
-  v4i th[WT / 8], c[WC / 8], g[GS == kGradF32 ? 4 : 2];
+  v4i th[WT / 8], c[WC / 8], g[GS == kGradF32 ? 4 : (GS == kGradI8 ? 1 : 2)];
 };
 
 template <int WT, int WC, int GS>
@@ -198,9 +198,11 @@ __device__ __forceinline__ void load_group(Group<WT, WC, GS>& G, const TensorDev
   if (GS == kGradF32) {
 #pragma unroll
     for (int j = 0; j < (GS == kGradF32 ? 4 : 2); ++j) G.g[j] = ld_stream((const v4i*)((const float*)T.src + e + 4 * j));
+  } else if (GS == kGradI8) {
+    G.g[0] = ld_stream((const v4i*)((const int8_t*)T.grad + e));
   } else {
     G.g[0] = ld_stream((const v4i*)((const int16_t*)T.grad + e));
-    G.g[1] = ld_stream((const v4i*)((const int16_t*)T.grad + e + 8));
+    G.g[GS == kGradI16 ? 1 : 0] = ld_stream((const v4i*)((const int16_t*)T.grad + e + 8));
   }
 }
 
@@ -233,7 +235,8 @@ __device__ __forceinline__ void compute_group(const StepParams& p, const WidePar
   for (int k = 0; k < 16; ++k) {
     float gf;
     if (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[(k >> 2) & (GS == kGradF32 ? 3 : 1)][k & 3]), tr.ab);
-    else                gf = (float)sx16(G.g[(k >> 3) & 1][(k >> 1) & 3], k & 1);
+    else if (GS == kGradI8) gf = (float)sx8(G.g[0][k >> 2], k & 3);
+    else                gf = (float)sx16(G.g[(k >> 3) & (GS == kGradI16 ? 1 : 0)][(k >> 1) & 3], k & 1);
     if (MODE == kModeSmall)     update_small<DECAY, (WC == 16)>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
     else if (MODE == kModeWide) update_wide<DECAY>(w, elem16<WT>(G.th, k), elem16<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
     else                        update_fast<DECAY>(p, elem16<WT>(G.th, k), elem16<WC>(G.c, k), gf, tn[k], cn[k], tr);
@@ -299,7 +302,7 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 {
   Track tr{0, 0, ab_max, 0.0, 0, 0};
   const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
-  constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : 8);     // VGPRs of one group
+  constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : (GS == kGradI8 ? 4 : 8));     // VGPRs of one group
   constexpr int kP = kRegs <= 16 ? (LAZY == kLazyNone ? LPK_I16_GROUPS : LPK_I16_GROUPS_LAZY) : LPK_KP_WIDE;   // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
   uint32_t gi = lane;
@@ -339,8 +342,8 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
 // wider gradient accesses for narrower theta/comp accesses.  This path is generic in E (4, 8 or 16).
 
 template <int E, int WT, int WC, int GS> struct GroupE {
-  static constexpr int kG = GS == kGradF32 ? E / 4 : (E >= 8 ? E / 8 : 1);      // gradient accesses
-  static constexpr int kGN = GS == kGradF32 ? 4 : (E >= 8 ? 4 : 2);            // dwords per gradient access
+  static constexpr int kG = GS == kGradF32 ? E / 4 : (GS == kGradI8 ? 1 : (E >= 8 ? E / 8 : 1));      // gradient accesses
+  static constexpr int kGN = GS == kGradF32 ? 4 : (GS == kGradI8 ? E / 4 : (E >= 8 ? 4 : 2));         // dwords per gradient access
   DW<E * WT / 32> th;
   DW<E * WC / 32> c;
   DW<kGN> g[kG];
@@ -354,8 +357,9 @@ __device__ __forceinline__ void load_group_e(GroupE<E, WT, WC, GS>& G, const Ten
   G.c  = ld_dw<E * WC / 32>((const int8_t*)T.comp + e * (WC / 8));
 #pragma unroll
   for (int j = 0; j < GT::kG; ++j) {
-    if constexpr (GS == kGradF32) G.g[j] = ld_dw<4>((const float*)T.src + e + 4 * j);
-    else                          G.g[j] = ld_dw<GT::kGN>((const int16_t*)T.grad + e + 8 * j);
+    if constexpr (GS == kGradF32)     G.g[j] = ld_dw<4>((const float*)T.src + e + 4 * j);
+    else if constexpr (GS == kGradI8) G.g[j] = ld_dw<GT::kGN>((const int8_t*)T.grad + e);
+    else                              G.g[j] = ld_dw<GT::kGN>((const int16_t*)T.grad + e + 8 * j);
   }
 }
 
@@ -369,6 +373,7 @@ __device__ __forceinline__ void compute_group_e(const StepParams& p, const WideP
   for (int k = 0; k < E; ++k) {
     float gf;
     if constexpr (GS == kGradF32) gf = quant_grad(p, __int_as_float(G.g[k >> 2].d[k & 3]), tr.ab);
+    else if constexpr (GS == kGradI8) gf = (float)sx8(G.g[0].d[k >> 2], k & 3);
     else                          gf = (float)sx16(G.g[k >> 3].d[(k >> 1) & 3], k & 1);
     if constexpr (MODE == kModeSmall)     update_small<DECAY, (WC == 16)>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), gf, tn[k], cn[k], tr);
     else if constexpr (MODE == kModeWide) update_wide<DECAY>(w, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), (double)gf, tn[k], cn[k], tr.vw);
@@ -463,7 +468,10 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   // is exact and |s| < 2^22), and every intermediate provably inside int32.
   const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
   const bool vec = T.vec_step && (GS == kGradI16 || (((uintptr_t)T.src) & 15u) == 0);
-  if (!p.has_comp || !vec || !widths_ok || p.wg != 16) return;
+  // gradients: 16 bits wide, or (int8 array, 8-bit theta and comp) 8 bits wide
+  // (from the fp32 source the width only sets the rails of the quantization)
+  const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (GS == kGradI16 && p.wg == 8 && p.wt == 8 && p.wc == 8);
+  if (!p.has_comp || !vec || !widths_ok || !grads_ok) return;
   p.path = 2;
   if (delta != 0 || p.d < 1 || p.kg < 1) return;
   if (p.kg < 9 && ((int64_t)lr << 15) >= (1ll << (22 + p.kg))) return;
@@ -593,7 +601,8 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+      if (p.wt == 8 && p.wc == 8) vm = (GS == kGradI16 && p.wg == 8) ? tile_vector<8, 8, (GS == kGradI16 ? kGradI8 : GS), STORE_ALL>(p, T, off, cnt, lane, ab_max, lz)
+                                                                     : tile_vector<8, 8, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
       else if (p.wt == 16)        vm = tile_vector<16, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
       else                        vm = tile_vector<8, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
     } else if (p.path == 1) {

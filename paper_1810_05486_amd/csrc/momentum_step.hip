@@ -124,10 +124,11 @@ __device__ __forceinline__ void update_fast_mom(const MomParams& p, int th, int 
 // access of a wave is still one contiguous run (with 16, a lane's 16-bit data would span two stores 32 bytes
 // apart, which reach HBM as partial lines).
 template <int E, int WT, int WM, int GS> struct MGroup {
-  static constexpr int kG = GS == kGradF32 ? E / 4 : E / 8;       // dwordx4 gradient accesses
+  static constexpr int kG = GS == kGradF32 ? E / 4 : (GS == kGradI8 ? 1 : E / 8);       // gradient accesses ...
+  static constexpr int kGN = GS == kGradI8 ? E / 4 : 4;                                  // ... of so many dwords
   DW<E * WT / 32> th, c;
   DW<E * WM / 32> m;
-  DW<4> g[kG];
+  DW<kGN> g[kG];
 };
 
 template <int E, int WT, int WM, int GS>
@@ -138,8 +139,9 @@ __device__ __forceinline__ void load_group_mom(MGroup<E, WT, WM, GS>& G, const T
   G.m  = ld_dw<E * WM / 32>((const int8_t*)T.mom + e * (WM / 8));
 #pragma unroll
   for (int j = 0; j < MGroup<E, WT, WM, GS>::kG; ++j) {
-    if constexpr (GS == kGradF32) G.g[j] = ld_dw<4>((const float*)T.src + e + 4 * j);
-    else                          G.g[j] = ld_dw<4>((const int16_t*)T.grad + e + 8 * j);
+    if constexpr (GS == kGradF32)     G.g[j] = ld_dw<4>((const float*)T.src + e + 4 * j);
+    else if constexpr (GS == kGradI8) G.g[j] = ld_dw<E / 4>((const int8_t*)T.grad + e);
+    else                              G.g[j] = ld_dw<4>((const int16_t*)T.grad + e + 8 * j);
   }
 }
 
@@ -152,8 +154,9 @@ __device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<
   for (int k = 0; k < E; ++k) {
     const int th = elem_dw<WT>(G.th, k), c = elem_dw<WT>(G.c, k), m = elem_dw<WM>(G.m, k);
     int g;
-    if constexpr (GS == kGradF32) g = (int)quant_f32(__int_as_float(G.g[k >> 2].d[k & 3]), p.gscale, p.glo, p.ghi, ab);
-    else                          g = elem_dw<16>(G.g[k >> 3], k & 7);
+    if constexpr (GS == kGradF32)     g = (int)quant_f32(__int_as_float(G.g[k >> 2].d[k & 3]), p.gscale, p.glo, p.ghi, ab);
+    else if constexpr (GS == kGradI8) g = elem_dw<8>(G.g[0], k);
+    else                              g = elem_dw<16>(G.g[k >> 3], k & 7);
     if (WIDE) update_wide_mom<DECAY>(p, th, c, m, g, tn[k], cn[k], mn[k], mx);
     else      update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, th, c, m, g, tn[k], cn[k], mn[k], mt);
   }
@@ -249,7 +252,10 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   // Vector path: aligned, comp present and as wide as theta, int16 grads.  32-bit arithmetic on it when theta's
   // grid is fixed, d >= 1, and every intermediate (including each rounding addend) is provably below 2^31 in
   // magnitude; the wide arithmetic otherwise.
-  if (!p.has_comp || !T.vec_mom || p.wt != p.wc || p.wg != 16) return;
+  // gradients: 16 bits wide; or 8 bits from the fp32 source (only the rails differ) or from an int8 array next to
+  // 8-bit theta, comp and velocity (the all-8-bit mode)
+  const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (GS == kGradI16 && p.wg == 8 && p.wt == 8 && p.wm == 8);
+  if (!p.has_comp || !T.vec_mom || p.wt != p.wc || !grads_ok) return;
   if (GS == kGradF32 && (((uintptr_t)T.src) & 15u) != 0) return;
   p.path = 2;
   if (delta != 0 || p.d < 1) return;
@@ -329,7 +335,8 @@ momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restri
       setup_mom<GS>(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_g[t], lr, mu, wd, status_bits);
     }
     if (p.path == 2) {
-      if (p.wt == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+      if (p.wt == 8) { if (p.wm == 8) { if (GS == kGradI16 && p.wg == 8) tile_fast_mom_dispatch<8, 8, (GS == kGradI16 ? kGradI8 : GS)>(p, T, off, cnt, lane, vm, wm, ab_max);
+                                        else tile_fast_mom_dispatch<8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); } else tile_fast_mom_dispatch<8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
       else           { if (p.wm == 8) tile_fast_mom_dispatch<16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
     } else if (p.path == 1) {
       tile_generic_mom<GS>(p, T, off, cnt, lane, vm, wm, ab_max);

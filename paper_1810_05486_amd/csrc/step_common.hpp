@@ -53,8 +53,9 @@ template <typename V> __device__ __forceinline__ void st_stream(V* p, V v)
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-// Where an update kernel takes its gradients from: the int16 array, or the fp32 source quantized in registers.
-enum { kGradI16 = 0, kGradF32 = 1 };
+// Where an update kernel takes its gradients from: the int16 array, the fp32 source quantized in registers, or an
+// int8 array (the all-8-bit mode of Section 4; vector path of the plain update with 8-bit theta and comp).
+enum { kGradI16 = 0, kGradF32 = 1, kGradI8 = 2 };
 
 // One fp32 gradient onto the int16 grid exactly as the quantization kernel does it: x * 2^fl is exact in fp32,
 // v_rndne rounds half to even, the rails clamp, NaN becomes 0.  The result is an integer-valued float.  `ab_max`

@@ -486,3 +486,51 @@ def test_lazy_stores_in_every_regime(tb, cb, store_all):
         assert bad_t == 0 and bad_c == 0, (step, bad_t, bad_c)
     assert len(np.unique(theta)) > 50 and int(np.abs(comp.astype(np.int64)).max()) > 0
     tl.destroy()
+
+
+@pytest.mark.parametrize("store_all", [0, 1])
+def test_all_int8_update_with_int8_gradients(store_all):
+    """The all-8-bit mode of Section 4 (int8 theta, int8 accumulator, int8 gradients) on the vector path: sparse and
+    dense steps, a weight-decay step and a step onto a finer grid (wide arithmetic), several tiles and a ragged tail,
+    every byte against the oracle."""
+    say("int8 theta + comp + gradients, store_all=%d" % store_all)
+    rng = np.random.default_rng(900 + store_all)
+    n = 37 * 4096 + 4090
+    theta = rng.integers(-100, 100, size=n).astype(np.int8)
+    comp = rng.integers(-50, 50, size=n).astype(np.int8)
+    d_theta = torch.from_numpy(theta).to(DEV); d_comp = torch.from_numpy(comp).to(DEV)
+    d_grad = torch.zeros(n, dtype=torch.int8, device=DEV); d_src = torch.zeros(n, dtype=torch.float32, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(d_theta, d_comp, d_grad, d_src)])
+    lpk.lpk_tensor_list_set_option(tl, lpk.LPK_OPT_STORE_ALL, store_all)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    vmax = torch.zeros(1, dtype=torch.int64, device=DEV); status = torch.zeros(1, **i32)
+    #        fl_in fl_out fl_g  lr     wd    gradients
+    plan = [(7,    7,     9,    655,   0,    "sparse"),
+            (7,    7,     4,    16384, 0,    "dense"),
+            (7,    7,     6,    6554,  7,    "dense"),
+            (7,    8,     6,    6554,  0,    "dense"),
+            (8,    8,     9,    655,   0,    "sparse")]
+    for step, (fl_in, fl_out, fl_g, lr_q, wd_q, kind) in enumerate(plan):
+        g = rng.integers(-128, 128, size=n).astype(np.int8)
+        if kind == "sparse":
+            g[rng.random(n) > 0.002] = 0
+        want_v = ref.kahan_sgd_step(theta, comp, g, 7, fl_in, fl_out, fl_g, lr_q, wd_q)
+        d_grad.copy_(torch.from_numpy(g))
+        lpk.lpk_kahan_sgd_step(tl, torch.tensor([fl_in], **i32), torch.tensor([fl_out], **i32), torch.tensor([fl_g], **i32),
+                               lr_q, wd_q, vmax, status)
+        torch.cuda.synchronize()
+        assert int(vmax.item()) == want_v and int(status.item()) == 0, step
+        bad_t = int((d_theta.cpu().numpy() != theta).sum()); bad_c = int((d_comp.cpu().numpy() != comp).sum())
+        assert bad_t == 0 and bad_c == 0, (step, bad_t, bad_c)
+    # the same mode fed from fp32 gradients: quantized to 8 bits in registers (values beyond the int8 rails saturate)
+    src = (rng.standard_normal(n) * 0.1).astype(np.float32)
+    st = ref.new_status()
+    g = ref.quantize(src, 8, 9, st)
+    want_v = ref.kahan_sgd_step(theta, comp, g, 7, 8, 8, 9, 6554, 0, st)
+    d_src.copy_(torch.from_numpy(src)); d_grad.zero_()
+    lpk.lpk_kahan_sgd_step_f32grad(tl, torch.tensor([8], **i32), torch.tensor([8], **i32), torch.tensor([9], **i32), 6554, 0, vmax, status)
+    torch.cuda.synchronize()
+    assert int(vmax.item()) == want_v and int(status.item()) == int(st[0]) == 0
+    assert int(g.min()) == -128 and int(g.max()) == 127 and not d_grad.any().item()
+    assert np.array_equal(d_theta.cpu().numpy(), theta) and np.array_equal(d_comp.cpu().numpy(), comp)
+    tl.destroy()

@@ -272,3 +272,51 @@ def test_momentum_fused_step_flags_non_finite_gradients():
     assert np.array_equal(d_mom.cpu().numpy(), mom)
     assert not d_grad.any().item()                          # the int16 gradient buffer was not touched
     tl.destroy()
+
+
+def test_momentum_all_int8_with_int8_gradients():
+    """The all-8-bit mode of Section 4 (int8 theta, accumulator, velocity and gradients) on the vector path: sparse and
+    dense steps, weight decay, a velocity grid move, several tiles and a ragged tail, every byte against the oracle;
+    then one step fed from fp32 gradients quantized to 8 bits in registers."""
+    say("momentum: int8 everything")
+    rng = np.random.default_rng(901)
+    n = 29 * 4096 + 4001
+    theta = rng.integers(-100, 100, size=n).astype(np.int8); comp = rng.integers(-50, 50, size=n).astype(np.int8)
+    mom = np.zeros(n, dtype=np.int8)
+    d_theta, d_comp, d_mom = (torch.from_numpy(x).to(DEV) for x in (theta, comp, mom))
+    d_grad = torch.zeros(n, dtype=torch.int8, device=DEV); d_src = torch.zeros(n, dtype=torch.float32, device=DEV)
+    tl = lpk.TensorList([lpk.make_desc(d_theta, d_comp, d_grad, d_src, momentum=d_mom)])
+    i32 = dict(dtype=torch.int32, device=DEV)
+    dev = lambda v: torch.tensor([v], **i32)
+    vmax = torch.zeros(1, dtype=torch.int64, device=DEV); mmax = torch.zeros(1, dtype=torch.int64, device=DEV)
+    status = torch.zeros(1, **i32)
+    #        fl_m_in fl_m_out fl_g lr     wd  gradients
+    plan = [(12,     12,      9,   655,   0,  "sparse"),
+            (12,     12,      9,   6554,  0,  "dense"),
+            (12,     11,      9,   6554,  7,  "dense"),
+            (11,     11,      9,   655,   0,  "sparse")]
+    for step, (fm_in, fm_out, fl_g, lr_q, wd_q, kind) in enumerate(plan):
+        g = rng.integers(-128, 128, size=n).astype(np.int8)
+        if kind == "sparse":
+            g[rng.random(n) > 0.002] = 0
+        want_v, want_m = ref.momentum_sgd_step(theta, comp, mom, g, 7, 7, 7, fm_in, fm_out, fl_g, lr_q, MU_Q16, wd_q)
+        d_grad.copy_(torch.from_numpy(g))
+        lpk.lpk_momentum_sgd_step(tl, dev(7), dev(7), dev(fm_in), dev(fm_out), dev(fl_g), lr_q, MU_Q16, wd_q, vmax, mmax, status)
+        torch.cuda.synchronize()
+        assert int(vmax.item()) == want_v and int(mmax.item()) == want_m and int(status.item()) == 0, step
+        for name, dv, hv in (("theta", d_theta, theta), ("comp", d_comp, comp), ("mom", d_mom, mom)):
+            bad = int((dv.cpu().numpy() != hv).sum())
+            assert bad == 0, (step, name, bad)
+    assert int(np.abs(mom.astype(int)).max()) > 20
+    src = (rng.standard_normal(n) * 0.1).astype(np.float32)
+    st = ref.new_status()
+    g = ref.quantize(src, 8, 9, st)
+    want_v, want_m = ref.momentum_sgd_step(theta, comp, mom, g, 7, 7, 7, 11, 11, 9, 6554, MU_Q16, 0, st)
+    d_src.copy_(torch.from_numpy(src)); d_grad.zero_()
+    lpk.lpk_momentum_sgd_step_f32grad(tl, dev(7), dev(7), dev(11), dev(11), dev(9), 6554, MU_Q16, 0, vmax, mmax, status)
+    torch.cuda.synchronize()
+    assert int(vmax.item()) == want_v and int(mmax.item()) == want_m and int(status.item()) == int(st[0]) == 0
+    assert int(g.min()) == -128 and int(g.max()) == 127 and not d_grad.any().item()
+    for dv, hv in ((d_theta, theta), (d_comp, comp), (d_mom, mom)):
+        assert np.array_equal(dv.cpu().numpy(), hv)
+    tl.destroy()
