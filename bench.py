@@ -32,7 +32,7 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def cpu_baseline(cfg, sample_elems, threads):
+def cpu_baseline(cfg, sample_elems, threads, gbits=16):
     """Time the oracle (as it stands) on the first `sample_elems` elements of tensor 0: one whole-path step
     (max-abs fraclen selection, quantization, lazy update), with `threads` host threads over contiguous
     element ranges (the selection scan stays on one thread, as the oracle has it)."""
@@ -47,8 +47,8 @@ def cpu_baseline(cfg, sample_elems, threads):
     theta = ref.quantize(theta0, bits, fl_t)
     comp = np.zeros(n, dtype=dt)
     t0 = time.perf_counter()
-    fl_g = ref.select_fraclen_f32(grad, 16, 15)
-    g = ref.quantize_mt(grad, 16, fl_g, threads=threads)
+    fl_g = ref.select_fraclen_f32(grad, gbits, gbits - 1)
+    g = ref.quantize_mt(grad, gbits, fl_g, threads=threads)
     ref.kahan_sgd_step_mt(theta, comp, g, bits - 1, fl_t, fl_t, fl_g, cfg.lr_q16(0), cfg.wd_q16, threads=threads)
     dt_s = time.perf_counter() - t0
     return {"value": n / dt_s / 1e9, "unit": "Gparam/s", "cores": threads, "kind": "oracle",
@@ -70,6 +70,8 @@ def main():
                     help="time the momentum variant of the update (velocity of this width, mu = 0.9) instead of plain SGD")
     ap.add_argument("--adam", action="store_true",
                     help="time the ADAM variant of the update (int16 first and second moments) instead of plain SGD")
+    ap.add_argument("--grad-bits", type=int, default=16, choices=[8, 16],
+                    help="width of the quantized gradients (8: the all-8-bit mode; not with --adam)")
     ap.add_argument("--comp-bits", type=int, default=0, choices=[0, 8, 16],
                     help="width of the accumulator when it differs from theta's (16 = the paper's 8+16 -> 22-bit example)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -104,7 +106,8 @@ def main():
     if args.adam:
         mom_bits = [16] * cfg.n_tensors
     sec_bits = [16] * cfg.n_tensors if args.adam else None
-    dev = DeviceState(cfg, n_src=n_src, mom_bits=mom_bits, comp_bits=comp_bits, sec_bits=sec_bits, fl_mom0=24, fl_sec0=38)
+    dev = DeviceState(cfg, n_src=n_src, mom_bits=mom_bits, comp_bits=comp_bits, sec_bits=sec_bits, fl_mom0=24, fl_sec0=38,
+                      grad_bits=args.grad_bits)
     views = dev.host_src_views()
 
     t0 = time.perf_counter()
@@ -262,14 +265,14 @@ def main():
         mix = {"bytes_read": 4 * nm, "bytes_written": 2 * nm, "ms": mms, "GB/s": 6 * nm / (mms * 1e-3) / 1e9}
         del a, b, c
 
-    upd_bytes = sum(n * (2 * (b // 8) + 2 * (cb // 8) + 2) for n, b, cb in zip(cfg.sizes, cfg.bits, dev.comp_bits))
+    upd_bytes = sum(n * (2 * (b // 8) + 2 * (cb // 8) + args.grad_bits // 8) for n, b, cb in zip(cfg.sizes, cfg.bits, dev.comp_bits))
     upd_bytes += 2 * (args.momentum_bits // 8) * cfg.n_params if args.momentum_bits else 0
     upd_bytes += 8 * cfg.n_params if args.adam else 0
     upd_kernel = "adam_step_kernel" if args.adam else ("momentum_step_kernel" if args.momentum_bits else "kahan_step_kernel")
     achieved = upd_bytes / (upd_ms * 1e-3) / 1e9
     traffic = traffic_all = None
     tpath = os.path.join(ROOT, "profiles", "traffic_config%d.json" % cfg.id)
-    if os.path.exists(tpath) and not args.lr_q16:
+    if os.path.exists(tpath) and not args.lr_q16 and args.grad_bits == 16 and not args.comp_bits:
         try:
             tj = json.load(open(tpath))
             traffic = tj.get(upd_kernel + "_bytes_per_launch")
@@ -293,7 +296,7 @@ def main():
         "dtype": "int32", "data": "synthetic",
         "storage": "int8/int16 dynamic fixed point (32-bit integer + FMA-rounded arithmetic on the fast path, exact fp64 arithmetic elsewhere)",
         "config": {"workload": "config %d: %s%s" % (cfg.id, cfg.name, ", momentum 0.9 with int%d velocity" % args.momentum_bits
-                                                    if args.momentum_bits else "") + (", ADAM with int16 moments" if args.adam else "") + (", int%d accumulator" % args.comp_bits if args.comp_bits else ""),
+                                                    if args.momentum_bits else "") + (", ADAM with int16 moments" if args.adam else "") + (", int%d accumulator" % args.comp_bits if args.comp_bits else "") + (", int8 gradients" if args.grad_bits == 8 else ""),
                    "n_tensors": cfg.n_tensors,
                    "n_params": cfg.n_params, "lr_q16": cfg.lr_q16(0), "wd_q16": cfg.wd_q16,
                    "grad_draws_cycled": n_src},
@@ -327,8 +330,8 @@ def main():
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
         cores = max(1, min(16, len(os.sched_getaffinity(0))))
-        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample, cores)
-        out["cpu_baseline_one_thread"] = cpu_baseline(cfg, args.cpu_sample // 4, 1)
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample, cores, args.grad_bits)
+        out["cpu_baseline_one_thread"] = cpu_baseline(cfg, args.cpu_sample // 4, 1, args.grad_bits)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)

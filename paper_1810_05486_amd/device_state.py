@@ -28,11 +28,12 @@ def _offsets(sizes, elem_bytes):
 
 class DeviceState:
     def __init__(self, cfg, device="cuda:0", kahan=True, n_src=1, comp_bits=None, mom_bits=None, fl_mom0=16,
-                 sec_bits=None, fl_sec0=40):
+                 sec_bits=None, fl_sec0=40, grad_bits=16):
         """cfg: workloads.Config.  n_src: how many fp32 source arenas stay resident (gradient cycle).
         comp_bits: per-tensor width of comp when it differs from theta's.  mom_bits: per-tensor width of a
         velocity tensor (momentum update; ADAM's first moment); its fraclen starts at fl_mom0 and is re-selected
-        every step.  sec_bits: per-tensor width of ADAM's second moment, fraclen from fl_sec0, re-selected too."""
+        every step.  sec_bits: per-tensor width of ADAM's second moment, fraclen from fl_sec0, re-selected too.
+        grad_bits: width of the quantized gradients (16, or 8 for the all-8-bit mode)."""
         self.cfg, self.device, self.kahan = cfg, torch.device(device), kahan
         nt = cfg.n_tensors
         tb = [b // 8 for b in cfg.bits]
@@ -44,7 +45,8 @@ class DeviceState:
 
         self.off_theta, tot_t = _offsets(cfg.sizes, tb)
         self.off_comp, tot_c = _offsets(cfg.sizes, cb)
-        self.off_grad, tot_g = _offsets(cfg.sizes, [2] * nt)
+        self.grad_bits = grad_bits
+        self.off_grad, tot_g = _offsets(cfg.sizes, [grad_bits // 8] * nt)
         self.off_src, tot_s = _offsets(cfg.sizes, [4] * nt)
         self.arena_theta = torch.zeros(tot_t, dtype=torch.uint8, device=dev)
         self.arena_comp = torch.zeros(tot_c, dtype=torch.uint8, device=dev) if kahan else None
@@ -69,7 +71,7 @@ class DeviceState:
         self.theta = [view(self.arena_theta, o, n, e, dt[e]) for o, n, e in zip(self.off_theta, cfg.sizes, tb)]
         self.comp = ([view(self.arena_comp, o, n, e, dt[e]) for o, n, e in zip(self.off_comp, cfg.sizes, cb)]
                      if kahan else [None] * nt)
-        self.grad = [view(self.arena_grad, o, n, 2, torch.int16) for o, n in zip(self.off_grad, cfg.sizes)]
+        self.grad = [view(self.arena_grad, o, n, grad_bits // 8, dt[grad_bits // 8]) for o, n in zip(self.off_grad, cfg.sizes)]
         self.src = [[view(a, o, n, 4, torch.float32) for o, n in zip(self.off_src, cfg.sizes)] for a in self.arena_src]
 
         self.mom = ([view(self.arena_mom, o, n, e, dt[e]) for o, n, e in zip(self.off_mom, cfg.sizes, mb)]
@@ -86,7 +88,7 @@ class DeviceState:
         self.fl_theta = torch.tensor([b - 1 for b in cfg.bits], **i32)   # grid theta is on now
         self.fl_next = self.fl_theta.clone()                               # grid the next step moves it to
         self.fl_spare = self.fl_theta.clone()
-        self.fl_grad = torch.full((nt,), 15, **i32)
+        self.fl_grad = torch.full((nt,), grad_bits - 1, **i32)
         self.fl_mom = torch.full((nt,), fl_mom0, **i32)                    # grid the velocity is on now
         self.fl_mom_next = self.fl_mom.clone()
         self.fl_mom_spare = self.fl_mom.clone()
