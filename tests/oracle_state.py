@@ -15,17 +15,18 @@ THREADS = max(1, min(16, len(os.sched_getaffinity(0))))
 
 
 class OracleState:
-    def __init__(self, cfg, kahan=True, comp_bits=None, mom_bits=None, fl_mom0=16, sec_bits=None, fl_sec0=40):
+    def __init__(self, cfg, kahan=True, comp_bits=None, mom_bits=None, fl_mom0=16, sec_bits=None, fl_sec0=40, grad_bits=16):
         self.cfg, self.kahan = cfg, kahan
         nt = cfg.n_tensors
         self.comp_bits = list(comp_bits) if comp_bits is not None else list(cfg.bits)
         self.theta = [np.zeros(n, dtype=DT[b]) for n, b in zip(cfg.sizes, cfg.bits)]
         self.comp = [np.zeros(n, dtype=DT[b]) if kahan else None for n, b in zip(cfg.sizes, self.comp_bits)]
-        self.grad = [np.zeros(n, dtype=np.int16) for n in cfg.sizes]
+        self.grad_bits = grad_bits
+        self.grad = [np.zeros(n, dtype=DT[grad_bits]) for n in cfg.sizes]
         self.d = [(b - 1) if kahan else 0 for b in self.comp_bits]
         self.fl_theta = [b - 1 for b in cfg.bits]
         self.fl_next = list(self.fl_theta)
-        self.fl_grad = [15] * nt
+        self.fl_grad = [grad_bits - 1] * nt
         self.vmax = [0] * nt
         self.status = ref.new_status()
         self.mom_bits = list(mom_bits) if mom_bits is not None else None
@@ -49,8 +50,8 @@ class OracleState:
 
     def quantize_grads(self, grads):
         for t, g in enumerate(grads):
-            self.fl_grad[t] = ref.select_fraclen_f32(g, 16, self.fl_grad[t], self.status)
-            ref.quantize_mt(g, 16, self.fl_grad[t], self.status, out=self.grad[t], threads=THREADS)
+            self.fl_grad[t] = ref.select_fraclen_f32(g, self.grad_bits, self.fl_grad[t], self.status)
+            ref.quantize_mt(g, self.grad_bits, self.fl_grad[t], self.status, out=self.grad[t], threads=THREADS)
 
     def update(self, lr_q16, wd_q16=0):
         new_next = list(self.fl_next)

@@ -42,10 +42,10 @@ def compare(dev, host, what, check_vmax=True):
             assert bad == 0, (what, "comp", t, bad)
 
 
-def run_config(cfg, step_ids, compare_every=1, kahan=True, always=(), comp_bits=None, fused=False):
+def run_config(cfg, step_ids, compare_every=1, kahan=True, always=(), comp_bits=None, fused=False, grad_bits=16):
     from paper_1810_05486_amd.device_state import DeviceState
-    dev = DeviceState(cfg, kahan=kahan, comp_bits=comp_bits)
-    host = OracleState(cfg, kahan=kahan, comp_bits=comp_bits)
+    dev = DeviceState(cfg, kahan=kahan, comp_bits=comp_bits, grad_bits=grad_bits)
+    host = OracleState(cfg, kahan=kahan, comp_bits=comp_bits, grad_bits=grad_bits)
     views = dev.host_src_views()
     theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
     dev.upload_src()
@@ -142,6 +142,20 @@ def test_int8_theta_with_int16_accumulator():
     cfg = workloads.config(5, big_elems=(1 << 22) + 5, n_tiny=100)
     run_config(cfg, range(4), comp_bits=[16] * cfg.n_tensors)
     run_config(cfg, range(4), comp_bits=[16] * cfg.n_tensors, fused=True)
+
+
+def test_all_8_bit_mode_whole_path():
+    """Section 4's INT8 training with the lazy update: int8 parameters, accumulators and gradients.  The whole path
+    (max-abs selection for an 8-bit grid, quantization to int8, update) on the single-tensor workload, the ResNet-18
+    shapes and the reduced stress shape, plain and fed from the fp32 gradients."""
+    say("all 8 bits: config 1, 60 steps")
+    run_config(workloads.config(1), range(60), grad_bits=8)
+    say("all 8 bits: config 3 (62 tensors, stepped learning rate)")
+    run_config(workloads.config(3), [0, 1, 2, 300, 600], grad_bits=8)
+    say("all 8 bits: config 5 reduced, plain and fused")
+    cfg = workloads.config(5, big_elems=(1 << 22) + 77, n_tiny=100)
+    run_config(cfg, range(4), grad_bits=8)
+    run_config(cfg, range(4), grad_bits=8, fused=True)
 
 
 def test_whole_step_replayed_from_a_hip_graph():
