@@ -468,9 +468,9 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   // is exact and |s| < 2^22), and every intermediate provably inside int32.
   const bool widths_ok = (p.wt == p.wc) || (p.wt == 8 && p.wc == 16);
   const bool vec = T.vec_step && (GS == kGradI16 || (((uintptr_t)T.src) & 15u) == 0);
-  // gradients: 16 bits wide, or (int8 array, 8-bit theta and comp) 8 bits wide
+  // gradients: 16 bits wide, or (int8 array next to an 8-bit theta) 8 bits wide
   // (from the fp32 source the width only sets the rails of the quantization)
-  const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (GS == kGradI16 && p.wg == 8 && p.wt == 8 && p.wc == 8);
+  const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (GS == kGradI16 && p.wg == 8 && p.wt == 8);
   if (!p.has_comp || !vec || !widths_ok || !grads_ok) return;
   p.path = 2;
   if (delta != 0 || p.d < 1 || p.kg < 1) return;
@@ -601,10 +601,14 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && p.wc == 8) vm = (GS == kGradI16 && p.wg == 8) ? tile_vector<8, 8, (GS == kGradI16 ? kGradI8 : GS), STORE_ALL>(p, T, off, cnt, lane, ab_max, lz)
-                                                                     : tile_vector<8, 8, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
-      else if (p.wt == 16)        vm = tile_vector<16, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
-      else                        vm = tile_vector<8, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+      if (p.wt == 8 && GS == kGradI16 && p.wg == 8) {       // int8 gradient array (8-bit training mode)
+        constexpr int G8 = GS == kGradI16 ? kGradI8 : GS;
+        if (p.wc == 8) vm = tile_vector<8, 8, G8, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+        else           vm = tile_vector<8, 16, G8, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+      }
+      else if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+      else if (p.wt == 16)             vm = tile_vector<16, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+      else                             vm = tile_vector<8, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
     } else if (p.path == 1) {
       vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
     }

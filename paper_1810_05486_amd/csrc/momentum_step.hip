@@ -253,8 +253,8 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   // grid is fixed, d >= 1, and every intermediate (including each rounding addend) is provably below 2^31 in
   // magnitude; the wide arithmetic otherwise.
   // gradients: 16 bits wide; or 8 bits from the fp32 source (only the rails differ) or from an int8 array next to
-  // 8-bit theta, comp and velocity (the all-8-bit mode)
-  const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (GS == kGradI16 && p.wg == 8 && p.wt == 8 && p.wm == 8);
+  // 8-bit theta and comp (the 8-bit training mode, with an 8- or 16-bit velocity)
+  const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (GS == kGradI16 && p.wg == 8 && p.wt == 8);
   if (!p.has_comp || !T.vec_mom || p.wt != p.wc || !grads_ok) return;
   if (GS == kGradF32 && (((uintptr_t)T.src) & 15u) != 0) return;
   p.path = 2;
@@ -335,8 +335,11 @@ momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restri
       setup_mom<GS>(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_g[t], lr, mu, wd, status_bits);
     }
     if (p.path == 2) {
-      if (p.wt == 8) { if (p.wm == 8) { if (GS == kGradI16 && p.wg == 8) tile_fast_mom_dispatch<8, 8, (GS == kGradI16 ? kGradI8 : GS)>(p, T, off, cnt, lane, vm, wm, ab_max);
-                                        else tile_fast_mom_dispatch<8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); } else tile_fast_mom_dispatch<8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+      if (p.wt == 8 && GS == kGradI16 && p.wg == 8) {
+        constexpr int G8 = GS == kGradI16 ? kGradI8 : GS;
+        if (p.wm == 8) tile_fast_mom_dispatch<8, 8, G8>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<8, 16, G8>(p, T, off, cnt, lane, vm, wm, ab_max);
+      }
+      else if (p.wt == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
       else           { if (p.wm == 8) tile_fast_mom_dispatch<16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
     } else if (p.path == 1) {
       tile_generic_mom<GS>(p, T, off, cnt, lane, vm, wm, ab_max);

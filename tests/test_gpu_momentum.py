@@ -274,15 +274,17 @@ def test_momentum_fused_step_flags_non_finite_gradients():
     tl.destroy()
 
 
-def test_momentum_all_int8_with_int8_gradients():
-    """The all-8-bit mode of Section 4 (int8 theta, accumulator, velocity and gradients) on the vector path: sparse and
-    dense steps, weight decay, a velocity grid move, several tiles and a ragged tail, every byte against the oracle;
-    then one step fed from fp32 gradients quantized to 8 bits in registers."""
-    say("momentum: int8 everything")
+@pytest.mark.parametrize("mb", [8, 16])
+def test_momentum_all_int8_with_int8_gradients(mb):
+    """The 8-bit training mode of Section 4 (int8 theta, accumulator and gradients, velocity int8 or int16) on the
+    vector path: sparse and dense steps, weight decay, a velocity grid move, several tiles and a ragged tail, every byte
+    against the oracle; then one step fed from fp32 gradients quantized to 8 bits in registers."""
+    say("momentum: int8 theta, accumulator and gradients, int%d velocity" % mb)
     rng = np.random.default_rng(901)
+    up = mb - 8                                            # a 16-bit velocity sits 8 bits finer
     n = 29 * 4096 + 4001
     theta = rng.integers(-100, 100, size=n).astype(np.int8); comp = rng.integers(-50, 50, size=n).astype(np.int8)
-    mom = np.zeros(n, dtype=np.int8)
+    mom = np.zeros(n, dtype=NP[mb])
     d_theta, d_comp, d_mom = (torch.from_numpy(x).to(DEV) for x in (theta, comp, mom))
     d_grad = torch.zeros(n, dtype=torch.int8, device=DEV); d_src = torch.zeros(n, dtype=torch.float32, device=DEV)
     tl = lpk.TensorList([lpk.make_desc(d_theta, d_comp, d_grad, d_src, momentum=d_mom)])
@@ -296,6 +298,7 @@ def test_momentum_all_int8_with_int8_gradients():
             (12,     11,      9,   6554,  7,  "dense"),
             (11,     11,      9,   655,   0,  "sparse")]
     for step, (fm_in, fm_out, fl_g, lr_q, wd_q, kind) in enumerate(plan):
+        fm_in, fm_out = fm_in + up, fm_out + up
         g = rng.integers(-128, 128, size=n).astype(np.int8)
         if kind == "sparse":
             g[rng.random(n) > 0.002] = 0
@@ -307,13 +310,13 @@ def test_momentum_all_int8_with_int8_gradients():
         for name, dv, hv in (("theta", d_theta, theta), ("comp", d_comp, comp), ("mom", d_mom, mom)):
             bad = int((dv.cpu().numpy() != hv).sum())
             assert bad == 0, (step, name, bad)
-    assert int(np.abs(mom.astype(int)).max()) > 20
+    assert int(np.abs(mom.astype(int)).max()) > 20 << up
     src = (rng.standard_normal(n) * 0.1).astype(np.float32)
     st = ref.new_status()
     g = ref.quantize(src, 8, 9, st)
-    want_v, want_m = ref.momentum_sgd_step(theta, comp, mom, g, 7, 7, 7, 11, 11, 9, 6554, MU_Q16, 0, st)
+    want_v, want_m = ref.momentum_sgd_step(theta, comp, mom, g, 7, 7, 7, 11 + up, 11 + up, 9, 6554, MU_Q16, 0, st)
     d_src.copy_(torch.from_numpy(src)); d_grad.zero_()
-    lpk.lpk_momentum_sgd_step_f32grad(tl, dev(7), dev(7), dev(11), dev(11), dev(9), 6554, MU_Q16, 0, vmax, mmax, status)
+    lpk.lpk_momentum_sgd_step_f32grad(tl, dev(7), dev(7), dev(11 + up), dev(11 + up), dev(9), 6554, MU_Q16, 0, vmax, mmax, status)
     torch.cuda.synchronize()
     assert int(vmax.item()) == want_v and int(mmax.item()) == want_m and int(status.item()) == int(st[0]) == 0
     assert int(g.min()) == -128 and int(g.max()) == 127 and not d_grad.any().item()

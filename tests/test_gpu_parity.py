@@ -156,6 +156,8 @@ def test_all_8_bit_mode_whole_path():
     cfg = workloads.config(5, big_elems=(1 << 22) + 77, n_tiny=100)
     run_config(cfg, range(4), grad_bits=8)
     run_config(cfg, range(4), grad_bits=8, fused=True)
+    say("8-bit parameters and gradients with a 16-bit accumulator")
+    run_config(cfg, range(3), grad_bits=8, comp_bits=[16] * cfg.n_tensors)
 
 
 def test_whole_step_replayed_from_a_hip_graph():
