@@ -71,11 +71,11 @@ typedef enum { LPK_SEL_GRAD = 0, LPK_SEL_THETA = 1, LPK_SEL_MOMENTUM = 2, LPK_SE
  * Element pointers must be aligned to their element size; when theta, comp,
  * grad (and src_f32, and the optimizer states) are all 16-byte aligned the
  * tensor takes the vector path (more than ten times faster than the
- * element-by-element one); the vector path covers comp as wide as theta or
- * int8 theta with an int16 comp, 16-bit gradients with any of these, int8
- * gradients (Section 4's 8-bit training) next to an int8 theta, and for ADAM
- * 16-bit moments and gradients.  Anything else is computed element by element,
- * with the same results.
+ * element-by-element one).  The vector path covers: comp as wide as theta, or
+ * (not in the momentum step) int8 theta with an int16 comp; 16-bit gradients
+ * with any of these; int8 gradients (Section 4's 8-bit training) next to an
+ * int8 theta; for ADAM 16-bit moments and gradients.  Anything else is
+ * computed element by element, with the same results.
  * Buffers of one tensor and of different tensors must not overlap. */
 typedef struct {
   void*       theta;       /* device; DFX ints, updated in place; destination of quantize(LPK_SEL_THETA) */
