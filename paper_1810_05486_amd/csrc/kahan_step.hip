@@ -437,7 +437,7 @@ __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const Tenso
 
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
 
-template <int GS>
+template <int GS, bool WITH_I8>
 __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, int fl_in, int fl_out, int fl_g,
                                              uint32_t lr, uint32_t wd, uint32_t& status_bits)
 {
@@ -470,7 +470,7 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   const bool vec = T.vec_step && (GS == kGradI16 || (((uintptr_t)T.src) & 15u) == 0);
   // gradients: 16 bits wide, or (int8 array next to an 8-bit theta) 8 bits wide
   // (from the fp32 source the width only sets the rails of the quantization)
-  const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (GS == kGradI16 && p.wg == 8 && p.wt == 8);
+  const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (WITH_I8 && GS == kGradI16 && p.wg == 8 && p.wt == 8);
   if (!p.has_comp || !vec || !widths_ok || !grads_ok) return;
   p.path = 2;
   if (delta != 0 || p.d < 1 || p.kg < 1) return;
@@ -568,7 +568,8 @@ __device__ __forceinline__ uint64_t tile_vector(const StepParams& p, const Tenso
 }
 
 // STORE_ALL: the instance for lists with LPK_OPT_STORE_ALL, which holds none of the store tests.
-template <int GS, bool STORE_ALL>
+// WITH_I8: the instance for lists that hold int8 gradient arrays (their vector path stays out of the others' code).
+template <int GS, bool STORE_ALL, bool WITH_I8>
 __global__ void __launch_bounds__(kBlock)
 kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                   const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out, const int32_t* __restrict__ fl_g,
@@ -597,11 +598,11 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
       lane_max = 0;
       cur = t;
       T = tensors[t];
-      setup_tensor<GS>(p, T, fl_in[t], fl_out[t], fl_g[t], lr, wd, status_bits);
+      setup_tensor<GS, WITH_I8>(p, T, fl_in[t], fl_out[t], fl_g[t], lr, wd, status_bits);
     }
     uint64_t vm = 0;
     if (p.path == 2) {
-      if (p.wt == 8 && GS == kGradI16 && p.wg == 8) {       // int8 gradient array (8-bit training mode)
+      if (WITH_I8 && p.wt == 8 && GS == kGradI16 && p.wg == 8) {       // int8 gradient array (8-bit training mode)
         constexpr int G8 = GS == kGradI16 ? kGradI8 : GS;
         if (p.wc == 8) vm = tile_vector<8, 8, G8, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
         else           vm = tile_vector<8, 16, G8, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
@@ -630,7 +631,8 @@ __global__ void __launch_bounds__(kBlock) fill_u64_kernel(uint64_t* p, uint32_t 
 
 hipError_t launch_kahan_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_g,
-                             uint32_t lr, uint32_t wd, uint32_t store_all, uint64_t* vmax, uint32_t* status, hipStream_t stream)
+                             uint32_t lr, uint32_t wd, uint32_t store_all, uint32_t with_i8, uint64_t* vmax, uint32_t* status,
+                             hipStream_t stream)
 {
   if (vmax) {
     hipLaunchKernelGGL(fill_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, n_tensors, 0ull);
@@ -639,8 +641,9 @@ hipError_t launch_kahan_step(const TensorDev* tensors, const Tile* tiles, uint32
     auto go = [&](auto kernel) {
       hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles, fl_in, fl_out, fl_g, lr, wd, vmax, status);
     };
-    if (grad_is_f32) { if (store_all) go(kahan_step_kernel<kGradF32, true>); else go(kahan_step_kernel<kGradF32, false>); }
-    else             { if (store_all) go(kahan_step_kernel<kGradI16, true>); else go(kahan_step_kernel<kGradI16, false>); }
+    if (grad_is_f32)  { if (store_all) go(kahan_step_kernel<kGradF32, true, false>); else go(kahan_step_kernel<kGradF32, false, false>); }
+    else if (with_i8) { if (store_all) go(kahan_step_kernel<kGradI16, true, true>);  else go(kahan_step_kernel<kGradI16, false, true>); }
+    else              { if (store_all) go(kahan_step_kernel<kGradI16, true, false>); else go(kahan_step_kernel<kGradI16, false, false>); }
   }
   return hipGetLastError();
 }

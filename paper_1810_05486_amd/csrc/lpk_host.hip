@@ -10,7 +10,7 @@
 namespace lpk {
 hipError_t launch_kahan_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int grad_is_f32, const int32_t*, const int32_t*, const int32_t*, uint32_t lr, uint32_t wd,
-                             uint32_t store_all, uint64_t* vmax, uint32_t* status, hipStream_t);
+                             uint32_t store_all, uint32_t with_i8, uint64_t* vmax, uint32_t* status, hipStream_t);
 hipError_t launch_select_f32(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int sel, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
                              uint32_t* status, hipStream_t);
@@ -46,6 +46,7 @@ struct lpk_tensor_list {
   bool       all_mom   = false;    // every non-empty tensor has a velocity buffer
   bool       all_sec   = false;    // ... and a second-moment buffer
   bool       store_all = false;    // LPK_OPT_STORE_ALL: write every result, changed or not
+  bool       any_grad_i8 = false;  // some tensor has an int8 gradient array
   TensorDev* d_tensors = nullptr;
   Tile*      d_tiles   = nullptr;
   uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls
@@ -72,7 +73,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
 
   std::vector<TensorDev> tensors(n_tensors);
   std::vector<Tile> tiles;
-  bool all_src = true, all_mom = true, all_sec = true;
+  bool all_src = true, all_mom = true, all_sec = true, any_grad_i8 = false;
   uint64_t total_tiles = 0;
   for (uint32_t t = 0; t < n_tensors; ++t) {
     const lpk_tensor_desc& D = descs[t];
@@ -88,6 +89,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     if (!aligned(D.theta, wt / 8) || !aligned(D.grad, wg / 8) || (D.comp && !aligned(D.comp, wc / 8)) ||
         !aligned(D.src_f32, 4)) return LPK_ERR_INVALID_ARG;
     if (D.n && !D.src_f32) all_src = false;
+    if (D.n && wg == 8) any_grad_i8 = true;
     const int wm = D.momentum ? dtype_bits(D.momentum_dtype) : 0;
     if (D.momentum && (!wm || !aligned(D.momentum, wm / 8))) return LPK_ERR_INVALID_ARG;
     if (D.n && !D.momentum) all_mom = false;
@@ -123,6 +125,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   L->all_src = all_src;
   L->all_mom = all_mom;
   L->all_sec = all_sec;
+  L->any_grad_i8 = any_grad_i8;
 
   hipDeviceProp_t prop;
   bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
@@ -225,7 +228,8 @@ int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int
   if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->store_all ? L->grid_dense : L->grid_step, 0, fl_theta_in, fl_theta_out,
-                                   fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, vmax_out, status, static_cast<hipStream_t>(stream));
+                                   fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, L->any_grad_i8 ? 1u : 0u, vmax_out, status,
+                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
@@ -237,7 +241,8 @@ int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, c
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
   if (!L->all_src) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->store_all ? L->grid_dense : L->grid_step, 1, fl_theta_in, fl_theta_out,
-                                   fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, vmax_out, status, static_cast<hipStream_t>(stream));
+                                   fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, L->any_grad_i8 ? 1u : 0u, vmax_out, status,
+                                   static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
