@@ -227,6 +227,18 @@ def main():
         gwall = time.perf_counter() - t2
         graph = {"ms_per_step": gwall * 1e3 / K, "value": cfg.n_params / (gwall / K) / 1e9, "unit": "Gparam/s"}
         del graphs
+        graphs = [dev.capture_step(args.warmup, k, fused=True) for k in range(n_src)]
+        for k in range(n_src):
+            graphs[k].replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for i in range(K):
+            graphs[i % n_src].replay()
+        torch.cuda.synchronize()
+        gwall = time.perf_counter() - t2
+        graph["fused_ms_per_step"] = gwall * 1e3 / K
+        graph["fused_value"] = cfg.n_params / (gwall / K) / 1e9
+        del graphs
 
     sel_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / K
     qnt_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / K

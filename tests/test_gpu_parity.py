@@ -160,12 +160,14 @@ def test_all_8_bit_mode_whole_path():
     run_config(cfg, range(3), grad_bits=8, comp_bits=[16] * cfg.n_tensors)
 
 
-def test_whole_step_replayed_from_a_hip_graph():
-    """The three hot calls only enqueue kernels, so a whole step can be recorded once and replayed: every replay
-    (fresh gradients uploaded eagerly in between, a synchronization and a download after each) matches the oracle."""
+@pytest.mark.parametrize("fused", [False, True])
+def test_whole_step_replayed_from_a_hip_graph(fused):
+    """The hot calls only enqueue kernels, so a whole step (three calls, or two with the quantization fused into the
+    update) can be recorded once and replayed: every replay (fresh gradients uploaded eagerly in between, a
+    synchronization and a download after each) matches the oracle."""
     from paper_1810_05486_amd.device_state import DeviceState
     for cfg in (workloads.config(1), workloads.config(3), workloads.config(5, big_elems=(1 << 21) + 77, n_tiny=64)):
-        say("hip graph replay: config %d" % cfg.id)
+        say("hip graph replay: config %d, fused=%s" % (cfg.id, fused))
         dev, host = DeviceState(cfg), OracleState(cfg)
         views = dev.host_src_views()
         theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
@@ -174,7 +176,7 @@ def test_whole_step_replayed_from_a_hip_graph():
         host.init_theta(theta0)
         grads = [cfg.grad(t, 0, out=views[t]) for t in range(cfg.n_tensors)]
         dev.upload_src()
-        graph = dev.capture_step(0)                 # runs step 0 eagerly once, then records it (recording executes nothing)
+        graph = dev.capture_step(0, fused=fused)    # runs step 0 eagerly once, then records it (recording executes nothing)
         host.step(0, grads)
         compare(dev, host, "config %d eager step before the replays" % cfg.id)
         for s in range(1, 7):
