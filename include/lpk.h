@@ -72,7 +72,7 @@ typedef enum { LPK_SEL_GRAD = 0, LPK_SEL_THETA = 1, LPK_SEL_MOMENTUM = 2, LPK_SE
  * grad (and src_f32, and the optimizer states) are all 16-byte aligned the
  * tensor takes the vector path (more than ten times faster than the
  * element-by-element one).  The vector path covers: comp as wide as theta, or
- * (not in the momentum step) int8 theta with an int16 comp; 16-bit gradients
+ * int8 theta with an int16 comp; 16-bit gradients
  * with any of these; int8 gradients (Section 4's 8-bit training) next to an
  * int8 theta; for ADAM 16-bit moments and gradients.  Anything else is
  * computed element by element, with the same results.

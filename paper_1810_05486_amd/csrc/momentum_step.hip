@@ -119,40 +119,42 @@ __device__ __forceinline__ void update_fast_mom(const MomParams& p, int th, int 
   cn = min(max(r, p.qmin_c), p.qmax_c);
 }
 
-// E consecutive elements per lane.  WT = width of theta and comp, WM = width of the velocity; grads int16.
+// E consecutive elements per lane.  WT / WC / WM = widths of theta, comp (WT, or 16 next to an 8-bit theta) and the
+// velocity.
 // E = 16 when all three are 8 bits wide (dwordx4 each), E = 8 as soon as one of them is 16 bits wide: then every
 // access of a wave is still one contiguous run (with 16, a lane's 16-bit data would span two stores 32 bytes
 // apart, which reach HBM as partial lines).
-template <int E, int WT, int WM, int GS> struct MGroup {
+template <int E, int WT, int WC, int WM, int GS> struct MGroup {
   static constexpr int kG = GS == kGradF32 ? E / 4 : (GS == kGradI8 ? 1 : E / 8);       // gradient accesses ...
   static constexpr int kGN = GS == kGradI8 ? E / 4 : 4;                                  // ... of so many dwords
-  DW<E * WT / 32> th, c;
+  DW<E * WT / 32> th;
+  DW<E * WC / 32> c;
   DW<E * WM / 32> m;
   DW<kGN> g[kG];
 };
 
-template <int E, int WT, int WM, int GS>
-__device__ __forceinline__ void load_group_mom(MGroup<E, WT, WM, GS>& G, const TensorDev& T, uint64_t e)
+template <int E, int WT, int WC, int WM, int GS>
+__device__ __forceinline__ void load_group_mom(MGroup<E, WT, WC, WM, GS>& G, const TensorDev& T, uint64_t e)
 {
   G.th = ld_dw<E * WT / 32>((const int8_t*)T.theta + e * (WT / 8));
-  G.c  = ld_dw<E * WT / 32>((const int8_t*)T.comp + e * (WT / 8));
+  G.c  = ld_dw<E * WC / 32>((const int8_t*)T.comp + e * (WC / 8));
   G.m  = ld_dw<E * WM / 32>((const int8_t*)T.mom + e * (WM / 8));
 #pragma unroll
-  for (int j = 0; j < MGroup<E, WT, WM, GS>::kG; ++j) {
+  for (int j = 0; j < MGroup<E, WT, WC, WM, GS>::kG; ++j) {
     if constexpr (GS == kGradF32)     G.g[j] = ld_dw<4>((const float*)T.src + e + 4 * j);
     else if constexpr (GS == kGradI8) G.g[j] = ld_dw<E / 4>((const int8_t*)T.grad + e);
     else                              G.g[j] = ld_dw<4>((const int16_t*)T.grad + e + 8 * j);
   }
 }
 
-template <int E, int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE, int GS>
-__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<E, WT, WM, GS>& G, const TensorDev& T, uint64_t e, MaxTrack& mt, WideMax& mx,
+template <int E, int WT, int WC, int WM, bool DECAY, bool K1ZERO, bool WIDE, int GS>
+__device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<E, WT, WC, WM, GS>& G, const TensorDev& T, uint64_t e, MaxTrack& mt, WideMax& mx,
                                                uint32_t& ab)
 {
   int tn[E], cn[E], mn[E];
 #pragma unroll
   for (int k = 0; k < E; ++k) {
-    const int th = elem_dw<WT>(G.th, k), c = elem_dw<WT>(G.c, k), m = elem_dw<WM>(G.m, k);
+    const int th = elem_dw<WT>(G.th, k), c = elem_dw<WC>(G.c, k), m = elem_dw<WM>(G.m, k);
     int g;
     if constexpr (GS == kGradF32)     g = (int)quant_f32(__int_as_float(G.g[k >> 2].d[k & 3]), p.gscale, p.glo, p.ghi, ab);
     else if constexpr (GS == kGradI8) g = elem_dw<8>(G.g[0], k);
@@ -161,33 +163,33 @@ __device__ __forceinline__ void group_fast_mom(const MomParams& p, const MGroup<
     else      update_fast_mom<DECAY, K1ZERO, (WM == 16)>(p, th, c, m, g, tn[k], cn[k], mn[k], mt);
   }
   st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
-  st_dw((int8_t*)T.comp + e * (WT / 8), pack_dw<WT, E>(cn));
+  st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
   st_dw((int8_t*)T.mom + e * (WM / 8), pack_dw<WM, E>(mn));
 }
 
-template <int WT, int WM, bool DECAY, bool K1ZERO, bool WIDE, int GS>
+template <int WT, int WC, int WM, bool DECAY, bool K1ZERO, bool WIDE, int GS>
 __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                               uint64_t& vm, uint64_t& wm, uint32_t& ab)
 {
   MaxTrack mt{0, 0, 0, 0};
   WideMax mx{0.0, 0.0};
-  constexpr int E = (WT == 16 || WM == 16 || GS == kGradF32) ? 8 : 16;   // fp32 gradients: two dwordx4 per lane, as in the plain update
+  constexpr int E = (WT == 16 || WC == 16 || WM == 16 || GS == kGradF32) ? 8 : 16;   // fp32 gradients: two dwordx4 per lane, as in the plain update
   constexpr int kP = WIDE ? 1 : 4;                         // groups in flight (the wide path would set the kernel's register count)
   const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;
   for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
-    MGroup<E, WT, WM, GS> G[kP];
+    MGroup<E, WT, WC, WM, GS> G[kP];
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps) load_group_mom(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
 #pragma unroll
     for (int ps = 0; ps < kP; ++ps)
-      group_fast_mom<E, WT, WM, DECAY, K1ZERO, WIDE, GS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, mt, mx, ab);
+      group_fast_mom<E, WT, WC, WM, DECAY, K1ZERO, WIDE, GS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, mt, mx, ab);
   }
   for (; gi < ngroups; gi += kWave) {
-    MGroup<E, WT, WM, GS> G;
+    MGroup<E, WT, WC, WM, GS> G;
     const uint64_t e = off + (uint64_t)gi * E;
     load_group_mom(G, T, e);
-    group_fast_mom<E, WT, WM, DECAY, K1ZERO, WIDE, GS>(p, G, T, e, mt, mx, ab);
+    group_fast_mom<E, WT, WC, WM, DECAY, K1ZERO, WIDE, GS>(p, G, T, e, mt, mx, ab);
   }
   int64_t a = mt.vmx, b = -(int64_t)mt.vmn;
   uint64_t x = (uint64_t)(a > b ? a : b);
@@ -200,17 +202,17 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
   if (tail) tile_generic_mom<GS>(p, T, off + (uint64_t)ngroups * E, tail, lane, vm, wm, ab);
 }
 
-template <int WT, int WM, int GS>
+template <int WT, int WC, int WM, int GS>
 __device__ __forceinline__ void tile_fast_mom_dispatch(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                                        uint64_t& vm, uint64_t& wm, uint32_t& ab)
 {
   if (p.wide) {
-    if (p.lrwd) tile_fast_mom<WT, WM, true, false, true, GS>(p, T, off, cnt, lane, vm, wm, ab); else tile_fast_mom<WT, WM, false, false, true, GS>(p, T, off, cnt, lane, vm, wm, ab);
+    if (p.lrwd) tile_fast_mom<WT, WC, WM, true, false, true, GS>(p, T, off, cnt, lane, vm, wm, ab); else tile_fast_mom<WT, WC, WM, false, false, true, GS>(p, T, off, cnt, lane, vm, wm, ab);
     return;
   }
   const bool k1z = p.k1 == 0;
-  if (p.lrwd) { if (k1z) tile_fast_mom<WT, WM, true, true, false, GS>(p, T, off, cnt, lane, vm, wm, ab);  else tile_fast_mom<WT, WM, true, false, false, GS>(p, T, off, cnt, lane, vm, wm, ab); }
-  else        { if (k1z) tile_fast_mom<WT, WM, false, true, false, GS>(p, T, off, cnt, lane, vm, wm, ab); else tile_fast_mom<WT, WM, false, false, false, GS>(p, T, off, cnt, lane, vm, wm, ab); }
+  if (p.lrwd) { if (k1z) tile_fast_mom<WT, WC, WM, true, true, false, GS>(p, T, off, cnt, lane, vm, wm, ab);  else tile_fast_mom<WT, WC, WM, true, false, false, GS>(p, T, off, cnt, lane, vm, wm, ab); }
+  else        { if (k1z) tile_fast_mom<WT, WC, WM, false, true, false, GS>(p, T, off, cnt, lane, vm, wm, ab); else tile_fast_mom<WT, WC, WM, false, false, false, GS>(p, T, off, cnt, lane, vm, wm, ab); }
 }
 
 // ---------------------------------------------------------------- per-tensor set-up
@@ -249,13 +251,14 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   p.glo = -(float)(1 << (p.wg - 1)); p.ghi = (float)((1 << (p.wg - 1)) - 1);
   p.path = 1; p.wide = 1;
 
-  // Vector path: aligned, comp present and as wide as theta, int16 grads.  32-bit arithmetic on it when theta's
+  // Vector path: aligned, comp present and as wide as theta (or int8 theta with an int16 comp), 16-bit grads.  32-bit arithmetic on it when theta's
   // grid is fixed, d >= 1, and every intermediate (including each rounding addend) is provably below 2^31 in
   // magnitude; the wide arithmetic otherwise.
   // gradients: 16 bits wide; or 8 bits from the fp32 source (only the rails differ) or from an int8 array next to
   // 8-bit theta and comp (the 8-bit training mode, with an 8- or 16-bit velocity)
   const bool grads_ok = p.wg == 16 || (GS == kGradF32 && p.wg == 8) || (GS == kGradI16 && p.wg == 8 && p.wt == 8);
-  if (!p.has_comp || !T.vec_mom || p.wt != p.wc || !grads_ok) return;
+  const bool widths_ok = p.wt == p.wc || (p.wt == 8 && p.wc == 16);
+  if (!p.has_comp || !T.vec_mom || !widths_ok || !grads_ok) return;
   if (GS == kGradF32 && (((uintptr_t)T.src) & 15u) != 0) return;
   p.path = 2;
   if (delta != 0 || p.d < 1) return;
@@ -335,12 +338,14 @@ momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restri
       setup_mom<GS>(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_g[t], lr, mu, wd, status_bits);
     }
     if (p.path == 2) {
-      if (p.wt == 8 && GS == kGradI16 && p.wg == 8) {
+      if (p.wt == 8 && GS == kGradI16 && p.wg == 8) {       // int8 gradient array (8-bit training mode)
         constexpr int G8 = GS == kGradI16 ? kGradI8 : GS;
-        if (p.wm == 8) tile_fast_mom_dispatch<8, 8, G8>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<8, 16, G8>(p, T, off, cnt, lane, vm, wm, ab_max);
+        if (p.wc == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, 8, G8>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 8, 16, G8>(p, T, off, cnt, lane, vm, wm, ab_max); }
+        else           { if (p.wm == 8) tile_fast_mom_dispatch<8, 16, 8, G8>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<8, 16, 16, G8>(p, T, off, cnt, lane, vm, wm, ab_max); }
       }
-      else if (p.wt == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
-      else           { if (p.wm == 8) tile_fast_mom_dispatch<16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+      else if (p.wt == 8 && p.wc == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+      else if (p.wt == 8)              { if (p.wm == 8) tile_fast_mom_dispatch<8, 16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<8, 16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+      else                             { if (p.wm == 8) tile_fast_mom_dispatch<16, 16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<16, 16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
     } else if (p.path == 1) {
       tile_generic_mom<GS>(p, T, off, cnt, lane, vm, wm, ab_max);
     }

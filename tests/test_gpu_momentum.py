@@ -47,10 +47,10 @@ def compare(dev, host, what):
         assert np.array_equal(dev.mom[t].cpu().numpy(), host.mom[t]), (what, "mom", t)
 
 
-def run_config(cfg, mom_bits, steps, fl_mom0=16, fused=False):
+def run_config(cfg, mom_bits, steps, fl_mom0=16, fused=False, comp_bits=None):
     from paper_1810_05486_amd.device_state import DeviceState
-    dev = DeviceState(cfg, mom_bits=mom_bits, fl_mom0=fl_mom0)
-    host = OracleState(cfg, mom_bits=mom_bits, fl_mom0=fl_mom0)
+    dev = DeviceState(cfg, mom_bits=mom_bits, fl_mom0=fl_mom0, comp_bits=comp_bits)
+    host = OracleState(cfg, mom_bits=mom_bits, fl_mom0=fl_mom0, comp_bits=comp_bits)
     views = dev.host_src_views()
     theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
     dev.upload_src()
@@ -323,3 +323,15 @@ def test_momentum_all_int8_with_int8_gradients(mb):
     for dv, hv in ((d_theta, theta), (d_comp, comp), (d_mom, mom)):
         assert np.array_equal(dv.cpu().numpy(), hv)
     tl.destroy()
+
+
+def test_momentum_int8_theta_with_int16_accumulator():
+    """Section 2's 22-bit parameter (8-bit theta, 16-bit accumulator) under the momentum optimizer: ResNet-18 shapes
+    and the reduced stress shape, int8 and int16 velocity, int16 and fp32 gradient sources."""
+    cfg = workloads.config(3)
+    say("momentum: int8 theta + int16 comp, config 3 shapes, int16 velocity")
+    run_config(cfg, [16] * cfg.n_tensors, [0, 1, 2, 300, 600], comp_bits=[16] * cfg.n_tensors)
+    cfg = workloads.config(5, big_elems=(1 << 22) + 9, n_tiny=100)
+    say("momentum: int8 theta + int16 comp, config 5 reduced, int8 velocity, then fed from fp32 gradients")
+    run_config(cfg, [8] * cfg.n_tensors, range(4), comp_bits=[16] * cfg.n_tensors)
+    run_config(cfg, [16] * cfg.n_tensors, range(3), comp_bits=[16] * cfg.n_tensors, fused=True)
