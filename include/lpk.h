@@ -206,6 +206,25 @@ int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* list,
                                uint64_t* vmax_out, uint32_t* status, void* stream);
 
 /*
+ * lpk_kahan_sgd_step for callers that cannot allocate device memory: code running under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It needs no lpk_tensor_list: it takes the host array of
+ * descriptors itself and keeps the tables that lpk_tensor_list_create would allocate in a fixed device array inside
+ * the library (9.1 MiB, held by every GPU the library runs on until the process ends).  The call allocates nothing,
+ * frees nothing and does not synchronize; the descriptors reach the device as kernel arguments, so `descs` may be
+ * reused as soon as the call returns.  Results (theta, comp, vmax_out, status) are bit-identical to
+ * lpk_tensor_list_create + lpk_kahan_sgd_step with default options on the same descriptors.
+ * Limits: n_tensors <= 16384 and at most 524288 tiles, a tile being 4096 elements of one tensor, counted per
+ * tensor as ceil(n / 4096) (so up to 2^31 elements in one tensor); beyond them LPK_ERR_UNSUPPORTED, nothing launched.
+ * Every call on a GPU rewrites that GPU's array: calls that overlap in time on one GPU (different streams, or
+ * threads) race on it and must be serialized by the caller; calls on one stream are ordered by the stream.
+ * Other arguments and errors as lpk_kahan_sgd_step (INVALID_ARG also for what lpk_tensor_list_create rejects).
+ */
+int lpk_kahan_sgd_step_noalloc(const lpk_tensor_desc* descs /* host */, uint32_t n_tensors,
+                               const int32_t* fl_theta_in, const int32_t* fl_theta_out, const int32_t* fl_grad,
+                               uint32_t lr_q16, uint32_t wd_q16,
+                               uint64_t* vmax_out, uint32_t* status, void* stream);
+
+/*
  * Momentum SGD with the lazy update inside (Section 4: the momentum optimizer, mu = 0.9, with Algorithm 1
  * implemented in the optimizer; INT8 or INT16 velocity).  Heavy-ball form with the learning rate inside
  * the velocity:  m <- mu*m - lr*(g + wd*theta);  theta <- theta + m  through Algorithm 1.

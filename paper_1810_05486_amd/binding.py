@@ -63,6 +63,8 @@ def lib():
         L.lpk_kahan_sgd_step.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
         L.lpk_kahan_sgd_step_f32grad.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
         L.lpk_kahan_sgd_step_f32grad.restype = ci
+        L.lpk_kahan_sgd_step_noalloc.argtypes = [ctypes.POINTER(lpk_tensor_desc), u32, vp, vp, vp, u32, u32, vp, vp, vp]
+        L.lpk_kahan_sgd_step_noalloc.restype = ci
         L.lpk_momentum_sgd_step.argtypes = [vp, vp, vp, vp, vp, vp, u32, u32, u32, vp, vp, vp, vp]
         L.lpk_momentum_sgd_step.restype = ci
         L.lpk_adam_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(lpk_adam_hyper), vp, vp, vp, vp, vp]
@@ -198,6 +200,15 @@ def lpk_kahan_sgd_step_f32grad(tl, fl_theta_in, fl_theta_out, fl_grad, lr_q16, w
     _check(lib().lpk_kahan_sgd_step_f32grad(tl.handle, _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_grad),
                                             int(lr_q16), int(wd_q16), _addr(vmax_out), _addr(status), _stream(stream)),
            "lpk_kahan_sgd_step_f32grad")
+
+
+def lpk_kahan_sgd_step_noalloc(descs, fl_theta_in, fl_theta_out, fl_grad, lr_q16, wd_q16=0, vmax_out=None, status=None,
+                               stream=None):
+    """descs: a list of lpk_tensor_desc (see make_desc), or a ctypes array of them."""
+    arr = descs if isinstance(descs, ctypes.Array) else (lpk_tensor_desc * len(descs))(*descs)
+    _check(lib().lpk_kahan_sgd_step_noalloc(arr, len(arr), _addr(fl_theta_in), _addr(fl_theta_out), _addr(fl_grad),
+                                            int(lr_q16), int(wd_q16), _addr(vmax_out), _addr(status), _stream(stream)),
+           "lpk_kahan_sgd_step_noalloc")
 
 
 def lpk_momentum_sgd_step(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16=0,

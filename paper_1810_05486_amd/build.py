@@ -15,8 +15,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "liblpk.so")
-SOURCES = ["lpk_host.hip", "kahan_step.hip", "momentum_step.hip", "adam_step.hip", "select_fraclen.hip", "quantize.hip"]
-HEADERS = [os.path.join(CSRC, "lpk_device.hpp"), os.path.join(CSRC, "step_common.hpp"),
+SOURCES = ["lpk_host.hip", "kahan_step.hip", "momentum_step.hip", "adam_step.hip", "select_fraclen.hip", "quantize.hip",
+           "noalloc_step.hip"]
+HEADERS = [os.path.join(CSRC, "lpk_device.hpp"), os.path.join(CSRC, "step_common.hpp"), os.path.join(CSRC, "host_common.hpp"),
            os.path.join(HERE, "..", "include", "lpk.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -1,16 +1,12 @@
 // Host layer of liblpk: the C ABI declared in include/lpk.h.  Validates
 // arguments, owns the per-list device tables, and enqueues the kernels.
-#include "../../include/lpk.h"
-#include "lpk_device.hpp"
+#include "host_common.hpp"
 
 #include <cstdlib>
 #include <new>
 #include <vector>
 
 namespace lpk {
-hipError_t launch_kahan_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                             int grad_is_f32, const int32_t*, const int32_t*, const int32_t*, uint32_t lr, uint32_t wd,
-                             uint32_t store_all, uint32_t with_i8, uint64_t* vmax, uint32_t* status, hipStream_t);
 hipError_t launch_select_f32(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int sel, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
                              uint32_t* status, hipStream_t);
@@ -52,9 +48,6 @@ struct lpk_tensor_list {
   uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls
 };
 
-static int dtype_bits(uint8_t dt) { return dt == LPK_I8 ? 8 : (dt == LPK_I16 ? 16 : 0); }
-static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
-
 static uint32_t env_u32(const char* name, uint32_t dflt)
 {
   const char* s = std::getenv(name);
@@ -73,43 +66,12 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
 
   std::vector<TensorDev> tensors(n_tensors);
   std::vector<Tile> tiles;
-  bool all_src = true, all_mom = true, all_sec = true, any_grad_i8 = false;
-  uint64_t total_tiles = 0;
+  ListFacts facts;
   for (uint32_t t = 0; t < n_tensors; ++t) {
-    const lpk_tensor_desc& D = descs[t];
-    const int wt = dtype_bits(D.theta_dtype), wg = dtype_bits(D.grad_dtype);
-    const int wc = D.comp ? dtype_bits(D.comp_dtype) : 0;
-    if (!wt || !wg || (D.comp && !wc)) return LPK_ERR_INVALID_ARG;
-    int d = 0;
-    if (D.comp) {
-      d = D.comp_shift == LPK_COMP_SHIFT_DEFAULT ? wc - 1 : (int)D.comp_shift;
-      if (d > kDMax) return LPK_ERR_INVALID_ARG;
-    }
-    if (D.n && (!D.theta || !D.grad)) return LPK_ERR_INVALID_ARG;
-    if (!aligned(D.theta, wt / 8) || !aligned(D.grad, wg / 8) || (D.comp && !aligned(D.comp, wc / 8)) ||
-        !aligned(D.src_f32, 4)) return LPK_ERR_INVALID_ARG;
-    if (D.n && !D.src_f32) all_src = false;
-    if (D.n && wg == 8) any_grad_i8 = true;
-    const int wm = D.momentum ? dtype_bits(D.momentum_dtype) : 0;
-    if (D.momentum && (!wm || !aligned(D.momentum, wm / 8))) return LPK_ERR_INVALID_ARG;
-    if (D.n && !D.momentum) all_mom = false;
-    const int wu = D.second ? dtype_bits(D.second_dtype) : 0;
-    if (D.second && (!wu || !aligned(D.second, wu / 8))) return LPK_ERR_INVALID_ARG;
-    if (D.n && !D.second) all_sec = false;
-
-    TensorDev& T = tensors[t];
-    T = TensorDev{};
-    T.theta = D.theta; T.comp = D.comp; T.grad = const_cast<void*>(D.grad); T.src = D.src_f32; T.n = D.n;
-    T.wt = (uint8_t)wt; T.wc = (uint8_t)wc; T.wg = (uint8_t)wg; T.d = (uint8_t)d;
-    T.vec_step      = aligned(D.theta, 16) && aligned(D.grad, 16) && D.comp && aligned(D.comp, 16);
-    T.vec_src_grad  = D.src_f32 && aligned(D.src_f32, 16) && aligned(D.grad, 16);
-    T.vec_src_theta = D.src_f32 && aligned(D.src_f32, 16) && aligned(D.theta, 16);
-    T.mom = D.momentum; T.wm = (uint8_t)wm;
-    T.vec_mom = T.vec_step && D.momentum && aligned(D.momentum, 16);
-    T.sec = D.second; T.wu = (uint8_t)wu;
-    T.vec_adam = T.vec_mom && D.second && aligned(D.second, 16);
-    total_tiles += (D.n + kTileElems - 1) / kTileElems;
+    const int rc = describe_tensor(descs[t], tensors[t], facts);
+    if (rc != LPK_OK) return rc;
   }
+  const uint64_t total_tiles = facts.total_tiles;
   if (total_tiles >= (1ull << 31)) return LPK_ERR_UNSUPPORTED;
   tiles.reserve((size_t)total_tiles);
   for (uint32_t t = 0; t < n_tensors; ++t)
@@ -122,10 +84,10 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   if (!L) return LPK_ERR_DEVICE;
   L->n_tensors = n_tensors;
   L->n_tiles = (uint32_t)tiles.size();
-  L->all_src = all_src;
-  L->all_mom = all_mom;
-  L->all_sec = all_sec;
-  L->any_grad_i8 = any_grad_i8;
+  L->all_src = facts.all_src;
+  L->all_mom = facts.all_mom;
+  L->all_sec = facts.all_sec;
+  L->any_grad_i8 = facts.any_grad_i8;
 
   hipDeviceProp_t prop;
   bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
@@ -133,12 +95,7 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     // Persistent grids, never more blocks than tile quads.  Measured on MI355X: update kernels that write as much
     // as they read stream fastest with ONE workgroup (one wave per SIMD) per CU, the read-mostly ones (max-abs,
     // quantization, the plain update once its unchanged groups are not stored) with two.
-    const uint32_t need = (L->n_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    auto clampg = [&](uint32_t per_cu) {
-      uint32_t g = (uint32_t)prop.multiProcessorCount * per_cu;
-      if (g > need) g = need;
-      return g ? g : 1u;
-    };
+    auto clampg = [&](uint32_t per_cu) { return persistent_grid(L->n_tiles, (uint32_t)prop.multiProcessorCount, per_cu); };
     L->grid = clampg(env_u32("LPK_BLOCKS_PER_CU", 2));
     // quantization: one workgroup per CU on long lists (measured 5 % faster there), two when a wave would get fewer
     // than sixteen tiles (short lists are latency-bound and want more waves)

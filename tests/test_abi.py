@@ -130,3 +130,24 @@ int main(void)
                            "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"])
     r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and r.stdout.strip() == "ok", (r.returncode, r.stdout, r.stderr[-2000:])
+
+
+def test_noalloc_step_rejects_what_does_not_fit_before_launching():
+    """Limits and argument errors of lpk_kahan_sgd_step_noalloc are found on the host: nothing touches a device."""
+    d = lpk.lpk_tensor_desc()
+    d.theta, d.comp, d.grad, d.n = 0x1000, 0x2000, 0x3000, 256
+    d.theta_dtype, d.comp_dtype, d.grad_dtype, d.comp_shift = lpk.LPK_I8, lpk.LPK_I8, lpk.LPK_I16, 0xFF
+    many = (lpk.lpk_tensor_desc * 16385)(*([d] * 16385))
+    assert lpk.lib().lpk_kahan_sgd_step_noalloc(many, 16385, 8, 8, 8, 1, 0, None, None, None) == lpk.LPK_ERR_UNSUPPORTED
+    d.n = (1 << 31) + 1                               # 524289 tiles
+    one = (lpk.lpk_tensor_desc * 1)(d)
+    assert lpk.lib().lpk_kahan_sgd_step_noalloc(one, 1, 8, 8, 8, 1, 0, None, None, None) == lpk.LPK_ERR_UNSUPPORTED
+    d.n = 256
+    one = (lpk.lpk_tensor_desc * 1)(d)
+    assert lpk.lib().lpk_kahan_sgd_step_noalloc(one, 1, 8, 8, 8, 65536, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert lpk.lib().lpk_kahan_sgd_step_noalloc(one, 1, None, 8, 8, 1, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert lpk.lib().lpk_kahan_sgd_step_noalloc(None, 1, 8, 8, 8, 1, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert lpk.lib().lpk_kahan_sgd_step_noalloc(one, 0, 8, 8, 8, 1, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG
+    d.comp_shift = 25
+    one = (lpk.lpk_tensor_desc * 1)(d)
+    assert lpk.lib().lpk_kahan_sgd_step_noalloc(one, 1, 8, 8, 8, 1, 0, None, None, None) == lpk.LPK_ERR_INVALID_ARG

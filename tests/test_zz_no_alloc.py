@@ -1,0 +1,106 @@
+"""lpk_kahan_sgd_step_noalloc (the entry point for callers that cannot allocate device memory) against
+lpk_tensor_list_create + lpk_kahan_sgd_step on the same inputs, through the C ABI: every output byte, vmax and the
+status word, on two calls in a row, the second with a smaller input (the library's fixed device tables keep the
+first call's contents)."""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_1810_05486_amd import binding as lpk
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+DT = {8: torch.int8, 16: torch.int16}
+
+
+def make_state(seed, specs):
+    """specs: (n, theta_bits, comp_bits or 0, grad_bits, byte misalignment) per tensor.  Returns host tensors."""
+    g = torch.Generator().manual_seed(seed)
+    state = []
+    for n, wt, wc, wg, mis in specs:
+        th = torch.randint(-(1 << (wt - 1)), 1 << (wt - 1), (n,), generator=g, dtype=torch.int32).to(DT[wt])
+        co = torch.randint(-(1 << (wc - 1)), 1 << (wc - 1), (n,), generator=g, dtype=torch.int32).to(DT[wc]) if wc else None
+        lim = 1 << (wg - 1)
+        gr = (torch.randn(n, generator=g) * (lim / 4)).round().clamp(-lim, lim - 1).to(DT[wg])
+        state.append((th, co, gr, mis))
+    return state
+
+
+def upload(state):
+    """Each tensor into its own 256-byte aligned device buffer, shifted by `mis` elements when asked."""
+    out = []
+    for th, co, gr, mis in state:
+        def dev(x):
+            if x is None:
+                return None
+            buf = torch.zeros(x.numel() + 64, dtype=x.dtype, device="cuda:0")
+            v = buf[mis:mis + x.numel()]
+            v.copy_(x)
+            return v
+        out.append((dev(th), dev(co), dev(gr)))
+    return out
+
+
+def run_both(seed, specs, fl_in, fl_out, fl_g, lr, wd, steps):
+    nt = len(specs)
+    state = make_state(seed, specs)
+    a, b = upload(state), upload(state)
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    d_in, d_out, d_g = torch.tensor(fl_in, **i32), torch.tensor(fl_out, **i32), torch.tensor(fl_g, **i32)
+    vm_a = torch.zeros(nt, dtype=torch.int64, device="cuda:0")
+    vm_b = torch.full((nt,), -1, dtype=torch.int64, device="cuda:0")
+    st_a = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    st_b = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    descs_a = [lpk.make_desc(t, c, g) for t, c, g in a]
+    descs_b = [lpk.make_desc(t, c, g) for t, c, g in b]
+    L = lpk.TensorList(descs_a)
+    for s in range(steps):
+        lpk.lpk_kahan_sgd_step(L, d_in, d_out, d_g, lr, wd, vm_a, st_a)
+        lpk.lpk_kahan_sgd_step_noalloc(descs_b, d_in, d_out, d_g, lr, wd, vm_b, st_b)
+        torch.cuda.synchronize()
+        assert vm_a.cpu().tolist() == vm_b.cpu().tolist(), ("vmax", s)
+        assert st_a.cpu().tolist() == st_b.cpu().tolist(), ("status", s)
+        changed = 0
+        for t in range(nt):
+            assert torch.equal(a[t][0], b[t][0]), ("theta", s, t)
+            changed += int((a[t][0].cpu() != state[t][0]).sum())
+            if a[t][1] is not None:
+                assert torch.equal(a[t][1], b[t][1]), ("comp", s, t)
+                changed += int((a[t][1].cpu() != state[t][1]).sum())
+            assert torch.equal(b[t][2].cpu(), state[t][2]), ("grad untouched", s, t)
+        assert changed > 0, "the step must move something for the comparison to mean anything"
+    L.destroy()
+    return int(st_a.cpu().view(torch.int32)[0])
+
+
+def test_noalloc_step_matches_the_list_step_on_two_calls_in_a_row():
+    # first call: 47 tensors (two staging chunks): a ragged multi-tile int8 tensor, tiny ones, int16 theta/comp,
+    # int8 theta under an int16 accumulator, an int8-gradient tensor, a misaligned one (element path), one without
+    # accumulator, an empty one, and one whose fraclen lies outside the domain (skipped, status bit 2)
+    specs = [((1 << 21) + 77, 8, 8, 16, 0)] + [(256, 8, 8, 16, 0)] * 36 + [
+        (70001, 16, 16, 16, 0), (9000, 8, 16, 16, 0), (5000, 8, 8, 8, 0), (4099, 8, 8, 16, 1), (3000, 8, 0, 16, 0),
+        (0, 8, 8, 16, 0), (4096, 8, 8, 16, 0), (12345, 16, 16, 16, 0), (1, 8, 8, 16, 0), (8191, 8, 8, 16, 0)]
+    nt = len(specs)
+    assert nt == 47
+    fl_in = [7 if s[1] == 8 else 15 for s in specs]
+    fl_out = list(fl_in)
+    fl_out[37] -= 1                                  # a grid move on the int16 tensor
+    fl_g = [19] * nt
+    fl_g[43] = 99                                    # outside the domain
+    say("noalloc call 1: %d tensors, %d elements" % (nt, sum(s[0] for s in specs)))
+    status = run_both(1, specs, fl_in, fl_out, fl_g, 655, 0, steps=2)
+    assert status == lpk.LPK_STATUS_DOMAIN
+    # second call: a smaller input (fewer, shorter tensors; weight decay on)
+    specs2 = [(300000 + 13, 8, 8, 16, 0), (256, 8, 8, 16, 0), (5000, 16, 16, 16, 0)]
+    say("noalloc call 2: %d tensors, %d elements" % (len(specs2), sum(s[0] for s in specs2)))
+    status = run_both(2, specs2, [7, 7, 15], [7, 7, 15], [18, 18, 18], 6554, 7, steps=2)
+    assert status == 0
