@@ -92,6 +92,32 @@ def select_fraclen_f32(x, bits, fl_default, status=None):
     return int(out[0])
 
 
+def select_fraclen_f32_mt(x, bits, fl_default, status=None, threads=1, chunk=1 << 22):
+    """Same result as select_fraclen_f32, the scan cut into contiguous chunks on a thread pool.  The rule's result
+    never grows with the maximum, so the fraclen of the whole tensor is the smallest of the chunks' fraclens; an
+    all-zero chunk reports a sentinel above the rule's range and is left out (all chunks zero: fl_default).  A
+    non-finite value gives the rule's lowest result in its chunk and so in the minimum.  Harness convenience for
+    large tensors; the arithmetic is the single C routine."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    n = x.size
+    if threads <= 1 or n <= chunk:
+        return select_fraclen_f32(x, bits, fl_default, status)
+    sentinel = 1000
+    stats = []
+
+    def work(lo):
+        st = new_status()
+        stats.append(st)
+        return select_fraclen_f32(x[lo:min(lo + chunk, n)], bits, sentinel, st)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        fls = [f for f in ex.map(work, range(0, n, chunk)) if f != sentinel]
+    if status is not None:
+        for st in stats:
+            status[0] |= st[0]
+    return min(fls) if fls else int(fl_default)
+
+
 def select_fraclen_vmax(vmax, vmax_fl, bits, fl_default, status=None):
     out = np.zeros(1, dtype=np.int32)
     _check(lib().lpk_ref_select_fraclen_vmax(int(vmax), int(vmax_fl), bits, int(fl_default), _ptr(out), _ptr(status)))

@@ -11,7 +11,7 @@ torch = pytest.importorskip("torch")
 from oracle import ref
 from paper_1810_05486_amd import binding as lpk
 from paper_1810_05486_amd import workloads
-from oracle_state import OracleState
+from oracle_state import OracleState, draw_grads
 
 NP = {8: np.int8, 16: np.int16}
 TT = {8: torch.int8, 16: torch.int16}
@@ -64,7 +64,7 @@ def run_config(cfg, steps, lr=1e-3, eps=1e-8, comp_bits=None, fl_mom0=24, fl_sec
     dev.init_theta()
     host.init_theta(theta0)
     for s in steps:
-        grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
+        grads = draw_grads(cfg, s, views)
         dev.upload_src()
         hyper = workloads.adam_hyper(s, lr=lr, eps=eps)
         if fused:                                          # fp32 gradients straight into the update, no int16 round trip
@@ -73,8 +73,7 @@ def run_config(cfg, steps, lr=1e-3, eps=1e-8, comp_bits=None, fl_mom0=24, fl_sec
         else:
             dev.quantize_grads()
             dev.update_adam(hyper)
-        host.quantize_grads(grads)
-        host.update_adam(hyper)
+        host.update_adam(hyper, grads)
         compare(dev, host, "config %d step %d" % (cfg.id, s))
     dev.close()
     return host

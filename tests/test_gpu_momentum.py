@@ -11,7 +11,7 @@ torch = pytest.importorskip("torch")
 from oracle import ref
 from paper_1810_05486_amd import binding as lpk
 from paper_1810_05486_amd import workloads
-from oracle_state import OracleState
+from oracle_state import OracleState, draw_grads
 
 MU_Q16 = 58982        # RNE(0.9 * 2^16)
 NP = {8: np.int8, 16: np.int16}
@@ -57,7 +57,7 @@ def run_config(cfg, mom_bits, steps, fl_mom0=16, fused=False, comp_bits=None):
     dev.init_theta()
     host.init_theta(theta0)
     for s in steps:
-        grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
+        grads = draw_grads(cfg, s, views)
         dev.upload_src()
         if fused:                                          # fp32 gradients straight into the update, no int16 round trip
             dev.select_grads()

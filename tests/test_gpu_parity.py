@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 from paper_1810_05486_amd import workloads
-from oracle_state import OracleState
+from oracle_state import OracleState, draw_grads
 
 
 def say(msg):
@@ -43,22 +43,33 @@ def compare(dev, host, what, check_vmax=True):
 
 
 def run_config(cfg, step_ids, compare_every=1, kahan=True, always=(), comp_bits=None, fused=False, grad_bits=16):
+    """A workload whose gradients cycle through a few draws (config 5) keeps every draw resident, in HBM and on the
+    host, as bench.py does: from the second round of the cycle on a step costs no draw and no upload."""
     from paper_1810_05486_amd.device_state import DeviceState
-    dev = DeviceState(cfg, kahan=kahan, comp_bits=comp_bits, grad_bits=grad_bits)
+    n_src = cfg.grad_cycle or 1
+    dev = DeviceState(cfg, kahan=kahan, comp_bits=comp_bits, grad_bits=grad_bits, n_src=n_src)
     host = OracleState(cfg, kahan=kahan, comp_bits=comp_bits, grad_bits=grad_bits)
     views = dev.host_src_views()
     theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(cfg.n_tensors)]
     dev.upload_src()
     dev.init_theta()
     host.init_theta(theta0)
+    del theta0
     compare(dev, host, "init", check_vmax=False)
+    resident = {}
     for i, s in enumerate(step_ids):
-        grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
-        dev.upload_src()
-        if fused:
-            dev.step_fused(s)
+        k = s % n_src
+        if k in resident:
+            grads = resident[k]
         else:
-            dev.step(s)
+            grads = draw_grads(cfg, s, views)
+            dev.upload_src(k)
+            if cfg.grad_cycle:
+                grads = resident[k] = [g.copy() for g in grads]
+        if fused:
+            dev.step_fused(s, k)
+        else:
+            dev.step(s, k)
         host.step(s, grads)
         if (i + 1) % compare_every == 0 or i == len(step_ids) - 1 or i in always:
             compare(dev, host, "config %d step %d" % (cfg.id, s))
@@ -84,22 +95,20 @@ def test_config1_without_accumulator():
 
 
 def test_config2_lenet_reselect():
-    say("config 2: LeNet-5 shapes, int16, fraclen re-selected every step")
-    full = os.environ.get("LPK_FULL_CONFIGS") == "1"
-    run_config(workloads.config(2), range(1000 if full else 150))
+    say("config 2: LeNet-5 shapes, int16, fraclen re-selected every step, all 1000 steps, every byte after each")
+    run_config(workloads.config(2), range(1000))
 
 
 def test_config3_resnet18_stepped_lr():
-    say("config 3: ResNet-18 shapes, int8, lr steps at 300 and 600")
-    full = os.environ.get("LPK_FULL_CONFIGS") == "1"
-    steps = list(range(1000)) if full else list(range(6)) + [299, 300, 301, 599, 600, 601, 999]
-    run_config(workloads.config(3), steps, compare_every=50 if full else 1)
+    """All 1000 steps, so the state follows the workload's own trajectory across both learning-rate drops: fraclens,
+    vmax and status compared after every step, every byte every 50 steps and on the steps around the drops."""
+    say("config 3: ResNet-18 shapes, int8, lr steps at 300 and 600, all 1000 steps")
+    run_config(workloads.config(3), range(1000), compare_every=50, always=(0, 1, 299, 300, 301, 599, 600, 601))
 
 
 def test_config4_resnet50_mixed_width_decay():
-    say("config 4: ResNet-50 shapes, int8 + int16 classifier, weight decay")
-    full = os.environ.get("LPK_FULL_CONFIGS") == "1"
-    run_config(workloads.config(4), range(200 if full else 8), compare_every=50 if full else 1)
+    say("config 4: ResNet-50 shapes, int8 + int16 classifier, weight decay, all 200 steps")
+    run_config(workloads.config(4), range(200), compare_every=50, always=(0, 1, 2))
 
 
 def test_config5_reduced():
@@ -109,14 +118,12 @@ def test_config5_reduced():
 
 
 def test_config5_full_size_in_bench_launch_configuration():
-    """The headline workload at full size (1 Gi + 10000 x 256 elements), same lists and launch shape as bench.py,
-    every output byte compared with the oracle after each of two steps."""
-    full = os.environ.get("LPK_FULL_CONFIGS") == "1"
-    say("config 5 at FULL size: 1073741824 + 10000*256 elements, %d steps (oracle on host threads)" % (50 if full else 2))
-    if full:
-        run_config(workloads.config(5), range(50), compare_every=50, always=(0, 1))
-    else:
-        run_config(workloads.config(5), range(2))
+    """The headline workload at full size (1 Gi + 10000 x 256 elements), same lists and launch shape as bench.py.
+    All 50 steps: every output byte compared with the oracle after steps 1, 2, 25 and 50, fraclens, vmax and status
+    after every step.  LPK_CONFIG5_STEPS=n shortens the run."""
+    steps = int(os.environ.get("LPK_CONFIG5_STEPS", "50"))
+    say("config 5 at FULL size: 1073741824 + 10000*256 elements, %d steps (oracle on host threads)" % steps)
+    run_config(workloads.config(5), range(steps), compare_every=25, always=(0, 1))
 
 
 def test_fused_fp32_gradient_step_equals_quantize_then_step():
@@ -180,7 +187,7 @@ def test_whole_step_replayed_from_a_hip_graph(fused):
         host.step(0, grads)
         compare(dev, host, "config %d eager step before the replays" % cfg.id)
         for s in range(1, 7):
-            grads = [cfg.grad(t, s, out=views[t]) for t in range(cfg.n_tensors)]
+            grads = draw_grads(cfg, s, views)
             dev.upload_src()
             graph.replay()
             host.step(s, grads)

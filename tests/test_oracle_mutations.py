@@ -11,6 +11,7 @@ import test_oracle_bruteforce as bf
 import test_oracle_pins as pins
 import test_oracle_momentum as mom
 import test_oracle_adam as adam
+import test_oracle_readings as readings
 
 SRC = os.path.join(os.path.dirname(ref.__file__), "lpk_ref.c")
 
@@ -60,6 +61,8 @@ MUTATIONS = [
     ("adam_lr_exponent_ignored", "const int e = F + R - 16 - (int)lr_exp - fl_m_out;", "const int e = F + R - 16 - fl_m_out;"),
     ("adam_second_moment_goes_negative", "wide un = clampw(uq, 0, qmax_of(sec_bits));", "wide un = sat(uq, sec_bits);"),
     ("adam_moment_guard_bits", "wide uq = rescale(wU, 16);", "wide uq = rescale(wU, 15);"),
+    ("momentum_mmax_truncates_the_guard_bits", "wide aw = mq < 0 ? -mq : mq;", "wide aw = (w < 0 ? -w : w) >> 16;"),
+    ("empty_tensor_flagged", "if (n == 0) return LPK_REF_OK;", ""),
 ]
 
 CHECKS = [
@@ -79,6 +82,8 @@ CHECKS = [
     lambda: adam.test_adam_step_bruteforce(0),
     adam.test_constant_gradient_moves_theta_by_lr_per_step,
     adam.test_against_float64_adam,
+    readings.test_an_empty_tensor_is_a_no_op_whatever_the_fraclens_hold,
+    readings.test_velocity_exponent_comes_from_the_rounded_velocity_at_a_power_of_two_boundary,
 ]
 
 

@@ -1,0 +1,144 @@
+"""Pins for readings the oracle takes where the paper is silent, and for the host-side scalar conversions that both
+harnesses consume (CPU only).
+
+* Section 4 uses momentum SGD with the lazy update but never writes it out: the velocity's exponent is chosen from
+  the maximum of the velocity AS STORED (rounded to its grid, before saturation), not from the wide sum with its
+  guard bits.  The property that makes this the right reading: the fraclen rule promises that a tensor moved onto
+  its selected grid does not saturate, and the tensor that exists in memory is the rounded velocity.
+* An empty tensor is a no-op whatever the fraclen arrays hold (there is nothing whose grid could be wrong).
+* Section 3, eq. 4 (>=) and eq. 5 (>) disagree when log2(|class| - 1) + log2(2 / alpha) is an integer; eq. 4, the
+  condition the rule of thumb is derived from, is the one followed.
+* q16_pair / adam_hyper turn real hyper-parameters into the integers the ADAM step takes.
+"""
+import math
+from fractions import Fraction as Fr
+
+import numpy as np
+import pytest
+
+from oracle import ref
+import exact_rational as ex
+from paper_1810_05486_amd import workloads
+
+
+# ---------------------------------------------------------------- velocity exponent: max of the stored velocity
+
+def fraclen_of(M, bits, cur):
+    """The fraclen rule on a magnitude M (Fraction), clamped to cur +- 15 as the re-selection does."""
+    return max(cur - 15, min(cur + 15, ex.fraclen(M, bits)))
+
+
+def test_velocity_exponent_comes_from_the_rounded_velocity_at_a_power_of_two_boundary():
+    """One element whose wide velocity sum is 63.67 velocity LSBs: it is stored as 64.  From the stored value the
+    rule keeps the grid (64 * 2 = 128 would saturate an 8-bit velocity); from the wide sum it would pick the next
+    finer grid (RNE(127.34) = 127 fits) -- on which the stored 64 becomes 128 and saturates.  The oracle follows the
+    stored value."""
+    fl_m = 12
+    theta, comp, mom = (np.zeros(1, dtype=np.int8) for _ in range(3))
+    g = np.array([-32600], dtype=np.int16)
+    # mu = 0; the gradient term lands on the velocity's guard-bit grid unchanged (fl_g = fl_m): w = 128 * 32600
+    vmax, mmax = ref.momentum_sgd_step(theta, comp, mom, g, 7, 7, 7, fl_m, fl_m, fl_m, 128, 0)
+    w = Fr(128 * 32600, 65536)
+    assert Fr(127, 2) < w < Fr(255, 4) and int(mom[0]) == 64 and mmax == 64
+    from_stored = fraclen_of(Fr(mmax) * ex.two(-fl_m), 8, fl_m)
+    from_wide = fraclen_of(w * ex.two(-fl_m), 8, fl_m)
+    assert (from_stored, from_wide) == (fl_m, fl_m + 1)                  # the two readings differ here ...
+    assert ref.select_fraclen_vmax(mmax, fl_m, 8, fl_m) == from_stored   # ... and the oracle takes the stored value
+    assert ex.rne(Fr(int(mom[0])) * 2) > 127                             # what the other reading's grid would do to it
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_the_stored_velocity_fits_the_grid_selected_from_mmax(seed):
+    """Whatever the step did, every stored velocity moved onto the grid selected from this step's mmax stays inside
+    the rails (a velocity that saturated in this step widens the grid: the one-step lag)."""
+    rng = np.random.default_rng(40 + seed)
+    for _ in range(150):
+        mb = int(rng.choice([8, 16]))
+        n = 24
+        fl_m = int(rng.integers(5, 20))
+        fl_g = fl_m + int(rng.integers(-3, 8))
+        theta = rng.integers(-100, 100, n).astype(np.int8); comp = rng.integers(-100, 100, n).astype(np.int8)
+        lim = 1 << (mb - 1)
+        mom = rng.integers(-lim, lim, n).astype(np.int8 if mb == 8 else np.int16)
+        g = rng.integers(-32768, 32768, n).astype(np.int16)
+        lr = int(rng.choice([1, 128, 655, 6554, 65535])); mu = int(rng.choice([0, 32768, 58982, 65535]))
+        _, mmax = ref.momentum_sgd_step(theta, comp, mom, g, 7, 7, 7, fl_m, fl_m, fl_g, lr, mu)
+        sel = ref.select_fraclen_vmax(mmax, fl_m, mb, fl_m)
+        if mmax == 0:
+            assert sel == fl_m
+            continue
+        assert sel == fraclen_of(Fr(mmax) * ex.two(-fl_m), mb, fl_m)
+        moved = [ex.rne(Fr(int(m)) * ex.two(sel - fl_m)) for m in mom]
+        assert all(-lim <= q <= lim - 1 for q in moved), (mb, fl_m, sel, mmax)
+
+
+# ---------------------------------------------------------------- empty tensors
+
+def test_an_empty_tensor_is_a_no_op_whatever_the_fraclens_hold():
+    e8, e16 = np.zeros(0, dtype=np.int8), np.zeros(0, dtype=np.int16)
+    for bad in (99, -99):
+        st = ref.new_status()
+        assert ref.kahan_sgd_step(e8, e8, e16, 7, bad, bad, bad, 655, 7, st) == 0
+        assert ref.momentum_sgd_step(e8, e8, e16, e16, 7, bad, bad, bad, bad, bad, 655, 58982, 0, st) == (0, 0)
+        assert ref.adam_step(e8, e8, e16, e16, e16, 7, bad, bad, bad, bad, bad, bad, bad, 66, 0, 58982, 65470, 0, 0, st) == (0, 0, 0)
+        assert int(st[0]) == 0
+    # the same fraclens on one element ARE flagged, and the element is left alone
+    one8, one16 = np.array([5], dtype=np.int8), np.array([9], dtype=np.int16)
+    st = ref.new_status()
+    ref.kahan_sgd_step(one8, one8.copy(), one16, 7, 99, 99, 99, 655, 0, st)
+    assert int(st[0]) == ref.STATUS_DOMAIN and int(one8[0]) == 5
+
+
+# ---------------------------------------------------------------- Section 3: eq. 4 against eq. 5 on the boundary
+
+def test_classifier_bits_follow_eq_4_where_eq_5_as_printed_differs():
+    """Nine classes, alpha = 1/2: log2(8) + log2(4) = 5 exactly.  Eq. 4 (alpha / (|class| - 1) >= 2^-(BW - 1)) admits
+    BW = 5; eq. 5 as printed (BW > ...) would ask for 6.  Eq. 5 is derived from eq. 4, so eq. 4 decides."""
+    alpha = Fr(1, 2)
+    eq4 = min(bw for bw in range(2, 40) if alpha / 8 >= Fr(1, 2 ** (bw - 1)))
+    eq5 = min(bw for bw in range(2, 40) if bw > math.log2(8) + math.log2(2 / 0.5))
+    assert (eq4, eq5) == (5, 6)
+    assert ref.classifier_min_bits(9, 32768) == 5
+    for n_classes, bw in ((3, 3), (5, 4), (17, 6), (1025, 12)):             # every power-of-two boundary at alpha = 1/2
+        assert ref.classifier_min_bits(n_classes, 32768) == bw
+        assert alpha / (n_classes - 1) == Fr(1, 2 ** (bw - 1))
+
+
+# ---------------------------------------------------------------- host-side scalar conversions
+
+def test_q16_pair_is_the_nearest_16_bit_mantissa_with_the_largest_exponent():
+    rng = np.random.default_rng(3)
+    xs = [1e-3, 1e-4, 1e-8, 0.1, 0.5, 0.999, 3e-7, 2.0 ** -20, 65535 / 65536, 1e-19] + list(10.0 ** rng.uniform(-18, 0, 200))
+    for x in xs:
+        q, e = workloads.q16_pair(float(x))
+        X = Fr(float(x))
+        assert 0 <= e <= 48 and 0 < q <= 65535, (x, q, e)
+        assert q == min(65535, ex.rne(X * ex.two(16 + e))), (x, q, e)
+        if q < 65535:
+            assert abs(X - Fr(q) * ex.two(-(16 + e))) <= ex.two(-(17 + e)), (x, q, e)        # within half a unit
+        assert e == 48 or X * ex.two(16 + e + 1) > 65535, (x, q, e)                         # no larger exponent fits
+        if e < 48:
+            assert q >= 32767, (x, q, e)                                                    # so the mantissa is normalised
+    assert workloads.q16_pair(0.0) == (0, 0) and workloads.q16_pair(-1.0) == (0, 0)
+
+
+def test_adam_hyper_quantizes_the_betas_and_folds_their_bias_corrections_into_the_step_size():
+    b1_q, b2_q = ex.rne(Fr(9, 10) * 65536), ex.rne(Fr(999, 1000) * 65536)
+    assert (b1_q, b2_q) == (58982, 65470)
+    lr = Fr(1e-3)
+    for step in (0, 1, 2, 9, 99, 999, 5000):
+        lr_q, lr_exp, h_b1, h_b2, eps_q, eps_exp = workloads.adam_hyper(step)
+        assert (h_b1, h_b2) == (b1_q, b2_q)
+        assert (eps_q, eps_exp) == workloads.q16_pair(1e-8)
+        t = step + 1
+        A = 1 - Fr(b2_q, 65536) ** t                      # 1 - beta2^t and 1 - beta1^t with the QUANTIZED betas
+        B = 1 - Fr(b1_q, 65536) ** t
+        want_sq = lr * lr * A / (B * B)                   # lr_t squared, exactly
+        unit = ex.two(-(16 + lr_exp))
+        tol = Fr(1, 10 ** 6)                              # of one mantissa unit: covers the float evaluation
+        assert ((lr_q - Fr(1, 2) - tol) * unit) ** 2 <= want_sq <= ((lr_q + Fr(1, 2) + tol) * unit) ** 2, step
+        assert lr_exp == 48 or lr_q >= 32767
+    # the pin bites: with the unquantized betas the first step's mantissa is another integer
+    lr_q, lr_exp = workloads.adam_hyper(0)[:2]
+    naive = 1e-3 * (1 - 0.999) ** 0.5 / (1 - 0.9)
+    assert workloads.q16_pair(naive) != (lr_q, lr_exp)
