@@ -38,6 +38,9 @@
  *     outside it is skipped untouched and LPK_STATUS_DOMAIN is raised.
  *   - Calls on one list that overlap in time (different streams) race on the
  *     list's reduction scratch; serialize them.
+ *   - One device per list: a list belongs to the device that was current in
+ *     lpk_tensor_list_create, its buffers live there, and every later call on
+ *     it must be made with that device current (else INVALID_ARG).
  */
 #ifndef LPK_H
 #define LPK_H
@@ -110,12 +113,22 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
  * synchronized every stream that still uses the list. */
 int lpk_tensor_list_destroy(lpk_tensor_list* list);
 
-/* Per-list options.  LPK_OPT_STORE_ALL (default 0): the update kernels normally do not issue the store of a
- * 16-byte group of theta or comp whose new value equals the one loaded (in the lazy update most parameters do not
- * move in a step, so this saves most of the write traffic); with value 1 every result is written.  The results
- * in memory are the same either way.  Takes effect for calls enqueued afterwards.
- * Errors: INVALID_ARG (NULL list, unknown option). */
-typedef enum { LPK_OPT_STORE_ALL = 1 } lpk_option;
+/* Per-list options; each takes effect for calls enqueued afterwards.
+ *   LPK_OPT_STORE_ALL (default 0): the plain update kernels normally do not issue the store of a 16-byte group of
+ *     theta or comp whose new value equals the one loaded (in the lazy update most parameters do not move in a step,
+ *     so this saves most of the write traffic); with value 1 every result is written.  The results in memory are the
+ *     same either way.
+ *   LPK_OPT_*_BLOCKS_PER_CU: launch shape of one family of kernels, in workgroups (of four wavefronts) per compute
+ *     unit, 1..64; 0 restores the built-in choice.  STEP: the plain update with lazy stores (built-in 2); DENSE: the
+ *     plain update with LPK_OPT_STORE_ALL and the momentum update (1); ADAM: the ADAM update (2); SCAN: the max-abs
+ *     scan of lpk_select_fraclen and the fp32-gradient momentum update (2); QUANT: lpk_quantize_tensor (1 on long
+ *     lists, 2 on short ones).  Results do not depend on the launch shape; these exist for tuning on other parts.
+ * Errors: INVALID_ARG (NULL list, unknown option, value out of range). */
+typedef enum {
+  LPK_OPT_STORE_ALL = 1,
+  LPK_OPT_STEP_BLOCKS_PER_CU = 2, LPK_OPT_DENSE_BLOCKS_PER_CU = 3, LPK_OPT_ADAM_BLOCKS_PER_CU = 4,
+  LPK_OPT_SCAN_BLOCKS_PER_CU = 5, LPK_OPT_QUANT_BLOCKS_PER_CU = 6
+} lpk_option;
 int lpk_tensor_list_set_option(lpk_tensor_list* list, int option, int value);
 
 /* Number of tensors / of tiles in a list (host-side facts, no device access); 0 for NULL. */
@@ -323,20 +336,6 @@ int lpk_adam_step_f32grad(lpk_tensor_list* list,
  * Examples at alpha = 0.5: 10 classes -> 6, 58 -> 8, 1000 -> 12 bits.
  */
 int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16);
-
-/* Measurement aid, not part of the method: dst[0..nbytes) = src[0..nbytes) with the same 16-byte
- * streaming accesses and grid shape as the update kernel.  Reads nbytes and writes nbytes of HBM,
- * which calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters and gives the practical copy
- * bandwidth of the device.  dst, src: device, 16-byte aligned, non-overlapping; nbytes % 16 == 0. */
-int lpk_stream_copy(void* dst, const void* src, uint64_t nbytes, void* stream);
-
-/* Measurement aid, not part of the method: the HBM byte mix of the int8 lazy update with no arithmetic.
- * For every 16-byte word j < nbytes / 16: reads a[j], b[j], c[2j], c[2j+1] and writes a[j] ^= c[2j],
- * b[j] ^= c[2j+1] in place -- 4 bytes read and 2 written per byte of a, in the update kernel's launch
- * shape.  Its bandwidth is what the memory system gives this access mix; the update kernel is read
- * against it.  a, b: device, nbytes each; c: device, 2 * nbytes; all 16-byte aligned, non-overlapping;
- * nbytes a multiple of 4096. */
-int lpk_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, void* stream);
 
 /* Static text for a return code ("ok", "invalid argument", ...). Never NULL. */
 const char* lpk_error_string(int code);

@@ -16,6 +16,8 @@ LPK_SEL_GRAD, LPK_SEL_THETA, LPK_SEL_MOMENTUM, LPK_SEL_SECOND = 0, 1, 2, 3
 LPK_STATUS_NONFINITE, LPK_STATUS_DOMAIN = 1, 2
 LPK_COMP_SHIFT_DEFAULT = 0xFF
 LPK_OPT_STORE_ALL = 1
+LPK_OPT_STEP_BLOCKS_PER_CU, LPK_OPT_DENSE_BLOCKS_PER_CU, LPK_OPT_ADAM_BLOCKS_PER_CU = 2, 3, 4
+LPK_OPT_SCAN_BLOCKS_PER_CU, LPK_OPT_QUANT_BLOCKS_PER_CU = 5, 6
 
 
 class lpk_tensor_desc(ctypes.Structure):
@@ -73,10 +75,6 @@ def lib():
         L.lpk_momentum_sgd_step_f32grad.restype = ci
         L.lpk_adam_step_f32grad.argtypes = L.lpk_adam_step.argtypes
         L.lpk_adam_step_f32grad.restype = ci
-        L.lpk_stream_copy.argtypes = [vp, vp, u64, vp]
-        L.lpk_stream_copy.restype = ci
-        L.lpk_stream_mix.argtypes = [vp, vp, vp, u64, vp]
-        L.lpk_stream_mix.restype = ci
         L.lpk_classifier_min_bits.argtypes = [u32, u32]
         L.lpk_classifier_min_bits.restype = ci
         L.lpk_error_string.argtypes = [ci]
@@ -245,14 +243,6 @@ def lpk_adam_step_f32grad(tl, fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, 
                                        _addr(fl_sec_in), _addr(fl_sec_out), _addr(fl_grad), ctypes.byref(h),
                                        _addr(vmax_out), _addr(mmax_out), _addr(umax_out), _addr(status), _stream(stream)),
            "lpk_adam_step_f32grad")
-
-
-def lpk_stream_mix(a, b, c, nbytes, stream=None):
-    _check(lib().lpk_stream_mix(_addr(a), _addr(b), _addr(c), int(nbytes), _stream(stream)), "lpk_stream_mix")
-
-
-def lpk_stream_copy(dst, src, nbytes, stream=None):
-    _check(lib().lpk_stream_copy(_addr(dst), _addr(src), int(nbytes), _stream(stream)), "lpk_stream_copy")
 
 
 def lpk_classifier_min_bits(n_classes, alpha_q16=32768):

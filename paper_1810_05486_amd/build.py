@@ -1,10 +1,12 @@
-"""Build liblpk.so (gfx950 only) in-tree with hipcc.
+"""Build liblpk.so and the benchmark's yardstick library libmembw.so (gfx950 only) in-tree with hipcc.
 
     python -m paper_1810_05486_amd.build [--force]
 
-Each csrc/*.hip is compiled to an object under csrc/_build/ and linked into
-paper_1810_05486_amd/liblpk.so.  Nothing is built at import time: the binding
-loads the library that is there and fails loudly when it is missing.
+Each source of liblpk is compiled to an object under csrc/_build/ and linked into
+paper_1810_05486_amd/liblpk.so; csrc/membw.hip (memory-system yardsticks, used by
+bench.py only, not part of the C ABI) becomes paper_1810_05486_amd/libmembw.so.
+Nothing is built at import time: the bindings load the libraries that are there
+and fail loudly when they are missing.
 """
 import os
 import subprocess
@@ -15,6 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "liblpk.so")
+MEMBW_SRC = os.path.join(CSRC, "membw.hip")
+MEMBW_LIB = os.path.join(HERE, "libmembw.so")
 SOURCES = ["lpk_host.hip", "kahan_step.hip", "momentum_step.hip", "adam_step.hip", "select_fraclen.hip", "quantize.hip",
            "noalloc_step.hip"]
 HEADERS = [os.path.join(CSRC, "lpk_device.hpp"), os.path.join(CSRC, "step_common.hpp"), os.path.join(CSRC, "host_common.hpp"),
@@ -42,6 +46,8 @@ def build(force=False, verbose=True):
         objs.append(obj)
         if force or _stale(obj, [src] + HEADERS):
             jobs.append([HIPCC] + FLAGS + ["-c", src, "-o", obj])
+    if force or _stale(MEMBW_LIB, [MEMBW_SRC]):
+        jobs.append([HIPCC] + FLAGS + ["-shared", MEMBW_SRC, "-o", MEMBW_LIB])
 
     def run(cmd):
         if verbose:
@@ -50,7 +56,7 @@ def build(force=False, verbose=True):
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         list(ex.map(run, jobs))
-    if force or jobs or _stale(LIB, objs):
+    if force or _stale(LIB, objs):
         run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs)
     return LIB
 

@@ -2,7 +2,6 @@
 // arguments, owns the per-list device tables, and enqueues the kernels.
 #include "host_common.hpp"
 
-#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -15,8 +14,6 @@ hipError_t launch_select_vmax(const TensorDev*, uint32_t n_tensors, int sel, con
                               hipStream_t);
 hipError_t launch_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t grid, int to_theta,
                            const int32_t* fl, uint32_t* status, hipStream_t);
-hipError_t launch_stream_copy(void* dst, const void* src, uint64_t nbytes, uint32_t grid, hipStream_t);
-hipError_t launch_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, uint32_t grid, hipStream_t);
 hipError_t launch_momentum_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                                 int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                                 const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
@@ -43,18 +40,34 @@ struct lpk_tensor_list {
   bool       all_sec   = false;    // ... and a second-moment buffer
   bool       store_all = false;    // LPK_OPT_STORE_ALL: write every result, changed or not
   bool       any_grad_i8 = false;  // some tensor has an int8 gradient array
+  uint32_t   n_cu = 0;             // compute units of the list's device
+  uint32_t   per_cu[8] = {};       // launch-shape options by lpk_option code, 0 = the built-in default
   TensorDev* d_tensors = nullptr;
   Tile*      d_tiles   = nullptr;
   uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls
 };
 
-static uint32_t env_u32(const char* name, uint32_t dflt)
+// Launch shapes (workgroups of four waves per compute unit) of the persistent kernels; measured on MI355X.
+// Update kernels that write as much as they read stream fastest with ONE workgroup (one wave per SIMD) per CU, the
+// read-mostly ones (max-abs, the plain update once its unchanged groups are not stored) and ADAM with two.
+// Quantization: one on long lists (measured 5 % faster there), two when a wave would get fewer than sixteen tiles
+// (short lists are latency-bound and want more waves).
+static void set_grids(lpk_tensor_list* L)
 {
-  const char* s = std::getenv(name);
-  if (!s || !*s) return dflt;
-  char* end = nullptr;
-  unsigned long v = std::strtoul(s, &end, 10);
-  return (end && *end == 0 && v > 0 && v < (1ul << 20)) ? (uint32_t)v : dflt;
+  auto grid = [&](uint32_t per_cu) { return persistent_grid(L->n_tiles, L->n_cu, per_cu); };
+  const uint32_t q_auto = L->n_tiles >= 16u * L->n_cu * kWavesPerBlock ? 1u : 2u;
+  L->grid       = grid(L->per_cu[LPK_OPT_SCAN_BLOCKS_PER_CU] ? L->per_cu[LPK_OPT_SCAN_BLOCKS_PER_CU] : 2u);
+  L->grid_quant = grid(L->per_cu[LPK_OPT_QUANT_BLOCKS_PER_CU] ? L->per_cu[LPK_OPT_QUANT_BLOCKS_PER_CU] : q_auto);
+  L->grid_step  = grid(L->per_cu[LPK_OPT_STEP_BLOCKS_PER_CU] ? L->per_cu[LPK_OPT_STEP_BLOCKS_PER_CU] : 2u);
+  L->grid_dense = grid(L->per_cu[LPK_OPT_DENSE_BLOCKS_PER_CU] ? L->per_cu[LPK_OPT_DENSE_BLOCKS_PER_CU] : 1u);
+  L->grid_adam  = grid(L->per_cu[LPK_OPT_ADAM_BLOCKS_PER_CU] ? L->per_cu[LPK_OPT_ADAM_BLOCKS_PER_CU] : 2u);
+}
+
+// A list belongs to the device that was current when it was made: its tables and the caller's buffers live there.
+static bool on_list_device(const lpk_tensor_list* L)
+{
+  int dev = -1;
+  return hipGetDevice(&dev) == hipSuccess && dev == L->device;
 }
 
 extern "C" {
@@ -89,22 +102,12 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   L->all_sec = facts.all_sec;
   L->any_grad_i8 = facts.any_grad_i8;
 
-  hipDeviceProp_t prop;
-  bool ok = hipGetDevice(&L->device) == hipSuccess && hipGetDeviceProperties(&prop, L->device) == hipSuccess;
+  int n_cu = 0;
+  bool ok = hipGetDevice(&L->device) == hipSuccess &&
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, L->device) == hipSuccess && n_cu > 0;
   if (ok) {
-    // Persistent grids, never more blocks than tile quads.  Measured on MI355X: update kernels that write as much
-    // as they read stream fastest with ONE workgroup (one wave per SIMD) per CU, the read-mostly ones (max-abs,
-    // quantization, the plain update once its unchanged groups are not stored) with two.
-    auto clampg = [&](uint32_t per_cu) { return persistent_grid(L->n_tiles, (uint32_t)prop.multiProcessorCount, per_cu); };
-    L->grid = clampg(env_u32("LPK_BLOCKS_PER_CU", 2));
-    // quantization: one workgroup per CU on long lists (measured 5 % faster there), two when a wave would get fewer
-    // than sixteen tiles (short lists are latency-bound and want more waves)
-    const uint32_t q_auto = L->n_tiles >= 16u * (uint32_t)prop.multiProcessorCount * kWavesPerBlock ? 1u : 2u;
-    L->grid_quant = clampg(env_u32("LPK_QUANT_BLOCKS_PER_CU", q_auto));
-    L->grid_step = clampg(env_u32("LPK_STEP_BLOCKS_PER_CU", 2));
-    L->grid_dense = clampg(env_u32("LPK_DENSE_BLOCKS_PER_CU", 1));
-    L->store_all = env_u32("LPK_STORE_ALL", 0) == 1;
-    L->grid_adam = clampg(env_u32("LPK_ADAM_BLOCKS_PER_CU", 2));
+    L->n_cu = (uint32_t)n_cu;
+    set_grids(L);
     ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
          hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * n_tensors) == hipSuccess &&
          (tiles.empty() || hipMalloc((void**)&L->d_tiles, sizeof(Tile) * tiles.size()) == hipSuccess);
@@ -139,6 +142,12 @@ int lpk_tensor_list_set_option(lpk_tensor_list* L, int option, int value)
 {
   if (!L) return LPK_ERR_INVALID_ARG;
   if (option == LPK_OPT_STORE_ALL) { L->store_all = value != 0; return LPK_OK; }
+  if (option >= LPK_OPT_STEP_BLOCKS_PER_CU && option <= LPK_OPT_QUANT_BLOCKS_PER_CU) {
+    if (value < 0 || value > 64) return LPK_ERR_INVALID_ARG;
+    L->per_cu[option] = (uint32_t)value;
+    set_grids(L);
+    return LPK_OK;
+  }
   return LPK_ERR_INVALID_ARG;
 }
 
@@ -150,6 +159,7 @@ int lpk_select_fraclen(lpk_tensor_list* L, int src_kind, int dst_sel,
                        int32_t* fl_out, uint32_t* status, void* stream)
 {
   if (!L || !fl_default || !fl_out) return LPK_ERR_INVALID_ARG;
+  if (!on_list_device(L)) return LPK_ERR_INVALID_ARG;
   if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA && dst_sel != LPK_SEL_MOMENTUM && dst_sel != LPK_SEL_SECOND)
     return LPK_ERR_INVALID_ARG;
   if (dst_sel == LPK_SEL_MOMENTUM && (src_kind != LPK_VMAX_U64 || !L->all_mom)) return LPK_ERR_INVALID_ARG;
@@ -172,6 +182,7 @@ int lpk_select_fraclen(lpk_tensor_list* L, int src_kind, int dst_sel,
 int lpk_quantize_tensor(lpk_tensor_list* L, int dst_sel, const int32_t* fl, uint32_t* status, void* stream)
 {
   if (!L || !fl) return LPK_ERR_INVALID_ARG;
+  if (!on_list_device(L)) return LPK_ERR_INVALID_ARG;
   if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA) return LPK_ERR_INVALID_ARG;
   if (!L->all_src) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_quantize(L->d_tensors, L->d_tiles, L->n_tiles, L->grid_quant, dst_sel == LPK_SEL_THETA, fl, status,
@@ -184,6 +195,7 @@ int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int
 {
   if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
+  if (!on_list_device(L)) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->store_all ? L->grid_dense : L->grid_step, 0, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, L->any_grad_i8 ? 1u : 0u, vmax_out, status,
                                    static_cast<hipStream_t>(stream));
@@ -196,6 +208,7 @@ int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, c
 {
   if (!L || !fl_theta_in || !fl_theta_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u) return LPK_ERR_INVALID_ARG;
+  if (!on_list_device(L)) return LPK_ERR_INVALID_ARG;
   if (!L->all_src) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->store_all ? L->grid_dense : L->grid_step, 1, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, L->any_grad_i8 ? 1u : 0u, vmax_out, status,
@@ -210,6 +223,7 @@ static int momentum_step(lpk_tensor_list* L, int grad_is_f32, const int32_t* fl_
 {
   if (!L || !fl_theta_in || !fl_theta_out || !fl_mom_in || !fl_mom_out || !fl_grad) return LPK_ERR_INVALID_ARG;
   if (lr_q16 > 65535u || wd_q16 > 65535u || mu_q16 > 65535u) return LPK_ERR_INVALID_ARG;
+  if (!on_list_device(L)) return LPK_ERR_INVALID_ARG;
   if (!L->all_mom || (grad_is_f32 && !L->all_src)) return LPK_ERR_INVALID_ARG;
   // fed from fp32 gradients the stream reads 7 bytes per 3 written and runs slightly faster with two workgroups per CU
   hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, grad_is_f32 ? L->grid : L->grid_dense, grad_is_f32,
@@ -245,6 +259,7 @@ static int adam_step(lpk_tensor_list* L, int grad_is_f32, const int32_t* fl_thet
     return LPK_ERR_INVALID_ARG;
   if (hyper->lr_q16 > 65535u || hyper->beta1_q16 > 65535u || hyper->beta2_q16 > 65535u || hyper->eps_q16 > 65535u ||
       hyper->lr_exp > 48u || hyper->eps_exp > 48u) return LPK_ERR_INVALID_ARG;
+  if (!on_list_device(L)) return LPK_ERR_INVALID_ARG;
   if (!L->all_mom || !L->all_sec || (grad_is_f32 && !L->all_src)) return LPK_ERR_INVALID_ARG;
   const AdamHyperDev h{hyper->lr_q16, hyper->lr_exp, hyper->beta1_q16, hyper->beta2_q16, hyper->eps_q16, hyper->eps_exp};
   hipError_t e = launch_adam_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_adam, grad_is_f32,
@@ -271,34 +286,6 @@ int lpk_adam_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, const 
                    vmax_out, mmax_out, umax_out, status, stream);
 }
 
-int lpk_stream_copy(void* dst, const void* src, uint64_t nbytes, void* stream)
-{
-  if (nbytes == 0) return LPK_OK;
-  if (!dst || !src || (nbytes & 15u) || !aligned(dst, 16) || !aligned(src, 16)) return LPK_ERR_INVALID_ARG;
-  int dev = 0;
-  hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return LPK_ERR_DEVICE;
-  uint64_t blocks = (nbytes / 16 + kBlock - 1) / kBlock;
-  const uint64_t cap = (uint64_t)prop.multiProcessorCount * env_u32("LPK_BLOCKS_PER_CU", 3);
-  if (blocks > cap) blocks = cap;
-  hipError_t e = launch_stream_copy(dst, src, nbytes, (uint32_t)blocks, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
-}
-
-int lpk_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, void* stream)
-{
-  if (nbytes == 0) return LPK_OK;
-  if (!a || !b || !c || (nbytes % (uint64_t)kTileElems) || !aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16)) return LPK_ERR_INVALID_ARG;
-  int dev = 0;
-  hipDeviceProp_t prop;
-  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return LPK_ERR_DEVICE;
-  uint64_t blocks = (nbytes / kTileElems + kWavesPerBlock - 1) / kWavesPerBlock;
-  const uint64_t cap = (uint64_t)prop.multiProcessorCount * env_u32("LPK_DENSE_BLOCKS_PER_CU", 1);
-  if (blocks > cap) blocks = cap;
-  hipError_t e = launch_stream_mix(a, b, c, nbytes, (uint32_t)blocks, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
-}
-
 const char* lpk_error_string(int code)
 {
   switch (code) {
@@ -320,6 +307,6 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
   return bw;
 }
 
-int lpk_version(void) { return 107; }
+int lpk_version(void) { return 200; }
 
 }  // extern "C"

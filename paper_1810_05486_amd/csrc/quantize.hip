@@ -112,53 +112,4 @@ hipError_t launch_quantize(const TensorDev* tensors, const Tile* tiles, uint32_t
   return hipGetLastError();
 }
 
-// Plain streaming copy (16 bytes per lane per access, grid-stride): the yardstick the HBM counters and
-// the update kernel's bandwidth are read against.
-__global__ void __launch_bounds__(kBlock) stream_copy_kernel(v4u* __restrict__ dst, const v4u* __restrict__ src, uint64_t n16)
-{
-  const uint64_t stride = (uint64_t)gridDim.x * kBlock;
-  for (uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride)
-    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
-}
-
-hipError_t launch_stream_copy(void* dst, const void* src, uint64_t nbytes, uint32_t grid, hipStream_t stream)
-{
-  if (nbytes)
-    hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(kBlock), 0, stream, (v4u*)dst, (const v4u*)src, nbytes / 16);
-  return hipGetLastError();
-}
-
-// The byte mix of the int8 lazy update without its arithmetic: per 16-byte word j, read a[j], b[j], c[2j], c[2j+1],
-// write a[j] and b[j] in place.  Same distribution of work as the update kernel: a persistent grid of wavefronts,
-// wave w takes 4096-byte tiles w, w + W, ..., all sixteen loads of a tile in flight before its eight stores.
-__global__ void __launch_bounds__(kBlock) stream_mix_kernel(v4u* a, v4u* b, const v4u* __restrict__ c, uint64_t n_tiles)
-{
-  const int lane = threadIdx.x & (kWave - 1);
-  const uint64_t w0 = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6), nw = (uint64_t)gridDim.x * kWavesPerBlock;
-  for (uint64_t t = w0; t < n_tiles; t += nw) {
-    v4u x[kPasses], y[kPasses], z0[kPasses], z1[kPasses];
-#pragma unroll
-    for (int u = 0; u < kPasses; ++u) {
-      const uint64_t j = (t * kPasses + u) * kWave + lane;
-      x[u]  = __builtin_nontemporal_load((const LPK_GLOBAL v4u*)(a + j));
-      y[u]  = __builtin_nontemporal_load((const LPK_GLOBAL v4u*)(b + j));
-      z0[u] = __builtin_nontemporal_load((const LPK_GLOBAL v4u*)(c + 2 * j));
-      z1[u] = __builtin_nontemporal_load((const LPK_GLOBAL v4u*)(c + 2 * j + 1));
-    }
-#pragma unroll
-    for (int u = 0; u < kPasses; ++u) {
-      const uint64_t j = (t * kPasses + u) * kWave + lane;
-      __builtin_nontemporal_store(x[u] ^ z0[u], (LPK_GLOBAL v4u*)(a + j));
-      __builtin_nontemporal_store(y[u] ^ z1[u], (LPK_GLOBAL v4u*)(b + j));
-    }
-  }
-}
-
-hipError_t launch_stream_mix(void* a, void* b, const void* c, uint64_t nbytes, uint32_t grid, hipStream_t stream)
-{
-  if (nbytes)
-    hipLaunchKernelGGL(stream_mix_kernel, dim3(grid), dim3(kBlock), 0, stream, (v4u*)a, (v4u*)b, (const v4u*)c, nbytes / kTileElems);
-  return hipGetLastError();
-}
-
 }  // namespace lpk
