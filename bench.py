@@ -666,7 +666,8 @@ def main():
 
     if not args.no_extras:
         mode_mix = "adam_i16" if args.adam else ({8: "momentum_i8v", 16: "momentum_i16v"}[args.momentum_bits] if args.momentum_bits
-                                                else ("update_i16" if args.theta_bits == 16 else "update_i8"))
+                                                else ("update_i16" if args.theta_bits == 16 else
+                                                      ("update_i8_c16" if args.comp_bits == 16 else "update_i8")))
         out["ceilings"] = measure_ceilings(args, cfg.n_params, mode_mix)
         mix_gbs = [v["GB/s"] for k, v in out["ceilings"].items() if isinstance(v, dict) and k.startswith(mode_mix)]
         if mix_gbs and plain and regimes:

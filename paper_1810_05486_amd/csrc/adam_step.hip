@@ -13,6 +13,17 @@
 // operations are repaired with exact residuals: the root by the sign of fma(r, r, -A), the quotient by the
 // remainder fma(-q, den, num) compared with half the divisor (ties to even).
 //
+// The usual case takes a shorter route with the same results ("fast": both moment grids standing still, the first
+// moment's grid at most eight bits finer than the gradient's, a step below 2^22 accumulator LSBs).  There the
+// first moment b1*m + (1-b1)*g*2^sh = 65536*m - (1-b1)*(m - g*2^sh) is ONE fp32 fused multiply-add onto the
+// constant 1.5*2^39 + 65536*m (ulp 2^16): its single IEEE rounding is the RNE at bit 16 and the new moment is read
+// from the significand.  The second moment is a 24-bit multiply-add and an integer round-half-even around one
+// fp64 FMA (the rounding of (1-b2)*g^2 onto u's guard-bit grid).  The root is the fp32 square root nudged below the
+// true root, truncated, and repaired upwards by the sign of one fp32 FMA (R*R - A is formed exactly inside it).
+// Only the quotient stays on the fp64 unit, without the Newton step: a quotient below 2^22 from the reciprocal's
+// documented 2^-23 relative accuracy is less than one away from the exact one, which is what the remainder test
+// repairs.  12 fp64 instructions per parameter instead of 46.
+//
 // Same work distribution as the plain update (persistent wavefronts over the tile table, non-temporal vector
 // accesses) for int16 moments and gradients on 16-byte aligned buffers; anything else goes element by element
 // through the same arithmetic.  Gradients come from the int16 array or, in a second kernel instance, from the
@@ -23,10 +34,11 @@
 #define LPK_ADAM_E 8                   // consecutive elements per lane per group (4 or 8)
 #endif
 #ifndef LPK_ADAM_GROUPS
-#define LPK_ADAM_GROUPS 4              // groups in flight per lane
+#define LPK_ADAM_GROUPS 4              // groups in flight per lane (measured: 2, 6, 8, 16 are slower for one or both gradient sources)
 #endif
 #ifndef LPK_ADAM_WAVES_PER_SIMD
-#define LPK_ADAM_WAVES_PER_SIMD 2      // register budget: 512 / this many VGPRs per lane
+#define LPK_ADAM_WAVES_PER_SIMD 1      // lower bound handed to the register allocator (no cap at 256 VGPRs: nothing spills; the kernel
+                                       // still fits two waves per SIMD, which is how it is launched)
 #endif
 
 namespace lpk {
@@ -37,22 +49,29 @@ struct AdamParams {
   int    caps;                     // some 2^40 cap may bind
   int    exact3;                   // a1, a2, a3 are integers (and no cap binds): three of the four products need no rounding
   double a1, a2, a3, a4;           // b1 * 2^-k1, (65536 - b1) * 2^-k2, b2 * 2^-k4, (65536 - b2) * 2^-k5
-  double qmin_t, qmax_t, qmin_c, qmax_c, qmin_m, qmax_m, qmax_u;
+  double qmin_m, qmax_m, qmax_u;
   double ascale;                   // 2^(24 + p): radicand scale
   double eps_r;                    // eps on the root's grid, at most 2^30
   double nlr;                      // -lr * 2^e
-  double p2d, p2u, inv_kth, p2kth, inv_kc;
+  Alg1Wide wa;                     // last stage of Algorithm 1 in fp64
   float  gscale, glo, ghi;         // fp32 gradient source: 2^fl_g and the rails of the gradient width
   // 32-bit tail (int8 theta, fixed grid, every |intermediate| of Algorithm 1 below 2^22): as in the plain update,
   // fma(v, 2^-d, 1.5 * 2^23) rounds v onto theta's grid and one 24-bit multiply-add forms the residual
   int    tail;                     // kTailWide, kTailSmall (int8 accumulator, d <= 8) or kTailSmallBigD (int16 accumulator)
-  int    d, neg2d, lo_cb, hi_cb, lo_c, hi_c;
-  float  inv2d_f, lo_tf, hi_tf;
+  int    d;
+  Alg1Small sm;
+  // fast route (see update_adam_fast)
+  int    fast;
+  int    neg2sh;                   // -2^sh, sh = fl_m_out - fl_g
+  float  nc1_f;                    // -(65536 - b1)
+  int    nc2;                      // -(65536 - b2)
+  int    qmin_mi, qmax_mi, qmax_ui, eps_i;
+  float  ascale_f;                 // 2^(24 + p)
 };
 
 enum { kTailWide = 0, kTailSmall = 1, kTailSmallBigD = 2 };
 
-struct AdamTrack { double vm, mm, um; int vmx, vmn; };
+struct AdamTrack { double vm, mm, um; VTrack v, m; int umx; };     // fp64 route's maxima; 32-bit routes' extremes of v and mq, max of uq
 
 __device__ __forceinline__ double cap_d() { return 1099511627776.0; }          // 2^40
 
@@ -116,20 +135,64 @@ __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, 
   // Algorithm 1 with this step
   if (TAIL != kTailWide) {
     const int v = (int)((unsigned)th << p.d) + c + (int)s;
-    tr.vmx = v > tr.vmx ? v : tr.vmx;
-    tr.vmn = v < tr.vmn ? v : tr.vmn;
-    tn = __float_as_int(__builtin_amdgcn_fmed3f(__builtin_fmaf((float)v, p.inv2d_f, 12582912.0f), p.lo_tf, p.hi_tf));
-    if (TAIL == kTailSmallBigD) cn = med3_i32(mad_i24(tn - 0x4B400000, p.neg2d, v), p.lo_c, p.hi_c);   // bits(1.5 * 2^23)
-    else                        cn = med3_i32(mad_i24(tn, p.neg2d, v), p.lo_cb, p.hi_cb);
+    track_v(tr.v, v);
+    alg1_small<(TAIL == kTailSmallBigD)>(p.sm, v, tn, cn);
     return;
   }
-  const double v = __builtin_fma((double)th, p.p2d, (double)c) + s;
-  tr.vm = __builtin_fmax(tr.vm, __builtin_fabs(v));
-  const double vG = v * p.p2u;
-  const double tnew = clampd(__builtin_rint(vG * p.inv_kth), p.qmin_t, p.qmax_t);
-  const double rr = __builtin_fma(-tnew, p.p2kth, vG);      // exact below 2^53; beyond that comp saturates either way
-  const double cnew = clampd(__builtin_rint(rr * p.inv_kc), p.qmin_c, p.qmax_c);
-  tn = (int)tnew; cn = (int)cnew;
+  alg1_wide(p.wa, th, c, s, tn, cn, tr.vm);
+}
+
+// The fast route (conditions in setup_adam; results identical to update_adam).
+//   first moment:  wM = b1*m + c1*g*2^sh = 65536*m - c1*y with c1 = 65536 - b1, y = m - g*2^sh (|y| < 2^24, exact in
+//     fp32).  fma(-c1, y, K + 65536*m) with K = 1.5*2^39 forms wM + K exactly and rounds it once to K's ulp, 2^16,
+//     ties to even (K / 2^16 is even): the result is K + 2^16 * RNE(wM / 2^16).  K + 65536*m is K's bit pattern
+//     plus m; the new moment is the result's bit pattern minus K's.  Needs |wM| < 2^38.
+//   second moment: wU = b2*u + t4 = 65536*u + w with w = t4 - c2*u in (-2^31, 2^30], t4 = RNE(g*g * a4) < 2^31 from
+//     one fp64 FMA onto 1.5*2^52 (whose low word is 0, so the sum's low word is t4).  RNE(wU / 2^16) is u plus w
+//     shifted right 16 with round-half-even, the parity taken from u + (w >> 16).
+//   root:  A = u' * 2^(24+p) < 2^40 is exact in fp32.  v_sqrt_f32 is within 1 ulp; times (1 - 2^-21) it lies
+//     strictly below the true root and less than 0.7 below it, so its truncation r0 is floor(root) or one less, and
+//     floor(root) = r0 + [(r0+1)^2 <= A].  That sign is exact: the FMA forms (r0+1)^2 - A (an integer) before rounding.
+//   quotient: q0 = RNE(num * rcp(den)) via the 1.5*2^52 constant (low word = q0).  |Q| < 0.99 * 2^22 and a reciprocal
+//     within 2^-23 (relative) put num * rcp(den) less than 0.5 from Q, so q0 is less than 1 from Q; the exact remainder
+//     num - q0*den against half the divisor (ties to even) moves q0 by at most one onto RNE(Q).
+template <int TAIL>
+__device__ __forceinline__ void update_adam_fast(const AdamParams& p, int th, int c, int m, int u, int g,
+                                                 int& tn, int& cn, int& mn, int& un, AdamTrack& tr)
+{
+  constexpr int kMagic39 = ((127 + 39) << 23) | 0x400000;          // bits(1.5 * 2^39)
+  const double kMagic52 = 6755399441055744.0;                      // 1.5 * 2^52
+  // first moment
+  const int y = mad_i24(g, p.neg2sh, m);
+  const int mq = __float_as_int(__builtin_fmaf(p.nc1_f, (float)y, __int_as_float(kMagic39 + m))) - kMagic39;
+  track_v(tr.m, mq);
+  mn = med3_i32(mq, p.qmin_mi, p.qmax_mi);
+  // second moment
+  const int t4 = __double2loint(__builtin_fma((double)mad_i24(g, g, 0), p.a4, kMagic52));
+  const int w = mad_i24(u, p.nc2, t4);
+  const int lsb = (u + (w >> 16)) & 1;
+  const int uq = u + ((w + 0x7fff + lsb) >> 16);
+  tr.umx = uq > tr.umx ? uq : tr.umx;
+  un = uq < p.qmax_ui ? uq : p.qmax_ui;
+  // root of the new second moment on its fixed grid
+  const float Af = (float)un * p.ascale_f;
+  const float r0 = __builtin_truncf(__builtin_amdgcn_sqrtf(Af) * 0.999999523162841796875f);     // 1 - 2^-21
+  const float r1 = r0 + 1.0f;
+  int den = (int)r0 + p.eps_i + (__builtin_fmaf(r1, r1, -Af) <= 0.0f ? 1 : 0);
+  den = den > 1 ? den : 1;
+  // step
+  const double dend = (double)den;
+  const double num = (double)mn * p.nlr;
+  const double qm = __builtin_fma(num, __builtin_amdgcn_rcp(dend), kMagic52);
+  const int q0 = __double2loint(qm);
+  const double rem = __builtin_fma(-(qm - kMagic52), dend, num);
+  const double t = __builtin_fabs(rem) + __builtin_fabs(rem);
+  const bool adj = (t > dend) | ((t == dend) & ((q0 & 1) != 0));
+  const int s = q0 + (adj ? ((__double2hiint(rem) >> 31) | 1) : 0);
+  // Algorithm 1 with this step, in 32 bits
+  const int v = (int)((unsigned)th << p.d) + c + s;
+  track_v(tr.v, v);
+  alg1_small<(TAIL == kTailSmallBigD)>(p.sm, v, tn, cn);
 }
 
 // Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
@@ -179,7 +242,7 @@ __device__ __forceinline__ void load_group_adam(AGroup<E, WT, WC, GS>& G, const 
   }
 }
 
-template <int E, int WT, int WC, bool CAPS, int TAIL, bool EXACT3, int GS>
+template <int E, int WT, int WC, bool CAPS, int TAIL, bool EXACT3, int GS, bool FAST>
 __device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, WT, WC, GS>& G, const TensorDev& T, uint64_t e, AdamTrack& tr,
                                            uint32_t& ab)
 {
@@ -189,8 +252,12 @@ __device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, 
     int g;
     if constexpr (GS == kGradF32) g = (int)quant_f32(__int_as_float(G.g[k >> 2].d[k & 3]), p.gscale, p.glo, p.ghi, ab);
     else                          g = elem_dw<16>(G.g[0], k);
-    update_adam<CAPS, TAIL, EXACT3>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), elem_dw<16>(G.m, k), elem_dw<16>(G.u, k), g,
-                                    tn[k], cn[k], mn[k], un[k], tr);
+    if constexpr (FAST)
+      update_adam_fast<TAIL>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), elem_dw<16>(G.m, k), elem_dw<16>(G.u, k), g,
+                             tn[k], cn[k], mn[k], un[k], tr);
+    else
+      update_adam<CAPS, TAIL, EXACT3>(p, elem_dw<WT>(G.th, k), elem_dw<WC>(G.c, k), elem_dw<16>(G.m, k), elem_dw<16>(G.u, k), g,
+                                      tn[k], cn[k], mn[k], un[k], tr);
   }
   st_dw((int8_t*)T.theta + e * (WT / 8), pack_dw<WT, E>(tn));
   st_dw((int8_t*)T.comp + e * (WC / 8), pack_dw<WC, E>(cn));
@@ -198,26 +265,16 @@ __device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, 
   st_dw((int16_t*)T.sec + e, pack_dw<16, E>(un));
 }
 
-template <int WT, int WC, bool CAPS, int TAIL, bool EXACT3, int GS>
+template <int WT, int WC, bool CAPS, int TAIL, bool EXACT3, int GS, bool FAST>
 __device__ __forceinline__ void tile_vec_adam_x(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr,
                                                 uint32_t& ab)
 {
   constexpr int E = LPK_ADAM_E, kP = LPK_ADAM_GROUPS;      // elements per lane per group, groups in flight per lane
   const uint32_t ngroups = cnt / E;
-  uint32_t gi = lane;
-  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
-    AGroup<E, WT, WC, GS> G[kP];
-#pragma unroll
-    for (int ps = 0; ps < kP; ++ps) load_group_adam(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
-#pragma unroll
-    for (int ps = 0; ps < kP; ++ps) group_adam<E, WT, WC, CAPS, TAIL, EXACT3, GS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr, ab);
-  }
-  for (; gi < ngroups; gi += kWave) {
-    AGroup<E, WT, WC, GS> G;
-    const uint64_t e = off + (uint64_t)gi * E;
-    load_group_adam(G, T, e);
-    group_adam<E, WT, WC, CAPS, TAIL, EXACT3, GS>(p, G, T, e, tr, ab);
-  }
+  using Grp = AGroup<E, WT, WC, GS>;
+  walk_groups<kP, Grp>(ngroups, lane,
+      [&](Grp& G, uint32_t gi) LPK_INLINE_LAMBDA { load_group_adam(G, T, off + (uint64_t)gi * E); },
+      [&](const Grp& G, uint32_t gi) LPK_INLINE_LAMBDA { group_adam<E, WT, WC, CAPS, TAIL, EXACT3, GS, FAST>(p, G, T, off + (uint64_t)gi * E, tr, ab); });
   const uint32_t tail = cnt - ngroups * E;
   if (tail) tile_generic_adam<CAPS, GS>(p, T, off + (uint64_t)ngroups * E, tail, lane, tr, ab);
 }
@@ -226,8 +283,11 @@ template <int WT, int WC, bool CAPS, int TAIL, int GS>
 __device__ __forceinline__ void tile_vec_adam(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr,
                                               uint32_t& ab)
 {
-  if (!CAPS && p.exact3) tile_vec_adam_x<WT, WC, false, TAIL, true, GS>(p, T, off, cnt, lane, tr, ab);
-  else                   tile_vec_adam_x<WT, WC, CAPS, TAIL, false, GS>(p, T, off, cnt, lane, tr, ab);
+  if constexpr (TAIL != kTailWide) {
+    if (p.fast) { tile_vec_adam_x<WT, WC, false, TAIL, true, GS, true>(p, T, off, cnt, lane, tr, ab); return; }
+  }
+  if (!CAPS && p.exact3) tile_vec_adam_x<WT, WC, false, TAIL, true, GS, false>(p, T, off, cnt, lane, tr, ab);
+  else                   tile_vec_adam_x<WT, WC, CAPS, TAIL, false, GS, false>(p, T, off, cnt, lane, tr, ab);
 }
 
 // ---------------------------------------------------------------- per-tensor set-up (wave-uniform)
@@ -253,16 +313,14 @@ __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, in
   p.a2 = (double)(65536u - h.b1) * pow2d(fl_m_out - fl_g);
   p.a3 = (double)h.b2 * pow2d(delta_u);
   p.a4 = (double)(65536u - h.b2) * pow2d(fl_u_out - 2 * fl_g);
-  p.qmax_t = (double)((1 << (p.wt - 1)) - 1); p.qmin_t = -(double)(1 << (p.wt - 1));
   const int wc = p.has_comp ? p.wc : 8;
-  p.qmax_c = (double)((1 << (wc - 1)) - 1);   p.qmin_c = -(double)(1 << (wc - 1));
   p.qmax_m = (double)((1 << (p.wm - 1)) - 1); p.qmin_m = -(double)(1 << (p.wm - 1));
   p.qmax_u = (double)((1 << (p.wu - 1)) - 1);
   p.ascale = pow2d(24 + par);
   p.eps_r  = __builtin_fmin(__builtin_rint((double)h.eps * pow2d(R - 16 - (int)h.eps_exp)), 1073741824.0);
   p.nlr    = -(double)h.lr * pow2d(e);
   const int u = delta > 0 ? delta : 0, kth = d + u - delta, kc = kth - d;
-  p.p2d = pow2d(d); p.p2u = pow2d(u); p.inv_kth = pow2d(-kth); p.p2kth = pow2d(kth); p.inv_kc = pow2d(-kc);
+  p.wa = make_alg1_wide(d, u, kth, kc, -(1 << (p.wt - 1)), (1 << (p.wt - 1)) - 1, -(1 << (wc - 1)), (1 << (wc - 1)) - 1);
   // Can a cap bind?  |g| <= 2^15 and g^2 <= 2^30 bound the two gradient terms; the step is at most
   // |num| / den <= 2^15 lr 2^e / max(eps_R, 1) (2^-e in the divisor when e < 0).
   const double step_bound = 32768.0 * (double)h.lr * pow2d(e) / __builtin_fmax(p.eps_r, 1.0);
@@ -283,20 +341,37 @@ __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, in
     if (p.wc == 8 && d <= 8 && vbound < 4194304.0) p.tail = kTailSmall;
     if (p.wc == 16 && d <= 22 && vbound < 8388608.0) p.tail = kTailSmallBigD;
   }
-  p.d = d; p.neg2d = -(1 << d);
-  p.inv2d_f = __uint_as_float((uint32_t)(127 - d) << 23);
-  p.lo_tf = 12582912.0f - (float)(1 << (p.wt - 1)); p.hi_tf = 12582912.0f + (float)((1 << (p.wt - 1)) - 1);
-  p.lo_c = -(1 << (wc - 1)); p.hi_c = (1 << (wc - 1)) - 1;
-  p.lo_cb = p.lo_c - (1 << (22 + (d <= 8 ? d : 8))); p.hi_cb = p.hi_c - (1 << (22 + (d <= 8 ? d : 8)));
+  // fast route: both moment grids standing still, 0 <= sh <= 8 with |wM| < 2^38, (1-b2)*g^2 below 2^30 on u's
+  // guard-bit grid, a 32-bit tail, and a step provably below 0.99 * 2^22
+  const int sh = fl_m_out - fl_g;
+  p.fast = p.exact3 && p.tail != kTailWide && delta_m == 0 && delta_u == 0 && sh >= 0 && sh <= 8 && p.a2 <= 4194304.0 &&
+           p.a4 <= 1.0 && step_bound < 4152360.0;
+  p.neg2sh = -(1 << (sh >= 0 && sh <= 8 ? sh : 0));
+  p.nc1_f = -(float)(65536u - h.b1);
+  p.nc2 = -(int)(65536u - h.b2);
+  p.qmin_mi = -(1 << (p.wm - 1)); p.qmax_mi = (1 << (p.wm - 1)) - 1; p.qmax_ui = (1 << (p.wu - 1)) - 1;
+  p.eps_i = (int)p.eps_r;
+  p.ascale_f = __uint_as_float((uint32_t)(127 + 24 + par) << 23);
+  p.d = d;
+  p.sm = make_alg1_small(d, -(1 << (p.wt - 1)), (1 << (p.wt - 1)) - 1, -(1 << (wc - 1)), (1 << (wc - 1)) - 1);
 }
 
 // ---------------------------------------------------------------- the kernel
 
 __device__ __forceinline__ uint64_t track_u64(double x) { return (uint64_t)x; }     // an integer below 2^53
-__device__ __forceinline__ uint64_t track_v(const AdamTrack& tr)                    // both tails' maxima of |v|
+__device__ __forceinline__ uint64_t track_m(const AdamTrack& tr)                    // both routes' maxima of |mq|
 {
-  const int64_t a = tr.vmx, b = -(int64_t)tr.vmn;
-  const uint64_t m32 = (uint64_t)(a > b ? a : b), m64 = (uint64_t)tr.vm;
+  const uint64_t mi = vtrack_max(tr.m), md = (uint64_t)tr.mm;
+  return mi > md ? mi : md;
+}
+__device__ __forceinline__ uint64_t track_um(const AdamTrack& tr)                   // ... of max(uq, 0)
+{
+  const uint64_t ui = (uint64_t)tr.umx, ud = (uint64_t)tr.um;
+  return ui > ud ? ui : ud;
+}
+__device__ __forceinline__ uint64_t track_vmax(const AdamTrack& tr)                 // both tails' maxima of |v|
+{
+  const uint64_t m32 = vtrack_max(tr.v), m64 = (uint64_t)tr.vm;
   return m32 > m64 ? m32 : m64;
 }
 
@@ -311,51 +386,46 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint64_t s_max[kWavesPerBlock];
 
-  const int lane   = threadIdx.x & (kWave - 1);
-  const int wave   = wave_uniform(threadIdx.x >> 6);
-  const uint32_t w0 = blockIdx.x * kWavesPerBlock + wave;
-  const uint32_t nw = gridDim.x * kWavesPerBlock;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = wave_uniform(threadIdx.x >> 6);
 
-  int cur = -1;
-  AdamTrack tr{0.0, 0.0, 0.0, 0, 0};
+  AdamTrack tr{0.0, 0.0, 0.0, {0, 0}, {0, 0}, 0};
   uint32_t status_bits = 0, ab_max = 0;
   AdamParams p; p.path = 0;
   TensorDev T;
 
-  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
-    int t; uint32_t cnt; uint64_t off;
-    read_tile(tiles, ti, t, cnt, off);
-    if (t != cur) {
-      if (cur >= 0) {
-        if (vmax) flush_wave(vmax, cur, track_v(tr), lane);
-        if (mmax) flush_wave(mmax, cur, track_u64(tr.mm), lane);
-        if (umax) flush_wave(umax, cur, track_u64(tr.um), lane);
-      }
-      tr = AdamTrack{0.0, 0.0, 0.0, 0, 0};
-      cur = t;
+  const int cur = walk_tiles(tiles, n_tiles,
+    [&](int t) LPK_INLINE_LAMBDA {
+      if (vmax) flush_wave(vmax, t, track_vmax(tr), lane);
+      if (mmax) flush_wave(mmax, t, track_m(tr), lane);
+      if (umax) flush_wave(umax, t, track_um(tr), lane);
+    },
+    [&](int t) LPK_INLINE_LAMBDA {
+      tr = AdamTrack{0.0, 0.0, 0.0, {0, 0}, {0, 0}, 0};
       T = tensors[t];
       setup_adam<GS>(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_u_in[t], fl_u_out[t], fl_g[t], h, status_bits);
-    }
-    if (p.path == 2 && !p.caps) {
-      if (p.wt == 8 && p.wc == 8) {
-        if (p.tail == kTailSmall) tile_vec_adam<8, 8, false, kTailSmall, GS>(p, T, off, cnt, lane, tr, ab_max);
-        else                      tile_vec_adam<8, 8, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
-      } else if (p.wt == 16) {
-        tile_vec_adam<16, 16, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
-      } else {
-        if (p.tail == kTailSmallBigD) tile_vec_adam<8, 16, false, kTailSmallBigD, GS>(p, T, off, cnt, lane, tr, ab_max);
-        else                          tile_vec_adam<8, 16, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
+    },
+    [&](uint64_t off, uint32_t cnt) LPK_INLINE_LAMBDA {
+      if (p.path == 2 && !p.caps) {
+        if (p.wt == 8 && p.wc == 8) {
+          if (p.tail == kTailSmall) tile_vec_adam<8, 8, false, kTailSmall, GS>(p, T, off, cnt, lane, tr, ab_max);
+          else                      tile_vec_adam<8, 8, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
+        } else if (p.wt == 16) {
+          tile_vec_adam<16, 16, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
+        } else {
+          if (p.tail == kTailSmallBigD) tile_vec_adam<8, 16, false, kTailSmallBigD, GS>(p, T, off, cnt, lane, tr, ab_max);
+          else                          tile_vec_adam<8, 16, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
+        }
+      } else if (p.path) {
+        if (p.caps) tile_generic_adam<true, GS>(p, T, off, cnt, lane, tr, ab_max); else tile_generic_adam<false, GS>(p, T, off, cnt, lane, tr, ab_max);
       }
-    } else if (p.path) {
-      if (p.caps) tile_generic_adam<true, GS>(p, T, off, cnt, lane, tr, ab_max); else tile_generic_adam<false, GS>(p, T, off, cnt, lane, tr, ab_max);
-    }
-  }
+    });
 
   if (GS == kGradF32 && __ballot(ab_max >= 0x7f800000u)) status_bits |= kStatusNonFinite;
-  if (status && status_bits && lane == 0) atomicOr(status, status_bits);
-  if (vmax) flush_block(vmax, cur, track_v(tr), lane, wave, s_tensor, s_max);
-  if (mmax) flush_block(mmax, cur, track_u64(tr.mm), lane, wave, s_tensor, s_max);
-  if (umax) flush_block(umax, cur, track_u64(tr.um), lane, wave, s_tensor, s_max);
+  raise_status(status, status_bits, lane);
+  if (vmax) flush_block(vmax, cur, track_vmax(tr), lane, wave, s_tensor, s_max);
+  if (mmax) flush_block(mmax, cur, track_m(tr), lane, wave, s_tensor, s_max);
+  if (umax) flush_block(umax, cur, track_um(tr), lane, wave, s_tensor, s_max);
 }
 
 __global__ void __launch_bounds__(kBlock) fill3_u64_kernel(uint64_t* a, uint64_t* b, uint64_t* c, uint32_t n)

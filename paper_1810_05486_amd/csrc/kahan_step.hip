@@ -52,21 +52,19 @@ struct StepParams {
   // fast path constants
   float    nlr_f;  float magic_f;  int magic_fi;
   double   nlrwd_d; double magic_d; int magic_dlo;
-  int      half_m1;         // 2^(d-1) - 1
+  Alg1Int  in;              // last stage by add-and-shift
   // small-value variant of the fast path (every |intermediate| < 2^22, d <= 8): roundings on the FMA unit
-  int      bias_i;          // -bits(1.5 * 2^23): takes the FMA's offset out of the step
-  float    inv2d_f;         // 2^-d
-  float    lo_tf, hi_tf;    // 1.5 * 2^23 + rails of theta
-  int      neg2d;           // -2^d
-  int      lo_cb, hi_cb;    // rails of comp minus 2^(22 + d)
+  int      bias_i;          // -bits(1.5 * 2^(23 + kg)): takes the FMA's offset out of the step
+  Alg1Small sm;             // last stage on the FMA unit
   int      mode;            // vector arithmetic: kModeFast, kModeSmall or kModeWide
 };
 
 // Constants of the wide path (fp64, any shifts), built from the shifts where that path starts so that they hold
-// no registers while the 32-bit loops run: -lr * 2^-kg, -lr * wd * 2^-kw, 2^d, 2^u, 2^-kth, 2^kth, 2^-kc, rails.
+// no registers while the 32-bit loops run: -lr * 2^-kg, -lr * wd * 2^-kw, and the last stage's powers of two and rails.
 struct WideParams {
-  bool   decay;
-  double ag, aw, p2d, p2u, inv_kth, p2kth, inv_kc, lo_t, hi_t, lo_c, hi_c;
+  bool     decay;
+  double   ag, aw;
+  Alg1Wide a;
 };
 
 enum { kModeFast = 0, kModeSmall = 1, kModeWide = 2 };
@@ -87,8 +85,7 @@ __device__ __forceinline__ float quant_grad(const StepParams& p, float x, uint32
 // Every quantity of the definition is an integer below 2^53 times a power of two: |lr * g| < 2^31,
 // |lr * wd * theta| < 2^47, each term capped at 2^40, |v| < 2^42.  Products, sums and scalings by powers of two are
 // therefore exact in binary64, and v_rndne_f64 is the round-to-nearest-even of the definition whichever way a
-// shift points -- no branches, no 64-bit integer sequences.  The residual v_G - theta' * 2^kth is exact while it is
-// below 2^53; beyond that the accumulator saturates whatever the last bits are.
+// shift points -- no branches, no 64-bit integer sequences.
 
 __device__ __forceinline__ WideParams make_wide(const StepParams& p)
 {
@@ -96,8 +93,7 @@ __device__ __forceinline__ WideParams make_wide(const StepParams& p)
   w.decay = p.lrwd != 0;
   w.ag = -(double)p.lr * pow2d(-p.kg);
   w.aw = -(double)p.lrwd * pow2d(-p.kw);
-  w.p2d = pow2d(p.d); w.p2u = pow2d(p.u); w.inv_kth = pow2d(-p.kth); w.p2kth = pow2d(p.kth); w.inv_kc = pow2d(-p.kc);
-  w.lo_t = (double)p.qmin_t; w.hi_t = (double)p.qmax_t; w.lo_c = (double)p.qmin_c; w.hi_c = (double)p.qmax_c;
+  w.a = make_alg1_wide(p.d, p.u, p.kth, p.kc, p.qmin_t, p.qmax_t, p.qmin_c, p.qmax_c);
   return w;
 }
 
@@ -109,13 +105,7 @@ __device__ __forceinline__ void update_wide(const WideParams& w, int th, int c, 
   const double cap = 1099511627776.0;                       // 2^40
   double s = clampd(__builtin_rint(g * w.ag), -cap, cap);
   if (DECAY) s += clampd(__builtin_rint((double)th * w.aw), -cap, cap);
-  const double v = __builtin_fma((double)th, w.p2d, (double)c) + s;
-  vabs_max = __builtin_fmax(vabs_max, __builtin_fabs(v));
-  const double vG = v * w.p2u;
-  const double tn = clampd(__builtin_rint(vG * w.inv_kth), w.lo_t, w.hi_t);
-  const double rr = __builtin_fma(-tn, w.p2kth, vG);
-  const double cn = clampd(__builtin_rint(rr * w.inv_kc), w.lo_c, w.hi_c);
-  th_new = (int)tn; c_new = (int)cn;
+  alg1_wide(w.a, th, c, s, th_new, c_new, vabs_max);
 }
 
 // Element-at-a-time tile: any alignment, any widths.  Lane l takes elements l, l+64, ...
@@ -140,7 +130,7 @@ __device__ __forceinline__ uint64_t tile_generic(const StepParams& p, const Tens
 
 // ---------------------------------------------------------------- fast (int32 + FMA rounding)
 
-struct Track { int vmx, vmn; uint32_t ab; double vw; int dense_t, dense_c; };     // groups of this tile whose theta / comp stores went out dense
+struct Track { VTrack vt; uint32_t ab; double vw; int dense_t, dense_c; };     // dense_*: groups of this tile whose theta / comp stores went out dense
 
 template <bool DECAY>
 __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, float gf, int& tn, int& cn, Track& tr)
@@ -150,24 +140,15 @@ __device__ __forceinline__ void update_fast(const StepParams& p, int th, int c, 
     double r = __builtin_fma((double)th, p.nlrwd_d, p.magic_d);
     s += __double2loint(r) - p.magic_dlo;
   }
-  int v = (int)((unsigned)th << p.d) + c + s;
-  tr.vmx = v > tr.vmx ? v : tr.vmx;
-  tr.vmn = v < tr.vmn ? v : tr.vmn;
-  int q = (v + p.half_m1 + ((v >> p.d) & 1)) >> p.d;      // RNE(v / 2^d), d >= 1, no overflow by path choice
-  tn = min(max(q, p.qmin_t), p.qmax_t);
-  int r = v - (int)((unsigned)tn << p.d);
-  cn = min(max(r, p.qmin_c), p.qmax_c);
+  const int v = (int)((unsigned)th << p.d) + c + s;
+  track_v(tr.vt, v);
+  alg1_int(p.in, v, tn, cn);                                // d >= 1, no overflow by path choice
 }
 
 // The same update when every intermediate is below 2^22 in magnitude and d <= 8 (int8 theta with an int8
-// accumulator): both roundings run on the FMA unit.  The step is the bit pattern of the same FMA as in
-// update_fast minus the bit pattern of its offset (folded into one constant added with comp).  With
-// M = 1.5 * 2^23 (ulp 1), fma(v, 2^-d, M) is M + RNE(v / 2^d) after its single IEEE rounding (v is exact in
-// fp32), clamped as a float between M + qmin and M + qmax.  The low
-// 24 bits of that float are 2^22 + theta', so one 24-bit multiply-add forms v - theta' * 2^d - 2^(22 + d); the
-// accumulator rails are shifted by the same constant, and the low bytes of both results are the bytes to store.
-// BIGD (d > 8, the int16 accumulator under an int8 theta): (2^22 + theta') * 2^d no longer fits 32 bits, so
-// theta' is first taken out of the float's bit pattern and the residual is formed and clamped unshifted.
+// accumulator), or below 2^23 under an int16 accumulator (BIGD): both roundings run on the FMA unit.  The step is
+// the bit pattern of the same FMA as in update_fast minus the bit pattern of its offset (folded into one constant
+// added with comp); the last stage is alg1_small.
 template <bool DECAY, bool BIGD>
 __device__ __forceinline__ void update_small(const StepParams& p, int th, int c, float gf, int& tn, int& cn, Track& tr)
 {
@@ -177,12 +158,8 @@ __device__ __forceinline__ void update_small(const StepParams& p, int th, int c,
     s += __double2loint(r) - p.magic_dlo;
   }
   const int v = (int)((unsigned)th << p.d) + (c + p.bias_i) + s;
-  tr.vmx = v > tr.vmx ? v : tr.vmx;
-  tr.vmn = v < tr.vmn ? v : tr.vmn;
-  const float q = __builtin_amdgcn_fmed3f(__builtin_fmaf((float)v, p.inv2d_f, 12582912.0f), p.lo_tf, p.hi_tf);
-  tn = __float_as_int(q);
-  if (BIGD) cn = med3_i32(mad_i24(tn - 0x4B400000, p.neg2d, v), p.qmin_c, p.qmax_c);      // 0x4B400000 = bits(1.5 * 2^23)
-  else      cn = med3_i32(mad_i24(tn, p.neg2d, v), p.lo_cb, p.hi_cb);
+  track_v(tr.vt, v);
+  alg1_small<BIGD>(p.sm, v, tn, cn);
 }
 
 // 16 consecutive elements of one lane.  WT / WC = widths of theta and comp; GS = gradient source.
@@ -291,8 +268,7 @@ __device__ __forceinline__ void compute_store_group(const StepParams& p, const W
 
 __device__ __forceinline__ uint64_t track_max(const Track& tr)
 {
-  int64_t a = tr.vmx, b = -(int64_t)tr.vmn;
-  const uint64_t m32 = (uint64_t)(a > b ? a : b), m64 = (uint64_t)tr.vw;
+  const uint64_t m32 = vtrack_max(tr.vt), m64 = (uint64_t)tr.vw;
   return m32 > m64 ? m32 : m64;
 }
 
@@ -300,25 +276,14 @@ __device__ __forceinline__ uint64_t track_max(const Track& tr)
 template <int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
 __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max, LazyRun& lz)
 {
-  Track tr{0, 0, ab_max, 0.0, 0, 0};
+  Track tr{{0, 0}, ab_max, 0.0, 0, 0};
   const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
   constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : (GS == kGradI8 ? 4 : 8));     // VGPRs of one group
   constexpr int kP = kRegs <= 16 ? (LAZY == kLazyNone ? LPK_I16_GROUPS : LPK_I16_GROUPS_LAZY) : LPK_KP_WIDE;   // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
-  uint32_t gi = lane;
-  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
-    Group<WT, WC, GS> G[kP];
-#pragma unroll
-    for (int ps = 0; ps < kP; ++ps) load_group(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
-#pragma unroll
-    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, MODE, LAZY>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
-  }
-  for (; gi < ngroups; gi += kWave) {
-    Group<WT, WC, GS> G;
-    const uint64_t e = off + (uint64_t)gi * kGroup;
-    load_group(G, T, e);
-    compute_store_group<WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, e, tr);
-  }
+  walk_groups<kP, Group<WT, WC, GS>>(ngroups, lane,
+      [&](Group<WT, WC, GS>& G, uint32_t gi) LPK_INLINE_LAMBDA { load_group(G, T, off + (uint64_t)gi * kGroup); },
+      [&](const Group<WT, WC, GS>& G, uint32_t gi) LPK_INLINE_LAMBDA { compute_store_group<WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, off + (uint64_t)gi * kGroup, tr); });
   ab_max = tr.ab;
   if (LAZY != kLazyNone) {                                 // most of this tile's groups dense in theta / in comp?
     const bool mt = 2 * (uint32_t)wave_uniform(tr.dense_t) * kWave > ngroups, mc = 2 * (uint32_t)wave_uniform(tr.dense_c) * kWave > ngroups;
@@ -403,23 +368,12 @@ __device__ __forceinline__ void compute_store_group_e(const StepParams& p, const
 template <int E, int KP, int WT, int WC, int GS, bool DECAY, int MODE, int LAZY>
 __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max, LazyRun& lz)
 {
-  Track tr{0, 0, ab_max, 0.0, 0, 0};
+  Track tr{{0, 0}, ab_max, 0.0, 0, 0};
   const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
   const uint32_t ngroups = cnt / E;
-  uint32_t gi = lane;
-  for (; gi + (KP - 1) * kWave < ngroups; gi += KP * kWave) {
-    GroupE<E, WT, WC, GS> G[KP];
-#pragma unroll
-    for (int ps = 0; ps < KP; ++ps) load_group_e(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
-#pragma unroll
-    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, MODE, LAZY>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
-  }
-  for (; gi < ngroups; gi += kWave) {
-    GroupE<E, WT, WC, GS> G;
-    const uint64_t e = off + (uint64_t)gi * E;
-    load_group_e(G, T, e);
-    compute_store_group_e<E, WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, e, tr);
-  }
+  walk_groups<KP, GroupE<E, WT, WC, GS>>(ngroups, lane,
+      [&](GroupE<E, WT, WC, GS>& G, uint32_t gi) LPK_INLINE_LAMBDA { load_group_e(G, T, off + (uint64_t)gi * E); },
+      [&](const GroupE<E, WT, WC, GS>& G, uint32_t gi) LPK_INLINE_LAMBDA { compute_store_group_e<E, WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, off + (uint64_t)gi * E, tr); });
   ab_max = tr.ab;
   if (LAZY != kLazyNone) {                                 // most of this tile's groups dense in theta / in comp?
     const bool mt = 2 * (uint32_t)wave_uniform(tr.dense_t) * kWave > ngroups, mc = 2 * (uint32_t)wave_uniform(tr.dense_c) * kWave > ngroups;
@@ -491,19 +445,14 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   p.magic_d   = __longlong_as_double(md);
   p.magic_dlo = (int)(md & 0xffffffffll);
   p.nlrwd_d   = -(double)p.lrwd;
-  p.half_m1   = (1 << (p.d - 1)) - 1;
+  p.in = Alg1Int{p.d, (1 << (p.d - 1)) - 1, p.qmin_t, p.qmax_t, p.qmin_c, p.qmax_c};
   // small-value variant, int8 theta: |v| plus the rounding addend below 2^22 and (2^22 + theta') * 2^d inside int32
   // (int8 accumulator, d <= 8), or below 2^23 with the residual formed unshifted (int16 accumulator, d <= 22);
   // either way v is exact in fp32 and the quotient sits inside the 2^22 window of the 1.5 * 2^23 offset
   if (p.wt == 8 && p.wc == 8 && p.d <= 8 && bound < (1ll << 22)) p.mode = kModeSmall;
   if (p.wt == 8 && p.wc == 16 && p.d <= 22 && bound < (1ll << 23)) p.mode = kModeSmall;
   p.bias_i  = -p.magic_fi;
-  p.inv2d_f = __uint_as_float((uint32_t)(127 - p.d) << 23);
-  p.lo_tf   = 12582912.0f + (float)p.qmin_t;
-  p.hi_tf   = 12582912.0f + (float)p.qmax_t;
-  p.neg2d   = -(1 << p.d);
-  p.lo_cb   = p.qmin_c - (1 << (22 + (p.d <= 8 ? p.d : 8)));
-  p.hi_cb   = p.qmax_c - (1 << (22 + (p.d <= 8 ? p.d : 8)));
+  p.sm = make_alg1_small(p.d, p.qmin_t, p.qmax_t, p.qmin_c, p.qmax_c);
 }
 
 // ---------------------------------------------------------------- the kernel
@@ -578,46 +527,41 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint64_t s_max[kWavesPerBlock];
 
-  const int lane   = threadIdx.x & (kWave - 1);
-  const int wave   = wave_uniform(threadIdx.x >> 6);
-  const uint32_t w0 = blockIdx.x * kWavesPerBlock + wave;
-  const uint32_t nw = gridDim.x * kWavesPerBlock;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = wave_uniform(threadIdx.x >> 6);
 
-  int cur = -1;
   uint64_t lane_max = 0;
   uint32_t status_bits = 0, ab_max = 0;
   StepParams p; p.path = 0;
   TensorDev T;
   LazyRun lz{0, kLazyNone};
 
-  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
-    int t; uint32_t cnt; uint64_t off;
-    read_tile(tiles, ti, t, cnt, off);
-    if (t != cur) {
-      if (cur >= 0 && vmax) flush_wave(vmax, cur, lane_max, lane);
+  const int cur = walk_tiles(tiles, n_tiles,
+    [&](int t) LPK_INLINE_LAMBDA { if (vmax) flush_wave(vmax, t, lane_max, lane); },
+    [&](int t) LPK_INLINE_LAMBDA {
       lane_max = 0;
-      cur = t;
       T = tensors[t];
       setup_tensor<GS, WITH_I8>(p, T, fl_in[t], fl_out[t], fl_g[t], lr, wd, status_bits);
-    }
-    uint64_t vm = 0;
-    if (p.path == 2) {
-      if (WITH_I8 && p.wt == 8 && GS == kGradI16 && p.wg == 8) {       // int8 gradient array (8-bit training mode)
-        constexpr int G8 = GS == kGradI16 ? kGradI8 : GS;
-        if (p.wc == 8) vm = tile_vector<8, 8, G8, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
-        else           vm = tile_vector<8, 16, G8, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+    },
+    [&](uint64_t off, uint32_t cnt) LPK_INLINE_LAMBDA {
+      uint64_t vm = 0;
+      if (p.path == 2) {
+        if (WITH_I8 && p.wt == 8 && GS == kGradI16 && p.wg == 8) {       // int8 gradient array (8-bit training mode)
+          constexpr int G8 = GS == kGradI16 ? kGradI8 : GS;
+          if (p.wc == 8) vm = tile_vector<8, 8, G8, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+          else           vm = tile_vector<8, 16, G8, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+        }
+        else if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+        else if (p.wt == 16)             vm = tile_vector<16, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+        else                             vm = tile_vector<8, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
+      } else if (p.path == 1) {
+        vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
       }
-      else if (p.wt == 8 && p.wc == 8) vm = tile_vector<8, 8, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
-      else if (p.wt == 16)             vm = tile_vector<16, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
-      else                             vm = tile_vector<8, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
-    } else if (p.path == 1) {
-      vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
-    }
-    lane_max = vm > lane_max ? vm : lane_max;
-  }
+      lane_max = vm > lane_max ? vm : lane_max;
+    });
 
   if (GS == kGradF32 && __ballot(ab_max >= 0x7f800000u)) status_bits |= kStatusNonFinite;
-  if (status && status_bits && lane == 0) atomicOr(status, status_bits);
+  raise_status(status, status_bits, lane);
 
   // LDS stage: the four waves of a block usually end on the same tensor.
   if (vmax) flush_block(vmax, cur, lane_max, lane, wave, s_tensor, s_max);

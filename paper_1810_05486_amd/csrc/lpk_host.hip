@@ -34,7 +34,7 @@ struct lpk_tensor_list {
   uint32_t   grid_quant = 0;       // blocks of the quantization launch (4 bytes read : 2 written, out of place)
   uint32_t   grid_step = 0;        // blocks of the plain update launches with lazy stores (read-dominated)
   uint32_t   grid_dense = 0;       // blocks of update launches that write everything (plain with LPK_OPT_STORE_ALL, momentum)
-  uint32_t   grid_adam = 0;        // blocks of the ADAM launch (two waves per SIMD: arithmetic and memory time are about equal)
+  uint32_t   grid_adam = 0;        // blocks of the ADAM launch
   bool       all_src   = false;    // every non-empty tensor has an fp32 source
   bool       all_mom   = false;    // every non-empty tensor has a velocity buffer
   bool       all_sec   = false;    // ... and a second-moment buffer

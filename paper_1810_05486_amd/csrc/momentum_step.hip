@@ -28,10 +28,10 @@ struct MomParams {
   int      c2, b2, h2, nz2;                // (-lr << a2) * g -> grid G
   int      a3, b3, h3, nz3;                // m' -> grid F
   double   nlrwd_d, magic_d;  int magic_dlo;
-  int      half_m1;                        // rounding addend of v -> theta
-  // wide path: mu * 2^-k1, -lr * 2^-k2, -lr * wd * 2^-k3w, 2^-k3, 2^d, 2^u, 2^-kth, 2^kth, 2^-kc, rails
-  double   w_a1, w_a2, w_a3, w_inv_k3, w_p2d, w_p2u, w_inv_kth, w_p2kth, w_inv_kc;
-  double   w_lo_t, w_hi_t, w_lo_c, w_hi_c, w_lo_m, w_hi_m;
+  Alg1Int  in;                             // last stage of Algorithm 1 by add-and-shift
+  // wide path: mu * 2^-k1, -lr * 2^-k2, -lr * wd * 2^-k3w, 2^-k3, the velocity's rails, the last stage's constants
+  double   w_a1, w_a2, w_a3, w_inv_k3, w_lo_m, w_hi_m;
+  Alg1Wide wa;
 };
 
 struct WideMax { double v, w; };
@@ -48,13 +48,8 @@ __device__ __forceinline__ void update_wide_mom(const MomParams& p, int th, int 
   mx.w = __builtin_fmax(mx.w, __builtin_fabs(mq));
   const double mn = clampd(mq, p.w_lo_m, p.w_hi_m);
   const double s = clampd(__builtin_rint(mn * p.w_inv_k3), -cap, cap);
-  const double v = __builtin_fma((double)th, p.w_p2d, (double)c) + s;
-  mx.v = __builtin_fmax(mx.v, __builtin_fabs(v));
-  const double vG = v * p.w_p2u;
-  const double tn = clampd(__builtin_rint(vG * p.w_inv_kth), p.w_lo_t, p.w_hi_t);
-  const double rr = __builtin_fma(-tn, p.w_p2kth, vG);      // exact below 2^53; beyond that comp saturates either way
-  const double cn = clampd(__builtin_rint(rr * p.w_inv_kc), p.w_lo_c, p.w_hi_c);
-  th_new = (int)tn; c_new = (int)cn; m_new = (int)mn;
+  alg1_wide(p.wa, th, c, s, th_new, c_new, mx.v);
+  m_new = (int)mn;
 }
 
 __device__ __forceinline__ void fold_wide(const WideMax& mx, uint64_t& vm, uint64_t& wm)
@@ -86,7 +81,7 @@ __device__ __forceinline__ void tile_generic_mom(const MomParams& p, const Tenso
 
 // ---------------------------------------------------------------- fast path
 
-struct MaxTrack { int vmx, vmn, wmx, wmn; };
+struct MaxTrack { VTrack v, w; };                      // extremes of the compensated sum and of the unsaturated velocity
 
 template <bool DECAY, bool K1ZERO, bool WIDEW>
 __device__ __forceinline__ void update_fast_mom(const MomParams& p, int th, int c, int m, int g, int& tn, int& cn, int& mn, MaxTrack& mt)
@@ -106,17 +101,12 @@ __device__ __forceinline__ void update_fast_mom(const MomParams& p, int th, int 
     const int w = t1 + t2;
     q = (w + 0x7fff + ((w >> 16) & 1)) >> 16;                        // RNE(w / 2^16)
   }
-  mt.wmx = q > mt.wmx ? q : mt.wmx;
-  mt.wmn = q < mt.wmn ? q : mt.wmn;
+  track_v(mt.w, q);
   mn = min(max(q, p.qmin_m), p.qmax_m);
-  int s = rne_shr32((int)((unsigned)mn << p.a3), p.b3, p.h3, p.nz3);
-  int v = (int)((unsigned)th << p.d) + c + s;
-  mt.vmx = v > mt.vmx ? v : mt.vmx;
-  mt.vmn = v < mt.vmn ? v : mt.vmn;
-  int qt = (v + p.half_m1 + ((v >> p.d) & 1)) >> p.d;
-  tn = min(max(qt, p.qmin_t), p.qmax_t);
-  int r = v - (int)((unsigned)tn << p.d);
-  cn = min(max(r, p.qmin_c), p.qmax_c);
+  const int s = rne_shr32((int)((unsigned)mn << p.a3), p.b3, p.h3, p.nz3);
+  const int v = (int)((unsigned)th << p.d) + c + s;
+  track_v(mt.v, v);
+  alg1_int(p.in, v, tn, cn);
 }
 
 // E consecutive elements per lane.  WT / WC / WM = widths of theta, comp (WT, or 16 next to an 8-bit theta) and the
@@ -171,31 +161,18 @@ template <int WT, int WC, int WM, bool DECAY, bool K1ZERO, bool WIDE, int GS>
 __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane,
                                               uint64_t& vm, uint64_t& wm, uint32_t& ab)
 {
-  MaxTrack mt{0, 0, 0, 0};
+  MaxTrack mt{{0, 0}, {0, 0}};
   WideMax mx{0.0, 0.0};
   constexpr int E = (WT == 16 || WC == 16 || WM == 16 || GS == kGradF32) ? 8 : 16;   // fp32 gradients: two dwordx4 per lane, as in the plain update
   constexpr int kP = WIDE ? 1 : 4;                         // groups in flight (the wide path would set the kernel's register count)
   const uint32_t ngroups = cnt / E;
-  uint32_t gi = lane;
-  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {
-    MGroup<E, WT, WC, WM, GS> G[kP];
-#pragma unroll
-    for (int ps = 0; ps < kP; ++ps) load_group_mom(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
-#pragma unroll
-    for (int ps = 0; ps < kP; ++ps)
-      group_fast_mom<E, WT, WC, WM, DECAY, K1ZERO, WIDE, GS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, mt, mx, ab);
-  }
-  for (; gi < ngroups; gi += kWave) {
-    MGroup<E, WT, WC, WM, GS> G;
-    const uint64_t e = off + (uint64_t)gi * E;
-    load_group_mom(G, T, e);
-    group_fast_mom<E, WT, WC, WM, DECAY, K1ZERO, WIDE, GS>(p, G, T, e, mt, mx, ab);
-  }
-  int64_t a = mt.vmx, b = -(int64_t)mt.vmn;
-  uint64_t x = (uint64_t)(a > b ? a : b);
+  using Grp = MGroup<E, WT, WC, WM, GS>;
+  walk_groups<kP, Grp>(ngroups, lane,
+      [&](Grp& G, uint32_t gi) LPK_INLINE_LAMBDA { load_group_mom(G, T, off + (uint64_t)gi * E); },
+      [&](const Grp& G, uint32_t gi) LPK_INLINE_LAMBDA { group_fast_mom<E, WT, WC, WM, DECAY, K1ZERO, WIDE, GS>(p, G, T, off + (uint64_t)gi * E, mt, mx, ab); });
+  uint64_t x = vtrack_max(mt.v);
   vm = x > vm ? x : vm;
-  a = mt.wmx; b = -(int64_t)mt.wmn;
-  x = (uint64_t)(a > b ? a : b);
+  x = vtrack_max(mt.w);
   wm = x > wm ? x : wm;
   fold_wide(mx, vm, wm);
   const uint32_t tail = cnt - ngroups * E;
@@ -244,8 +221,7 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   p.qmax_m = (1 << (p.wm - 1)) - 1; p.qmin_m = -(1 << (p.wm - 1));
   p.w_a1 = (double)mu * pow2d(-p.k1); p.w_a2 = -(double)lr * pow2d(-p.k2); p.w_a3 = -(double)p.lrwd * pow2d(-p.k3w);
   p.w_inv_k3 = pow2d(-p.k3);
-  p.w_p2d = pow2d(p.d); p.w_p2u = pow2d(p.u); p.w_inv_kth = pow2d(-p.kth); p.w_p2kth = pow2d(p.kth); p.w_inv_kc = pow2d(-p.kc);
-  p.w_lo_t = (double)p.qmin_t; p.w_hi_t = (double)p.qmax_t; p.w_lo_c = (double)p.qmin_c; p.w_hi_c = (double)p.qmax_c;
+  p.wa = make_alg1_wide(p.d, p.u, p.kth, p.kc, p.qmin_t, p.qmax_t, p.qmin_c, p.qmax_c);
   p.w_lo_m = (double)p.qmin_m; p.w_hi_m = (double)p.qmax_m;
   p.gscale = __uint_as_float((uint32_t)(127 + fl_g) << 23);
   p.glo = -(float)(1 << (p.wg - 1)); p.ghi = (float)((1 << (p.wg - 1)) - 1);
@@ -298,7 +274,7 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   p.magic_d   = __longlong_as_double(md);
   p.magic_dlo = (int)(md & 0xffffffffll);
   p.nlrwd_d   = -(double)p.lrwd;
-  p.half_m1   = (1 << (p.d - 1)) - 1;
+  p.in = Alg1Int{p.d, (1 << (p.d - 1)) - 1, p.qmin_t, p.qmax_t, p.qmin_c, p.qmax_c};
 }
 
 // ---------------------------------------------------------------- the kernel
@@ -313,46 +289,41 @@ momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restri
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint64_t s_max[kWavesPerBlock];
 
-  const int lane   = threadIdx.x & (kWave - 1);
-  const int wave   = wave_uniform(threadIdx.x >> 6);
-  const uint32_t w0 = blockIdx.x * kWavesPerBlock + wave;
-  const uint32_t nw = gridDim.x * kWavesPerBlock;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = wave_uniform(threadIdx.x >> 6);
 
-  int cur = -1;
   uint64_t vm = 0, wm = 0;
   uint32_t status_bits = 0, ab_max = 0;
   MomParams p; p.path = 0;
   TensorDev T;
 
-  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
-    int t; uint32_t cnt; uint64_t off;
-    read_tile(tiles, ti, t, cnt, off);
-    if (t != cur) {
-      if (cur >= 0) {
-        if (vmax) flush_wave(vmax, cur, vm, lane);
-        if (mmax) flush_wave(mmax, cur, wm, lane);
-      }
+  const int cur = walk_tiles(tiles, n_tiles,
+    [&](int t) LPK_INLINE_LAMBDA {
+      if (vmax) flush_wave(vmax, t, vm, lane);
+      if (mmax) flush_wave(mmax, t, wm, lane);
+    },
+    [&](int t) LPK_INLINE_LAMBDA {
       vm = wm = 0;
-      cur = t;
       T = tensors[t];
       setup_mom<GS>(p, T, fl_in[t], fl_out[t], fl_m_in[t], fl_m_out[t], fl_g[t], lr, mu, wd, status_bits);
-    }
-    if (p.path == 2) {
-      if (p.wt == 8 && GS == kGradI16 && p.wg == 8) {       // int8 gradient array (8-bit training mode)
-        constexpr int G8 = GS == kGradI16 ? kGradI8 : GS;
-        if (p.wc == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, 8, G8>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 8, 16, G8>(p, T, off, cnt, lane, vm, wm, ab_max); }
-        else           { if (p.wm == 8) tile_fast_mom_dispatch<8, 16, 8, G8>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<8, 16, 16, G8>(p, T, off, cnt, lane, vm, wm, ab_max); }
+    },
+    [&](uint64_t off, uint32_t cnt) LPK_INLINE_LAMBDA {
+      if (p.path == 2) {
+        if (p.wt == 8 && GS == kGradI16 && p.wg == 8) {       // int8 gradient array (8-bit training mode)
+          constexpr int G8 = GS == kGradI16 ? kGradI8 : GS;
+          if (p.wc == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, 8, G8>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 8, 16, G8>(p, T, off, cnt, lane, vm, wm, ab_max); }
+          else           { if (p.wm == 8) tile_fast_mom_dispatch<8, 16, 8, G8>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<8, 16, 16, G8>(p, T, off, cnt, lane, vm, wm, ab_max); }
+        }
+        else if (p.wt == 8 && p.wc == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+        else if (p.wt == 8)              { if (p.wm == 8) tile_fast_mom_dispatch<8, 16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<8, 16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+        else                             { if (p.wm == 8) tile_fast_mom_dispatch<16, 16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<16, 16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
+      } else if (p.path == 1) {
+        tile_generic_mom<GS>(p, T, off, cnt, lane, vm, wm, ab_max);
       }
-      else if (p.wt == 8 && p.wc == 8) { if (p.wm == 8) tile_fast_mom_dispatch<8, 8, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max);  else tile_fast_mom_dispatch<8, 8, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
-      else if (p.wt == 8)              { if (p.wm == 8) tile_fast_mom_dispatch<8, 16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<8, 16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
-      else                             { if (p.wm == 8) tile_fast_mom_dispatch<16, 16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<16, 16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
-    } else if (p.path == 1) {
-      tile_generic_mom<GS>(p, T, off, cnt, lane, vm, wm, ab_max);
-    }
-  }
+    });
 
   if (GS == kGradF32 && __ballot(ab_max >= 0x7f800000u)) status_bits |= kStatusNonFinite;
-  if (status && status_bits && lane == 0) atomicOr(status, status_bits);
+  raise_status(status, status_bits, lane);
   if (vmax) flush_block(vmax, cur, vm, lane, wave, s_tensor, s_max);
   if (mmax) flush_block(mmax, cur, wm, lane, wave, s_tensor, s_max);
 }

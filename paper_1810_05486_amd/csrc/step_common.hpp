@@ -1,5 +1,7 @@
-// Pieces shared by the update kernels (plain lazy update, momentum, ADAM): exact fp64 helpers of the wide
-// arithmetic, element and vector accesses, byte/halfword unpacking, the per-tensor vmax flush.
+// Pieces shared by the update kernels (plain lazy update, momentum, ADAM): the persistent walk over the tile table,
+// the groups-in-flight loop of a tile, the last stage of Algorithm 1 (compensated sum -> new parameter and new
+// accumulator) in its three arithmetic forms, exact fp64 helpers, element and vector accesses, byte/halfword
+// unpacking, the per-tensor maxima flush, stores that skip unchanged data.
 #pragma once
 #include "lpk_device.hpp"
 
@@ -189,6 +191,142 @@ __device__ __forceinline__ void flush_block(uint64_t* vmax, int cur, uint64_t la
     }
   }
   __syncthreads();
+}
+
+// ---------------------------------------------------------------- the walk over the tile table
+//
+// The callables handed to walk_tiles / walk_groups are lambdas that capture the kernel's state by reference; they
+// must be inlined (LPK_INLINE_LAMBDA after the parameter list), or that state is forced out of registers into
+// scratch memory.
+#define LPK_INLINE_LAMBDA __attribute__((always_inline))
+//
+// A persistent grid of wavefronts: wave w takes tiles w, w + W, w + 2W, ... of the table, so at any moment the grid
+// streams one contiguous window of the parameter set.  `leave(t)` runs when the walk moves on from tensor t (flush
+// its maxima), `enter(t)` when it reaches a tile of another tensor (load its descriptor, derive its constants),
+// `tile(off, cnt)` for every tile; all three are wave-uniform.  Returns the tensor the wave ended on, -1 if it
+// had no tile.
+template <typename Leave, typename Enter, typename TileFn>
+__device__ __forceinline__ int walk_tiles(const Tile* __restrict__ tiles, uint32_t n_tiles, Leave&& leave, Enter&& enter, TileFn&& tile)
+{
+  const uint32_t w0 = blockIdx.x * kWavesPerBlock + (uint32_t)wave_uniform(threadIdx.x >> 6);
+  const uint32_t nw = gridDim.x * kWavesPerBlock;
+  int cur = -1;
+  for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
+    int t; uint32_t cnt; uint64_t off;
+    read_tile(tiles, ti, t, cnt, off);
+    if (t != cur) {
+      if (cur >= 0) leave(cur);
+      cur = t;
+      enter(t);
+    }
+    tile(off, cnt);
+  }
+  return cur;
+}
+
+// The groups of one tile: lane l takes groups l, l + 64, ...; KP groups are in flight together (all their loads
+// are issued before the first of them is computed and stored), the remainder one at a time.  `load(G&, gi)` fills a
+// group from memory, `work(const G&, gi)` computes and stores it; gi = index of the group inside the tile.
+template <int KP, typename G, typename LoadFn, typename WorkFn>
+__device__ __forceinline__ void walk_groups(uint32_t ngroups, int lane, LoadFn&& load, WorkFn&& work)
+{
+  uint32_t gi = lane;
+  for (; gi + (KP - 1) * kWave < ngroups; gi += KP * kWave) {
+    G g[KP];
+#pragma unroll
+    for (int ps = 0; ps < KP; ++ps) load(g[ps], gi + ps * kWave);
+#pragma unroll
+    for (int ps = 0; ps < KP; ++ps) work(g[ps], gi + ps * kWave);
+  }
+  for (; gi < ngroups; gi += kWave) {
+    G g;
+    load(g, gi);
+    work(g, gi);
+  }
+}
+
+// End of a persistent update kernel: raise the status bits a wave collected.
+__device__ __forceinline__ void raise_status(uint32_t* status, uint32_t bits, int lane)
+{
+  if (status && bits && lane == 0) atomicOr(status, bits);
+}
+
+// ---------------------------------------------------------------- last stage of Algorithm 1
+//
+// v = theta * 2^d + c + s (the compensated sum on grid F) -> theta' = sat(RNE(v on theta's new grid)),
+// c' = sat(RNE((v - theta') on the accumulator's new grid)), and the running maximum of |v|.  Three forms with
+// identical results; which one a tensor takes is decided per tensor from its shifts (wave-uniform).
+
+// wide: exact fp64, any shifts of the domain (grid moves included).  Every quantity is an integer below 2^53 times
+// a power of two, so sums and power-of-two scalings are exact and v_rndne_f64 is the RNE of the definition.  The
+// residual v_G - theta' * 2^kth is exact while it is below 2^53; beyond that the accumulator saturates whatever the
+// last bits are.
+struct Alg1Wide { double p2d, p2u, inv_kth, p2kth, inv_kc, lo_t, hi_t, lo_c, hi_c; };
+
+__device__ __forceinline__ Alg1Wide make_alg1_wide(int d, int u, int kth, int kc, int qmin_t, int qmax_t, int qmin_c, int qmax_c)
+{
+  Alg1Wide a;
+  a.p2d = pow2d(d); a.p2u = pow2d(u); a.inv_kth = pow2d(-kth); a.p2kth = pow2d(kth); a.inv_kc = pow2d(-kc);
+  a.lo_t = (double)qmin_t; a.hi_t = (double)qmax_t; a.lo_c = (double)qmin_c; a.hi_c = (double)qmax_c;
+  return a;
+}
+
+__device__ __forceinline__ void alg1_wide(const Alg1Wide& a, int th, int c, double s, int& tn, int& cn, double& vabs_max)
+{
+  const double v = __builtin_fma((double)th, a.p2d, (double)c) + s;
+  vabs_max = __builtin_fmax(vabs_max, __builtin_fabs(v));
+  const double vG = v * a.p2u;
+  const double t = clampd(__builtin_rint(vG * a.inv_kth), a.lo_t, a.hi_t);
+  const double rr = __builtin_fma(-t, a.p2kth, vG);
+  const double cc = clampd(__builtin_rint(rr * a.inv_kc), a.lo_c, a.hi_c);
+  tn = (int)t; cn = (int)cc;
+}
+
+// Running extremes of a 32-bit v (its |maximum| is folded into the tensor's 64-bit maximum at the end of a tile).
+struct VTrack { int vmx, vmn; };
+__device__ __forceinline__ void track_v(VTrack& t, int v) { t.vmx = v > t.vmx ? v : t.vmx; t.vmn = v < t.vmn ? v : t.vmn; }
+__device__ __forceinline__ uint64_t vtrack_max(const VTrack& t)
+{
+  const int64_t a = t.vmx, b = -(int64_t)t.vmn;
+  return (uint64_t)(a > b ? a : b);
+}
+
+// int: theta's grid fixed, 1 <= d, |v| + 2^(d-1) < 2^31 shown by the caller.  RNE(v / 2^d) by add-and-shift.
+struct Alg1Int { int d, half_m1, qmin_t, qmax_t, qmin_c, qmax_c; };         // half_m1 = 2^(d-1) - 1
+
+__device__ __forceinline__ void alg1_int(const Alg1Int& a, int v, int& tn, int& cn)
+{
+  const int q = (v + a.half_m1 + ((v >> a.d) & 1)) >> a.d;
+  tn = min(max(q, a.qmin_t), a.qmax_t);
+  cn = min(max(v - (int)((unsigned)tn << a.d), a.qmin_c), a.qmax_c);
+}
+
+// small: int8 theta, theta's grid fixed, |v| plus the rounding addend below 2^22 (int8 accumulator, d <= 8) or
+// 2^23 (int16 accumulator, d <= 22: BIGD).  v is exact in fp32; with M = 1.5 * 2^23 (ulp 1), fma(v, 2^-d, M) is
+// M + RNE(v / 2^d) after its single IEEE rounding, clamped as a float between M + qmin and M + qmax.  The low 24
+// bits of that float are 2^22 + theta', so one 24-bit multiply-add forms v - theta' * 2^d - 2^(22 + d); the
+// accumulator rails are shifted by the same constant, and the low bytes of both results are the bytes to store.
+// BIGD: (2^22 + theta') * 2^d no longer fits 32 bits, so theta' is first taken out of the float's bit pattern and
+// the residual is formed and clamped unshifted.  tn holds theta' in its LOW BYTE only.
+struct Alg1Small { float inv2d_f, lo_tf, hi_tf; int neg2d, lo_cb, hi_cb, lo_c, hi_c; };
+
+__device__ __forceinline__ Alg1Small make_alg1_small(int d, int qmin_t, int qmax_t, int qmin_c, int qmax_c)
+{
+  Alg1Small a;
+  a.inv2d_f = __uint_as_float((uint32_t)(127 - d) << 23);
+  a.lo_tf = 12582912.0f + (float)qmin_t; a.hi_tf = 12582912.0f + (float)qmax_t;
+  a.neg2d = -(1 << d);
+  a.lo_c = qmin_c; a.hi_c = qmax_c;
+  a.lo_cb = qmin_c - (1 << (22 + (d <= 8 ? d : 8))); a.hi_cb = qmax_c - (1 << (22 + (d <= 8 ? d : 8)));
+  return a;
+}
+
+template <bool BIGD>
+__device__ __forceinline__ void alg1_small(const Alg1Small& a, int v, int& tn, int& cn)
+{
+  tn = __float_as_int(__builtin_amdgcn_fmed3f(__builtin_fmaf((float)v, a.inv2d_f, 12582912.0f), a.lo_tf, a.hi_tf));
+  if (BIGD) cn = med3_i32(mad_i24(tn - 0x4B400000, a.neg2d, v), a.lo_c, a.hi_c);        // 0x4B400000 = bits(1.5 * 2^23)
+  else      cn = med3_i32(mad_i24(tn, a.neg2d, v), a.lo_cb, a.hi_cb);
 }
 
 // ---------------------------------------------------------------- stores that skip unchanged data

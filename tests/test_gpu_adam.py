@@ -119,6 +119,70 @@ def test_adam_config5_full_size_in_bench_launch_configuration(fused):
     run_config(workloads.config(5), range(2), fused=fused)
 
 
+def make_case(rng, n, tb, cb, mb, ub, gb, d, fls, mis=0, sec_lo=0, sec_hi=None, gmax=None, extremes=False):
+    """One tensor of a hand-made list: random theta / comp / moments / gradients of the given widths on the host and in
+    device buffers shifted by `mis` elements.  fls = (fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g)."""
+    c = dict(n=n, tb=tb, cb=cb, mb=mb, ub=ub, gb=gb, d=d, fls=list(fls))
+    c["theta"] = rng.integers(-(2 ** (tb - 1)), 2 ** (tb - 1), size=n).astype(NP[tb])
+    c["comp"] = rng.integers(-(2 ** (cb - 1)), 2 ** (cb - 1), size=n).astype(NP[cb]) if cb else None
+    c["mom"] = rng.integers(-(2 ** (mb - 1)), 2 ** (mb - 1), size=n).astype(NP[mb])
+    c["sec"] = rng.integers(sec_lo, sec_hi if sec_hi is not None else 2 ** (ub - 1), size=n).astype(NP[ub])
+    glim = gmax if gmax is not None else 2 ** (gb - 1)
+    c["grad"] = rng.integers(-glim, glim, size=n).astype(NP[gb])
+    if extremes and n >= 16:                       # rails of every operand against each other
+        lo_m, hi_m, lo_g, hi_g = -(2 ** (mb - 1)), 2 ** (mb - 1) - 1, -(2 ** (gb - 1)), 2 ** (gb - 1) - 1
+        c["mom"][:8] = [hi_m, hi_m, lo_m, lo_m, 0, 0, 1, -1]
+        c["grad"][:8] = [hi_g, lo_g, hi_g, lo_g, hi_g, lo_g, 0, 0]
+        c["sec"][:8] = [0, 2 ** (ub - 1) - 1, 0, 2 ** (ub - 1) - 1, 1, 2, 3, 0]
+        c["sec"][8:16] = [0, 1, 2, 3, 4, 15, 16, 17]
+        c["grad"][8:16] = 0
+
+    def dev(a, bits):
+        buf = torch.zeros(n + 64, dtype=TT[bits], device=DEV)
+        v = buf[mis:mis + n]
+        v.copy_(torch.from_numpy(a))
+        return buf, v
+    c["bufs"] = []
+    for key, bits in (("theta", tb), ("comp", cb), ("mom", mb), ("sec", ub), ("grad", gb)):
+        if c[key] is None:
+            c["d_" + key] = None
+            continue
+        b, v = dev(c[key], bits)
+        c["bufs"].append(b); c["d_" + key] = v
+    return c
+
+
+def run_list(cases, hyper):
+    """One lpk_adam_step over the list, the oracle tensor by tensor on the host copies, everything compared."""
+    tl = lpk.TensorList([lpk.make_desc(c["d_theta"], c["d_comp"], c["d_grad"], None,
+                                       c["d"] if c["cb"] and c["d"] is not None else lpk.LPK_COMP_SHIFT_DEFAULT,
+                                       momentum=c["d_mom"], second=c["d_sec"]) for c in cases])
+    i32 = dict(dtype=torch.int32, device=DEV)
+    arr = [torch.tensor([c["fls"][j] for c in cases], **i32) for j in range(7)]
+    vmax, mmax, umax = (torch.full((len(cases),), 5 + k, dtype=torch.int64, device=DEV) for k in range(3))
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    lpk.lpk_adam_step(tl, arr[0], arr[1], arr[2], arr[3], arr[4], arr[5], arr[6], hyper, vmax, mmax, umax, status)
+    torch.cuda.synchronize()
+    st = ref.new_status()
+    for i, c in enumerate(cases):
+        dd = c["d"] if c["d"] is not None else (c["cb"] - 1 if c["cb"] else 0)
+        f = c["fls"]
+        want = ref.adam_step(c["theta"], c["comp"], c["mom"], c["sec"], c["grad"], dd, f[0], f[1], f[2], f[3], f[4], f[5], f[6],
+                             *hyper, status=st)
+        ctx = {k: c[k] for k in ("n", "tb", "cb", "mb", "ub", "gb", "d", "fls")}
+        ctx.update(hyper=hyper, i=i)
+        assert np.array_equal(c["d_theta"].cpu().numpy(), c["theta"]), ("theta", ctx)
+        if c["cb"]:
+            assert np.array_equal(c["d_comp"].cpu().numpy(), c["comp"]), ("comp", ctx)
+        assert np.array_equal(c["d_mom"].cpu().numpy(), c["mom"]), ("mom", ctx)
+        assert np.array_equal(c["d_sec"].cpu().numpy(), c["sec"]), ("sec", ctx)
+        got = (int(vmax[i].item()), int(mmax[i].item()), int(umax[i].item()))
+        assert got == want, ("max", got, want, ctx)
+    assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
+    tl.destroy()
+    return int(st[0])
+
+
 @pytest.mark.parametrize("seed", fuzz_seeds(4))
 def test_adam_random_lists(seed):
     """Random widths, shifts, grid moves, alignments, sizes and hyper-parameters straight through the C ABI,
@@ -143,58 +207,49 @@ def test_adam_random_lists(seed):
             fl_u_in = 2 * fl_g + pr.choice([0, -3, pr.randint(-25, 8), pr.randint(-40, 30)])
             fl_u_out = fl_u_in + pr.choice([0, 0, 0, 0, 1, -1, pr.randint(-15, 15)])
             fls = [max(-64, min(64, f)) for f in (fl_in, fl_in + delta, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g)]
-            n = pr.choice(sizes)
-            mis = pr.choice([0, 0, 0, 1, 8, 16])
-            c = dict(n=n, tb=tb, cb=cb, mb=mb, ub=ub, gb=gb, d=d, fls=fls)
-            c["theta"] = rng.integers(-(2 ** (tb - 1)), 2 ** (tb - 1), size=n).astype(NP[tb])
-            c["comp"] = rng.integers(-(2 ** (cb - 1)), 2 ** (cb - 1), size=n).astype(NP[cb]) if cb else None
-            c["mom"] = rng.integers(-(2 ** (mb - 1)), 2 ** (mb - 1), size=n).astype(NP[mb])
             lo_u = pr.choice([0, 0, 0, -(2 ** (ub - 1))])                       # mostly valid (non-negative) second moments
-            c["sec"] = rng.integers(lo_u, pr.choice([4, 300, 2 ** (ub - 1)]), size=n).astype(NP[ub])
-            c["grad"] = rng.integers(-(2 ** (gb - 1)), 2 ** (gb - 1), size=n).astype(NP[gb])
-
-            def dev(a, bits):
-                buf = torch.zeros(n + 64, dtype=TT[bits], device=DEV)
-                v = buf[mis:mis + n]
-                v.copy_(torch.from_numpy(a))
-                return buf, v
-            c["bufs"] = []
-            for key, bits in (("theta", tb), ("comp", cb), ("mom", mb), ("sec", ub), ("grad", gb)):
-                if c[key] is None:
-                    c["d_" + key] = None
-                    continue
-                b, v = dev(c[key], bits)
-                c["bufs"].append(b); c["d_" + key] = v
-            cases.append(c)
+            cases.append(make_case(rng, pr.choice(sizes), tb, cb, mb, ub, gb, d, fls, mis=pr.choice([0, 0, 0, 1, 8, 16]),
+                                   sec_lo=lo_u, sec_hi=pr.choice([4, 300, 2 ** (ub - 1)])))
         hyper = (pr.choice([1, 66, 21000, 65535]), pr.choice([0, 0, 4, 11, pr.randint(0, 48)]),
                  pr.choice([58982, 32768, 0, 65535]), pr.choice([65470, 58982, 0, 65535]),
                  pr.choice([0, 43980, 65535, 1]), pr.choice([0, 26, 10, pr.randint(0, 48)]))
-        tl = lpk.TensorList([lpk.make_desc(c["d_theta"], c["d_comp"], c["d_grad"], None,
-                                           c["d"] if c["cb"] and c["d"] is not None else lpk.LPK_COMP_SHIFT_DEFAULT,
-                                           momentum=c["d_mom"], second=c["d_sec"]) for c in cases])
-        i32 = dict(dtype=torch.int32, device=DEV)
-        arr = [torch.tensor([c["fls"][j] for c in cases], **i32) for j in range(7)]
-        vmax, mmax, umax = (torch.full((len(cases),), 5 + k, dtype=torch.int64, device=DEV) for k in range(3))
-        status = torch.zeros(1, dtype=torch.int32, device=DEV)
-        lpk.lpk_adam_step(tl, arr[0], arr[1], arr[2], arr[3], arr[4], arr[5], arr[6], hyper, vmax, mmax, umax, status)
-        torch.cuda.synchronize()
-        st = ref.new_status()
-        for i, c in enumerate(cases):
-            dd = c["d"] if c["d"] is not None else (c["cb"] - 1 if c["cb"] else 0)
-            f = c["fls"]
-            want = ref.adam_step(c["theta"], c["comp"], c["mom"], c["sec"], c["grad"], dd, f[0], f[1], f[2], f[3], f[4], f[5], f[6],
-                                 *hyper, status=st)
-            ctx = {k: c[k] for k in ("n", "tb", "cb", "mb", "ub", "gb", "d", "fls")}
-            ctx.update(hyper=hyper, i=i)
-            assert np.array_equal(c["d_theta"].cpu().numpy(), c["theta"]), ("theta", ctx)
-            if c["cb"]:
-                assert np.array_equal(c["d_comp"].cpu().numpy(), c["comp"]), ("comp", ctx)
-            assert np.array_equal(c["d_mom"].cpu().numpy(), c["mom"]), ("mom", ctx)
-            assert np.array_equal(c["d_sec"].cpu().numpy(), c["sec"]), ("sec", ctx)
-            got = (int(vmax[i].item()), int(mmax[i].item()), int(umax[i].item()))
-            assert got == want, ("max", got, want, ctx)
-        assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
-        tl.destroy()
+        run_list(cases, hyper)
+
+
+@pytest.mark.parametrize("seed", fuzz_seeds(3))
+def test_adam_standing_grids_around_every_condition_of_the_short_route(seed):
+    """The usual case of a running optimizer -- 16-bit moments on grids that stand still, an int8 theta, a small step --
+    takes a shorter arithmetic route inside the kernel (fp32 FMA roundings for the first moment and the root, integer
+    rounding for the second moment, a reciprocal without refinement).  Lists of aligned tensors whose fraclens and
+    hyper-parameters sit on both sides of each condition of that route (first-moment grid 0..8 bits finer than the
+    gradient's, or coarser, or further; (1 - beta2) g^2 below / above 2^30 on the second moment's guard grid; step bound
+    below / above 2^22; accumulator 8 or 16 bits wide; theta 16 bits wide), operands on their rails, ragged sizes."""
+    say("adam: standing grids around the short route's conditions, seed %d" % seed)
+    rng = np.random.default_rng(1300 + seed)
+    pr = random.Random(1400 + seed)
+    for rep in range(10):
+        b1 = pr.choice([58982, 58982, 32768, 65535, 1, 62259])
+        b2 = pr.choice([65470, 65470, 64881, 65535, 58982])
+        lr_q, lr_exp = pr.choice([(33554, 9), (65535, 9), (40000, 4), (33554, 14), (21000, 7), (65535, 2)])
+        eps_q, eps_exp = pr.choice([(43980, 26), (0, 0), (65535, 0), (1, 48), (40000, 12)])
+        hyper = (lr_q, lr_exp, b1, b2, eps_q, eps_exp)
+        cases = []
+        for _ in range(pr.randint(3, 9)):
+            tb, cb = pr.choice([(8, 8), (8, 8), (8, 8), (8, 16), (16, 16)])
+            fl_g = pr.randint(8, 30)
+            sh = pr.choice([0, 0, 1, 2, 3, 8, 8, 9, -1, 5])
+            fl_m = fl_g + sh
+            sh2 = pr.choice([-6, -7, -7, -8, -11, -11, -15, -20, -3])
+            fl_u = 2 * fl_g + sh2
+            fl_t = pr.choice([7, 7, 5, 10]) if tb == 8 else pr.choice([15, 12])
+            if not all(-64 <= f <= 64 for f in (fl_t, fl_m, fl_u, fl_g)):
+                continue
+            gmax = pr.choice([None, None, 3000, 40])
+            cases.append(make_case(rng, pr.choice([16, 4096, 4097, 8200, 33000, 70001]), tb, cb, 16, 16, 16, None,
+                                   (fl_t, fl_t, fl_m, fl_m, fl_u, fl_u, fl_g), sec_hi=pr.choice([None, 300, 4]), gmax=gmax,
+                                   extremes=True))
+        if cases:
+            run_list(cases, hyper)
 
 
 def test_adam_argument_errors():
