@@ -438,7 +438,7 @@ def main():
     ap.add_argument("--no-traffic", action="store_true", help="do not run the two rocprofv3 counter passes")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the secondary measurements (regimes, ceilings, int16 path, small configs, graph replay)")
-    ap.add_argument("--traffic-timeout", type=int, default=240, help="seconds allowed per rocprofv3 counter pass")
+    ap.add_argument("--traffic-timeout", type=int, default=150, help="seconds allowed per rocprofv3 counter pass")
     ap.add_argument("--traffic-child", default="", help=argparse.SUPPRESS)
     ap.add_argument("--write-traffic", default="", help="also write the measured traffic figures to this JSON file")
     ap.add_argument("--cpu-sample", type=int, default=1 << 30,
@@ -450,10 +450,12 @@ def main():
     if args.traffic_child:
         return traffic_child(args)
 
-    # counter passes first: child processes are started before this process initialises the GPU
+    # Counter passes first: the child processes are started before this process initialises the GPU.  Importing torch
+    # (no GPU call yet) pages the libraries in, so that on a fresh machine the children do not spend their time limit
+    # on that.
+    import torch
     traffic = None if args.no_traffic else measure_traffic(args)
 
-    import torch
     from paper_1810_05486_amd import workloads
     from paper_1810_05486_amd import binding as lpk
 

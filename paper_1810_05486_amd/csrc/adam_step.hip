@@ -271,10 +271,20 @@ __device__ __forceinline__ void tile_vec_adam_x(const AdamParams& p, const Tenso
 {
   constexpr int E = LPK_ADAM_E, kP = LPK_ADAM_GROUPS;      // elements per lane per group, groups in flight per lane
   const uint32_t ngroups = cnt / E;
-  using Grp = AGroup<E, WT, WC, GS>;
-  walk_groups<kP, Grp>(ngroups, lane,
-      [&](Grp& G, uint32_t gi) LPK_INLINE_LAMBDA { load_group_adam(G, T, off + (uint64_t)gi * E); },
-      [&](const Grp& G, uint32_t gi) LPK_INLINE_LAMBDA { group_adam<E, WT, WC, CAPS, TAIL, EXACT3, GS, FAST>(p, G, T, off + (uint64_t)gi * E, tr, ab); });
+  uint32_t gi = lane;
+  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {             // kP groups in flight: all loads, then compute and store
+    AGroup<E, WT, WC, GS> G[kP];
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps) load_group_adam(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps) group_adam<E, WT, WC, CAPS, TAIL, EXACT3, GS, FAST>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr, ab);
+  }
+  for (; gi < ngroups; gi += kWave) {
+    AGroup<E, WT, WC, GS> G;
+    const uint64_t e = off + (uint64_t)gi * E;
+    load_group_adam(G, T, e);
+    group_adam<E, WT, WC, CAPS, TAIL, EXACT3, GS, FAST>(p, G, T, e, tr, ab);
+  }
   const uint32_t tail = cnt - ngroups * E;
   if (tail) tile_generic_adam<CAPS, GS>(p, T, off + (uint64_t)ngroups * E, tail, lane, tr, ab);
 }

@@ -281,9 +281,20 @@ __device__ __forceinline__ uint64_t tile_fast(const StepParams& p, const TensorD
   constexpr int kRegs = (WT + WC) / 2 + (GS == kGradF32 ? 16 : (GS == kGradI8 ? 4 : 8));     // VGPRs of one group
   constexpr int kP = kRegs <= 16 ? (LAZY == kLazyNone ? LPK_I16_GROUPS : LPK_I16_GROUPS_LAZY) : LPK_KP_WIDE;   // groups in flight per lane
   const uint32_t ngroups = cnt / kGroup;
-  walk_groups<kP, Group<WT, WC, GS>>(ngroups, lane,
-      [&](Group<WT, WC, GS>& G, uint32_t gi) LPK_INLINE_LAMBDA { load_group(G, T, off + (uint64_t)gi * kGroup); },
-      [&](const Group<WT, WC, GS>& G, uint32_t gi) LPK_INLINE_LAMBDA { compute_store_group<WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, off + (uint64_t)gi * kGroup, tr); });
+  uint32_t gi = lane;
+  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {             // kP groups in flight: all loads, then compute and store
+    Group<WT, WC, GS> G[kP];
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps) load_group(G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup);
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps) compute_store_group<WT, WC, GS, DECAY, MODE, LAZY>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * kGroup, tr);
+  }
+  for (; gi < ngroups; gi += kWave) {
+    Group<WT, WC, GS> G;
+    const uint64_t e = off + (uint64_t)gi * kGroup;
+    load_group(G, T, e);
+    compute_store_group<WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, e, tr);
+  }
   ab_max = tr.ab;
   if (LAZY != kLazyNone) {                                 // most of this tile's groups dense in theta / in comp?
     const bool mt = 2 * (uint32_t)wave_uniform(tr.dense_t) * kWave > ngroups, mc = 2 * (uint32_t)wave_uniform(tr.dense_c) * kWave > ngroups;
@@ -371,9 +382,20 @@ __device__ __forceinline__ uint64_t tile_fast_e(const StepParams& p, const Tenso
   Track tr{{0, 0}, ab_max, 0.0, 0, 0};
   const WideParams w = MODE == kModeWide ? make_wide(p) : WideParams{};
   const uint32_t ngroups = cnt / E;
-  walk_groups<KP, GroupE<E, WT, WC, GS>>(ngroups, lane,
-      [&](GroupE<E, WT, WC, GS>& G, uint32_t gi) LPK_INLINE_LAMBDA { load_group_e(G, T, off + (uint64_t)gi * E); },
-      [&](const GroupE<E, WT, WC, GS>& G, uint32_t gi) LPK_INLINE_LAMBDA { compute_store_group_e<E, WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, off + (uint64_t)gi * E, tr); });
+  uint32_t gi = lane;
+  for (; gi + (KP - 1) * kWave < ngroups; gi += KP * kWave) {             // KP groups in flight: all loads, then compute and store
+    GroupE<E, WT, WC, GS> G[KP];
+#pragma unroll
+    for (int ps = 0; ps < KP; ++ps) load_group_e(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
+#pragma unroll
+    for (int ps = 0; ps < KP; ++ps) compute_store_group_e<E, WT, WC, GS, DECAY, MODE, LAZY>(p, w, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, tr);
+  }
+  for (; gi < ngroups; gi += kWave) {
+    GroupE<E, WT, WC, GS> G;
+    const uint64_t e = off + (uint64_t)gi * E;
+    load_group_e(G, T, e);
+    compute_store_group_e<E, WT, WC, GS, DECAY, MODE, LAZY>(p, w, G, T, e, tr);
+  }
   ab_max = tr.ab;
   if (LAZY != kLazyNone) {                                 // most of this tile's groups dense in theta / in comp?
     const bool mt = 2 * (uint32_t)wave_uniform(tr.dense_t) * kWave > ngroups, mc = 2 * (uint32_t)wave_uniform(tr.dense_c) * kWave > ngroups;

@@ -166,10 +166,21 @@ __device__ __forceinline__ void tile_fast_mom(const MomParams& p, const TensorDe
   constexpr int E = (WT == 16 || WC == 16 || WM == 16 || GS == kGradF32) ? 8 : 16;   // fp32 gradients: two dwordx4 per lane, as in the plain update
   constexpr int kP = WIDE ? 1 : 4;                         // groups in flight (the wide path would set the kernel's register count)
   const uint32_t ngroups = cnt / E;
-  using Grp = MGroup<E, WT, WC, WM, GS>;
-  walk_groups<kP, Grp>(ngroups, lane,
-      [&](Grp& G, uint32_t gi) LPK_INLINE_LAMBDA { load_group_mom(G, T, off + (uint64_t)gi * E); },
-      [&](const Grp& G, uint32_t gi) LPK_INLINE_LAMBDA { group_fast_mom<E, WT, WC, WM, DECAY, K1ZERO, WIDE, GS>(p, G, T, off + (uint64_t)gi * E, mt, mx, ab); });
+  uint32_t gi = lane;
+  for (; gi + (kP - 1) * kWave < ngroups; gi += kP * kWave) {             // kP groups in flight: all loads, then compute and store
+    MGroup<E, WT, WC, WM, GS> G[kP];
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps) load_group_mom(G[ps], T, off + (uint64_t)(gi + ps * kWave) * E);
+#pragma unroll
+    for (int ps = 0; ps < kP; ++ps)
+      group_fast_mom<E, WT, WC, WM, DECAY, K1ZERO, WIDE, GS>(p, G[ps], T, off + (uint64_t)(gi + ps * kWave) * E, mt, mx, ab);
+  }
+  for (; gi < ngroups; gi += kWave) {
+    MGroup<E, WT, WC, WM, GS> G;
+    const uint64_t e = off + (uint64_t)gi * E;
+    load_group_mom(G, T, e);
+    group_fast_mom<E, WT, WC, WM, DECAY, K1ZERO, WIDE, GS>(p, G, T, e, mt, mx, ab);
+  }
   uint64_t x = vtrack_max(mt.v);
   vm = x > vm ? x : vm;
   x = vtrack_max(mt.w);

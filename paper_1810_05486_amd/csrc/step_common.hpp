@@ -195,9 +195,9 @@ __device__ __forceinline__ void flush_block(uint64_t* vmax, int cur, uint64_t la
 
 // ---------------------------------------------------------------- the walk over the tile table
 //
-// The callables handed to walk_tiles / walk_groups are lambdas that capture the kernel's state by reference; they
-// must be inlined (LPK_INLINE_LAMBDA after the parameter list), or that state is forced out of registers into
-// scratch memory.
+// The callables handed to walk_tiles are lambdas that capture the kernel's state by reference; they must be
+// inlined (LPK_INLINE_LAMBDA after the parameter list), or that state is forced out of registers into scratch
+// memory.
 #define LPK_INLINE_LAMBDA __attribute__((always_inline))
 //
 // A persistent grid of wavefronts: wave w takes tiles w, w + W, w + 2W, ... of the table, so at any moment the grid
@@ -222,27 +222,6 @@ __device__ __forceinline__ int walk_tiles(const Tile* __restrict__ tiles, uint32
     tile(off, cnt);
   }
   return cur;
-}
-
-// The groups of one tile: lane l takes groups l, l + 64, ...; KP groups are in flight together (all their loads
-// are issued before the first of them is computed and stored), the remainder one at a time.  `load(G&, gi)` fills a
-// group from memory, `work(const G&, gi)` computes and stores it; gi = index of the group inside the tile.
-template <int KP, typename G, typename LoadFn, typename WorkFn>
-__device__ __forceinline__ void walk_groups(uint32_t ngroups, int lane, LoadFn&& load, WorkFn&& work)
-{
-  uint32_t gi = lane;
-  for (; gi + (KP - 1) * kWave < ngroups; gi += KP * kWave) {
-    G g[KP];
-#pragma unroll
-    for (int ps = 0; ps < KP; ++ps) load(g[ps], gi + ps * kWave);
-#pragma unroll
-    for (int ps = 0; ps < KP; ++ps) work(g[ps], gi + ps * kWave);
-  }
-  for (; gi < ngroups; gi += kWave) {
-    G g;
-    load(g, gi);
-    work(g, gi);
-  }
 }
 
 // End of a persistent update kernel: raise the status bits a wave collected.

@@ -292,7 +292,62 @@ def test_host_side_argument_errors_with_a_live_list():
     assert L.lpk_select_fraclen(tl.handle, 3, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_select_fraclen(tl.handle, lpk.LPK_VMAX_U64, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_tensor_list_size(tl.handle) == 1 and L.lpk_tensor_list_tiles(tl.handle) == 1
+    # options: unknown code, launch-shape value out of range
+    assert L.lpk_tensor_list_set_option(tl.handle, 99, 1) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_tensor_list_set_option(tl.handle, lpk.LPK_OPT_STEP_BLOCKS_PER_CU, 65) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_tensor_list_set_option(tl.handle, lpk.LPK_OPT_STEP_BLOCKS_PER_CU, -1) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_tensor_list_set_option(None, lpk.LPK_OPT_STORE_ALL, 1) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_tensor_list_set_option(tl.handle, lpk.LPK_OPT_QUANT_BLOCKS_PER_CU, 64) == lpk.LPK_OK
     tl.destroy()
+
+
+@pytest.mark.parametrize("mode", ["plain", "momentum", "adam"])
+def test_results_do_not_depend_on_the_launch_shape(mode):
+    """Every family of kernels under 1, 3, 8 and 64 workgroups per CU (and back to the built-in choice) on a ragged
+    multi-tensor set and on a one-tensor workload: whole steps, bit for bit against the oracle."""
+    from paper_1810_05486_amd import workloads
+    from paper_1810_05486_amd.device_state import DeviceState
+    sys.path.insert(0, __file__.rsplit("/", 1)[0])
+    from oracle_state import OracleState, draw_grads
+    say("launch shapes, %s" % mode)
+    opts = (lpk.LPK_OPT_STEP_BLOCKS_PER_CU, lpk.LPK_OPT_DENSE_BLOCKS_PER_CU, lpk.LPK_OPT_ADAM_BLOCKS_PER_CU,
+            lpk.LPK_OPT_SCAN_BLOCKS_PER_CU, lpk.LPK_OPT_QUANT_BLOCKS_PER_CU)
+    for cfg in (workloads.config(3), workloads.config(5, big_elems=(1 << 21) + 5, n_tiny=3)):
+        nt = cfg.n_tensors
+        kw = dict(mom_bits=[16] * nt, fl_mom0=24) if mode != "plain" else {}
+        if mode == "adam":
+            kw.update(sec_bits=[16] * nt, fl_sec0=38)
+        dev, host = DeviceState(cfg, **kw), OracleState(cfg, **kw)
+        views = dev.host_src_views()
+        theta0 = [cfg.theta0(t, out=views[t]).copy() for t in range(nt)]
+        dev.upload_src()
+        dev.init_theta()
+        host.init_theta(theta0)
+        for s, per_cu in enumerate((1, 3, 8, 64, 0)):
+            for o in opts:
+                lpk.lpk_tensor_list_set_option(dev.lists[0], o, per_cu)
+            grads = draw_grads(cfg, s, views)
+            dev.upload_src()
+            if mode == "adam":
+                hyper = workloads.adam_hyper(s)
+                dev.quantize_grads()
+                dev.update_adam(hyper)
+                host.update_adam(hyper, grads)
+            else:
+                mu = 58982 if mode == "momentum" else None
+                dev.step(s, mu_q16=mu)
+                host.step(s, grads, mu_q16=mu)
+            th, co, fl_t, fl_g, vm, status = dev.download()
+            ctx = (mode, cfg.id, per_cu)
+            assert status == int(host.status[0]) == 0, ctx
+            assert fl_g.tolist() == host.fl_grad and vm.tolist() == host.vmax, ctx
+            for t in range(nt):
+                assert np.array_equal(th[t], host.theta[t]) and np.array_equal(co[t], host.comp[t]), (ctx, t)
+                if mode != "plain":
+                    assert np.array_equal(dev.mom[t].cpu().numpy(), host.mom[t]), (ctx, t)
+                if mode == "adam":
+                    assert np.array_equal(dev.sec[t].cpu().numpy(), host.sec[t]), (ctx, t)
+        dev.close()
 
 
 def test_fused_step_with_special_gradient_values():
