@@ -56,7 +56,7 @@ typedef enum {
   LPK_ERR_INVALID_ARG = -1,  /* NULL where forbidden, bad dtype / selector code, n_tensors == 0,
                                 misaligned pointer, lr/wd above 65535; nothing was launched   */
   LPK_ERR_UNSUPPORTED = -2,  /* a well-formed request this build does not implement          */
-  LPK_ERR_DEVICE      = -3   /* a HIP runtime call failed (allocation, copy, launch)         */
+  LPK_ERR_DEVICE      = -3   /* a HIP runtime call failed (allocation, copy, launch), or host memory ran out */
 } lpk_status_code;
 
 typedef enum { LPK_I8 = 1, LPK_I16 = 2, LPK_F32 = 4, LPK_VMAX_U64 = 8 } lpk_dtype;

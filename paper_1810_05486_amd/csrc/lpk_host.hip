@@ -83,21 +83,25 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
   if (out) *out = nullptr;
   if (!descs || !out || n_tensors == 0) return LPK_ERR_INVALID_ARG;
 
-  std::vector<TensorDev> tensors(n_tensors);
+  std::vector<TensorDev> tensors;
   std::vector<Tile> tiles;
   ListFacts facts;
-  for (uint32_t t = 0; t < n_tensors; ++t) {
-    const int rc = describe_tensor(descs[t], tensors[t], facts);
-    if (rc != LPK_OK) return rc;
-  }
-  const uint64_t total_tiles = facts.total_tiles;
-  if (total_tiles >= (1ull << 31)) return LPK_ERR_UNSUPPORTED;
-  tiles.reserve((size_t)total_tiles);
-  for (uint32_t t = 0; t < n_tensors; ++t)
-    for (uint64_t off = 0; off < descs[t].n; off += kTileElems) {
-      const uint64_t left = descs[t].n - off;
-      tiles.push_back(Tile{t, (uint32_t)(left < (uint64_t)kTileElems ? left : (uint64_t)kTileElems), off});
+  try {                                              // no exception may cross the C boundary
+    tensors.resize(n_tensors);
+    for (uint32_t t = 0; t < n_tensors; ++t) {
+      const int rc = describe_tensor(descs[t], tensors[t], facts);
+      if (rc != LPK_OK) return rc;
     }
+    if (facts.total_tiles >= (1ull << 31)) return LPK_ERR_UNSUPPORTED;
+    tiles.reserve((size_t)facts.total_tiles);
+    for (uint32_t t = 0; t < n_tensors; ++t)
+      for (uint64_t off = 0; off < descs[t].n; off += kTileElems) {
+        const uint64_t left = descs[t].n - off;
+        tiles.push_back(Tile{t, (uint32_t)(left < (uint64_t)kTileElems ? left : (uint64_t)kTileElems), off});
+      }
+  } catch (...) {
+    return LPK_ERR_DEVICE;                           // host memory for the tables could not be had
+  }
 
   lpk_tensor_list* L = new (std::nothrow) lpk_tensor_list;
   if (!L) return LPK_ERR_DEVICE;

@@ -12,8 +12,10 @@
 // l, l + 64, ... of the wave's piece of the array -- the friendliest form for the memory system, the one the table
 // of ceilings uses) and "lane-consecutive" (a lane's words are adjacent in memory, so a wave's access has a stride of
 // words * 16 bytes between lanes -- what a kernel does when one lane owns 16 consecutive parameters of every
-// array).  `groups` passes of a wave are in flight together: all their loads are issued before the first store,
-// as in the update kernels.
+// array).  A third layout halves the unit to 8 parameters per lane ("half units": an int8 array is then read and
+// written 8 bytes per lane, a 16-bit one 16 bytes per lane, coalesced) -- the shape of the kernels whose state
+// includes a 16-bit array.  `groups` passes of a wave are in flight together: all their loads are issued before the
+// first store, as in the update kernels.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
@@ -36,63 +38,90 @@ template <int... WM> struct Mix {
   static constexpr int total_words() { int t = 0; for (int i = 0; i < n; ++i) t += code[i] >> 2; return t; }
 };
 
-// Word index of a lane's k-th word of an array with `words` words per unit, in the pass that starts at unit ub.
-template <bool COALESCED> __device__ __forceinline__ uint64_t word_at(uint64_t ub, int lane, int words, int k)
+typedef unsigned v2u __attribute__((ext_vector_type(2)));
+
+// One lane's share of one array in one pass, as up to four 16-byte registers.
+//   LAYOUT 0 (coalesced): words k * 64 + lane of the pass's piece of the array, k < words.
+//   LAYOUT 1 (lane-consecutive): words lane * words + k.
+//   LAYOUT 2 (half units, 8 parameters per lane): an array of `words` words per 16 parameters holds words * 8 bytes
+//     per lane: one 8-byte access when words == 1, else words / 2 coalesced 16-byte accesses.
+template <int LAYOUT>
+__device__ __forceinline__ void load_share(v4u (&r)[4], const v4u* base, uint64_t ub, int lane, int words)
 {
-  return COALESCED ? ub * words + (uint64_t)k * kWave + lane : (ub + lane) * words + k;
+  if (LAYOUT == 2) {
+    if (words == 1) {
+      const v2u x = __builtin_nontemporal_load((const MEMBW_GLOBAL v2u*)((const v2u*)base + ub + lane));
+      r[0] = v4u{x[0], x[1], 0u, 0u};
+    } else {
+#pragma unroll
+      for (int k = 0; k < words / 2; ++k)
+        r[k] = __builtin_nontemporal_load((const MEMBW_GLOBAL v4u*)(base + ub * (words / 2) + (uint64_t)k * kWave + lane));
+    }
+    return;
+  }
+#pragma unroll
+  for (int k = 0; k < words; ++k)
+    r[k] = __builtin_nontemporal_load((const MEMBW_GLOBAL v4u*)(base + (LAYOUT == 0 ? ub * words + (uint64_t)k * kWave + lane : (ub + lane) * words + k)));
 }
 
-template <typename M, int KP, bool COALESCED>
+template <int LAYOUT>
+__device__ __forceinline__ void store_share(const v4u (&r)[4], v4u* base, uint64_t ub, int lane, int words)
+{
+  if (LAYOUT == 2) {
+    if (words == 1) {
+      __builtin_nontemporal_store(v2u{r[0][0], r[0][1]}, (MEMBW_GLOBAL v2u*)((v2u*)base + ub + lane));
+    } else {
+#pragma unroll
+      for (int k = 0; k < words / 2; ++k)
+        __builtin_nontemporal_store(r[k], (MEMBW_GLOBAL v4u*)(base + ub * (words / 2) + (uint64_t)k * kWave + lane));
+    }
+    return;
+  }
+#pragma unroll
+  for (int k = 0; k < words; ++k)
+    __builtin_nontemporal_store(r[k], (MEMBW_GLOBAL v4u*)(base + (LAYOUT == 0 ? ub * words + (uint64_t)k * kWave + lane : (ub + lane) * words + k)));
+}
+
+template <typename M, int KP, int LAYOUT>
 __global__ void __launch_bounds__(kBlock) membw_kernel(Ptrs p, uint64_t n_tiles, unsigned* sink)
 {
-  constexpr int TW = M::total_words();
   const int lane = threadIdx.x & (kWave - 1);
   const uint64_t w0 = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6), nw = (uint64_t)gridDim.x * kWavesPerBlock;
   v4u acc = {0u, 0u, 0u, 0u};
   for (uint64_t t = w0; t < n_tiles; t += nw) {
-    v4u r[KP][TW > 0 ? TW : 1];
+    v4u r[KP][M::n][4];
 #pragma unroll
     for (int ps = 0; ps < KP; ++ps) {
       const uint64_t ub = (t * KP + ps) * kWave;
-      int base = 0;
 #pragma unroll
       for (int i = 0; i < M::n; ++i) {
         const int words = M::code[i] >> 2, mode = M::code[i] & 3;
-        if (mode & kRead) {
 #pragma unroll
-          for (int k = 0; k < words; ++k)
-            r[ps][base + k] = __builtin_nontemporal_load((const MEMBW_GLOBAL v4u*)(p.a[i] + word_at<COALESCED>(ub, lane, words, k)));
-        }
-        base += words;
+        for (int k = 0; k < 4; ++k) r[ps][i][k] = v4u{0u, 0u, 0u, 0u};
+        if (mode & kRead) load_share<LAYOUT>(r[ps][i], p.a[i], ub, lane, words);
       }
     }
 #pragma unroll
     for (int ps = 0; ps < KP; ++ps) {
       const uint64_t ub = (t * KP + ps) * kWave;
       v4u ro = {(unsigned)lane, 0u, 0u, 0u};                  // what the written words depend on: every read-only word
-      int base = 0;
 #pragma unroll
       for (int i = 0; i < M::n; ++i) {
-        const int words = M::code[i] >> 2, mode = M::code[i] & 3;
-        if (mode == kRead) {
+        if ((M::code[i] & 3) == kRead) {
 #pragma unroll
-          for (int k = 0; k < words; ++k) ro ^= r[ps][base + k];
+          for (int k = 0; k < 4; ++k) ro ^= r[ps][i][k];
         }
-        base += words;
       }
       acc ^= ro;
-      base = 0;
 #pragma unroll
       for (int i = 0; i < M::n; ++i) {
         const int words = M::code[i] >> 2, mode = M::code[i] & 3;
         if (mode & kWrite) {
+          v4u o[4];
 #pragma unroll
-          for (int k = 0; k < words; ++k) {
-            const v4u v = mode == kReadWrite ? (r[ps][base + k] ^ ro) : ro;
-            __builtin_nontemporal_store(v, (MEMBW_GLOBAL v4u*)(p.a[i] + word_at<COALESCED>(ub, lane, words, k)));
-          }
+          for (int k = 0; k < 4; ++k) o[k] = mode == kReadWrite ? (r[ps][i][k] ^ ro) : ro;
+          store_share<LAYOUT>(o, p.a[i], ub, lane, words);
         }
-        base += words;
       }
     }
   }
@@ -132,10 +161,11 @@ const MixInfo kMixes[] = {
 };
 constexpr int kNumMixes = sizeof(kMixes) / sizeof(kMixes[0]);
 
-template <typename M, bool C>
+// n_units: units of 16 parameters; a pass of the half-unit layout covers 64 * 8 parameters, the others 64 * 16.
+template <typename M, int C>
 hipError_t launch(int groups, uint32_t grid, const Ptrs& p, uint64_t n_units, unsigned* sink, hipStream_t s)
 {
-  const uint64_t n_tiles = n_units / ((uint64_t)groups * kWave);
+  const uint64_t n_tiles = (C == 2 ? 2 * n_units : n_units) / ((uint64_t)groups * kWave);
   if (n_tiles == 0) return hipSuccess;
   if (grid > (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock) grid = (uint32_t)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
   switch (groups) {
@@ -168,12 +198,12 @@ int membw_mix_describe(int mix, char* name, int name_cap, int* words, int* modes
 // Run one mix over n_units units (rounded down to whole tiles of groups * 64 units; every access stays inside the
 // first n_units * words * 16 bytes of each array).  arrays: host array of device pointers, one per array of the
 // mix, each 16-byte aligned and at least n_units * words * 16 bytes long, not overlapping.  groups in {1, 2, 4, 8};
-// blocks_per_cu >= 1; layout 0 = coalesced, 1 = lane-consecutive.  Only enqueues.
+// blocks_per_cu >= 1; layout 0 = coalesced, 1 = lane-consecutive, 2 = half units (8 parameters per lane).  Only enqueues.
 // Returns 0, or -1 for a bad argument, -3 for a HIP failure.
 int membw_run(int mix, int groups, int blocks_per_cu, int layout, void* const* arrays, uint64_t n_units, void* stream)
 {
   if (mix < 0 || mix >= kNumMixes || !arrays || blocks_per_cu < 1 || blocks_per_cu > 64) return -1;
-  if ((groups != 1 && groups != 2 && groups != 4 && groups != 8) || (layout != 0 && layout != 1)) return -1;
+  if ((groups != 1 && groups != 2 && groups != 4 && groups != 8) || layout < 0 || layout > 2) return -1;
   Ptrs p{};
   for (int i = 0; i < kMixes[mix].n; ++i) {
     if (!arrays[i] || ((uintptr_t)arrays[i] & 15u)) return -1;
@@ -185,7 +215,7 @@ int membw_run(int mix, int groups, int blocks_per_cu, int layout, void* const* a
   const uint32_t grid = (uint32_t)n_cu * (uint32_t)blocks_per_cu;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipErrorInvalidValue;
-#define MEMBW_CASE(id, M) case id: e = layout ? launch<M, false>(groups, grid, p, n_units, nullptr, s) : launch<M, true>(groups, grid, p, n_units, nullptr, s); break
+#define MEMBW_CASE(id, M) case id: e = layout == 0 ? launch<M, 0>(groups, grid, p, n_units, nullptr, s) : (layout == 1 ? launch<M, 1>(groups, grid, p, n_units, nullptr, s) : launch<M, 2>(groups, grid, p, n_units, nullptr, s)); break
   switch (mix) {
     MEMBW_CASE(0, MixRead);
     MEMBW_CASE(1, MixWrite);

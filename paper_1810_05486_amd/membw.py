@@ -65,7 +65,8 @@ class Runner:
         self.bytes_written = sum(w for w, m in self.arrays_desc if m & WRITE) * 16 * self.n_units
 
     def launch(self, groups=4, blocks_per_cu=1, layout=0):
-        """layout 0: coalesced accesses; 1: a lane's words adjacent in memory."""
+        """layout 0: coalesced accesses, 16 parameters per lane; 1: a lane's words adjacent in memory; 2: 8 parameters per
+        lane (an int8 array moves 8 bytes per lane and access, a 16-bit one 16), coalesced."""
         rc = lib().membw_run(self.mix, groups, blocks_per_cu, layout, self.ptrs, self.n_units,
                              self.torch.cuda.current_stream().cuda_stream)
         if rc != 0:
@@ -103,18 +104,21 @@ def main():
     torch.cuda.set_device(0)
     print("memory ceilings on %s: GB/s of the median of %d launches, %d units of 16 parameters (HBM peak 8000 GB/s)"
           % (torch.cuda.get_device_name(0), args.reps, args.units))
-    print("cells: GB/s (groups in flight of the best case) at 1 / 2 / 4 workgroups per CU; left: coalesced lane layout, "
-          "right: a lane's words adjacent in memory (differs only where an array has more than one word per unit)")
-    print("%-34s %8s %8s | %-38s | %s" % ("mix", "GB read", "GB writ.", "coalesced: 1, 2, 4 wg/CU", "lane-consecutive: 1, 2, 4 wg/CU"))
+    print("cells: GB/s (groups in flight of the best case) at 1 / 2 / 4 workgroups per CU.  Layouts: coalesced (16 parameters "
+          "per lane, every access of a wave one contiguous run); lane-consecutive (a lane's words adjacent in memory; "
+          "differs only where an array has more than one word per unit); half units (8 parameters per lane, coalesced: "
+          "an int8 array moves 8 bytes per lane and access)")
+    print("%-34s %8s %8s | %-32s | %-32s | %s" % ("mix", "GB read", "GB writ.", "coalesced: 1, 2, 4 wg/CU", "lane-consecutive: 1, 2, 4 wg/CU",
+                                                  "half units: 1, 2, 4 wg/CU"))
     for m, (name, desc) in enumerate(mixes()):
         r = Runner(m, args.units)
         cols = []
-        for layout in (0, 1):
+        for layout in (0, 1, 2):
             if layout == 1 and all(w == 1 for w, _ in desc):
                 cols.append("(same)")
                 continue
             cols.append("  ".join("%5.0f (%d)" % r.best(bpc, reps=args.reps, layout=layout) for bpc in (1, 2, 4)))
-        print("%-34s %8.2f %8.2f | %-38s | %s" % (name, r.bytes_read / 1e9, r.bytes_written / 1e9, cols[0], cols[1]), flush=True)
+        print("%-34s %8.2f %8.2f | %-32s | %-32s | %s" % (name, r.bytes_read / 1e9, r.bytes_written / 1e9, cols[0], cols[1], cols[2]), flush=True)
         del r
         torch.cuda.empty_cache()
 
