@@ -402,7 +402,7 @@ def measure_ceilings(args, n_params, mode_mix):
     units = min(n_params, 1 << 30) // 16
     out = {"unit": "GB/s", "note": "median of %d launches, best of 1/2/4 workgroups per CU and 1/2/4/8 groups in flight; "
                                    "no arithmetic, same accesses as the kernels (libmembw, outside the library's ABI)" % 10}
-    for name in ("read", "write", "copy", mode_mix):
+    for name in ("read", "write", "copy", "quantize", mode_mix):
         r = membw.Runner(name, units)
         best = max((r.best(b) + (b,)) for b in (1, 2, 4))
         out[r.name] = {"GB/s": best[0], "groups": best[1], "workgroups_per_cu": best[2], "frac_of_peak": best[0] / HBM_PEAK_GBS,
@@ -676,6 +676,11 @@ def main():
             out["ceilings"]["all_stores_kernel_over_its_mix"] = (nbytes / (regimes["all_stores"]["mean"] * 1e-3) / 1e9) / mix_gbs[0]
         elif mix_gbs:
             out["ceilings"]["update_kernel_over_its_mix"] = achieved / mix_gbs[0]
+        c = out["ceilings"]
+        qmix = [v["GB/s"] for k, v in c.items() if isinstance(v, dict) and k.startswith("quantize")]
+        if qmix and args.grad_bits == 16:
+            c["quantize_kernel_over_its_mix"] = out["other_kernels"]["quantize_kernel"]["GB/s"] / qmix[0]
+        c["maxabs_kernel_over_read"] = out["other_kernels"]["maxabs_f32_kernel"]["GB/s"] / c["read"]["GB/s"]
         if plain and args.config == 5 and not args.theta_bits and not args.comp_bits and args.grad_bits == 16:
             out["int16_update"] = measure_int16_update(args)
             out["small_configs"] = measure_small_configs(args)

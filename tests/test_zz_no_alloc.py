@@ -104,3 +104,15 @@ def test_noalloc_step_matches_the_list_step_on_two_calls_in_a_row():
     say("noalloc call 2: %d tensors, %d elements" % (len(specs2), sum(s[0] for s in specs2)))
     status = run_both(2, specs2, [7, 7, 15], [7, 7, 15], [18, 18, 18], 6554, 7, steps=2)
     assert status == 0
+
+
+def test_noalloc_step_with_many_staging_chunks():
+    """2001 tensors (51 staging launches of 40 descriptors): one multi-tile tensor and 2000 tensors of 256 elements, the
+    shape of the stress workload; then again after a call with other tables has overwritten the library's array."""
+    specs = [((1 << 20) + 4096 + 9, 8, 8, 16, 0)] + [(256, 8, 8, 16, 0)] * 2000
+    nt = len(specs)
+    say("noalloc: %d tensors" % nt)
+    assert run_both(3, specs, [7] * nt, [7] * nt, [19] * nt, 655, 0, steps=1) == 0
+    assert run_both(4, [(5000, 16, 16, 16, 0)], [15], [15], [18], 6554, 0, steps=1) == 0
+    assert run_both(5, specs, [7] * nt, [7] * nt, [18] * nt, 6554, 7, steps=1) == 0
+
