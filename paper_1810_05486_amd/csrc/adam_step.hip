@@ -6,7 +6,7 @@
 //   rt = floor(sqrt(u' * 2^(24+p)));  den = max(rt + eps_R, 1);  s = cap(RNE(-lr*m'*2^e / den))
 //   then Algorithm 1 with step s.
 //
-// Arithmetic: everything runs on the fp64 unit, and every value is exact.  Each intermediate above is an integer
+// Arithmetic, general route: everything runs on the fp64 unit, and every value is exact.  Each intermediate above is an integer
 // below 2^53 times a power of two (16-bit words times 17-bit constants, 2^40 caps, shifts of the documented
 // domain), so products, sums and scalings by powers of two are exact in binary64 and v_rndne_f64 is the
 // round-to-nearest-even of the definition, for every shift direction, without a branch.  The two inexact
