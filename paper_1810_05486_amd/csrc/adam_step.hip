@@ -391,7 +391,7 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
                  const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out,
                  const int32_t* __restrict__ fl_m_in, const int32_t* __restrict__ fl_m_out,
                  const int32_t* __restrict__ fl_u_in, const int32_t* __restrict__ fl_u_out, const int32_t* __restrict__ fl_g,
-                 AdamHyperDev h, uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status)
+                 AdamHyperDev h, uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, MaxFold fold)
 {
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint64_t s_max[kWavesPerBlock];
@@ -436,6 +436,7 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
   if (vmax) flush_block(vmax, cur, track_vmax(tr), lane, wave, s_tensor, s_max);
   if (mmax) flush_block(mmax, cur, track_m(tr), lane, wave, s_tensor, s_max);
   if (umax) flush_block(umax, cur, track_um(tr), lane, wave, s_tensor, s_max);
+  if (fold.arrivals) { uint64_t* const acc[3] = {vmax, mmax, umax}; fold_maxima<3>(fold, acc, &s_tensor[0]); }
 }
 
 __global__ void __launch_bounds__(kBlock) fill3_u64_kernel(uint64_t* a, uint64_t* b, uint64_t* c, uint32_t n)
@@ -447,17 +448,19 @@ __global__ void __launch_bounds__(kBlock) fill3_u64_kernel(uint64_t* a, uint64_t
 hipError_t launch_adam_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                             int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                             const int32_t* fl_u_in, const int32_t* fl_u_out, const int32_t* fl_g, AdamHyperDev h,
-                            uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, hipStream_t stream)
+                            uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, uint64_t* fold_acc, uint32_t* arrivals,
+                            hipStream_t stream)
 {
-  if (vmax || mmax || umax)
+  const MaxPlan m = plan_maxima(fold_acc, arrivals, n_tensors, n_tiles, grid, vmax, mmax, umax);
+  if ((vmax || mmax || umax) && !m.fold.arrivals)
     hipLaunchKernelGGL(fill3_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, mmax, umax, n_tensors);
   if (n_tiles) {
     if (grad_is_f32)
       hipLaunchKernelGGL(adam_step_kernel<kGradF32>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                         fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, h, vmax, mmax, umax, status);
+                         fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, h, m.acc[0], m.acc[1], m.acc[2], status, m.fold);
     else
       hipLaunchKernelGGL(adam_step_kernel<kGradI16>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                         fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, h, vmax, mmax, umax, status);
+                         fl_in, fl_out, fl_m_in, fl_m_out, fl_u_in, fl_u_out, fl_g, h, m.acc[0], m.acc[1], m.acc[2], status, m.fold);
   }
   return hipGetLastError();
 }

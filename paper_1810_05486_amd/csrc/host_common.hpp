@@ -67,6 +67,7 @@ inline uint32_t persistent_grid(uint32_t n_tiles, uint32_t n_cu, uint32_t per_cu
 
 hipError_t launch_kahan_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int grad_is_f32, const int32_t*, const int32_t*, const int32_t*, uint32_t lr, uint32_t wd,
-                             uint32_t store_all, uint32_t with_i8, uint64_t* vmax, uint32_t* status, hipStream_t);
+                             uint32_t store_all, uint32_t with_i8, uint64_t* vmax, uint32_t* status,
+                             uint64_t* fold_acc, uint32_t* arrivals, hipStream_t);
 
 }  // namespace lpk

@@ -544,7 +544,7 @@ template <int GS, bool STORE_ALL, bool WITH_I8>
 __global__ void __launch_bounds__(kBlock)
 kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                   const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out, const int32_t* __restrict__ fl_g,
-                  uint32_t lr, uint32_t wd, uint64_t* vmax, uint32_t* status)
+                  uint32_t lr, uint32_t wd, uint64_t* vmax, uint32_t* status, MaxFold fold)
 {
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint64_t s_max[kWavesPerBlock];
@@ -587,6 +587,7 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
 
   // LDS stage: the four waves of a block usually end on the same tensor.
   if (vmax) flush_block(vmax, cur, lane_max, lane, wave, s_tensor, s_max);
+  if (fold.arrivals) { uint64_t* const acc[1] = {vmax}; fold_maxima<1>(fold, acc, &s_tensor[0]); }
 }
 
 __global__ void __launch_bounds__(kBlock) fill_u64_kernel(uint64_t* p, uint32_t n, uint64_t v)
@@ -595,17 +596,19 @@ __global__ void __launch_bounds__(kBlock) fill_u64_kernel(uint64_t* p, uint32_t 
   if (i < n) p[i] = v;
 }
 
+// `fold_acc`, `arrivals`: the list's accumulators for per-tensor maxima and its workgroup counter (see plan_maxima),
+// or nullptr for a launch that has none.
 hipError_t launch_kahan_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                              int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_g,
                              uint32_t lr, uint32_t wd, uint32_t store_all, uint32_t with_i8, uint64_t* vmax, uint32_t* status,
-                             hipStream_t stream)
+                             uint64_t* fold_acc, uint32_t* arrivals, hipStream_t stream)
 {
-  if (vmax) {
+  const MaxPlan m = plan_maxima(fold_acc, arrivals, n_tensors, n_tiles, grid, vmax, nullptr, nullptr);
+  if (vmax && !m.fold.arrivals)
     hipLaunchKernelGGL(fill_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, n_tensors, 0ull);
-  }
   if (n_tiles) {
     auto go = [&](auto kernel) {
-      hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles, fl_in, fl_out, fl_g, lr, wd, vmax, status);
+      hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles, fl_in, fl_out, fl_g, lr, wd, m.acc[0], status, m.fold);
     };
     if (grad_is_f32)  { if (store_all) go(kahan_step_kernel<kGradF32, true, false>); else go(kahan_step_kernel<kGradF32, false, false>); }
     else if (with_i8) { if (store_all) go(kahan_step_kernel<kGradI16, true, true>);  else go(kahan_step_kernel<kGradI16, false, true>); }

@@ -61,6 +61,12 @@
 #ifndef LPK_Q_GROUPS
 #define LPK_Q_GROUPS 8        // such groups in flight per lane (with one workgroup per CU; measured best of 2-16 x 1-3)
 #endif
+#ifndef LPK_FOLD_MAX_TENSORS
+#define LPK_FOLD_MAX_TENSORS 4096   // lists up to this length (0: none) ...
+#endif
+#ifndef LPK_FOLD_MAX_BLOCKS
+#define LPK_FOLD_MAX_BLOCKS 128     // ... in launches of up to this many workgroups end their maxima in the last workgroup
+#endif
 #ifndef LPK_NT_LOAD
 #define LPK_NT_LOAD 1         // non-temporal hint on streaming loads
 #endif
@@ -144,5 +150,91 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
 }
 
 __device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// ---- ending a launch in its last workgroup ---------------------------------
+// Per-tensor maxima are gathered with atomics from every workgroup of a launch.  In small launches (up to
+// kFoldMaxBlocks workgroups, lists of up to kFoldMaxTensors tensors) the workgroup that finishes last turns them
+// into the call's outputs and re-arms the accumulators, which saves the launches that would otherwise clear before
+// and convert after: 5-6 us of the 28-34 us a whole step takes on parameter sets of up to two million elements.
+// Nobody waits for anybody: a workgroup counts itself in when its own atomics are performed, and the one that
+// counts last does the work.  Counting in costs every workgroup one atomic with a returned value on one shared
+// word, which the device serialises (about 10 ns each): at 256 workgroups that has eaten the gain, at 2048 it costs
+// 10 us per step, hence the limit.
+constexpr uint32_t kFoldMaxTensors = LPK_FOLD_MAX_TENSORS;
+constexpr uint32_t kFoldMaxBlocks  = LPK_FOLD_MAX_BLOCKS;
+
+// True in every thread of exactly one workgroup of the launch: the last to get here.  `arrivals` must be 0 when
+// the launch starts (the caller of this function puts it back); `s_flag` is one LDS word the block can spare.
+//
+// Only device-scope read-modify-write atomics carry data between the workgroups here (the maxima, the counter;
+// the last workgroup reads with atomic exchanges too), so every access to those words is performed at the one place
+// where the device performs its atomics; what has to be added is their order.  vmcnt(0) means that every atomic this
+// wave issued has been performed, the barrier extends that to the block, and only then does the block count itself
+// in, so the workgroup that reads gridDim.x - 1 reads after every maximum is in.  A device-scope fence is not used:
+// on this chip it writes back and invalidates the whole L2 of the XCD, and a few thousand workgroups doing that cost
+// four times the step (measured).
+__device__ __forceinline__ bool last_workgroup(uint32_t* arrivals, int* s_flag)
+{
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) *s_flag = atomicAdd(arrivals, 1u) == gridDim.x - 1;
+  __syncthreads();
+  return *s_flag != 0;
+}
+
+// Accumulators of up to three per-tensor maxima (in the list's own memory, zero between launches) and where the
+// call wants them.  arrivals == nullptr: the kernel's pointers are the outputs themselves, cleared by a launch before.
+struct MaxFold {
+  uint32_t* arrivals;
+  uint32_t  n_tensors;
+  uint64_t* out[3];
+};
+
+// Host side: where a launch gathers its maxima.  With the list's accumulators (`fold_acc`: three arrays of
+// n_tensors words; `arrivals`: its workgroup counter) in a launch small enough, the kernel gathers there and its last
+// workgroup fills the outputs; otherwise the kernel gathers in the outputs, which a launch before must clear.
+struct MaxPlan { MaxFold fold; uint64_t* acc[3]; };
+inline MaxPlan plan_maxima(uint64_t* fold_acc, uint32_t* arrivals, uint32_t n_tensors, uint32_t n_tiles, uint32_t grid,
+                           uint64_t* out0, uint64_t* out1, uint64_t* out2)
+{
+  uint64_t* const out[3] = {out0, out1, out2};
+  const bool fold = fold_acc && arrivals && n_tiles && n_tensors <= kFoldMaxTensors && grid <= kFoldMaxBlocks &&
+                    (out0 || out1 || out2);
+  MaxPlan p{};
+  p.fold.arrivals = fold ? arrivals : nullptr;
+  p.fold.n_tensors = n_tensors;
+  for (int i = 0; i < 3; ++i) {
+    p.fold.out[i] = out[i];
+    p.acc[i] = !fold ? out[i] : (out[i] ? fold_acc + (size_t)i * n_tensors : nullptr);
+  }
+  return p;
+}
+
+template <int N>
+__device__ __forceinline__ void fold_maxima(const MaxFold& f, uint64_t* const (&acc)[N], int* s_flag)
+{
+  if (!last_workgroup(f.arrivals, s_flag)) return;
+  constexpr int K = 4;                   // exchanges in flight per thread and array
+  for (uint32_t base = 0; base < f.n_tensors; base += K * kBlock) {
+    uint64_t v[N][K];
+#pragma unroll
+    for (int a = 0; a < N; ++a)
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        const uint32_t t = base + k * kBlock + threadIdx.x;
+        v[a][k] = 0;
+        if (acc[a] && t < f.n_tensors)   // read and re-arm in one atomic
+          v[a][k] = atomicExch((unsigned long long*)&acc[a][t], 0ull);
+      }
+#pragma unroll
+    for (int a = 0; a < N; ++a)
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        const uint32_t t = base + k * kBlock + threadIdx.x;
+        if (acc[a] && t < f.n_tensors) f.out[a][t] = v[a][k];
+      }
+  }
+  if (threadIdx.x == 0) atomicExch(f.arrivals, 0u);
+}
 
 }  // namespace lpk

@@ -7,7 +7,7 @@
 
 namespace lpk {
 hipError_t launch_select_f32(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                             int sel, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
+                             int sel, uint32_t* scratch, uint32_t* arrivals, const int32_t* fl_default, int32_t* fl_out,
                              uint32_t* status, hipStream_t);
 hipError_t launch_select_vmax(const TensorDev*, uint32_t n_tensors, int sel, const uint64_t* vmax,
                               const int32_t* fl_theta_in, const int32_t* fl_default, int32_t* fl_out, uint32_t* status,
@@ -17,11 +17,12 @@ hipError_t launch_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint
 hipError_t launch_momentum_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                                 int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                                 const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
-                                uint64_t* vmax, uint64_t* mmax, uint32_t* status, hipStream_t);
+                                uint64_t* vmax, uint64_t* mmax, uint32_t* status, uint64_t* fold_acc, uint32_t* arrivals, hipStream_t);
 hipError_t launch_adam_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                             int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                             const int32_t* fl_u_in, const int32_t* fl_u_out, const int32_t* fl_g, AdamHyperDev h,
-                            uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, hipStream_t);
+                            uint64_t* vmax, uint64_t* mmax, uint64_t* umax, uint32_t* status, uint64_t* fold_acc, uint32_t* arrivals,
+                            hipStream_t);
 }  // namespace lpk
 
 using namespace lpk;
@@ -44,7 +45,9 @@ struct lpk_tensor_list {
   uint32_t   per_cu[8] = {};       // launch-shape options by lpk_option code, 0 = the built-in default
   TensorDev* d_tensors = nullptr;
   Tile*      d_tiles   = nullptr;
-  uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls
+  uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls; then two workgroup counters (max-abs
+                                   // scan, update kernels), zero between launches
+  uint64_t*  d_fold    = nullptr;  // three per-tensor accumulators for the update kernels' maxima, zero between launches
 };
 
 // Launch shapes (workgroups of four waves per compute unit) of the persistent kernels; measured on MI355X.
@@ -119,12 +122,14 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     L->n_cu = (uint32_t)n_cu;
     set_grids(L);
     ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
-         hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * n_tensors) == hipSuccess &&
+         hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * ((size_t)n_tensors + 2)) == hipSuccess &&
+         hipMalloc((void**)&L->d_fold, sizeof(uint64_t) * 3 * (size_t)n_tensors) == hipSuccess &&
          (tiles.empty() || hipMalloc((void**)&L->d_tiles, sizeof(Tile) * tiles.size()) == hipSuccess);
   }
   if (ok) {
     ok = hipMemcpy(L->d_tensors, tensors.data(), sizeof(TensorDev) * n_tensors, hipMemcpyHostToDevice) == hipSuccess &&
-         hipMemset(L->d_scratch, 0, sizeof(uint32_t) * n_tensors) == hipSuccess &&
+         hipMemset(L->d_scratch, 0, sizeof(uint32_t) * ((size_t)n_tensors + 2)) == hipSuccess &&
+         hipMemset(L->d_fold, 0, sizeof(uint64_t) * 3 * (size_t)n_tensors) == hipSuccess &&
          (tiles.empty() || hipMemcpy(L->d_tiles, tiles.data(), sizeof(Tile) * tiles.size(), hipMemcpyHostToDevice) == hipSuccess) &&
          hipDeviceSynchronize() == hipSuccess;
   }
@@ -144,6 +149,7 @@ int lpk_tensor_list_destroy(lpk_tensor_list* L)
   if (L->d_tensors) ok &= hipFree(L->d_tensors) == hipSuccess;
   if (L->d_tiles)   ok &= hipFree(L->d_tiles) == hipSuccess;
   if (L->d_scratch) ok &= hipFree(L->d_scratch) == hipSuccess;
+  if (L->d_fold)    ok &= hipFree(L->d_fold) == hipSuccess;
   delete L;
   return ok ? LPK_OK : LPK_ERR_DEVICE;
 }
@@ -179,7 +185,7 @@ int lpk_select_fraclen(lpk_tensor_list* L, int src_kind, int dst_sel,
   if (src_kind == LPK_F32) {
     if (!L->all_src) return LPK_ERR_INVALID_ARG;
     e = launch_select_f32(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid, dst_sel,
-                          L->d_scratch, fl_default, fl_out, status, s);
+                          L->d_scratch, L->d_scratch + L->n_tensors, fl_default, fl_out, status, s);
   } else if (src_kind == LPK_VMAX_U64) {
     if (!vmax || !fl_theta_in) return LPK_ERR_INVALID_ARG;
     e = launch_select_vmax(L->d_tensors, L->n_tensors, dst_sel, vmax, fl_theta_in, fl_default, fl_out, status, s);
@@ -208,7 +214,7 @@ int lpk_kahan_sgd_step(lpk_tensor_list* L, const int32_t* fl_theta_in, const int
   if (!on_list_device(L)) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->store_all ? L->grid_dense : L->grid_step, 0, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, L->any_grad_i8 ? 1u : 0u, vmax_out, status,
-                                   static_cast<hipStream_t>(stream));
+                                   L->d_fold, L->d_scratch + L->n_tensors + 1, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
@@ -222,7 +228,7 @@ int lpk_kahan_sgd_step_f32grad(lpk_tensor_list* L, const int32_t* fl_theta_in, c
   if (!L->all_src) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_kahan_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->store_all ? L->grid_dense : L->grid_step, 1, fl_theta_in, fl_theta_out,
                                    fl_grad, lr_q16, wd_q16, L->store_all ? 1u : 0u, L->any_grad_i8 ? 1u : 0u, vmax_out, status,
-                                   static_cast<hipStream_t>(stream));
+                                   L->d_fold, L->d_scratch + L->n_tensors + 1, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
@@ -238,7 +244,8 @@ static int momentum_step(lpk_tensor_list* L, int grad_is_f32, const int32_t* fl_
   // fed from fp32 gradients the stream reads 7 bytes per 3 written and runs slightly faster with two workgroups per CU
   hipError_t e = launch_momentum_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, grad_is_f32 ? L->grid : L->grid_dense, grad_is_f32,
                                       fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_grad, lr_q16, mu_q16, wd_q16,
-                                      vmax_out, mmax_out, status, static_cast<hipStream_t>(stream));
+                                      vmax_out, mmax_out, status, L->d_fold, L->d_scratch + L->n_tensors + 1,
+                                      static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 
@@ -274,7 +281,8 @@ static int adam_step(lpk_tensor_list* L, int grad_is_f32, const int32_t* fl_thet
   const AdamHyperDev h{hyper->lr_q16, hyper->lr_exp, hyper->beta1_q16, hyper->beta2_q16, hyper->eps_q16, hyper->eps_exp};
   hipError_t e = launch_adam_step(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_adam, grad_is_f32,
                                   fl_theta_in, fl_theta_out, fl_mom_in, fl_mom_out, fl_sec_in, fl_sec_out, fl_grad, h,
-                                  vmax_out, mmax_out, umax_out, status, static_cast<hipStream_t>(stream));
+                                  vmax_out, mmax_out, umax_out, status, L->d_fold, L->d_scratch + L->n_tensors + 1,
+                                  static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 

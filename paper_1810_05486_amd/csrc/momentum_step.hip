@@ -295,7 +295,7 @@ __global__ void __launch_bounds__(kBlock)
 momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles,
                      const int32_t* __restrict__ fl_in, const int32_t* __restrict__ fl_out,
                      const int32_t* __restrict__ fl_m_in, const int32_t* __restrict__ fl_m_out, const int32_t* __restrict__ fl_g,
-                     uint32_t lr, uint32_t mu, uint32_t wd, uint64_t* vmax, uint64_t* mmax, uint32_t* status)
+                     uint32_t lr, uint32_t mu, uint32_t wd, uint64_t* vmax, uint64_t* mmax, uint32_t* status, MaxFold fold)
 {
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint64_t s_max[kWavesPerBlock];
@@ -337,6 +337,7 @@ momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restri
   raise_status(status, status_bits, lane);
   if (vmax) flush_block(vmax, cur, vm, lane, wave, s_tensor, s_max);
   if (mmax) flush_block(mmax, cur, wm, lane, wave, s_tensor, s_max);
+  if (fold.arrivals) { uint64_t* const acc[2] = {vmax, mmax}; fold_maxima<2>(fold, acc, &s_tensor[0]); }
 }
 
 __global__ void __launch_bounds__(kBlock) fill2_u64_kernel(uint64_t* a, uint64_t* b, uint32_t n)
@@ -348,17 +349,19 @@ __global__ void __launch_bounds__(kBlock) fill2_u64_kernel(uint64_t* a, uint64_t
 hipError_t launch_momentum_step(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                                 int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                                 const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
-                                uint64_t* vmax, uint64_t* mmax, uint32_t* status, hipStream_t stream)
+                                uint64_t* vmax, uint64_t* mmax, uint32_t* status, uint64_t* fold_acc, uint32_t* arrivals,
+                                hipStream_t stream)
 {
-  if (vmax || mmax)
+  const MaxPlan m = plan_maxima(fold_acc, arrivals, n_tensors, n_tiles, grid, vmax, mmax, nullptr);
+  if ((vmax || mmax) && !m.fold.arrivals)
     hipLaunchKernelGGL(fill2_u64_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, vmax, mmax, n_tensors);
   if (n_tiles) {
     if (grad_is_f32)
       hipLaunchKernelGGL(momentum_step_kernel<kGradF32>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                         fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr, mu, wd, vmax, mmax, status);
+                         fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr, mu, wd, m.acc[0], m.acc[1], status, m.fold);
     else
       hipLaunchKernelGGL(momentum_step_kernel<kGradI16>, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles,
-                         fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr, mu, wd, vmax, mmax, status);
+                         fl_in, fl_out, fl_m_in, fl_m_out, fl_g, lr, mu, wd, m.acc[0], m.acc[1], status, m.fold);
   }
   return hipGetLastError();
 }

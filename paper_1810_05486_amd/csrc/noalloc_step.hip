@@ -130,6 +130,6 @@ extern "C" int lpk_kahan_sgd_step_noalloc(const lpk_tensor_desc* descs, uint32_t
   const uint32_t n_tiles = next_tile;
   const uint32_t grid = persistent_grid(n_tiles, slot.n_cu, 2);      // the launch shape of a list with default options
   hipError_t e = launch_kahan_step(d_tensors, d_tiles, n_tiles, n_tensors, grid, 0, fl_theta_in, fl_theta_out, fl_grad,
-                                   lr_q16, wd_q16, 0u, facts.any_grad_i8 ? 1u : 0u, vmax_out, status, s);
+                                   lr_q16, wd_q16, 0u, facts.any_grad_i8 ? 1u : 0u, vmax_out, status, nullptr, nullptr, s);
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }

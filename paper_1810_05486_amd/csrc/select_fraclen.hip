@@ -7,9 +7,10 @@
 // fp32 source: |x| of a finite float is ordered like its bit pattern with the
 // sign cleared, and every NaN/Inf pattern is >= 0x7f800000, so the reduction is
 // an unsigned integer max over (bits & 0x7fffffff): per-lane max, DPP wave max,
-// LDS across the waves of a block, one atomic per (block, tensor).  A second
-// small kernel turns each maximum into a fraclen in closed form and re-arms the
-// scratch word for the next call.
+// LDS across the waves of a block, one atomic per (block, tensor).  Each maximum
+// becomes a fraclen in closed form, and its scratch word is re-armed for the
+// next call: in the scan's last workgroup when the launch is small, in a second
+// small kernel otherwise.
 #include "lpk_device.hpp"
 
 namespace lpk {
@@ -18,8 +19,36 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t absbits(uint32_t b) { return b & 0x7fffffffu; }
 
+__device__ __forceinline__ int clamp_fl(int fl) { return fl > kFlMax ? kFlMax : (fl < kFlMin ? kFlMin : fl); }
+
+// Max bit pattern of a tensor -> fraclen.  With e = floor(log2 M) the candidate is W - 2 - e (M lands in
+// [2^(W-2), 2^(W-1))); it is one too fine exactly when M * 2^fl reaches 2^(W-1) - 1/2, i.e. when the 24-bit
+// significand m satisfies m >= 2^24 - 2^(24-W).
+__device__ __forceinline__ int fraclen_of_f32max(uint32_t b, int W, int fl_default, uint32_t* status)
+{
+  if (b >= 0x7f800000u) { if (status) atomicOr(status, kStatusNonFinite); return kFlMin; }
+  if (b == 0) return fl_default;
+  const int E = (int)(b >> 23);
+  if (E == 0) return kFlMax;                          // subnormal maximum: far finer than the domain allows
+  const uint32_t m = (b & 0x7fffffu) | 0x800000u;
+  int fl = W - 2 - (E - 127);
+  if (m >= (1u << 24) - (1u << (24 - W))) fl -= 1;
+  return clamp_fl(fl);
+}
+
+// What the scan's last workgroup needs to finish the selection (arrivals == nullptr: a second kernel does it).
+struct SelectFold {
+  uint32_t*      arrivals;
+  uint32_t       n_tensors;
+  int            sel;
+  const int32_t* fl_default;
+  int32_t*       fl_out;
+  uint32_t*      status;
+};
+
 __global__ void __launch_bounds__(kBlock)
-maxabs_f32_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles, uint32_t* scratch)
+maxabs_f32_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ tiles, uint32_t n_tiles, uint32_t* scratch,
+                  SelectFold fold)
 {
   __shared__ int      s_tensor[kWavesPerBlock];
   __shared__ uint32_t s_max[kWavesPerBlock];
@@ -87,13 +116,29 @@ maxabs_f32_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
       if (ma) atomicMax(&scratch[ta], ma);
     }
   }
+
+  if (!fold.arrivals) return;
+  if (!last_workgroup(fold.arrivals, &s_tensor[0])) return;
+  constexpr int K = 4;                                // exchanges in flight per thread
+  for (uint32_t base = 0; base < fold.n_tensors; base += K * kBlock) {
+    uint32_t b[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const uint32_t t = base + k * kBlock + threadIdx.x;
+      b[k] = t < fold.n_tensors ? atomicExch(&scratch[t], 0u) : 0u;     // read, and re-arm for the next call
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const uint32_t t = base + k * kBlock + threadIdx.x;
+      if (t >= fold.n_tensors) continue;
+      const int W = fold.sel == 1 ? tensors[t].wt : tensors[t].wg;
+      fold.fl_out[t] = fraclen_of_f32max(b[k], W, fold.fl_default[t], fold.status);
+    }
+  }
+  if (threadIdx.x == 0) atomicExch(fold.arrivals, 0u);
 }
 
-__device__ __forceinline__ int clamp_fl(int fl) { return fl > kFlMax ? kFlMax : (fl < kFlMin ? kFlMin : fl); }
-
-// One thread per tensor: max bit pattern -> fraclen.  With e = floor(log2 M) the candidate is
-// W - 2 - e (M lands in [2^(W-2), 2^(W-1))); it is one too fine exactly when M * 2^fl reaches
-// 2^(W-1) - 1/2, i.e. when the 24-bit significand m satisfies m >= 2^24 - 2^(24-W).
+// One thread per tensor: the same conversion as a launch of its own (larger launches; lists without a single element).
 __global__ void __launch_bounds__(kBlock)
 fraclen_from_f32max_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tensors, int sel,
                            uint32_t* scratch, const int32_t* __restrict__ fl_default, int32_t* fl_out, uint32_t* status)
@@ -103,21 +148,9 @@ fraclen_from_f32max_kernel(const TensorDev* __restrict__ tensors, uint32_t n_ten
   const uint32_t b = scratch[t];
   scratch[t] = 0;                                   // re-arm for the next call
   const int W = sel == 1 ? tensors[t].wt : tensors[t].wg;
-  int fl;
-  if (b >= 0x7f800000u) { fl = kFlMin; if (status) atomicOr(status, kStatusNonFinite); }
-  else if (b == 0)      { fl = fl_default[t]; }
-  else {
-    const int E = (int)(b >> 23);
-    if (E == 0) fl = kFlMax;                        // subnormal maximum: far finer than the domain allows
-    else {
-      const uint32_t m = (b & 0x7fffffu) | 0x800000u;
-      fl = W - 2 - (E - 127);
-      if (m >= (1u << 24) - (1u << (24 - W))) fl -= 1;
-      fl = clamp_fl(fl);
-    }
-  }
-  fl_out[t] = fl;
+  fl_out[t] = fraclen_of_f32max(b, W, fl_default[t], status);
 }
+
 
 // One thread per tensor: vmax (an integer on grid F = fl_theta_in + d) -> fraclen, clamped to default +- 15.
 __global__ void __launch_bounds__(kBlock)
@@ -152,13 +185,19 @@ fraclen_from_vmax_kernel(const TensorDev* __restrict__ tensors, uint32_t n_tenso
   fl_out[t] = clamp_fl(fl);
 }
 
+// `arrivals`: the list's workgroup counter for this launch (zero between launches), or nullptr to convert in a
+// second launch whatever the launch's size.
 hipError_t launch_select_f32(const TensorDev* tensors, const Tile* tiles, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
-                             int sel, uint32_t* scratch, const int32_t* fl_default, int32_t* fl_out,
+                             int sel, uint32_t* scratch, uint32_t* arrivals, const int32_t* fl_default, int32_t* fl_out,
                              uint32_t* status, hipStream_t stream)
 {
-  if (n_tiles)
-    hipLaunchKernelGGL(maxabs_f32_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles, scratch);
-  hipLaunchKernelGGL(fraclen_from_f32max_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream,
+  const bool fold = arrivals && n_tiles && n_tensors <= kFoldMaxTensors && grid <= kFoldMaxBlocks;
+  if (n_tiles) {
+    const SelectFold f{fold ? arrivals : nullptr, n_tensors, sel, fl_default, fl_out, status};
+    hipLaunchKernelGGL(maxabs_f32_kernel, dim3(grid), dim3(kBlock), 0, stream, tensors, tiles, n_tiles, scratch, f);
+  }
+  if (!fold)
+    hipLaunchKernelGGL(fraclen_from_f32max_kernel, dim3((n_tensors + kBlock - 1) / kBlock), dim3(kBlock), 0, stream,
                      tensors, n_tensors, sel, scratch, fl_default, fl_out, status);
   return hipGetLastError();
 }

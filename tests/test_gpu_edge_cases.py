@@ -589,3 +589,88 @@ def test_all_int8_update_with_int8_gradients(store_all):
     assert int(g.min()) == -128 and int(g.max()) == 127 and not d_grad.any().item()
     assert np.array_equal(d_theta.cpu().numpy(), theta) and np.array_equal(d_comp.cpu().numpy(), comp)
     tl.destroy()
+
+
+@pytest.mark.parametrize("mode", ["plain", "momentum", "adam"])
+@pytest.mark.parametrize("n_tensors,p_empty,small_launch", [(1, 0.0, True), (257, 0.05, True), (700, 0.05, False),
+                                                            (4096, 0.93, True), (4097, 0.93, False)])
+def test_fraclens_and_maxima_on_both_sides_of_the_launch_size_where_the_last_workgroup_finishes_them(n_tensors, p_empty, small_launch, mode):
+    """Small launches (at most 128 workgroups, i.e. 512 tiles, over at most 4096 tensors) have their per-tensor results
+    (fraclens from the max-abs scan; vmax, mmax, umax of the update kernels) finished by the launch's last workgroup,
+    larger ones by separate launches.  Both sides of both limits, and list lengths around multiples of the block
+    size, against the oracle tensor by tensor -- twice in a row, the second time with a far smaller gradient and a
+    quarter of the state, so a maximum left over from the first call (an accumulator that was not put back to zero)
+    would show."""
+    say("last-workgroup results: %d tensors, %s" % (n_tensors, mode))
+    rng = np.random.default_rng(1000 + n_tensors)
+    p = np.array([.1, .2, .2, .2, .15, .05, .05]) * (1 - p_empty) / .95
+    sizes = rng.choice([0, 1, 7, 16, 64, 300, 4096, 5000], size=n_tensors, p=[p_empty] + list(p))
+    if n_tensors == 1:
+        sizes[:] = 5000
+    n_tiles = int(((sizes + 4095) // 4096).sum())
+    assert (n_tiles <= 512 and n_tensors <= 4096) == small_launch, (n_tiles, n_tensors)
+    starts = np.concatenate([[0], np.cumsum((sizes + 15) // 16 * 16)])      # every tensor 16-element aligned
+    total = int(starts[-1]) + 16
+    theta = rng.integers(-128, 128, total).astype(np.int8)
+    comp = rng.integers(-128, 128, total).astype(np.int8)
+    mom = rng.integers(-2000, 2000, total).astype(np.int16)
+    sec = rng.integers(0, 3000, total).astype(np.int16)
+    d_theta, d_comp, d_mom, d_sec = (torch.from_numpy(a.copy()).to(DEV) for a in (theta, comp, mom, sec))
+    d_grad = torch.zeros(total, dtype=torch.int16, device=DEV)
+    d_src = torch.zeros(total, dtype=torch.float32, device=DEV)
+    sl = [slice(int(starts[t]), int(starts[t]) + int(sizes[t])) for t in range(n_tensors)]
+    tl = lpk.TensorList([lpk.make_desc(d_theta[s], d_comp[s], d_grad[s], d_src[s], momentum=d_mom[s], second=d_sec[s])
+                         for s in sl])
+    i32 = dict(dtype=torch.int32, device=DEV)
+    fl_t = rng.integers(5, 9, n_tensors); fl_m = rng.integers(12, 16, n_tensors); fl_u = rng.integers(24, 28, n_tensors)
+    fl_g0 = rng.integers(10, 14, n_tensors)                                 # defaults: kept by empty and all-zero tensors
+    d_fl_t, d_fl_m, d_fl_u, d_fl_g0 = (torch.tensor(a, **i32) for a in (fl_t, fl_m, fl_u, fl_g0))
+    hyper = (66, 0, 58982, 65470, 43, 10)
+    scale = 2.0 ** rng.integers(-12, -3, n_tensors)
+    for rnd in range(2):
+        src = rng.standard_normal(total).astype(np.float32)
+        for t in range(n_tensors):
+            src[sl[t]] *= scale[t] * (1.0 if rnd == 0 else 1.0 / 256)
+        src[sl[n_tensors // 2]] = 0.0                                        # an all-zero tensor keeps its default
+        d_src.copy_(torch.from_numpy(src))
+        d_fl_g = torch.full((n_tensors,), -77, **i32)
+        mx = [torch.full((n_tensors,), 99, dtype=torch.int64, device=DEV) for _ in range(3)]
+        status = torch.zeros(1, **i32)
+        lpk.lpk_select_fraclen(tl, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, d_fl_g0, d_fl_g, status)
+        lpk.lpk_quantize_tensor(tl, lpk.LPK_SEL_GRAD, d_fl_g, status)
+        if mode == "plain":
+            lpk.lpk_kahan_sgd_step(tl, d_fl_t, d_fl_t, d_fl_g, 6554, 0, mx[0], status)
+        elif mode == "momentum":
+            lpk.lpk_momentum_sgd_step(tl, d_fl_t, d_fl_t, d_fl_m, d_fl_m, d_fl_g, 6554, 58982, 0, mx[0], mx[1], status)
+        else:
+            lpk.lpk_adam_step(tl, d_fl_t, d_fl_t, d_fl_m, d_fl_m, d_fl_u, d_fl_u, d_fl_g, hyper, mx[0], mx[1], mx[2], status)
+        torch.cuda.synchronize()
+        st = ref.new_status()
+        want_fl, want_mx = [], [[], [], []]
+        for t in range(n_tensors):
+            s = sl[t]
+            fl = ref.select_fraclen_f32(src[s], 16, int(fl_g0[t]), st)
+            g = ref.quantize(src[s], 16, fl, st)
+            if mode == "plain":
+                m = (ref.kahan_sgd_step(theta[s], comp[s], g, 7, fl_t[t], fl_t[t], fl, 6554, 0, st), 0, 0)
+            elif mode == "momentum":
+                m = ref.momentum_sgd_step(theta[s], comp[s], mom[s], g, 7, fl_t[t], fl_t[t], fl_m[t], fl_m[t], fl, 6554, 58982, 0, st) + (0,)
+            else:
+                m = ref.adam_step(theta[s], comp[s], mom[s], sec[s], g, 7, fl_t[t], fl_t[t], fl_m[t], fl_m[t], fl_u[t], fl_u[t], fl, *hyper, st)
+            want_fl.append(fl)
+            for k in range(3):
+                want_mx[k].append(m[k])
+        ctx = (n_tensors, mode, rnd)
+        assert d_fl_g.cpu().tolist() == want_fl, ctx
+        n_max = {"plain": 1, "momentum": 2, "adam": 3}[mode]
+        for k in range(n_max):
+            assert mx[k].cpu().tolist() == want_mx[k], ctx + (k,)
+        for k in range(n_max, 3):
+            assert mx[k].cpu().tolist() == [99] * n_tensors, ctx + (k,)      # arrays the call was not given stay untouched
+        assert np.array_equal(d_theta.cpu().numpy(), theta) and np.array_equal(d_comp.cpu().numpy(), comp), ctx
+        assert np.array_equal(d_mom.cpu().numpy(), mom) and np.array_equal(d_sec.cpu().numpy(), sec), ctx
+        assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0]), ctx
+        for host, dev in ((theta, d_theta), (comp, d_comp), (mom, d_mom), (sec, d_sec)):
+            host //= 4
+            dev.copy_(torch.from_numpy(host))
+    tl.destroy()
