@@ -25,8 +25,9 @@
 // repairs.  12 fp64 instructions per parameter instead of 46.
 //
 // Same work distribution as the plain update (persistent wavefronts over the tile table, non-temporal vector
-// accesses) for int16 moments and gradients on 16-byte aligned buffers; anything else goes element by element
-// through the same arithmetic.  Gradients come from the int16 array or, in a second kernel instance, from the
+// accesses) for int16 moments and gradients on 16-byte aligned buffers -- in 1024-element rows with a cross-lane
+// swap for int8 theta and accumulator with int16 gradients (see ARow), in groups of 8 consecutive elements per lane
+// otherwise; anything else goes element by element through the same arithmetic.  Gradients come from the int16 array or, in a second kernel instance, from the
 // fp32 source, quantized in registers.
 #include "step_common.hpp"
 
@@ -35,6 +36,10 @@
 #endif
 #ifndef LPK_ADAM_GROUPS
 #define LPK_ADAM_GROUPS 4              // groups in flight per lane (measured: 2, 6, 8, 16 are slower for one or both gradient sources)
+#endif
+#ifndef LPK_ADAM_ROWS
+#define LPK_ADAM_ROWS 2                // int8 theta and accumulator, int16 gradients: 1024-element rows in flight per wave (0: groups only;
+                                       // 2 and 4 measure the same, 3 is slower; 4 needs more than 256 registers)
 #endif
 #ifndef LPK_ADAM_WAVES_PER_SIMD
 #define LPK_ADAM_WAVES_PER_SIMD 1      // lower bound handed to the register allocator (no cap at 256 VGPRs: nothing spills; the kernel
@@ -265,10 +270,95 @@ __device__ __forceinline__ void group_adam(const AdamParams& p, const AGroup<E, 
   st_dw((int16_t*)T.sec + e, pack_dw<16, E>(un));
 }
 
+// Row form for int8 theta and accumulator with int16 moments and gradients: a wave takes 1024 consecutive elements
+// with ONE dwordx4 access per 8-bit array (lane l: bytes 16l .. 16l+15) and TWO per 16-bit array, each of them one
+// contiguous 1-KiB run of the wave (the row's first and second half).  The memory system delivers this 8-read :
+// 6-written stream 5-10 % faster in that shape than with 8-byte accesses to the 8-bit arrays or with a lane's 32
+// bytes of a 16-bit array adjacent.  A lane then holds sixteen 8-bit values from one place and two groups of eight
+// 16-bit values from two places; which 16-byte chunk of each half a lane takes is free (any assignment of a run's
+// chunks to lanes is one contiguous run), and it is chosen so that ONE swap of the upper 32 lanes of a register
+// with the lower 32 lanes of another (v_permlane32_swap) lines the 8-bit data up with the 16-bit data: lane l < 32
+// works on chunks 2l of both halves, lane 32 + s on chunks 2s + 1.  Before the swap lane s < 32 holds the 8-bit
+// chunks 2s (dwords 0, 1) and 2s + 1 (dwords 2, 3) of the first half, lane 32 + s those of the second half; swapping
+// dword 0 with 2 and 1 with 3 leaves every lane with its first-half chunk in dwords 0, 1 and its second-half
+// chunk in dwords 2, 3.  The same two swaps on the results restore the order in memory for the store.
+struct ARow { DW<4> th, c, m[2], u[2], g[2]; };
+
+__device__ __forceinline__ void swap_halves(int& upper_of, int& lower_of)
+{
+  const auto r = __builtin_amdgcn_permlane32_swap((unsigned)upper_of, (unsigned)lower_of, false, false);
+  upper_of = (int)r[0]; lower_of = (int)r[1];
+}
+__device__ __forceinline__ void align_bytes_with_halves(DW<4>& b) { swap_halves(b.d[0], b.d[2]); swap_halves(b.d[1], b.d[3]); }
+
+__device__ __forceinline__ void load_row_adam(ARow& R, const TensorDev& T, uint64_t e0, int lane, int chunk)
+{
+  R.th = ld_dw<4>((const int8_t*)T.theta + e0 + 16 * lane);
+  R.c  = ld_dw<4>((const int8_t*)T.comp + e0 + 16 * lane);
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t e = e0 + 512 * h + 8 * chunk;
+    R.m[h] = ld_dw<4>((const int16_t*)T.mom + e);
+    R.u[h] = ld_dw<4>((const int16_t*)T.sec + e);
+    R.g[h] = ld_dw<4>((const int16_t*)T.grad + e);
+  }
+}
+
+template <bool CAPS, int TAIL, bool EXACT3, bool FAST>
+__device__ __forceinline__ void row_adam(const AdamParams& p, ARow R, const TensorDev& T, uint64_t e0, int lane, int chunk, AdamTrack& tr)
+{
+  align_bytes_with_halves(R.th);
+  align_bytes_with_halves(R.c);
+  int tn[16], cn[16];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    int mn[8], un[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int j = 8 * h + k;
+      if constexpr (FAST)
+        update_adam_fast<TAIL>(p, elem_dw<8>(R.th, j), elem_dw<8>(R.c, j), elem_dw<16>(R.m[h], k), elem_dw<16>(R.u[h], k),
+                               elem_dw<16>(R.g[h], k), tn[j], cn[j], mn[k], un[k], tr);
+      else
+        update_adam<CAPS, TAIL, EXACT3>(p, elem_dw<8>(R.th, j), elem_dw<8>(R.c, j), elem_dw<16>(R.m[h], k), elem_dw<16>(R.u[h], k),
+                                        elem_dw<16>(R.g[h], k), tn[j], cn[j], mn[k], un[k], tr);
+    }
+    const uint64_t e = e0 + 512 * h + 8 * chunk;
+    st_dw((int16_t*)T.mom + e, pack_dw<16, 8>(mn));
+    st_dw((int16_t*)T.sec + e, pack_dw<16, 8>(un));
+  }
+  DW<4> th = pack_dw<8, 16>(tn), c = pack_dw<8, 16>(cn);
+  align_bytes_with_halves(th);
+  align_bytes_with_halves(c);
+  st_dw((int8_t*)T.theta + e0 + 16 * lane, th);
+  st_dw((int8_t*)T.comp + e0 + 16 * lane, c);
+}
+
 template <int WT, int WC, bool CAPS, int TAIL, bool EXACT3, int GS, bool FAST>
 __device__ __forceinline__ void tile_vec_adam_x(const AdamParams& p, const TensorDev& T, uint64_t off, uint32_t cnt, int lane, AdamTrack& tr,
                                                 uint32_t& ab)
 {
+  if constexpr (LPK_ADAM_ROWS > 0 && WT == 8 && WC == 8 && GS == kGradI16) {
+    constexpr int kR = LPK_ADAM_ROWS > 0 ? LPK_ADAM_ROWS : 1;    // rows in flight per wave
+    const uint32_t rows = cnt / 1024;
+    const int chunk = lane < 32 ? 2 * lane : 2 * (lane - 32) + 1;
+    uint32_t r = 0;
+    for (; r + kR <= rows; r += kR) {
+      ARow R[kR];
+#pragma unroll
+      for (int i = 0; i < kR; ++i) load_row_adam(R[i], T, off + (uint64_t)(r + i) * 1024, lane, chunk);
+#pragma unroll
+      for (int i = 0; i < kR; ++i) row_adam<CAPS, TAIL, EXACT3, FAST>(p, R[i], T, off + (uint64_t)(r + i) * 1024, lane, chunk, tr);
+    }
+    for (; r < rows; ++r) {
+      ARow R;
+      load_row_adam(R, T, off + (uint64_t)r * 1024, lane, chunk);
+      row_adam<CAPS, TAIL, EXACT3, FAST>(p, R, T, off + (uint64_t)r * 1024, lane, chunk, tr);
+    }
+    off += (uint64_t)rows * 1024;                           // what is left of a ragged tile goes group by group
+    cnt -= rows * 1024;
+    if (cnt == 0) return;
+  }
   constexpr int E = LPK_ADAM_E, kP = LPK_ADAM_GROUPS;      // elements per lane per group, groups in flight per lane
   const uint32_t ngroups = cnt / E;
   uint32_t gi = lane;

@@ -16,6 +16,10 @@
 // written 8 bytes per lane, a 16-bit one 16 bytes per lane, coalesced) -- the shape of the kernels whose state
 // includes a 16-bit array.  `groups` passes of a wave are in flight together: all their loads are issued before the
 // first store, as in the update kernels.
+//
+// `work` > 0 puts that many dependent fp32 multiply-adds per parameter between a pass's loads and its stores (four
+// independent chains per lane; the stored words depend on their results): the same traffic with a kernel's amount
+// of arithmetic in between, to tell what the arithmetic's mere presence costs a stream that is not bound by it.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
@@ -83,7 +87,7 @@ __device__ __forceinline__ void store_share(const v4u (&r)[4], v4u* base, uint64
 }
 
 template <typename M, int KP, int LAYOUT>
-__global__ void __launch_bounds__(kBlock) membw_kernel(Ptrs p, uint64_t n_tiles, unsigned* sink)
+__global__ void __launch_bounds__(kBlock) membw_kernel(Ptrs p, uint64_t n_tiles, unsigned* sink, int work)
 {
   const int lane = threadIdx.x & (kWave - 1);
   const uint64_t w0 = (uint64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6), nw = (uint64_t)gridDim.x * kWavesPerBlock;
@@ -111,6 +115,14 @@ __global__ void __launch_bounds__(kBlock) membw_kernel(Ptrs p, uint64_t n_tiles,
 #pragma unroll
           for (int k = 0; k < 4; ++k) ro ^= r[ps][i][k];
         }
+      }
+      if (work > 0) {
+        float f0 = (float)(ro[0] & 0xffu), f1 = (float)(ro[1] & 0xffu), f2 = (float)(ro[2] & 0xffu), f3 = (float)(ro[3] & 0xffu);
+        for (int w = 0; w < 4 * work; ++w) {                  // 16 parameters per lane and pass, four multiply-adds per turn
+          f0 = __builtin_fmaf(f0, 0.5f, 1.0f); f1 = __builtin_fmaf(f1, 0.25f, 3.0f);
+          f2 = __builtin_fmaf(f2, 0.75f, 5.0f); f3 = __builtin_fmaf(f3, 0.125f, 7.0f);
+        }
+        ro ^= v4u{__float_as_uint(f0), __float_as_uint(f1), __float_as_uint(f2), __float_as_uint(f3)};
       }
       acc ^= ro;
 #pragma unroll
@@ -163,16 +175,16 @@ constexpr int kNumMixes = sizeof(kMixes) / sizeof(kMixes[0]);
 
 // n_units: units of 16 parameters; a pass of the half-unit layout covers 64 * 8 parameters, the others 64 * 16.
 template <typename M, int C>
-hipError_t launch(int groups, uint32_t grid, const Ptrs& p, uint64_t n_units, unsigned* sink, hipStream_t s)
+hipError_t launch(int groups, uint32_t grid, const Ptrs& p, uint64_t n_units, unsigned* sink, int work, hipStream_t s)
 {
   const uint64_t n_tiles = (C == 2 ? 2 * n_units : n_units) / ((uint64_t)groups * kWave);
   if (n_tiles == 0) return hipSuccess;
   if (grid > (n_tiles + kWavesPerBlock - 1) / kWavesPerBlock) grid = (uint32_t)((n_tiles + kWavesPerBlock - 1) / kWavesPerBlock);
   switch (groups) {
-    case 1: hipLaunchKernelGGL((membw_kernel<M, 1, C>), dim3(grid), dim3(kBlock), 0, s, p, n_tiles, sink); break;
-    case 2: hipLaunchKernelGGL((membw_kernel<M, 2, C>), dim3(grid), dim3(kBlock), 0, s, p, n_tiles, sink); break;
-    case 4: hipLaunchKernelGGL((membw_kernel<M, 4, C>), dim3(grid), dim3(kBlock), 0, s, p, n_tiles, sink); break;
-    case 8: hipLaunchKernelGGL((membw_kernel<M, 8, C>), dim3(grid), dim3(kBlock), 0, s, p, n_tiles, sink); break;
+    case 1: hipLaunchKernelGGL((membw_kernel<M, 1, C>), dim3(grid), dim3(kBlock), 0, s, p, n_tiles, sink, work); break;
+    case 2: hipLaunchKernelGGL((membw_kernel<M, 2, C>), dim3(grid), dim3(kBlock), 0, s, p, n_tiles, sink, work); break;
+    case 4: hipLaunchKernelGGL((membw_kernel<M, 4, C>), dim3(grid), dim3(kBlock), 0, s, p, n_tiles, sink, work); break;
+    case 8: hipLaunchKernelGGL((membw_kernel<M, 8, C>), dim3(grid), dim3(kBlock), 0, s, p, n_tiles, sink, work); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -198,11 +210,14 @@ int membw_mix_describe(int mix, char* name, int name_cap, int* words, int* modes
 // Run one mix over n_units units (rounded down to whole tiles of groups * 64 units; every access stays inside the
 // first n_units * words * 16 bytes of each array).  arrays: host array of device pointers, one per array of the
 // mix, each 16-byte aligned and at least n_units * words * 16 bytes long, not overlapping.  groups in {1, 2, 4, 8};
-// blocks_per_cu >= 1; layout 0 = coalesced, 1 = lane-consecutive, 2 = half units (8 parameters per lane).  Only enqueues.
+// blocks_per_cu >= 1; layout 0 = coalesced, 1 = lane-consecutive, 2 = half units (8 parameters per lane); work: fp32
+// multiply-adds per parameter between loads and stores, 0..4096 (in the half-unit layout a pass holds half the
+// parameters, so the count per parameter is twice `work`).  Only enqueues.
 // Returns 0, or -1 for a bad argument, -3 for a HIP failure.
-int membw_run(int mix, int groups, int blocks_per_cu, int layout, void* const* arrays, uint64_t n_units, void* stream)
+int membw_run_work(int mix, int groups, int blocks_per_cu, int layout, void* const* arrays, uint64_t n_units, int work,
+                   void* stream)
 {
-  if (mix < 0 || mix >= kNumMixes || !arrays || blocks_per_cu < 1 || blocks_per_cu > 64) return -1;
+  if (mix < 0 || mix >= kNumMixes || !arrays || blocks_per_cu < 1 || blocks_per_cu > 64 || work < 0 || work > 4096) return -1;
   if ((groups != 1 && groups != 2 && groups != 4 && groups != 8) || layout < 0 || layout > 2) return -1;
   Ptrs p{};
   for (int i = 0; i < kMixes[mix].n; ++i) {
@@ -215,7 +230,7 @@ int membw_run(int mix, int groups, int blocks_per_cu, int layout, void* const* a
   const uint32_t grid = (uint32_t)n_cu * (uint32_t)blocks_per_cu;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipErrorInvalidValue;
-#define MEMBW_CASE(id, M) case id: e = layout == 0 ? launch<M, 0>(groups, grid, p, n_units, nullptr, s) : (layout == 1 ? launch<M, 1>(groups, grid, p, n_units, nullptr, s) : launch<M, 2>(groups, grid, p, n_units, nullptr, s)); break
+#define MEMBW_CASE(id, M) case id: e = layout == 0 ? launch<M, 0>(groups, grid, p, n_units, nullptr, work, s) : (layout == 1 ? launch<M, 1>(groups, grid, p, n_units, nullptr, work, s) : launch<M, 2>(groups, grid, p, n_units, nullptr, work, s)); break
   switch (mix) {
     MEMBW_CASE(0, MixRead);
     MEMBW_CASE(1, MixWrite);
@@ -232,6 +247,12 @@ int membw_run(int mix, int groups, int blocks_per_cu, int layout, void* const* a
   }
 #undef MEMBW_CASE
   return e == hipSuccess ? 0 : -3;
+}
+
+// The plain yardstick: no arithmetic between loads and stores.
+int membw_run(int mix, int groups, int blocks_per_cu, int layout, void* const* arrays, uint64_t n_units, void* stream)
+{
+  return membw_run_work(mix, groups, blocks_per_cu, layout, arrays, n_units, 0, stream);
 }
 
 }  // extern "C"

@@ -28,6 +28,9 @@ def lib():
         L.membw_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_void_p),
                                 ctypes.c_uint64, ctypes.c_void_p]
         L.membw_run.restype = ctypes.c_int
+        L.membw_run_work.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_void_p),
+                                     ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p]
+        L.membw_run_work.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -64,32 +67,33 @@ class Runner:
         self.bytes_read = sum(w for w, m in self.arrays_desc if m & READ) * 16 * self.n_units
         self.bytes_written = sum(w for w, m in self.arrays_desc if m & WRITE) * 16 * self.n_units
 
-    def launch(self, groups=4, blocks_per_cu=1, layout=0):
+    def launch(self, groups=4, blocks_per_cu=1, layout=0, work=0):
         """layout 0: coalesced accesses, 16 parameters per lane; 1: a lane's words adjacent in memory; 2: 8 parameters per
-        lane (an int8 array moves 8 bytes per lane and access, a 16-bit one 16), coalesced."""
-        rc = lib().membw_run(self.mix, groups, blocks_per_cu, layout, self.ptrs, self.n_units,
-                             self.torch.cuda.current_stream().cuda_stream)
+        lane (an int8 array moves 8 bytes per lane and access, a 16-bit one 16), coalesced.  work: dependent fp32
+        multiply-adds per parameter between a pass's loads and its stores (0: none)."""
+        rc = lib().membw_run_work(self.mix, groups, blocks_per_cu, layout, self.ptrs, self.n_units, int(work),
+                                  self.torch.cuda.current_stream().cuda_stream)
         if rc != 0:
-            raise RuntimeError("membw_run failed (%d)" % rc)
+            raise RuntimeError("membw_run_work failed (%d)" % rc)
 
-    def time_ms(self, groups=4, blocks_per_cu=1, reps=10, warmup=2, layout=0):
+    def time_ms(self, groups=4, blocks_per_cu=1, reps=10, warmup=2, layout=0, work=0):
         """Per-launch times in ms (HIP events on the launch stream around each launch)."""
         torch = self.torch
         for _ in range(warmup):
-            self.launch(groups, blocks_per_cu, layout)
+            self.launch(groups, blocks_per_cu, layout, work)
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for a, b in ev:
             a.record()
-            self.launch(groups, blocks_per_cu, layout)
+            self.launch(groups, blocks_per_cu, layout, work)
             b.record()
         torch.cuda.synchronize()
         return sorted(a.elapsed_time(b) for a, b in ev)
 
-    def best(self, blocks_per_cu, groups=(1, 2, 4, 8), reps=10, layout=0):
+    def best(self, blocks_per_cu, groups=(1, 2, 4, 8), reps=10, layout=0, work=0):
         """(GB/s of the median launch, groups) for the best number of groups in flight at this launch shape."""
         res = []
         for g in groups:
-            ms = self.time_ms(g, blocks_per_cu, reps, layout=layout)
+            ms = self.time_ms(g, blocks_per_cu, reps, layout=layout, work=work)
             res.append(((self.bytes_read + self.bytes_written) / (ms[len(ms) // 2] * 1e-3) / 1e9, g))
         return max(res)
 
@@ -119,6 +123,16 @@ def main():
                 continue
             cols.append("  ".join("%5.0f (%d)" % r.best(bpc, reps=args.reps, layout=layout) for bpc in (1, 2, 4)))
         print("%-34s %8.2f %8.2f | %-32s | %-32s | %s" % (name, r.bytes_read / 1e9, r.bytes_written / 1e9, cols[0], cols[1], cols[2]), flush=True)
+        del r
+        torch.cuda.empty_cache()
+    print()
+    print("the same mixes with arithmetic between a pass's loads and its stores (dependent fp32 multiply-adds per parameter; "
+          "coalesced layout; best of 1-8 groups at 1 / 2 / 4 workgroups per CU)")
+    for name in ("update_i8", "momentum_i16v", "adam_i16"):
+        r = Runner(name, args.units)
+        for work in (0, 16, 32, 64, 96):
+            print("%-34s work %3d | %s" % (r.name, work, "  ".join("%5.0f (%d)" % r.best(bpc, reps=args.reps, work=work) for bpc in (1, 2, 4))),
+                  flush=True)
         del r
         torch.cuda.empty_cache()
 
