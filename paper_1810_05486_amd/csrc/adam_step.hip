@@ -152,9 +152,10 @@ __device__ __forceinline__ void update_adam(const AdamParams& p, int th, int c, 
 //     fp32).  fma(-c1, y, K + 65536*m) with K = 1.5*2^39 forms wM + K exactly and rounds it once to K's ulp, 2^16,
 //     ties to even (K / 2^16 is even): the result is K + 2^16 * RNE(wM / 2^16).  K + 65536*m is K's bit pattern
 //     plus m; the new moment is the result's bit pattern minus K's.  Needs |wM| < 2^38.
-//   second moment: wU = b2*u + t4 = 65536*u + w with w = t4 - c2*u in (-2^31, 2^30], t4 = RNE(g*g * a4) < 2^31 from
-//     one fp64 FMA onto 1.5*2^52 (whose low word is 0, so the sum's low word is t4).  RNE(wU / 2^16) is u plus w
-//     shifted right 16 with round-half-even, the parity taken from u + (w >> 16).
+//   second moment: wU = b2*u + t4 = 65536*u + w with w = t4 - c2*u, t4 = RNE(g*g * a4) <= 2^30 from one fp64 FMA
+//     onto 1.5*2^52 (whose low word is 0, so the sum's low word is t4).  RNE(wU / 2^16) is u plus w shifted right 16
+//     with round-half-even, the parity taken from u + (w >> 16).  w is a signed word for u >= 0, an unsigned one for
+//     u < 0 (see there); the result is clamped to [0, qmax] as the definition says, whatever sign u came with.
 //   root:  A = u' * 2^(24+p) < 2^40 is exact in fp32.  v_sqrt_f32 is within 1 ulp; times (1 - 2^-21) it lies
 //     strictly below the true root and less than 0.7 below it, so its truncation r0 is floor(root) or one less, and
 //     floor(root) = r0 + [(r0+1)^2 <= A].  That sign is exact: the FMA forms (r0+1)^2 - A (an integer) before rounding.
@@ -174,11 +175,16 @@ __device__ __forceinline__ void update_adam_fast(const AdamParams& p, int th, in
   mn = med3_i32(mq, p.qmin_mi, p.qmax_mi);
   // second moment
   const int t4 = __double2loint(__builtin_fma((double)mad_i24(g, g, 0), p.a4, kMagic52));
+  // w = t4 - c2*u lies in (-2^31, 2^30] for u >= 0 and in [0, 2^31 + 2^30) for u < 0 (a negative second moment is
+  // not a state the optimizer reaches, but the definition covers every int16 input): a signed word in the first
+  // case, an unsigned one in the second, and the 32-bit multiply-add is exact modulo 2^32 in both
   const int w = mad_i24(u, p.nc2, t4);
-  const int lsb = (u + (w >> 16)) & 1;
-  const int uq = u + ((w + 0x7fff + lsb) >> 16);
+  const bool uneg = u < 0;
+  const int lsb = (u + (uneg ? (int)((unsigned)w >> 16) : (w >> 16))) & 1;
+  const unsigned ww = (unsigned)w + 0x7fffu + (unsigned)lsb;
+  const int uq = u + (uneg ? (int)(ww >> 16) : ((int)ww >> 16));
   tr.umx = uq > tr.umx ? uq : tr.umx;
-  un = uq < p.qmax_ui ? uq : p.qmax_ui;
+  un = med3_i32(uq, 0, p.qmax_ui);
   // root of the new second moment on its fixed grid
   const float Af = (float)un * p.ascale_f;
   const float r0 = __builtin_truncf(__builtin_amdgcn_sqrtf(Af) * 0.999999523162841796875f);     // 1 - 2^-21

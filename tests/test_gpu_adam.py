@@ -252,6 +252,27 @@ def test_adam_standing_grids_around_every_condition_of_the_short_route(seed):
             run_list(cases, hyper)
 
 
+@pytest.mark.parametrize("b2", [0, 1, 58982, 65470, 65535])
+def test_adam_short_route_with_negative_second_moments(b2):
+    """A negative second moment is a state the optimizer never reaches, but every int16 input has a defined result
+    (the new moment is clamped to [0, qmax]).  On the short route the 32-bit sum t4 - (1 - beta2) u passes 2^31 for
+    negative u, so both signs are run on standing grids with every beta2 that stretches it (0: the whole of -65536 u),
+    the rails of u against the rails of g included, through the 1024-element rows and the groups of 8."""
+    say("adam: short route, second moments of both signs, beta2 = %d" % b2)
+    rng = np.random.default_rng(1700 + b2)
+    hyper = (33554, 9, 58982, b2, 43980, 26)
+    cases = []
+    for n, tb, cb, sh2 in ((4096 + 1024 + 24, 8, 8, -7), (2048, 8, 8, -11), (8200, 8, 16, -7), (70001, 8, 8, -20)):
+        fl_g = 20
+        c = make_case(rng, n, tb, cb, 16, 16, 16, None, (7, 7, fl_g + 1, fl_g + 1, 2 * fl_g + sh2, 2 * fl_g + sh2, fl_g),
+                      sec_lo=-32768, sec_hi=32768)
+        c["sec"][:6] = [-32768, -32768, -32768, -1, -1, 32767]
+        c["grad"][:6] = [-32768, 32767, 0, -32768, 0, -32768]
+        c["d_sec"].copy_(torch.from_numpy(c["sec"])); c["d_grad"].copy_(torch.from_numpy(c["grad"]))
+        cases.append(c)
+    run_list(cases, hyper)
+
+
 def test_adam_argument_errors():
     say("adam: host-side argument errors")
     n = 64
