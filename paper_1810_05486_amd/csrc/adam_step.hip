@@ -49,7 +49,7 @@
 namespace lpk {
 
 struct AdamParams {
-  int    path;                     // 0 skip, 1 element by element, 2 vector
+  int    path;                     // 0 skip (-1: skip, but look at the fp32 gradients), 1 element by element, 2 vector
   int    wt, wc, wg, wm, wu, has_comp;
   int    caps;                     // some 2^40 cap may bind
   int    exact3;                   // a1, a2, a3 are integers (and no cap binds): three of the four products need no rounding
@@ -413,7 +413,7 @@ __device__ __forceinline__ void setup_adam(AdamParams& p, const TensorDev& T, in
   auto far = [](int x) { return x > kDeltaMax || x < -kDeltaMax; };
   if (bad(fl_in) || bad(fl_out) || bad(fl_m_in) || bad(fl_m_out) || bad(fl_u_in) || bad(fl_u_out) || bad(fl_g) ||
       d > kDMax || far(delta) || far(delta_m) || far(delta_u) || e > 20) {
-    p.path = 0; status_bits |= kStatusDomain; return;
+    p.path = skipped_path<GS>(fl_g); status_bits |= kStatusDomain; return;
   }
   p.a1 = (double)h.b1 * pow2d(delta_m);                     // b1 * 2^-(fl_m_in - fl_m_out)
   p.a2 = (double)(65536u - h.b1) * pow2d(fl_m_out - fl_g);
@@ -522,8 +522,10 @@ adam_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__
           if (p.tail == kTailSmallBigD) tile_vec_adam<8, 16, false, kTailSmallBigD, GS>(p, T, off, cnt, lane, tr, ab_max);
           else                          tile_vec_adam<8, 16, false, kTailWide, GS>(p, T, off, cnt, lane, tr, ab_max);
         }
-      } else if (p.path) {
+      } else if (p.path > 0) {
         if (p.caps) tile_generic_adam<true, GS>(p, T, off, cnt, lane, tr, ab_max); else tile_generic_adam<false, GS>(p, T, off, cnt, lane, tr, ab_max);
+      } else if (GS == kGradF32 && p.path == kPathSkipButScan) {
+        scan_nonfinite(T.src, off, cnt, lane, ab_max);
       }
     });
 

@@ -422,7 +422,7 @@ __device__ __forceinline__ void setup_tensor(StepParams& p, const TensorDev& T, 
   const int delta = fl_out - fl_in;
   if (fl_in < kFlMin || fl_in > kFlMax || fl_out < kFlMin || fl_out > kFlMax || fl_g < kFlMin || fl_g > kFlMax ||
       p.d > kDMax || delta > kDeltaMax || delta < -kDeltaMax) {
-    p.path = 0; status_bits |= kStatusDomain; return;
+    p.path = skipped_path<GS>(fl_g); status_bits |= kStatusDomain; return;
   }
   const int F = fl_in + p.d;
   p.kg = fl_g + 16 - F;
@@ -578,6 +578,8 @@ kahan_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
         else                             vm = tile_vector<8, 16, GS, STORE_ALL>(p, T, off, cnt, lane, ab_max, lz);
       } else if (p.path == 1) {
         vm = tile_generic<GS>(p, T, off, cnt, lane, ab_max);
+      } else if (GS == kGradF32 && p.path == kPathSkipButScan) {
+        scan_nonfinite(T.src, off, cnt, lane, ab_max);
       }
       lane_max = vm > lane_max ? vm : lane_max;
     });

@@ -215,7 +215,7 @@ __device__ __forceinline__ void setup_mom(MomParams& p, const TensorDev& T, int 
   auto bad = [](int f) { return f < kFlMin || f > kFlMax; };
   if (bad(fl_in) || bad(fl_out) || bad(fl_m_in) || bad(fl_m_out) || bad(fl_g) || p.d > kDMax ||
       delta > kDeltaMax || delta < -kDeltaMax || delta_m > kDeltaMax || delta_m < -kDeltaMax) {
-    p.path = 0; status_bits |= kStatusDomain; return;
+    p.path = skipped_path<GS>(fl_g); status_bits |= kStatusDomain; return;
   }
   const int F = fl_in + p.d, G = fl_m_out + 16;
   p.k1 = fl_m_in + 16 - G;
@@ -330,6 +330,8 @@ momentum_step_kernel(const TensorDev* __restrict__ tensors, const Tile* __restri
         else                             { if (p.wm == 8) tile_fast_mom_dispatch<16, 16, 8, GS>(p, T, off, cnt, lane, vm, wm, ab_max); else tile_fast_mom_dispatch<16, 16, 16, GS>(p, T, off, cnt, lane, vm, wm, ab_max); }
       } else if (p.path == 1) {
         tile_generic_mom<GS>(p, T, off, cnt, lane, vm, wm, ab_max);
+      } else if (GS == kGradF32 && p.path == kPathSkipButScan) {
+        scan_nonfinite(T.src, off, cnt, lane, ab_max);
       }
     });
 

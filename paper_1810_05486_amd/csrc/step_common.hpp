@@ -71,6 +71,23 @@ __device__ __forceinline__ float quant_f32(float x, float scale, float lo, float
   return ab > 0x7f800000u ? 0.0f : y;
 }
 
+// A tensor that a kernel fed from the fp32 gradients skips for its domain (path -1 in the kernels' parameter blocks:
+// some fraclen other than the gradients' is out of range): the quantization the call stands for would still have
+// looked at the gradients and reported a NaN or an infinity among them, so the status word must too.
+constexpr int kPathSkipButScan = -1;
+__device__ __forceinline__ void scan_nonfinite(const void* src, uint64_t off, uint32_t cnt, int lane, uint32_t& ab_max)
+{
+  const uint32_t* s = (const uint32_t*)src + off;
+  for (uint32_t j = lane; j < cnt; j += kWave) {
+    const uint32_t ab = s[j] & 0x7fffffffu;
+    ab_max = ab > ab_max ? ab : ab_max;
+  }
+}
+template <int GS> __device__ __forceinline__ int skipped_path(int fl_g)
+{
+  return GS == kGradF32 && fl_g >= kFlMin && fl_g <= kFlMax ? kPathSkipButScan : 0;
+}
+
 __device__ __forceinline__ int sx8(int w, int b)  { return (int)(int8_t)(w >> (8 * b)); }
 __device__ __forceinline__ int sx16(int w, int h) { return (int)(int16_t)(w >> (16 * h)); }
 
