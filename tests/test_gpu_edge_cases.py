@@ -674,3 +674,65 @@ def test_fraclens_and_maxima_on_both_sides_of_the_launch_size_where_the_last_wor
             host //= 4
             dev.copy_(torch.from_numpy(host))
     tl.destroy()
+
+
+@pytest.mark.parametrize("seed", fuzz_seeds(3))
+def test_select_and_quantize_random_lists(seed):
+    """Max-abs fraclen selection followed by quantization on random lists: any size, sources that are only 4-byte
+    aligned, 8- and 16-bit destinations (the gradient array or theta), magnitudes anywhere in fp32's range, the
+    tensor's maximum planted on both sides of the significand edge of the fraclen rule, and now and then zeros only,
+    subnormals only, a NaN or an infinity."""
+    say("select + quantize: random lists, seed %d" % seed)
+    rng = np.random.default_rng(3100 + seed)
+    pr = random.Random(3200 + seed)
+    f = np.float32
+    for rep in range(4):
+        sel = pr.choice([lpk.LPK_SEL_GRAD, lpk.LPK_SEL_THETA])
+        xs, bits, keep, descs, outs = [], [], [], [], []
+        for _ in range(pr.randint(1, 14)):
+            n = pr.choice(SIZES + [70001])
+            W = pr.choice([8, 16])
+            kind = pr.random()
+            e = pr.randint(-120, 120)
+            if kind < 0.08:
+                x = np.zeros(n, dtype=f)
+            elif kind < 0.14:
+                x = (rng.integers(-200, 200, n).astype(np.int32).view(np.uint32) & np.uint32(0x807fffff)).view(f).copy()   # subnormals
+            else:
+                with np.errstate(over="ignore"):
+                    x = (rng.standard_normal(n) * 2.0 ** e).astype(f)
+                if n and kind < 0.6:           # plant a maximum whose significand sits at the edge where the candidate is one too fine
+                    E = int(np.clip(127 + e + 3, 1, 254))
+                    m = pr.choice([0x7FFFFF, 0x7FFFFF - (1 << (24 - W)) + 1, 0x7FFFFF - (1 << (24 - W)), 0x7FFFFF - (1 << (24 - W)) + 2, 0])
+                    x[pr.randrange(n)] = np.array([(E << 23) | m | (pr.getrandbits(1) << 31)], dtype=np.uint32).view(f)[0]
+                if n and kind > 0.93:
+                    x[pr.randrange(n)] = pr.choice([np.nan, np.inf, -np.inf])
+            mis = pr.choice([0, 0, 1, 3, 4])
+            sbuf = torch.zeros(n + 16, dtype=torch.float32, device=DEV)
+            src = sbuf[mis:mis + n]; src.copy_(torch.from_numpy(x))
+            obuf = torch.full((n + 32,), 9, dtype=TT[W], device=DEV)
+            omis = pr.choice([0, 0, 1, 8])
+            out = obuf[omis:omis + n]
+            other = torch.zeros(max(n, 1), dtype=torch.int16 if sel == lpk.LPK_SEL_THETA else torch.int8, device=DEV)[:n]
+            descs.append(lpk.make_desc(out, None, other, src) if sel == lpk.LPK_SEL_THETA else lpk.make_desc(other, None, out, src))
+            xs.append(x); bits.append(W); keep += [sbuf, obuf, other]; outs.append((obuf, out, omis, n))
+        tl = lpk.TensorList(descs)
+        defaults = [pr.randint(-64, 64) for _ in xs]
+        fl = torch.tensor(defaults, dtype=torch.int32, device=DEV)
+        fl_out = torch.full((len(xs),), -99, dtype=torch.int32, device=DEV)
+        status = torch.zeros(1, dtype=torch.int32, device=DEV)
+        lpk.lpk_select_fraclen(tl, lpk.LPK_F32, sel, None, None, fl, fl_out, status)
+        lpk.lpk_quantize_tensor(tl, sel, fl_out, status)
+        torch.cuda.synchronize()
+        st = ref.new_status()
+        got_fl = fl_out.cpu().tolist()
+        for t, x in enumerate(xs):
+            want_fl = ref.select_fraclen_f32(x, bits[t], defaults[t], st)
+            assert got_fl[t] == want_fl, (t, x.size, bits[t], got_fl[t], want_fl)
+            want_q = ref.quantize(x, bits[t], want_fl, st)
+            obuf, out, omis, n = outs[t]
+            assert np.array_equal(out.cpu().numpy(), want_q), (t, x.size, bits[t], want_fl)
+            host = obuf.cpu().numpy()
+            assert (host[:omis] == 9).all() and (host[omis + n:] == 9).all(), ("bytes around the destination written", t)
+        assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
+        tl.destroy()
