@@ -543,6 +543,68 @@ def test_lazy_stores_in_every_regime(tb, cb, store_all):
     tl.destroy()
 
 
+@pytest.mark.parametrize("seed", fuzz_seeds(3))
+def test_lazy_stores_random_sparsity(seed):
+    """The store-skipping forms of the update on random lists: several tensors of the three vector width pairs, any
+    length, gradients that are zero except for random patterns per 1024-element run (nothing, one element, a few,
+    one aligned 64-byte stretch of the accumulator, half, everything; small enough to touch only the accumulator
+    or large enough to move theta), six steps alternating between the int16 and the fp32 gradient entry points,
+    with and without LPK_OPT_STORE_ALL; every byte against the oracle after each step."""
+    say("lazy stores: random sparsity, seed %d" % seed)
+    rng = np.random.default_rng(3300 + seed)
+    pr = random.Random(3400 + seed)
+    store_all = seed % 2
+    tens = []
+    for _ in range(pr.randint(1, 5)):
+        tb, cb = pr.choice([(8, 8), (8, 8), (8, 16), (16, 16)])
+        n = pr.choice([1000, 4096, 9000, 70 * 4096 + 1000, 33000, 150000])
+        t = dict(tb=tb, cb=cb, n=n, d=cb - 1, fl_t=7 if tb == 8 else 12)
+        t["fl_g"] = t["fl_t"] + t["d"] - 4                 # step shift 12: the 32-bit arithmetic, where stores are lazy
+        t["theta"] = rng.integers(-100, 100, size=n).astype(NP[tb]); t["comp"] = np.zeros(n, dtype=NP[cb])
+        t["d_theta"] = torch.from_numpy(t["theta"]).to(DEV); t["d_comp"] = torch.from_numpy(t["comp"]).to(DEV)
+        t["d_grad"] = torch.zeros(n, dtype=torch.int16, device=DEV); t["d_src"] = torch.zeros(n, dtype=torch.float32, device=DEV)
+        tens.append(t)
+    tl = lpk.TensorList([lpk.make_desc(t["d_theta"], t["d_comp"], t["d_grad"], t["d_src"]) for t in tens])
+    lpk.lpk_tensor_list_set_option(tl, lpk.LPK_OPT_STORE_ALL, store_all)
+    i32 = dict(dtype=torch.int32, device=DEV)
+    a_fl_t = torch.tensor([t["fl_t"] for t in tens], **i32); a_fl_g = torch.tensor([t["fl_g"] for t in tens], **i32)
+    vmax = torch.zeros(len(tens), dtype=torch.int64, device=DEV); status = torch.zeros(1, **i32)
+    lr_q = 16384
+    for step in range(6):
+        fused = pr.random() < 0.5
+        want_v = []
+        for t in tens:
+            n = t["n"]
+            g = np.zeros(n, dtype=np.int16)
+            mode = pr.choice(["mixed", "mixed", "none", "all", "rare"])
+            for lo in range(0, n, 1024):
+                m = min(1024, n - lo)
+                k = {"none": 0, "all": 5, "rare": pr.choice([0] * 15 + [1])}.get(mode, pr.randint(0, 5))
+                big = pr.random() < 0.2
+                val = (lambda size: rng.integers(3000, 30000, size=size) * rng.choice([-1, 1], size=size)) if big else \
+                      (lambda size: rng.choice([8, -8, 16, 4, -4], size=size))
+                if k == 1:   g[lo + pr.randrange(m)] = val(1)[0]
+                elif k == 2: idx = rng.choice(m, size=min(m, pr.randint(2, 20)), replace=False); g[lo + idx] = val(idx.size)
+                elif k == 3: a = (pr.randrange(m) // 64) * 64; w = min(64, m - a); g[lo + a:lo + a + w] = val(w)
+                elif k == 4: idx = rng.choice(m, size=m // 2, replace=False); g[lo + idx] = val(idx.size)
+                elif k == 5: g[lo:lo + m] = val(m)
+            want_v.append(ref.kahan_sgd_step(t["theta"], t["comp"], g, t["d"], t["fl_t"], t["fl_t"], t["fl_g"], lr_q))
+            if fused:
+                t["d_src"].copy_(torch.from_numpy(g.astype(np.float32) * np.float32(2.0 ** -t["fl_g"])))
+            else:
+                t["d_grad"].copy_(torch.from_numpy(g))
+        if fused:
+            lpk.lpk_kahan_sgd_step_f32grad(tl, a_fl_t, a_fl_t, a_fl_g, lr_q, 0, vmax, status)
+        else:
+            lpk.lpk_kahan_sgd_step(tl, a_fl_t, a_fl_t, a_fl_g, lr_q, 0, vmax, status)
+        torch.cuda.synchronize()
+        assert vmax.cpu().tolist() == want_v and int(status.item()) == 0, (step, fused)
+        for i, t in enumerate(tens):
+            bad_t = int((t["d_theta"].cpu().numpy() != t["theta"]).sum()); bad_c = int((t["d_comp"].cpu().numpy() != t["comp"]).sum())
+            assert bad_t == 0 and bad_c == 0, (step, fused, i, t["tb"], t["cb"], t["n"], bad_t, bad_c)
+    tl.destroy()
+
+
 @pytest.mark.parametrize("store_all", [0, 1])
 def test_all_int8_update_with_int8_gradients(store_all):
     """The all-8-bit mode of Section 4 (int8 theta, int8 accumulator, int8 gradients) on the vector path: sparse and
