@@ -278,6 +278,42 @@ def test_reselect_from_vmax_matches_oracle():
     tl.destroy()
 
 
+@pytest.mark.parametrize("sel", [lpk.LPK_SEL_MOMENTUM, lpk.LPK_SEL_SECOND])
+def test_reselect_of_the_moment_grids_from_their_maxima(sel):
+    """The same rule for the velocity / first moment and the second moment: the maximum is on the state's own grid
+    (no comp shift), the width is the state's, the result stays within 15 of the current fraclen; out-of-range
+    fraclens are flagged."""
+    say("fraclen re-selection of the moments' grids, sel %d" % sel)
+    pr = random.Random(50 + sel)
+    n_t = 400
+    z8 = torch.zeros(16, dtype=torch.int8, device=DEV); z16 = torch.zeros(16, dtype=torch.int16, device=DEV)
+    descs, widths = [], []
+    for t in range(n_t):
+        wm, wu = pr.choice([8, 16]), pr.choice([8, 16])
+        descs.append(lpk.make_desc(z8, z8, z16, None, momentum=z8 if wm == 8 else z16, second=z8 if wu == 8 else z16))
+        widths.append(wm if sel == lpk.LPK_SEL_MOMENTUM else wu)
+    tl = lpk.TensorList(descs)
+    mx, fin, cur = [], [], []
+    for t in range(n_t):
+        W = widths[t]
+        mx.append(pr.choice([0, 1, 127, 128, 255, 32767, 32768, (1 << pr.randint(1, 40)) - 1, pr.randint(1, 1 << 38),
+                             ((1 << W) - 1) << pr.randint(0, 20), (((1 << W) - 1) << pr.randint(1, 20)) - 1]))
+        fi = pr.randint(-64, 64) if pr.random() < .95 else pr.choice([-70, 70])
+        fin.append(fi)
+        cur.append(max(-64, min(64, fi + pr.randint(-15, 15))) if pr.random() < .97 else 80)
+    d_mx = torch.tensor(mx, dtype=torch.int64, device=DEV)
+    d_fin = torch.tensor(fin, dtype=torch.int32, device=DEV); d_cur = torch.tensor(cur, dtype=torch.int32, device=DEV)
+    d_out = torch.zeros(n_t, dtype=torch.int32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    lpk.lpk_select_fraclen(tl, lpk.LPK_VMAX_U64, sel, d_mx, d_fin, d_cur, d_out, status)
+    torch.cuda.synchronize()
+    st = ref.new_status()
+    want = [ref.select_fraclen_vmax(mx[t], fin[t], widths[t], cur[t], st) for t in range(n_t)]
+    assert d_out.cpu().tolist() == want
+    assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
+    tl.destroy()
+
+
 def test_host_side_argument_errors_with_a_live_list():
     say("argument errors")
     t = torch.zeros(64, dtype=torch.int8, device=DEV)
