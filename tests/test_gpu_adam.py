@@ -310,3 +310,35 @@ def test_adam_fused_fp32_gradient_step_equals_quantize_then_step():
     run_config(cfg, range(4), fused=True)
     run_config(cfg, range(3), comp_bits=[16] * cfg.n_tensors, fused=True)
     run_config(workloads.config(5, big_elems=70001, n_tiny=20), range(3), state_bits=8, fl_mom0=16, fl_sec0=30, fused=True)
+
+
+def random_workload(pr, cid):
+    """A small random parameter set with its own training recipe: 1-12 tensors of any rank and length up to 50 000,
+    8- or 16-bit parameters per tensor, a learning-rate drop halfway, any of the gradient distributions."""
+    shapes = []
+    for _ in range(pr.randint(1, 12)):
+        r = pr.random()
+        if r < 0.3:
+            shapes.append((pr.choice([1, 7, 64, 256, 1000, 4096, 4097, 20000]),))
+        elif r < 0.8:
+            shapes.append((pr.randint(1, 200), pr.randint(1, 250)))
+        else:
+            shapes.append((pr.randint(1, 24), pr.randint(1, 24), 3, 3))
+    bits = [pr.choice([8, 8, 16]) for _ in shapes]
+    lr0 = pr.choice([66, 655, 3277, 6554, 32768])
+    return workloads.Config(cid, "random workload", shapes, bits, 40, [(0, lr0), (pr.randint(8, 25), max(1, lr0 // pr.choice([2, 10])))],
+                            pr.choice([0, 0, 7, 300]), pr.choice(["normal_1e-3", "normal_loguniform", "laplace_1e-4", "normal_fanin"]),
+                            pr.random() < 0.5)
+
+
+@pytest.mark.parametrize("seed", fuzz_seeds(3))
+def test_adam_random_workloads_follow_the_oracle_step_by_step(seed):
+    """Random parameter sets through 30 consecutive ADAM steps (bias-corrected step size per step, both moment grids
+    re-selected every step with the one-step lag: the kernel's short and general arithmetic routes alternate as the
+    grids settle), plain or fed from the fp32 gradients; everything after every step."""
+    pr = random.Random(4500 + seed)
+    cfg = random_workload(pr, 300 + seed)
+    fused = pr.random() < 0.4
+    say("adam: random workload %d: %d tensors, %d parameters, reselect=%s, fused=%s" % (seed, cfg.n_tensors, cfg.n_params,
+                                                                                       cfg.reselect, fused))
+    run_config(cfg, range(30), lr=pr.choice([1e-3, 1e-2, 1e-4]), state_bits=pr.choice([16, 16, 8]), fused=fused)

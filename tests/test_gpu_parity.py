@@ -2,6 +2,8 @@
 import os
 import sys
 
+import random
+
 import numpy as np
 import pytest
 
@@ -194,3 +196,46 @@ def test_whole_step_replayed_from_a_hip_graph(fused):
             compare(dev, host, "config %d graph replay %d" % (cfg.id, s))
         del graph
         dev.close()
+
+
+def fuzz_seeds(default_count):
+    """Seeds of the random tests: 0..default_count-1, or LPK_FUZZ_SEEDS=lo:hi for a longer differential run."""
+    spec = os.environ.get("LPK_FUZZ_SEEDS")
+    if not spec:
+        return range(default_count)
+    lo, hi = (int(x) for x in spec.split(":"))
+    return range(lo, hi)
+
+
+def random_workload(pr, cid):
+    """A small random parameter set with its own training recipe: 1-12 tensors of any rank and length up to 50 000,
+    8- or 16-bit parameters per tensor, a learning-rate drop halfway, any of the gradient distributions."""
+    shapes = []
+    for _ in range(pr.randint(1, 12)):
+        r = pr.random()
+        if r < 0.3:
+            shapes.append((pr.choice([1, 7, 64, 256, 1000, 4096, 4097, 20000]),))
+        elif r < 0.8:
+            shapes.append((pr.randint(1, 200), pr.randint(1, 250)))
+        else:
+            shapes.append((pr.randint(1, 24), pr.randint(1, 24), 3, 3))
+    bits = [pr.choice([8, 8, 16]) for _ in shapes]
+    lr0 = pr.choice([66, 655, 3277, 6554, 32768])
+    return workloads.Config(cid, "random workload", shapes, bits, 40, [(0, lr0), (pr.randint(8, 25), max(1, lr0 // pr.choice([2, 10])))],
+                            pr.choice([0, 0, 7, 300]), pr.choice(["normal_1e-3", "normal_loguniform", "laplace_1e-4", "normal_fanin"]),
+                            pr.random() < 0.5)
+
+
+@pytest.mark.parametrize("seed", fuzz_seeds(3))
+def test_random_workloads_follow_the_oracle_step_by_step(seed):
+    """Whole trajectories, not single calls: random parameter sets through 30 consecutive steps of select, quantize and
+    update (or the fused update), with or without fraclen re-selection, weight decay, a 16-bit accumulator under
+    8-bit parameters, or no accumulator at all; every byte and every scalar after every step."""
+    pr = random.Random(4100 + seed)
+    cfg = random_workload(pr, 100 + seed)
+    kahan = pr.random() < 0.85
+    comp_bits = [16 if b == 8 and pr.random() < 0.3 else b for b in cfg.bits] if kahan and pr.random() < 0.4 else None
+    fused = pr.random() < 0.4
+    say("random workload %d: %d tensors, %d parameters, reselect=%s, kahan=%s, fused=%s" % (seed, cfg.n_tensors, cfg.n_params,
+                                                                                            cfg.reselect, kahan, fused))
+    run_config(cfg, range(30), kahan=kahan, comp_bits=comp_bits, fused=fused)
