@@ -116,3 +116,23 @@ def test_noalloc_step_with_many_staging_chunks():
     assert run_both(4, [(5000, 16, 16, 16, 0)], [15], [15], [18], 6554, 0, steps=1) == 0
     assert run_both(5, specs, [7] * nt, [7] * nt, [18] * nt, 6554, 7, steps=1) == 0
 
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_noalloc_step_on_random_lists(seed):
+    """Random lists (1-90 tensors: one to three staging launches; every width combination, empty and misaligned
+    tensors, no accumulator, grid moves) through both entry points, three steps each."""
+    import random
+    pr = random.Random(5100 + seed)
+    specs = []
+    for _ in range(pr.randint(1, 90)):
+        wt = pr.choice([8, 8, 16])
+        wc = pr.choice([wt, wt, 16 if wt == 8 else wt, 0])
+        wg = pr.choice([16, 16, 8]) if wt == 8 else 16
+        specs.append((pr.choice([0, 1, 17, 256, 1024, 4096, 4097, 9001, 70001]), wt, wc, wg, pr.choice([0, 0, 0, 1, 8])))
+    specs.append((20000, 8, 8, 16, 0))               # something that certainly moves
+    fl_in = [7 if s[1] == 8 else 15 for s in specs]
+    fl_out = [f + pr.choice([0, 0, 0, 1, -1]) for f in fl_in]
+    fl_g = [pr.choice([17, 18, 19, 20]) if s[3] == 16 else pr.choice([9, 10, 11]) for s in specs]
+    say("noalloc: random list %d, %d tensors" % (seed, len(specs)))
+    run_both(10 + seed, specs, fl_in, fl_out, fl_g, pr.choice([655, 6554]), pr.choice([0, 7]), steps=3)
