@@ -66,8 +66,10 @@ class Case:
                              self.d if self.cb and self.d is not None else lpk.LPK_COMP_SHIFT_DEFAULT)
 
 
-def run_list(cases, lr_q, wd_q, want_vmax=True):
+def run_list(cases, lr_q, wd_q, want_vmax=True, store_all=False):
     tl = lpk.TensorList([c.desc() for c in cases])
+    if store_all:
+        lpk.lpk_tensor_list_set_option(tl, lpk.LPK_OPT_STORE_ALL, 1)
     i32 = dict(dtype=torch.int32, device=DEV)
     fl_in = torch.tensor([c.fl_in for c in cases], **i32)
     fl_out = torch.tensor([c.fl_out for c in cases], **i32)
@@ -117,7 +119,7 @@ def test_random_lists_all_widths_shifts_and_alignments(seed):
             cases.append(Case(rng, pr.choice(SIZES), tb, cb, gb, d, fl_in, fl_out, fl_g,
                               misalign=pr.choice([0, 0, 0, 1, 3, 8, 16])))
         run_list(cases, pr.choice([1, 655, 6554, 32768, 65535]), pr.choice([0, 0, 7, 65535]),
-                 want_vmax=pr.random() < 0.8)
+                 want_vmax=pr.random() < 0.8, store_all=pr.random() < 0.3)
 
 
 @pytest.mark.parametrize("tb", [8, 16])
