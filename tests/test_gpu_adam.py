@@ -342,3 +342,49 @@ def test_adam_random_workloads_follow_the_oracle_step_by_step(seed):
     say("adam: random workload %d: %d tensors, %d parameters, reselect=%s, fused=%s" % (seed, cfg.n_tensors, cfg.n_params,
                                                                                        cfg.reselect, fused))
     run_config(cfg, range(30), lr=pr.choice([1e-3, 1e-2, 1e-4]), state_bits=pr.choice([16, 16, 8]), fused=fused)
+
+
+def test_momentum_and_adam_on_a_tensor_longer_than_2_to_the_32_elements():
+    """Element offsets past 32 bits in the two optimizer kernels (rows of 1024 and groups of 8 in ADAM, the momentum
+    kernel's vector path): one tensor of 2^32 + 3 tiles + 77 elements, filled on the device; elements are independent,
+    so the oracle runs on windows -- the start, both sides of the 2^32 boundary, the ragged end, and a few tiles
+    picked at random -- downloaded before the step and compared after it."""
+    n = (1 << 32) + 3 * 4096 + 77
+    say("momentum and ADAM on a tensor of %d elements" % n)
+    g = torch.Generator(device=DEV).manual_seed(5)
+
+    def fill(lo, hi, dtype):
+        out = torch.empty(n, dtype=dtype, device=DEV)
+        step = 1 << 28
+        for a in range(0, n, step):                    # in pieces: randint's int64 intermediate stays small
+            m = min(step, n - a)
+            out[a:a + m] = torch.randint(lo, hi, (m,), generator=g, device=DEV, dtype=torch.int32).to(dtype)
+        return out
+    d = dict(theta=fill(-128, 128, torch.int8), comp=fill(-128, 128, torch.int8), mom=fill(-3000, 3000, torch.int16),
+             sec=fill(0, 3000, torch.int16), grad=fill(-32768, 32768, torch.int16))
+    rnd = random.Random(9)
+    windows = [(0, 8192), ((1 << 32) - 8192, (1 << 32) + 8192), (n - 5000, n)] + \
+              [(t * 4096, t * 4096 + 4096) for t in (rnd.randrange(n // 4096) for _ in range(6))]
+    tl = lpk.TensorList([lpk.make_desc(d["theta"], d["comp"], d["grad"], None, momentum=d["mom"], second=d["sec"])])
+    i32 = dict(dtype=torch.int32, device=DEV)
+    fl = {k: torch.tensor([v], **i32) for k, v in dict(t=7, m=21, u=33, g=20).items()}
+    status = torch.zeros(1, **i32)
+    hyper = (33554, 9, 58982, 65470, 43980, 26)
+    for kernel in ("momentum", "adam"):
+        host = {k: [v[a:b].cpu().numpy().copy() for a, b in windows] for k, v in d.items()}
+        if kernel == "momentum":
+            lpk.lpk_momentum_sgd_step(tl, fl["t"], fl["t"], fl["m"], fl["m"], fl["g"], 6554, 58982, 0, None, None, status)
+        else:
+            lpk.lpk_adam_step(tl, fl["t"], fl["t"], fl["m"], fl["m"], fl["u"], fl["u"], fl["g"], hyper, None, None, None, status)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        for w, (a, b) in enumerate(windows):
+            th, co, mo, se, gr = (host[k][w] for k in ("theta", "comp", "mom", "sec", "grad"))
+            if kernel == "momentum":
+                ref.momentum_sgd_step(th, co, mo, gr, 7, 7, 7, 21, 21, 20, 6554, 58982, 0)
+            else:
+                ref.adam_step(th, co, mo, se, gr, 7, 7, 7, 21, 21, 33, 33, 20, *hyper)
+            for k, want in (("theta", th), ("comp", co), ("mom", mo), ("sec", se)):
+                assert np.array_equal(d[k][a:b].cpu().numpy(), want), (kernel, k, a, b)
+        say("  %s: %d windows bit-exact" % (kernel, len(windows)))
+    tl.destroy()
