@@ -81,12 +81,18 @@ def test_an_empty_tensor_is_a_no_op_whatever_the_fraclens_hold():
         assert ref.kahan_sgd_step(e8, e8, e16, 7, bad, bad, bad, 655, 7, st) == 0
         assert ref.momentum_sgd_step(e8, e8, e16, e16, 7, bad, bad, bad, bad, bad, 655, 58982, 0, st) == (0, 0)
         assert ref.adam_step(e8, e8, e16, e16, e16, 7, bad, bad, bad, bad, bad, bad, bad, 66, 0, 58982, 65470, 0, 0, st) == (0, 0, 0)
+        assert ref.quantize(np.zeros(0, dtype=np.float32), 16, bad, st).size == 0        # quantization too: nothing to put on a grid
+        assert ref.select_fraclen_f32(np.zeros(0, dtype=np.float32), 16, bad, st) == bad  # and the selection keeps the default
         assert int(st[0]) == 0
     # the same fraclens on one element ARE flagged, and the element is left alone
     one8, one16 = np.array([5], dtype=np.int8), np.array([9], dtype=np.int16)
     st = ref.new_status()
     ref.kahan_sgd_step(one8, one8.copy(), one16, 7, 99, 99, 99, 655, 0, st)
     assert int(st[0]) == ref.STATUS_DOMAIN and int(one8[0]) == 5
+    st = ref.new_status()
+    out = np.full(1, 9, dtype=np.int16)
+    ref.quantize(np.ones(1, dtype=np.float32), 16, 99, st, out=out)
+    assert int(st[0]) == ref.STATUS_DOMAIN and int(out[0]) == 9
 
 
 # ---------------------------------------------------------------- Section 3: eq. 4 against eq. 5 on the boundary
