@@ -375,8 +375,13 @@ def measure_small_configs(args):
             dev.step_fused(5 + s)
         torch.cuda.synchronize()
         eager_fused = (time.perf_counter() - t0) / reps * 1e6
+        t0 = time.perf_counter()
+        for s in range(reps):
+            dev.step(5 + s, onepass=True)
+        torch.cuda.synchronize()
+        eager_onepass = (time.perf_counter() - t0) / reps * 1e6
         r = {"params": cfg.n_params, "tensors": cfg.n_tensors, "eager_us": eager, "eager_fused_us": eager_fused,
-             "hbm_floor_us": FLOOR_US[cid]}
+             "eager_onepass_us": eager_onepass, "hbm_floor_us": FLOOR_US[cid]}
         if not cfg.reselect:                                 # re-selection rotates device arrays between steps
             for key, fused in (("graph_us", False), ("graph_fused_us", True)):
                 g = dev.capture_step(5, fused=fused)
@@ -528,6 +533,42 @@ def main():
     torch.cuda.synchronize()
     fwall = time.perf_counter() - t1
     f_upd = [e[1].elapsed_time(e[2]) for e in fev]
+
+    # ---- the whole path with selection and quantization in one pass (lpk_select_quantize: last step's fraclens are the
+    #      guess; the int16 gradients are written as in the three-call path), then the same update
+    def plain_update(s, k):
+        if args.adam:
+            dev.update_adam(workloads.adam_hyper(s), k)
+        elif mu_q16 is None:
+            dev.update(cfg.lr_q16(s), cfg.wd_q16, k)
+        else:
+            dev.update_momentum(cfg.lr_q16(s), mu_q16, cfg.wd_q16, k)
+    oev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    for s in range(2):
+        dev.quantize_grads_onepass(s % n_src)
+        plain_update(s, s % n_src)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for i in range(K):
+        s = args.warmup + 2 * K + i
+        k = s % n_src
+        oev[i][0].record()
+        dev.quantize_grads_onepass(k)
+        oev[i][1].record()
+        plain_update(s, k)
+        oev[i][2].record()
+    torch.cuda.synchronize()
+    owall = time.perf_counter() - t1
+    o_sq = [e[0].elapsed_time(e[1]) for e in oev]
+    sq_bytes = (4 + args.grad_bits // 8) * cfg.n_params
+    onepass = {"value": cfg.n_params / (owall / K) / 1e9, "unit": "Gparam/s", "ms_per_step": owall * 1e3 / K,
+               "stage_ms": {"select_quantize": statistics.mean(o_sq), "update": sum(e[1].elapsed_time(e[2]) for e in oev) / K},
+               "select_quantize_ms": dict(spread(o_sq), max=max(o_sq)),
+               "roofline": {"bound": "hbm", "kernel": "quantize_guess_kernel", "bytes_per_launch": sq_bytes, "peak": HBM_PEAK_GBS,
+                            "unit": "GB/s", "achieved": sq_bytes / (statistics.mean(o_sq) * 1e-3) / 1e9,
+                            "frac": sq_bytes / (statistics.mean(o_sq) * 1e-3) / 1e9 / HBM_PEAK_GBS},
+               "note": "same outputs as the three-call path (fraclens, int gradients, update); every guess held in these steps "
+                       "unless select_quantize_ms.max stands out: a wrong guess costs that tensor one more quantization pass"}
     f_upd_ms = sum(f_upd) / K
     upd_kernel, fus_kernel = kernel_names(args)
     nbytes = update_bytes(cfg, dev, args)
@@ -649,6 +690,7 @@ def main():
                                 "frac": (4 + args.grad_bits // 8) * cfg.n_params / (qnt_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                 "traffic": tk.get("quantize", {}).get("bytes")}},
         "fused_path": fused,
+        "onepass_path": onepass,
         "graph_replay": graph,
         "device_status_word": status,
     }

@@ -184,6 +184,22 @@ int lpk_quantize_tensor(lpk_tensor_list* list, int dst_sel, const int32_t* fl,
                         uint32_t* status, void* stream);
 
 /*
+ * lpk_select_fraclen(LPK_F32, dst_sel) followed by lpk_quantize_tensor(dst_sel), with ONE read of the fp32 data
+ * where the caller's guess holds (Section 6: the exponent follows the scanned maximum; it also mentions the
+ * history of maxima, and from one training step to the next a tensor's exponent rarely changes).
+ * fl_guess[t] is the fraclen the caller expects for tensor t -- normally last step's -- and, as fl_default does in
+ * lpk_select_fraclen, the value an empty or all-zero tensor keeps.  The pass quantizes every tensor with its guess
+ * while it scans for the maximum; the true fraclen from the maximum goes to fl_out[t]; a tensor whose guess was
+ * wrong (or outside [-64, 64]) is quantized again with the true one.  Tensors of at most 4096 elements never need
+ * that: one wavefront finds the maximum first.  dst, fl_out and the status word end up exactly as after the two
+ * calls with fl_default = fl_guess; only the time differs (a wrong guess costs one more pass over that tensor).
+ * fl_guess, fl_out: device int32[n_tensors]; they may be the same array.  Every non-empty tensor needs src_f32.
+ * Errors: INVALID_ARG (NULL argument, bad dst_sel, a tensor without src_f32, wrong device), DEVICE.
+ */
+int lpk_select_quantize(lpk_tensor_list* list, int dst_sel, const int32_t* fl_guess, int32_t* fl_out,
+                        uint32_t* status, void* stream);
+
+/*
  * One lazy-update step over every tensor of the list in a single fused launch
  * (Algorithm 1; eq. 1 when comp == NULL).  Per tensor t and element i, with
  * F = fl_theta_in[t] + d the working grid (units: LSBs of c) and

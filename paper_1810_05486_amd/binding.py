@@ -62,6 +62,8 @@ def lib():
         L.lpk_tensor_list_tiles.restype = u64
         L.lpk_select_fraclen.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, vp]
         L.lpk_quantize_tensor.argtypes = [vp, ci, vp, vp, vp]
+        L.lpk_select_quantize.argtypes = [vp, ci, vp, vp, vp, vp]
+        L.lpk_select_quantize.restype = ci
         L.lpk_kahan_sgd_step.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
         L.lpk_kahan_sgd_step_f32grad.argtypes = [vp, vp, vp, vp, u32, u32, vp, vp, vp]
         L.lpk_kahan_sgd_step_f32grad.restype = ci
@@ -184,6 +186,11 @@ def lpk_select_fraclen(tl, src_kind, dst_sel, vmax, fl_theta_in, fl_default, fl_
 def lpk_quantize_tensor(tl, dst_sel, fl, status=None, stream=None):
     _check(lib().lpk_quantize_tensor(tl.handle, dst_sel, _addr(fl), _addr(status), _stream(stream)),
            "lpk_quantize_tensor")
+
+
+def lpk_select_quantize(tl, dst_sel, fl_guess, fl_out, status=None, stream=None):
+    _check(lib().lpk_select_quantize(tl.handle, dst_sel, _addr(fl_guess), _addr(fl_out), _addr(status), _stream(stream)),
+           "lpk_select_quantize")
 
 
 def lpk_kahan_sgd_step(tl, fl_theta_in, fl_theta_out, fl_grad, lr_q16, wd_q16=0, vmax_out=None, status=None,

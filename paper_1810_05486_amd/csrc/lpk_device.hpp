@@ -151,6 +151,24 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
 
 __device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// ---- fraclen of an fp32 maximum ------------------------------------------------
+__device__ __forceinline__ int clamp_fl(int fl) { return fl > kFlMax ? kFlMax : (fl < kFlMin ? kFlMin : fl); }
+
+// Max bit pattern of a tensor -> fraclen.  With e = floor(log2 M) the candidate is W - 2 - e (M lands in
+// [2^(W-2), 2^(W-1))); it is one too fine exactly when M * 2^fl reaches 2^(W-1) - 1/2, i.e. when the 24-bit
+// significand m satisfies m >= 2^24 - 2^(24-W).
+__device__ __forceinline__ int fraclen_of_f32max(uint32_t b, int W, int fl_default, uint32_t* status)
+{
+  if (b >= 0x7f800000u) { if (status) atomicOr(status, kStatusNonFinite); return kFlMin; }
+  if (b == 0) return fl_default;
+  const int E = (int)(b >> 23);
+  if (E == 0) return kFlMax;                          // subnormal maximum: far finer than the domain allows
+  const uint32_t m = (b & 0x7fffffu) | 0x800000u;
+  int fl = W - 2 - (E - 127);
+  if (m >= (1u << 24) - (1u << (24 - W))) fl -= 1;
+  return clamp_fl(fl);
+}
+
 // ---- ending a launch in its last workgroup ---------------------------------
 // Per-tensor maxima are gathered with atomics from every workgroup of a launch.  In small launches (up to
 // kFoldMaxBlocks workgroups, lists of up to kFoldMaxTensors tensors) the workgroup that finishes last turns them

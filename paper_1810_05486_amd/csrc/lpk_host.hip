@@ -14,6 +14,9 @@ hipError_t launch_select_vmax(const TensorDev*, uint32_t n_tensors, int sel, con
                               hipStream_t);
 hipError_t launch_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t grid, int to_theta,
                            const int32_t* fl, uint32_t* status, hipStream_t);
+hipError_t launch_select_quantize(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid, int to_theta,
+                                  const int32_t* fl_guess, int32_t* fl_out, uint32_t* scratch, uint32_t* redo, uint32_t* redo_any,
+                                  uint32_t* status, hipStream_t);
 hipError_t launch_momentum_step(const TensorDev*, const Tile*, uint32_t n_tiles, uint32_t n_tensors, uint32_t grid,
                                 int grad_is_f32, const int32_t* fl_in, const int32_t* fl_out, const int32_t* fl_m_in, const int32_t* fl_m_out,
                                 const int32_t* fl_g, uint32_t lr, uint32_t mu, uint32_t wd,
@@ -46,7 +49,8 @@ struct lpk_tensor_list {
   TensorDev* d_tensors = nullptr;
   Tile*      d_tiles   = nullptr;
   uint32_t*  d_scratch = nullptr;  // one max word per tensor, zero between calls; then two workgroup counters (max-abs
-                                   // scan, update kernels), zero between launches
+                                   // scan, update kernels), zero between launches; then lpk_select_quantize's
+                                   // "quantize again" flag per tensor and its "any" word
   uint64_t*  d_fold    = nullptr;  // three per-tensor accumulators for the update kernels' maxima, zero between launches
 };
 
@@ -122,13 +126,13 @@ int lpk_tensor_list_create(const lpk_tensor_desc* descs, uint32_t n_tensors, lpk
     L->n_cu = (uint32_t)n_cu;
     set_grids(L);
     ok = hipMalloc((void**)&L->d_tensors, sizeof(TensorDev) * n_tensors) == hipSuccess &&
-         hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * ((size_t)n_tensors + 2)) == hipSuccess &&
+         hipMalloc((void**)&L->d_scratch, sizeof(uint32_t) * (2 * (size_t)n_tensors + 3)) == hipSuccess &&
          hipMalloc((void**)&L->d_fold, sizeof(uint64_t) * 3 * (size_t)n_tensors) == hipSuccess &&
          (tiles.empty() || hipMalloc((void**)&L->d_tiles, sizeof(Tile) * tiles.size()) == hipSuccess);
   }
   if (ok) {
     ok = hipMemcpy(L->d_tensors, tensors.data(), sizeof(TensorDev) * n_tensors, hipMemcpyHostToDevice) == hipSuccess &&
-         hipMemset(L->d_scratch, 0, sizeof(uint32_t) * ((size_t)n_tensors + 2)) == hipSuccess &&
+         hipMemset(L->d_scratch, 0, sizeof(uint32_t) * (2 * (size_t)n_tensors + 3)) == hipSuccess &&
          hipMemset(L->d_fold, 0, sizeof(uint64_t) * 3 * (size_t)n_tensors) == hipSuccess &&
          (tiles.empty() || hipMemcpy(L->d_tiles, tiles.data(), sizeof(Tile) * tiles.size(), hipMemcpyHostToDevice) == hipSuccess) &&
          hipDeviceSynchronize() == hipSuccess;
@@ -203,6 +207,19 @@ int lpk_quantize_tensor(lpk_tensor_list* L, int dst_sel, const int32_t* fl, uint
   if (!L->all_src) return LPK_ERR_INVALID_ARG;
   hipError_t e = launch_quantize(L->d_tensors, L->d_tiles, L->n_tiles, L->grid_quant, dst_sel == LPK_SEL_THETA, fl, status,
                                  static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
+}
+
+int lpk_select_quantize(lpk_tensor_list* L, int dst_sel, const int32_t* fl_guess, int32_t* fl_out, uint32_t* status, void* stream)
+{
+  if (!L || !fl_guess || !fl_out) return LPK_ERR_INVALID_ARG;
+  if (!on_list_device(L)) return LPK_ERR_INVALID_ARG;
+  if (dst_sel != LPK_SEL_GRAD && dst_sel != LPK_SEL_THETA) return LPK_ERR_INVALID_ARG;
+  if (!L->all_src) return LPK_ERR_INVALID_ARG;
+  uint32_t* redo = L->d_scratch + L->n_tensors + 2;
+  hipError_t e = launch_select_quantize(L->d_tensors, L->d_tiles, L->n_tiles, L->n_tensors, L->grid_quant, dst_sel == LPK_SEL_THETA,
+                                        fl_guess, fl_out, L->d_scratch, redo, redo + L->n_tensors, status,
+                                        static_cast<hipStream_t>(stream));
   return e == hipSuccess ? LPK_OK : LPK_ERR_DEVICE;
 }
 

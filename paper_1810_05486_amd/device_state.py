@@ -139,6 +139,11 @@ class DeviceState:
         lpk.lpk_select_fraclen(L, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, self.fl_grad, self.fl_grad, self.status)
         lpk.lpk_quantize_tensor(L, lpk.LPK_SEL_GRAD, self.fl_grad, self.status)
 
+    def quantize_grads_onepass(self, k=0):
+        """The same result as quantize_grads with one read of the fp32 gradients where last step's fraclens still
+        hold (lpk_select_quantize: fl_grad is guess and result)."""
+        lpk.lpk_select_quantize(self.lists[k], lpk.LPK_SEL_GRAD, self.fl_grad, self.fl_grad, self.status)
+
     def select_grads(self, k=0):
         """fp32 gradients in source arena k -> per-tensor fraclen only (for the steps that quantize in registers)."""
         lpk.lpk_select_fraclen(self.lists[k], lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, self.fl_grad, self.fl_grad, self.status)
@@ -200,9 +205,12 @@ class DeviceState:
                                    self.fl_next, self.fl_spare, self.status)
             self.fl_theta, self.fl_next, self.fl_spare = self.fl_next, self.fl_spare, self.fl_theta
 
-    def step(self, step_idx, k=0, mu_q16=None):
+    def step(self, step_idx, k=0, mu_q16=None, onepass=False):
         """One pass of the whole hot path over gradients already resident in source arena k."""
-        self.quantize_grads(k)
+        if onepass:
+            self.quantize_grads_onepass(k)
+        else:
+            self.quantize_grads(k)
         if mu_q16 is None:
             self.update(self.cfg.lr_q16(step_idx), self.cfg.wd_q16, k)
         else:

@@ -470,6 +470,11 @@ def test_a_list_of_empty_tensors_is_a_no_op():
     status = torch.zeros(1, **i32)
     lpk.lpk_select_fraclen(tl, lpk.LPK_F32, lpk.LPK_SEL_GRAD, None, None, fl, out, status)
     lpk.lpk_quantize_tensor(tl, lpk.LPK_SEL_GRAD, fl, status)
+    lpk.lpk_quantize_tensor(tl, lpk.LPK_SEL_GRAD, fl_bad, status)
+    out2 = torch.full((3,), 77, **i32)
+    lpk.lpk_select_quantize(tl, lpk.LPK_SEL_GRAD, fl_bad, out2, status)       # an empty tensor keeps the guess, whatever it is
+    torch.cuda.synchronize()
+    assert out2.cpu().tolist() == [99, 99, 99]
     lpk.lpk_kahan_sgd_step(tl, fl_bad, fl_bad, fl_bad, 655, 7, mx[0], status)
     lpk.lpk_kahan_sgd_step_f32grad(tl, fl_bad, fl_bad, fl_bad, 655, 0, mx[0], status)
     lpk.lpk_momentum_sgd_step(tl, fl_bad, fl_bad, fl_bad, fl_bad, fl_bad, 655, 58982, 0, mx[0], mx[1], status)
@@ -835,4 +840,34 @@ def test_select_and_quantize_random_lists(seed):
             host = obuf.cpu().numpy()
             assert (host[:omis] == 9).all() and (host[omis + n:] == 9).all(), ("bytes around the destination written", t)
         assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0])
+        # the same through lpk_select_quantize, with guesses that hold, miss by one, miss by far, or lie outside the domain
+        want_fls = [ref.select_fraclen_f32(x, bits[t], defaults[t]) for t, x in enumerate(xs)]
+        for rnd in range(3):
+            guesses = []
+            for t, x in enumerate(xs):
+                zero = x.size == 0 or not np.any(x.view(np.uint32) & np.uint32(0x7fffffff))
+                if zero:                       # the guess doubles as the default an empty or all-zero tensor keeps
+                    guesses.append(pr.choice([defaults[t], defaults[t], 70, -70]))
+                else:
+                    guesses.append(pr.choice([want_fls[t], want_fls[t], want_fls[t] + 1, want_fls[t] - 1, pr.randint(-64, 64), 99, -99]))
+            for obuf, out, omis, n in outs:
+                obuf.fill_(9)
+            fl_g = torch.tensor(guesses, dtype=torch.int32, device=DEV)
+            inplace = rnd == 2
+            fl_o = fl_g if inplace else torch.full((len(xs),), -99, dtype=torch.int32, device=DEV)
+            status.zero_()
+            lpk.lpk_select_quantize(tl, sel, fl_g, fl_o, status)
+            torch.cuda.synchronize()
+            st = ref.new_status()
+            got_fl = fl_o.cpu().tolist()
+            for t, x in enumerate(xs):
+                want_fl = ref.select_fraclen_f32(x, bits[t], guesses[t], st)
+                assert got_fl[t] == want_fl, ("one pass", rnd, t, x.size, bits[t], guesses[t], got_fl[t], want_fl)
+                obuf, out, omis, n = outs[t]
+                want_q = np.full(n, 9, dtype=NP[bits[t]])
+                ref.quantize(x, bits[t], want_fl, st, out=want_q)            # out of range: flagged, destination untouched
+                assert np.array_equal(out.cpu().numpy(), want_q), ("one pass", rnd, t, x.size, bits[t], guesses[t], want_fl)
+                host = obuf.cpu().numpy()
+                assert (host[:omis] == 9).all() and (host[omis + n:] == 9).all(), ("bytes around the destination written", t)
+            assert int(status.cpu().numpy().view(np.uint32)[0]) == int(st[0]), ("one pass", rnd, guesses)
         tl.destroy()

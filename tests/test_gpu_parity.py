@@ -44,7 +44,7 @@ def compare(dev, host, what, check_vmax=True):
             assert bad == 0, (what, "comp", t, bad)
 
 
-def run_config(cfg, step_ids, compare_every=1, kahan=True, always=(), comp_bits=None, fused=False, grad_bits=16):
+def run_config(cfg, step_ids, compare_every=1, kahan=True, always=(), comp_bits=None, fused=False, grad_bits=16, onepass=False):
     """A workload whose gradients cycle through a few draws (config 5) keeps every draw resident, in HBM and on the
     host, as bench.py does: from the second round of the cycle on a step costs no draw and no upload."""
     from paper_1810_05486_amd.device_state import DeviceState
@@ -71,7 +71,7 @@ def run_config(cfg, step_ids, compare_every=1, kahan=True, always=(), comp_bits=
         if fused:
             dev.step_fused(s, k)
         else:
-            dev.step(s, k)
+            dev.step(s, k, onepass=onepass)
         host.step(s, grads)
         if (i + 1) % compare_every == 0 or i == len(step_ids) - 1 or i in always:
             compare(dev, host, "config %d step %d" % (cfg.id, s))
@@ -169,6 +169,25 @@ def test_all_8_bit_mode_whole_path():
     run_config(cfg, range(3), grad_bits=8, comp_bits=[16] * cfg.n_tensors)
 
 
+def test_selection_and_quantization_in_one_pass_on_every_workload():
+    """lpk_select_quantize in place of select + quantize, with last step's fraclens as the guess: the first step's
+    guess is the initial default (wrong for most tensors: quantized again), later ones mostly hold on the single-tensor
+    and stress workloads and often fail on the small networks, whose maxima move from draw to draw; every byte, every
+    fraclen and the status word after every step either way."""
+    say("one-pass selection + quantization: config 1")
+    run_config(workloads.config(1), range(30), onepass=True)
+    say("one-pass selection + quantization: config 2 (int16, grid moves)")
+    run_config(workloads.config(2), range(40), onepass=True)
+    say("one-pass selection + quantization: config 3")
+    run_config(workloads.config(3), range(12), onepass=True)
+    say("one-pass selection + quantization: config 4 (mixed widths)")
+    run_config(workloads.config(4), range(6), onepass=True)
+    say("one-pass selection + quantization: config 5 reduced")
+    run_config(workloads.config(5, big_elems=(1 << 23) + 37, n_tiny=300), range(7), onepass=True)
+    say("one-pass selection + quantization: all 8 bits, config 5 reduced")
+    run_config(workloads.config(5, big_elems=(1 << 22) + 77, n_tiny=100), range(4), onepass=True, grad_bits=8)
+
+
 @pytest.mark.parametrize("fused", [False, True])
 def test_whole_step_replayed_from_a_hip_graph(fused):
     """The hot calls only enqueue kernels, so a whole step (three calls, or two with the quantization fused into the
@@ -236,6 +255,7 @@ def test_random_workloads_follow_the_oracle_step_by_step(seed):
     kahan = pr.random() < 0.85
     comp_bits = [16 if b == 8 and pr.random() < 0.3 else b for b in cfg.bits] if kahan and pr.random() < 0.4 else None
     fused = pr.random() < 0.4
-    say("random workload %d: %d tensors, %d parameters, reselect=%s, kahan=%s, fused=%s" % (seed, cfg.n_tensors, cfg.n_params,
-                                                                                            cfg.reselect, kahan, fused))
-    run_config(cfg, range(30), kahan=kahan, comp_bits=comp_bits, fused=fused)
+    onepass = not fused and pr.random() < 0.5          # lpk_select_quantize in place of select + quantize
+    say("random workload %d: %d tensors, %d parameters, reselect=%s, kahan=%s, fused=%s, onepass=%s"
+        % (seed, cfg.n_tensors, cfg.n_params, cfg.reselect, kahan, fused, onepass))
+    run_config(cfg, range(30), kahan=kahan, comp_bits=comp_bits, fused=fused, onepass=onepass)
