@@ -535,6 +535,14 @@ def test_select_and_quantize_longer_than_2_to_the_32_elements():
     assert want_fl == 18 and int(fl.item()) == want_fl and int(status.item()) == 0      # 0.0625 * 2^18 = 16384 fits, 2^19 does not
     want = ref.quantize_mt(x, 16, want_fl, threads=16)
     assert np.array_equal(d_grad.cpu().numpy(), want)
+    # the same through the one-pass call: with the guess that holds, and with one that is wrong (the whole tensor again)
+    for guess in (want_fl, want_fl + 1):
+        d_grad.zero_()
+        fl.fill_(guess)
+        lpk.lpk_select_quantize(tl, lpk.LPK_SEL_GRAD, fl, fl, status)
+        torch.cuda.synchronize()
+        assert int(fl.item()) == want_fl and int(status.item()) == 0, guess
+        assert torch.equal(d_grad.cpu(), torch.from_numpy(want)), guess
     tl.destroy()
 
 
