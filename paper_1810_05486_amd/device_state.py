@@ -216,15 +216,15 @@ class DeviceState:
         else:
             self.update_momentum(self.cfg.lr_q16(step_idx), mu_q16, self.cfg.wd_q16, k)
 
-    def capture_step(self, step_idx, k=0, fused=False):
+    def capture_step(self, step_idx, k=0, fused=False, onepass=False):
         """Record one whole step over source arena k (max-abs selection, quantization, update; or, fused, max-abs
-        selection and the update fed from the fp32 gradients) into a HIP graph and
+        selection and the update fed from the fp32 gradients; or, onepass, lpk_select_quantize and the update) into a HIP graph and
         return it (a torch.cuda.CUDAGraph; `.replay()` enqueues the step).  The library calls only enqueue kernels --
         no allocation, no synchronization, no memset node -- so they can be captured as they are.  The learning
         rate is a kernel argument and is frozen into the graph; workloads that rotate their fraclen arrays between
         steps (fraclen re-selection) cannot be replayed from one recording."""
         assert not self.cfg.reselect, "fraclen re-selection swaps device arrays between steps"
-        step = self.step_fused if fused else self.step
+        step = self.step_fused if fused else (lambda s, kk: self.step(s, kk, onepass=onepass))
         step(step_idx, k)                           # warm-up outside the capture (first-use initialisation)
         torch.cuda.synchronize(self.device)
         graph = torch.cuda.CUDAGraph()

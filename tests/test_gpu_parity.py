@@ -188,7 +188,7 @@ def test_selection_and_quantization_in_one_pass_on_every_workload():
     run_config(workloads.config(5, big_elems=(1 << 22) + 77, n_tiny=100), range(4), onepass=True, grad_bits=8)
 
 
-@pytest.mark.parametrize("fused", [False, True])
+@pytest.mark.parametrize("fused", [False, True, "onepass"])
 def test_whole_step_replayed_from_a_hip_graph(fused):
     """The hot calls only enqueue kernels, so a whole step (three calls, or two with the quantization fused into the
     update) can be recorded once and replayed: every replay (fresh gradients uploaded eagerly in between, a
@@ -204,7 +204,8 @@ def test_whole_step_replayed_from_a_hip_graph(fused):
         host.init_theta(theta0)
         grads = [cfg.grad(t, 0, out=views[t]) for t in range(cfg.n_tensors)]
         dev.upload_src()
-        graph = dev.capture_step(0, fused=fused)    # runs step 0 eagerly once, then records it (recording executes nothing)
+        # runs step 0 eagerly once, then records it (recording executes nothing); "onepass": lpk_select_quantize + update
+        graph = dev.capture_step(0, fused=fused is True, onepass=fused == "onepass")
         host.step(0, grads)
         compare(dev, host, "config %d eager step before the replays" % cfg.id)
         for s in range(1, 7):
