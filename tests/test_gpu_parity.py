@@ -71,7 +71,7 @@ def run_config(cfg, step_ids, compare_every=1, kahan=True, always=(), comp_bits=
         if fused:
             dev.step_fused(s, k)
         else:
-            dev.step(s, k, onepass=onepass)
+            dev.step(s, k, onepass=onepass(s) if callable(onepass) else onepass)
         host.step(s, grads)
         if (i + 1) % compare_every == 0 or i == len(step_ids) - 1 or i in always:
             compare(dev, host, "config %d step %d" % (cfg.id, s))
@@ -122,10 +122,12 @@ def test_config5_reduced():
 def test_config5_full_size_in_bench_launch_configuration():
     """The headline workload at full size (1 Gi + 10000 x 256 elements), same lists and launch shape as bench.py.
     All 50 steps: every output byte compared with the oracle after steps 1, 2, 25 and 50, fraclens, vmax and status
-    after every step.  LPK_CONFIG5_STEPS=n shortens the run."""
+    after every step; the first half through select + quantize, the second half (every other step of a shortened run)
+    through lpk_select_quantize.  LPK_CONFIG5_STEPS=n shortens the run."""
     steps = int(os.environ.get("LPK_CONFIG5_STEPS", "50"))
     say("config 5 at FULL size: 1073741824 + 10000*256 elements, %d steps (oracle on host threads)" % steps)
-    run_config(workloads.config(5), range(steps), compare_every=25, always=(0, 1))
+    run_config(workloads.config(5), range(steps), compare_every=25, always=(0, 1),
+               onepass=(lambda s: s >= 25) if steps >= 50 else (lambda s: s % 2 == 1))
 
 
 def test_fused_fp32_gradient_step_equals_quantize_then_step():
