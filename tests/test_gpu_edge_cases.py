@@ -329,6 +329,17 @@ def test_host_side_argument_errors_with_a_live_list():
     assert L.lpk_select_fraclen(tl.handle, lpk.LPK_F32, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_select_fraclen(tl.handle, 3, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
     assert L.lpk_select_fraclen(tl.handle, lpk.LPK_VMAX_U64, 0, None, None, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    # the one-pass selection + quantization: no fp32 source, NULL arrays, a destination it does not have
+    assert L.lpk_select_quantize(tl.handle, lpk.LPK_SEL_GRAD, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    src = torch.zeros(64, dtype=torch.float32, device=DEV)
+    tl2 = lpk.TensorList([lpk.make_desc(t, t.clone(), g, src)])
+    assert L.lpk_select_quantize(tl2.handle, lpk.LPK_SEL_GRAD, None, fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_select_quantize(tl2.handle, lpk.LPK_SEL_GRAD, fl.data_ptr(), None, None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_select_quantize(tl2.handle, lpk.LPK_SEL_MOMENTUM, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_select_quantize(None, lpk.LPK_SEL_GRAD, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_ERR_INVALID_ARG
+    assert L.lpk_select_quantize(tl2.handle, lpk.LPK_SEL_GRAD, fl.data_ptr(), fl.data_ptr(), None, None) == lpk.LPK_OK   # status may be NULL
+    torch.cuda.synchronize()
+    tl2.destroy()
     assert L.lpk_tensor_list_size(tl.handle) == 1 and L.lpk_tensor_list_tiles(tl.handle) == 1
     # options: unknown code, launch-shape value out of range
     assert L.lpk_tensor_list_set_option(tl.handle, 99, 1) == lpk.LPK_ERR_INVALID_ARG
