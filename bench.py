@@ -166,6 +166,9 @@ def traffic_child(args):
     for _ in range(2):
         dev.quantize_grads(0)
         note("maxabs_f32_kernel", "maxabs"); note("quantize_kernel", "quantize")
+    for _ in range(2):                                       # the fraclens just selected are the guess: it holds
+        dev.quantize_grads_onepass(0)
+        note("quantize_guess_kernel", "select_quantize")
     s0 = args.warmup
     if plain:
         for label, lr in REGIME_LRS:
@@ -240,7 +243,7 @@ def _run_counter_pass(counter, args, workdir):
     rows.sort()
     per_kernel, cursor, values = {}, {}, {}
     for key in {k for k, _ in meta["plan"]}:
-        per_kernel[key] = [v for _, name, v in rows if key in name]
+        per_kernel[key] = [v for _, name, v in rows if ("::" + key) in name]      # whole names: not requantize for quantize
         cursor[key] = 0
     for key, label in meta["plan"]:
         i = cursor[key]
@@ -566,7 +569,8 @@ def main():
                "select_quantize_ms": dict(spread(o_sq), max=max(o_sq)),
                "roofline": {"bound": "hbm", "kernel": "quantize_guess_kernel", "bytes_per_launch": sq_bytes, "peak": HBM_PEAK_GBS,
                             "unit": "GB/s", "achieved": sq_bytes / (statistics.mean(o_sq) * 1e-3) / 1e9,
-                            "frac": sq_bytes / (statistics.mean(o_sq) * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                            "frac": sq_bytes / (statistics.mean(o_sq) * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "traffic": (traffic or {}).get("kernels", {}).get("select_quantize", {}).get("bytes")},
                "note": "same outputs as the three-call path (fraclens, int gradients, update); every guess held in these steps "
                        "unless select_quantize_ms.max stands out: a wrong guess costs that tensor one more quantization pass"}
     f_upd_ms = sum(f_upd) / K
