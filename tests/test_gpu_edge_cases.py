@@ -841,6 +841,8 @@ def test_select_and_quantize_random_lists(seed):
             descs.append(lpk.make_desc(out, None, other, src) if sel == lpk.LPK_SEL_THETA else lpk.make_desc(other, None, out, src))
             xs.append(x); bits.append(W); keep += [sbuf, obuf, other]; outs.append((obuf, out, omis, n))
         tl = lpk.TensorList(descs)
+        lpk.lpk_tensor_list_set_option(tl, lpk.LPK_OPT_QUANT_BLOCKS_PER_CU, pr.choice([0, 0, 1, 3, 8, 64]))   # any launch shape
+        lpk.lpk_tensor_list_set_option(tl, lpk.LPK_OPT_SCAN_BLOCKS_PER_CU, pr.choice([0, 0, 1, 3, 8, 64]))
         defaults = [pr.randint(-64, 64) for _ in xs]
         fl = torch.tensor(defaults, dtype=torch.int32, device=DEV)
         fl_out = torch.full((len(xs),), -99, dtype=torch.int32, device=DEV)
