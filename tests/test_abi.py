@@ -119,6 +119,7 @@ int main(void)
   if (lpk_adam_step_f32grad(list, 0, 0, 0, 0, 0, 0, 0, &h, 0, 0, 0, 0, 0) != LPK_ERR_INVALID_ARG) return 9;
   if (lpk_momentum_sgd_step_f32grad(list, 0, 0, 0, 0, 0, 655u, 58982u, 0u, 0, 0, 0, 0) != LPK_ERR_INVALID_ARG) return 10;
   if (lpk_tensor_list_set_option(list, LPK_OPT_STORE_ALL, 1) != LPK_ERR_INVALID_ARG) return 11;
+  if (lpk_select_quantize(list, LPK_SEL_GRAD, 0, 0, 0, 0) != LPK_ERR_INVALID_ARG) return 12;
   puts("ok");
   return 0;
 }
