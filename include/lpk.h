@@ -121,7 +121,7 @@ int lpk_tensor_list_destroy(lpk_tensor_list* list);
  *   LPK_OPT_*_BLOCKS_PER_CU: launch shape of one family of kernels, in workgroups (of four wavefronts) per compute
  *     unit, 1..64; 0 restores the built-in choice.  STEP: the plain update with lazy stores (built-in 2); DENSE: the
  *     plain update with LPK_OPT_STORE_ALL and the momentum update (1); ADAM: the ADAM update (2); SCAN: the max-abs
- *     scan of lpk_select_fraclen and the fp32-gradient momentum update (2); QUANT: lpk_quantize_tensor (1 on long
+ *     scan of lpk_select_fraclen and the fp32-gradient momentum update (2); QUANT: lpk_quantize_tensor and lpk_select_quantize (1 on long
  *     lists, 2 on short ones); every family 8 on short lists of many tensors (at least 8 tensors, fewer than 32
  *     tiles of 4096 elements per compute unit).  The grid never exceeds what the tiles need.  Results do not depend
  *     on the launch shape; these exist for tuning on other parts.
