@@ -151,6 +151,26 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
 
 __device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Block-level end of a persistent scan: the waves of a block usually end on the same tensor, so their (tensor, max)
+// pairs are combined in LDS and each tensor gets one atomic.  s_tensor, s_max: one LDS word per wave each.
+__device__ __forceinline__ void flush_block_u32(uint32_t* scratch, int cur, uint32_t lane_max, int lane, int wave,
+                                                int* s_tensor, uint32_t* s_max)
+{
+  const uint32_t m = wave_max_u32(lane_max);
+  if (lane == 0) { s_tensor[wave] = cur; s_max[wave] = m; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int a = 0; a < kWavesPerBlock; ++a) {
+      const int ta = s_tensor[a];
+      if (ta < 0) continue;
+      uint32_t ma = s_max[a];
+      for (int b = a + 1; b < kWavesPerBlock; ++b)
+        if (s_tensor[b] == ta) { ma = ma > s_max[b] ? ma : s_max[b]; s_tensor[b] = -1; }
+      if (ma) atomicMax(&scratch[ta], ma);
+    }
+  }
+}
+
 // ---- fraclen of an fp32 maximum ------------------------------------------------
 __device__ __forceinline__ int clamp_fl(int fl) { return fl > kFlMax ? kFlMax : (fl < kFlMin ? kFlMin : fl); }
 

@@ -184,19 +184,7 @@ quantize_guess_kernel(const TensorDev* __restrict__ tensors, const Tile* __restr
   if (__ballot(nf)) bits |= kStatusNonFinite;
   if (status && bits && lane == 0) atomicOr(status, bits);
 
-  const uint32_t m = wave_max_u32(lane_max);
-  if (lane == 0) { s_tensor[wave] = cur; s_max[wave] = m; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    for (int a = 0; a < kWavesPerBlock; ++a) {
-      const int ta = s_tensor[a];
-      if (ta < 0) continue;
-      uint32_t ma = s_max[a];
-      for (int b = a + 1; b < kWavesPerBlock; ++b)
-        if (s_tensor[b] == ta) { ma = ma > s_max[b] ? ma : s_max[b]; s_tensor[b] = -1; }
-      if (ma) atomicMax(&scratch[ta], ma);
-    }
-  }
+  flush_block_u32(scratch, cur, lane_max, lane, wave, s_tensor, s_max);
 }
 
 // Pass 2, one thread per tensor: the true fraclen of every tensor longer than a tile, and whether its guess was wrong.
