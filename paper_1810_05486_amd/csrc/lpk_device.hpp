@@ -151,6 +151,15 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v)
 
 __device__ __forceinline__ int wave_uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// Decode one tile-table entry into wave-uniform scalars.
+__device__ __forceinline__ void read_tile(const Tile* __restrict__ tiles, uint32_t ti, int& tensor, uint32_t& cnt, uint64_t& off)
+{
+  const Tile tl = tiles[ti];
+  tensor = wave_uniform((int)tl.tensor);
+  cnt = (uint32_t)wave_uniform((int)tl.count);
+  off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
+}
+
 // Block-level end of a persistent scan: the waves of a block usually end on the same tensor, so their (tensor, max)
 // pairs are combined in LDS and each tensor gets one atomic.  s_tensor, s_max: one LDS word per wave each.
 __device__ __forceinline__ void flush_block_u32(uint32_t* scratch, int cur, uint32_t lane_max, int lane, int wave,

@@ -96,10 +96,8 @@ quantize_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict__ 
   uint32_t bits = 0, unused_max = 0;
 
   for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
-    const Tile tl = tiles[ti];
-    const int t = wave_uniform((int)tl.tensor);
-    const uint32_t cnt = (uint32_t)wave_uniform((int)tl.count);
-    const uint64_t off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
+    int t; uint32_t cnt; uint64_t off;
+    read_tile(tiles, ti, t, cnt, off);
     const TensorDev T = tensors[t];
     const int f = fl[t];
     if (f < kFlMin || f > kFlMax) { bits |= kStatusDomain; continue; }
@@ -145,10 +143,8 @@ quantize_guess_kernel(const TensorDev* __restrict__ tensors, const Tile* __restr
   int cur = -1;
 
   for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
-    const Tile tl = tiles[ti];
-    const int t = wave_uniform((int)tl.tensor);
-    const uint32_t cnt = (uint32_t)wave_uniform((int)tl.count);
-    const uint64_t off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
+    int t; uint32_t cnt; uint64_t off;
+    read_tile(tiles, ti, t, cnt, off);
     if (t != cur) {
       if (cur >= 0) {
         const uint32_t m = wave_max_u32(lane_max);
@@ -224,12 +220,10 @@ requantize_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
   int cur = -1, f = 0;
   bool again = false;
   for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
-    const Tile tl = tiles[ti];
-    const int t = wave_uniform((int)tl.tensor);
+    int t; uint32_t cnt; uint64_t off;
+    read_tile(tiles, ti, t, cnt, off);
     if (t != cur) { cur = t; again = redo[t] != 0; f = fl[t]; }
     if (!again) continue;
-    const uint32_t cnt = (uint32_t)wave_uniform((int)tl.count);
-    const uint64_t off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
     const TensorDev T = tensors[t];
     quant_tile_any(to_theta ? T.wt : T.wg, (const float*)T.src, to_theta ? T.theta : T.grad,
                    to_theta ? T.vec_src_theta : T.vec_src_grad, off, cnt, f, lane, nf, unused_max);

@@ -47,10 +47,8 @@ maxabs_f32_kernel(const TensorDev* __restrict__ tensors, const Tile* __restrict_
   bool vec = false;
 
   for (uint32_t ti = w0; ti < n_tiles; ti += nw) {
-    const Tile tl = tiles[ti];
-    const int t = wave_uniform((int)tl.tensor);
-    const uint32_t cnt = (uint32_t)wave_uniform((int)tl.count);
-    const uint64_t off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
+    int t; uint32_t cnt; uint64_t off;
+    read_tile(tiles, ti, t, cnt, off);
     if (t != cur) {
       if (cur >= 0) {
         uint32_t m = wave_max_u32(lane_max);

@@ -181,15 +181,6 @@ __device__ __forceinline__ int rne_shr32(int y, int b, int half_m1, int nz)
   return (y + half_m1 + lsb) >> b;
 }
 
-// Decode one tile-table entry into wave-uniform scalars.
-__device__ __forceinline__ void read_tile(const Tile* __restrict__ tiles, uint32_t ti, int& tensor, uint32_t& cnt, uint64_t& off)
-{
-  const Tile tl = tiles[ti];
-  tensor = wave_uniform((int)tl.tensor);
-  cnt = (uint32_t)wave_uniform((int)tl.count);
-  off = ((uint64_t)(uint32_t)wave_uniform((int)(tl.offset >> 32)) << 32) | (uint32_t)wave_uniform((int)tl.offset);
-}
-
 // Block-level end of a persistent kernel: combine the four waves' (tensor, max) pairs in LDS, one atomic per tensor.
 __device__ __forceinline__ void flush_block(uint64_t* vmax, int cur, uint64_t lane_max, int lane, int wave,
                                             int* s_tensor, uint64_t* s_max)
