@@ -342,6 +342,6 @@ int lpk_classifier_min_bits(uint32_t n_classes, uint32_t alpha_q16)
   return bw;
 }
 
-int lpk_version(void) { return 200; }
+int lpk_version(void) { return 300; }      // 0.3.0: lpk_select_quantize
 
 }  // extern "C"
